@@ -1,0 +1,110 @@
+"""Seeded synthetic workloads: shapes, inputs and initial parameters.
+
+Serves both the HIP path (through the binding) and the CPU oracle (through the
+tests and the benchmark).  Holds none of the method's arithmetic: only shape
+tables, random draws and the bf16 value rounding of generated inputs.
+
+The images stand in for the paper's datasets (Section 4.1: CIFAR-10 and SVHN are
+32x32x3, STL-10 is 96x96x3, all with 10 classes): shape and class count are kept,
+pixels are N(0,1), labels uniform.  No item of those datasets is used.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# arch / input_kind / optimizer / precision codes are the ones of include/ppll.h
+VIT, RESNET = 0, 1
+IMAGE, ACTIVATION = 0, 1
+SGD, ADAMW = 0, 1
+FP32, BF16 = 0, 1
+
+_VIT_STAGE = dict(arch=VIT, precision=BF16, input_kind=IMAGE, batch=128, num_classes=10,
+                  img_h=32, img_w=32, img_c=3, patch=4, tokens=65, dim=384, heads=6,
+                  mlp_dim=1536, depth=3, aux_depth=1, optimizer=ADAMW, weight_decay=0.01,
+                  beta1=0.9, beta2=0.999, adam_eps=1e-8, ln_eps=1e-6, lr=1e-3)
+
+WORKLOADS = {
+    # configs[0]: tiny fp32 ViT block, one plain SGD step
+    "vit_tiny_fp32": dict(arch=VIT, precision=FP32, input_kind=IMAGE, batch=8, num_classes=10,
+                          img_h=32, img_w=32, img_c=3, patch=4, tokens=65, dim=64, heads=4,
+                          mlp_dim=128, depth=2, aux_depth=0, optimizer=SGD, momentum=0.0,
+                          nesterov=0, weight_decay=0.0, ln_eps=1e-6, lr=0.01),
+    # configs[1]: one of 4 blocks of a 12-layer ViT
+    "vit_stage_bf16": dict(_VIT_STAGE),
+    # blocks 2..4 of configs[4]: same stage fed with token activations
+    "vit_stage_act_bf16": dict(_VIT_STAGE, input_kind=ACTIVATION),
+    # configs[2]: ResNet stage (Section 4.1 optimizer: Nesterov 0.9, L2 1e-4, lr 0.01)
+    "resnet_stage_bf16": dict(arch=RESNET, precision=BF16, input_kind=ACTIVATION, batch=128,
+                              num_classes=10, channels=32, height=16, width=16,
+                              n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
+                              nesterov=1, weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1,
+                              lr=0.01),
+    # configs[3]: STL-10-shaped ViT stage
+    "vit_large_image_bf16": dict(_VIT_STAGE, batch=64, img_h=96, img_w=96, patch=8, tokens=145),
+}
+
+
+def workload(name: str, **overrides) -> dict:
+    wl = dict(WORKLOADS[name])
+    wl.update(overrides)
+    return wl
+
+
+def round_to_bf16(a: np.ndarray) -> np.ndarray:
+    """fp32 values rounded to the nearest bf16-representable value (ties to even),
+    returned as fp32."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32)
+
+
+def input_shape(wl: dict) -> tuple:
+    if wl["arch"] == VIT:
+        if wl["input_kind"] == IMAGE:
+            return (wl["batch"], wl["img_h"], wl["img_w"], wl["img_c"])
+        return (wl["batch"], wl["tokens"], wl["dim"])
+    return (wl["batch"], wl["height"], wl["width"], wl["channels"])
+
+
+def output_shape(wl: dict) -> tuple:
+    if wl["arch"] == VIT:
+        return (wl["batch"], wl["tokens"], wl["dim"])
+    return (wl["batch"], wl["height"], wl["width"], wl["channels"])
+
+
+def make_batch(wl: dict, seed: int = 0, index: int = 0):
+    """(x, labels): x ~ N(0,1) fp32 (bf16-representable on the bf16 path),
+    labels uniform int32.  `index` selects the batch within the seeded stream."""
+    rng = np.random.default_rng([seed, index])
+    x = rng.standard_normal(input_shape(wl), dtype=np.float32)
+    if wl["precision"] == BF16:
+        x = round_to_bf16(x)
+    y = rng.integers(0, wl["num_classes"], size=wl["batch"], dtype=np.int32)
+    return x, y
+
+
+def make_params(spec, seed: int = 0, jitter: bool = False) -> np.ndarray:
+    """Flat fp32 parameter blob for an ordered (name, shape) table.
+
+    Linear, patch-embed, cls and pos ~ N(0, 0.02^2); 3x3 convolutions
+    ~ N(0, 2/(9 Cin)); biases 0 and norm scales 1 / shifts 0 unless `jitter`,
+    which perturbs them (bias ~ N(0, 0.02^2), scale ~ 1 + N(0, 0.1^2), shift
+    ~ N(0, 0.1^2)) so that parity runs exercise every tensor."""
+    rng = np.random.default_rng([seed, 12345])
+    parts = []
+    for name, shape in spec:
+        n = int(np.prod(shape))
+        leaf = name.split(".")[-1]
+        is_norm = ".ln" in name or ".bn" in name
+        if len(shape) == 4:
+            v = rng.standard_normal(n) * np.sqrt(2.0 / (9.0 * shape[2]))
+        elif is_norm and leaf == "g":
+            v = 1.0 + (rng.standard_normal(n) * 0.1 if jitter else np.zeros(n))
+        elif is_norm and leaf == "b":
+            v = rng.standard_normal(n) * 0.1 if jitter else np.zeros(n)
+        elif leaf == "b":
+            v = rng.standard_normal(n) * 0.02 if jitter else np.zeros(n)
+        else:
+            v = rng.standard_normal(n) * 0.02
+        parts.append(v.astype(np.float32))
+    return np.concatenate(parts)

@@ -1,0 +1,295 @@
+"""Pins for the oracle's whole local-block step (CPU only).
+
+The step is pinned by (i) central finite differences of the local loss in
+float64, (ii) torch.autograd over library ops plus torch.optim for the update,
+(iii) closed forms (zero head -> ln 10), (iv) the structural facts of
+Algorithm 1: gradient isolation, the output being pre-update, and the
+sequential chain that the pipeline must reproduce.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import ppll_oracle as O
+from paper_2411_12780_amd import synth
+from helpers import oracle_cfg, rel_l2
+
+TINY_VIT_IMG = dict(arch=0, input_kind=0, batch=2, num_classes=10, img_h=8, img_w=8, img_c=3,
+                    patch=4, tokens=5, dim=8, heads=2, mlp_dim=16, depth=1, aux_depth=1,
+                    optimizer=0, ln_eps=1e-6, precision=0)
+TINY_VIT_ACT = dict(TINY_VIT_IMG, input_kind=1, depth=2, aux_depth=0)
+TINY_RESNET = dict(arch=1, input_kind=1, batch=2, num_classes=10, channels=4, height=6, width=6,
+                   n_basic_blocks=2, aux_channels=6, optimizer=0, momentum=0.9, nesterov=1,
+                   weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1, precision=0)
+CASES = {"vit_img": TINY_VIT_IMG, "vit_act": TINY_VIT_ACT, "resnet": TINY_RESNET}
+
+
+def make(wl, seed=0, dtype=np.float64):
+    cfg = oracle_cfg(wl)
+    flat = synth.make_params(O.param_spec(cfg), seed=seed, jitter=True).astype(np.float64)
+    flat = flat + np.random.default_rng(seed + 99).standard_normal(flat.size) * 0.05  # livelier than the bench init
+    st = O.block_init(cfg, flat, dtype)
+    x, y = synth.make_batch(wl, seed=seed)
+    return cfg, st, x.astype(np.float64), y
+
+
+# ------------------------------------------------------------------ counts
+def test_param_counts_of_the_named_workloads():
+    assert O.param_count(oracle_cfg(synth.workload("vit_tiny_fp32"))) == 75082
+    assert O.param_count(oracle_cfg(synth.workload("vit_stage_bf16"))) == 7146634
+    assert O.param_count(oracle_cfg(synth.workload("vit_stage_act_bf16"))) == 7102474
+    assert O.param_count(oracle_cfg(synth.workload("vit_large_image_bf16"))) == 7232650
+    assert O.param_count(oracle_cfg(synth.workload("resnet_stage_bf16"))) == 112010
+
+
+# ------------------------------------------------------------------ finite differences
+@pytest.mark.parametrize("case", list(CASES))
+def test_gradients_match_central_finite_differences(case):
+    cfg, st, x, y = make(CASES[case])
+    O.block_step(st_copy := O.block_init(cfg, O.flatten(cfg, st.params)), x, y, 0.0)
+    grads = st_copy.grads
+    rng = np.random.default_rng(3)
+    h = 1e-5
+    for name, shape in O.param_spec(cfg):
+        n = int(np.prod(shape))
+        for idx in rng.choice(n, size=min(n, 20), replace=False):
+            flat = st.params[name].reshape(-1)
+            old = flat[idx]
+            flat[idx] = old + h
+            lp = O.local_loss(st, x, y)
+            flat[idx] = old - h
+            lm = O.local_loss(st, x, y)
+            flat[idx] = old
+            fd = (lp - lm) / (2 * h)
+            an = grads[name].reshape(-1)[idx]
+            assert abs(fd - an) <= 1e-6 * max(1.0, abs(fd)) + 1e-9, (name, idx, fd, an)
+
+
+# ------------------------------------------------------------------ torch autograd reference
+def _t(a):
+    return torch.tensor(np.asarray(a), dtype=torch.float64)
+
+
+def _torch_encoder(x, p, pre, heads, eps):
+    D = x.shape[-1]
+    u = F.layer_norm(x, (D,), p[pre + ".ln1.g"], p[pre + ".ln1.b"], eps)
+    qkv = F.linear(u, p[pre + ".qkv.w"].T, p[pre + ".qkv.b"])
+    B, T, _ = qkv.shape
+    q, k, v = (qkv[:, :, i * D:(i + 1) * D].reshape(B, T, heads, D // heads).transpose(1, 2) for i in range(3))
+    o = F.scaled_dot_product_attention(q, k, v).transpose(1, 2).reshape(B, T, D)
+    x = x + F.linear(o, p[pre + ".proj.w"].T, p[pre + ".proj.b"])
+    u = F.layer_norm(x, (D,), p[pre + ".ln2.g"], p[pre + ".ln2.b"], eps)
+    h = F.gelu(F.linear(u, p[pre + ".fc1.w"].T, p[pre + ".fc1.b"]))
+    return x + F.linear(h, p[pre + ".fc2.w"].T, p[pre + ".fc2.b"])
+
+
+def _torch_vit(cfg, p, x):
+    if cfg.input_kind == O.IN_IMAGE:
+        P = cfg.patch
+        # F.unfold yields (channel, row, col) order per patch; the block uses (row, col, channel)
+        cols = F.unfold(x.permute(0, 3, 1, 2), kernel_size=P, stride=P)          # [B, C*P*P, N]
+        B, _, N = cols.shape
+        pt = cols.reshape(B, cfg.img_c, P, P, N).permute(0, 4, 2, 3, 1).reshape(B, N, P * P * cfg.img_c)
+        e = F.linear(pt, p["pe.w"].T, p["pe.b"])
+        x = torch.cat([p["cls"].expand(B, 1, -1), e], dim=1) + p["pos"]
+    x = x.detach() if cfg.input_kind != O.IN_IMAGE else x
+    for l in range(cfg.depth):
+        x = _torch_encoder(x, p, f"blk{l}", cfg.heads, cfg.ln_eps)
+    x_out = x
+    for a in range(cfg.aux_depth):
+        x = _torch_encoder(x, p, f"aux{a}", cfg.heads, cfg.ln_eps)
+    z = F.layer_norm(x[:, 0, :], (cfg.dim,), p["head.ln.g"], p["head.ln.b"], cfg.ln_eps)
+    return x_out, F.linear(z, p["head.w"].T, p["head.b"])
+
+
+def _torch_conv(x, w, stride):
+    return F.conv2d(x.permute(0, 3, 1, 2), w.permute(3, 2, 0, 1), stride=stride, padding=1).permute(0, 2, 3, 1)
+
+
+def _torch_bn(x, g, b, eps, run):
+    y = F.batch_norm(x.permute(0, 3, 1, 2), run[0], run[1], g, b, training=True, momentum=0.1, eps=eps)
+    return y.permute(0, 2, 3, 1)
+
+
+def _torch_resnet(cfg, p, x, run):
+    for i in range(cfg.n_basic_blocks):
+        pre = f"rb{i}"
+        y = F.relu(_torch_bn(_torch_conv(x, p[pre + ".conv1.w"], 1), p[pre + ".bn1.g"], p[pre + ".bn1.b"], cfg.bn_eps, run[pre + ".bn1"]))
+        y = _torch_bn(_torch_conv(y, p[pre + ".conv2.w"], 1), p[pre + ".bn2.g"], p[pre + ".bn2.b"], cfg.bn_eps, run[pre + ".bn2"])
+        x = F.relu(x + y)
+    x_out = x
+    a = F.relu(_torch_bn(_torch_conv(x, p["aux.conv.w"], 2), p["aux.bn.g"], p["aux.bn.b"], cfg.bn_eps, run["aux.bn"]))
+    return x_out, F.linear(a.mean(dim=(1, 2)), p["head.w"].T, p["head.b"])
+
+
+@pytest.mark.parametrize("case,opt", [("vit_img", "sgd"), ("vit_act", "adamw"), ("vit_img", "adamw"),
+                                      ("resnet", "sgd_nesterov")])
+def test_three_steps_match_torch_autograd_and_optim(case, opt):
+    wl = dict(CASES[case])
+    if opt == "adamw":
+        wl.update(optimizer=1, weight_decay=0.01, beta1=0.9, beta2=0.999, adam_eps=1e-8)
+    elif opt == "sgd":
+        wl.update(optimizer=0, momentum=0.0, nesterov=0, weight_decay=0.0)
+    cfg, st, _, _ = make(wl)
+    tp = {k: _t(v).requires_grad_(True) for k, v in st.params.items()}
+    run = {n: (torch.zeros(c, dtype=torch.float64), torch.ones(c, dtype=torch.float64)) for n, c in O.bn_stat_spec(cfg)}
+    lr = 0.05
+    if opt == "adamw":
+        topt = torch.optim.AdamW(tp.values(), lr=lr, betas=(0.9, 0.999), eps=1e-8, weight_decay=0.01)
+    elif opt == "sgd":
+        topt = torch.optim.SGD(tp.values(), lr=lr)
+    else:
+        topt = torch.optim.SGD(tp.values(), lr=lr, momentum=0.9, nesterov=True, weight_decay=1e-4)
+    for step in range(3):
+        x, y = synth.make_batch(wl, seed=5, index=step)
+        tx = _t(x)
+        topt.zero_grad()
+        if cfg.arch == O.ARCH_VIT:
+            t_out, t_logits = _torch_vit(cfg, tp, tx)
+        else:
+            t_out, t_logits = _torch_resnet(cfg, tp, tx, run)
+        t_loss = F.cross_entropy(t_logits, torch.tensor(y, dtype=torch.long))
+        t_loss.backward()
+        x_out, loss = O.block_step(st, x.astype(np.float64), y, lr)
+        assert abs(loss - t_loss.item()) < 1e-10
+        assert rel_l2(x_out, t_out.detach().numpy()) < 1e-10
+        for name in tp:
+            assert rel_l2(st.grads[name], tp[name].grad.numpy()) < 1e-8, (step, name)
+        topt.step()
+        for name in tp:
+            assert rel_l2(st.params[name], tp[name].detach().numpy()) < 1e-10, (step, name)
+    for n, _ in O.bn_stat_spec(cfg):
+        assert rel_l2(st.bn_mean[n], run[n][0].numpy()) < 1e-10
+        assert rel_l2(st.bn_var[n], run[n][1].numpy()) < 1e-10
+
+
+# ------------------------------------------------------------------ closed forms
+@pytest.mark.parametrize("case", ["vit_img", "resnet"])
+def test_zero_head_gives_ln10_and_no_upstream_gradient(case):
+    cfg, st, x, y = make(CASES[case])
+    st.params["head.w"][:] = 0.0
+    st.params["head.b"][:] = 0.0
+    _, loss = O.block_step(st, x, y, 0.0)
+    assert abs(loss - math.log(10.0)) < 1e-14
+    freq = np.bincount(y, minlength=10) / len(y)
+    np.testing.assert_allclose(st.grads["head.b"], 0.1 - freq, atol=1e-15)
+    for name, g in st.grads.items():
+        if name not in ("head.w", "head.b"):
+            assert np.abs(g).max() == 0.0, name
+
+
+def test_fp32_oracle_tracks_fp64_oracle():
+    wl = synth.workload("vit_tiny_fp32")
+    cfg = oracle_cfg(wl)
+    flat = synth.make_params(O.param_spec(cfg), seed=0, jitter=True)
+    x, y = synth.make_batch(wl)
+    s64, s32 = O.block_init(cfg, flat, np.float64), O.block_init(cfg, flat, np.float32)
+    o64, l64 = O.block_step(s64, x, y, 0.01)
+    o32, l32 = O.block_step(s32, x, y, 0.01)
+    assert o32.dtype == np.float32
+    assert abs(l32 - l64) < 1e-5 * abs(l64)
+    assert rel_l2(o32, o64) < 1e-5
+    for name in s64.grads:
+        assert rel_l2(s32.grads[name], s64.grads[name]) < 1e-4, name
+
+
+# ------------------------------------------------------------------ Algorithm 1 structure
+def _two_block_chain(seed_b2=1, head_scale=1.0):
+    wl1 = dict(TINY_VIT_IMG, aux_depth=0)
+    wl2 = dict(TINY_VIT_ACT, depth=1, aux_depth=1)
+    c1, s1, x, y = make(wl1, seed=0)
+    c2, s2, _, _ = make(wl2, seed=seed_b2)
+    s2.params["head.w"] *= head_scale
+    return [s1, s2], x, y
+
+
+def test_gradient_isolation_block_update_ignores_later_blocks():
+    ref, x, y = _two_block_chain()
+    alt, _, _ = _two_block_chain(seed_b2=2, head_scale=50.0)
+    for _ in range(2):
+        O.chain_step(ref, x, y, 0.1)
+        O.chain_step(alt, x, y, 0.1)
+    for name in ref[0].params:
+        assert np.array_equal(ref[0].params[name], alt[0].params[name]), name
+    assert not np.array_equal(ref[1].params["head.w"], alt[1].params["head.w"])
+
+
+def test_block_gradient_is_of_its_own_local_loss_only():
+    # block 1's analytic gradient equals the finite difference of block 1's loss,
+    # and differs from the finite difference of block 2's loss through x_1
+    states, x, y = _two_block_chain()
+    s1, s2 = states
+    snap = O.block_init(s1.cfg, O.flatten(s1.cfg, s1.params))
+    O.block_step(snap, x, y, 0.0)
+    name, idx, h = "blk0.fc2.w", 5, 1e-5
+    flat = s1.params[name].reshape(-1)
+
+    def losses():
+        x1, _, _ = O.block_forward(s1, x)
+        return O.local_loss(s1, x, y), O.local_loss(s2, x1, y)
+
+    old = flat[idx]
+    flat[idx] = old + h; a1, a2 = losses()
+    flat[idx] = old - h; b1, b2 = losses()
+    flat[idx] = old
+    own, downstream = (a1 - b1) / (2 * h), (a2 - b2) / (2 * h)
+    an = snap.grads[name].reshape(-1)[idx]
+    assert abs(own - an) < 1e-7 * max(1, abs(own))
+    assert abs(downstream) > 1e-6 and abs(downstream - an) > 1e-6
+
+
+def test_output_is_computed_with_pre_update_parameters():
+    cfg, st, x, y = make(TINY_VIT_IMG)
+    before = O.block_init(cfg, O.flatten(cfg, st.params))
+    x_out, _ = O.block_step(st, x, y, 0.5)
+    pre, _, _ = O.block_forward(before, x)
+    post, _, _ = O.block_forward(st, x)
+    assert np.array_equal(x_out, pre)
+    assert rel_l2(post, pre) > 1e-6
+
+
+def test_chain_equals_blocks_called_in_order_and_labels_ride_along():
+    a, x, y = _two_block_chain()
+    b, _, _ = _two_block_chain()
+    losses, outs = O.chain_step(a, x, y, 0.1)
+    x1, l1 = O.block_step(b[0], x, y, 0.1)
+    x2, l2 = O.block_step(b[1], x1, y, 0.1)
+    assert losses == [l1, l2]
+    assert np.array_equal(outs[0], x1) and np.array_equal(outs[1], x2)
+    c, _, _ = _two_block_chain()
+    y_other = (y + 1) % 10
+    lo, _ = O.chain_step(c, x, y_other, 0.1)
+    assert lo[1] != l2                        # block 2 sees the labels of its batch
+
+
+def test_batch_permutation_leaves_loss_unchanged():
+    for case in ("vit_img", "resnet"):
+        cfg, st, x, y = make(CASES[case])
+        perm = np.array([1, 0])
+        assert abs(O.local_loss(st, x, y) - O.local_loss(st, x[perm], y[perm])) < 1e-12
+
+
+def test_token_permutation_with_pos_rows_leaves_logits_unchanged():
+    cfg, st, x, y = make(TINY_VIT_IMG)
+    _, logits, _ = O.block_forward(st, x)
+    # swap patches 0 and 3 of the 2x2 grid in the image and the matching pos rows (cls row 0 stays)
+    P = cfg.patch
+    x2 = x.copy()
+    x2[:, :P, :P], x2[:, P:, P:] = x[:, P:, P:], x[:, :P, :P]
+    pos = st.params["pos"].copy()
+    st.params["pos"][1], st.params["pos"][4] = pos[4], pos[1]
+    _, logits2, _ = O.block_forward(st, x2)
+    assert rel_l2(logits2, logits) < 1e-12
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_loss_decreases_when_overfitting_one_batch(case):
+    cfg, st, x, y = make(CASES[case])
+    first = None
+    for i in range(20):
+        _, loss = O.block_step(st, x, y, 0.05)
+        first = loss if first is None else first
+    assert loss < 0.8 * first
