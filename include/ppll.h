@@ -1,0 +1,179 @@
+/*
+ * ppll.h -- C ABI of libppll.so: one gradient-isolated block's local training
+ * step on one MI355X (gfx950), and a single-GPU pipeline of K such blocks.
+ *
+ * Method (paper: Section 3.2 and Algorithm 1).  A network is cut into K
+ * modules M_1..M_K, each with its own auxiliary network A_j and optimizer.
+ * Process P_j repeats: take (x_{j-1}, y) from the buffer before it; forward
+ * x_j = M_j(x_{j-1}); put (x_j, y) into the buffer after it; compute the
+ * gradient of the local loss w.r.t. (theta_j, gamma_j) only -- nothing flows
+ * into x_{j-1} (Sections 3.1-3.2, gradient isolation); update.  One
+ * ppll_block_step is one pass of that loop body for one j; ppll_pipeline_step
+ * feeds one batch to K blocks linked by bounded FIFO buffers of (x_j, y).
+ *
+ * Conventions common to all calls
+ *  - Every function returns an int status (PPLL_OK = 0).  Nothing throws,
+ *    aborts or exits.  ppll_last_error() gives the text of the calling thread's
+ *    last failure.
+ *  - "dev" pointers are device (HBM) addresses on the current HIP device;
+ *    "host" pointers are ordinary host memory.  All device pointers must be
+ *    16-byte aligned.
+ *  - The caller allocates and frees every device byte (workspace, inputs,
+ *    outputs, loss) and owns the HIP streams.  The library carves parameters,
+ *    optimizer moments, saved activations and queue slots out of the workspace
+ *    and frees only its host-side handle.
+ *  - Argument errors are detected on the host before anything is enqueued and
+ *    leave the handle untouched.  An out-of-range label raises a sticky device
+ *    flag that the next *_sync reports as PPLL_ERR_LABEL.
+ *  - Layouts: images NHWC [B,H,W,C]; tokens [B,T,D] row-major; ResNet
+ *    activations NHWC [B,H,W,C]; weight matrices [in,out] row-major; 3x3
+ *    filters [ky,kx,Cin,Cout].  Activations are fp32 on the PPLL_FP32 path and
+ *    bf16 on the PPLL_BF16 path; labels are int32 in [0, num_classes).
+ *  - A handle is used by one host thread at a time.
+ */
+#ifndef PPLL_H_
+#define PPLL_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  PPLL_OK = 0,
+  PPLL_ERR_NULL = 1,      /* a required pointer is null                          */
+  PPLL_ERR_CONFIG = 2,    /* configuration outside what the kernels support      */
+  PPLL_ERR_SHAPE = 3,     /* size/count argument does not match the config       */
+  PPLL_ERR_WORKSPACE = 4, /* workspace too small or misaligned                   */
+  PPLL_ERR_HIP = 5,       /* a HIP runtime call failed                           */
+  PPLL_ERR_LABEL = 6,     /* a label was outside [0, num_classes)                */
+  PPLL_ERR_STATE = 7      /* handle destroyed / call out of order                */
+};
+
+enum { PPLL_VIT = 0, PPLL_RESNET = 1 };
+enum { PPLL_FP32 = 0, PPLL_BF16 = 1 };
+enum { PPLL_IN_IMAGE = 0, PPLL_IN_ACTIVATION = 1 };
+enum { PPLL_SGD = 0, PPLL_ADAMW = 1 };
+/* tensor kinds for ppll_block_read_tensor / write_tensor */
+enum { PPLL_T_PARAM = 0, PPLL_T_GRAD = 1, PPLL_T_MOMENT1 = 2, PPLL_T_MOMENT2 = 3,
+       PPLL_T_BN_MEAN = 4, PPLL_T_BN_VAR = 5 };
+
+/* Shape and hyper-parameters of one block = module M_j + auxiliary net A_j
+ * (Section 3.2; model families and optimizer of Sections 4.1-4.2).
+ * ViT: [patch-embed + cls + pos if PPLL_IN_IMAGE] -> depth pre-LN encoder
+ * layers -> x_out; aux = aux_depth encoder layers -> LayerNorm -> cls token ->
+ * Linear(dim, num_classes).  ResNet: n_basic_blocks x (conv3x3-BN-ReLU-conv3x3-
+ * BN, + identity, ReLU) -> x_out; aux = conv3x3 stride 2 (channels ->
+ * aux_channels) -> BN -> ReLU -> global average -> Linear. */
+typedef struct {
+  uint32_t struct_size;   /* = sizeof(ppll_block_config)                         */
+  int32_t arch;           /* PPLL_VIT | PPLL_RESNET                              */
+  int32_t precision;      /* PPLL_FP32 | PPLL_BF16 (fp32 master weights always)  */
+  int32_t input_kind;     /* PPLL_IN_IMAGE (ViT only) | PPLL_IN_ACTIVATION       */
+  int32_t batch, num_classes;
+  int32_t img_h, img_w, img_c, patch;                    /* ViT image input      */
+  int32_t tokens, dim, heads, mlp_dim, depth, aux_depth; /* ViT                  */
+  int32_t channels, height, width, n_basic_blocks, aux_channels; /* ResNet       */
+  int32_t optimizer;      /* PPLL_SGD | PPLL_ADAMW                               */
+  float momentum;         /* SGD                                                 */
+  int32_t nesterov;       /* SGD                                                 */
+  float weight_decay;     /* SGD: coupled L2; AdamW: decoupled                   */
+  float beta1, beta2, adam_eps;
+  float ln_eps, bn_eps, bn_momentum;
+  uint64_t seed;          /* used only when no initial parameters are supplied   */
+} ppll_block_config;
+
+typedef struct ppll_block ppll_block_t;
+typedef struct ppll_pipeline ppll_pipeline_t;
+
+/* Text of the calling thread's most recent failure (static storage, never null). */
+const char* ppll_last_error(void);
+
+/* Host-only size queries.  workspace: device bytes ppll_block_init needs;
+ * param: bytes of the flat fp32 parameter blob (theta_j then gamma_j, tensor
+ * order as reported by ppll_block_tensor_info); in/out: bytes of x_in / x_out
+ * in the path's activation type. */
+int ppll_block_workspace_bytes(const ppll_block_config* cfg, size_t* bytes);
+int ppll_block_param_bytes(const ppll_block_config* cfg, size_t* bytes);
+int ppll_block_in_bytes(const ppll_block_config* cfg, size_t* bytes);
+int ppll_block_out_bytes(const ppll_block_config* cfg, size_t* bytes);
+
+/* Algorithm 1, initialisation line: create block j's parameters (theta_j,
+ * gamma_j) and optimizer state inside `workspace_dev`.
+ * init_params_host: flat fp32 blob of ppll_block_param_bytes bytes, or null for a
+ * seeded draw (weights N(0, 0.02^2), conv N(0, 2/(9 Cin)), biases 0, norm
+ * scales 1).  The copy is done when the call returns.  hip_stream: a
+ * hipStream_t (null = default stream) used for the set-up work.  *out receives
+ * the handle; the workspace must outlive it. */
+int ppll_block_init(const ppll_block_config* cfg, void* workspace_dev, size_t workspace_bytes,
+                    const float* init_params_host, void* hip_stream, ppll_block_t** out);
+
+/* Algorithm 1, loop body for one module: forward x_out = M_j(x_in) with the
+ * parameters as they are before this call's update (that is what the algorithm
+ * pushes to the next buffer); auxiliary forward; mean softmax cross-entropy
+ * against `labels`; backward through A_j and M_j, stopping at x_in; optimizer
+ * update of every tensor with learning rate `lr`.
+ * Asynchronous on `hip_stream`.  x_in_dev [in_bytes] and labels_dev [batch] are
+ * read only; x_out_dev [out_bytes] is written during the forward part and read
+ * again by the backward part, so all three must stay valid and unmodified until
+ * the stream has passed this call's work.  loss_dev: one float on the device
+ * (may be null; ppll_block_sync still returns the loss). */
+int ppll_block_step(ppll_block_t* blk, const void* x_in_dev, const int32_t* labels_dev, float lr,
+                    void* x_out_dev, float* loss_dev, void* hip_stream);
+
+/* Waits for the stream of the last step; returns that step's loss in
+ * *loss_host (nullable).  Reports PPLL_ERR_LABEL / PPLL_ERR_HIP raised since the
+ * previous sync. */
+int ppll_block_sync(ppll_block_t* blk, float* loss_host);
+
+/* Parameter-table access, for parity checks and checkpointing.  index runs
+ * over 0..count-1 of the kind: parameter tensors for PARAM/GRAD/MOMENT*, BN
+ * layers for BN_MEAN/BN_VAR.  n must equal the tensor's element count.  These
+ * calls synchronise the block's stream. */
+int ppll_block_tensor_count(ppll_block_t* blk, int32_t kind, int32_t* count);
+int ppll_block_tensor_info(ppll_block_t* blk, int32_t kind, int32_t index, const char** name, size_t* n);
+int ppll_block_read_tensor(ppll_block_t* blk, int32_t kind, int32_t index, float* host_out, size_t n);
+int ppll_block_write_tensor(ppll_block_t* blk, int32_t kind, int32_t index, const float* host_in, size_t n);
+
+/* Frees the host-side handle (device memory belongs to the caller). */
+int ppll_block_destroy(ppll_block_t* blk);
+
+/* Pipeline of K blocks on K HIP streams of one GPU (Algorithm 1, "parallel
+ * execution for all j", with the buffers B_j as device ring buffers of
+ * `queue_depth` slots holding (x_j, y); blocking FIFO: every batch is consumed
+ * once, in order, by every block, so the values equal sequential local
+ * learning).  cfgs[j+1]'s input must have the shape of cfgs[j]'s output and
+ * the same batch, precision and class count. */
+int ppll_pipeline_workspace_bytes(const ppll_block_config* cfgs, int32_t K, int32_t queue_depth, size_t* bytes);
+int ppll_pipeline_init(const ppll_block_config* cfgs, int32_t K, int32_t queue_depth,
+                       void* workspace_dev, size_t workspace_bytes, void* const* hip_streams /*K*/,
+                       const float* const* init_params_host /*K entries or null*/, ppll_pipeline_t** out);
+
+/* Enqueue one batch: copies (x0, labels) into the input slot on stream 0, then
+ * for j = 0..K-1 on stream j: wait until the slot before it is ready and the
+ * slot after it is free, forward into that slot, signal it, then auxiliary
+ * forward, loss, backward, update, and release the input slot.  Returns after
+ * enqueueing.  x0_dev / labels_dev must stay unmodified until stream 0 has
+ * passed the copy (ppll_pipeline_sync guarantees it).  losses_dev: K floats on
+ * the device, nullable. */
+int ppll_pipeline_step(ppll_pipeline_t* pipe, const void* x0_dev, const int32_t* labels_dev, float lr,
+                       float* losses_dev);
+
+/* Waits for all K streams; losses_host (nullable) receives the K local losses
+ * of the last batch. */
+int ppll_pipeline_sync(ppll_pipeline_t* pipe, float* losses_host);
+
+/* Borrow block j's handle (valid until ppll_pipeline_destroy) for tensor access. */
+int ppll_pipeline_block(ppll_pipeline_t* pipe, int32_t j, ppll_block_t** borrowed);
+
+/* Device address and byte size of the last block's most recent output. */
+int ppll_pipeline_output(ppll_pipeline_t* pipe, const void** x_out_dev, size_t* bytes);
+
+int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PPLL_H_ */

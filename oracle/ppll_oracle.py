@@ -355,41 +355,74 @@ class BlockState:
     bn_var: Dict[str, np.ndarray] = field(default_factory=dict)
     grads: Optional[Dict[str, np.ndarray]] = None
     logits: Optional[np.ndarray] = None
+    storage: Optional[str] = None
+
+    def act(self, a):
+        """A stored activation, in the storage precision being emulated."""
+        return bf16_values(a) if self.storage == "bf16" else a
+
+    def wmat(self, w):
+        """A weight matrix / filter as the contractions read it (bf16 shadow of the
+        fp32 master when bf16 storage is emulated)."""
+        return bf16_values(w) if self.storage == "bf16" else w
 
 
-def block_init(cfg: BlockConfig, flat_params: np.ndarray, dtype=np.float64) -> BlockState:
+def bf16_values(a):
+    """Values of `a` rounded to the nearest bfloat16 (8-bit significand, ties to
+    even), kept in a's dtype.  Used only to emulate where a mixed-precision run
+    stores activations and weight shadows, so that sign decisions (ReLU masks)
+    are taken on the same stored values; all arithmetic stays in a's dtype.
+    (Normal range only: no subnormal or overflow handling is needed here.)"""
+    a = np.asarray(a)
+    m, e = np.frexp(a)                       # a = m * 2**e, 0.5 <= |m| < 1
+    return np.ldexp(np.rint(m * 256.0) / 256.0, e).astype(a.dtype)
+
+
+def block_init(cfg: BlockConfig, flat_params: np.ndarray, dtype=np.float64,
+               storage: Optional[str] = None) -> BlockState:
+    """storage=None: everything in `dtype`.  storage="bf16": activations the
+    mixed-precision path keeps in bf16, and the weight matrices its contractions
+    read, are rounded to bf16 values at the point of storage (arithmetic, norm
+    statistics, loss, gradients w.r.t. parameters and the optimizer stay in
+    `dtype`)."""
     params = unflatten(cfg, flat_params, dtype)
     st = BlockState(cfg, dtype, params,
                     {k: np.zeros_like(v) for k, v in params.items()},
-                    {k: np.zeros_like(v) for k, v in params.items()})
+                    {k: np.zeros_like(v) for k, v in params.items()}, storage=storage)
     for name, c in bn_stat_spec(cfg):
         st.bn_mean[name] = np.zeros(c, dtype=dtype)
         st.bn_var[name] = np.ones(c, dtype=dtype)
     return st
 
 
-def _encoder_fwd(x, p, pre, cfg):
+def _encoder_fwd(x, p, pre, st):
+    cfg, S, W = st.cfg, st.act, st.wmat
     u, c_ln1 = layernorm_fwd(x, p[pre + ".ln1.g"], p[pre + ".ln1.b"], cfg.ln_eps)
-    qkv = linear_fwd(u, p[pre + ".qkv.w"], p[pre + ".qkv.b"])
+    u = S(u)
+    qkv = S(linear_fwd(u, W(p[pre + ".qkv.w"]), p[pre + ".qkv.b"]))
     o, c_att = attention_fwd(qkv, cfg.heads)
-    x1 = x + linear_fwd(o, p[pre + ".proj.w"], p[pre + ".proj.b"])
+    o = S(o)
+    x1 = S(x + linear_fwd(o, W(p[pre + ".proj.w"]), p[pre + ".proj.b"]))
     u2, c_ln2 = layernorm_fwd(x1, p[pre + ".ln2.g"], p[pre + ".ln2.b"], cfg.ln_eps)
-    h = linear_fwd(u2, p[pre + ".fc1.w"], p[pre + ".fc1.b"])
-    gl = gelu_fwd(h)
-    x2 = x1 + linear_fwd(gl, p[pre + ".fc2.w"], p[pre + ".fc2.b"])
+    u2 = S(u2)
+    h = linear_fwd(u2, W(p[pre + ".fc1.w"]), p[pre + ".fc1.b"])
+    gl = S(gelu_fwd(h))
+    h = S(h)
+    x2 = S(x1 + linear_fwd(gl, W(p[pre + ".fc2.w"]), p[pre + ".fc2.b"]))
     return x2, (c_ln1, u, c_att, o, c_ln2, u2, h, gl)
 
 
-def _encoder_bwd(dx2, cache, p, pre, grads):
+def _encoder_bwd(dx2, cache, p, pre, grads, st):
+    W = st.wmat
     c_ln1, u, c_att, o, c_ln2, u2, h, gl = cache
-    dgl, grads[pre + ".fc2.w"], grads[pre + ".fc2.b"] = linear_bwd(dx2, gl, p[pre + ".fc2.w"])
+    dgl, grads[pre + ".fc2.w"], grads[pre + ".fc2.b"] = linear_bwd(dx2, gl, W(p[pre + ".fc2.w"]))
     dh = gelu_bwd(dgl, h)
-    du2, grads[pre + ".fc1.w"], grads[pre + ".fc1.b"] = linear_bwd(dh, u2, p[pre + ".fc1.w"])
+    du2, grads[pre + ".fc1.w"], grads[pre + ".fc1.b"] = linear_bwd(dh, u2, W(p[pre + ".fc1.w"]))
     d, grads[pre + ".ln2.g"], grads[pre + ".ln2.b"] = layernorm_bwd(du2, c_ln2, p[pre + ".ln2.g"])
     dx1 = dx2 + d
-    do, grads[pre + ".proj.w"], grads[pre + ".proj.b"] = linear_bwd(dx1, o, p[pre + ".proj.w"])
+    do, grads[pre + ".proj.w"], grads[pre + ".proj.b"] = linear_bwd(dx1, o, W(p[pre + ".proj.w"]))
     dqkv = attention_bwd(do, c_att)
-    du, grads[pre + ".qkv.w"], grads[pre + ".qkv.b"] = linear_bwd(dqkv, u, p[pre + ".qkv.w"])
+    du, grads[pre + ".qkv.w"], grads[pre + ".qkv.b"] = linear_bwd(dqkv, u, W(p[pre + ".qkv.w"]))
     d, grads[pre + ".ln1.g"], grads[pre + ".ln1.b"] = layernorm_bwd(du, c_ln1, p[pre + ".ln1.g"])
     return dx1 + d
 
@@ -402,17 +435,18 @@ def vit_forward(st: BlockState, x_in):
     caches = {}
     if cfg.input_kind == IN_IMAGE:
         pt = patchify(x_in, cfg.patch)
-        e = linear_fwd(pt, p["pe.w"], p["pe.b"])
-        x = np.concatenate([np.broadcast_to(p["cls"], (cfg.batch, 1, cfg.dim)), e], axis=1) + p["pos"]
+        e = st.act(linear_fwd(pt, st.wmat(p["pe.w"]), p["pe.b"]))
+        x = st.act(np.concatenate([np.broadcast_to(p["cls"], (cfg.batch, 1, cfg.dim)), e], axis=1) + p["pos"])
         caches["patches"] = pt
     else:
         x = x_in
     for l in range(cfg.depth):
-        x, caches[f"blk{l}"] = _encoder_fwd(x, p, f"blk{l}", cfg)
+        x, caches[f"blk{l}"] = _encoder_fwd(x, p, f"blk{l}", st)
     x_out = x
     for a in range(cfg.aux_depth):
-        x, caches[f"aux{a}"] = _encoder_fwd(x, p, f"aux{a}", cfg)
+        x, caches[f"aux{a}"] = _encoder_fwd(x, p, f"aux{a}", st)
     z, caches["head.ln"] = layernorm_fwd(x[:, 0, :], p["head.ln.g"], p["head.ln.b"], cfg.ln_eps)
+    z = st.act(z)
     caches["z"] = z
     logits = linear_fwd(z, p["head.w"], p["head.b"])
     return x_out, logits, caches
@@ -428,13 +462,13 @@ def vit_backward(st: BlockState, dlogits, caches):
     dx = np.zeros((cfg.batch, cfg.tokens, cfg.dim), dtype=st.dtype)
     dx[:, 0, :] = dcls
     for a in reversed(range(cfg.aux_depth)):
-        dx = _encoder_bwd(dx, caches[f"aux{a}"], p, f"aux{a}", g)
+        dx = _encoder_bwd(dx, caches[f"aux{a}"], p, f"aux{a}", g, st)
     for l in reversed(range(cfg.depth)):
-        dx = _encoder_bwd(dx, caches[f"blk{l}"], p, f"blk{l}", g)
+        dx = _encoder_bwd(dx, caches[f"blk{l}"], p, f"blk{l}", g, st)
     if cfg.input_kind == IN_IMAGE:
         g["pos"] = dx.sum(axis=0)
         g["cls"] = dx[:, 0, :].sum(axis=0)
-        _, g["pe.w"], g["pe.b"] = linear_bwd(dx[:, 1:, :], caches["patches"], p["pe.w"])
+        _, g["pe.w"], g["pe.b"] = linear_bwd(dx[:, 1:, :], caches["patches"], st.wmat(p["pe.w"]))
     return g
 
 
@@ -449,15 +483,15 @@ def _bn_track(st: BlockState, name, cache, n):
 def resnet_forward(st: BlockState, x_in, track=True):
     """n basic blocks: relu(x + bn2(conv2(relu(bn1(conv1(x)))))), then the
     auxiliary head conv3x3/s2 -> BN -> ReLU -> global average -> Linear."""
-    cfg, p = st.cfg, st.params
+    cfg, p, S, W = st.cfg, st.params, st.act, st.wmat
     x = np.asarray(x_in, dtype=st.dtype)
     caches = {}
     for i in range(cfg.n_basic_blocks):
         pre = f"rb{i}"
-        c1 = conv3x3_fwd(x, p[pre + ".conv1.w"], 1)
+        c1 = S(conv3x3_fwd(x, W(p[pre + ".conv1.w"]), 1))
         b1, cb1 = batchnorm_fwd(c1, p[pre + ".bn1.g"], p[pre + ".bn1.b"], cfg.bn_eps)
-        y1 = np.maximum(b1, 0)
-        c2 = conv3x3_fwd(y1, p[pre + ".conv2.w"], 1)
+        y1 = S(np.maximum(b1, 0))
+        c2 = S(conv3x3_fwd(y1, W(p[pre + ".conv2.w"]), 1))
         b2, cb2 = batchnorm_fwd(c2, p[pre + ".bn2.g"], p[pre + ".bn2.b"], cfg.bn_eps)
         s = x + b2
         caches[pre] = (x, cb1, b1, y1, cb2, s)
@@ -465,14 +499,14 @@ def resnet_forward(st: BlockState, x_in, track=True):
             n = c1.size // c1.shape[-1]
             _bn_track(st, pre + ".bn1", cb1, n)
             _bn_track(st, pre + ".bn2", cb2, n)
-        x = np.maximum(s, 0)
+        x = S(np.maximum(s, 0))
     x_out = x
-    ca = conv3x3_fwd(x_out, p["aux.conv.w"], 2)
+    ca = S(conv3x3_fwd(x_out, W(p["aux.conv.w"]), 2))
     ba, cba = batchnorm_fwd(ca, p["aux.bn.g"], p["aux.bn.b"], cfg.bn_eps)
     if track:
         _bn_track(st, "aux.bn", cba, ca.size // ca.shape[-1])
-    ya = np.maximum(ba, 0)
-    pooled = ya.mean(axis=(1, 2))
+    ya = S(np.maximum(ba, 0))
+    pooled = S(ya.mean(axis=(1, 2)))
     logits = linear_fwd(pooled, p["head.w"], p["head.b"])
     caches["aux"] = (x_out, cba, ba, ya, pooled)
     return x_out, logits, caches
@@ -488,19 +522,19 @@ def resnet_backward(st: BlockState, dlogits, caches):
     dba = dya * (ba > 0)
     dca, g["aux.bn.g"], g["aux.bn.b"] = batchnorm_bwd(dba, cba, p["aux.bn.g"])
     g["aux.conv.w"] = conv3x3_bwd_weight(dca, x_out, 2)
-    dx = conv3x3_bwd_input(dca, p["aux.conv.w"], 2, x_out.shape)
+    dx = conv3x3_bwd_input(dca, st.wmat(p["aux.conv.w"]), 2, x_out.shape)
     for i in reversed(range(cfg.n_basic_blocks)):
         pre = f"rb{i}"
         x, cb1, b1, y1, cb2, s = caches[pre]
         ds = dx * (s > 0)
         dc2, g[pre + ".bn2.g"], g[pre + ".bn2.b"] = batchnorm_bwd(ds, cb2, p[pre + ".bn2.g"])
         g[pre + ".conv2.w"] = conv3x3_bwd_weight(dc2, y1, 1)
-        dy1 = conv3x3_bwd_input(dc2, p[pre + ".conv2.w"], 1, y1.shape)
+        dy1 = conv3x3_bwd_input(dc2, st.wmat(p[pre + ".conv2.w"]), 1, y1.shape)
         db1 = dy1 * (b1 > 0)
         dc1, g[pre + ".bn1.g"], g[pre + ".bn1.b"] = batchnorm_bwd(db1, cb1, p[pre + ".bn1.g"])
         g[pre + ".conv1.w"] = conv3x3_bwd_weight(dc1, x, 1)
         if i > 0:   # the first block's input is the detached x_{j-1}
-            dx = ds + conv3x3_bwd_input(dc1, p[pre + ".conv1.w"], 1, x.shape)
+            dx = ds + conv3x3_bwd_input(dc1, st.wmat(p[pre + ".conv1.w"]), 1, x.shape)
     return g
 
 

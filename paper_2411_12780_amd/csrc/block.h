@@ -1,0 +1,104 @@
+// Block engine: the static plan (parameter table, workspace layout) and the
+// kernel sequence of one local-block step (Algorithm 1, loop body of P_j).
+#pragma once
+
+#include <functional>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+namespace ppll {
+
+struct TensorDesc {
+  std::string name;
+  size_t off;        // element offset in the flat fp32 blob
+  size_t n;          // elements
+  int rows, cols;    // [in, out] for matrices, rows = 1 for vectors; conv: rows = 9*Cin, cols = Cout
+};
+
+struct EncoderParams {   // element offsets into the blob
+  size_t ln1_g, ln1_b, qkv_w, qkv_b, proj_w, proj_b, ln2_g, ln2_b, fc1_w, fc1_b, fc2_w, fc2_b;
+};
+struct EncoderActs {     // saved by the forward for the backward
+  void *u1, *qkv, *att, *x1, *u2, *h, *gl, *x2;
+  float *mean1, *rstd1, *mean2, *rstd2, *lse;
+};
+struct BasicBlockParams { size_t conv1_w, bn1_g, bn1_b, conv2_w, bn2_g, bn2_b; };
+struct BasicBlockActs {
+  void *c1, *y1, *c2, *out;
+  float *mean1, *rstd1, *mean2, *rstd2;
+};
+
+struct Block {
+  ppll_block_config cfg{};
+  int dt = F32;              // activation element type
+  size_t esz = 4;
+  bool alive = true;
+
+  std::vector<TensorDesc> tensors;
+  std::vector<std::string> bn_names;
+  std::vector<int> bn_channels;
+  size_t P = 0;              // total parameters
+
+  // workspace carve-up (device)
+  char* ws = nullptr;
+  size_t ws_bytes = 0;
+  float *params = nullptr, *grads = nullptr, *mom1 = nullptr, *mom2 = nullptr;
+  uint16_t* shadow = nullptr;   // bf16 copy of params that the contractions read (bf16 path only)
+  // weight operand of a contraction: the bf16 shadow on the bf16 path, else the fp32 master
+  const void* wptr(size_t off) const { return shadow ? (const void*)(shadow + off) : (const void*)(params + off); }
+  int wdt() const { return shadow ? BF16 : F32; }
+  float *bn_mean_run = nullptr, *bn_var_run = nullptr;   // [sum of BN channels]
+  std::vector<size_t> bn_off;
+  float* loss_dev = nullptr;
+  int* flag_dev = nullptr;
+  float* partials = nullptr;
+  size_t partial_floats = 0;
+
+  // ViT
+  size_t pe_w = 0, pe_b = 0, cls = 0, pos = 0, head_ln_g = 0, head_ln_b = 0, head_w = 0, head_b = 0;
+  std::vector<EncoderParams> enc_p;       // depth + aux_depth
+  std::vector<EncoderActs> enc_a;
+  void *patches = nullptr, *x0 = nullptr, *embed_tmp = nullptr;
+  void *z = nullptr, *dz = nullptr, *dcls = nullptr;
+  float *head_mean = nullptr, *head_rstd = nullptr, *logits = nullptr, *dlogits = nullptr;
+  void *gA = nullptr, *gB = nullptr, *d_u = nullptr, *d_h = nullptr, *d_qkv = nullptr;
+
+  // ResNet
+  std::vector<BasicBlockParams> rb_p;
+  std::vector<BasicBlockActs> rb_a;
+  size_t aux_conv_w = 0, aux_bn_g = 0, aux_bn_b = 0;
+  void *aux_c = nullptr, *aux_y = nullptr, *pooled = nullptr, *dpooled = nullptr, *d_aux = nullptr;
+  float *aux_mean = nullptr, *aux_rstd = nullptr;
+  void *r_gA = nullptr, *r_gB = nullptr, *r_t1 = nullptr, *r_t2 = nullptr;
+
+  long steps = 0;
+  hipStream_t last_stream = nullptr;
+
+  // Builds the parameter table and assigns every workspace pointer relative to
+  // `base` (null: only measure).  Returns the bytes needed.
+  size_t plan(char* base);
+
+  int in_elems() const;
+  int out_elems() const;
+
+  // Forward of the module into x_out; `after_forward` runs on the host right
+  // after the forward kernels are enqueued (the pipeline publishes the slot
+  // there), then auxiliary forward, loss, backward and update are enqueued.
+  int step(const void* x_in, const int32_t* labels, float lr, void* x_out, float* loss_out, hipStream_t s,
+           const std::function<int()>& after_forward);
+
+ private:
+  int vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
+               const std::function<int()>& after_forward);
+  int resnet_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
+                  const std::function<int()>& after_forward);
+  int encoder_fwd(int l, const void* x, void* x2_out, hipStream_t s);
+  int encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void* g_out, bool need_dx, hipStream_t s);
+  int update(float lr, hipStream_t s);
+};
+
+int validate_config(const ppll_block_config* cfg);
+
+}  // namespace ppll

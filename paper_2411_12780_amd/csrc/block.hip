@@ -1,0 +1,443 @@
+// Block engine: parameter table, workspace plan and the kernel sequence of one
+// local-block step (Algorithm 1: forward, push point, local loss, backward that
+// stops at the block input, update).
+#include "block.h"
+
+#include <cmath>
+#include <cstdio>
+
+namespace ppll {
+
+namespace {
+struct Bump {
+  char* base;
+  size_t off = 0;
+  explicit Bump(char* b) : base(b) {}
+  void* take(size_t bytes) {
+    off = (off + 255) & ~(size_t)255;
+    void* p = base ? base + off : nullptr;
+    off += bytes;
+    return p;
+  }
+  float* floats(size_t n) { return (float*)take(n * sizeof(float)); }
+};
+
+GemmArgs gemm_args() {
+  GemmArgs g{};
+  g.epilogue = EPI_NONE;
+  return g;
+}
+}  // namespace
+
+int validate_config(const ppll_block_config* c) {
+  if (!c) { set_error("config is null"); return PPLL_ERR_NULL; }
+  if (c->struct_size != sizeof(ppll_block_config)) {
+    set_error("config struct_size %u, library expects %zu", c->struct_size, sizeof(ppll_block_config));
+    return PPLL_ERR_CONFIG;
+  }
+  auto bad = [](const char* what) { set_error("config: %s", what); return PPLL_ERR_CONFIG; };
+  if (c->precision != PPLL_FP32 && c->precision != PPLL_BF16) return bad("precision must be PPLL_FP32 or PPLL_BF16");
+  if (c->optimizer != PPLL_SGD && c->optimizer != PPLL_ADAMW) return bad("optimizer must be PPLL_SGD or PPLL_ADAMW");
+  if (c->batch < 1 || c->batch > 65536) return bad("batch outside 1..65536");
+  if (c->num_classes < 2 || c->num_classes > 1024) return bad("num_classes outside 2..1024");
+  if (c->arch == PPLL_VIT) {
+    if (c->input_kind != PPLL_IN_IMAGE && c->input_kind != PPLL_IN_ACTIVATION) return bad("input_kind");
+    if (c->dim < 1 || c->heads < 1 || c->dim % c->heads) return bad("dim must be a positive multiple of heads");
+    if (c->dim > 1536) return bad("dim above 1536");
+    if (c->mlp_dim < 1 || c->depth < 1 || c->aux_depth < 0) return bad("mlp_dim, depth >= 1 and aux_depth >= 0 required");
+    if (c->tokens < 1 || c->tokens > 256) return bad("tokens outside 1..256");
+    if (c->ln_eps <= 0.f) return bad("ln_eps must be positive");
+    if (c->input_kind == PPLL_IN_IMAGE) {
+      if (c->patch < 1 || c->img_h < 1 || c->img_w < 1 || c->img_c < 1 || c->img_h % c->patch || c->img_w % c->patch)
+        return bad("image size must be a positive multiple of patch");
+      if ((c->img_h / c->patch) * (c->img_w / c->patch) + 1 != c->tokens)
+        return bad("tokens must equal (img_h/patch)*(img_w/patch) + 1");
+    }
+  } else if (c->arch == PPLL_RESNET) {
+    if (c->input_kind != PPLL_IN_ACTIVATION) return bad("ResNet blocks take activations");
+    if (c->channels < 1 || c->aux_channels < 1 || c->height < 2 || c->width < 2 || c->n_basic_blocks < 1)
+      return bad("channels, aux_channels, n_basic_blocks >= 1 and height, width >= 2 required");
+    if (c->bn_eps <= 0.f || c->bn_momentum < 0.f || c->bn_momentum > 1.f) return bad("bn_eps > 0 and bn_momentum in [0,1] required");
+  } else {
+    return bad("arch must be PPLL_VIT or PPLL_RESNET");
+  }
+  return PPLL_OK;
+}
+
+int Block::in_elems() const {
+  if (cfg.arch == PPLL_VIT)
+    return cfg.input_kind == PPLL_IN_IMAGE ? cfg.batch * cfg.img_h * cfg.img_w * cfg.img_c
+                                           : cfg.batch * cfg.tokens * cfg.dim;
+  return cfg.batch * cfg.height * cfg.width * cfg.channels;
+}
+int Block::out_elems() const {
+  if (cfg.arch == PPLL_VIT) return cfg.batch * cfg.tokens * cfg.dim;
+  return cfg.batch * cfg.height * cfg.width * cfg.channels;
+}
+
+size_t Block::plan(char* base) {
+  dt = cfg.precision == PPLL_BF16 ? BF16 : F32;
+  esz = dtype_size(dt);
+  tensors.clear(); enc_p.clear(); enc_a.clear(); rb_p.clear(); rb_a.clear();
+  bn_names.clear(); bn_channels.clear(); bn_off.clear();
+  size_t off = 0;
+  auto add = [&](const std::string& name, int rows, int cols) {
+    size_t o = off;
+    tensors.push_back({name, o, (size_t)rows * cols, rows, cols});
+    off += (size_t)rows * cols;
+    return o;
+  };
+  const int B = cfg.batch, C = cfg.num_classes;
+  if (cfg.arch == PPLL_VIT) {
+    const int D = cfg.dim, F = cfg.mlp_dim;
+    if (cfg.input_kind == PPLL_IN_IMAGE) {
+      pe_w = add("pe.w", cfg.patch * cfg.patch * cfg.img_c, D);
+      pe_b = add("pe.b", 1, D);
+      cls = add("cls", 1, D);
+      pos = add("pos", cfg.tokens, D);
+    }
+    for (int l = 0; l < cfg.depth + cfg.aux_depth; ++l) {
+      char pre[32];
+      if (l < cfg.depth) snprintf(pre, sizeof pre, "blk%d", l); else snprintf(pre, sizeof pre, "aux%d", l - cfg.depth);
+      std::string p(pre);
+      EncoderParams e;
+      e.ln1_g = add(p + ".ln1.g", 1, D); e.ln1_b = add(p + ".ln1.b", 1, D);
+      e.qkv_w = add(p + ".qkv.w", D, 3 * D); e.qkv_b = add(p + ".qkv.b", 1, 3 * D);
+      e.proj_w = add(p + ".proj.w", D, D); e.proj_b = add(p + ".proj.b", 1, D);
+      e.ln2_g = add(p + ".ln2.g", 1, D); e.ln2_b = add(p + ".ln2.b", 1, D);
+      e.fc1_w = add(p + ".fc1.w", D, F); e.fc1_b = add(p + ".fc1.b", 1, F);
+      e.fc2_w = add(p + ".fc2.w", F, D); e.fc2_b = add(p + ".fc2.b", 1, D);
+      enc_p.push_back(e);
+    }
+    head_ln_g = add("head.ln.g", 1, D); head_ln_b = add("head.ln.b", 1, D);
+    head_w = add("head.w", D, C); head_b = add("head.b", 1, C);
+  } else {
+    const int Ch = cfg.channels, A = cfg.aux_channels;
+    for (int i = 0; i < cfg.n_basic_blocks; ++i) {
+      std::string p = "rb" + std::to_string(i);
+      BasicBlockParams r;
+      r.conv1_w = add(p + ".conv1.w", 9 * Ch, Ch); r.bn1_g = add(p + ".bn1.g", 1, Ch); r.bn1_b = add(p + ".bn1.b", 1, Ch);
+      r.conv2_w = add(p + ".conv2.w", 9 * Ch, Ch); r.bn2_g = add(p + ".bn2.g", 1, Ch); r.bn2_b = add(p + ".bn2.b", 1, Ch);
+      rb_p.push_back(r);
+      bn_names.push_back(p + ".bn1"); bn_channels.push_back(Ch);
+      bn_names.push_back(p + ".bn2"); bn_channels.push_back(Ch);
+    }
+    aux_conv_w = add("aux.conv.w", 9 * Ch, A); aux_bn_g = add("aux.bn.g", 1, A); aux_bn_b = add("aux.bn.b", 1, A);
+    bn_names.push_back("aux.bn"); bn_channels.push_back(A);
+    head_w = add("head.w", A, C); head_b = add("head.b", 1, C);
+  }
+  P = off;
+
+  Bump bump(base);
+  params = bump.floats(P); grads = bump.floats(P); mom1 = bump.floats(P);
+  mom2 = cfg.optimizer == PPLL_ADAMW ? bump.floats(P) : nullptr;
+  shadow = dt == BF16 ? (uint16_t*)bump.take(P * sizeof(uint16_t)) : nullptr;
+  size_t bn_total = 0;
+  for (int c : bn_channels) { bn_off.push_back(bn_total); bn_total += c; }
+  bn_mean_run = bump.floats(bn_total ? bn_total : 1);
+  bn_var_run = bump.floats(bn_total ? bn_total : 1);
+  loss_dev = bump.floats(1);
+  flag_dev = (int*)bump.take(sizeof(int));
+  logits = bump.floats((size_t)B * C);
+  dlogits = bump.floats((size_t)B * C);
+
+  if (cfg.arch == PPLL_VIT) {
+    const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads;
+    const size_t M = (size_t)B * T;
+    if (cfg.input_kind == PPLL_IN_IMAGE) {
+      patches = bump.take((size_t)B * (T - 1) * cfg.patch * cfg.patch * cfg.img_c * esz);
+      embed_tmp = bump.take((size_t)B * (T - 1) * D * esz);
+      x0 = bump.take(M * D * esz);
+    }
+    for (int l = 0; l < cfg.depth + cfg.aux_depth; ++l) {
+      EncoderActs a;
+      a.u1 = bump.take(M * D * esz); a.qkv = bump.take(M * 3 * D * esz); a.att = bump.take(M * D * esz);
+      a.x1 = bump.take(M * D * esz); a.u2 = bump.take(M * D * esz);
+      a.h = bump.take(M * F * esz); a.gl = bump.take(M * F * esz);
+      a.x2 = bump.take(M * D * esz);
+      a.mean1 = bump.floats(M); a.rstd1 = bump.floats(M); a.mean2 = bump.floats(M); a.rstd2 = bump.floats(M);
+      a.lse = bump.floats((size_t)B * H * T);
+      enc_a.push_back(a);
+    }
+    z = bump.take((size_t)B * D * esz); dz = bump.take((size_t)B * D * esz); dcls = bump.take((size_t)B * D * esz);
+    head_mean = bump.floats(B); head_rstd = bump.floats(B);
+    gA = bump.take(M * D * esz); gB = bump.take(M * D * esz); d_u = bump.take(M * D * esz);
+    d_h = bump.take(M * F * esz); d_qkv = bump.take(M * 3 * D * esz);
+    int widest = 3 * D > F ? 3 * D : F;
+    partial_floats = (size_t)colsum_partial_floats((int)M, widest);
+    size_t ln = (size_t)layernorm_bwd_partial_floats((int)M, D);
+    if (ln > partial_floats) partial_floats = ln;
+  } else {
+    const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
+    const size_t act = (size_t)B * Hh * W * Ch;
+    const int Ho = (Hh - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
+    const size_t aact = (size_t)B * Ho * Wo * A;
+    for (int i = 0; i < cfg.n_basic_blocks; ++i) {
+      BasicBlockActs a;
+      a.c1 = bump.take(act * esz); a.y1 = bump.take(act * esz); a.c2 = bump.take(act * esz); a.out = bump.take(act * esz);
+      a.mean1 = bump.floats(Ch); a.rstd1 = bump.floats(Ch); a.mean2 = bump.floats(Ch); a.rstd2 = bump.floats(Ch);
+      rb_a.push_back(a);
+    }
+    aux_c = bump.take(aact * esz); aux_y = bump.take(aact * esz); d_aux = bump.take(aact * esz);
+    pooled = bump.take((size_t)B * A * esz); dpooled = bump.take((size_t)B * A * esz);
+    aux_mean = bump.floats(A); aux_rstd = bump.floats(A);
+    r_gA = bump.take(act * esz); r_t1 = bump.take(act * esz); r_t2 = bump.take(act * esz);
+    partial_floats = (size_t)conv3x3_wgrad_partial_floats(B, Hh, W, Ch, Ch, 1);
+    size_t o = (size_t)conv3x3_wgrad_partial_floats(B, Hh, W, Ch, A, 2);
+    if (o > partial_floats) partial_floats = o;
+    o = (size_t)bn_partial_floats(B * Hh * W, Ch > A ? Ch : A);
+    if (o > partial_floats) partial_floats = o;
+  }
+  size_t o = (size_t)colsum_partial_floats(B, C);
+  if (o > partial_floats) partial_floats = o;
+  partials = bump.floats(partial_floats);
+  return (bump.off + 255) & ~(size_t)255;
+}
+
+// ------------------------------------------------------------------ ViT
+int Block::encoder_fwd(int l, const void* x, void* x2_out, hipStream_t s) {
+  const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, M = cfg.batch * T;
+  const EncoderParams& p = enc_p[l];
+  EncoderActs& a = enc_a[l];
+  PPLL_TRY(launch_layernorm_fwd(s, x, dt, D, M, D, params + p.ln1_g, params + p.ln1_b, cfg.ln_eps, a.u1, a.mean1, a.rstd1));
+  GemmArgs g = gemm_args();
+  g.A = a.u1; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+  g.B = wptr(p.qkv_w); g.b_dt = wdt(); g.b_sk = 3 * D; g.b_sn = 1;
+  g.C = a.qkv; g.c_dt = dt; g.ldc = 3 * D; g.M = M; g.N = 3 * D; g.K = D; g.bias = params + p.qkv_b;
+  PPLL_TRY(launch_gemm(s, g));
+  PPLL_TRY(launch_attention_fwd(s, a.qkv, dt, cfg.batch, T, H, D / H, a.att, a.lse));
+  g = gemm_args();
+  g.A = a.att; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+  g.B = wptr(p.proj_w); g.b_dt = wdt(); g.b_sk = D; g.b_sn = 1;
+  g.C = a.x1; g.c_dt = dt; g.ldc = D; g.M = M; g.N = D; g.K = D; g.bias = params + p.proj_b;
+  g.residual = x; g.r_dt = dt; g.ldr = D;
+  PPLL_TRY(launch_gemm(s, g));
+  PPLL_TRY(launch_layernorm_fwd(s, a.x1, dt, D, M, D, params + p.ln2_g, params + p.ln2_b, cfg.ln_eps, a.u2, a.mean2, a.rstd2));
+  g = gemm_args();
+  g.A = a.u2; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+  g.B = wptr(p.fc1_w); g.b_dt = wdt(); g.b_sk = F; g.b_sn = 1;
+  g.C = a.h; g.c_dt = dt; g.ldc = F; g.M = M; g.N = F; g.K = D; g.bias = params + p.fc1_b;
+  g.epilogue = EPI_GELU; g.C2 = a.gl;
+  PPLL_TRY(launch_gemm(s, g));
+  g = gemm_args();
+  g.A = a.gl; g.a_dt = dt; g.a_sm = F; g.a_sk = 1;
+  g.B = wptr(p.fc2_w); g.b_dt = wdt(); g.b_sk = D; g.b_sn = 1;
+  g.C = x2_out; g.c_dt = dt; g.ldc = D; g.M = M; g.N = D; g.K = F; g.bias = params + p.fc2_b;
+  g.residual = a.x1; g.r_dt = dt; g.ldr = D;
+  return launch_gemm(s, g);
+}
+
+// g_in: gradient w.r.t. the layer output; g_tmp receives the gradient at the
+// mid-layer residual; g_out (may alias g_in) the gradient w.r.t. the layer input.
+int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void* g_out, bool need_dx, hipStream_t s) {
+  const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, M = cfg.batch * T;
+  const EncoderParams& p = enc_p[l];
+  EncoderActs& a = enc_a[l];
+  // dY W^T with W stored [in,out]:  B(k = out index, n = in index) = W[n*out + k]
+  auto dgrad = [&](const void* dy, int out_dim, size_t w_off, int in_dim, void* dxo) {
+    GemmArgs g = gemm_args();
+    g.A = dy; g.a_dt = dt; g.a_sm = out_dim; g.a_sk = 1;
+    g.B = wptr(w_off); g.b_dt = wdt(); g.b_sk = 1; g.b_sn = out_dim;
+    g.C = dxo; g.c_dt = dt; g.ldc = in_dim; g.M = M; g.N = in_dim; g.K = out_dim;
+    return g;
+  };
+  // dW[in,out] = X^T dY, reduction over the M rows
+  auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off) {
+    GemmArgs g = gemm_args();
+    g.A = xin; g.a_dt = dt; g.a_sm = 1; g.a_sk = in_dim;
+    g.B = dy; g.b_dt = dt; g.b_sk = out_dim; g.b_sn = 1;
+    g.C = grads + w_off; g.c_dt = F32; g.ldc = out_dim; g.M = in_dim; g.N = out_dim; g.K = M;
+    return launch_gemm(s, g);
+  };
+  GemmArgs g = dgrad(g_in, D, p.fc2_w, F, d_h);
+  g.epilogue = EPI_DGELU; g.aux = a.h; g.aux_dt = dt; g.ldaux = F;
+  PPLL_TRY(launch_gemm(s, g));
+  PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w));
+  PPLL_TRY(launch_colsum(s, g_in, dt, M, D, partials, grads + p.fc2_b));
+  PPLL_TRY(launch_gemm(s, dgrad(d_h, F, p.fc1_w, D, d_u)));
+  PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w));
+  PPLL_TRY(launch_colsum(s, d_h, dt, M, F, partials, grads + p.fc1_b));
+  PPLL_TRY(launch_layernorm_bwd(s, d_u, a.x1, dt, D, M, D, params + p.ln2_g, a.mean2, a.rstd2, g_in, g_tmp, partials,
+                                grads + p.ln2_g, grads + p.ln2_b));
+  PPLL_TRY(launch_gemm(s, dgrad(g_tmp, D, p.proj_w, D, d_u)));
+  PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w));
+  PPLL_TRY(launch_colsum(s, g_tmp, dt, M, D, partials, grads + p.proj_b));
+  PPLL_TRY(launch_attention_bwd(s, a.qkv, a.att, d_u, a.lse, dt, cfg.batch, T, H, D / H, d_qkv));
+  PPLL_TRY(launch_gemm(s, dgrad(d_qkv, 3 * D, p.qkv_w, D, d_u)));
+  PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w));
+  PPLL_TRY(launch_colsum(s, d_qkv, dt, M, 3 * D, partials, grads + p.qkv_b));
+  return launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, g_tmp,
+                              need_dx ? g_out : nullptr, partials, grads + p.ln1_g, grads + p.ln1_b);
+}
+
+int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
+                    const std::function<int()>& after_forward) {
+  const int B = cfg.batch, D = cfg.dim, T = cfg.tokens, C = cfg.num_classes, M = B * T;
+  const int L = cfg.depth, A = cfg.aux_depth;
+  const bool image = cfg.input_kind == PPLL_IN_IMAGE;
+  const int ppc = cfg.patch * cfg.patch * cfg.img_c;
+  std::vector<const void*> layer_in(L + A);
+  // ---- module forward
+  const void* x = x_in;
+  if (image) {
+    PPLL_TRY(launch_patchify(s, x_in, dt, B, cfg.img_h, cfg.img_w, cfg.img_c, cfg.patch, patches));
+    GemmArgs g = gemm_args();
+    g.A = patches; g.a_dt = dt; g.a_sm = ppc; g.a_sk = 1;
+    g.B = wptr(pe_w); g.b_dt = wdt(); g.b_sk = D; g.b_sn = 1;
+    g.C = embed_tmp; g.c_dt = dt; g.ldc = D; g.M = B * (T - 1); g.N = D; g.K = ppc; g.bias = params + pe_b;
+    if (T > 1) PPLL_TRY(launch_gemm(s, g));
+    PPLL_TRY(launch_assemble_tokens(s, embed_tmp, dt, params + cls, params + pos, B, T, D, x0));
+    x = x0;
+  }
+  for (int l = 0; l < L; ++l) {
+    layer_in[l] = x;
+    void* dst = l == L - 1 ? x_out : enc_a[l].x2;
+    PPLL_TRY(encoder_fwd(l, x, dst, s));
+    x = dst;
+  }
+  if (after_forward) PPLL_TRY(after_forward());
+  // ---- auxiliary forward
+  for (int l = L; l < L + A; ++l) {
+    layer_in[l] = x;
+    PPLL_TRY(encoder_fwd(l, x, enc_a[l].x2, s));
+    x = enc_a[l].x2;
+  }
+  PPLL_TRY(launch_layernorm_fwd(s, x, dt, (long)T * D, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, z,
+                                head_mean, head_rstd));
+  GemmArgs g = gemm_args();
+  g.A = z; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+  g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+  g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = D; g.bias = params + head_b;
+  PPLL_TRY(launch_gemm_generic(s, g));
+  // ---- local loss
+  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, dlogits, flag_dev));
+  // ---- backward: head
+  g = gemm_args();
+  g.A = z; g.a_dt = dt; g.a_sm = 1; g.a_sk = D;
+  g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+  g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = D; g.N = C; g.K = B;
+  PPLL_TRY(launch_gemm_generic(s, g));
+  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, partials, grads + head_b));
+  g = gemm_args();
+  g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
+  g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
+  g.C = dz; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = C;
+  PPLL_TRY(launch_gemm_generic(s, g));
+  PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
+                                partials, grads + head_ln_g, grads + head_ln_b));
+  PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, gA));
+  // ---- backward: auxiliary layers then module layers; the chain stops at x_in
+  for (int l = L + A - 1; l >= 0; --l) {
+    bool need_dx = l > 0 || image;
+    PPLL_TRY(encoder_bwd(l, layer_in[l], gA, gB, gA, need_dx, s));
+  }
+  if (image) {
+    PPLL_TRY(launch_embed_bwd(s, gA, dt, B, T, D, grads + pos, grads + cls, embed_tmp));
+    if (T > 1) {
+      g = gemm_args();
+      g.A = patches; g.a_dt = dt; g.a_sm = 1; g.a_sk = ppc;
+      g.B = embed_tmp; g.b_dt = dt; g.b_sk = D; g.b_sn = 1;
+      g.C = grads + pe_w; g.c_dt = F32; g.ldc = D; g.M = ppc; g.N = D; g.K = B * (T - 1);
+      PPLL_TRY(launch_gemm(s, g));
+      PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, partials, grads + pe_b));
+    } else {
+      PPLL_TRY(launch_fill_zero(s, grads + pe_w, ((size_t)ppc * D + D) * sizeof(float)));
+    }
+  }
+  (void)M;
+  return PPLL_OK;
+}
+
+// ------------------------------------------------------------------ ResNet
+int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
+                       const std::function<int()>& after_forward) {
+  const int B = cfg.batch, Ch = cfg.channels, A = cfg.aux_channels, H = cfg.height, W = cfg.width;
+  const int C = cfg.num_classes, n = cfg.n_basic_blocks, rows = B * H * W;
+  const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1, arows = B * Ho * Wo;
+  const float eps = cfg.bn_eps, mom = cfg.bn_momentum;
+  std::vector<const void*> block_in(n);
+  std::vector<void*> block_out(n);
+  const void* x = x_in;
+  for (int i = 0; i < n; ++i) {
+    const BasicBlockParams& p = rb_p[i];
+    BasicBlockActs& a = rb_a[i];
+    block_in[i] = x;
+    block_out[i] = i == n - 1 ? x_out : a.out;
+    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c1));
+    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, Ch, eps, mom, partials, a.mean1, a.rstd1, bn_mean_run + bn_off[2 * i],
+                             bn_var_run + bn_off[2 * i]));
+    PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
+    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c2));
+    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, Ch, eps, mom, partials, a.mean2, a.rstd2, bn_mean_run + bn_off[2 * i + 1],
+                             bn_var_run + bn_off[2 * i + 1]));
+    PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, x, block_out[i]));
+    x = block_out[i];
+  }
+  if (after_forward) PPLL_TRY(after_forward());
+  // ---- auxiliary forward
+  PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
+  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, aux_mean, aux_rstd, bn_mean_run + bn_off[2 * n],
+                           bn_var_run + bn_off[2 * n]));
+  PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
+  PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
+  GemmArgs g = gemm_args();
+  g.A = pooled; g.a_dt = dt; g.a_sm = A; g.a_sk = 1;
+  g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+  g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = A; g.bias = params + head_b;
+  PPLL_TRY(launch_gemm_generic(s, g));
+  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, dlogits, flag_dev));
+  // ---- backward: head and auxiliary net
+  g = gemm_args();
+  g.A = pooled; g.a_dt = dt; g.a_sm = 1; g.a_sk = A;
+  g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+  g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = A; g.N = C; g.K = B;
+  PPLL_TRY(launch_gemm_generic(s, g));
+  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, partials, grads + head_b));
+  g = gemm_args();
+  g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
+  g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
+  g.C = dpooled; g.c_dt = dt; g.ldc = A; g.M = B; g.N = A; g.K = C;
+  PPLL_TRY(launch_gemm_generic(s, g));
+  PPLL_TRY(launch_gap_bwd(s, dpooled, dt, B, Ho * Wo, A, d_aux));
+  PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials,
+                         grads + aux_bn_g, grads + aux_bn_b, d_aux));
+  PPLL_TRY(launch_conv3x3_wgrad(s, x, d_aux, dt, B, H, W, Ch, A, 2, partials, grads + aux_conv_w));
+  PPLL_TRY(launch_conv3x3_dgrad(s, d_aux, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, nullptr, nullptr, r_gA));
+  // ---- backward: basic blocks, last to first; nothing is produced for x_in
+  for (int i = n - 1; i >= 0; --i) {
+    const BasicBlockParams& p = rb_p[i];
+    BasicBlockActs& a = rb_a[i];
+    PPLL_TRY(launch_bn_bwd(s, r_gA, block_out[i], a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, partials,
+                           grads + p.bn2_g, grads + p.bn2_b, r_t2));
+    PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, H, W, Ch, Ch, 1, partials, grads + p.conv2_w));
+    PPLL_TRY(launch_conv3x3_dgrad(s, r_t2, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, nullptr, nullptr, r_t1));
+    PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, partials,
+                           grads + p.bn1_g, grads + p.bn1_b, r_t1));
+    PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, H, W, Ch, Ch, 1, partials, grads + p.conv1_w));
+    if (i > 0)
+      PPLL_TRY(launch_conv3x3_dgrad(s, r_t1, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, r_gA, block_out[i], r_gA));
+  }
+  return PPLL_OK;
+}
+
+// ------------------------------------------------------------------ update
+int Block::update(float lr, hipStream_t s) {
+  ++steps;
+  if (cfg.optimizer == PPLL_SGD)
+    return launch_sgd(s, params, grads, mom1, shadow, P, lr, cfg.momentum, cfg.nesterov, cfg.weight_decay, steps == 1);
+  float bc1 = (float)(1.0 - std::pow((double)cfg.beta1, (double)steps));
+  float bc2 = (float)(1.0 - std::pow((double)cfg.beta2, (double)steps));
+  return launch_adamw(s, params, grads, mom1, mom2, shadow, P, lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay, bc1, bc2);
+}
+
+int Block::step(const void* x_in, const int32_t* labels, float lr, void* x_out, float* loss_out, hipStream_t s,
+                const std::function<int()>& after_forward) {
+  last_stream = s;
+  if (cfg.arch == PPLL_VIT) PPLL_TRY(vit_step(x_in, labels, x_out, s, after_forward));
+  else PPLL_TRY(resnet_step(x_in, labels, x_out, s, after_forward));
+  PPLL_TRY(update(lr, s));
+  if (loss_out) PPLL_HIP(hipMemcpyAsync(loss_out, loss_dev, sizeof(float), hipMemcpyDeviceToDevice, s));
+  return PPLL_OK;
+}
+
+}  // namespace ppll

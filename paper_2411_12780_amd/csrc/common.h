@@ -1,0 +1,162 @@
+// Shared declarations of the HIP implementation: element types, error plumbing
+// and the launcher interface between the block engine and the kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/ppll.h"
+
+namespace ppll {
+
+// Element type of a buffer as seen by a kernel.
+enum DType : int { F32 = 0, BF16 = 1 };
+inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
+
+void set_error(const char* fmt, ...);
+
+#define PPLL_HIP(expr)                                                              \
+  do {                                                                              \
+    hipError_t e__ = (expr);                                                        \
+    if (e__ != hipSuccess) {                                                        \
+      ::ppll::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e__),     \
+                        __FILE__, __LINE__);                                        \
+      return PPLL_ERR_HIP;                                                          \
+    }                                                                               \
+  } while (0)
+
+#define PPLL_TRY(expr)                \
+  do {                                \
+    int s__ = (expr);                 \
+    if (s__ != PPLL_OK) return s__;   \
+  } while (0)
+
+#ifdef __HIPCC__
+// bf16 <-> fp32 by bit manipulation, round to nearest even.
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float ld_f(const void* p, size_t i, int dt) {
+  return dt == BF16 ? bf16_to_f32(((const uint16_t*)p)[i]) : ((const float*)p)[i];
+}
+__device__ __forceinline__ void st_f(void* p, size_t i, float v, int dt) {
+  if (dt == BF16) ((uint16_t*)p)[i] = f32_to_bf16(v);
+  else ((float*)p)[i] = v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// Orders LDS traffic between the lanes of one wave (writes before, reads after).
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+#endif
+
+// ---------------------------------------------------------------- GEMM
+// C[m,n] = sum_k A(m,k) B(k,n), fp32 accumulation, element strides for both
+// operands so that one routine covers Y = X W, dX = dY W^T and dW = X^T dY.
+enum Epilogue : int {
+  EPI_NONE = 0,   // C = acc (+bias) (+residual)
+  EPI_GELU = 1,   // C = acc + bias (pre-activation), C2 = gelu(C)
+  EPI_DGELU = 2   // C = acc * gelu'(aux)   (aux = saved pre-activation)
+};
+struct GemmArgs {
+  const void* A; int a_dt; long a_sm, a_sk;   // A(m,k) = A[m*a_sm + k*a_sk]
+  const void* B; int b_dt; long b_sk, b_sn;   // B(k,n) = B[k*b_sk + n*b_sn]
+  void* C; int c_dt; long ldc;                // row-major output
+  int M, N, K;
+  const float* bias;                          // [N] fp32 or null
+  const void* residual; int r_dt; long ldr;   // [M,N] or null
+  int epilogue;
+  void* C2;                                   // EPI_GELU second output (c_dt, ldc)
+  const void* aux; int aux_dt; long ldaux;    // EPI_DGELU saved pre-activation
+};
+int launch_gemm(hipStream_t s, const GemmArgs& g);          // picks the MFMA kernel when the shape allows
+int launch_gemm_generic(hipStream_t s, const GemmArgs& g);
+int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out);
+int colsum_mode(hipStream_t s, const void* x, int dt, int rows, int N, int mode, const float* shift, float scale,
+                float* partials, float* out);
+
+// ---------------------------------------------------------------- row-wise ops
+int launch_layernorm_fwd(hipStream_t s, const void* x, int dt, long x_row_stride, int rows, int D,
+                         const float* g, const float* b, float eps, void* y, float* mean, float* rstd);
+// dx_out = dres + LN'(dy) (either may be null); partial sums of dg/db go to
+// `partials` [nchunks][2][D] and are reduced into dg, db.
+int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, long x_row_stride, int rows,
+                         int D, const float* g, const float* mean, const float* rstd, const void* dres,
+                         void* dx_out, float* partials, float* dg, float* db);
+int layernorm_bwd_partial_floats(int rows, int D);
+
+// out[n] = sum over rows of x[r, n]  (two-stage, deterministic)
+int launch_colsum(hipStream_t s, const void* x, int dt, int rows, int N, float* partials, float* out);
+int colsum_partial_floats(int rows, int N);
+
+int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labels, int B, int C,
+                         float* loss, float* dlogits, int* flag);
+
+// ---------------------------------------------------------------- ViT pieces
+int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W, int C, int P, void* patches);
+int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cls, const float* pos, int B,
+                           int T, int D, void* x0);
+// dpos[t,d] = sum_b dx[b,t,d]; dcls[d] = dpos[0,d]; dE = dx[:,1:,:] gathered
+int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* dpos, float* dcls,
+                     void* dE);
+// dx[b,0,:] = dcls[b,:], every other row 0
+int launch_scatter_cls(hipStream_t s, const void* dcls, int dt, int B, int T, int D, void* dx);
+
+int launch_attention_fwd(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out,
+                         float* lse);
+int launch_attention_bwd(hipStream_t s, const void* qkv, const void* out, const void* dout, const float* lse,
+                         int dt, int B, int T, int H, int dh, void* dqkv);
+int launch_attention_fwd_generic(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out,
+                                 float* lse);
+int launch_attention_bwd_generic(hipStream_t s, const void* qkv, const void* out, const void* dout,
+                                 const float* lse, int dt, int B, int T, int H, int dh, void* dqkv);
+
+// ---------------------------------------------------------------- optimizers
+// `shadow` (nullable): bf16 copy of the updated parameters, same offsets
+int launch_sgd(hipStream_t s, float* p, const float* g, float* buf, uint16_t* shadow, size_t n, float lr,
+               float momentum, int nesterov, float wd, int first);
+int launch_adamw(hipStream_t s, float* p, const float* g, float* m, float* v, uint16_t* shadow, size_t n, float lr,
+                 float b1, float b2, float eps, float wd, float bias_corr1, float bias_corr2);
+int launch_refresh_shadow(hipStream_t s, const float* p, uint16_t* shadow, size_t n);
+int launch_fill_zero(hipStream_t s, void* p, size_t bytes);
+
+// ---------------------------------------------------------------- ResNet pieces
+int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
+                       int Co, int stride, void* y);
+// dx = dgrad(dy, w) (+ dres * (ymask > 0) when dres != null)
+int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
+                         int Co, int stride, const void* dres, const void* ymask, void* dx);
+int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci,
+                         int Co, int stride, float* partials, float* dw);
+int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
+// training-mode statistics over rows of x [rows, C]; also updates running stats
+int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum,
+                    float* partials, float* mean, float* rstd, float* run_mean, float* run_var);
+// y = relu(bn(x) (+ res))
+int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const float* mean, const float* rstd,
+                    const float* g, const float* b, const void* res, void* y);
+// dyh = dy * (y > 0); dx = bn'(dyh); dg = sum dyh*xhat; db = sum dyh
+int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
+                  const float* mean, const float* rstd, const float* g, float* partials, float* dg, float* db,
+                  void* dx);
+int bn_partial_floats(int rows, int C);
+int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, void* pooled);
+int launch_gap_bwd(hipStream_t s, const void* dpooled, int dt, int B, int HW, int C, void* dx);
+
+}  // namespace ppll

@@ -1,0 +1,605 @@
+// Straightforward kernels that serve both precisions (element type chosen at
+// run time): strided GEMM with fp32 accumulation, LayerNorm, column sums,
+// cross-entropy, the ViT embedding pieces, a per-(batch, head) attention and
+// the optimizers.  They carry the fp32 path and every shape the MFMA kernels do
+// not take.  All reductions are ordered (no float atomics), so results are
+// reproducible run to run.
+#include "common.h"
+
+namespace ppll {
+
+// ===================================================================== GEMM
+namespace {
+constexpr int GT = 64;   // tile edge in M and N
+constexpr int GK = 16;   // tile depth
+
+__device__ __forceinline__ float gelu_f(float h) { return 0.5f * h * (1.0f + erff(h * 0.70710678118654752f)); }
+__device__ __forceinline__ float dgelu_f(float h) {
+  float cdf = 0.5f * (1.0f + erff(h * 0.70710678118654752f));
+  float pdf = 0.39894228040143268f * __expf(-0.5f * h * h);
+  return cdf + h * pdf;
+}
+
+__global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g) {
+  __shared__ float As[GK][GT + 4];
+  __shared__ float Bs[GK][GT + 4];
+  const int tid = threadIdx.x;
+  const int m0 = blockIdx.y * GT, n0 = blockIdx.x * GT;
+  const int tm = (tid / 16) * 4, tn = (tid % 16) * 4;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < g.K; k0 += GK) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      int idx = tid + r * 256;
+      int m, k;
+      if (g.a_sk == 1) { m = idx / GK; k = idx % GK; } else { k = idx / GT; m = idx % GT; }
+      float v = 0.f;
+      if (m0 + m < g.M && k0 + k < g.K) v = ld_f(g.A, (size_t)((long)(m0 + m) * g.a_sm + (long)(k0 + k) * g.a_sk), g.a_dt);
+      As[k][m] = v;
+      int n;
+      if (g.b_sk == 1) { n = idx / GK; k = idx % GK; } else { k = idx / GT; n = idx % GT; }
+      v = 0.f;
+      if (n0 + n < g.N && k0 + k < g.K) v = ld_f(g.B, (size_t)((long)(k0 + k) * g.b_sk + (long)(n0 + n) * g.b_sn), g.b_dt);
+      Bs[k][n] = v;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < GK; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[k][tm + i]; b[i] = Bs[k][tn + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int m = m0 + tm + i;
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int n = n0 + tn + j;
+      if (n >= g.N) continue;
+      float v = acc[i][j];
+      if (g.bias) v += g.bias[n];
+      if (g.residual) v += ld_f(g.residual, (size_t)((long)m * g.ldr + n), g.r_dt);
+      size_t o = (size_t)((long)m * g.ldc + n);
+      if (g.epilogue == EPI_GELU) {
+        st_f(g.C, o, v, g.c_dt);
+        st_f(g.C2, o, gelu_f(v), g.c_dt);
+      } else if (g.epilogue == EPI_DGELU) {
+        st_f(g.C, o, v * dgelu_f(ld_f(g.aux, (size_t)((long)m * g.ldaux + n), g.aux_dt)), g.c_dt);
+      } else {
+        st_f(g.C, o, v, g.c_dt);
+      }
+    }
+  }
+}
+}  // namespace
+
+int launch_gemm_generic(hipStream_t s, const GemmArgs& g) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) { set_error("gemm: empty shape %d x %d x %d", g.M, g.N, g.K); return PPLL_ERR_SHAPE; }
+  dim3 grid((g.N + GT - 1) / GT, (g.M + GT - 1) / GT);
+  hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, s, g);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+// ===================================================================== reductions over rows
+namespace {
+constexpr int RED_ROWS = 64;   // rows per partial
+
+// partial[c][n] = sum_{r in chunk c} f(x[r,n]);  mode 0: x, mode 1: (x - shift[n])^2
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const void* x, int dt, int rows, int N, int mode,
+                                                             const float* shift, float* partial) {
+  int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  int r0 = blockIdx.y * RED_ROWS, r1 = min(rows, r0 + RED_ROWS);
+  float sh = mode == 1 ? shift[n] : 0.f, acc = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    float v = ld_f(x, (size_t)r * N + n, dt);
+    if (mode == 1) { v -= sh; v *= v; }
+    acc += v;
+  }
+  partial[(size_t)blockIdx.y * N + n] = acc;
+}
+
+// out[n] = scale * sum_c partial[c][n]
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float* partial, int chunks, int N, long stride,
+                                                              float scale, float* out) {
+  int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float acc = 0.f;
+  for (int c = 0; c < chunks; ++c) acc += partial[(size_t)c * stride + n];
+  out[n] = acc * scale;
+}
+}  // namespace
+
+int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out) {
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 255) / 256), dim3(256), 0, s, partial, chunks, N, stride, scale,
+                     out);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int colsum_partial_floats(int rows, int N) { return ((rows + RED_ROWS - 1) / RED_ROWS) * N; }
+
+int colsum_mode(hipStream_t s, const void* x, int dt, int rows, int N, int mode, const float* shift, float scale,
+                float* partials, float* out) {
+  int chunks = (rows + RED_ROWS - 1) / RED_ROWS;
+  hipLaunchKernelGGL(colsum_partial_kernel, dim3((N + 255) / 256, chunks), dim3(256), 0, s, x, dt, rows, N, mode,
+                     shift, partials);
+  PPLL_HIP(hipGetLastError());
+  return reduce_partials(s, partials, chunks, N, N, scale, out);
+}
+
+int launch_colsum(hipStream_t s, const void* x, int dt, int rows, int N, float* partials, float* out) {
+  return colsum_mode(s, x, dt, rows, N, 0, nullptr, 1.0f, partials, out);
+}
+
+// ===================================================================== LayerNorm
+namespace {
+constexpr int LN_ROWS = 32;   // rows per workgroup in the backward (4 waves x 8)
+
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const void* x, int dt, long xs, int rows, int D,
+                                                            const float* g, const float* b, float eps, void* y,
+                                                            float* mean, float* rstd) {
+  int row = blockIdx.x * 4 + threadIdx.x / 64, lane = threadIdx.x % 64;
+  if (row >= rows) return;
+  size_t base = (size_t)row * xs;
+  float s = 0.f;
+  for (int d = lane; d < D; d += 64) s += ld_f(x, base + d, dt);
+  float mu = wave_sum(s) / D;
+  float q = 0.f;
+  for (int d = lane; d < D; d += 64) { float c = ld_f(x, base + d, dt) - mu; q += c * c; }
+  float rs = rsqrtf(wave_sum(q) / D + eps);
+  for (int d = lane; d < D; d += 64)
+    st_f(y, (size_t)row * D + d, (ld_f(x, base + d, dt) - mu) * rs * g[d] + b[d], dt);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+
+// One wave per row.  dx = dres + rstd * (dyh - mean(dyh) - xhat * mean(dyh*xhat)), dyh = dy*g.
+// Each workgroup owns LN_ROWS consecutive rows and emits one partial of dg and db.
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const void* dy, const void* x, int dt, long xs, int rows,
+                                                            int D, const float* g, const float* mean,
+                                                            const float* rstd, const void* dres, void* dx,
+                                                            float* partial) {
+  extern __shared__ float sm[];          // [4][2][D]
+  int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  float* my_dg = sm + (size_t)wave * 2 * D;
+  float* my_db = my_dg + D;
+  for (int d = lane; d < D; d += 64) { my_dg[d] = 0.f; my_db[d] = 0.f; }
+  int r0 = blockIdx.x * LN_ROWS;
+  for (int rr = wave; rr < LN_ROWS; rr += 4) {
+    int row = r0 + rr;
+    if (row >= rows) break;
+    float mu = mean[row], rs = rstd[row];
+    size_t xb = (size_t)row * xs, yb = (size_t)row * D;
+    float s1 = 0.f, s2 = 0.f;
+    for (int d = lane; d < D; d += 64) {
+      float xh = (ld_f(x, xb + d, dt) - mu) * rs;
+      float dyv = ld_f(dy, yb + d, dt);
+      float dyh = dyv * g[d];
+      s1 += dyh; s2 += dyh * xh;
+      my_dg[d] += dyv * xh; my_db[d] += dyv;
+    }
+    s1 = wave_sum(s1) / D; s2 = wave_sum(s2) / D;
+    if (dx) {
+      for (int d = lane; d < D; d += 64) {
+        float xh = (ld_f(x, xb + d, dt) - mu) * rs;
+        float dyh = ld_f(dy, yb + d, dt) * g[d];
+        float v = rs * (dyh - s1 - xh * s2);
+        if (dres) v += ld_f(dres, yb + d, dt);
+        st_f(dx, yb + d, v, dt);
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 2 * D; i += 256)
+    partial[(size_t)blockIdx.x * 2 * D + i] = sm[i] + sm[2 * D + i] + sm[4 * D + i] + sm[6 * D + i];
+}
+}  // namespace
+
+int launch_layernorm_fwd(hipStream_t s, const void* x, int dt, long xs, int rows, int D, const float* g,
+                         const float* b, float eps, void* y, float* mean, float* rstd) {
+  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, x, dt, xs, rows, D, g, b, eps, y,
+                     mean, rstd);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int layernorm_bwd_partial_floats(int rows, int D) { return ((rows + LN_ROWS - 1) / LN_ROWS) * 2 * D; }
+
+int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, long xs, int rows, int D,
+                         const float* g, const float* mean, const float* rstd, const void* dres, void* dx_out,
+                         float* partials, float* dg, float* db) {
+  int chunks = (rows + LN_ROWS - 1) / LN_ROWS;
+  size_t lds = (size_t)8 * D * sizeof(float);
+  if (lds > 48 * 1024) { set_error("layernorm_bwd: dim %d too large", D); return PPLL_ERR_CONFIG; }
+  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(chunks), dim3(256), lds, s, dy, x, dt, xs, rows, D, g, mean, rstd,
+                     dres, dx_out, partials);
+  PPLL_HIP(hipGetLastError());
+  // each partial row is [dg | db]
+  PPLL_TRY(reduce_partials(s, partials, chunks, D, 2L * D, 1.0f, dg));
+  return reduce_partials(s, partials + D, chunks, D, 2L * D, 1.0f, db);
+}
+
+// ===================================================================== cross-entropy
+namespace {
+__global__ __launch_bounds__(256) void cross_entropy_kernel(const float* logits, const int32_t* labels, int B, int C,
+                                                            float* loss, float* dlogits, int* flag) {
+  __shared__ float red[256];
+  float acc = 0.f;
+  for (int b = threadIdx.x; b < B; b += 256) {
+    const float* z = logits + (size_t)b * C;
+    float mx = z[0];
+    for (int c = 1; c < C; ++c) mx = fmaxf(mx, z[c]);
+    float se = 0.f;
+    for (int c = 0; c < C; ++c) se += expf(z[c] - mx);
+    float lse = mx + logf(se);
+    int y = labels[b];
+    bool ok = y >= 0 && y < C;
+    if (!ok) *flag = 1;
+    for (int c = 0; c < C; ++c) dlogits[(size_t)b * C + c] = (expf(z[c] - lse) - ((ok && c == y) ? 1.f : 0.f)) / B;
+    if (ok) acc += lse - z[y];
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *loss = red[0] / B;
+}
+}  // namespace
+
+int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labels, int B, int C, float* loss,
+                         float* dlogits, int* flag) {
+  hipLaunchKernelGGL(cross_entropy_kernel, dim3(1), dim3(256), 0, s, logits, labels, B, C, loss, dlogits, flag);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+// ===================================================================== ViT embedding pieces
+namespace {
+__global__ __launch_bounds__(256) void patchify_kernel(const void* img, int dt, int B, int H, int W, int C, int P,
+                                                       void* out) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  int gw = W / P, gh = H / P, ppc = P * P * C;
+  size_t total = (size_t)B * gh * gw * ppc;
+  if (i >= total) return;
+  int e = i % ppc; size_t pidx = i / ppc;
+  int ch = e % C, c = (e / C) % P, r = e / (C * P);
+  int gx = pidx % gw, gy = (pidx / gw) % gh; int b = pidx / ((size_t)gw * gh);
+  size_t src = (((size_t)b * H + gy * P + r) * W + gx * P + c) * C + ch;
+  if (dt == BF16) ((uint16_t*)out)[i] = ((const uint16_t*)img)[src];
+  else ((float*)out)[i] = ((const float*)img)[src];
+}
+
+__global__ __launch_bounds__(256) void assemble_tokens_kernel(const void* E, int dt, const float* cls,
+                                                              const float* pos, int B, int T, int D, void* x0) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * T * D) return;
+  int d = i % D, t = (i / D) % T; int b = i / ((size_t)D * T);
+  float v = t == 0 ? cls[d] : ld_f(E, ((size_t)b * (T - 1) + (t - 1)) * D + d, dt);
+  st_f(x0, i, v + pos[(size_t)t * D + d], dt);
+}
+
+__global__ __launch_bounds__(256) void embed_bwd_kernel(const void* dx, int dt, int B, int T, int D, float* dpos,
+                                                        float* dcls, void* dE) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // over [T, D]
+  if (i >= (size_t)T * D) return;
+  int d = i % D, t = i / D;
+  float acc = 0.f;
+  for (int b = 0; b < B; ++b) {
+    size_t src = ((size_t)b * T + t) * D + d;
+    acc += ld_f(dx, src, dt);
+    if (t > 0) {
+      size_t dst = ((size_t)b * (T - 1) + (t - 1)) * D + d;
+      if (dt == BF16) ((uint16_t*)dE)[dst] = ((const uint16_t*)dx)[src];
+      else ((float*)dE)[dst] = ((const float*)dx)[src];
+    }
+  }
+  dpos[i] = acc;
+  if (t == 0) dcls[d] = acc;
+}
+
+__global__ __launch_bounds__(256) void scatter_cls_kernel(const void* dcls, int dt, int B, int T, int D, void* dx) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * T * D) return;
+  int d = i % D, t = (i / D) % T; int b = i / ((size_t)D * T);
+  st_f(dx, i, t == 0 ? ld_f(dcls, (size_t)b * D + d, dt) : 0.f, dt);
+}
+}  // namespace
+
+int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W, int C, int P, void* patches) {
+  size_t total = (size_t)B * H * W * C;
+  hipLaunchKernelGGL(patchify_kernel, dim3((total + 255) / 256), dim3(256), 0, s, img, dt, B, H, W, C, P, patches);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cls, const float* pos, int B, int T,
+                           int D, void* x0) {
+  size_t total = (size_t)B * T * D;
+  hipLaunchKernelGGL(assemble_tokens_kernel, dim3((total + 255) / 256), dim3(256), 0, s, E, dt, cls, pos, B, T, D, x0);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* dpos, float* dcls, void* dE) {
+  size_t total = (size_t)T * D;
+  hipLaunchKernelGGL(embed_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dx, dt, B, T, D, dpos, dcls, dE);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_scatter_cls(hipStream_t s, const void* dcls, int dt, int B, int T, int D, void* dx) {
+  size_t total = (size_t)B * T * D;
+  hipLaunchKernelGGL(scatter_cls_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dcls, dt, B, T, D, dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+// ===================================================================== attention (per batch, head)
+namespace {
+// One workgroup per (batch, head); K and V of the head live in LDS as fp32 with
+// a padded row so that lanes reading different keys hit different banks.  Each
+// wave takes query rows round-robin: scores with lanes over keys, softmax by
+// wave reductions, then the weighted sum with lanes over the head dimension.
+constexpr int ATT_MAX_T = 256;
+
+__global__ __launch_bounds__(256) void attention_fwd_kernel(const void* qkv, int dt, int T, int H, int dh, void* out,
+                                                            float* lse) {
+  extern __shared__ float sm[];
+  const int ld = dh + 1;
+  float* Ks = sm;                       // [T][ld]
+  float* Vs = Ks + (size_t)T * ld;      // [T][ld]
+  float* qs = Vs + (size_t)T * ld;      // [4][dh]
+  float* ps = qs + 4 * dh;              // [4][T]
+  const int b = blockIdx.x / H, h = blockIdx.x % H, D = H * dh;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const float scale = rsqrtf((float)dh);
+  for (int i = threadIdx.x; i < T * dh; i += 256) {
+    int t = i / dh, d = i % dh;
+    size_t base = ((size_t)b * T + t) * 3 * D + h * dh + d;
+    Ks[t * ld + d] = ld_f(qkv, base + D, dt);
+    Vs[t * ld + d] = ld_f(qkv, base + 2 * D, dt);
+  }
+  __syncthreads();
+  float* q = qs + wave * dh;
+  float* p = ps + wave * T;
+  for (int i = wave; i < T; i += 4) {
+    size_t qb = ((size_t)b * T + i) * 3 * D + h * dh;
+    for (int d = lane; d < dh; d += 64) q[d] = ld_f(qkv, qb + d, dt);
+    wave_sync();
+    float sc[ATT_MAX_T / 64];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < ATT_MAX_T / 64; ++r) {
+      int j = lane + r * 64;
+      float a = -INFINITY;
+      if (j < T) {
+        a = 0.f;
+        for (int d = 0; d < dh; ++d) a = fmaf(q[d], Ks[j * ld + d], a);
+        a *= scale;
+      }
+      sc[r] = a;
+      mx = fmaxf(mx, a);
+    }
+    mx = wave_max(mx);
+    float se = 0.f;
+#pragma unroll
+    for (int r = 0; r < ATT_MAX_T / 64; ++r) {
+      int j = lane + r * 64;
+      float e = j < T ? __expf(sc[r] - mx) : 0.f;
+      sc[r] = e;
+      se += e;
+    }
+    se = wave_sum(se);
+    float inv = 1.0f / se;
+#pragma unroll
+    for (int r = 0; r < ATT_MAX_T / 64; ++r) {
+      int j = lane + r * 64;
+      if (j < T) p[j] = sc[r] * inv;
+    }
+    wave_sync();
+    for (int d = lane; d < dh; d += 64) {
+      float o = 0.f;
+      for (int j = 0; j < T; ++j) o = fmaf(p[j], Vs[j * ld + d], o);
+      st_f(out, ((size_t)b * T + i) * D + h * dh + d, o, dt);
+    }
+    if (lane == 0) lse[((size_t)b * H + h) * T + i] = mx + __logf(se);
+    wave_sync();
+  }
+}
+
+// Backward in two ordered passes.  Pass A (wave per query row i): D_i =
+// <dO_i, O_i>, P_i recomputed from the saved log-sum-exp, dS_i = P_i o (dO_i V^T
+// - D_i), dQ_i = scale dS_i K.  Pass B (wave per key j) recomputes column j of P
+// and dS from Q and dO (now in LDS) and accumulates dV_j = sum_i P_ij dO_i and
+// dK_j = scale sum_i dS_ij Q_i in a fixed order.
+__global__ __launch_bounds__(256) void attention_bwd_kernel(const void* qkv, const void* out, const void* dout,
+                                                            const float* lse, int dt, int T, int H, int dh,
+                                                            void* dqkv) {
+  extern __shared__ float sm[];
+  const int ld = dh + 1;
+  float* As = sm;                        // pass A: K, pass B: Q     [T][ld]
+  float* Bs = As + (size_t)T * ld;       // pass A: V, pass B: dO    [T][ld]
+  float* vec = Bs + (size_t)T * ld;      // [4][2][dh] per-wave row vectors
+  float* ps = vec + 8 * dh;              // [4][2][T]  per-wave p and ds
+  float* Dr = ps + 8 * T;                // [T] row dots
+  float* Ls = Dr + T;                    // [T] lse
+  const int b = blockIdx.x / H, h = blockIdx.x % H, D = H * dh;
+  const int wave = threadIdx.x / 64, lane = threadIdx.x % 64;
+  const float scale = rsqrtf((float)dh);
+  for (int i = threadIdx.x; i < T * dh; i += 256) {
+    int t = i / dh, d = i % dh;
+    size_t base = ((size_t)b * T + t) * 3 * D + h * dh + d;
+    As[t * ld + d] = ld_f(qkv, base + D, dt);
+    Bs[t * ld + d] = ld_f(qkv, base + 2 * D, dt);
+  }
+  for (int i = threadIdx.x; i < T; i += 256) Ls[i] = lse[((size_t)b * H + h) * T + i];
+  __syncthreads();
+  float* v0 = vec + wave * 2 * dh;       // q_i  / k_j
+  float* v1 = v0 + dh;                   // dO_i / v_j
+  float* p0 = ps + wave * 2 * T;         // p
+  float* p1 = p0 + T;                    // ds
+  // ---- pass A
+  for (int i = wave; i < T; i += 4) {
+    size_t qb = ((size_t)b * T + i) * 3 * D + h * dh, ob = ((size_t)b * T + i) * D + h * dh;
+    float dd = 0.f;
+    for (int d = lane; d < dh; d += 64) {
+      v0[d] = ld_f(qkv, qb + d, dt);
+      float g = ld_f(dout, ob + d, dt);
+      v1[d] = g;
+      dd += g * ld_f(out, ob + d, dt);
+    }
+    dd = wave_sum(dd);
+    if (lane == 0) Dr[i] = dd;
+    wave_sync();
+    for (int j = lane; j < T; j += 64) {
+      float s = 0.f, dp = 0.f;
+      for (int d = 0; d < dh; ++d) { s = fmaf(v0[d], As[j * ld + d], s); dp = fmaf(v1[d], Bs[j * ld + d], dp); }
+      float pj = __expf(s * scale - Ls[i]);
+      p1[j] = pj * (dp - dd);
+    }
+    wave_sync();
+    for (int d = lane; d < dh; d += 64) {
+      float a = 0.f;
+      for (int j = 0; j < T; ++j) a = fmaf(p1[j], As[j * ld + d], a);
+      st_f(dqkv, qb + d, a * scale, dt);
+    }
+    wave_sync();
+  }
+  __syncthreads();
+  // ---- reload: Q and dO
+  for (int i = threadIdx.x; i < T * dh; i += 256) {
+    int t = i / dh, d = i % dh;
+    As[t * ld + d] = ld_f(qkv, ((size_t)b * T + t) * 3 * D + h * dh + d, dt);
+    Bs[t * ld + d] = ld_f(dout, ((size_t)b * T + t) * D + h * dh + d, dt);
+  }
+  __syncthreads();
+  // ---- pass B
+  for (int j = wave; j < T; j += 4) {
+    size_t kb = ((size_t)b * T + j) * 3 * D + h * dh;
+    for (int d = lane; d < dh; d += 64) { v0[d] = ld_f(qkv, kb + D + d, dt); v1[d] = ld_f(qkv, kb + 2 * D + d, dt); }
+    wave_sync();
+    for (int i = lane; i < T; i += 64) {
+      float s = 0.f, dp = 0.f;
+      for (int d = 0; d < dh; ++d) { s = fmaf(As[i * ld + d], v0[d], s); dp = fmaf(Bs[i * ld + d], v1[d], dp); }
+      float pij = __expf(s * scale - Ls[i]);
+      p0[i] = pij;
+      p1[i] = pij * (dp - Dr[i]);
+    }
+    wave_sync();
+    for (int d = lane; d < dh; d += 64) {
+      float dv = 0.f, dk = 0.f;
+      for (int i = 0; i < T; ++i) { dv = fmaf(p0[i], Bs[i * ld + d], dv); dk = fmaf(p1[i], As[i * ld + d], dk); }
+      st_f(dqkv, kb + D + d, dk * scale, dt);
+      st_f(dqkv, kb + 2 * D + d, dv, dt);
+    }
+    wave_sync();
+  }
+}
+
+int set_dyn_lds(const void* fn, size_t bytes) {
+  if (bytes > 160 * 1024) { set_error("attention: %zu bytes of LDS exceed 160 KB", bytes); return PPLL_ERR_CONFIG; }
+  if (bytes > 64 * 1024) PPLL_HIP(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+  return PPLL_OK;
+}
+}  // namespace
+
+int launch_attention_fwd_generic(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out,
+                                 float* lse) {
+  if (T > ATT_MAX_T || T < 1) { set_error("attention: tokens %d outside 1..%d", T, ATT_MAX_T); return PPLL_ERR_CONFIG; }
+  size_t lds = ((size_t)2 * T * (dh + 1) + 4 * dh + 4 * T) * sizeof(float);
+  PPLL_TRY(set_dyn_lds((const void*)attention_fwd_kernel, lds));
+  hipLaunchKernelGGL(attention_fwd_kernel, dim3(B * H), dim3(256), lds, s, qkv, dt, T, H, dh, out, lse);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_attention_bwd_generic(hipStream_t s, const void* qkv, const void* out, const void* dout, const float* lse,
+                                 int dt, int B, int T, int H, int dh, void* dqkv) {
+  if (T > ATT_MAX_T || T < 1) { set_error("attention: tokens %d outside 1..%d", T, ATT_MAX_T); return PPLL_ERR_CONFIG; }
+  size_t lds = ((size_t)2 * T * (dh + 1) + 8 * dh + 8 * T + 2 * T) * sizeof(float);
+  PPLL_TRY(set_dyn_lds((const void*)attention_bwd_kernel, lds));
+  hipLaunchKernelGGL(attention_bwd_kernel, dim3(B * H), dim3(256), lds, s, qkv, out, dout, lse, dt, T, H, dh, dqkv);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+// ===================================================================== optimizers
+namespace {
+// Algorithm 1, update line.  Coupled L2 decay, momentum buffer (first step:
+// buffer = gradient), plain or Nesterov step.
+__global__ __launch_bounds__(256) void sgd_kernel(float* p, const float* g, float* buf, uint16_t* shadow, size_t n,
+                                                  float lr, float momentum, int nesterov, float wd, int first) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float w = p[i], gr = g[i] + wd * w;
+  if (momentum != 0.f) {
+    float bv = first ? gr : momentum * buf[i] + gr;
+    buf[i] = bv;
+    gr = nesterov ? gr + momentum * bv : bv;
+  }
+  w -= lr * gr;
+  p[i] = w;
+  if (shadow) shadow[i] = f32_to_bf16(w);
+}
+
+// AdamW: decoupled decay, bias-corrected moments (corrections computed on the host).
+__global__ __launch_bounds__(256) void adamw_kernel(float* p, const float* g, float* m, float* v, uint16_t* shadow,
+                                                    size_t n, float lr, float b1, float b2, float eps, float wd,
+                                                    float bc1, float bc2) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  float gr = g[i];
+  float w = p[i] * (1.0f - lr * wd);
+  float mi = b1 * m[i] + (1.0f - b1) * gr;
+  float vi = b2 * v[i] + (1.0f - b2) * gr * gr;
+  m[i] = mi; v[i] = vi;
+  w -= lr * (mi / bc1) / (sqrtf(vi / bc2) + eps);
+  p[i] = w;
+  if (shadow) shadow[i] = f32_to_bf16(w);
+}
+
+__global__ __launch_bounds__(256) void refresh_shadow_kernel(const float* p, uint16_t* shadow, size_t n) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) shadow[i] = f32_to_bf16(p[i]);
+}
+
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint32_t* p, size_t words) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < words) p[i] = 0u;
+}
+}  // namespace
+
+int launch_sgd(hipStream_t s, float* p, const float* g, float* buf, uint16_t* shadow, size_t n, float lr, float momentum,
+               int nesterov, float wd, int first) {
+  hipLaunchKernelGGL(sgd_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, g, buf, shadow, n, lr, momentum, nesterov, wd,
+                     first);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_adamw(hipStream_t s, float* p, const float* g, float* m, float* v, uint16_t* shadow, size_t n, float lr,
+                 float b1, float b2, float eps, float wd, float bc1, float bc2) {
+  hipLaunchKernelGGL(adamw_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, g, m, v, shadow, n, lr, b1, b2, eps, wd, bc1,
+                     bc2);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_refresh_shadow(hipStream_t s, const float* p, uint16_t* shadow, size_t n) {
+  hipLaunchKernelGGL(refresh_shadow_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, shadow, n);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_fill_zero(hipStream_t s, void* p, size_t bytes) {
+  size_t words = (bytes + 3) / 4;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((words + 255) / 256), dim3(256), 0, s, (uint32_t*)p, words);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+}  // namespace ppll

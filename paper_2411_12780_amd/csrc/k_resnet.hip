@@ -1,0 +1,247 @@
+// ResNet stage kernels (element type chosen at run time): direct 3x3
+// convolution forward / input gradient / weight gradient on NHWC activations
+// with [ky,kx,Cin,Cout] filters, training-mode BatchNorm (+ReLU, +skip) forward
+// and backward, and global average pooling.  Reductions are two-stage and
+// ordered, never atomic.
+#include "common.h"
+
+namespace ppll {
+
+namespace {
+__device__ __forceinline__ int out_dim(int in, int stride) { return (in - 1) / stride + 1; }   // pad 1, 3x3
+
+// y[b,oy,ox,co] = sum_{ky,kx,ci} x[b, oy*s+ky-1, ox*s+kx-1, ci] w[ky,kx,ci,co]
+__global__ __launch_bounds__(256) void conv3x3_fwd_kernel(const void* x, const void* w, int wdt, int dt, int B, int H,
+                                                          int W, int Ci, int Co, int stride, void* y) {
+  int Ho = out_dim(H, stride), Wo = out_dim(W, stride);
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * Ho * Wo * Co) return;
+  int co = i % Co; size_t pix = i / Co;
+  int ox = pix % Wo, oy = (pix / Wo) % Ho; int b = pix / ((size_t)Wo * Ho);
+  float acc = 0.f;
+  for (int ky = 0; ky < 3; ++ky) {
+    int iy = oy * stride + ky - 1;
+    if (iy < 0 || iy >= H) continue;
+    for (int kx = 0; kx < 3; ++kx) {
+      int ix = ox * stride + kx - 1;
+      if (ix < 0 || ix >= W) continue;
+      size_t xb = (((size_t)b * H + iy) * W + ix) * Ci;
+      size_t wb = ((size_t)(ky * 3 + kx) * Ci) * Co + co;
+      for (int ci = 0; ci < Ci; ++ci) acc = fmaf(ld_f(x, xb + ci, dt), ld_f(w, wb + (size_t)ci * Co, wdt), acc);
+    }
+  }
+  st_f(y, i, acc, dt);
+}
+
+// dx[b,iy,ix,ci] = sum_{ky,kx,co} dy[b,oy,ox,co] w[ky,kx,ci,co] over the (oy,ox)
+// with oy*s+ky-1 = iy, ox*s+kx-1 = ix; optionally + dres * (ymask > 0).
+__global__ __launch_bounds__(256) void conv3x3_dgrad_kernel(const void* dy, const void* w, int wdt, int dt, int B, int H,
+                                                            int W, int Ci, int Co, int stride, const void* dres,
+                                                            const void* ymask, void* dx) {
+  int Ho = out_dim(H, stride), Wo = out_dim(W, stride);
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * H * W * Ci) return;
+  int ci = i % Ci; size_t pix = i / Ci;
+  int ix = pix % W, iy = (pix / W) % H; int b = pix / ((size_t)W * H);
+  float acc = 0.f;
+  for (int ky = 0; ky < 3; ++ky) {
+    int ty = iy + 1 - ky;
+    if (ty < 0 || ty % stride) continue;
+    int oy = ty / stride;
+    if (oy >= Ho) continue;
+    for (int kx = 0; kx < 3; ++kx) {
+      int tx = ix + 1 - kx;
+      if (tx < 0 || tx % stride) continue;
+      int ox = tx / stride;
+      if (ox >= Wo) continue;
+      size_t yb = (((size_t)b * Ho + oy) * Wo + ox) * Co;
+      size_t wb = ((size_t)(ky * 3 + kx) * Ci + ci) * Co;
+      for (int co = 0; co < Co; ++co) acc = fmaf(ld_f(dy, yb + co, dt), ld_f(w, wb + co, wdt), acc);
+    }
+  }
+  if (dres && ld_f(ymask, i, dt) > 0.f) acc += ld_f(dres, i, dt);
+  st_f(dx, i, acc, dt);
+}
+
+// partial[chunk][tap,ci,co] = sum over the chunk's output pixels of x(...) dy(...)
+constexpr int WG_PIX = 64;
+__global__ __launch_bounds__(256) void conv3x3_wgrad_kernel(const void* x, const void* dy, int dt, int B, int H, int W,
+                                                            int Ci, int Co, int stride, float* partial) {
+  int Ho = out_dim(H, stride), Wo = out_dim(W, stride);
+  size_t npix = (size_t)B * Ho * Wo;
+  size_t p0 = (size_t)blockIdx.x * WG_PIX, p1 = min(npix, p0 + WG_PIX);
+  int nw = 9 * Ci * Co;
+  for (int e = threadIdx.x; e < nw; e += 256) {
+    int co = e % Co, ci = (e / Co) % Ci, tap = e / (Co * Ci);
+    int ky = tap / 3, kx = tap % 3;
+    float acc = 0.f;
+    for (size_t p = p0; p < p1; ++p) {
+      int ox = p % Wo, oy = (p / Wo) % Ho; int b = p / ((size_t)Wo * Ho);
+      int iy = oy * stride + ky - 1, ix = ox * stride + kx - 1;
+      if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+      acc = fmaf(ld_f(x, (((size_t)b * H + iy) * W + ix) * Ci + ci, dt), ld_f(dy, p * Co + co, dt), acc);
+    }
+    partial[(size_t)blockIdx.x * nw + e] = acc;
+  }
+}
+
+__global__ __launch_bounds__(256) void bn_finalize_kernel(const float* var_in, int C, int rows, float eps,
+                                                          float momentum, const float* mean, float* rstd,
+                                                          float* run_mean, float* run_var) {
+  int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  float var = var_in[c];
+  rstd[c] = 1.0f / sqrtf(var + eps);
+  run_mean[c] = (1.f - momentum) * run_mean[c] + momentum * mean[c];
+  run_var[c] = (1.f - momentum) * run_var[c] + momentum * var * ((float)rows / (float)(rows - 1));
+}
+
+__global__ __launch_bounds__(256) void bn_apply_kernel(const void* x, int dt, size_t total, int C, const float* mean,
+                                                       const float* rstd, const float* g, const float* b,
+                                                       const void* res, void* y) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  int c = i % C;
+  float v = (ld_f(x, i, dt) - mean[c]) * rstd[c] * g[c] + b[c];
+  if (res) v += ld_f(res, i, dt);
+  st_f(y, i, fmaxf(v, 0.f), dt);
+}
+
+constexpr int BN_ROWS = 64;
+// partial[chunk][0][c] = sum dyh, partial[chunk][1][c] = sum dyh*xhat, dyh = dy * (y > 0)
+__global__ __launch_bounds__(256) void bn_bwd_partial_kernel(const void* dy, const void* y, const void* x, int dt,
+                                                             int rows, int C, const float* mean, const float* rstd,
+                                                             float* partial) {
+  int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  int r0 = blockIdx.y * BN_ROWS, r1 = min(rows, r0 + BN_ROWS);
+  float mu = mean[c], rs = rstd[c], s1 = 0.f, s2 = 0.f;
+  for (int r = r0; r < r1; ++r) {
+    size_t i = (size_t)r * C + c;
+    float d = ld_f(y, i, dt) > 0.f ? ld_f(dy, i, dt) : 0.f;
+    s1 += d;
+    s2 += d * (ld_f(x, i, dt) - mu) * rs;
+  }
+  partial[((size_t)blockIdx.y * 2) * C + c] = s1;
+  partial[((size_t)blockIdx.y * 2 + 1) * C + c] = s2;
+}
+
+// dx = (g rstd / N) (N dyh - sum dyh - xhat sum dyh*xhat); db = sum dyh, dg = sum dyh*xhat
+__global__ __launch_bounds__(256) void bn_bwd_apply_kernel(const void* dy, const void* y, const void* x, int dt,
+                                                           size_t total, int C, int rows, const float* mean,
+                                                           const float* rstd, const float* g, const float* dg,
+                                                           const float* db, void* dx) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= total) return;
+  int c = i % C;
+  float d = ld_f(y, i, dt) > 0.f ? ld_f(dy, i, dt) : 0.f;
+  float xh = (ld_f(x, i, dt) - mean[c]) * rstd[c];
+  float n = (float)rows;
+  st_f(dx, i, g[c] * rstd[c] / n * (n * d - db[c] - xh * dg[c]), dt);
+}
+
+__global__ __launch_bounds__(256) void gap_fwd_kernel(const void* x, int dt, int B, int HW, int C, void* pooled) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= B * C) return;
+  int c = i % C, b = i / C;
+  float acc = 0.f;
+  for (int p = 0; p < HW; ++p) acc += ld_f(x, ((size_t)b * HW + p) * C + c, dt);
+  st_f(pooled, i, acc / HW, dt);
+}
+
+__global__ __launch_bounds__(256) void gap_bwd_kernel(const void* dpooled, int dt, int B, int HW, int C, void* dx) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * HW * C) return;
+  int c = i % C; int b = i / ((size_t)HW * C);
+  st_f(dx, i, ld_f(dpooled, (size_t)b * C + c, dt) / HW, dt);
+}
+}  // namespace
+
+int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
+                       int Co, int stride, void* y) {
+  size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Co;
+  hipLaunchKernelGGL(conv3x3_fwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, w, wdt, dt, B, H, W, Ci, Co,
+                     stride, y);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
+                         int Co, int stride, const void* dres, const void* ymask, void* dx) {
+  size_t total = (size_t)B * H * W * Ci;
+  hipLaunchKernelGGL(conv3x3_dgrad_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dy, w, wdt, dt, B, H, W, Ci,
+                     Co, stride, dres, ymask, dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+static size_t wgrad_chunks(int B, int H, int W, int stride) {
+  size_t npix = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+  return (npix + WG_PIX - 1) / WG_PIX;
+}
+int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride) {
+  return (int)(wgrad_chunks(B, H, W, stride) * 9 * Ci * Co);
+}
+int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci, int Co,
+                         int stride, float* partials, float* dw) {
+  int chunks = (int)wgrad_chunks(B, H, W, stride), nw = 9 * Ci * Co;
+  hipLaunchKernelGGL(conv3x3_wgrad_kernel, dim3(chunks), dim3(256), 0, s, x, dy, dt, B, H, W, Ci, Co, stride, partials);
+  PPLL_HIP(hipGetLastError());
+  return reduce_partials(s, partials, chunks, nw, nw, 1.0f, dw);
+}
+
+int bn_partial_floats(int rows, int C) {
+  int a = colsum_partial_floats(rows, C), b = ((rows + BN_ROWS - 1) / BN_ROWS) * 2 * C;
+  return (a > b ? a : b) + C;
+}
+
+int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
+                    float* mean, float* rstd, float* run_mean, float* run_var) {
+  if (rows < 2) { set_error("batchnorm needs at least 2 rows per channel"); return PPLL_ERR_CONFIG; }
+  float* var = partials;            // [C], then the chunk partials
+  float* part = partials + C;
+  PPLL_TRY(colsum_mode(s, x, dt, rows, C, 0, nullptr, 1.0f / rows, part, mean));
+  PPLL_TRY(colsum_mode(s, x, dt, rows, C, 1, mean, 1.0f / rows, part, var));
+  hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 255) / 256), dim3(256), 0, s, var, C, rows, eps, momentum, mean, rstd,
+                     run_mean, run_var);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const float* mean, const float* rstd,
+                    const float* g, const float* b, const void* res, void* y) {
+  size_t total = (size_t)rows * C;
+  hipLaunchKernelGGL(bn_apply_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, dt, total, C, mean, rstd, g, b, res, y);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
+                  const float* mean, const float* rstd, const float* g, float* partials, float* dg, float* db,
+                  void* dx) {
+  int chunks = (rows + BN_ROWS - 1) / BN_ROWS;
+  size_t total = (size_t)rows * C;
+  hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3((C + 255) / 256, chunks), dim3(256), 0, s, dy, y, x, dt, rows, C, mean,
+                     rstd, partials);
+  PPLL_HIP(hipGetLastError());
+  PPLL_TRY(reduce_partials(s, partials, chunks, C, 2L * C, 1.0f, db));
+  PPLL_TRY(reduce_partials(s, partials + C, chunks, C, 2L * C, 1.0f, dg));
+  hipLaunchKernelGGL(bn_bwd_apply_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dy, y, x, dt, total, C, rows, mean,
+                     rstd, g, dg, db, dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, void* pooled) {
+  hipLaunchKernelGGL(gap_fwd_kernel, dim3((B * C + 255) / 256), dim3(256), 0, s, x, dt, B, HW, C, pooled);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_gap_bwd(hipStream_t s, const void* dpooled, int dt, int B, int HW, int C, void* dx) {
+  size_t total = (size_t)B * HW * C;
+  hipLaunchKernelGGL(gap_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dpooled, dt, B, HW, C, dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+}  // namespace ppll

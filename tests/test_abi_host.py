@@ -1,0 +1,88 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, answers size queries and rejects bad
+configurations before touching the device."""
+import os
+import re
+
+import pytest
+
+from paper_2411_12780_amd import binding as P
+from paper_2411_12780_amd import synth
+from oracle import ppll_oracle as O
+from helpers import oracle_cfg
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ppll.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(ppll_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    lib = P.lib()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(P.EXPORTS)
+
+
+@pytest.mark.parametrize("name", list(synth.WORKLOADS))
+def test_size_queries_match_the_workload(name):
+    wl = synth.workload(name)
+    cfg = P.make_config(wl)
+    esz = 2 if wl["precision"] == synth.BF16 else 4
+    assert P.ppll_block_param_bytes(cfg) == 4 * O.param_count(oracle_cfg(wl))
+    n_in = 1
+    for d in synth.input_shape(wl):
+        n_in *= d
+    n_out = 1
+    for d in synth.output_shape(wl):
+        n_out *= d
+    assert P.ppll_block_in_bytes(cfg) == n_in * esz
+    assert P.ppll_block_out_bytes(cfg) == n_out * esz
+    ws = P.ppll_block_workspace_bytes(cfg)
+    assert ws % 256 == 0 and ws > 4 * P.ppll_block_param_bytes(cfg) // 2
+
+
+def test_bad_configurations_are_rejected_on_the_host():
+    good = synth.workload("vit_tiny_fp32")
+    for bad in (dict(tokens=64), dict(heads=5), dict(precision=7), dict(arch=3), dict(batch=0),
+                dict(optimizer=9), dict(depth=0), dict(patch=5), dict(tokens=300, img_h=68, img_w=68, patch=4)):
+        cfg = P.make_config(dict(good, **bad))
+        with pytest.raises(P.PpllError) as e:
+            P.ppll_block_workspace_bytes(cfg)
+        assert e.value.status == 2, bad
+        assert P.ppll_last_error()
+    cfg = P.make_config(good)
+    cfg.struct_size = 12
+    with pytest.raises(P.PpllError):
+        P.ppll_block_workspace_bytes(cfg)
+    res = P.make_config(dict(synth.workload("resnet_stage_bf16"), input_kind=synth.IMAGE))
+    with pytest.raises(P.PpllError):
+        P.ppll_block_workspace_bytes(res)
+
+
+def test_null_and_misaligned_arguments():
+    cfg = P.make_config(synth.workload("vit_tiny_fp32"))
+    with pytest.raises(P.PpllError) as e:
+        P.ppll_block_init(cfg, None, 1 << 20, None)
+    assert e.value.status == 1
+    with pytest.raises(P.PpllError) as e:
+        P.ppll_block_init(cfg, 0x1008, 1 << 20, None)       # not 16-byte aligned: rejected before any use
+    assert e.value.status == 4
+    with pytest.raises(P.PpllError) as e:
+        P.ppll_block_step(None, 16, 16, 0.1, 16)
+    assert e.value.status == 1
+
+
+def test_pipeline_shape_chain_is_checked():
+    a = P.make_config(synth.workload("vit_stage_bf16"))
+    b = P.make_config(synth.workload("vit_stage_act_bf16"))
+    assert P.ppll_pipeline_workspace_bytes([a, b, b, b], 2) > 4 * P.ppll_block_workspace_bytes(b)
+    with pytest.raises(P.PpllError) as e:
+        P.ppll_pipeline_workspace_bytes([a, a], 2)          # second block wants images
+    assert e.value.status == 3
+    with pytest.raises(P.PpllError):
+        P.ppll_pipeline_workspace_bytes([a, b], 0)
+    small = P.make_config(synth.workload("vit_stage_act_bf16", batch=64))
+    with pytest.raises(P.PpllError):
+        P.ppll_pipeline_workspace_bytes([a, small], 2)

@@ -1,0 +1,243 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by
+element on the same seeded inputs.
+
+Tolerances (relative L2 per tensor, |dloss|/|loss| for the loss): 1e-4 on the
+fp32 path, 2e-2 on the bf16 path, for the output activation, the local loss,
+every parameter-gradient tensor and every updated parameter tensor.
+
+bf16 path.  The gate is the float64 oracle with bf16 *storage* emulated
+(activations and weight shadows rounded to bf16 values at the points where the
+kernels store them; arithmetic, statistics, loss and parameter gradients stay
+float64), so that sign decisions (ReLU masks) are taken on the same stored
+values on both sides.  The distance to the pure float64 oracle is asserted for
+the loss and the output activation and printed for the gradients.
+
+ReLU masks.  A ReLU gradient is discontinuous in the pre-activation: one
+element whose mask differs changes a gradient tensor by that element's full
+magnitude.  Two bf16 evaluations that differ only in accumulation order (fp32 on
+the GPU, float64 in the oracle) disagree on a few roundings of stored values
+after the first convolution, and every disagreement reaches 9*C outputs of the
+next one, so the stored values decorrelate to the bf16 noise level within a few
+layers and masks then differ at that rate, whatever the oracle emulates.
+Measured: GPU vs storage-emulating oracle gradients agree to 7e-3 with one basic
+block, 2e-2 with two, 6e-2 with three and 1.4e-1 with five; oracle vs oracle
+(pure vs bf16 storage, CPU only, tests/test_oracle_step.py) is 9-19 % at five.
+The bf16 ResNet arithmetic is therefore gated at 2e-2 on one- and two-block
+stages at the full activation size, the same kernels at five blocks on the fp32
+path (1e-3; 1e-4 class agreement needs every mask equal, and fp32 summation order
+already flips about one in a million), and the named five-block bf16 workload at
+2e-2 on loss and output with a 0.3 ceiling on gradients.
+"""
+import numpy as np
+import pytest
+
+from oracle import ppll_oracle as O
+from paper_2411_12780_amd import synth
+from helpers import oracle_cfg, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.FP32: 1e-4, synth.BF16: 2e-2}
+
+
+def run_case(wl, steps, seed=0, check_bn=False, tol=None, grad_tol=None, tweak=None):
+    from gpu_harness import GpuBlock
+    from paper_2411_12780_amd import binding as P
+    wl = {**dict(beta1=0.9, beta2=0.999, adam_eps=1e-8, momentum=0.0, nesterov=0, weight_decay=0.0), **wl}
+    cfg = oracle_cfg(wl)
+    flat = synth.make_params(O.param_spec(cfg), seed=seed, jitter=True)
+    if tweak is not None:
+        tensors = O.unflatten(cfg, flat, np.float32)
+        tweak(tensors)
+        flat = O.flatten(cfg, tensors).astype(np.float32)
+    bf16 = wl["precision"] == synth.BF16
+    st = O.block_init(cfg, flat, np.float64, storage="bf16" if bf16 else None)
+    pure = O.block_init(cfg, flat, np.float64) if bf16 else None
+    gb = GpuBlock(wl, flat)
+    assert gb.names == [n for n, _ in O.param_spec(cfg)]
+    tol = tol or TOL[wl["precision"]]
+    grad_tol = grad_tol or tol
+    adamw = wl["optimizer"] == synth.ADAMW
+    # AdamW moves a coordinate by about lr*sign(g) however small |g| is, so where the true
+    # gradient is zero (key bias) or under the bf16 noise floor the end-to-end parameter is
+    # noise-determined.  There the update is checked as arithmetic on the GPU's own gradient
+    # (always done, tight tolerance) and end to end on coordinates with a resolvable gradient.
+    masked = adamw and wl["precision"] == synth.BF16
+    worst = {}
+    try:
+        for i in range(steps):
+            x, y = synth.make_batch(wl, seed=seed, index=i)
+            print(f"  step {i}: arch={wl['arch']} batch={wl['batch']}", flush=True)
+            if masked and i > 0:
+                # noise-determined AdamW coordinates make the two trajectories drift apart; each
+                # further step is checked from the oracle's state (oracle -> GPU, never back)
+                for idx, name in enumerate(gb.names):
+                    P.ppll_block_write_tensor(gb.h, P.T_PARAM, idx, st.params[name])
+                    P.ppll_block_write_tensor(gb.h, P.T_MOMENT1, idx, st.mom1[name])
+                    P.ppll_block_write_tensor(gb.h, P.T_MOMENT2, idx, st.mom2[name])
+            p_before, m_before = gb.tensors(P.T_PARAM), gb.tensors(P.T_MOMENT1)
+            v_before = gb.tensors(P.T_MOMENT2) if adamw else None
+            ref_out, ref_loss = O.block_step(st, x.astype(np.float64), y, wl["lr"])
+            out, loss = gb.step(x, y, wl["lr"])
+            assert abs(loss - ref_loss) <= tol * abs(ref_loss), (i, loss, ref_loss)
+            e = rel_l2(out, ref_out)
+            assert e <= tol, (i, "x_out", e)
+            worst["x_out"] = max(worst.get("x_out", 0), e)
+            grads, params = gb.tensors(P.T_GRAD), gb.tensors(P.T_PARAM)
+            if pure is not None and i == 0:
+                pure_out, pure_loss = O.block_step(pure, x.astype(np.float64), y, wl["lr"])
+                assert abs(loss - pure_loss) <= tol * abs(pure_loss), ("pure oracle", loss, pure_loss)
+                worst["pure_x_out"] = rel_l2(out, pure_out)
+                assert worst["pure_x_out"] <= tol, ("pure oracle x_out", worst["pure_x_out"])
+                worst["pure_grad"] = max(rel_l2(grads[n], pure.grads[n]) for n in grads)
+            gerr = {name: rel_l2(grads[name], st.grads[name]) for name, _ in O.param_spec(cfg)}
+            top = sorted(gerr.items(), key=lambda kv: -kv[1])[:8]
+            print("  largest gradient errors:", [(n, f"{e:.2e}") for n, e in top], flush=True)
+            for name, shape in O.param_spec(cfg):
+                g_ref = st.grads[name].reshape(-1)
+                e = gerr[name]
+                assert e <= grad_tol, (i, "grad", name, e)
+                worst["grad"] = max(worst.get("grad", 0), e)
+                # update arithmetic: the oracle's rule applied to the GPU's own tensors
+                if adamw:
+                    want, _, _ = O.adamw_update(p_before[name], grads[name], m_before[name], v_before[name], i + 1,
+                                                wl["lr"], wl["beta1"], wl["beta2"], wl["adam_eps"], wl["weight_decay"])
+                else:
+                    want, _ = O.sgd_update(p_before[name], grads[name], m_before[name], wl["lr"], wl["momentum"],
+                                           bool(wl["nesterov"]), wl["weight_decay"], i == 0)
+                e = rel_l2(params[name], want)
+                assert e <= 1e-5, (i, "update", name, e)
+                worst["update"] = max(worst.get("update", 0), e)
+                p_ref = st.params[name].reshape(-1)
+                if masked:
+                    keep = np.abs(g_ref) >= 0.05 * np.sqrt(np.mean(g_ref ** 2) + 1e-300)
+                    e = rel_l2(params[name][keep], p_ref[keep]) if keep.any() else 0.0
+                else:
+                    e = rel_l2(params[name], p_ref)
+                assert e <= tol, (i, "param", name, e)
+                worst["param"] = max(worst.get("param", 0), e)
+        if check_bn:
+            mean, var = gb.bn(P.T_BN_MEAN), gb.bn(P.T_BN_VAR)
+            for name, _ in O.bn_stat_spec(cfg):
+                assert rel_l2(mean[name], st.bn_mean[name]) <= tol, name
+                assert rel_l2(var[name], st.bn_var[name]) <= tol, name
+    finally:
+        gb.close()
+    print("  worst rel L2:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    return worst
+
+
+def _decisive_shifts(tensors):
+    """BatchNorm shifts of +6 / -6 by channel parity: every ReLU decision has a wide margin."""
+    for name, v in tensors.items():
+        if ".bn" in name and name.endswith(".b"):
+            v[:] = np.where(np.arange(v.size) % 2 == 0, 6.0, -6.0)
+        if name.endswith("bn2.b") or name == "aux.bn.b":      # keep the skip sum and the pooled features alive
+            v[:] = 6.0
+
+
+# ------------------------------------------------------------------ fp32 path
+def test_vit_tiny_fp32_one_sgd_step():
+    run_case(synth.workload("vit_tiny_fp32"), steps=1)
+
+
+def test_vit_tiny_fp32_three_steps():
+    run_case(synth.workload("vit_tiny_fp32"), steps=3, seed=1)
+
+
+def test_vit_fp32_ragged_activation_input_adamw():
+    # sizes off every tile edge: 7 tokens, dim 24 (3 heads of 8), mlp 40, batch 3
+    wl = synth.workload("vit_tiny_fp32", input_kind=synth.ACTIVATION, batch=3, tokens=7, dim=24, heads=3,
+                        mlp_dim=40, depth=2, aux_depth=1, optimizer=synth.ADAMW, weight_decay=0.01, lr=1e-3)
+    run_case(wl, steps=3)
+
+
+def test_vit_fp32_single_token():
+    wl = synth.workload("vit_tiny_fp32", input_kind=synth.ACTIVATION, batch=2, tokens=1, dim=16, heads=2,
+                        mlp_dim=32, depth=1, aux_depth=1)
+    run_case(wl, steps=2)
+
+
+def test_vit_fp32_image_many_tokens():
+    wl = synth.workload("vit_tiny_fp32", batch=2, img_h=40, img_w=48, patch=4, tokens=121, dim=32, heads=2,
+                        mlp_dim=64, depth=1, aux_depth=1)
+    run_case(wl, steps=2)
+
+
+def test_resnet_fp32_small():
+    wl = synth.workload("resnet_stage_bf16", precision=synth.FP32, batch=3, channels=8, height=6, width=10,
+                        n_basic_blocks=2, aux_channels=12)
+    run_case(wl, steps=3, check_bn=True)
+
+
+def test_resnet_fp32_odd_spatial_plain_sgd():
+    wl = synth.workload("resnet_stage_bf16", precision=synth.FP32, batch=2, channels=4, height=7, width=5,
+                        n_basic_blocks=1, aux_channels=6, momentum=0.0, nesterov=0, weight_decay=0.0)
+    run_case(wl, steps=2, check_bn=True)
+
+
+# ------------------------------------------------------------------ bf16 path
+def test_vit_bf16_medium():
+    wl = synth.workload("vit_stage_bf16", batch=8, dim=128, heads=2, mlp_dim=256, depth=2, aux_depth=1)
+    run_case(wl, steps=2)
+
+
+def test_vit_bf16_activation_input_ragged():
+    wl = synth.workload("vit_stage_act_bf16", batch=5, tokens=37, dim=192, heads=3, mlp_dim=320, depth=1,
+                        aux_depth=1)
+    run_case(wl, steps=2)
+
+
+def test_resnet_fp32_stage_full_size_decisive_masks():
+    # not a named workload: fp32 at the full ResNet size.  Gradients pass 10 BatchNorm backward
+    # stages, each a cancelling 32768-term reduction in fp32, so 1e-3 instead of 1e-4
+    run_case(synth.workload("resnet_stage_bf16", precision=synth.FP32), steps=1, check_bn=True, tol=1e-3,
+             tweak=_decisive_shifts)
+
+
+def test_resnet_fp32_stage_full_size_natural_statistics():
+    # a single flipped mask among ~1e6 elements moves a layer's gradient by ~1e-3
+    run_case(synth.workload("resnet_stage_bf16", precision=synth.FP32), steps=1, check_bn=True, tol=1e-3, grad_tol=5e-3)
+
+
+def test_resnet_bf16_one_block_full_activation_size():
+    run_case(synth.workload("resnet_stage_bf16", n_basic_blocks=1), steps=1, check_bn=True)
+
+
+def test_resnet_bf16_two_narrow_blocks():
+    # second block exercises the input-gradient + skip path; 8 channels keep the fan-out small
+    wl = synth.workload("resnet_stage_bf16", n_basic_blocks=2, channels=8, aux_channels=16, batch=16)
+    run_case(wl, steps=1, check_bn=True)
+
+
+def test_resnet_bf16_stage_full_size_natural_statistics():
+    run_case(synth.workload("resnet_stage_bf16"), steps=2, check_bn=True, grad_tol=0.3)
+
+
+def test_vit_stage_bf16_full_size():
+    run_case(synth.workload("vit_stage_bf16"), steps=1)
+
+
+def test_vit_large_image_bf16_full_size():
+    run_case(synth.workload("vit_large_image_bf16"), steps=1)
+
+
+# ------------------------------------------------------------------ error surfaced at sync
+def test_out_of_range_label_is_reported_at_sync():
+    from gpu_harness import GpuBlock
+    from paper_2411_12780_amd import binding as P
+    wl = synth.workload("vit_tiny_fp32")
+    cfg = oracle_cfg(wl)
+    gb = GpuBlock(wl, synth.make_params(O.param_spec(cfg), seed=0))
+    x, y = synth.make_batch(wl)
+    y = y.copy()
+    y[3] = 10
+    with pytest.raises(P.PpllError) as e:
+        gb.step(x, y, 0.01)
+    assert e.value.status == 6
+    y[3] = 9
+    gb.step(x, y, 0.01)                 # flag is cleared by the failed sync
+    gb.close()
+    with pytest.raises(P.PpllError) as e:
+        P.ppll_block_sync(gb.h)         # use after destroy is an error, not a crash
+    assert e.value.status == 7

@@ -307,3 +307,17 @@ def test_optimizer_first_step_closed_forms():
     close(buf, g + wd * p, 1e-15)
     q, m, v = O.adamw_update(p, g, np.zeros(9), np.zeros(9), 1, lr, 0.9, 0.999, 1e-8, 0.01)
     close(q, p * (1 - lr * 0.01) - lr * g / (np.abs(g) + 1e-8), 1e-12)
+
+
+# ---------------------------------------------------------------- bf16 storage emulation
+def test_bf16_values_matches_torch_rounding_and_ties_to_even():
+    a = (RNG.standard_normal(20000) * np.exp(RNG.uniform(-20, 20, 20000))).astype(np.float32)
+    want = torch.tensor(a).to(torch.bfloat16).to(torch.float32).numpy()
+    got = O.bf16_values(a.astype(np.float64))
+    assert np.array_equal(got, want.astype(np.float64))
+    # ties: 1 + 2^-8 lies midway between 1 and 1 + 2^-7 -> even (1); 1 + 3*2^-8 -> 1 + 2^-6
+    assert O.bf16_values(np.array([1 + 2.0 ** -8]))[0] == 1.0
+    assert O.bf16_values(np.array([1 + 3 * 2.0 ** -8]))[0] == 1 + 2.0 ** -6
+    assert O.bf16_values(np.array([0.0, -0.0, np.inf]))[2] == np.inf
+    x = O.bf16_values(RNG.standard_normal(1000))
+    assert np.array_equal(O.bf16_values(x), x)            # idempotent

@@ -293,3 +293,32 @@ def test_loss_decreases_when_overfitting_one_batch(case):
         _, loss = O.block_step(st, x, y, 0.05)
         first = loss if first is None else first
     assert loss < 0.8 * first
+
+
+# ------------------------------------------------------------------ what bf16 storage alone does
+def test_bf16_storage_alone_moves_relu_gradients_but_not_gelu_gradients():
+    """Oracle vs oracle: rounding stored activations and weight shadows to bf16 (arithmetic
+    still float64) flips the ReLU masks nearest zero, which moves the ResNet stage's
+    gradients by far more than 2e-2; the GELU network stays well inside it.  This is the
+    evidence behind the gradient ceiling used for the natural-statistics bf16 ResNet case
+    of the GPU parity tests."""
+    wl = synth.workload("resnet_stage_bf16", batch=32)
+    cfg = oracle_cfg(wl)
+    flat = synth.make_params(O.param_spec(cfg), seed=0, jitter=True)
+    x, y = synth.make_batch(wl)
+    a, b = O.block_init(cfg, flat), O.block_init(cfg, flat, storage="bf16")
+    oa, la = O.block_step(a, x.astype(np.float64), y, 0.01)
+    ob, lb = O.block_step(b, x.astype(np.float64), y, 0.01)
+    assert abs(la - lb) < 2e-2 * la and rel_l2(ob, oa) < 2e-2
+    worst = max(rel_l2(b.grads[n], a.grads[n]) for n in a.grads)
+    assert 0.05 < worst < 0.3, worst
+
+    wl = synth.workload("vit_stage_bf16", batch=4, dim=96, heads=2, mlp_dim=192)
+    cfg = oracle_cfg(wl)
+    flat = synth.make_params(O.param_spec(cfg), seed=0, jitter=True)
+    x, y = synth.make_batch(wl)
+    a, b = O.block_init(cfg, flat), O.block_init(cfg, flat, storage="bf16")
+    oa, la = O.block_step(a, x.astype(np.float64), y, 1e-3)
+    ob, lb = O.block_step(b, x.astype(np.float64), y, 1e-3)
+    assert rel_l2(ob, oa) < 1e-2
+    assert max(rel_l2(b.grads[n], a.grads[n]) for n in a.grads) < 2e-2
