@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the local-block training step on one MI355X.
+
+A step is one pass of the whole hot path (module forward, auxiliary forward,
+local cross-entropy, backward stopping at the block input, optimizer update)
+over one batch of seeded synthetic images already resident in HBM.  Prints one
+JSON line: images/s, the dominant kernel's roofline fraction (HIP events around
+every GEMM launch, in a second pass over the same workload) and the CPU oracle
+timed on the host cores of the same box.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def step_flops(wl: dict) -> float:
+    """Dense-definition flop count of one step (multiply-add = 2): forward + 2x backward for
+    every contraction, minus the input gradient that gradient isolation never needs."""
+    B = wl["batch"]
+    if wl["arch"] == 0:
+        T, D, F, H = wl["tokens"], wl["dim"], wl["mlp_dim"], wl["heads"]
+        M = B * T
+        layer_fwd = 2.0 * M * (D * 3 * D + D * D + 2 * D * F) + 4.0 * B * H * T * T * (D // H)
+        total = 3.0 * layer_fwd * (wl["depth"] + wl["aux_depth"])
+        total += 3.0 * 2.0 * B * D * wl["num_classes"]
+        if wl["input_kind"] == 0:
+            total += 2.0 * 2.0 * B * (T - 1) * wl["patch"] ** 2 * wl["img_c"] * D
+        return total
+    C, A, HW = wl["channels"], wl["aux_channels"], wl["height"] * wl["width"]
+    conv = 2.0 * B * HW * 9 * C * C
+    aux = 2.0 * B * (HW // 4) * 9 * C * A
+    return 3.0 * conv * 2 * wl["n_basic_blocks"] - conv + 3.0 * aux + 3.0 * 2.0 * B * A * wl["num_classes"]
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vit_stage_bf16")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-roofline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the pipeline: a block's local step runs on a single "
+              "MI355X and this build uses no second GPU; run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2411_12780_amd import binding as P
+    from paper_2411_12780_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
+    dev = "cuda:0"
+    wl = synth.workload(args.workload)
+    wl["seed"] = 0
+    cfg = P.make_config(wl)
+    ws_bytes = P.ppll_block_workspace_bytes(cfg)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    bf16 = wl["precision"] == synth.BF16
+    tdt = torch.bfloat16 if bf16 else torch.float32
+    blk = P.ppll_block_init(cfg, ws, ws_bytes, None, None)       # seeded draw inside the library
+    ring = 8
+    xs, ys = [], []
+    for i in range(ring):
+        x, y = synth.make_batch(wl, seed=0, index=i)
+        xs.append(torch.from_numpy(x).to(tdt).to(dev))
+        ys.append(torch.from_numpy(y).to(dev))
+    x_out = torch.empty(synth.output_shape(wl), dtype=tdt, device=dev)
+    loss = torch.zeros(1, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    lr = float(wl["lr"])
+
+    def run(n):
+        for i in range(n):
+            P.ppll_block_step(blk, xs[i % ring], ys[i % ring], lr, x_out, loss, stream)
+
+    run(args.warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    last_loss = P.ppll_block_sync(blk)
+    ms_per_step = 1e3 * elapsed / args.steps
+    flops = step_flops(wl)
+    out = {
+        "metric": "local-block train step images/sec on 1 MI355X; % bf16 MFMA peak",
+        "value": wl["batch"] / (elapsed / args.steps),
+        "unit": "images/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "batch": wl["batch"],
+                   "shape": {k: wl[k] for k in ("tokens", "dim", "heads", "mlp_dim", "depth", "aux_depth",
+                                                "channels", "height", "width", "n_basic_blocks") if k in wl},
+                   "optimizer": "adamw" if wl["optimizer"] == synth.ADAMW else "sgd"},
+        "step_gflop": flops / 1e9,
+        "step_tflops": flops / (elapsed / args.steps) / 1e12,
+        "mfma_peak_frac_step": flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
+        "loss_last_step": last_loss,
+    }
+
+    if not args.no_roofline:
+        # second pass over the same workload with every GEMM launch bracketed by HIP events
+        P.ppll_profile_enable(True)
+        P.ppll_profile_read()
+        run(args.steps)
+        torch.cuda.synchronize()
+        gemm_ms, gemm_flops, launches = P.ppll_profile_read()
+        P.ppll_profile_enable(False)
+        achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+        out["roofline"] = {"bound": "mfma", "kernel": "gemm (all Linear fwd/dgrad/wgrad launches)",
+                           "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                           "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                           "launches_per_step": launches / args.steps,
+                           "avg_launch_us": 1e3 * gemm_ms / max(launches, 1),
+                           "gemm_ms_per_step": gemm_ms / args.steps,
+                           "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
+
+    if not args.no_cpu_baseline:
+        from oracle import ppll_oracle as O
+        from helpers import oracle_cfg
+        from threadpoolctl import threadpool_info
+        ocfg = oracle_cfg(wl)
+        st = O.block_init(ocfg, synth.make_params(O.param_spec(ocfg), seed=0), np.float64)
+        x, y = synth.make_batch(wl, seed=0, index=0)
+        n_steps = 10 if wl["batch"] * wl.get("tokens", 1) < 2048 else 1
+        t0 = time.perf_counter()
+        for _ in range(n_steps):
+            O.block_step(st, x.astype(np.float64), y, lr)
+        cpu_s = (time.perf_counter() - t0) / n_steps
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
+        out["cpu_baseline"] = {"value": wl["batch"] / cpu_s, "unit": "images/s", "cores": threads,
+                               "kind": "oracle", "sample": f"{n_steps} full step(s) of the same workload "
+                               f"(batch {wl['batch']}), float64 numpy oracle, {cpu_s:.2f} s per step"}
+    P.ppll_block_destroy(blk)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -173,6 +173,16 @@ int ppll_pipeline_output(ppll_pipeline_t* pipe, const void** x_out_dev, size_t* 
 
 int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
 
+/* Measurement aid (no part of the method).  While enabled, every launch of the
+ * dense-contraction (GEMM) kernels, which carry the bulk of the step's
+ * arithmetic, is bracketed by a pair of HIP events on its own stream.
+ * ppll_profile_read waits for those events and returns, since the previous
+ * read: their summed duration in milliseconds, the algorithmic flops 2*M*N*K of
+ * the bracketed launches, and their count (each pointer nullable).  The events
+ * add host and stream overhead: time whole steps with profiling off. */
+int ppll_profile_enable(int32_t on);
+int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
+
 #ifdef __cplusplus
 }
 #endif

@@ -79,6 +79,8 @@ _SIGS = {
     "ppll_pipeline_block": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]),
     "ppll_pipeline_output": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
     "ppll_pipeline_destroy": (C.c_int, [C.c_void_p]),
+    "ppll_profile_enable": (C.c_int, [C.c_int32]),
+    "ppll_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -90,6 +92,9 @@ def lib() -> C.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
                                "(there is no CPU fallback)")
+        # PyTorch-ROCm ships its own HIP runtime and owns the device memory and streams handed to
+        # the library: load it first so that the process holds a single libamdhip64.
+        import torch  # noqa: F401
         l = C.CDLL(LIB_PATH)
         for name, (res, args) in _SIGS.items():
             fn = getattr(l, name)
@@ -236,3 +241,14 @@ def ppll_pipeline_output(pipe: int):
 
 def ppll_pipeline_destroy(pipe: int) -> None:
     _check(lib().ppll_pipeline_destroy(pipe))
+
+
+def ppll_profile_enable(on: bool) -> None:
+    _check(lib().ppll_profile_enable(1 if on else 0))
+
+
+def ppll_profile_read():
+    """(milliseconds, flops, launches) of the GEMM launches bracketed since the last read."""
+    ms, fl, n = C.c_double(0), C.c_double(0), C.c_int64(0)
+    _check(lib().ppll_profile_read(C.byref(ms), C.byref(fl), C.byref(n)))
+    return ms.value, fl.value, n.value

@@ -118,6 +118,15 @@ extern "C" {
 
 const char* ppll_last_error(void) { return g_err; }
 
+int ppll_profile_enable(int32_t on) { profile_enable(on != 0); return PPLL_OK; }
+
+int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches) {
+  long long n = 0;
+  PPLL_TRY(profile_read(gemm_ms, gemm_flops, &n));
+  if (gemm_launches) *gemm_launches = n;
+  return PPLL_OK;
+}
+
 int ppll_block_workspace_bytes(const ppll_block_config* cfg, size_t* bytes) {
   PPLL_TRY(validate_config(cfg));
   if (!bytes) { set_error("bytes is null"); return PPLL_ERR_NULL; }

@@ -87,6 +87,8 @@ struct GemmArgs {
 };
 int launch_gemm(hipStream_t s, const GemmArgs& g);          // picks the MFMA kernel when the shape allows
 int launch_gemm_generic(hipStream_t s, const GemmArgs& g);
+void profile_enable(bool on);
+int profile_read(double* ms, double* flops, long long* launches);
 int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out);
 int colsum_mode(hipStream_t s, const void* x, int dt, int rows, int N, int mode, const float* shift, float scale,
                 float* partials, float* out);

@@ -1,10 +1,59 @@
 // Kernel selection: the MFMA kernels take the bf16 shapes they are built for,
-// everything else goes to the run-time-typed kernels.
+// everything else goes to the run-time-typed kernels.  Also holds the optional
+// per-launch timing of the contraction kernels used by the benchmark.
+#include <vector>
+
 #include "common.h"
 
 namespace ppll {
 
-int launch_gemm(hipStream_t s, const GemmArgs& g) { return launch_gemm_generic(s, g); }
+namespace {
+struct TimedLaunch { hipEvent_t a, b; double flops; };
+bool g_profile = false;
+std::vector<TimedLaunch> g_timed;
+std::vector<hipEvent_t> g_pool;
+
+hipEvent_t pooled_event() {
+  if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+}  // namespace
+
+void profile_enable(bool on) { g_profile = on; }
+
+// Sums the elapsed time of every bracketed launch since the last read.
+int profile_read(double* ms, double* flops, long long* launches) {
+  double t = 0.0, f = 0.0;
+  for (TimedLaunch& l : g_timed) {
+    PPLL_HIP(hipEventSynchronize(l.b));
+    float dt = 0.f;
+    PPLL_HIP(hipEventElapsedTime(&dt, l.a, l.b));
+    t += dt; f += l.flops;
+    g_pool.push_back(l.a); g_pool.push_back(l.b);
+  }
+  if (ms) *ms = t;
+  if (flops) *flops = f;
+  if (launches) *launches = (long long)g_timed.size();
+  g_timed.clear();
+  return PPLL_OK;
+}
+
+int launch_gemm(hipStream_t s, const GemmArgs& g) {
+  TimedLaunch tl{nullptr, nullptr, 2.0 * g.M * g.N * g.K};
+  if (g_profile) {
+    tl.a = pooled_event(); tl.b = pooled_event();
+    if (!tl.a || !tl.b) { set_error("hipEventCreate failed"); return PPLL_ERR_HIP; }
+    PPLL_HIP(hipEventRecord(tl.a, s));
+  }
+  int st = launch_gemm_generic(s, g);
+  if (g_profile) {
+    PPLL_HIP(hipEventRecord(tl.b, s));
+    g_timed.push_back(tl);
+  }
+  return st;
+}
 
 int launch_attention_fwd(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out, float* lse) {
   return launch_attention_fwd_generic(s, qkv, dt, B, T, H, dh, out, lse);

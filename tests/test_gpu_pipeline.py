@@ -1,0 +1,160 @@
+"""K blocks on K streams linked by bounded device queues (Algorithm 1 run for all
+j at once) must compute exactly what K block steps called in order compute:
+bit-identical on the GPU for every queue depth, and within tolerance of the
+oracle's sequential chain."""
+import numpy as np
+import pytest
+
+from oracle import ppll_oracle as O
+from paper_2411_12780_amd import synth
+from helpers import oracle_cfg, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def _blocks(first, rest, K, seed=0):
+    wls = [first] + [rest] * (K - 1)
+    flats = [synth.make_params(O.param_spec(oracle_cfg(w)), seed=seed + j, jitter=True) for j, w in enumerate(wls)]
+    return wls, flats
+
+
+def _run_pipeline(wls, flats, batches, depth, lr):
+    import torch
+    from paper_2411_12780_amd import binding as P
+    from gpu_harness import to_device, DEV
+    cfgs = [P.make_config(w) for w in wls]
+    K = len(cfgs)
+    nbytes = P.ppll_pipeline_workspace_bytes(cfgs, depth)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    streams = [torch.cuda.Stream(device=DEV) for _ in range(K)]
+    pipe = P.ppll_pipeline_init(cfgs, depth, ws, nbytes, [s.cuda_stream for s in streams], flats)
+    losses_dev = torch.zeros(K, dtype=torch.float32, device=DEV)
+    xs = [to_device(x, wls[0]) for x, _ in batches]
+    ys = [torch.from_numpy(y.astype(np.int32)).to(DEV) for _, y in batches]
+    torch.cuda.synchronize()
+    all_losses = []
+    for x, y in zip(xs, ys):
+        P.ppll_pipeline_step(pipe, x, y, lr, losses_dev)
+        # reading the losses of every batch needs a sync; the last test runs without it
+        all_losses.append(P.ppll_pipeline_sync(pipe, K).copy())
+        assert np.array_equal(all_losses[-1], losses_dev.cpu().numpy())
+    params = []
+    for j in range(K):
+        h = P.ppll_pipeline_block(pipe, j)
+        n = P.ppll_block_tensor_count(h, P.T_PARAM)
+        params.append([P.ppll_block_read_tensor(h, P.T_PARAM, i) for i in range(n)])
+    ptr, nb = P.ppll_pipeline_output(pipe)
+    assert nb == P.ppll_block_out_bytes(cfgs[-1]) and ptr
+    P.ppll_pipeline_destroy(pipe)
+    return np.array(all_losses), params
+
+
+def _run_sequential(wls, flats, batches, lr):
+    from gpu_harness import GpuBlock, to_device
+    from paper_2411_12780_amd import binding as P
+    import torch
+    blocks = [GpuBlock(w, f) for w, f in zip(wls, flats)]
+    all_losses = []
+    for x, y in batches:
+        cur = to_device(x, wls[0])
+        yd = torch.from_numpy(y.astype(np.int32)).to("cuda:0")
+        losses = []
+        for b in blocks:
+            P.ppll_block_step(b.h, cur, yd, lr, b.x_out, b.loss, torch.cuda.current_stream().cuda_stream)
+            losses.append(P.ppll_block_sync(b.h))
+            cur = b.x_out
+        all_losses.append(losses)
+    params = [[P.ppll_block_read_tensor(b.h, P.T_PARAM, i) for i in range(len(b.names))] for b in blocks]
+    for b in blocks:
+        b.close()
+    return np.array(all_losses, dtype=np.float32), params
+
+
+def _oracle_chain(wls, flats, batches, lr, storage=None):
+    states = [O.block_init(oracle_cfg(w), f, np.float64, storage=storage) for w, f in zip(wls, flats)]
+    out = []
+    for x, y in batches:
+        losses, _ = O.chain_step(states, x.astype(np.float64), y, lr)
+        out.append(losses)
+    return np.array(out), states
+
+
+def test_pipeline_equals_sequential_chain_fp32_all_depths():
+    first = synth.workload("vit_tiny_fp32", depth=1)
+    rest = synth.workload("vit_tiny_fp32", depth=1, aux_depth=1, input_kind=synth.ACTIVATION)
+    wls, flats = _blocks(first, rest, K=3)
+    batches = [synth.make_batch(first, seed=3, index=i) for i in range(5)]
+    seq_losses, seq_params = _run_sequential(wls, flats, batches, 0.01)
+    ref_losses, states = _oracle_chain(wls, flats, batches, 0.01)
+    assert np.abs(seq_losses - ref_losses).max() <= 1e-4 * np.abs(ref_losses).max()
+    for depth in (1, 2, 4):
+        print(f"  depth {depth}", flush=True)
+        losses, params = _run_pipeline(wls, flats, batches, depth, 0.01)
+        assert np.array_equal(losses, seq_losses), depth
+        for j in range(3):
+            for a, b in zip(params[j], seq_params[j]):
+                assert np.array_equal(a, b), (depth, j)
+    for j, st in enumerate(states):
+        for (name, _), got in zip(O.param_spec(st.cfg), seq_params[j]):
+            assert rel_l2(got, st.params[name]) <= 1e-4, (j, name)
+
+
+def test_pipeline_resnet_two_stages_fp32():
+    wl = synth.workload("resnet_stage_bf16", precision=synth.FP32, batch=4, channels=8, height=8, width=8,
+                        n_basic_blocks=1, aux_channels=8)
+    wls, flats = _blocks(wl, wl, K=2)
+    batches = [synth.make_batch(wl, seed=4, index=i) for i in range(4)]
+    seq_losses, seq_params = _run_sequential(wls, flats, batches, 0.01)
+    losses, params = _run_pipeline(wls, flats, batches, 2, 0.01)
+    assert np.array_equal(losses, seq_losses)
+    ref_losses, _ = _oracle_chain(wls, flats, batches, 0.01)
+    assert np.abs(seq_losses - ref_losses).max() <= 1e-4 * np.abs(ref_losses).max()
+
+
+def test_pipeline_four_vit_blocks_bf16_full_size():
+    """The 12-layer ViT cut into 4 blocks of 3 layers, each with its own aux head and AdamW."""
+    first = synth.workload("vit_stage_bf16")
+    rest = synth.workload("vit_stage_act_bf16")
+    wls, flats = _blocks(first, rest, K=4)
+    batches = [synth.make_batch(first, seed=5, index=i) for i in range(3)]
+    print("  sequential", flush=True)
+    seq_losses, seq_params = _run_sequential(wls, flats, batches, 1e-3)
+    print("  pipeline depth 2", flush=True)
+    losses, params = _run_pipeline(wls, flats, batches, 2, 1e-3)
+    assert np.array_equal(losses, seq_losses)
+    for j in range(4):
+        for a, b in zip(params[j], seq_params[j]):
+            assert np.array_equal(a, b), j
+    print("  oracle chain, first batch", flush=True)
+    ref_losses, _ = _oracle_chain(wls, flats, batches[:1], 1e-3, storage="bf16")
+    assert np.abs(seq_losses[0] - ref_losses[0]).max() <= 2e-2 * np.abs(ref_losses[0]).max()
+
+
+def test_pipeline_runs_ahead_without_host_syncs():
+    """Enqueue several batches back to back (no sync in between): the bounded queues and the
+    event edges alone must keep the order; results equal the synchronised run."""
+    import torch
+    from paper_2411_12780_amd import binding as P
+    from gpu_harness import to_device, DEV
+    first = synth.workload("vit_tiny_fp32", depth=1)
+    rest = synth.workload("vit_tiny_fp32", depth=1, aux_depth=1, input_kind=synth.ACTIVATION)
+    wls, flats = _blocks(first, rest, K=3)
+    batches = [synth.make_batch(first, seed=6, index=i) for i in range(7)]
+    want_losses, want_params = _run_pipeline(wls, flats, batches, 2, 0.01)
+    cfgs = [P.make_config(w) for w in wls]
+    nbytes = P.ppll_pipeline_workspace_bytes(cfgs, 2)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    streams = [torch.cuda.Stream(device=DEV) for _ in range(3)]
+    pipe = P.ppll_pipeline_init(cfgs, 2, ws, nbytes, [s.cuda_stream for s in streams], flats)
+    xs = [to_device(x, first) for x, _ in batches]
+    ys = [torch.from_numpy(y.astype(np.int32)).to(DEV) for _, y in batches]
+    torch.cuda.synchronize()
+    for x, y in zip(xs, ys):
+        P.ppll_pipeline_step(pipe, x, y, 0.01)
+    last = P.ppll_pipeline_sync(pipe, 3)
+    assert np.array_equal(last, want_losses[-1])
+    for j in range(3):
+        h = P.ppll_pipeline_block(pipe, j)
+        for i, b in enumerate(want_params[j]):
+            assert np.array_equal(P.ppll_block_read_tensor(h, P.T_PARAM, i), b), j
+    P.ppll_pipeline_destroy(pipe)
