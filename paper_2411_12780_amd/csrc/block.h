@@ -55,6 +55,8 @@ struct Block {
   int* flag_dev = nullptr;
   float* partials = nullptr;
   size_t partial_floats = 0;
+  float* splitk = nullptr;       // split-K partial sums of the weight-gradient GEMMs
+  size_t splitk_floats = 0;
 
   // ViT
   size_t pe_w = 0, pe_b = 0, cls = 0, pos = 0, head_ln_g = 0, head_ln_b = 0, head_w = 0, head_b = 0;

@@ -163,6 +163,15 @@ size_t Block::plan(char* base) {
     head_mean = bump.floats(B); head_rstd = bump.floats(B);
     gA = bump.take(M * D * esz); gB = bump.take(M * D * esz); d_u = bump.take(M * D * esz);
     d_h = bump.take(M * F * esz); d_qkv = bump.take(M * 3 * D * esz);
+    if (dt == BF16) {
+      const size_t cand[] = {gemm_mfma_partial_floats(D, 3 * D, (int)M), gemm_mfma_partial_floats(D, D, (int)M),
+                             gemm_mfma_partial_floats(D, F, (int)M), gemm_mfma_partial_floats(F, D, (int)M),
+                             cfg.input_kind == PPLL_IN_IMAGE
+                                 ? gemm_mfma_partial_floats(cfg.patch * cfg.patch * cfg.img_c, D, B * (T - 1)) : 0};
+      splitk_floats = 0;
+      for (size_t c : cand) if (c > splitk_floats) splitk_floats = c;
+      splitk = splitk_floats ? bump.floats(splitk_floats) : nullptr;
+    }
     int widest = 3 * D > F ? 3 * D : F;
     partial_floats = (size_t)colsum_partial_floats((int)M, widest);
     size_t ln = (size_t)layernorm_bwd_partial_floats((int)M, D);
@@ -247,6 +256,7 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
     g.A = xin; g.a_dt = dt; g.a_sm = 1; g.a_sk = in_dim;
     g.B = dy; g.b_dt = dt; g.b_sk = out_dim; g.b_sn = 1;
     g.C = grads + w_off; g.c_dt = F32; g.ldc = out_dim; g.M = in_dim; g.N = out_dim; g.K = M;
+    g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
     return launch_gemm(s, g);
   };
   GemmArgs g = dgrad(g_in, D, p.fc2_w, F, d_h);
@@ -338,6 +348,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
       g.A = patches; g.a_dt = dt; g.a_sm = 1; g.a_sk = ppc;
       g.B = embed_tmp; g.b_dt = dt; g.b_sk = D; g.b_sn = 1;
       g.C = grads + pe_w; g.c_dt = F32; g.ldc = D; g.M = ppc; g.N = D; g.K = B * (T - 1);
+      g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
       PPLL_TRY(launch_gemm(s, g));
       PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, partials, grads + pe_b));
     } else {

@@ -47,7 +47,7 @@ int launch_gemm(hipStream_t s, const GemmArgs& g) {
     if (!tl.a || !tl.b) { set_error("hipEventCreate failed"); return PPLL_ERR_HIP; }
     PPLL_HIP(hipEventRecord(tl.a, s));
   }
-  int st = launch_gemm_generic(s, g);
+  int st = gemm_mfma_supported(g) ? launch_gemm_mfma(s, g, g.splitk_ws, g.splitk_floats) : launch_gemm_generic(s, g);
   if (g_profile) {
     PPLL_HIP(hipEventRecord(tl.b, s));
     g_timed.push_back(tl);
