@@ -250,32 +250,31 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
     g.C = dxo; g.c_dt = dt; g.ldc = in_dim; g.M = M; g.N = in_dim; g.K = out_dim;
     return g;
   };
-  // dW[in,out] = X^T dY, reduction over the M rows
-  auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off) {
+  // dW[in,out] = X^T dY and db = column sums of dY, reduction over the M rows
+  auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off, size_t b_off) {
     GemmArgs g = gemm_args();
     g.A = xin; g.a_dt = dt; g.a_sm = 1; g.a_sk = in_dim;
     g.B = dy; g.b_dt = dt; g.b_sk = out_dim; g.b_sn = 1;
     g.C = grads + w_off; g.c_dt = F32; g.ldc = out_dim; g.M = in_dim; g.N = out_dim; g.K = M;
     g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
-    return launch_gemm(s, g);
+    g.colsum = grads + b_off;
+    const bool fused = gemm_fuses_colsum(g);
+    PPLL_TRY(launch_gemm(s, g));
+    return fused ? (int)PPLL_OK : launch_colsum(s, dy, dt, M, out_dim, partials, grads + b_off);
   };
   GemmArgs g = dgrad(g_in, D, p.fc2_w, F, d_h);
   g.epilogue = EPI_DGELU; g.aux = a.h; g.aux_dt = dt; g.ldaux = F;
   PPLL_TRY(launch_gemm(s, g));
-  PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w));
-  PPLL_TRY(launch_colsum(s, g_in, dt, M, D, partials, grads + p.fc2_b));
+  PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w, p.fc2_b));
   PPLL_TRY(launch_gemm(s, dgrad(d_h, F, p.fc1_w, D, d_u)));
-  PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w));
-  PPLL_TRY(launch_colsum(s, d_h, dt, M, F, partials, grads + p.fc1_b));
+  PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w, p.fc1_b));
   PPLL_TRY(launch_layernorm_bwd(s, d_u, a.x1, dt, D, M, D, params + p.ln2_g, a.mean2, a.rstd2, g_in, g_tmp, partials,
                                 grads + p.ln2_g, grads + p.ln2_b));
   PPLL_TRY(launch_gemm(s, dgrad(g_tmp, D, p.proj_w, D, d_u)));
-  PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w));
-  PPLL_TRY(launch_colsum(s, g_tmp, dt, M, D, partials, grads + p.proj_b));
+  PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w, p.proj_b));
   PPLL_TRY(launch_attention_bwd(s, a.qkv, a.att, d_u, a.lse, dt, cfg.batch, T, H, D / H, d_qkv));
   PPLL_TRY(launch_gemm(s, dgrad(d_qkv, 3 * D, p.qkv_w, D, d_u)));
-  PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w));
-  PPLL_TRY(launch_colsum(s, d_qkv, dt, M, 3 * D, partials, grads + p.qkv_b));
+  PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b));
   return launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, g_tmp,
                               need_dx ? g_out : nullptr, partials, grads + p.ln1_g, grads + p.ln1_b);
 }

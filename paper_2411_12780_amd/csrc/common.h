@@ -85,10 +85,13 @@ struct GemmArgs {
   void* C2;                                   // EPI_GELU second output (c_dt, ldc)
   const void* aux; int aux_dt; long ldaux;    // EPI_DGELU saved pre-activation
   float* splitk_ws; size_t splitk_floats;     // optional scratch for split-K partial sums
+  float* colsum;                              // optional: out[n] = sum_k B(k,n) (bias gradient of a dW product);
+                                              // honoured only by the MFMA kernel, see gemm_fuses_colsum()
 };
 int launch_gemm(hipStream_t s, const GemmArgs& g);          // picks the MFMA kernel when the shape allows
 int launch_gemm_generic(hipStream_t s, const GemmArgs& g);
 bool gemm_mfma_supported(const GemmArgs& g);
+inline bool gemm_fuses_colsum(const GemmArgs& g) { return g.colsum && gemm_mfma_supported(g); }
 size_t gemm_mfma_partial_floats(int M, int N, int K);
 int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t partial_floats);
 void profile_enable(bool on);

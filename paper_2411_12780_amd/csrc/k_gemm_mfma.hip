@@ -42,6 +42,7 @@ struct MfmaArgs {
   int tiles_m, tiles_n;
   int kt_per_split;                 // k-tiles per split
   float* partial;                   // [splits][M][N] when split-K
+  float* colsum;                    // optional: [splits][N] sums over k of B(k, n) (bias gradient), else null
   const float* bias;
   const uint16_t* residual; long ldr;
   int epilogue;
@@ -142,12 +143,26 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   };
   if (kt0 < kt1) load_tiles(kt0);
   const int frag_row = lane & 31, frag_g = lane >> 5;
+  // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k
+  const bool do_colsum = p.colsum != nullptr && m0 == 0;
+  float csum = 0.f;
   for (int kt = kt0; kt < kt1; ++kt) {
     __syncthreads();
     if (AT) store_transposed(lds_a, tid, ra); else store_direct(lds_a, tid, ra);
     if (BT) store_transposed(lds_b, tid, rb); else store_direct(lds_b, tid, rb);
     __syncthreads();
     if (kt + 1 < kt1) load_tiles(kt + 1);
+    if (do_colsum) {   // thread (row = tid/2, half = tid%2) sums 4 of the row's 8 granules; their order is irrelevant
+      const char* rowp = lds_b + (tid >> 1) * ROW_BYTES + (tid & 1) * 64;
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        uint4 w = *reinterpret_cast<const uint4*>(rowp + gq * 16);
+        csum += bf16_to_f32((uint16_t)(w.x & 0xffff)) + bf16_to_f32((uint16_t)(w.x >> 16)) +
+                bf16_to_f32((uint16_t)(w.y & 0xffff)) + bf16_to_f32((uint16_t)(w.y >> 16)) +
+                bf16_to_f32((uint16_t)(w.z & 0xffff)) + bf16_to_f32((uint16_t)(w.z >> 16)) +
+                bf16_to_f32((uint16_t)(w.w & 0xffff)) + bf16_to_f32((uint16_t)(w.w >> 16));
+      }
+    }
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 fa[2], fb[2];
@@ -165,6 +180,11 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
     }
   }
 
+  if (do_colsum) {
+    csum += __shfl_xor(csum, 1, 64);
+    const int n = n0 + (tid >> 1);
+    if (!(tid & 1) && n < p.N) p.colsum[(size_t)split * p.N + n] = csum;
+  }
   // acc[jn][im][4q + e] = C[m][n] with m = m0 + wm*64 + im*32 + lane%32, n = n0 + wn*64 + jn*32 + 8q + 4*(lane/32) + e
 #pragma unroll
   for (int im = 0; im < 2; ++im) {
@@ -262,7 +282,7 @@ int gemm_mfma_splits(int M, int N, int K) {
 }
 size_t gemm_mfma_partial_floats(int M, int N, int K) {
   int s = gemm_mfma_splits(M, N, K);
-  return s > 1 ? (size_t)s * M * N : 0;
+  return s > 1 ? (size_t)s * M * N + (size_t)s * N : 0;   // tile partials, then bias-gradient partials
 }
 
 int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t partial_floats) {
@@ -280,8 +300,10 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   const bool plain = !g.bias && !g.residual && g.epilogue == EPI_NONE && g.c_dt == F32 && g.ldc == g.N;
   if (plain && partial) {
     splits = gemm_mfma_splits(g.M, g.N, g.K);
-    if ((size_t)splits * g.M * g.N > partial_floats) splits = 1;
+    if ((size_t)splits * g.M * g.N + (size_t)splits * g.N > partial_floats) splits = 1;
   }
+  float* colsum_partial = splits > 1 ? partial + (size_t)splits * g.M * g.N : nullptr;
+  p.colsum = g.colsum ? (splits > 1 ? colsum_partial : g.colsum) : nullptr;
   p.kt_per_split = (nkt + splits - 1) / splits;
   p.partial = splits > 1 ? partial : nullptr;
   dim3 grid(p.tiles_m * p.tiles_n, splits);
@@ -294,6 +316,7 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
     size_t mn = (size_t)g.M * g.N;
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((mn / 4 + 255) / 256), dim3(256), 0, s, partial, splits, mn, (float*)g.C);
     PPLL_HIP(hipGetLastError());
+    if (g.colsum) PPLL_TRY(reduce_partials(s, colsum_partial, splits, g.N, g.N, 1.0f, g.colsum));
   }
   return PPLL_OK;
 }

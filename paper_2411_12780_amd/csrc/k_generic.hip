@@ -107,19 +107,29 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(const void* x, int 
   partial[(size_t)blockIdx.y * N + n] = acc;
 }
 
-// out[n] = scale * sum_c partial[c][n]
+// out[n] = scale * sum_c partial[c*stride + n].  A workgroup owns 16 columns; 16 thread groups
+// take the chunks round-robin and are combined through LDS in a fixed order.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* partial, int chunks, int N, long stride,
                                                               float scale, float* out) {
-  int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= N) return;
+  __shared__ float red[16][17];
+  const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int n = blockIdx.x * 16 + col;
   float acc = 0.f;
-  for (int c = 0; c < chunks; ++c) acc += partial[(size_t)c * stride + n];
-  out[n] = acc * scale;
+  if (n < N)
+    for (int c = grp; c < chunks; c += 16) acc += partial[(size_t)c * stride + n];
+  red[grp][col] = acc;
+  __syncthreads();
+  if (grp == 0 && n < N) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) t += red[g][col];
+    out[n] = t * scale;
+  }
 }
 }  // namespace
 
 int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out) {
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 255) / 256), dim3(256), 0, s, partial, chunks, N, stride, scale,
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 15) / 16), dim3(256), 0, s, partial, chunks, N, stride, scale,
                      out);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
@@ -203,10 +213,131 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const void* dy, cons
 }
 }  // namespace
 
+// ---- bf16 fast path: one wave per row, the row held in registers (NJ x 2 values per lane), one pass
+namespace {
+__device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack_bf(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+
+template <int NJ>
+__global__ __launch_bounds__(256) void layernorm_fwd_bf16_kernel(const uint16_t* x, long xs, int rows,
+                                                                 const float* g, const float* b, float eps,
+                                                                 uint16_t* y, float* mean, float* rstd) {
+  constexpr int D = NJ * 128;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + (size_t)row * xs);
+  float v[2 * NJ];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    uint32_t w = xr[lane + 64 * j];
+    v[2 * j] = lo_bf(w); v[2 * j + 1] = hi_bf(w);
+    s += v[2 * j] + v[2 * j + 1];
+  }
+  const float mu = wave_sum(s) * (1.0f / D);
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < 2 * NJ; ++j) { v[j] -= mu; q += v[j] * v[j]; }
+  const float rs = rsqrtf(wave_sum(q) * (1.0f / D) + eps);
+  uint32_t* yr = reinterpret_cast<uint32_t*>(y + (size_t)row * D);
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = 2 * lane + 128 * j;
+    float2 gg = *reinterpret_cast<const float2*>(g + c), bb = *reinterpret_cast<const float2*>(b + c);
+    yr[lane + 64 * j] = pack_bf(v[2 * j] * rs * gg.x + bb.x, v[2 * j + 1] * rs * gg.y + bb.y);
+  }
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+}
+
+constexpr int LNF_ROWS = 64;   // rows per workgroup in the fast backward (4 waves x 16)
+template <int NJ>
+__global__ __launch_bounds__(256) void layernorm_bwd_bf16_kernel(const uint16_t* dy, const uint16_t* x, long xs,
+                                                                 int rows, const float* g, const float* mean,
+                                                                 const float* rstd, const uint16_t* dres,
+                                                                 uint16_t* dx, float* partial) {
+  constexpr int D = NJ * 128;
+  __shared__ float sm[4][2 * D];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float gg[2 * NJ], adg[2 * NJ], adb[2 * NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    float2 t = *reinterpret_cast<const float2*>(g + 2 * lane + 128 * j);
+    gg[2 * j] = t.x; gg[2 * j + 1] = t.y;
+  }
+#pragma unroll
+  for (int j = 0; j < 2 * NJ; ++j) { adg[j] = 0.f; adb[j] = 0.f; }
+  const int r0 = blockIdx.x * LNF_ROWS;
+  for (int rr = wave; rr < LNF_ROWS; rr += 4) {
+    const int row = r0 + rr;
+    if (row >= rows) break;
+    const float mu = mean[row], rs = rstd[row];
+    const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + (size_t)row * xs);
+    const uint32_t* dyr = reinterpret_cast<const uint32_t*>(dy + (size_t)row * D);
+    float xh[2 * NJ], dyh[2 * NJ];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      uint32_t wx = xr[lane + 64 * j], wd = dyr[lane + 64 * j];
+      float d0 = lo_bf(wd), d1 = hi_bf(wd);
+      xh[2 * j] = (lo_bf(wx) - mu) * rs; xh[2 * j + 1] = (hi_bf(wx) - mu) * rs;
+      adg[2 * j] += d0 * xh[2 * j]; adg[2 * j + 1] += d1 * xh[2 * j + 1];
+      adb[2 * j] += d0; adb[2 * j + 1] += d1;
+      dyh[2 * j] = d0 * gg[2 * j]; dyh[2 * j + 1] = d1 * gg[2 * j + 1];
+      s1 += dyh[2 * j] + dyh[2 * j + 1];
+      s2 += dyh[2 * j] * xh[2 * j] + dyh[2 * j + 1] * xh[2 * j + 1];
+    }
+    s1 = wave_sum(s1) * (1.0f / D); s2 = wave_sum(s2) * (1.0f / D);
+    if (dx) {
+      uint32_t* dxr = reinterpret_cast<uint32_t*>(dx + (size_t)row * D);
+      const uint32_t* rr_ = dres ? reinterpret_cast<const uint32_t*>(dres + (size_t)row * D) : nullptr;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        float a = rs * (dyh[2 * j] - s1 - xh[2 * j] * s2), c = rs * (dyh[2 * j + 1] - s1 - xh[2 * j + 1] * s2);
+        if (rr_) { uint32_t w = rr_[lane + 64 * j]; a += lo_bf(w); c += hi_bf(w); }
+        dxr[lane + 64 * j] = pack_bf(a, c);
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    const int c = 2 * lane + 128 * j;
+    sm[wave][c] = adg[2 * j]; sm[wave][c + 1] = adg[2 * j + 1];
+    sm[wave][D + c] = adb[2 * j]; sm[wave][D + c + 1] = adb[2 * j + 1];
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < 2 * D; i += 256)
+    partial[(size_t)blockIdx.x * 2 * D + i] = sm[0][i] + sm[1][i] + sm[2][i] + sm[3][i];
+}
+
+bool ln_fast_ok(int dt, int D, long xs, const void* a, const void* b, const void* c, const void* d) {
+  if (dt != BF16 || (xs & 1)) return false;
+  if (!(D == 128 || D == 256 || D == 384 || D == 512 || D == 768 || D == 1024)) return false;
+  return !((((uintptr_t)a) | ((uintptr_t)b) | ((uintptr_t)c) | ((uintptr_t)d)) & 7);
+}
+}  // namespace
+
+#define LN_DISPATCH(NJ_EXPR, CALL)                  \
+  switch (NJ_EXPR) {                                \
+    case 1: { constexpr int NJ = 1; CALL; break; }  \
+    case 2: { constexpr int NJ = 2; CALL; break; }  \
+    case 3: { constexpr int NJ = 3; CALL; break; }  \
+    case 4: { constexpr int NJ = 4; CALL; break; }  \
+    case 6: { constexpr int NJ = 6; CALL; break; }  \
+    default: { constexpr int NJ = 8; CALL; break; } \
+  }
+
 int launch_layernorm_fwd(hipStream_t s, const void* x, int dt, long xs, int rows, int D, const float* g,
                          const float* b, float eps, void* y, float* mean, float* rstd) {
-  hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, x, dt, xs, rows, D, g, b, eps, y,
-                     mean, rstd);
+  if (ln_fast_ok(dt, D, xs, x, y, g, b)) {
+    LN_DISPATCH(D / 128, hipLaunchKernelGGL((layernorm_fwd_bf16_kernel<NJ>), dim3((rows + 3) / 4), dim3(256), 0, s,
+                                            (const uint16_t*)x, xs, rows, g, b, eps, (uint16_t*)y, mean, rstd));
+  } else {
+    hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, x, dt, xs, rows, D, g, b, eps, y,
+                       mean, rstd);
+  }
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
@@ -216,13 +347,22 @@ int layernorm_bwd_partial_floats(int rows, int D) { return ((rows + LN_ROWS - 1)
 int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, long xs, int rows, int D,
                          const float* g, const float* mean, const float* rstd, const void* dres, void* dx_out,
                          float* partials, float* dg, float* db) {
-  int chunks = (rows + LN_ROWS - 1) / LN_ROWS;
-  size_t lds = (size_t)8 * D * sizeof(float);
-  if (lds > 48 * 1024) { set_error("layernorm_bwd: dim %d too large", D); return PPLL_ERR_CONFIG; }
-  hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(chunks), dim3(256), lds, s, dy, x, dt, xs, rows, D, g, mean, rstd,
-                     dres, dx_out, partials);
+  int chunks;
+  if (ln_fast_ok(dt, D, xs, x, dy, dres, dx_out) && !(((uintptr_t)g) & 7)) {
+    chunks = (rows + LNF_ROWS - 1) / LNF_ROWS;
+    LN_DISPATCH(D / 128, hipLaunchKernelGGL((layernorm_bwd_bf16_kernel<NJ>), dim3(chunks), dim3(256), 0, s,
+                                            (const uint16_t*)dy, (const uint16_t*)x, xs, rows, g, mean, rstd,
+                                            (const uint16_t*)dres, (uint16_t*)dx_out, partials));
+  } else {
+    chunks = (rows + LN_ROWS - 1) / LN_ROWS;
+    size_t lds = (size_t)8 * D * sizeof(float);
+    if (lds > 48 * 1024) { set_error("layernorm_bwd: dim %d too large", D); return PPLL_ERR_CONFIG; }
+    hipLaunchKernelGGL(layernorm_bwd_kernel, dim3(chunks), dim3(256), lds, s, dy, x, dt, xs, rows, D, g, mean, rstd,
+                       dres, dx_out, partials);
+  }
   PPLL_HIP(hipGetLastError());
-  // each partial row is [dg | db]
+  // each partial row is [dg | db]; the two gradients are neighbours in the parameter table
+  if (db == dg + D) return reduce_partials(s, partials, chunks, 2 * D, 2L * D, 1.0f, dg);
   PPLL_TRY(reduce_partials(s, partials, chunks, D, 2L * D, 1.0f, dg));
   return reduce_partials(s, partials + D, chunks, D, 2L * D, 1.0f, db);
 }
