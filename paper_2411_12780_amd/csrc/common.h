@@ -131,6 +131,11 @@ int launch_attention_fwd(hipStream_t s, const void* qkv, int dt, int B, int T, i
                          float* lse);
 int launch_attention_bwd(hipStream_t s, const void* qkv, const void* out, const void* dout, const float* lse,
                          int dt, int B, int T, int H, int dh, void* dqkv);
+bool attention_mfma_supported(int dt, int T, int H, int dh, const void* a, const void* b, const void* c,
+                              const void* d);
+int launch_attention_fwd_mfma(hipStream_t s, const void* qkv, int B, int T, int H, void* out, float* lse);
+int launch_attention_bwd_mfma(hipStream_t s, const void* qkv, const void* out, const void* dout, const float* lse,
+                              int B, int T, int H, void* dqkv);
 int launch_attention_fwd_generic(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out,
                                  float* lse);
 int launch_attention_bwd_generic(hipStream_t s, const void* qkv, const void* out, const void* dout,

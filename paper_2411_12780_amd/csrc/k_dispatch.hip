@@ -56,11 +56,14 @@ int launch_gemm(hipStream_t s, const GemmArgs& g) {
 }
 
 int launch_attention_fwd(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out, float* lse) {
+  if (attention_mfma_supported(dt, T, H, dh, qkv, out, nullptr, nullptr)) return launch_attention_fwd_mfma(s, qkv, B, T, H, out, lse);
   return launch_attention_fwd_generic(s, qkv, dt, B, T, H, dh, out, lse);
 }
 
 int launch_attention_bwd(hipStream_t s, const void* qkv, const void* out, const void* dout, const float* lse, int dt,
                          int B, int T, int H, int dh, void* dqkv) {
+  if (attention_mfma_supported(dt, T, H, dh, qkv, out, dout, dqkv))
+    return launch_attention_bwd_mfma(s, qkv, out, dout, lse, B, T, H, dqkv);
   return launch_attention_bwd_generic(s, qkv, out, dout, lse, dt, B, T, H, dh, dqkv);
 }
 

@@ -200,6 +200,14 @@ def test_resnet_fp32_stage_full_size_natural_statistics():
     run_case(synth.workload("resnet_stage_bf16", precision=synth.FP32), steps=1, check_bn=True, tol=1e-3, grad_tol=5e-3)
 
 
+@pytest.mark.parametrize("tokens", [1, 32, 64, 256])
+def test_vit_bf16_token_counts_at_tile_edges(tokens):
+    # head dim 64: 1 token, exactly one / two 32-token tiles, and the 256-token maximum
+    wl = synth.workload("vit_stage_act_bf16", batch=3, tokens=tokens, dim=128, heads=2, mlp_dim=256, depth=1,
+                        aux_depth=1)
+    run_case(wl, steps=1)
+
+
 def test_resnet_bf16_one_block_full_activation_size():
     run_case(synth.workload("resnet_stage_bf16", n_basic_blocks=1), steps=1, check_bn=True)
 
