@@ -48,13 +48,25 @@ struct MfmaArgs {
   int epilogue;
   uint16_t* C2;
   const uint16_t* aux; long ldaux;
+  int xcd_map;                      // 1: ids 8 apart share a tile row (many tile rows), 0: row-major ids
 };
 
-__device__ __forceinline__ float gelu_f(float h) { return 0.5f * h * (1.0f + erff(h * 0.70710678118654752f)); }
-__device__ __forceinline__ float dgelu_f(float h) {
-  float cdf = 0.5f * (1.0f + erff(h * 0.70710678118654752f));
-  float pdf = 0.39894228040143268f * __expf(-0.5f * h * h);
-  return cdf + h * pdf;
+// Exact-form GELU through the rational erf approximation of Abramowitz & Stegun 7.1.26
+// (|error| < 1.5e-7, far below bf16 resolution); erf(h/sqrt 2) and the normal density share
+// one exponential: e^{-z^2} with z = h/sqrt 2 is e^{-h^2/2}.
+__device__ __forceinline__ void cdf_pdf(float h, float& cdf, float& pdf) {
+  const float z = fabsf(h) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
+  const float ex = __expf(-z * z);
+  const float poly = ((((1.061405429f * t - 1.453152027f) * t + 1.421413741f) * t - 0.284496736f) * t + 0.254829592f) * t;
+  const float erf_abs = 1.0f - poly * ex;
+  cdf = 0.5f * (1.0f + copysignf(erf_abs, h));
+  pdf = 0.39894228040143268f * ex;
+}
+__device__ __forceinline__ float gelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return h * c; }
+__device__ __forceinline__ float dgelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return c + h * d; }
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
 
 __device__ __forceinline__ int lds_off(int row, int granule16) {
@@ -112,18 +124,34 @@ __device__ __forceinline__ void store_transposed(char* lds, int tid, const uint4
   }
 }
 
+constexpr int OPER_BYTES = (BM + BN) * ROW_BYTES;     // one stage of both operand tiles
+constexpr int STAGE_LD = BN + 4;                      // fp32 staging tile of the epilogue, padded row
+constexpr int LDS_BYTES = 2 * OPER_BYTES;             // two stages; the epilogue tile reuses them
+static_assert(BM * STAGE_LD * 4 <= LDS_BYTES, "epilogue staging tile must fit in the operand stages");
+
+struct TileRegs { uint4 a[4], b[4]; };
+
 template <bool AT, bool BT>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
-  __shared__ __align__(16) char lds_a[BM * ROW_BYTES];
-  __shared__ __align__(16) char lds_b[BN * ROW_BYTES];
+  extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;
-  const int tile = blockIdx.x;
-  const int m0 = (tile / p.tiles_n) * BM, n0 = (tile % p.tiles_n) * BN;
+  // Workgroup id -> tile.  Consecutive ids go to the 8 XCDs round-robin and each XCD has its own
+  // L2, so the tiles of one row (they share the A panel) are given ids that are 8 apart: they
+  // land on one XCD, next to each other in its dispatch order, and the panel is fetched once.
+  int tm, tn;
+  if (p.xcd_map) {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    tm = (slot / p.tiles_n) * 8 + xcd; tn = slot % p.tiles_n;
+    if (tm >= p.tiles_m) return;
+  } else {
+    tm = blockIdx.x / p.tiles_n; tn = blockIdx.x % p.tiles_n;
+  }
+  const int m0 = tm * BM, n0 = tn * BN;
   const int split = blockIdx.y;
   const int nkt = (p.K + BK - 1) / BK;
   const int kt0 = split * p.kt_per_split;
-  const int kt1 = min(nkt, kt0 + p.kt_per_split);
+  const int nk = min(nkt, kt0 + p.kt_per_split) - kt0;
 
   f32x16 acc[2][2];
 #pragma unroll
@@ -133,27 +161,30 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  uint4 ra[4], rb[4];
-  auto load_tiles = [&](int kt) {
-    int k0 = kt * BK;
-    if (AT) load_transposed(p.A, p.lda, m0, p.M, k0, p.K, tid, ra);
-    else load_direct<BM>(p.A, p.lda, m0, p.M, k0, p.K, tid, ra);
-    if (BT) load_transposed(p.B, p.ldb, n0, p.N, k0, p.K, tid, rb);
-    else load_direct<BN>(p.B, p.ldb, n0, p.N, k0, p.K, tid, rb);
+  // Software pipeline: two LDS stages and two register sets, so that the global loads of
+  // k-tile i+2 and i+3 are in flight while tile i is multiplied and tile i+1 is written to LDS.
+  auto gload = [&](int i, TileRegs& r) {
+    const int k0 = (kt0 + i) * BK;
+    if (AT) load_transposed(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
+    else load_direct<BM>(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
+    if (BT) load_transposed(p.B, p.ldb, n0, p.N, k0, p.K, tid, r.b);
+    else load_direct<BN>(p.B, p.ldb, n0, p.N, k0, p.K, tid, r.b);
   };
-  if (kt0 < kt1) load_tiles(kt0);
+  auto lstore = [&](int stage, const TileRegs& r) {
+    char* la = smem + stage * OPER_BYTES;
+    char* lb = la + BM * ROW_BYTES;
+    if (AT) store_transposed(la, tid, r.a); else store_direct(la, tid, r.a);
+    if (BT) store_transposed(lb, tid, r.b); else store_direct(lb, tid, r.b);
+  };
   const int frag_row = lane & 31, frag_g = lane >> 5;
   // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k
   const bool do_colsum = p.colsum != nullptr && m0 == 0;
   float csum = 0.f;
-  for (int kt = kt0; kt < kt1; ++kt) {
-    __syncthreads();
-    if (AT) store_transposed(lds_a, tid, ra); else store_direct(lds_a, tid, ra);
-    if (BT) store_transposed(lds_b, tid, rb); else store_direct(lds_b, tid, rb);
-    __syncthreads();
-    if (kt + 1 < kt1) load_tiles(kt + 1);
+  auto compute = [&](int stage) {
+    const char* la = smem + stage * OPER_BYTES;
+    const char* lb = la + BM * ROW_BYTES;
     if (do_colsum) {   // thread (row = tid/2, half = tid%2) sums 4 of the row's 8 granules; their order is irrelevant
-      const char* rowp = lds_b + (tid >> 1) * ROW_BYTES + (tid & 1) * 64;
+      const char* rowp = lb + (tid >> 1) * ROW_BYTES + (tid & 1) * 64;
 #pragma unroll
       for (int gq = 0; gq < 4; ++gq) {
         uint4 w = *reinterpret_cast<const uint4*>(rowp + gq * 16);
@@ -168,16 +199,36 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
       bf16x8 fa[2], fb[2];
 #pragma unroll
       for (int im = 0; im < 2; ++im)
-        fa[im] = *reinterpret_cast<const bf16x8*>(lds_a + lds_off(wm * 64 + im * 32 + frag_row, kk * 2 + frag_g));
+        fa[im] = *reinterpret_cast<const bf16x8*>(la + lds_off(wm * 64 + im * 32 + frag_row, kk * 2 + frag_g));
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
-        fb[jn] = *reinterpret_cast<const bf16x8*>(lds_b + lds_off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
+        fb[jn] = *reinterpret_cast<const bf16x8*>(lb + lds_off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
         for (int im = 0; im < 2; ++im)
           acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[jn], fa[im], acc[jn][im], 0, 0, 0);
     }
+  };
+
+  TileRegs rx, ry;
+  if (nk > 0) gload(0, rx);
+  if (nk > 1) gload(1, ry);
+  if (nk > 0) lstore(0, rx);
+  __syncthreads();
+  if (nk > 2) gload(2, rx);
+  for (int i = 0; i < nk; i += 2) {
+    // stage 0 holds tile i; ry holds tile i+1, rx tile i+2
+    compute(0);
+    if (i + 1 < nk) lstore(1, ry);
+    __syncthreads();
+    if (i + 3 < nk) gload(i + 3, ry);
+    if (i + 1 >= nk) break;
+    // stage 1 holds tile i+1; rx holds tile i+2, ry tile i+3
+    compute(1);
+    if (i + 2 < nk) lstore(0, rx);
+    __syncthreads();
+    if (i + 4 < nk) gload(i + 4, rx);
   }
 
   if (do_colsum) {
@@ -185,52 +236,72 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
     const int n = n0 + (tid >> 1);
     if (!(tid & 1) && n < p.N) p.colsum[(size_t)split * p.N + n] = csum;
   }
-  // acc[jn][im][4q + e] = C[m][n] with m = m0 + wm*64 + im*32 + lane%32, n = n0 + wn*64 + jn*32 + 8q + 4*(lane/32) + e
+
+  // Epilogue through LDS: the accumulators (lane = one C row, 4 consecutive columns per group)
+  // are laid down as an fp32 tile, then every thread takes 8 consecutive columns of a row, so
+  // bias / residual / saved pre-activation are read and C is written in full 128-column rows.
+  __syncthreads();   // every wave is done with the operand stages
+  float* stage = reinterpret_cast<float*>(smem);
 #pragma unroll
-  for (int im = 0; im < 2; ++im) {
-    const int m = m0 + wm * 64 + im * 32 + (lane & 31);
-    if (m >= p.M) continue;
+  for (int im = 0; im < 2; ++im)
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn) {
+    for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn * 64 + jn * 32 + 8 * q + 4 * (lane >> 5);
-        if (n >= p.N) continue;
-        float v[4];
+        const int row = wm * 64 + im * 32 + (lane & 31), col = wn * 64 + jn * 32 + 8 * q + 4 * (lane >> 5);
+        *reinterpret_cast<float4*>(stage + row * STAGE_LD + col) =
+            make_float4(acc[jn][im][4 * q], acc[jn][im][4 * q + 1], acc[jn][im][4 * q + 2], acc[jn][im][4 * q + 3]);
+      }
+  __syncthreads();
+#pragma unroll 2
+  for (int pass = 0; pass < 8; ++pass) {
+    const int row = pass * 16 + (tid >> 4), c8 = (tid & 15) * 8;
+    const int m = m0 + row, n = n0 + c8;
+    if (m >= p.M || n >= p.N) continue;
+    float v[8];
+    {
+      const float4 lo = *reinterpret_cast<const float4*>(stage + row * STAGE_LD + c8);
+      const float4 hi = *reinterpret_cast<const float4*>(stage + row * STAGE_LD + c8 + 4);
+      v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+    }
+    if (p.partial) {
+      float* dst = p.partial + ((size_t)split * p.M + m) * p.N + n;
+      *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      continue;
+    }
+    if (p.bias) {
+      const float4 b0 = *reinterpret_cast<const float4*>(p.bias + n), b1 = *reinterpret_cast<const float4*>(p.bias + n + 4);
+      v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
+    }
+    if (p.residual) {
+      const uint4 r = *reinterpret_cast<const uint4*>(p.residual + (size_t)m * p.ldr + n);
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(&r);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[jn][im][4 * q + e];
-        if (p.partial) {
-          *reinterpret_cast<float4*>(p.partial + ((size_t)split * p.M + m) * p.N + n) = make_float4(v[0], v[1], v[2], v[3]);
-          continue;
-        }
-        if (p.bias) {
-          float4 b = *reinterpret_cast<const float4*>(p.bias + n);
-          v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
-        }
-        if (p.residual) {
-          uint2 r = *reinterpret_cast<const uint2*>(p.residual + (size_t)m * p.ldr + n);
-          v[0] += bf16_to_f32((uint16_t)(r.x & 0xffff)); v[1] += bf16_to_f32((uint16_t)(r.x >> 16));
-          v[2] += bf16_to_f32((uint16_t)(r.y & 0xffff)); v[3] += bf16_to_f32((uint16_t)(r.y >> 16));
-        }
-        if (p.epilogue == EPI_DGELU) {
-          uint2 h = *reinterpret_cast<const uint2*>(p.aux + (size_t)m * p.ldaux + n);
-          v[0] *= dgelu_f(bf16_to_f32((uint16_t)(h.x & 0xffff))); v[1] *= dgelu_f(bf16_to_f32((uint16_t)(h.x >> 16)));
-          v[2] *= dgelu_f(bf16_to_f32((uint16_t)(h.y & 0xffff))); v[3] *= dgelu_f(bf16_to_f32((uint16_t)(h.y >> 16)));
-        }
-        if (p.c_f32) {
-          *reinterpret_cast<float4*>((float*)p.C + (size_t)m * p.ldc + n) = make_float4(v[0], v[1], v[2], v[3]);
-        } else {
-          uint2 o;
-          o.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-          o.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-          *reinterpret_cast<uint2*>((uint16_t*)p.C + (size_t)m * p.ldc + n) = o;
-          if (p.epilogue == EPI_GELU) {
-            uint2 g;
-            g.x = (uint32_t)f32_to_bf16(gelu_f(v[0])) | ((uint32_t)f32_to_bf16(gelu_f(v[1])) << 16);
-            g.y = (uint32_t)f32_to_bf16(gelu_f(v[2])) | ((uint32_t)f32_to_bf16(gelu_f(v[3])) << 16);
-            *reinterpret_cast<uint2*>(p.C2 + (size_t)m * p.ldc + n) = g;
-          }
-        }
+      for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(w[e] << 16); v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u); }
+    }
+    if (p.epilogue == EPI_DGELU) {
+      const uint4 hq = *reinterpret_cast<const uint4*>(p.aux + (size_t)m * p.ldaux + n);
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(&hq);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[2 * e] *= dgelu_fast(__uint_as_float(w[e] << 16));
+        v[2 * e + 1] *= dgelu_fast(__uint_as_float(w[e] & 0xffff0000u));
+      }
+    }
+    if (p.c_f32) {
+      float* dst = (float*)p.C + (size_t)m * p.ldc + n;
+      *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    } else {
+      uint4 o;
+      o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]); o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
+      *reinterpret_cast<uint4*>((uint16_t*)p.C + (size_t)m * p.ldc + n) = o;
+      if (p.epilogue == EPI_GELU) {
+        uint4 g;
+        g.x = pack_bf16x2(gelu_fast(v[0]), gelu_fast(v[1])); g.y = pack_bf16x2(gelu_fast(v[2]), gelu_fast(v[3]));
+        g.z = pack_bf16x2(gelu_fast(v[4]), gelu_fast(v[5])); g.w = pack_bf16x2(gelu_fast(v[6]), gelu_fast(v[7]));
+        *reinterpret_cast<uint4*>(p.C2 + (size_t)m * p.ldc + n) = g;
       }
     }
   }
@@ -259,14 +330,13 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   if (!at && g.a_sk != 1) return false;
   if (!bt && g.b_sk != 1) return false;
   const long lda = at ? g.a_sk : g.a_sm, ldb = bt ? g.b_sk : g.b_sn;
-  if ((lda & 7) || (ldb & 7) || (g.ldc & 3)) return false;
+  if ((lda & 7) || (ldb & 7) || (g.ldc & (g.c_dt == BF16 ? 7 : 3))) return false;
   if (at && (g.M & 7)) return false;
   if (!aligned16(g.A) || !aligned16(g.B) || !aligned16(g.C)) return false;
   if (g.bias && !aligned16(g.bias)) return false;
-  if (g.residual && (g.r_dt != BF16 || (g.ldr & 3) || !aligned16(g.residual))) return false;
+  if (g.residual && (g.r_dt != BF16 || (g.ldr & 7) || !aligned16(g.residual))) return false;
   if (g.epilogue == EPI_GELU && (g.c_dt != BF16 || !g.C2 || !aligned16(g.C2))) return false;
-  if (g.epilogue == EPI_DGELU && (g.aux_dt != BF16 || (g.ldaux & 3) || !aligned16(g.aux))) return false;
-  if (g.c_dt == BF16 && (g.ldc & 3)) return false;
+  if (g.epilogue == EPI_DGELU && (g.aux_dt != BF16 || (g.ldaux & 7) || !aligned16(g.aux))) return false;
   return true;
 }
 
@@ -306,11 +376,20 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   p.colsum = g.colsum ? (splits > 1 ? colsum_partial : g.colsum) : nullptr;
   p.kt_per_split = (nkt + splits - 1) / splits;
   p.partial = splits > 1 ? partial : nullptr;
-  dim3 grid(p.tiles_m * p.tiles_n, splits);
-  if (at && bt) hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), grid, dim3(256), 0, s, p);
-  else if (at) hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), grid, dim3(256), 0, s, p);
-  else if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(256), 0, s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), grid, dim3(256), 0, s, p);
+  p.xcd_map = p.tiles_m >= 16;
+  dim3 grid(p.xcd_map ? ((p.tiles_m + 7) / 8) * 8 * p.tiles_n : p.tiles_m * p.tiles_n, splits);
+  static bool lds_opted_in = false;   // > 64 KB of dynamic LDS needs a one-time opt-in per kernel
+  if (!lds_opted_in) {
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    lds_opted_in = true;
+  }
+  if (at && bt) hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), grid, dim3(256), LDS_BYTES, s, p);
+  else if (at) hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), grid, dim3(256), LDS_BYTES, s, p);
+  else if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(256), LDS_BYTES, s, p);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), grid, dim3(256), LDS_BYTES, s, p);
   PPLL_HIP(hipGetLastError());
   if (splits > 1) {
     size_t mn = (size_t)g.M * g.N;
