@@ -176,6 +176,10 @@ size_t Block::plan(char* base) {
     partial_floats = (size_t)colsum_partial_floats((int)M, widest);
     size_t ln = (size_t)layernorm_bwd_partial_floats((int)M, D);
     if (ln > partial_floats) partial_floats = ln;
+    if (cfg.input_kind == PPLL_IN_IMAGE) {
+      size_t eb = (size_t)embed_bwd_partial_floats(B, T, D);
+      if (eb > partial_floats) partial_floats = eb;
+    }
   } else {
     const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
     const size_t act = (size_t)B * Hh * W * Ch;
@@ -341,7 +345,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     PPLL_TRY(encoder_bwd(l, layer_in[l], gA, gB, gA, need_dx, s));
   }
   if (image) {
-    PPLL_TRY(launch_embed_bwd(s, gA, dt, B, T, D, grads + pos, grads + cls, embed_tmp));
+    PPLL_TRY(launch_embed_bwd(s, gA, dt, B, T, D, partials, grads + pos, grads + cls, embed_tmp));
     if (T > 1) {
       g = gemm_args();
       g.A = patches; g.a_dt = dt; g.a_sm = 1; g.a_sk = ppc;

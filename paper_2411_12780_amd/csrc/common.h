@@ -122,8 +122,9 @@ int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W,
 int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cls, const float* pos, int B,
                            int T, int D, void* x0);
 // dpos[t,d] = sum_b dx[b,t,d]; dcls[d] = dpos[0,d]; dE = dx[:,1:,:] gathered
-int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* dpos, float* dcls,
-                     void* dE);
+int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* partials, float* dpos,
+                     float* dcls, void* dE);
+int embed_bwd_partial_floats(int B, int T, int D);
 // dx[b,0,:] = dcls[b,:], every other row 0
 int launch_scatter_cls(hipStream_t s, const void* dcls, int dt, int B, int T, int D, void* dx);
 

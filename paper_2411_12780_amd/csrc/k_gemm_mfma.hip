@@ -307,8 +307,19 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   }
 }
 
-// C[i] = sum over splits of partial[s][i], fixed order
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial, int splits, size_t mn, float* C) {
+// C[i] = sum over splits of partial[s][i], fixed order; the trailing workgroups do the same for
+// the bias-gradient partials [splits][N] when there are any.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial, int splits, size_t mn, float* C,
+                                                            int main_blocks, const float* cs_partial, int N,
+                                                            float* cs_out) {
+  if ((int)blockIdx.x >= main_blocks) {
+    const int n = ((int)blockIdx.x - main_blocks) * 256 + threadIdx.x;
+    if (n >= N) return;
+    float acc = 0.f;
+    for (int s = 0; s < splits; ++s) acc += cs_partial[(size_t)s * N + n];
+    cs_out[n] = acc;
+    return;
+  }
   size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
   if (i >= mn) return;
   float4 acc = *reinterpret_cast<const float4*>(partial + i);
@@ -393,9 +404,10 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   PPLL_HIP(hipGetLastError());
   if (splits > 1) {
     size_t mn = (size_t)g.M * g.N;
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((mn / 4 + 255) / 256), dim3(256), 0, s, partial, splits, mn, (float*)g.C);
+    const int main_blocks = (int)((mn / 4 + 255) / 256), extra = g.colsum ? (g.N + 255) / 256 : 0;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(main_blocks + extra), dim3(256), 0, s, partial, splits, mn, (float*)g.C,
+                       main_blocks, colsum_partial, g.N, g.colsum);
     PPLL_HIP(hipGetLastError());
-    if (g.colsum) PPLL_TRY(reduce_partials(s, colsum_partial, splits, g.N, g.N, 1.0f, g.colsum));
   }
   return PPLL_OK;
 }

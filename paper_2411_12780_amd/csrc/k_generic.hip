@@ -80,8 +80,43 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g) {
 }
 }  // namespace
 
+namespace {
+// Few outputs (classifier head): one wave per output element, lanes stride over k.
+__global__ __launch_bounds__(256) void gemm_wave_per_output_kernel(GemmArgs g) {
+  const long o = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (o >= (long)g.M * g.N) return;
+  const int m = (int)(o / g.N), n = (int)(o % g.N), lane = threadIdx.x & 63;
+  float acc = 0.f;
+  for (int k = lane; k < g.K; k += 64)
+    acc = fmaf(ld_f(g.A, (size_t)((long)m * g.a_sm + (long)k * g.a_sk), g.a_dt),
+               ld_f(g.B, (size_t)((long)k * g.b_sk + (long)n * g.b_sn), g.b_dt), acc);
+  acc = wave_sum(acc);
+  if (lane == 0) st_f(g.C, (size_t)((long)m * g.ldc + n), acc + (g.bias ? g.bias[n] : 0.f), g.c_dt);
+}
+// Short reductions: one thread per output element.
+__global__ __launch_bounds__(256) void gemm_thread_per_output_kernel(GemmArgs g) {
+  const long o = (long)blockIdx.x * 256 + threadIdx.x;
+  if (o >= (long)g.M * g.N) return;
+  const int m = (int)(o / g.N), n = (int)(o % g.N);
+  float acc = 0.f;
+  for (int k = 0; k < g.K; ++k)
+    acc = fmaf(ld_f(g.A, (size_t)((long)m * g.a_sm + (long)k * g.a_sk), g.a_dt),
+               ld_f(g.B, (size_t)((long)k * g.b_sk + (long)n * g.b_sn), g.b_dt), acc);
+  st_f(g.C, (size_t)((long)m * g.ldc + n), acc + (g.bias ? g.bias[n] : 0.f), g.c_dt);
+}
+}  // namespace
+
 int launch_gemm_generic(hipStream_t s, const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) { set_error("gemm: empty shape %d x %d x %d", g.M, g.N, g.K); return PPLL_ERR_SHAPE; }
+  const long outputs = (long)g.M * g.N;
+  if (g.epilogue == EPI_NONE && !g.residual && outputs <= 65536) {
+    if (g.K <= 32) hipLaunchKernelGGL(gemm_thread_per_output_kernel, dim3((outputs + 255) / 256), dim3(256), 0, s, g);
+    else if (outputs <= 16384) hipLaunchKernelGGL(gemm_wave_per_output_kernel, dim3((outputs + 3) / 4), dim3(256), 0, s, g);
+    else goto tiled;
+    PPLL_HIP(hipGetLastError());
+    return PPLL_OK;
+  }
+tiled:
   dim3 grid((g.N + GT - 1) / GT, (g.M + GT - 1) / GT);
   hipLaunchKernelGGL(gemm_generic_kernel, grid, dim3(256), 0, s, g);
   PPLL_HIP(hipGetLastError());
@@ -252,7 +287,7 @@ __global__ __launch_bounds__(256) void layernorm_fwd_bf16_kernel(const uint16_t*
   if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
 }
 
-constexpr int LNF_ROWS = 64;   // rows per workgroup in the fast backward (4 waves x 16)
+constexpr int LNF_ROWS = 32;   // rows per workgroup in the fast backward (4 waves x 4 pairs)
 template <int NJ>
 __global__ __launch_bounds__(256) void layernorm_bwd_bf16_kernel(const uint16_t* dy, const uint16_t* x, long xs,
                                                                  int rows, const float* g, const float* mean,
@@ -270,34 +305,51 @@ __global__ __launch_bounds__(256) void layernorm_bwd_bf16_kernel(const uint16_t*
 #pragma unroll
   for (int j = 0; j < 2 * NJ; ++j) { adg[j] = 0.f; adb[j] = 0.f; }
   const int r0 = blockIdx.x * LNF_ROWS;
-  for (int rr = wave; rr < LNF_ROWS; rr += 4) {
-    const int row = r0 + rr;
-    if (row >= rows) break;
-    const float mu = mean[row], rs = rstd[row];
-    const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + (size_t)row * xs);
-    const uint32_t* dyr = reinterpret_cast<const uint32_t*>(dy + (size_t)row * D);
-    float xh[2 * NJ], dyh[2 * NJ];
-    float s1 = 0.f, s2 = 0.f;
+  // two rows per pass so that their loads are in flight together
+  for (int rr = 2 * wave; rr < LNF_ROWS; rr += 8) {
+    uint32_t wx[2][NJ], wd[2][NJ], wr[2][NJ];
+    float mu[2], rs[2];
+    bool ok[2];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) {
-      uint32_t wx = xr[lane + 64 * j], wd = dyr[lane + 64 * j];
-      float d0 = lo_bf(wd), d1 = hi_bf(wd);
-      xh[2 * j] = (lo_bf(wx) - mu) * rs; xh[2 * j + 1] = (hi_bf(wx) - mu) * rs;
-      adg[2 * j] += d0 * xh[2 * j]; adg[2 * j + 1] += d1 * xh[2 * j + 1];
-      adb[2 * j] += d0; adb[2 * j + 1] += d1;
-      dyh[2 * j] = d0 * gg[2 * j]; dyh[2 * j + 1] = d1 * gg[2 * j + 1];
-      s1 += dyh[2 * j] + dyh[2 * j + 1];
-      s2 += dyh[2 * j] * xh[2 * j] + dyh[2 * j + 1] * xh[2 * j + 1];
-    }
-    s1 = wave_sum(s1) * (1.0f / D); s2 = wave_sum(s2) * (1.0f / D);
-    if (dx) {
-      uint32_t* dxr = reinterpret_cast<uint32_t*>(dx + (size_t)row * D);
-      const uint32_t* rr_ = dres ? reinterpret_cast<const uint32_t*>(dres + (size_t)row * D) : nullptr;
+    for (int u = 0; u < 2; ++u) {
+      const int row = r0 + rr + u;
+      ok[u] = row < rows;
+      mu[u] = ok[u] ? mean[row] : 0.f; rs[u] = ok[u] ? rstd[row] : 0.f;
+      const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + (size_t)row * xs);
+      const uint32_t* dyr = reinterpret_cast<const uint32_t*>(dy + (size_t)row * D);
+      const uint32_t* rr_ = reinterpret_cast<const uint32_t*>(dres + (size_t)row * D);
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        float a = rs * (dyh[2 * j] - s1 - xh[2 * j] * s2), c = rs * (dyh[2 * j + 1] - s1 - xh[2 * j + 1] * s2);
-        if (rr_) { uint32_t w = rr_[lane + 64 * j]; a += lo_bf(w); c += hi_bf(w); }
-        dxr[lane + 64 * j] = pack_bf(a, c);
+        wx[u][j] = ok[u] ? xr[lane + 64 * j] : 0u;
+        wd[u][j] = ok[u] ? dyr[lane + 64 * j] : 0u;
+        wr[u][j] = (ok[u] && dres) ? rr_[lane + 64 * j] : 0u;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (!ok[u]) continue;
+      const int row = r0 + rr + u;
+      float xh[2 * NJ], dyh[2 * NJ];
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        float d0 = lo_bf(wd[u][j]), d1 = hi_bf(wd[u][j]);
+        xh[2 * j] = (lo_bf(wx[u][j]) - mu[u]) * rs[u]; xh[2 * j + 1] = (hi_bf(wx[u][j]) - mu[u]) * rs[u];
+        adg[2 * j] += d0 * xh[2 * j]; adg[2 * j + 1] += d1 * xh[2 * j + 1];
+        adb[2 * j] += d0; adb[2 * j + 1] += d1;
+        dyh[2 * j] = d0 * gg[2 * j]; dyh[2 * j + 1] = d1 * gg[2 * j + 1];
+        s1 += dyh[2 * j] + dyh[2 * j + 1];
+        s2 += dyh[2 * j] * xh[2 * j] + dyh[2 * j + 1] * xh[2 * j + 1];
+      }
+      s1 = wave_sum(s1) * (1.0f / D); s2 = wave_sum(s2) * (1.0f / D);
+      if (dx) {
+        uint32_t* dxr = reinterpret_cast<uint32_t*>(dx + (size_t)row * D);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+          float a = rs[u] * (dyh[2 * j] - s1 - xh[2 * j] * s2), c = rs[u] * (dyh[2 * j + 1] - s1 - xh[2 * j + 1] * s2);
+          if (dres) { a += lo_bf(wr[u][j]); c += hi_bf(wr[u][j]); }
+          dxr[lane + 64 * j] = pack_bf(a, c);
+        }
       }
     }
   }
@@ -428,13 +480,16 @@ __global__ __launch_bounds__(256) void assemble_tokens_kernel(const void* E, int
   st_f(x0, i, v + pos[(size_t)t * D + d], dt);
 }
 
-__global__ __launch_bounds__(256) void embed_bwd_kernel(const void* dx, int dt, int B, int T, int D, float* dpos,
-                                                        float* dcls, void* dE) {
+constexpr int EMB_ROWS = 8;   // batch entries per partial
+// partial[c][t,d] = sum over the chunk's batch entries of dx[b,t,d]; dE = dx[:,1:,:] gathered
+__global__ __launch_bounds__(256) void embed_bwd_kernel(const void* dx, int dt, int B, int T, int D, float* partial,
+                                                        void* dE) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;   // over [T, D]
   if (i >= (size_t)T * D) return;
   int d = i % D, t = i / D;
+  const int b0 = blockIdx.y * EMB_ROWS, b1 = min(B, b0 + EMB_ROWS);
   float acc = 0.f;
-  for (int b = 0; b < B; ++b) {
+  for (int b = b0; b < b1; ++b) {
     size_t src = ((size_t)b * T + t) * D + d;
     acc += ld_f(dx, src, dt);
     if (t > 0) {
@@ -443,8 +498,7 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const void* dx, int dt, 
       else ((float*)dE)[dst] = ((const float*)dx)[src];
     }
   }
-  dpos[i] = acc;
-  if (t == 0) dcls[d] = acc;
+  partial[(size_t)blockIdx.y * T * D + i] = acc;
 }
 
 __global__ __launch_bounds__(256) void scatter_cls_kernel(const void* dcls, int dt, int B, int T, int D, void* dx) {
@@ -468,11 +522,14 @@ int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cl
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
-int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* dpos, float* dcls, void* dE) {
-  size_t total = (size_t)T * D;
-  hipLaunchKernelGGL(embed_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dx, dt, B, T, D, dpos, dcls, dE);
+int embed_bwd_partial_floats(int B, int T, int D) { return ((B + EMB_ROWS - 1) / EMB_ROWS) * T * D; }
+int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* partials, float* dpos,
+                     float* dcls, void* dE) {
+  const int total = T * D, chunks = (B + EMB_ROWS - 1) / EMB_ROWS;
+  hipLaunchKernelGGL(embed_bwd_kernel, dim3((total + 255) / 256, chunks), dim3(256), 0, s, dx, dt, B, T, D, partials, dE);
   PPLL_HIP(hipGetLastError());
-  return PPLL_OK;
+  PPLL_TRY(reduce_partials(s, partials, chunks, total, total, 1.0f, dpos));
+  return reduce_partials(s, partials, chunks, D, total, 1.0f, dcls);   // the cls row is token 0
 }
 int launch_scatter_cls(hipStream_t s, const void* dcls, int dt, int B, int T, int D, void* dx) {
   size_t total = (size_t)B * T * D;
