@@ -48,6 +48,9 @@ struct MfmaArgs {
   int epilogue;
   uint16_t* C2;
   const uint16_t* aux; long ldaux;
+#ifdef PPLL_GEMM_TRACE
+  long long* trace;                 // [workgroup][8] wall-clock stamps (development builds only)
+#endif
   int xcd_map;                      // 1: ids 8 apart share a tile row (many tile rows), 0: row-major ids
 };
 
@@ -73,12 +76,12 @@ __device__ __forceinline__ int lds_off(int row, int granule16) {
   return row * ROW_BYTES + ((granule16 ^ ((row >> 4) & 7)) << 4);
 }
 
-// k contiguous in memory: 4 chunks of 8 bf16 per thread
+// k contiguous in memory: ROWS/32 chunks of 8 bf16 per thread
 template <int ROWS>
 __device__ __forceinline__ void load_direct(const uint16_t* __restrict__ base, long ld, int row0, int nrows, int k0,
                                             int kend, int tid, uint4 (&r)[4]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < ROWS / 32; ++i) {
     int c = tid + 256 * i, row = c >> 3, g = c & 7;
     int k = k0 + g * 8;
     uint4 v = make_uint4(0, 0, 0, 0);
@@ -86,9 +89,10 @@ __device__ __forceinline__ void load_direct(const uint16_t* __restrict__ base, l
     r[i] = v;
   }
 }
+template <int ROWS>
 __device__ __forceinline__ void store_direct(char* lds, int tid, const uint4 (&r)[4]) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
+  for (int i = 0; i < ROWS / 32; ++i) {
     int c = tid + 256 * i, row = c >> 3, g = c & 7;
     *reinterpret_cast<uint4*>(lds + lds_off(row, g)) = r[i];
   }
@@ -124,15 +128,21 @@ __device__ __forceinline__ void store_transposed(char* lds, int tid, const uint4
   }
 }
 
-constexpr int OPER_BYTES = (BM + BN) * ROW_BYTES;     // one stage of both operand tiles
 constexpr int STAGE_LD = BN + 4;                      // fp32 staging tile of the epilogue, padded row
-constexpr int LDS_BYTES = 2 * OPER_BYTES;             // two stages; the epilogue tile reuses them
-static_assert(BM * STAGE_LD * 4 <= LDS_BYTES, "epilogue staging tile must fit in the operand stages");
+constexpr int oper_bytes(int tm) { return (tm + BN) * ROW_BYTES; }   // one stage of both operand tiles
+constexpr int lds_bytes(int tm) { return 2 * oper_bytes(tm); }        // two stages; the epilogue tile reuses them
+static_assert(BM * STAGE_LD * 4 <= lds_bytes(BM) && 64 * STAGE_LD * 4 <= lds_bytes(64),
+              "epilogue staging tile must fit in the operand stages");
 
 struct TileRegs { uint4 a[4], b[4]; };
 
-template <bool AT, bool BT>
+// TM = rows of the output tile: 128 (wave tile 64 x 64) or, for outputs with too few 128-row
+// tiles to fill the chip, 64 (wave tile 32 x 64; direct A loader only).
+template <bool AT, bool BT, int TM>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
+  static_assert(TM == 128 || (TM == 64 && !AT), "64-row tiles are for the direct A loader");
+  constexpr int IM = TM / 64;                  // 32-row MFMA tiles per wave along m
+  constexpr int OPER_BYTES = oper_bytes(TM);
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;
@@ -147,17 +157,17 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   } else {
     tm = blockIdx.x / p.tiles_n; tn = blockIdx.x % p.tiles_n;
   }
-  const int m0 = tm * BM, n0 = tn * BN;
+  const int m0 = tm * TM, n0 = tn * BN;
   const int split = blockIdx.y;
   const int nkt = (p.K + BK - 1) / BK;
   const int kt0 = split * p.kt_per_split;
   const int nk = min(nkt, kt0 + p.kt_per_split) - kt0;
 
-  f32x16 acc[2][2];
+  f32x16 acc[2][IM];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < IM; ++b)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
@@ -166,15 +176,15 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   auto gload = [&](int i, TileRegs& r) {
     const int k0 = (kt0 + i) * BK;
     if (AT) load_transposed(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
-    else load_direct<BM>(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
+    else load_direct<TM>(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
     if (BT) load_transposed(p.B, p.ldb, n0, p.N, k0, p.K, tid, r.b);
     else load_direct<BN>(p.B, p.ldb, n0, p.N, k0, p.K, tid, r.b);
   };
   auto lstore = [&](int stage, const TileRegs& r) {
     char* la = smem + stage * OPER_BYTES;
-    char* lb = la + BM * ROW_BYTES;
-    if (AT) store_transposed(la, tid, r.a); else store_direct(la, tid, r.a);
-    if (BT) store_transposed(lb, tid, r.b); else store_direct(lb, tid, r.b);
+    char* lb = la + TM * ROW_BYTES;
+    if (AT) store_transposed(la, tid, r.a); else store_direct<TM>(la, tid, r.a);
+    if (BT) store_transposed(lb, tid, r.b); else store_direct<BN>(lb, tid, r.b);
   };
   const int frag_row = lane & 31, frag_g = lane >> 5;
   // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k
@@ -182,7 +192,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   float csum = 0.f;
   auto compute = [&](int stage) {
     const char* la = smem + stage * OPER_BYTES;
-    const char* lb = la + BM * ROW_BYTES;
+    const char* lb = la + TM * ROW_BYTES;
     if (do_colsum) {   // thread (row = tid/2, half = tid%2) sums 4 of the row's 8 granules; their order is irrelevant
       const char* rowp = lb + (tid >> 1) * ROW_BYTES + (tid & 1) * 64;
 #pragma unroll
@@ -196,26 +206,34 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
     }
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[2], fb[2];
+      bf16x8 fa[IM], fb[2];
 #pragma unroll
-      for (int im = 0; im < 2; ++im)
-        fa[im] = *reinterpret_cast<const bf16x8*>(la + lds_off(wm * 64 + im * 32 + frag_row, kk * 2 + frag_g));
+      for (int im = 0; im < IM; ++im)
+        fa[im] = *reinterpret_cast<const bf16x8*>(la + lds_off(wm * (TM / 2) + im * 32 + frag_row, kk * 2 + frag_g));
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
         fb[jn] = *reinterpret_cast<const bf16x8*>(lb + lds_off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
-        for (int im = 0; im < 2; ++im)
+        for (int im = 0; im < IM; ++im)
           acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[jn], fa[im], acc[jn][im], 0, 0, 0);
     }
   };
 
+#ifdef PPLL_GEMM_TRACE
+  long long* tr = p.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
+  if (tid == 0) tr[0] = wall_clock64();
+#define TRACE(i) if (tid == 0) tr[i] = wall_clock64();
+#else
+#define TRACE(i)
+#endif
   TileRegs rx, ry;
   if (nk > 0) gload(0, rx);
   if (nk > 1) gload(1, ry);
   if (nk > 0) lstore(0, rx);
   __syncthreads();
+  TRACE(1)
   if (nk > 2) gload(2, rx);
   for (int i = 0; i < nk; i += 2) {
     // stage 0 holds tile i; ry holds tile i+1, rx tile i+2
@@ -231,6 +249,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
     if (i + 4 < nk) gload(i + 4, rx);
   }
 
+  TRACE(2)
   if (do_colsum) {
     csum += __shfl_xor(csum, 1, 64);
     const int n = n0 + (tid >> 1);
@@ -243,18 +262,19 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   __syncthreads();   // every wave is done with the operand stages
   float* stage = reinterpret_cast<float*>(smem);
 #pragma unroll
-  for (int im = 0; im < 2; ++im)
+  for (int im = 0; im < IM; ++im)
 #pragma unroll
     for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int row = wm * 64 + im * 32 + (lane & 31), col = wn * 64 + jn * 32 + 8 * q + 4 * (lane >> 5);
+        const int row = wm * (TM / 2) + im * 32 + (lane & 31), col = wn * 64 + jn * 32 + 8 * q + 4 * (lane >> 5);
         *reinterpret_cast<float4*>(stage + row * STAGE_LD + col) =
             make_float4(acc[jn][im][4 * q], acc[jn][im][4 * q + 1], acc[jn][im][4 * q + 2], acc[jn][im][4 * q + 3]);
       }
   __syncthreads();
+  TRACE(3)
 #pragma unroll 2
-  for (int pass = 0; pass < 8; ++pass) {
+  for (int pass = 0; pass < TM / 16; ++pass) {
     const int row = pass * 16 + (tid >> 4), c8 = (tid & 15) * 8;
     const int m = m0 + row, n = n0 + c8;
     if (m >= p.M || n >= p.N) continue;
@@ -305,6 +325,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
       }
     }
   }
+  TRACE(4)
 }
 
 // C[i] = sum over splits of partial[s][i], fixed order; the trailing workgroups do the same for
@@ -330,6 +351,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial
   *reinterpret_cast<float4*>(C + i) = acc;
 }
 
+#ifdef PPLL_GEMM_TRACE
+long long* g_gemm_trace = nullptr;
+#endif
 bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 }  // namespace
 
@@ -373,9 +397,16 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   p.B = (const uint16_t*)g.B; p.ldb = bt ? g.b_sk : g.b_sn;
   p.C = g.C; p.c_f32 = g.c_dt == F32; p.ldc = g.ldc;
   p.M = g.M; p.N = g.N; p.K = g.K;
-  p.tiles_m = (g.M + BM - 1) / BM; p.tiles_n = (g.N + BN - 1) / BN;
+  p.tiles_n = (g.N + BN - 1) / BN;
+  // 64-row tiles when 128-row tiles would leave compute units without a workgroup
+  const bool small_m = !at && ((g.M + BM - 1) / BM) * p.tiles_n < 256;
+  const int tm_rows = small_m ? 64 : BM;
+  p.tiles_m = (g.M + tm_rows - 1) / tm_rows;
   p.bias = g.bias; p.residual = (const uint16_t*)g.residual; p.ldr = g.ldr;
   p.epilogue = g.epilogue; p.C2 = (uint16_t*)g.C2; p.aux = (const uint16_t*)g.aux; p.ldaux = g.ldaux;
+#ifdef PPLL_GEMM_TRACE
+  p.trace = g_gemm_trace;
+#endif
   const int nkt = (g.K + BK - 1) / BK;
   int splits = 1;
   const bool plain = !g.bias && !g.residual && g.epilogue == EPI_NONE && g.c_dt == F32 && g.ldc == g.N;
@@ -391,16 +422,19 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   dim3 grid(p.xcd_map ? ((p.tiles_m + 7) / 8) * 8 * p.tiles_n : p.tiles_m * p.tiles_n, splits);
   static bool lds_opted_in = false;   // > 64 KB of dynamic LDS needs a one-time opt-in per kernel
   if (!lds_opted_in) {
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
     lds_opted_in = true;
   }
-  if (at && bt) hipLaunchKernelGGL((gemm_mfma_kernel<true, true>), grid, dim3(256), LDS_BYTES, s, p);
-  else if (at) hipLaunchKernelGGL((gemm_mfma_kernel<true, false>), grid, dim3(256), LDS_BYTES, s, p);
-  else if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true>), grid, dim3(256), LDS_BYTES, s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<false, false>), grid, dim3(256), LDS_BYTES, s, p);
+  if (small_m) {
+    if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 64>), grid, dim3(256), lds_bytes(64), s, p);
+    else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 64>), grid, dim3(256), lds_bytes(64), s, p);
+  } else if (at && bt) hipLaunchKernelGGL((gemm_mfma_kernel<true, true, 128>), grid, dim3(256), lds_bytes(128), s, p);
+  else if (at) hipLaunchKernelGGL((gemm_mfma_kernel<true, false, 128>), grid, dim3(256), lds_bytes(128), s, p);
+  else if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 128>), grid, dim3(256), lds_bytes(128), s, p);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 128>), grid, dim3(256), lds_bytes(128), s, p);
   PPLL_HIP(hipGetLastError());
   if (splits > 1) {
     size_t mn = (size_t)g.M * g.N;
