@@ -53,6 +53,7 @@ struct Block {
   std::vector<size_t> bn_off;
   float* loss_dev = nullptr;
   int* flag_dev = nullptr;
+  int* ticket_dev = nullptr;     // arrival counter of the last-workgroup reductions (self-resetting)
   float* partials = nullptr;
   size_t partial_floats = 0;
   float* splitk = nullptr;       // split-K partial sums of the weight-gradient GEMMs

@@ -138,6 +138,7 @@ size_t Block::plan(char* base) {
   bn_var_run = bump.floats(bn_total ? bn_total : 1);
   loss_dev = bump.floats(1);
   flag_dev = (int*)bump.take(sizeof(int));
+  ticket_dev = (int*)bump.take(sizeof(int));
   logits = bump.floats((size_t)B * C);
   dlogits = bump.floats((size_t)B * C);
 
@@ -378,11 +379,11 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     block_in[i] = x;
     block_out[i] = i == n - 1 ? x_out : a.out;
     PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c1));
-    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, Ch, eps, mom, partials, a.mean1, a.rstd1, bn_mean_run + bn_off[2 * i],
+    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, Ch, eps, mom, partials, ticket_dev, a.mean1, a.rstd1, bn_mean_run + bn_off[2 * i],
                              bn_var_run + bn_off[2 * i]));
     PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
     PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c2));
-    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, Ch, eps, mom, partials, a.mean2, a.rstd2, bn_mean_run + bn_off[2 * i + 1],
+    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, Ch, eps, mom, partials, ticket_dev, a.mean2, a.rstd2, bn_mean_run + bn_off[2 * i + 1],
                              bn_var_run + bn_off[2 * i + 1]));
     PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, x, block_out[i]));
     x = block_out[i];
@@ -390,7 +391,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   if (after_forward) PPLL_TRY(after_forward());
   // ---- auxiliary forward
   PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
-  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, aux_mean, aux_rstd, bn_mean_run + bn_off[2 * n],
+  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, ticket_dev, aux_mean, aux_rstd, bn_mean_run + bn_off[2 * n],
                            bn_var_run + bn_off[2 * n]));
   PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
   PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
@@ -413,7 +414,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   g.C = dpooled; g.c_dt = dt; g.ldc = A; g.M = B; g.N = A; g.K = C;
   PPLL_TRY(launch_gemm_generic(s, g));
   PPLL_TRY(launch_gap_bwd(s, dpooled, dt, B, Ho * Wo, A, d_aux));
-  PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials,
+  PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials, ticket_dev,
                          grads + aux_bn_g, grads + aux_bn_b, d_aux));
   PPLL_TRY(launch_conv3x3_wgrad(s, x, d_aux, dt, B, H, W, Ch, A, 2, partials, grads + aux_conv_w));
   PPLL_TRY(launch_conv3x3_dgrad(s, d_aux, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, nullptr, nullptr, r_gA));
@@ -421,11 +422,11 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   for (int i = n - 1; i >= 0; --i) {
     const BasicBlockParams& p = rb_p[i];
     BasicBlockActs& a = rb_a[i];
-    PPLL_TRY(launch_bn_bwd(s, r_gA, block_out[i], a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, partials,
+    PPLL_TRY(launch_bn_bwd(s, r_gA, block_out[i], a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, partials, ticket_dev,
                            grads + p.bn2_g, grads + p.bn2_b, r_t2));
     PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, H, W, Ch, Ch, 1, partials, grads + p.conv2_w));
     PPLL_TRY(launch_conv3x3_dgrad(s, r_t2, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, nullptr, nullptr, r_t1));
-    PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, partials,
+    PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, partials, ticket_dev,
                            grads + p.bn1_g, grads + p.bn1_b, r_t1));
     PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, H, W, Ch, Ch, 1, partials, grads + p.conv1_w));
     if (i > 0)

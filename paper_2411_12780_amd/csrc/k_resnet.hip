@@ -159,6 +159,8 @@ __global__ __launch_bounds__(256) void gap_bwd_kernel(const void* dpooled, int d
 
 int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                        int Co, int stride, void* y) {
+  if (conv_bf16_supported(dt, wdt, Ci, Co, x, w, y) && conv_fwd_bf16_ok(Ci, Co))
+    return launch_conv3x3_fwd_bf16(s, x, w, B, H, W, Ci, Co, stride, y);
   size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Co;
   hipLaunchKernelGGL(conv3x3_fwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, w, wdt, dt, B, H, W, Ci, Co,
                      stride, y);
@@ -168,6 +170,9 @@ int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int
 
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, const void* dres, const void* ymask, void* dx) {
+  if (conv_bf16_supported(dt, wdt, Ci, Co, dy, w, dx) && conv_dgrad_bf16_ok(Ci, Co) &&
+      !((((uintptr_t)dres) | ((uintptr_t)ymask)) & 15))
+    return launch_conv3x3_dgrad_bf16(s, dy, w, B, H, W, Ci, Co, stride, dres, ymask, dx);
   size_t total = (size_t)B * H * W * Ci;
   hipLaunchKernelGGL(conv3x3_dgrad_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dy, w, wdt, dt, B, H, W, Ci,
                      Co, stride, dres, ymask, dx);
@@ -180,10 +185,13 @@ static size_t wgrad_chunks(int B, int H, int W, int stride) {
   return (npix + WG_PIX - 1) / WG_PIX;
 }
 int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride) {
-  return (int)(wgrad_chunks(B, H, W, stride) * 9 * Ci * Co);
+  size_t a = wgrad_chunks(B, H, W, stride) * 9 * Ci * Co, b = conv3x3_wgrad_bf16_partial_floats(B, H, W, Ci, Co, stride);
+  return (int)(a > b ? a : b);
 }
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci, int Co,
                          int stride, float* partials, float* dw) {
+  if (conv_bf16_supported(dt, BF16, Ci, Co, x, dy, dw) && conv_wgrad_bf16_ok(Ci, Co))
+    return launch_conv3x3_wgrad_bf16(s, x, dy, B, H, W, Ci, Co, stride, partials, dw);
   int chunks = (int)wgrad_chunks(B, H, W, stride), nw = 9 * Ci * Co;
   hipLaunchKernelGGL(conv3x3_wgrad_kernel, dim3(chunks), dim3(256), 0, s, x, dy, dt, B, H, W, Ci, Co, stride, partials);
   PPLL_HIP(hipGetLastError());
@@ -192,12 +200,16 @@ int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, i
 
 int bn_partial_floats(int rows, int C) {
   int a = colsum_partial_floats(rows, C), b = ((rows + BN_ROWS - 1) / BN_ROWS) * 2 * C;
-  return (a > b ? a : b) + C;
+  int c = (C % 8 == 0 && C >= 8 && C <= 128 && 256 % (C / 8) == 0) ? (int)bn_bf16_partial_floats(rows, C) : 0;
+  a = a > b ? a : b;
+  return (a > c ? a : c) + C;
 }
 
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
-                    float* mean, float* rstd, float* run_mean, float* run_var) {
+                    int* ticket, float* mean, float* rstd, float* run_mean, float* run_var) {
   if (rows < 2) { set_error("batchnorm needs at least 2 rows per channel"); return PPLL_ERR_CONFIG; }
+  if (bn_bf16_supported(dt, C, x, nullptr, nullptr, nullptr))
+    return launch_bn_stats_bf16(s, x, rows, C, eps, momentum, partials, ticket, mean, rstd, run_mean, run_var);
   float* var = partials;            // [C], then the chunk partials
   float* part = partials + C;
   PPLL_TRY(colsum_mode(s, x, dt, rows, C, 0, nullptr, 1.0f / rows, part, mean));
@@ -210,6 +222,8 @@ int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float
 
 int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const float* mean, const float* rstd,
                     const float* g, const float* b, const void* res, void* y) {
+  if (bn_bf16_supported(dt, C, x, res, y, nullptr))
+    return launch_bn_apply_bf16(s, x, rows, C, mean, rstd, g, b, res, y);
   size_t total = (size_t)rows * C;
   hipLaunchKernelGGL(bn_apply_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, dt, total, C, mean, rstd, g, b, res, y);
   PPLL_HIP(hipGetLastError());
@@ -217,8 +231,10 @@ int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const
 }
 
 int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
-                  const float* mean, const float* rstd, const float* g, float* partials, float* dg, float* db,
-                  void* dx) {
+                  const float* mean, const float* rstd, const float* g, float* partials, int* ticket, float* dg,
+                  float* db, void* dx) {
+  if (bn_bf16_supported(dt, C, dy, y, x, dx))
+    return launch_bn_bwd_bf16(s, dy, y, x, rows, C, mean, rstd, g, partials, ticket, dg, db, dx);
   int chunks = (rows + BN_ROWS - 1) / BN_ROWS;
   size_t total = (size_t)rows * C;
   hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3((C + 255) / 256, chunks), dim3(256), 0, s, dy, y, x, dt, rows, C, mean,

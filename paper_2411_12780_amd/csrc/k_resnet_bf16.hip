@@ -1,0 +1,454 @@
+// bf16 fast path of the ResNet stage (channel counts that are multiples of 16):
+//  * 3x3 convolution forward and input gradient as an implicit GEMM on the
+//    matrix cores: a lane owns one output pixel, reads its 3x3 neighbourhood
+//    straight from the NHWC tensor in MFMA fragment order (8 consecutive
+//    channels = 16 bytes), the filter sits in LDS as [out channel][tap, in
+//    channel]; the product is issued filter-first so that a lane ends up with 4
+//    consecutive output channels of its pixel (8-byte stores).
+//  * weight gradient: 64 output pixels per workgroup, their nine shifted input
+//    vectors and dy staged in LDS, 36 / 72 fp32 accumulators per thread; partials
+//    per workgroup, summed in a fixed order.
+//  * BatchNorm statistics / backward sums: 8 channels per thread (16-byte loads),
+//    per-workgroup partials, and the last workgroup to arrive (integer ticket)
+//    adds the partials in workgroup order and finishes mean / rstd / running
+//    stats or dgamma / dbeta: one launch, still deterministic.
+#include "common.h"
+
+namespace ppll {
+
+namespace {
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+}
+__device__ __forceinline__ int out_dim(int in, int stride) { return (in - 1) / stride + 1; }
+
+struct ConvArgs {
+  const uint16_t* src;     // forward: x [B,H,W,Ci]; input gradient: dy [B,Ho,Wo,Co]
+  const uint16_t* w;       // [9][Ci][Co]
+  uint16_t* dst;           // forward: y [B,Ho,Wo,Co]; input gradient: dx [B,H,W,Ci]
+  int B, H, W, Ci, Co, stride;
+  const uint16_t* dres;    // input gradient only: dx += dres * (ymask > 0)
+  const uint16_t* ymask;
+};
+
+// MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = channels reduced.
+template <int MODE>
+__global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
+  extern __shared__ __align__(16) char wl[];        // [NO][9*KC] bf16, row stride RSW bytes
+  const int NO = MODE == 0 ? p.Co : p.Ci, KC = MODE == 0 ? p.Ci : p.Co;
+  const int RSW = 18 * KC + 16;
+  const int Ho = out_dim(p.H, p.stride), Wo = out_dim(p.W, p.stride);
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  // filter -> LDS as [produced channel][tap*KC + reduced channel]
+  for (int e = tid; e < 9 * p.Ci * p.Co; e += 256) {
+    const int co = e % p.Co, ci = (e / p.Co) % p.Ci, tap = e / (p.Co * p.Ci);
+    const int row = MODE == 0 ? co : ci, k = tap * KC + (MODE == 0 ? ci : co);
+    *reinterpret_cast<uint16_t*>(wl + row * RSW + 2 * k) = p.w[e];
+  }
+  __syncthreads();
+  const int OH = MODE == 0 ? Ho : p.H, OW = MODE == 0 ? Wo : p.W;      // output spatial size
+  const int SH = MODE == 0 ? p.H : Ho, SW = MODE == 0 ? p.W : Wo;      // source spatial size
+  const long P = (long)p.B * OH * OW;
+  const long pix = (long)blockIdx.x * 128 + wave * 32 + li;
+  const bool live = pix < P;
+  const int ox = (int)(pix % OW), oy = (int)((pix / OW) % OH), b = (int)(pix / ((long)OW * OH));
+  const int NT = NO / 32;
+  f32x16 acc[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+#pragma unroll 1
+  for (int tap = 0; tap < 9; ++tap) {
+    const int ky = tap / 3, kx = tap % 3;
+    int sy, sx;
+    bool ok = live;
+    if (MODE == 0) {
+      sy = oy * p.stride + ky - 1; sx = ox * p.stride + kx - 1;
+    } else {
+      const int ty = oy + 1 - ky, tx = ox + 1 - kx;
+      ok = ok && ty >= 0 && tx >= 0 && (ty % p.stride) == 0 && (tx % p.stride) == 0;
+      sy = ty / p.stride; sx = tx / p.stride;
+    }
+    ok = ok && sy >= 0 && sy < SH && sx >= 0 && sx < SW;
+    const uint16_t* sp = p.src + (((long)b * SH + sy) * SW + sx) * KC + 8 * hh;
+    const char* wrow = wl + 2 * (tap * KC + 8 * hh);
+    for (int c16 = 0; c16 < KC / 16; ++c16) {
+      uint4 xv = make_uint4(0, 0, 0, 0);
+      if (ok) xv = *reinterpret_cast<const uint4*>(sp + 16 * c16);
+      const bf16x8 xf = __builtin_bit_cast(bf16x8, xv);
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        if (t < NT) {
+          const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
+          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
+        }
+    }
+  }
+  if (!live) return;
+  // acc[t][4q+e] = out[pix][32t + 8q + 4hh + e]
+  uint16_t* drow = p.dst + pix * NO;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+    if (t < NT) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int c = 32 * t + 8 * q + 4 * hh;
+        float v[4] = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+        if (MODE == 1 && p.dres) {
+          const uint2 m = *reinterpret_cast<const uint2*>(p.ymask + pix * NO + c);
+          const uint2 r = *reinterpret_cast<const uint2*>(p.dres + pix * NO + c);
+          if (lo_bf(m.x) > 0.f) v[0] += lo_bf(r.x);
+          if (hi_bf(m.x) > 0.f) v[1] += hi_bf(r.x);
+          if (lo_bf(m.y) > 0.f) v[2] += lo_bf(r.y);
+          if (hi_bf(m.y) > 0.f) v[3] += hi_bf(r.y);
+        }
+        *reinterpret_cast<uint2*>(drow + c) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+      }
+    }
+}
+
+// Weight gradient.  CO = 32 or 64.  Thread (co = tid % CO, cig = tid / CO) owns
+// dw[tap][cig*CPT .. +CPT-1][co], CPT = Ci / (256 / CO) input channels.
+constexpr int WG_PIX_F = 64;
+template <int CO, int CPT>
+__global__ __launch_bounds__(256) void conv3x3_wgrad_bf16_kernel(const uint16_t* __restrict__ x,
+                                                                 const uint16_t* __restrict__ dy, int B, int H, int W,
+                                                                 int Ci, int stride, float* __restrict__ partial) {
+  extern __shared__ __align__(16) char sm[];
+  uint16_t* xs = reinterpret_cast<uint16_t*>(sm);                 // [pixels][9][Ci]
+  uint16_t* dys = xs + WG_PIX_F * 9 * Ci;                         // [pixels][CO]
+  const int Ho = out_dim(H, stride), Wo = out_dim(W, stride);
+  const long P = (long)B * Ho * Wo, p0 = (long)blockIdx.x * WG_PIX_F;
+  const int tid = threadIdx.x;
+  const int cpc = Ci / 8;                                         // 16-byte chunks per pixel vector
+  for (int item = tid; item < WG_PIX_F * 9 * cpc; item += 256) {
+    const int ch = item % cpc, tap = (item / cpc) % 9, lp = item / (cpc * 9);
+    const long pp = p0 + lp;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (pp < P) {
+      const int ox = (int)(pp % Wo), oy = (int)((pp / Wo) % Ho), b = (int)(pp / ((long)Wo * Ho));
+      const int iy = oy * stride + tap / 3 - 1, ix = ox * stride + tap % 3 - 1;
+      if (iy >= 0 && iy < H && ix >= 0 && ix < W)
+        v = *reinterpret_cast<const uint4*>(x + (((long)b * H + iy) * W + ix) * Ci + 8 * ch);
+    }
+    *reinterpret_cast<uint4*>(xs + ((size_t)lp * 9 + tap) * Ci + 8 * ch) = v;
+  }
+  for (int item = tid; item < WG_PIX_F * (CO / 8); item += 256) {
+    const int ch = item % (CO / 8), lp = item / (CO / 8);
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (p0 + lp < P) v = *reinterpret_cast<const uint4*>(dy + (p0 + lp) * CO + 8 * ch);
+    *reinterpret_cast<uint4*>(dys + (size_t)lp * CO + 8 * ch) = v;
+  }
+  __syncthreads();
+  const int co = tid % CO, cig = tid / CO;
+  float acc[9][CPT];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) acc[t][j] = 0.f;
+#pragma unroll 2
+  for (int lp = 0; lp < WG_PIX_F; ++lp) {
+    const float d = bf16_to_f32(dys[(size_t)lp * CO + co]);
+    const uint16_t* xp = xs + (size_t)lp * 9 * Ci + cig * CPT;
+    uint32_t xv[9][CPT / 2];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+      const uint32_t* xw = reinterpret_cast<const uint32_t*>(xp + t * Ci);
+#pragma unroll
+      for (int j = 0; j < CPT / 2; ++j) xv[t][j] = xw[j];
+    }
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+      for (int j = 0; j < CPT / 2; ++j) {
+        acc[t][2 * j] = fmaf(lo_bf(xv[t][j]), d, acc[t][2 * j]);
+        acc[t][2 * j + 1] = fmaf(hi_bf(xv[t][j]), d, acc[t][2 * j + 1]);
+      }
+  }
+  float* out = partial + (size_t)blockIdx.x * 9 * Ci * CO;
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int j = 0; j < CPT; ++j) out[((size_t)t * Ci + cig * CPT + j) * CO + co] = acc[t][j];
+}
+
+// ---------------------------------------------------------------- BatchNorm
+// Per-channel sums over rows with 8 channels per thread.  KIND 0: (sum x, sum x^2) -> mean, rstd,
+// running stats.  KIND 1: (sum dyh, sum dyh*xhat), dyh = dy*(y>0) -> dbeta, dgamma.
+struct BnSumArgs {
+  const uint16_t* x; const uint16_t* dy; const uint16_t* y;
+  int rows, C;
+  const float* mean; const float* rstd;        // KIND 1 inputs
+  float* partial;                              // [blocks][2][C]
+  int* ticket;                                 // zero before the launch; reset by the last workgroup
+  float eps, momentum;
+  float* out0; float* out1;                    // KIND 0: mean, rstd; KIND 1: dbeta, dgamma
+  float* run_mean; float* run_var;
+};
+
+template <int KIND>
+__global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
+  __shared__ float red[256][17];
+  __shared__ int is_last;
+  const int groups = p.C / 8;                   // channel groups of 8
+  const int lanes = 256 / groups;               // row lanes per workgroup
+  const int tid = threadIdx.x, cg = tid % groups, rl = tid / groups;
+  float a0[8], a1[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { a0[j] = 0.f; a1[j] = 0.f; }
+  float mu[8], rs[8];
+  if (KIND == 1) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) { mu[j] = p.mean[8 * cg + j]; rs[j] = p.rstd[8 * cg + j]; }
+  }
+  if (rl < lanes) {
+    for (int r = blockIdx.x * lanes + rl; r < p.rows; r += gridDim.x * lanes) {
+      const size_t off = (size_t)r * p.C + 8 * cg;
+      const uint4 xv = *reinterpret_cast<const uint4*>(p.x + off);
+      const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
+      if (KIND == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float u = lo_bf(xw[j]), v = hi_bf(xw[j]);
+          a0[2 * j] += u; a0[2 * j + 1] += v; a1[2 * j] += u * u; a1[2 * j + 1] += v * v;
+        }
+      } else {
+        const uint4 dv = *reinterpret_cast<const uint4*>(p.dy + off);
+        const uint4 yv = *reinterpret_cast<const uint4*>(p.y + off);
+        const uint32_t* dw = reinterpret_cast<const uint32_t*>(&dv);
+        const uint32_t* yw = reinterpret_cast<const uint32_t*>(&yv);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float d0 = lo_bf(yw[j]) > 0.f ? lo_bf(dw[j]) : 0.f, d1 = hi_bf(yw[j]) > 0.f ? hi_bf(dw[j]) : 0.f;
+          a0[2 * j] += d0; a0[2 * j + 1] += d1;
+          a1[2 * j] += d0 * (lo_bf(xw[j]) - mu[2 * j]) * rs[2 * j];
+          a1[2 * j + 1] += d1 * (hi_bf(xw[j]) - mu[2 * j + 1]) * rs[2 * j + 1];
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) { red[tid][j] = a0[j]; red[tid][8 + j] = a1[j]; }
+  __syncthreads();
+  // thread c < 2C adds the row lanes of its (sum kind, channel) in order
+  if (tid < 2 * p.C) {
+    const int which = tid / p.C, c = tid % p.C, g = c / 8, j = c % 8;
+    float t = 0.f;
+    for (int l = 0; l < lanes; ++l) t += red[l * groups + g][8 * which + j];
+    p.partial[(size_t)blockIdx.x * 2 * p.C + tid] = t;
+  }
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) is_last = atomicAdd(p.ticket, 1) == (int)gridDim.x - 1;
+  __syncthreads();
+  if (!is_last) return;
+  __threadfence();
+  {
+    // 2C values; 256/(2C) thread groups take the workgroup partials round-robin, then one thread
+    // per value adds the groups in order
+    const int nv = 2 * p.C, parts = 256 / nv;
+    if (tid < nv * parts) {
+      const int v = tid % nv, part = tid / nv;
+      float t = 0.f;
+      for (unsigned bk = part; bk < gridDim.x; bk += parts) t += p.partial[(size_t)bk * nv + v];
+      red[tid][0] = t;
+    }
+    __syncthreads();
+    if (tid < p.C) {
+      float s0 = 0.f, s1 = 0.f;
+      for (int part = 0; part < parts; ++part) { s0 += red[part * nv + tid][0]; s1 += red[part * nv + p.C + tid][0]; }
+      if (KIND == 0) {
+        const float n = (float)p.rows, m = s0 / n;
+        const float var = fmaxf(s1 / n - m * m, 0.f);
+        p.out0[tid] = m;
+        p.out1[tid] = 1.0f / sqrtf(var + p.eps);
+        p.run_mean[tid] = (1.f - p.momentum) * p.run_mean[tid] + p.momentum * m;
+        p.run_var[tid] = (1.f - p.momentum) * p.run_var[tid] + p.momentum * var * (n / (n - 1.f));
+      } else {
+        p.out0[tid] = s0;
+        p.out1[tid] = s1;
+      }
+    }
+  }
+  if (tid == 0) *p.ticket = 0;
+}
+
+// y = relu(bn(x) (+ res)), 8 channels per thread
+__global__ __launch_bounds__(256) void bn_apply_bf16_kernel(const uint16_t* x, size_t chunks, int C, const float* mean,
+                                                            const float* rstd, const float* g, const float* b,
+                                                            const uint16_t* res, uint16_t* y) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  const int c0 = (int)((i * 8) % C);
+  const uint4 xv = *reinterpret_cast<const uint4*>(x + i * 8);
+  const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
+  uint4 rv = make_uint4(0, 0, 0, 0);
+  if (res) rv = *reinterpret_cast<const uint4*>(res + i * 8);
+  const uint32_t* rw = reinterpret_cast<const uint32_t*>(&rv);
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int c = c0 + 2 * j;
+    float u = (lo_bf(xw[j]) - mean[c]) * rstd[c] * g[c] + b[c] + lo_bf(rw[j]);
+    float v = (hi_bf(xw[j]) - mean[c + 1]) * rstd[c + 1] * g[c + 1] + b[c + 1] + hi_bf(rw[j]);
+    o[j] = pack2(fmaxf(u, 0.f), fmaxf(v, 0.f));
+  }
+  *reinterpret_cast<uint4*>(y + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// dx = (g rstd / N) (N dyh - dbeta - xhat dgamma)
+__global__ __launch_bounds__(256) void bn_bwd_apply_bf16_kernel(const uint16_t* dy, const uint16_t* y,
+                                                                const uint16_t* x, size_t chunks, int C, int rows,
+                                                                const float* mean, const float* rstd, const float* g,
+                                                                const float* dg, const float* db, uint16_t* dx) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  const int c0 = (int)((i * 8) % C);
+  const uint4 xv = *reinterpret_cast<const uint4*>(x + i * 8);
+  const uint4 dv = *reinterpret_cast<const uint4*>(dy + i * 8);
+  const uint4 yv = *reinterpret_cast<const uint4*>(y + i * 8);
+  const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
+  const uint32_t* dw = reinterpret_cast<const uint32_t*>(&dv);
+  const uint32_t* yw = reinterpret_cast<const uint32_t*>(&yv);
+  const float n = (float)rows;
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float r[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c = c0 + 2 * j + h;
+      const float yy = h ? hi_bf(yw[j]) : lo_bf(yw[j]), dd = h ? hi_bf(dw[j]) : lo_bf(dw[j]);
+      const float xx = h ? hi_bf(xw[j]) : lo_bf(xw[j]);
+      const float d = yy > 0.f ? dd : 0.f, xh = (xx - mean[c]) * rstd[c];
+      r[h] = g[c] * rstd[c] / n * (n * d - db[c] - xh * dg[c]);
+    }
+    o[j] = pack2(r[0], r[1]);
+  }
+  *reinterpret_cast<uint4*>(dx + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+bool al16(const void* p) { return !(((uintptr_t)p) & 15); }
+}  // namespace
+
+bool conv_bf16_supported(int dt, int wdt, int Ci, int Co, const void* a, const void* b, const void* c) {
+  if (dt != BF16 || wdt != BF16) return false;
+  if ((Ci % 16) || (Co % 16) || Ci > 128 || Co > 128) return false;
+  return al16(a) && al16(b) && al16(c);
+}
+
+int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, int H, int W, int Ci, int Co,
+                            int stride, void* y) {
+  ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr};
+  const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+  const size_t lds = (size_t)Co * (18 * Ci + 16);
+  hipLaunchKernelGGL(conv3x3_mfma_kernel<0>, dim3((unsigned)((P + 127) / 128)), dim3(256), lds, s, p);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
+                              int stride, const void* dres, const void* ymask, void* dx) {
+  ConvArgs p{(const uint16_t*)dy, (const uint16_t*)w, (uint16_t*)dx, B, H, W, Ci, Co, stride, (const uint16_t*)dres,
+             (const uint16_t*)ymask};
+  const long P = (long)B * H * W;
+  const size_t lds = (size_t)Ci * (18 * Co + 16);
+  hipLaunchKernelGGL(conv3x3_mfma_kernel<1>, dim3((unsigned)((P + 127) / 128)), dim3(256), lds, s, p);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+// forward and input gradient need Co resp. Ci to be a multiple of 32 (one MFMA tile of produced channels)
+bool conv_fwd_bf16_ok(int Ci, int Co) { return Co % 32 == 0 && Co <= 64 && (size_t)Co * (18 * Ci + 16) <= 64 * 1024; }
+bool conv_dgrad_bf16_ok(int Ci, int Co) { return Ci % 32 == 0 && Ci <= 64 && (size_t)Ci * (18 * Co + 16) <= 64 * 1024; }
+bool conv_wgrad_bf16_ok(int Ci, int Co) { return (Co == 32 || Co == 64) && Ci % 16 == 0 && Ci >= 16 && Ci <= 64; }
+
+size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride) {
+  const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+  return (size_t)((P + WG_PIX_F - 1) / WG_PIX_F) * 9 * Ci * Co;
+}
+
+template <int CO, int CPT>
+static int wgrad_launch(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int stride,
+                        float* partials, int chunks) {
+  const size_t lds = ((size_t)WG_PIX_F * 9 * Ci + (size_t)WG_PIX_F * CO) * 2;
+  if (lds > 64 * 1024)
+    PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_wgrad_bf16_kernel<CO, CPT>,
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL((conv3x3_wgrad_bf16_kernel<CO, CPT>), dim3(chunks), dim3(256), lds, s, (const uint16_t*)x,
+                     (const uint16_t*)dy, B, H, W, Ci, stride, partials);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co,
+                              int stride, float* partials, float* dw) {
+  const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+  const int chunks = (int)((P + WG_PIX_F - 1) / WG_PIX_F), nw = 9 * Ci * Co;
+  const int cpt = Ci / (256 / Co);
+  int st = PPLL_ERR_CONFIG;
+  if (Co == 32 && cpt == 2) st = wgrad_launch<32, 2>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 32 && cpt == 4) st = wgrad_launch<32, 4>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 32 && cpt == 6) st = wgrad_launch<32, 6>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 32 && cpt == 8) st = wgrad_launch<32, 8>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 64 && cpt == 4) st = wgrad_launch<64, 4>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 64 && cpt == 8) st = wgrad_launch<64, 8>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 64 && cpt == 12) st = wgrad_launch<64, 12>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 64 && cpt == 16) st = wgrad_launch<64, 16>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else set_error("conv3x3 weight gradient: no kernel for %d -> %d channels", Ci, Co);
+  PPLL_TRY(st);
+  return reduce_partials(s, partials, chunks, nw, nw, 1.0f, dw);
+}
+
+bool bn_bf16_supported(int dt, int C, const void* a, const void* b, const void* c, const void* d) {
+  if (dt != BF16 || (C % 8) || C < 8 || C > 128 || (256 % (C / 8))) return false;
+  return al16(a) && al16(b) && al16(c) && al16(d);
+}
+static int bn_blocks(int rows, int C) {
+  const int lanes = 256 / (C / 8);
+  int blocks = (rows + lanes * 8 - 1) / (lanes * 8);     // about eight rows per thread
+  return blocks < 1 ? 1 : (blocks > 64 ? 64 : blocks);
+}
+size_t bn_bf16_partial_floats(int rows, int C) { return (size_t)bn_blocks(rows, C) * 2 * C; }
+
+int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
+                         int* ticket, float* mean, float* rstd, float* run_mean, float* run_var) {
+  BnSumArgs p{};
+  p.x = (const uint16_t*)x; p.rows = rows; p.C = C; p.partial = partials; p.ticket = ticket; p.eps = eps;
+  p.momentum = momentum; p.out0 = mean; p.out1 = rstd; p.run_mean = run_mean; p.run_var = run_var;
+  hipLaunchKernelGGL(bn_sums_kernel<0>, dim3(bn_blocks(rows, C)), dim3(256), 0, s, p);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_bn_apply_bf16(hipStream_t s, const void* x, int rows, int C, const float* mean, const float* rstd,
+                         const float* g, const float* b, const void* res, void* y) {
+  const size_t chunks = (size_t)rows * C / 8;
+  hipLaunchKernelGGL(bn_apply_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, (const uint16_t*)x,
+                     chunks, C, mean, rstd, g, b, (const uint16_t*)res, (uint16_t*)y);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void* x, int rows, int C, const float* mean,
+                       const float* rstd, const float* g, float* partials, int* ticket, float* dg, float* db, void* dx) {
+  BnSumArgs p{};
+  p.x = (const uint16_t*)x; p.dy = (const uint16_t*)dy; p.y = (const uint16_t*)y; p.rows = rows; p.C = C;
+  p.mean = mean; p.rstd = rstd; p.partial = partials; p.ticket = ticket; p.out0 = db; p.out1 = dg;
+  hipLaunchKernelGGL(bn_sums_kernel<1>, dim3(bn_blocks(rows, C)), dim3(256), 0, s, p);
+  PPLL_HIP(hipGetLastError());
+  const size_t chunks = (size_t)rows * C / 8;
+  hipLaunchKernelGGL(bn_bwd_apply_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
+                     (const uint16_t*)dy, (const uint16_t*)y, (const uint16_t*)x, chunks, C, rows, mean, rstd, g, dg, db,
+                     (uint16_t*)dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
+}  // namespace ppll
