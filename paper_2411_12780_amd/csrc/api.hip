@@ -288,6 +288,8 @@ int ppll_block_write_tensor(ppll_block_t* h, int32_t kind, int32_t index, const 
 int ppll_block_destroy(ppll_block_t* h) {
   if (!h) { set_error("block handle is null"); return PPLL_ERR_NULL; }
   if (!h->b.alive) { set_error("block handle was destroyed"); return PPLL_ERR_STATE; }
+  (void)hipStreamSynchronize(h->b.last_stream);
+  h->b.release_side_stream();
   h->b.alive = false;   // the handle stays allocated so that later misuse is reported, not undefined
   return PPLL_OK;
 }
@@ -466,7 +468,7 @@ int ppll_pipeline_destroy(ppll_pipeline_t* p) {
   for (auto& v : p->ready) for (hipEvent_t e : v) (void)hipEventDestroy(e);
   for (auto& v : p->freed) for (hipEvent_t e : v) (void)hipEventDestroy(e);
   p->ready.clear(); p->freed.clear();
-  for (ppll_block* h : p->blocks) h->b.alive = false;
+  for (ppll_block* h : p->blocks) { h->b.release_side_stream(); h->b.alive = false; }
   p->alive = false;
   return PPLL_OK;
 }

@@ -79,6 +79,17 @@ struct Block {
   long steps = 0;
   hipStream_t last_stream = nullptr;
 
+  // Weight-gradient GEMMs do not feed the backward chain, so they run on a second stream and
+  // fill the compute units the chain's small kernels leave idle.  ev_fork[i]: operands ready
+  // (main -> side); ev_done[i]: product finished (side -> main, waited on before a buffer the
+  // product reads is overwritten, and before the optimizer).
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> ev_fork, ev_done;
+  hipEvent_t pending[4] = {nullptr, nullptr, nullptr, nullptr};   // last reader of gA, d_h, gB, d_qkv
+  hipEvent_t side_tail = nullptr;
+  int ensure_side_stream();
+  void release_side_stream();
+
   // Builds the parameter table and assigns every workspace pointer relative to
   // `base` (null: only measure).  Returns the bytes needed.
   size_t plan(char* base);

@@ -5,6 +5,7 @@
 
 #include <cmath>
 #include <cstdio>
+#include <cstdlib>
 
 namespace ppll {
 
@@ -208,6 +209,29 @@ size_t Block::plan(char* base) {
   return (bump.off + 255) & ~(size_t)255;
 }
 
+// ------------------------------------------------------------------ second stream
+int Block::ensure_side_stream() {
+  if (side) return PPLL_OK;
+  static const bool single = getenv("PPLL_SINGLE_STREAM") != nullptr;
+  if (single || cfg.arch != PPLL_VIT || dt != BF16) return PPLL_OK;
+  PPLL_HIP(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
+  const int n = 4 * (cfg.depth + cfg.aux_depth);
+  for (int i = 0; i < n; ++i) {
+    hipEvent_t a = nullptr, b = nullptr;
+    PPLL_HIP(hipEventCreateWithFlags(&a, hipEventDisableTiming));
+    PPLL_HIP(hipEventCreateWithFlags(&b, hipEventDisableTiming));
+    ev_fork.push_back(a); ev_done.push_back(b);
+  }
+  return PPLL_OK;
+}
+
+void Block::release_side_stream() {
+  if (side) { (void)hipStreamSynchronize(side); (void)hipStreamDestroy(side); side = nullptr; }
+  for (hipEvent_t e : ev_fork) (void)hipEventDestroy(e);
+  for (hipEvent_t e : ev_done) (void)hipEventDestroy(e);
+  ev_fork.clear(); ev_done.clear();
+}
+
 // ------------------------------------------------------------------ ViT
 int Block::encoder_fwd(int l, const void* x, void* x2_out, hipStream_t s) {
   const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, M = cfg.batch * T;
@@ -255,8 +279,11 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
     g.C = dxo; g.c_dt = dt; g.ldc = in_dim; g.M = M; g.N = in_dim; g.K = out_dim;
     return g;
   };
-  // dW[in,out] = X^T dY and db = column sums of dY, reduction over the M rows
-  auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off, size_t b_off) {
+  // dW[in,out] = X^T dY and db = column sums of dY, reduction over the M rows.  `slot` names the
+  // buffer dY lives in (0 gA, 1 d_h, 2 gB, 3 d_qkv).  With the fused MFMA kernel the product goes
+  // to the second stream; the buffer's next writer waits for it (before_write below).
+  auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off, size_t b_off,
+                   int slot) -> int {
     GemmArgs g = gemm_args();
     g.A = xin; g.a_dt = dt; g.a_sm = 1; g.a_sk = in_dim;
     g.B = dy; g.b_dt = dt; g.b_sk = out_dim; g.b_sn = 1;
@@ -264,22 +291,43 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
     g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
     g.colsum = grads + b_off;
     const bool fused = gemm_fuses_colsum(g);
+    if (fused && side) {
+      const int i = 4 * l + slot;
+      PPLL_HIP(hipEventRecord(ev_fork[i], s));
+      PPLL_HIP(hipStreamWaitEvent(side, ev_fork[i], 0));
+      PPLL_TRY(launch_gemm(side, g));
+      PPLL_HIP(hipEventRecord(ev_done[i], side));
+      pending[slot] = ev_done[i];
+      side_tail = ev_done[i];
+      return (int)PPLL_OK;
+    }
     PPLL_TRY(launch_gemm(s, g));
     return fused ? (int)PPLL_OK : launch_colsum(s, dy, dt, M, out_dim, partials, grads + b_off);
   };
+  auto before_write = [&](int slot) -> int {
+    if (pending[slot]) {
+      PPLL_HIP(hipStreamWaitEvent(s, pending[slot], 0));
+      pending[slot] = nullptr;
+    }
+    return (int)PPLL_OK;
+  };
   GemmArgs g = dgrad(g_in, D, p.fc2_w, F, d_h);
   g.epilogue = EPI_DGELU; g.aux = a.h; g.aux_dt = dt; g.ldaux = F;
+  PPLL_TRY(before_write(1));
   PPLL_TRY(launch_gemm(s, g));
-  PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w, p.fc2_b));
+  PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w, p.fc2_b, 0));
   PPLL_TRY(launch_gemm(s, dgrad(d_h, F, p.fc1_w, D, d_u)));
-  PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w, p.fc1_b));
+  PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w, p.fc1_b, 1));
+  PPLL_TRY(before_write(2));
   PPLL_TRY(launch_layernorm_bwd(s, d_u, a.x1, dt, D, M, D, params + p.ln2_g, a.mean2, a.rstd2, g_in, g_tmp, partials,
                                 grads + p.ln2_g, grads + p.ln2_b));
   PPLL_TRY(launch_gemm(s, dgrad(g_tmp, D, p.proj_w, D, d_u)));
-  PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w, p.proj_b));
+  PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w, p.proj_b, 2));
+  PPLL_TRY(before_write(3));
   PPLL_TRY(launch_attention_bwd(s, a.qkv, a.att, d_u, a.lse, dt, cfg.batch, T, H, D / H, d_qkv));
   PPLL_TRY(launch_gemm(s, dgrad(d_qkv, 3 * D, p.qkv_w, D, d_u)));
-  PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b));
+  PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b, 3));
+  PPLL_TRY(before_write(0));
   return launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, g_tmp,
                               need_dx ? g_out : nullptr, partials, grads + p.ln1_g, grads + p.ln1_b);
 }
@@ -344,6 +392,11 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   for (int l = L + A - 1; l >= 0; --l) {
     bool need_dx = l > 0 || image;
     PPLL_TRY(encoder_bwd(l, layer_in[l], gA, gB, gA, need_dx, s));
+  }
+  if (side_tail) {   // every weight gradient is in place (and the split-K scratch free) from here on
+    PPLL_HIP(hipStreamWaitEvent(s, side_tail, 0));
+    side_tail = nullptr;
+    for (hipEvent_t& e : pending) e = nullptr;
   }
   if (image) {
     PPLL_TRY(launch_embed_bwd(s, gA, dt, B, T, D, partials, grads + pos, grads + cls, embed_tmp));
@@ -448,6 +501,7 @@ int Block::update(float lr, hipStream_t s) {
 int Block::step(const void* x_in, const int32_t* labels, float lr, void* x_out, float* loss_out, hipStream_t s,
                 const std::function<int()>& after_forward) {
   last_stream = s;
+  PPLL_TRY(ensure_side_stream());
   if (cfg.arch == PPLL_VIT) PPLL_TRY(vit_step(x_in, labels, x_out, s, after_forward));
   else PPLL_TRY(resnet_step(x_in, labels, x_out, s, after_forward));
   PPLL_TRY(update(lr, s));
