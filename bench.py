@@ -50,6 +50,8 @@ def main() -> int:
     ap.add_argument("--workload", default="vit_stage_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also run the 256 MiB copy probe 5 times (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the pipeline: a block's local step runs on a single "
@@ -128,6 +130,15 @@ def main() -> int:
                            "avg_launch_us": 1e3 * gemm_ms / max(launches, 1),
                            "gemm_ms_per_step": gemm_ms / args.steps,
                            "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
+
+    if args.probe_copy:
+        nbytes = 256 << 20
+        src = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        for _ in range(5):
+            P.ppll_probe_copy(src, dst, nbytes, stream)
+        torch.cuda.synchronize()
+        out["probe_copy_bytes"] = nbytes
 
     if not args.no_cpu_baseline:
         from oracle import ppll_oracle as O

@@ -174,14 +174,20 @@ int ppll_pipeline_output(ppll_pipeline_t* pipe, const void** x_out_dev, size_t* 
 int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
 
 /* Measurement aid (no part of the method).  While enabled, every launch of the
- * dense-contraction (GEMM) kernels, which carry the bulk of the step's
- * arithmetic, is bracketed by a pair of HIP events on its own stream.
+ * bf16 matrix-core GEMM kernel (gemm_mfma_kernel, all variants), which carries
+ * the bulk of the step's arithmetic, is bracketed by a pair of HIP events on its
+ * own stream (the split-K reduce that may follow is outside the bracket).
  * ppll_profile_read waits for those events and returns, since the previous
  * read: their summed duration in milliseconds, the algorithmic flops 2*M*N*K of
  * the bracketed launches, and their count (each pointer nullable).  The events
  * add host and stream overhead: time whole steps with profiling off. */
 int ppll_profile_enable(int32_t on);
 int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
+
+/* Measurement aid: one plain copy kernel (copy_probe_kernel) moving `bytes` (a multiple of 16)
+ * from src_dev to dst_dev on `hip_stream`.  Its known traffic (bytes read, bytes written) is
+ * what the hardware byte counters of a profiler run are scaled against. */
+int ppll_probe_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

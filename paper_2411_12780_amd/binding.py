@@ -79,6 +79,7 @@ _SIGS = {
     "ppll_pipeline_block": (C.c_int, [C.c_void_p, C.c_int32, C.POINTER(C.c_void_p)]),
     "ppll_pipeline_output": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
     "ppll_pipeline_destroy": (C.c_int, [C.c_void_p]),
+    "ppll_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ppll_profile_enable": (C.c_int, [C.c_int32]),
     "ppll_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
@@ -252,3 +253,7 @@ def ppll_profile_read():
     ms, fl, n = C.c_double(0), C.c_double(0), C.c_int64(0)
     _check(lib().ppll_profile_read(C.byref(ms), C.byref(fl), C.byref(n)))
     return ms.value, fl.value, n.value
+
+
+def ppll_probe_copy(src, dst, nbytes: int, stream=None) -> None:
+    _check(lib().ppll_probe_copy(_ptr(src), _ptr(dst), nbytes, _ptr(stream)))

@@ -118,6 +118,12 @@ extern "C" {
 
 const char* ppll_last_error(void) { return g_err; }
 
+int ppll_probe_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_stream) {
+  if (!src_dev || !dst_dev) { set_error("probe buffers are null"); return PPLL_ERR_NULL; }
+  if ((((uintptr_t)src_dev) | ((uintptr_t)dst_dev) | bytes) & 15) { set_error("probe copy needs 16-byte alignment and size"); return PPLL_ERR_SHAPE; }
+  return launch_copy_probe((hipStream_t)hip_stream, src_dev, dst_dev, bytes);
+}
+
 int ppll_profile_enable(int32_t on) { profile_enable(on != 0); return PPLL_OK; }
 
 int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches) {

@@ -95,6 +95,8 @@ inline bool gemm_fuses_colsum(const GemmArgs& g) { return g.colsum && gemm_mfma_
 size_t gemm_mfma_partial_floats(int M, int N, int K);
 int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t partial_floats);
 void profile_enable(bool on);
+int profile_begin(hipStream_t s, double flops, void** token);   // event pair around one launch (profiling only)
+int profile_end(hipStream_t s, void* token);
 int profile_read(double* ms, double* flops, long long* launches);
 int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out);
 int colsum_mode(hipStream_t s, const void* x, int dt, int rows, int N, int mode, const float* shift, float scale,
@@ -150,6 +152,7 @@ int launch_adamw(hipStream_t s, float* p, const float* g, float* m, float* v, ui
                  float b1, float b2, float eps, float wd, float bias_corr1, float bias_corr2);
 int launch_refresh_shadow(hipStream_t s, const float* p, uint16_t* shadow, size_t n);
 int launch_fill_zero(hipStream_t s, void* p, size_t bytes);
+int launch_copy_probe(hipStream_t s, const void* src, void* dst, size_t bytes);
 
 // ---------------------------------------------------------------- ResNet pieces
 int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,

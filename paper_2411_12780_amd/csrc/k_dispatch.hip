@@ -40,19 +40,25 @@ int profile_read(double* ms, double* flops, long long* launches) {
   return PPLL_OK;
 }
 
+// Brackets one kernel launch with a pair of events when profiling is on.
+int profile_begin(hipStream_t s, double flops, void** token) {
+  *token = nullptr;
+  if (!g_profile) return PPLL_OK;
+  TimedLaunch tl{pooled_event(), pooled_event(), flops};
+  if (!tl.a || !tl.b) { set_error("hipEventCreate failed"); return PPLL_ERR_HIP; }
+  PPLL_HIP(hipEventRecord(tl.a, s));
+  g_timed.push_back(tl);
+  *token = (void*)(uintptr_t)g_timed.size();
+  return PPLL_OK;
+}
+int profile_end(hipStream_t s, void* token) {
+  if (!token) return PPLL_OK;
+  PPLL_HIP(hipEventRecord(g_timed[(size_t)(uintptr_t)token - 1].b, s));
+  return PPLL_OK;
+}
+
 int launch_gemm(hipStream_t s, const GemmArgs& g) {
-  TimedLaunch tl{nullptr, nullptr, 2.0 * g.M * g.N * g.K};
-  if (g_profile) {
-    tl.a = pooled_event(); tl.b = pooled_event();
-    if (!tl.a || !tl.b) { set_error("hipEventCreate failed"); return PPLL_ERR_HIP; }
-    PPLL_HIP(hipEventRecord(tl.a, s));
-  }
-  int st = gemm_mfma_supported(g) ? launch_gemm_mfma(s, g, g.splitk_ws, g.splitk_floats) : launch_gemm_generic(s, g);
-  if (g_profile) {
-    PPLL_HIP(hipEventRecord(tl.b, s));
-    g_timed.push_back(tl);
-  }
-  return st;
+  return gemm_mfma_supported(g) ? launch_gemm_mfma(s, g, g.splitk_ws, g.splitk_floats) : launch_gemm_generic(s, g);
 }
 
 int launch_attention_fwd(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out, float* lse) {

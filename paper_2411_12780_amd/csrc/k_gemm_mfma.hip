@@ -51,7 +51,9 @@ struct MfmaArgs {
 #ifdef PPLL_GEMM_TRACE
   long long* trace;                 // [workgroup][8] wall-clock stamps (development builds only)
 #endif
-  int xcd_map;                      // 1: ids 8 apart share a tile row (many tile rows), 0: row-major ids
+  int xcd_map;                      // 1: ids 8 apart share a tile row (many tile rows), 2: ids 8 apart share a
+                                    // split (split-K), 0: row-major ids
+  int splits;
 };
 
 // Exact-form GELU through the rational erf approximation of Abramowitz & Stegun 7.1.26
@@ -138,7 +140,8 @@ struct TileRegs { uint4 a[4], b[4]; };
 
 // TM = rows of the output tile: 128 (wave tile 64 x 64) or, for outputs with too few 128-row
 // tiles to fill the chip, 64 (wave tile 32 x 64; direct A loader only).
-template <bool AT, bool BT, int TM>
+// PF = k-tiles in flight in registers ahead of the one being multiplied (4 measured slower than 2).
+template <bool AT, bool BT, int TM, int PF = 2>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   static_assert(TM == 128 || (TM == 64 && !AT), "64-row tiles are for the direct A loader");
   constexpr int IM = TM / 64;                  // 32-row MFMA tiles per wave along m
@@ -149,16 +152,24 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   // Workgroup id -> tile.  Consecutive ids go to the 8 XCDs round-robin and each XCD has its own
   // L2, so the tiles of one row (they share the A panel) are given ids that are 8 apart: they
   // land on one XCD, next to each other in its dispatch order, and the panel is fetched once.
-  int tm, tn;
-  if (p.xcd_map) {
+  // With split-K (xcd_map 2) it is the splits that are dealt to the XCDs: all tiles of one k-range
+  // run on one XCD, so the two token panels of that range are fetched from HBM once.
+  int tm, tn, split = blockIdx.y;
+  if (p.xcd_map == 1) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     tm = (slot / p.tiles_n) * 8 + xcd; tn = slot % p.tiles_n;
     if (tm >= p.tiles_m) return;
+  } else if (p.xcd_map == 2) {
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    split = (slot / tiles) * 8 + xcd;
+    const int tile = slot % tiles;
+    tm = tile / p.tiles_n; tn = tile % p.tiles_n;
+    if (split >= p.splits) return;
   } else {
     tm = blockIdx.x / p.tiles_n; tn = blockIdx.x % p.tiles_n;
   }
   const int m0 = tm * TM, n0 = tn * BN;
-  const int split = blockIdx.y;
   const int nkt = (p.K + BK - 1) / BK;
   const int kt0 = split * p.kt_per_split;
   const int nk = min(nkt, kt0 + p.kt_per_split) - kt0;
@@ -171,8 +182,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  // Software pipeline: two LDS stages and two register sets, so that the global loads of
-  // k-tile i+2 and i+3 are in flight while tile i is multiplied and tile i+1 is written to LDS.
+  // Software pipeline: two LDS stages and PF register sets, so that the global loads of k-tiles
+  // i+2 .. i+1+PF are in flight while tile i is multiplied and tile i+1 is written to LDS.
+  const int frag_row = lane & 31, frag_g = lane >> 5;
   auto gload = [&](int i, TileRegs& r) {
     const int k0 = (kt0 + i) * BK;
     if (AT) load_transposed(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
@@ -186,7 +198,6 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
     if (AT) store_transposed(la, tid, r.a); else store_direct<TM>(la, tid, r.a);
     if (BT) store_transposed(lb, tid, r.b); else store_direct<BN>(lb, tid, r.b);
   };
-  const int frag_row = lane & 31, frag_g = lane >> 5;
   // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k
   const bool do_colsum = p.colsum != nullptr && m0 == 0;
   float csum = 0.f;
@@ -225,31 +236,44 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   long long* tr = p.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
   if (tid == 0) tr[0] = wall_clock64();
 #define TRACE(i) if (tid == 0) tr[i] = wall_clock64();
+  long long tacc[3] = {0, 0, 0}, tlast = 0;   // compute, LDS store (incl. wait for the loads), barrier
+#define TRACE_T(k) { long long now = __builtin_readcyclecounter(); if (k > 0) tacc[k - 1] += now - tlast; tlast = now; }
 #else
 #define TRACE(i)
+#define TRACE_T(k)
 #endif
-  TileRegs rx, ry;
-  if (nk > 0) gload(0, rx);
-  if (nk > 1) gload(1, ry);
-  if (nk > 0) lstore(0, rx);
+  // tile t travels in register set t % 2 and LDS stage t % 2.  (Reading the A fragments of a
+  // k-contiguous A straight from global memory instead, to halve the LDS traffic, was measured
+  // 18 % slower: 32-byte pieces of 32 different rows per load instruction.)
+  static_assert(PF == 2, "the loop below is written for two register sets");
+  TileRegs r[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if (j < nk) gload(j, r[j]);
+  if (nk > 0) lstore(0, r[0]);
   __syncthreads();
   TRACE(1)
-  if (nk > 2) gload(2, rx);
-  for (int i = 0; i < nk; i += 2) {
-    // stage 0 holds tile i; ry holds tile i+1, rx tile i+2
-    compute(0);
-    if (i + 1 < nk) lstore(1, ry);
-    __syncthreads();
-    if (i + 3 < nk) gload(i + 3, ry);
-    if (i + 1 >= nk) break;
-    // stage 1 holds tile i+1; rx holds tile i+2, ry tile i+3
-    compute(1);
-    if (i + 2 < nk) lstore(0, rx);
-    __syncthreads();
-    if (i + 4 < nk) gload(i + 4, rx);
+  if (2 < nk) gload(2, r[0]);
+  for (int i0 = 0; i0 < nk; i0 += 2) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int i = i0 + u;
+      if (i >= nk) break;
+      TRACE_T(0)
+      compute(u);
+      TRACE_T(1)
+      if (i + 1 < nk) lstore(u ^ 1, r[u ^ 1]);
+      TRACE_T(2)
+      __syncthreads();
+      TRACE_T(3)
+      if (i + 3 < nk) gload(i + 3, r[u ^ 1]);
+    }
   }
 
   TRACE(2)
+#ifdef PPLL_GEMM_TRACE
+  if (tid == 0) { tr[5] = tacc[0]; tr[6] = tacc[1]; tr[7] = tacc[2]; }
+#endif
   if (do_colsum) {
     csum += __shfl_xor(csum, 1, 64);
     const int n = n0 + (tid >> 1);
@@ -381,9 +405,15 @@ int gemm_mfma_splits(int M, int N, int K) {
   const int nkt = (K + BK - 1) / BK;
   if (tiles >= 128 || nkt < 8) return 1;
   int splits = (256 + tiles - 1) / tiles;          // about one workgroup per compute unit
-  if (splits > nkt / 2) splits = nkt / 2;
+  if (nkt >= 32) {                                  // a multiple of 8, so that splits can be dealt to the 8 XCDs evenly
+    splits = ((splits + 7) / 8) * 8;
+    while (splits > 8 && splits > nkt / 4) splits -= 8;
+  } else if (splits > nkt / 2) {
+    splits = nkt / 2;
+  }
   int per = (nkt + splits - 1) / splits;
-  return (nkt + per - 1) / per;
+  int real = (nkt + per - 1) / per;
+  return (nkt >= 32 && real != splits) ? splits : real;   // keep the multiple of 8 (a trailing split may be short or empty)
 }
 size_t gemm_mfma_partial_floats(int M, int N, int K) {
   int s = gemm_mfma_splits(M, N, K);
@@ -418,8 +448,11 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   p.colsum = g.colsum ? (splits > 1 ? colsum_partial : g.colsum) : nullptr;
   p.kt_per_split = (nkt + splits - 1) / splits;
   p.partial = splits > 1 ? partial : nullptr;
-  p.xcd_map = p.tiles_m >= 16;
-  dim3 grid(p.xcd_map ? ((p.tiles_m + 7) / 8) * 8 * p.tiles_n : p.tiles_m * p.tiles_n, splits);
+  p.splits = splits;
+  p.xcd_map = (splits > 1 && splits % 8 == 0) ? 2 : (p.tiles_m >= 16 ? 1 : 0);
+  dim3 grid(p.tiles_m * p.tiles_n, splits);
+  if (p.xcd_map == 1) grid = dim3(((p.tiles_m + 7) / 8) * 8 * p.tiles_n, splits);
+  if (p.xcd_map == 2) grid = dim3(p.tiles_m * p.tiles_n * splits, 1);
   static bool lds_opted_in = false;   // > 64 KB of dynamic LDS needs a one-time opt-in per kernel
   if (!lds_opted_in) {
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
@@ -428,6 +461,8 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
     lds_opted_in = true;
   }
+  void* prof = nullptr;
+  PPLL_TRY(profile_begin(s, 2.0 * g.M * g.N * g.K, &prof));
   if (small_m) {
     if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 64>), grid, dim3(256), lds_bytes(64), s, p);
     else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 64>), grid, dim3(256), lds_bytes(64), s, p);
@@ -436,6 +471,7 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   else if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 128>), grid, dim3(256), lds_bytes(128), s, p);
   else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 128>), grid, dim3(256), lds_bytes(128), s, p);
   PPLL_HIP(hipGetLastError());
+  PPLL_TRY(profile_end(s, prof));
   if (splits > 1) {
     size_t mn = (size_t)g.M * g.N;
     const int main_blocks = (int)((mn / 4 + 255) / 256), extra = g.colsum ? (g.N + 255) / 256 : 0;

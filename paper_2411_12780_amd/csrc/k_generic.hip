@@ -792,6 +792,19 @@ int launch_refresh_shadow(hipStream_t s, const float* p, uint16_t* shadow, size_
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
+namespace {
+__global__ __launch_bounds__(256) void copy_probe_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+}  // namespace
+// Plain copy of known size: the reference that hardware byte counters are scaled against.
+int launch_copy_probe(hipStream_t s, const void* src, void* dst, size_t bytes) {
+  size_t n16 = bytes / 16;
+  hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
 int launch_fill_zero(hipStream_t s, void* p, size_t bytes) {
   size_t words = (bytes + 3) / 4;
   hipLaunchKernelGGL(fill_zero_kernel, dim3((words + 255) / 256), dim3(256), 0, s, (uint32_t*)p, words);
