@@ -42,6 +42,56 @@ def step_flops(wl: dict) -> float:
     return 3.0 * conv * 2 * wl["n_basic_blocks"] - conv + 3.0 * aux + 3.0 * 2.0 * B * A * wl["num_classes"]
 
 
+def bench_pipeline(args, torch, P, synth, dev) -> int:
+    """configs[4]: the 12-layer ViT as 4 blocks of 3 layers on 4 HIP streams, depth-2 device queues.
+    A step is one batch entering the pipeline; timing is steady state (queues full)."""
+    first, rest = synth.workload("vit_stage_bf16"), synth.workload("vit_stage_act_bf16")
+    wls = [first, rest, rest, rest]
+    for j, w in enumerate(wls):
+        w["seed"] = j
+    cfgs = [P.make_config(w) for w in wls]
+    depth = 2
+    nbytes = P.ppll_pipeline_workspace_bytes(cfgs, depth)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    streams = [torch.cuda.Stream(device=dev) for _ in cfgs]
+    pipe = P.ppll_pipeline_init(cfgs, depth, ws, nbytes, [s.cuda_stream for s in streams], None)
+    ring = 8
+    xs, ys = [], []
+    for i in range(ring):
+        x, y = synth.make_batch(first, seed=0, index=i)
+        xs.append(torch.from_numpy(x).to(torch.bfloat16).to(dev))
+        ys.append(torch.from_numpy(y).to(dev))
+    lr = float(first["lr"])
+
+    def run(n):
+        for i in range(n):
+            P.ppll_pipeline_step(pipe, xs[i % ring], ys[i % ring], lr)
+
+    run(max(args.warmup, 8))
+    P.ppll_pipeline_sync(pipe, len(cfgs))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps)
+    losses = P.ppll_pipeline_sync(pipe, len(cfgs))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    flops = sum(step_flops(w) for w in wls)
+    out = {
+        "metric": "local-block train step images/sec on 1 MI355X; % bf16 MFMA peak",
+        "value": first["batch"] / (elapsed / args.steps), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": max(args.warmup, 8), "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "vit_pipeline4", "batch": first["batch"], "blocks": 4, "queue_depth": depth,
+                   "streams": 4, "optimizer": "adamw"},
+        "step_gflop": flops / 1e9, "step_tflops": flops / (elapsed / args.steps) / 1e12,
+        "mfma_peak_frac_step": flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
+        "losses_last_batch": [float(v) for v in losses],
+    }
+    P.ppll_pipeline_destroy(pipe)
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -65,6 +115,8 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     dev = "cuda:0"
+    if args.workload == "vit_pipeline4":
+        return bench_pipeline(args, torch, P, synth, dev)
     wl = synth.workload(args.workload)
     wl["seed"] = 0
     cfg = P.make_config(wl)

@@ -370,7 +370,7 @@ int ppll_pipeline_init(const ppll_block_config* cfgs, int32_t K, int32_t depth, 
     }
     ppll_block* h = nullptr;
     st = ppll_block_init(&cfgs[j], bws, ws, init_params_host ? init_params_host[j] : nullptr, hip_streams[j], &h);
-    if (st == PPLL_OK) { p->blocks.push_back(h); p->streams.push_back((hipStream_t)hip_streams[j]); }
+    if (st == PPLL_OK) { h->b.allow_side = false; p->blocks.push_back(h); p->streams.push_back((hipStream_t)hip_streams[j]); }
   }
   p->losses = (float*)take((size_t)K * sizeof(float));
   auto cleanup = [&]() {

@@ -84,6 +84,7 @@ struct Block {
   // (main -> side); ev_done[i]: product finished (side -> main, waited on before a buffer the
   // product reads is overwritten, and before the optimizer).
   hipStream_t side = nullptr;
+  bool allow_side = true;        // the pipeline turns it off: its K blocks already overlap on K streams
   std::vector<hipEvent_t> ev_fork, ev_done;
   hipEvent_t pending[4] = {nullptr, nullptr, nullptr, nullptr};   // last reader of gA, d_h, gB, d_qkv
   hipEvent_t side_tail = nullptr;

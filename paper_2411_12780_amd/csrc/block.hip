@@ -213,7 +213,7 @@ size_t Block::plan(char* base) {
 int Block::ensure_side_stream() {
   if (side) return PPLL_OK;
   static const bool single = getenv("PPLL_SINGLE_STREAM") != nullptr;
-  if (single || cfg.arch != PPLL_VIT || dt != BF16) return PPLL_OK;
+  if (single || !allow_side || cfg.arch != PPLL_VIT || dt != BF16) return PPLL_OK;
   PPLL_HIP(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
   const int n = 4 * (cfg.depth + cfg.aux_depth);
   for (int i = 0; i < n; ++i) {
