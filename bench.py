@@ -42,6 +42,17 @@ def step_flops(wl: dict) -> float:
     return 3.0 * conv * 2 * wl["n_basic_blocks"] - conv + 3.0 * aux + 3.0 * 2.0 * B * A * wl["num_classes"]
 
 
+def measured_traffic(workload: str):
+    """HBM bytes per GEMM launch from the committed counter summary of this workload (two rocprofv3
+    --pmc runs, scaled by the copy probe); None for a workload without such a summary."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_gemm_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return float(json.load(f)["bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def bench_pipeline(args, torch, P, synth, dev) -> int:
     """configs[4]: the 12-layer ViT as 4 blocks of 3 layers on 4 HIP streams, depth-2 device queues.
     A step is one batch entering the pipeline; timing is steady state (queues full)."""
@@ -174,14 +185,16 @@ def main() -> int:
         torch.cuda.synchronize()
         gemm_ms, gemm_flops, launches = P.ppll_profile_read()
         P.ppll_profile_enable(False)
-        achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
-        out["roofline"] = {"bound": "mfma", "kernel": "gemm (all Linear fwd/dgrad/wgrad launches)",
-                           "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                           "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
-                           "launches_per_step": launches / args.steps,
-                           "avg_launch_us": 1e3 * gemm_ms / max(launches, 1),
-                           "gemm_ms_per_step": gemm_ms / args.steps,
-                           "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
+        if launches > 0:
+            achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+            out["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all variants: Linear fwd/dgrad/wgrad)",
+                               "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                               "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.workload),
+                               "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy probe)",
+                               "launches_per_step": launches / args.steps,
+                               "avg_launch_us": 1e3 * gemm_ms / launches,
+                               "gemm_ms_per_step": gemm_ms / args.steps,
+                               "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
 
     if args.probe_copy:
         nbytes = 256 << 20
