@@ -56,6 +56,8 @@ struct Block {
   int* ticket_dev = nullptr;     // arrival counter of the last-workgroup reductions (self-resetting)
   float* partials = nullptr;
   size_t partial_floats = 0;
+  ReduceQueue rq;                 // second stages of the gradient reductions, run in one launch before the update
+  size_t arena_floats = 0;
   float* splitk = nullptr;       // split-K partial sums of the weight-gradient GEMMs
   size_t splitk_floats = 0;
 

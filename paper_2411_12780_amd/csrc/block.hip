@@ -206,6 +206,23 @@ size_t Block::plan(char* base) {
   size_t o = (size_t)colsum_partial_floats(B, C);
   if (o > partial_floats) partial_floats = o;
   partials = bump.floats(partial_floats);
+  rq.scratch = partials;
+  // room for every queued reduction of a step: LayerNorm scale/shift gradients of all layers and the
+  // head, position / class-token / bias gradients (a reduction that finds no room runs at once)
+  arena_floats = 0;
+  if (cfg.arch == PPLL_VIT) {
+    const int B = cfg.batch, T = cfg.tokens, D = cfg.dim;
+    const size_t M = (size_t)B * T;
+    const int widest = cfg.mlp_dim > 3 * D ? cfg.mlp_dim : 3 * D;
+    arena_floats = (size_t)(2 * (cfg.depth + cfg.aux_depth)) * (layernorm_bwd_partial_floats((int)M, D) + 64) +
+                   (size_t)layernorm_bwd_partial_floats(B, D) + (size_t)colsum_partial_floats(B, C) + 256;
+    if (cfg.input_kind == PPLL_IN_IMAGE)
+      arena_floats += (size_t)embed_bwd_partial_floats(B, T, D) + (size_t)colsum_partial_floats((int)M, D) + 128;
+    if (!(dt == BF16))   // the generic GEMM does not fold bias gradients: one column sum per Linear layer
+      arena_floats += (size_t)(cfg.depth + cfg.aux_depth) * 4 * ((size_t)colsum_partial_floats((int)M, widest) + 64);
+  }
+  rq.arena = arena_floats ? bump.floats(arena_floats) : nullptr;
+  rq.arena_floats = arena_floats;
   return (bump.off + 255) & ~(size_t)255;
 }
 
@@ -302,7 +319,7 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
       return (int)PPLL_OK;
     }
     PPLL_TRY(launch_gemm(s, g));
-    return fused ? (int)PPLL_OK : launch_colsum(s, dy, dt, M, out_dim, partials, grads + b_off);
+    return fused ? (int)PPLL_OK : launch_colsum(s, dy, dt, M, out_dim, rq, grads + b_off);
   };
   auto before_write = [&](int slot) -> int {
     if (pending[slot]) {
@@ -319,7 +336,7 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
   PPLL_TRY(launch_gemm(s, dgrad(d_h, F, p.fc1_w, D, d_u)));
   PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w, p.fc1_b, 1));
   PPLL_TRY(before_write(2));
-  PPLL_TRY(launch_layernorm_bwd(s, d_u, a.x1, dt, D, M, D, params + p.ln2_g, a.mean2, a.rstd2, g_in, g_tmp, partials,
+  PPLL_TRY(launch_layernorm_bwd(s, d_u, a.x1, dt, D, M, D, params + p.ln2_g, a.mean2, a.rstd2, g_in, g_tmp, rq,
                                 grads + p.ln2_g, grads + p.ln2_b));
   PPLL_TRY(launch_gemm(s, dgrad(g_tmp, D, p.proj_w, D, d_u)));
   PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w, p.proj_b, 2));
@@ -329,7 +346,7 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
   PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b, 3));
   PPLL_TRY(before_write(0));
   return launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, g_tmp,
-                              need_dx ? g_out : nullptr, partials, grads + p.ln1_g, grads + p.ln1_b);
+                              need_dx ? g_out : nullptr, rq, grads + p.ln1_g, grads + p.ln1_b);
 }
 
 int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
@@ -379,14 +396,14 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
   g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = D; g.N = C; g.K = B;
   PPLL_TRY(launch_gemm_generic(s, g));
-  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, partials, grads + head_b));
+  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, rq, grads + head_b));
   g = gemm_args();
   g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
   g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
   g.C = dz; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = C;
   PPLL_TRY(launch_gemm_generic(s, g));
   PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
-                                partials, grads + head_ln_g, grads + head_ln_b));
+                                rq, grads + head_ln_g, grads + head_ln_b));
   PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, gA));
   // ---- backward: auxiliary layers then module layers; the chain stops at x_in
   for (int l = L + A - 1; l >= 0; --l) {
@@ -399,7 +416,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     for (hipEvent_t& e : pending) e = nullptr;
   }
   if (image) {
-    PPLL_TRY(launch_embed_bwd(s, gA, dt, B, T, D, partials, grads + pos, grads + cls, embed_tmp));
+    PPLL_TRY(launch_embed_bwd(s, gA, dt, B, T, D, rq, grads + pos, grads + cls, embed_tmp));
     if (T > 1) {
       g = gemm_args();
       g.A = patches; g.a_dt = dt; g.a_sm = 1; g.a_sk = ppc;
@@ -407,7 +424,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
       g.C = grads + pe_w; g.c_dt = F32; g.ldc = D; g.M = ppc; g.N = D; g.K = B * (T - 1);
       g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
       PPLL_TRY(launch_gemm(s, g));
-      PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, partials, grads + pe_b));
+      PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, rq, grads + pe_b));
     } else {
       PPLL_TRY(launch_fill_zero(s, grads + pe_w, ((size_t)ppc * D + D) * sizeof(float)));
     }
@@ -460,7 +477,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
   g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = A; g.N = C; g.K = B;
   PPLL_TRY(launch_gemm_generic(s, g));
-  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, partials, grads + head_b));
+  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, rq, grads + head_b));
   g = gemm_args();
   g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
   g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
@@ -502,8 +519,10 @@ int Block::step(const void* x_in, const int32_t* labels, float lr, void* x_out, 
                 const std::function<int()>& after_forward) {
   last_stream = s;
   PPLL_TRY(ensure_side_stream());
+  rq.reset();
   if (cfg.arch == PPLL_VIT) PPLL_TRY(vit_step(x_in, labels, x_out, s, after_forward));
   else PPLL_TRY(resnet_step(x_in, labels, x_out, s, after_forward));
+  PPLL_TRY(rq.flush(s));
   PPLL_TRY(update(lr, s));
   if (loss_out) PPLL_HIP(hipMemcpyAsync(loss_out, loss_dev, sizeof(float), hipMemcpyDeviceToDevice, s));
   return PPLL_OK;

@@ -3,6 +3,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <vector>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -99,21 +100,38 @@ int profile_begin(hipStream_t s, double flops, void** token);   // event pair ar
 int profile_end(hipStream_t s, void* token);
 int profile_read(double* ms, double* flops, long long* launches);
 int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out);
+
+// Second stage of the two-stage (ordered, atomic-free) reductions.  A first-stage kernel asks for
+// room for its partial sums: from the arena, if there is one with space left, and then the second
+// stage is only queued and all queued ones run as one launch in flush() (parameter gradients are
+// not needed before the optimizer update); otherwise from the shared scratch buffer, and the
+// second stage runs at once.  The summation order is the same either way.
+struct ReduceJob { const float* src; float* dst; int chunks, N; long stride; float scale; };
+struct ReduceQueue {
+  float* scratch = nullptr;            // shared by all reductions that finish at once
+  float* arena = nullptr;              // private room for the queued ones, handed out front to back
+  size_t arena_floats = 0, used = 0;
+  std::vector<ReduceJob> jobs;
+  float* space(size_t floats, bool* queued);
+  int reduce(hipStream_t s, bool queued, const float* src, int chunks, int N, long stride, float scale, float* out);
+  int flush(hipStream_t s);
+  void reset() { used = 0; jobs.clear(); }
+};
 int colsum_mode(hipStream_t s, const void* x, int dt, int rows, int N, int mode, const float* shift, float scale,
-                float* partials, float* out);
+                ReduceQueue& rq, float* out);
 
 // ---------------------------------------------------------------- row-wise ops
 int launch_layernorm_fwd(hipStream_t s, const void* x, int dt, long x_row_stride, int rows, int D,
                          const float* g, const float* b, float eps, void* y, float* mean, float* rstd);
-// dx_out = dres + LN'(dy) (either may be null); partial sums of dg/db go to
-// `partials` [nchunks][2][D] and are reduced into dg, db.
+// dx_out = dres + LN'(dy) (either may be null); partial sums of dg/db ([nchunks][2][D]) are
+// reduced into dg, db through the queue.
 int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, long x_row_stride, int rows,
                          int D, const float* g, const float* mean, const float* rstd, const void* dres,
-                         void* dx_out, float* partials, float* dg, float* db);
+                         void* dx_out, ReduceQueue& rq, float* dg, float* db);
 int layernorm_bwd_partial_floats(int rows, int D);
 
 // out[n] = sum over rows of x[r, n]  (two-stage, deterministic)
-int launch_colsum(hipStream_t s, const void* x, int dt, int rows, int N, float* partials, float* out);
+int launch_colsum(hipStream_t s, const void* x, int dt, int rows, int N, ReduceQueue& rq, float* out);
 int colsum_partial_floats(int rows, int N);
 
 int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labels, int B, int C,
@@ -124,7 +142,7 @@ int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W,
 int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cls, const float* pos, int B,
                            int T, int D, void* x0);
 // dpos[t,d] = sum_b dx[b,t,d]; dcls[d] = dpos[0,d]; dE = dx[:,1:,:] gathered
-int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* partials, float* dpos,
+int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, ReduceQueue& rq, float* dpos,
                      float* dcls, void* dE);
 int embed_bwd_partial_floats(int B, int T, int D);
 // dx[b,0,:] = dcls[b,:], every other row 0

@@ -51,6 +51,7 @@ struct MfmaArgs {
 #ifdef PPLL_GEMM_TRACE
   long long* trace;                 // [workgroup][8] wall-clock stamps (development builds only)
 #endif
+  uint32_t a_bytes, b_bytes, c_bytes, r_bytes, aux_bytes, partial_bytes;   // extents of the buffers above
   int xcd_map;                      // 1: ids 8 apart share a tile row (many tile rows), 2: ids 8 apart share a
                                     // split (split-K), 0: row-major ids
   int splits;
@@ -78,57 +79,85 @@ __device__ __forceinline__ int lds_off(int row, int granule16) {
   return row * ROW_BYTES + ((granule16 ^ ((row >> 4) & 7)) << 4);
 }
 
-// k contiguous in memory: ROWS/32 chunks of 8 bf16 per thread
-template <int ROWS>
-__device__ __forceinline__ void load_direct(const uint16_t* __restrict__ base, long ld, int row0, int nrows, int k0,
-                                            int kend, int tid, uint4 (&r)[4]) {
-#pragma unroll
-  for (int i = 0; i < ROWS / 32; ++i) {
-    int c = tid + 256 * i, row = c >> 3, g = c & 7;
-    int k = k0 + g * 8;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row0 + row < nrows && k < kend) v = *reinterpret_cast<const uint4*>(base + (long)(row0 + row) * ld + k);
-    r[i] = v;
-  }
+// ---- Buffer addressing.  Operands, outputs and epilogue inputs are reached through raw buffer
+// descriptors: a load whose byte offset lies beyond the buffer returns 0 and a store there is
+// dropped, so the tile edges (rows beyond M or N, k beyond K or beyond a split's range) need no
+// branches: an out-of-range lane simply gets the offset OOB.  Straight-line code also lets the
+// compiler count outstanding loads exactly, so the loads of the k-tile two steps ahead stay in
+// flight while the previous one is written to LDS.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+constexpr int OOB = 0x7fffffff;   // no buffer here reaches 2^30 bytes (checked on the host)
+constexpr int OOB_BASE = 0x40000000;   // a base offset that stays out of range after a k-step (< 2^30) is added
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* ptr, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(ptr), 0, (int)bytes, 0x00020000);
 }
-template <int ROWS>
-__device__ __forceinline__ void store_direct(char* lds, int tid, const uint4 (&r)[4]) {
-#pragma unroll
-  for (int i = 0; i < ROWS / 32; ++i) {
-    int c = tid + 256 * i, row = c >> 3, g = c & 7;
-    *reinterpret_cast<uint4*>(lds + lds_off(row, g)) = r[i];
-  }
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, int off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, int off, uint4 v) {
+  const u32x4 w = {v.x, v.y, v.z, v.w};
+  __builtin_amdgcn_raw_buffer_store_b128(w, r, off, 0, 0);
 }
 
-// the row index contiguous in memory: thread (mg, kg) takes rows mg*8..+7 and k = kg*4..+3
-__device__ __forceinline__ void load_transposed(const uint16_t* __restrict__ base, long ld, int row0, int nrows, int k0,
-                                                int kend, int tid, uint4 (&r)[4]) {
-  int mg = tid & 15, kg = tid >> 4;
-  int row = row0 + mg * 8;
+// One operand tile (ROWS x 64) on its way from memory to LDS, as seen by one thread.
+//  direct (k contiguous in memory): ROWS/32 pieces of 8 bf16; piece i is row (tid + 256 i)/8,
+//    k-granule tid%8.
+//  transposed (row index contiguous): thread (mg = tid%16, kg = tid/16) takes rows 8 mg..+7 at
+//    k = 4 kg..+3, four 16-byte loads, and turns them into eight 8-byte LDS writes.
+template <bool TR, int ROWS>
+struct OperandLoader {
+  static constexpr int NP = TR ? 4 : ROWS / 32;
+  int off[NP];      // byte offset of each piece at k = 0 of the thread's k-range; OOB_BASE if its row does not exist
+  int kl;           // first k (within a tile) of the thread's pieces
+  int ld2;          // transposed: bytes between consecutive k
+  __device__ __forceinline__ void init(long ld, int row0, int nrows, int tid) {
+    if (TR) {
+      const int mg = tid & 15, kg = tid >> 4, row = row0 + mg * 8;
+      kl = kg * 4; ld2 = (int)(ld * 2);
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    int k = k0 + kg * 4 + j;
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (row < nrows && k < kend) v = *reinterpret_cast<const uint4*>(base + (long)k * ld + row);
-    r[j] = v;
-  }
-}
-__device__ __forceinline__ void store_transposed(char* lds, int tid, const uint4 (&r)[4]) {
-  int mg = tid & 15, kg = tid >> 4;
-  const uint32_t* w0 = reinterpret_cast<const uint32_t*>(&r[0]);
-  const uint32_t* w1 = reinterpret_cast<const uint32_t*>(&r[1]);
-  const uint32_t* w2 = reinterpret_cast<const uint32_t*>(&r[2]);
-  const uint32_t* w3 = reinterpret_cast<const uint32_t*>(&r[3]);
+      for (int j = 0; j < 4; ++j) off[j] = row < nrows ? (int)(((long)(kl + j) * ld + row) * 2) : OOB_BASE;
+    } else {
+      kl = (tid & 7) * 8; ld2 = 0;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-    uint2 o;
-    o.x = __builtin_amdgcn_perm(w1[i >> 1], w0[i >> 1], sel);   // k, k+1
-    o.y = __builtin_amdgcn_perm(w3[i >> 1], w2[i >> 1], sel);   // k+2, k+3
-    int row = mg * 8 + i;
-    *reinterpret_cast<uint2*>(lds + lds_off(row, kg >> 1) + (kg & 1) * 8) = o;
+      for (int i = 0; i < NP; ++i) {
+        const int row = row0 + ((tid + 256 * i) >> 3);
+        off[i] = row < nrows ? (int)(((long)row * ld + kl) * 2) : OOB_BASE;
+      }
+    }
   }
-}
+  // pieces of the k-tile starting at k0; k >= kend reads as zero
+  __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t rsrc, int k0, int kend, uint4 (&r)[4]) const {
+    if (TR) {
+      const int step = k0 * ld2;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) r[j] = buf_load16(rsrc, (k0 + kl + j < kend) ? off[j] + step : OOB);
+    } else {
+      const bool kin = k0 + kl < kend;
+#pragma unroll
+      for (int i = 0; i < NP; ++i) r[i] = buf_load16(rsrc, kin ? off[i] + 2 * k0 : OOB);
+    }
+  }
+  // quarter q (0..3) of the thread's LDS writes of one tile
+  __device__ __forceinline__ void store_part(char* lds, int tid, const uint4 (&r)[4], int q) const {
+    if (TR) {
+      const int mg = tid & 15, kg = tid >> 4;
+      const uint32_t w0 = reinterpret_cast<const uint32_t*>(&r[0])[q], w1 = reinterpret_cast<const uint32_t*>(&r[1])[q];
+      const uint32_t w2 = reinterpret_cast<const uint32_t*>(&r[2])[q], w3 = reinterpret_cast<const uint32_t*>(&r[3])[q];
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const uint32_t sel = h ? 0x07060302u : 0x05040100u;
+        uint2 o;
+        o.x = __builtin_amdgcn_perm(w1, w0, sel);   // k, k+1 of row 8 mg + 2 q + h
+        o.y = __builtin_amdgcn_perm(w3, w2, sel);   // k+2, k+3
+        *reinterpret_cast<uint2*>(lds + lds_off(mg * 8 + 2 * q + h, kg >> 1) + (kg & 1) * 8) = o;
+      }
+    } else if (q < NP) {
+      const int c = tid + 256 * q;
+      *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = r[q];
+    }
+  }
+};
 
 constexpr int STAGE_LD = BN + 4;                      // fp32 staging tile of the epilogue, padded row
 constexpr int oper_bytes(int tm) { return (tm + BN) * ROW_BYTES; }   // one stage of both operand tiles
@@ -138,10 +167,10 @@ static_assert(BM * STAGE_LD * 4 <= lds_bytes(BM) && 64 * STAGE_LD * 4 <= lds_byt
 
 struct TileRegs { uint4 a[4], b[4]; };
 
+// AT: A is stored [K][M] (transposing loader), else [M][K].  BT likewise for B ([K][N] / [N][K]).
 // TM = rows of the output tile: 128 (wave tile 64 x 64) or, for outputs with too few 128-row
 // tiles to fill the chip, 64 (wave tile 32 x 64; direct A loader only).
-// PF = k-tiles in flight in registers ahead of the one being multiplied (4 measured slower than 2).
-template <bool AT, bool BT, int TM, int PF = 2>
+template <bool AT, bool BT, int TM>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   static_assert(TM == 128 || (TM == 64 && !AT), "64-row tiles are for the direct A loader");
   constexpr int IM = TM / 64;                  // 32-row MFMA tiles per wave along m
@@ -172,7 +201,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   const int m0 = tm * TM, n0 = tn * BN;
   const int nkt = (p.K + BK - 1) / BK;
   const int kt0 = split * p.kt_per_split;
-  const int nk = min(nkt, kt0 + p.kt_per_split) - kt0;
+  const int nk = min(nkt, kt0 + p.kt_per_split) - kt0;   // k-tiles of this workgroup (a trailing split may have none)
+  const int kbeg = kt0 * BK, kend = min(p.K, (kt0 + nk) * BK);
 
   f32x16 acc[2][IM];
 #pragma unroll
@@ -182,30 +212,51 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-  // Software pipeline: two LDS stages and PF register sets, so that the global loads of k-tiles
-  // i+2 .. i+1+PF are in flight while tile i is multiplied and tile i+1 is written to LDS.
-  const int frag_row = lane & 31, frag_g = lane >> 5;
+#ifdef PPLL_GEMM_TRACE
+  long long* tr = p.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
+  if (tid == 0) tr[0] = wall_clock64();
+#define TRACE(i) if (tid == 0) tr[i] = wall_clock64();
+#else
+#define TRACE(i)
+#endif
+
+  const __amdgpu_buffer_rsrc_t rsA = make_rsrc(p.A, p.a_bytes), rsB = make_rsrc(p.B, p.b_bytes);
+  OperandLoader<AT, TM> ldA;
+  OperandLoader<BT, BN> ldB;
+  ldA.init(p.lda, m0, p.M, tid);
+  ldB.init(p.ldb, n0, p.N, tid);
+  // k-tile i of this workgroup -> registers; tiles past the end read as zeros without touching memory
   auto gload = [&](int i, TileRegs& r) {
-    const int k0 = (kt0 + i) * BK;
-    if (AT) load_transposed(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
-    else load_direct<TM>(p.A, p.lda, m0, p.M, k0, p.K, tid, r.a);
-    if (BT) load_transposed(p.B, p.ldb, n0, p.N, k0, p.K, tid, r.b);
-    else load_direct<BN>(p.B, p.ldb, n0, p.N, k0, p.K, tid, r.b);
+    const int k0 = kbeg + i * BK;
+    ldA.load(rsA, k0, kend, r.a);
+    ldB.load(rsB, k0, kend, r.b);
   };
-  auto lstore = [&](int stage, const TileRegs& r) {
+  auto lstore_part = [&](int stage, const TileRegs& r, int q) {
     char* la = smem + stage * OPER_BYTES;
-    char* lb = la + TM * ROW_BYTES;
-    if (AT) store_transposed(la, tid, r.a); else store_direct<TM>(la, tid, r.a);
-    if (BT) store_transposed(lb, tid, r.b); else store_direct<BN>(lb, tid, r.b);
+    ldA.store_part(la, tid, r.a, q);
+    ldB.store_part(la + TM * ROW_BYTES, tid, r.b, q);
+  };
+  const int frag_row = lane & 31, frag_g = lane >> 5;
+  auto load_frags = [&](int stage, int kk, bf16x8 (&fa)[IM], bf16x8 (&fb)[2]) {
+    const char* la = smem + stage * OPER_BYTES;
+    const char* lb = la + TM * ROW_BYTES;
+#pragma unroll
+    for (int im = 0; im < IM; ++im)
+      fa[im] = *reinterpret_cast<const bf16x8*>(la + lds_off(wm * (TM / 2) + im * 32 + frag_row, kk * 2 + frag_g));
+#pragma unroll
+    for (int jn = 0; jn < 2; ++jn)
+      fb[jn] = *reinterpret_cast<const bf16x8*>(lb + lds_off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
   };
   // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k
   const bool do_colsum = p.colsum != nullptr && m0 == 0;
   float csum = 0.f;
-  auto compute = [&](int stage) {
-    const char* la = smem + stage * OPER_BYTES;
-    const char* lb = la + TM * ROW_BYTES;
+  bf16x8 fa[2][IM], fb[2][2];   // operand fragments of two consecutive 16-wide k-steps
+  // Multiplies the k-tile in LDS stage `stage` (its first fragments are already in fa[0], fb[0])
+  // and, between the groups of MFMAs, writes the next tile (registers rn) to the other stage, so
+  // that the LDS writes and the fragment reads of the following k-step run under the matrix pipe.
+  auto multiply = [&](int stage, const TileRegs& rn, bool stage_next) {
     if (do_colsum) {   // thread (row = tid/2, half = tid%2) sums 4 of the row's 8 granules; their order is irrelevant
-      const char* rowp = lb + (tid >> 1) * ROW_BYTES + (tid & 1) * 64;
+      const char* rowp = smem + stage * OPER_BYTES + TM * ROW_BYTES + (tid >> 1) * ROW_BYTES + (tid & 1) * 64;
 #pragma unroll
       for (int gq = 0; gq < 4; ++gq) {
         uint4 w = *reinterpret_cast<const uint4*>(rowp + gq * 16);
@@ -217,63 +268,53 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
     }
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[IM], fb[2];
-#pragma unroll
-      for (int im = 0; im < IM; ++im)
-        fa[im] = *reinterpret_cast<const bf16x8*>(la + lds_off(wm * (TM / 2) + im * 32 + frag_row, kk * 2 + frag_g));
-#pragma unroll
-      for (int jn = 0; jn < 2; ++jn)
-        fb[jn] = *reinterpret_cast<const bf16x8*>(lb + lds_off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
+      if (kk + 1 < BK / 16) load_frags(stage, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
 #pragma unroll
       for (int jn = 0; jn < 2; ++jn)
 #pragma unroll
         for (int im = 0; im < IM; ++im)
-          acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[jn], fa[im], acc[jn][im], 0, 0, 0);
+          acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][jn], fa[kk & 1][im], acc[jn][im], 0, 0, 0);
+      if (stage_next) lstore_part(stage ^ 1, rn, kk);
     }
   };
+  // One full step: multiply tile i (stage u), stage tile i+1, then refill the freed register
+  // set with tile i+3 and fetch the first fragments of tile i+1.
+  auto step = [&](int u, TileRegs& rn, int i) {
+    multiply(u, rn, true);
+    __syncthreads();
+    load_frags(u ^ 1, 0, fa[0], fb[0]);
+    gload(i + 3, rn);
+  };
 
-#ifdef PPLL_GEMM_TRACE
-  long long* tr = p.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
-  if (tid == 0) tr[0] = wall_clock64();
-#define TRACE(i) if (tid == 0) tr[i] = wall_clock64();
-  long long tacc[3] = {0, 0, 0}, tlast = 0;   // compute, LDS store (incl. wait for the loads), barrier
-#define TRACE_T(k) { long long now = __builtin_readcyclecounter(); if (k > 0) tacc[k - 1] += now - tlast; tlast = now; }
-#else
-#define TRACE(i)
-#define TRACE_T(k)
-#endif
-  // tile t travels in register set t % 2 and LDS stage t % 2.  (Reading the A fragments of a
-  // k-contiguous A straight from global memory instead, to halve the LDS traffic, was measured
-  // 18 % slower: 32-byte pieces of 32 different rows per load instruction.)
-  static_assert(PF == 2, "the loop below is written for two register sets");
+  // Software pipeline: two LDS stages and two register sets.  Tile t travels in register set
+  // t % 2 and LDS stage t % 2; while tile i is multiplied, tile i+1 moves from registers to LDS
+  // and tiles i+2, i+3 are in flight from memory.  (Reading the A fragments of a k-contiguous A
+  // straight from global memory instead, to halve the LDS traffic, was measured 18 % slower:
+  // 32-byte pieces of 32 different rows per load instruction.)
   TileRegs r[2];
+  gload(0, r[0]);
+  gload(1, r[1]);
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
-    if (j < nk) gload(j, r[j]);
-  if (nk > 0) lstore(0, r[0]);
+  for (int q = 0; q < 4; ++q) lstore_part(0, r[0], q);
   __syncthreads();
   TRACE(1)
-  if (2 < nk) gload(2, r[0]);
-  for (int i0 = 0; i0 < nk; i0 += 2) {
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int i = i0 + u;
-      if (i >= nk) break;
-      TRACE_T(0)
-      compute(u);
-      TRACE_T(1)
-      if (i + 1 < nk) lstore(u ^ 1, r[u ^ 1]);
-      TRACE_T(2)
-      __syncthreads();
-      TRACE_T(3)
-      if (i + 3 < nk) gload(i + 3, r[u ^ 1]);
+  gload(2, r[0]);
+  if (nk > 0) {
+    load_frags(0, 0, fa[0], fb[0]);
+    int i = 0;
+    for (; i + 2 < nk; i += 2) {
+      step(0, r[1], i);
+      step(1, r[0], i + 1);
+    }
+    if (nk - i == 2) {
+      step(0, r[1], i);
+      multiply(1, r[0], false);
+    } else {
+      multiply(0, r[1], false);
     }
   }
 
   TRACE(2)
-#ifdef PPLL_GEMM_TRACE
-  if (tid == 0) { tr[5] = tacc[0]; tr[6] = tacc[1]; tr[7] = tacc[2]; }
-#endif
   if (do_colsum) {
     csum += __shfl_xor(csum, 1, 64);
     const int n = n0 + (tid >> 1);
@@ -283,6 +324,38 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   // Epilogue through LDS: the accumulators (lane = one C row, 4 consecutive columns per group)
   // are laid down as an fp32 tile, then every thread takes 8 consecutive columns of a row, so
   // bias / residual / saved pre-activation are read and C is written in full 128-column rows.
+  // What the write-out needs from memory is requested first, so it arrives during the staging.
+  constexpr int NPASS = TM / 16;
+  const int prow = tid >> 4, c8 = (tid & 15) * 8, n = n0 + c8;
+  const bool nok = n < p.N;
+  const int ncol2 = nok ? 2 * n : OOB_BASE, ncol4 = nok ? 4 * n : OOB_BASE;   // column part of a byte offset; out of range beyond N
+  float bias8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  uint4 resv[NPASS], auxv[NPASS];
+  const bool has_bias = p.bias != nullptr && !p.partial, has_res = p.residual != nullptr && !p.partial;
+  const bool has_aux = p.epilogue == EPI_DGELU && !p.partial;
+  if (has_bias) {
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.bias, (uint32_t)p.N * 4u);
+    const uint4 b0 = buf_load16(rs, nok ? n * 4 : OOB), b1 = buf_load16(rs, nok ? n * 4 + 16 : OOB);
+    bias8[0] = __uint_as_float(b0.x); bias8[1] = __uint_as_float(b0.y); bias8[2] = __uint_as_float(b0.z);
+    bias8[3] = __uint_as_float(b0.w); bias8[4] = __uint_as_float(b1.x); bias8[5] = __uint_as_float(b1.y);
+    bias8[6] = __uint_as_float(b1.z); bias8[7] = __uint_as_float(b1.w);
+  }
+  if (has_res) {
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.residual, p.r_bytes);
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int m = m0 + pass * 16 + prow;
+      resv[pass] = buf_load16(rs, m < p.M ? (int)(((long)m * p.ldr) * 2) + ncol2 : OOB);
+    }
+  }
+  if (has_aux) {
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(p.aux, p.aux_bytes);
+#pragma unroll
+    for (int pass = 0; pass < NPASS; ++pass) {
+      const int m = m0 + pass * 16 + prow;
+      auxv[pass] = buf_load16(rs, m < p.M ? (int)(((long)m * p.ldaux) * 2) + ncol2 : OOB);
+    }
+  }
   __syncthreads();   // every wave is done with the operand stages
   float* stage = reinterpret_cast<float*>(smem);
 #pragma unroll
@@ -297,55 +370,49 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
       }
   __syncthreads();
   TRACE(3)
-#pragma unroll 2
-  for (int pass = 0; pass < TM / 16; ++pass) {
-    const int row = pass * 16 + (tid >> 4), c8 = (tid & 15) * 8;
-    const int m = m0 + row, n = n0 + c8;
-    if (m >= p.M || n >= p.N) continue;
+  const __amdgpu_buffer_rsrc_t rsC = p.partial ? make_rsrc(p.partial, p.partial_bytes) : make_rsrc(p.C, p.c_bytes);
+  const __amdgpu_buffer_rsrc_t rsC2 = make_rsrc(p.C2 ? (const void*)p.C2 : p.C, p.C2 ? p.c_bytes : 0u);
+  const bool out_f32 = p.partial != nullptr || p.c_f32;
+#pragma unroll
+  for (int pass = 0; pass < NPASS; ++pass) {
+    const int row = pass * 16 + prow, m = m0 + row;
+    const bool ok = m < p.M;
     float v[8];
     {
       const float4 lo = *reinterpret_cast<const float4*>(stage + row * STAGE_LD + c8);
       const float4 hi = *reinterpret_cast<const float4*>(stage + row * STAGE_LD + c8 + 4);
       v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
     }
-    if (p.partial) {
-      float* dst = p.partial + ((size_t)split * p.M + m) * p.N + n;
-      *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-      *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
-      continue;
-    }
-    if (p.bias) {
-      const float4 b0 = *reinterpret_cast<const float4*>(p.bias + n), b1 = *reinterpret_cast<const float4*>(p.bias + n + 4);
-      v[0] += b0.x; v[1] += b0.y; v[2] += b0.z; v[3] += b0.w; v[4] += b1.x; v[5] += b1.y; v[6] += b1.z; v[7] += b1.w;
-    }
-    if (p.residual) {
-      const uint4 r = *reinterpret_cast<const uint4*>(p.residual + (size_t)m * p.ldr + n);
-      const uint32_t* w = reinterpret_cast<const uint32_t*>(&r);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += bias8[e];
+    if (has_res) {
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(&resv[pass]);
 #pragma unroll
       for (int e = 0; e < 4; ++e) { v[2 * e] += __uint_as_float(w[e] << 16); v[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u); }
     }
-    if (p.epilogue == EPI_DGELU) {
-      const uint4 hq = *reinterpret_cast<const uint4*>(p.aux + (size_t)m * p.ldaux + n);
-      const uint32_t* w = reinterpret_cast<const uint32_t*>(&hq);
+    if (has_aux) {
+      const uint32_t* w = reinterpret_cast<const uint32_t*>(&auxv[pass]);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         v[2 * e] *= dgelu_fast(__uint_as_float(w[e] << 16));
         v[2 * e + 1] *= dgelu_fast(__uint_as_float(w[e] & 0xffff0000u));
       }
     }
-    if (p.c_f32) {
-      float* dst = (float*)p.C + (size_t)m * p.ldc + n;
-      *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-      *reinterpret_cast<float4*>(dst + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    if (out_f32) {
+      const long e0 = p.partial ? ((long)split * p.M + m) * p.N : (long)m * p.ldc;
+      const int off = ok ? (int)(e0 * 4) + ncol4 : OOB;
+      buf_store16(rsC, off, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
+      buf_store16(rsC, ok ? off + 16 : OOB, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
     } else {
+      const int off = ok ? (int)(((long)m * p.ldc) * 2) + ncol2 : OOB;
       uint4 o;
       o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]); o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
-      *reinterpret_cast<uint4*>((uint16_t*)p.C + (size_t)m * p.ldc + n) = o;
+      buf_store16(rsC, off, o);
       if (p.epilogue == EPI_GELU) {
         uint4 g;
         g.x = pack_bf16x2(gelu_fast(v[0]), gelu_fast(v[1])); g.y = pack_bf16x2(gelu_fast(v[2]), gelu_fast(v[3]));
         g.z = pack_bf16x2(gelu_fast(v[4]), gelu_fast(v[5])); g.w = pack_bf16x2(gelu_fast(v[6]), gelu_fast(v[7]));
-        *reinterpret_cast<uint4*>(p.C2 + (size_t)m * p.ldc + n) = g;
+        buf_store16(rsC2, off, g);
       }
     }
   }
@@ -379,6 +446,10 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial
 long long* g_gemm_trace = nullptr;
 #endif
 bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
+// bytes from the first to one past the last element of an operand (transposed: [K][rows], else [rows][K])
+long operand_bytes(bool transposed, int rows, int K, long ld) {
+  return 2 * (transposed ? (long)(K - 1) * ld + rows : (long)(rows - 1) * ld + K);
+}
 }  // namespace
 
 // True when the MFMA kernel can take this product as it stands.
@@ -396,6 +467,12 @@ bool gemm_mfma_supported(const GemmArgs& g) {
   if (g.residual && (g.r_dt != BF16 || (g.ldr & 7) || !aligned16(g.residual))) return false;
   if (g.epilogue == EPI_GELU && (g.c_dt != BF16 || !g.C2 || !aligned16(g.C2))) return false;
   if (g.epilogue == EPI_DGELU && (g.aux_dt != BF16 || (g.ldaux & 7) || !aligned16(g.aux))) return false;
+  // the kernel addresses every buffer with 32-bit byte offsets
+  const long lim = (1L << 30) - 64;
+  if (operand_bytes(at, g.M, g.K, lda) > lim || operand_bytes(bt, g.N, g.K, ldb) > lim) return false;
+  if (((long)(g.M - 1) * g.ldc + g.N) * 4 > lim) return false;
+  if (g.residual && ((long)(g.M - 1) * g.ldr + g.N) * 2 > lim) return false;
+  if (g.epilogue == EPI_DGELU && ((long)(g.M - 1) * g.ldaux + g.N) * 2 > lim) return false;
   return true;
 }
 
@@ -443,12 +520,19 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   if (plain && partial) {
     splits = gemm_mfma_splits(g.M, g.N, g.K);
     if ((size_t)splits * g.M * g.N + (size_t)splits * g.N > partial_floats) splits = 1;
+    if ((size_t)splits * g.M * g.N * 4 > ((size_t)1 << 30) - 64) splits = 1;
   }
   float* colsum_partial = splits > 1 ? partial + (size_t)splits * g.M * g.N : nullptr;
   p.colsum = g.colsum ? (splits > 1 ? colsum_partial : g.colsum) : nullptr;
   p.kt_per_split = (nkt + splits - 1) / splits;
   p.partial = splits > 1 ? partial : nullptr;
   p.splits = splits;
+  p.a_bytes = (uint32_t)operand_bytes(at, g.M, g.K, p.lda);
+  p.b_bytes = (uint32_t)operand_bytes(bt, g.N, g.K, p.ldb);
+  p.c_bytes = (uint32_t)(((long)(g.M - 1) * g.ldc + g.N) * (p.c_f32 ? 4 : 2));
+  p.r_bytes = g.residual ? (uint32_t)(((long)(g.M - 1) * g.ldr + g.N) * 2) : 0u;
+  p.aux_bytes = g.epilogue == EPI_DGELU ? (uint32_t)(((long)(g.M - 1) * g.ldaux + g.N) * 2) : 0u;
+  p.partial_bytes = splits > 1 ? (uint32_t)((size_t)splits * g.M * g.N * 4) : 0u;
   p.xcd_map = (splits > 1 && splits % 8 == 0) ? 2 : (p.tiles_m >= 16 ? 1 : 0);
   dim3 grid(p.tiles_m * p.tiles_n, splits);
   if (p.xcd_map == 1) grid = dim3(((p.tiles_m + 7) / 8) * 8 * p.tiles_n, splits);

@@ -161,7 +161,71 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* parti
     out[n] = t * scale;
   }
 }
+
+// the same for up to 16 reductions in one launch: workgroups first[j] .. first[j+1]-1 belong to job j
+constexpr int RED_BATCH = 16;
+struct ReduceBatch { int n; int first[RED_BATCH + 1]; ReduceJob job[RED_BATCH]; };
+__global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch a) {
+  __shared__ float red[16][17];
+  int j = 0;
+  while (j + 1 < a.n && (int)blockIdx.x >= a.first[j + 1]) ++j;
+  const float* partial = a.job[j].src;
+  const int chunks = a.job[j].chunks, N = a.job[j].N;
+  const long stride = a.job[j].stride;
+  const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int n = ((int)blockIdx.x - a.first[j]) * 16 + col;
+  float acc = 0.f;
+  if (n < N)
+    for (int c = grp; c < chunks; c += 16) acc += partial[(size_t)c * stride + n];
+  red[grp][col] = acc;
+  __syncthreads();
+  if (grp == 0 && n < N) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) t += red[g][col];
+    a.job[j].dst[n] = t * a.job[j].scale;
+  }
+}
 }  // namespace
+
+float* ReduceQueue::space(size_t floats, bool* queued) {
+  const size_t need = (floats + 63) & ~(size_t)63;
+  if (arena && used + need <= arena_floats) {
+    float* p = arena + used;
+    used += need;
+    *queued = true;
+    return p;
+  }
+  *queued = false;
+  return scratch;
+}
+
+int ReduceQueue::reduce(hipStream_t s, bool queued, const float* src, int chunks, int N, long stride, float scale,
+                        float* out) {
+  if (!queued) return reduce_partials(s, src, chunks, N, stride, scale, out);
+  jobs.push_back(ReduceJob{src, out, chunks, N, stride, scale});
+  return PPLL_OK;
+}
+
+int ReduceQueue::flush(hipStream_t s) {
+  for (size_t j0 = 0; j0 < jobs.size(); j0 += RED_BATCH) {
+    ReduceBatch b{};
+    b.n = (int)(jobs.size() - j0 < (size_t)RED_BATCH ? jobs.size() - j0 : (size_t)RED_BATCH);
+    int blocks = 0;
+    for (int j = 0; j < b.n; ++j) {
+      b.job[j] = jobs[j0 + j];
+      b.first[j] = blocks;
+      blocks += (b.job[j].N + 15) / 16;
+    }
+    b.first[b.n] = blocks;
+    if (blocks > 0) {
+      hipLaunchKernelGGL(reduce_batch_kernel, dim3(blocks), dim3(256), 0, s, b);
+      PPLL_HIP(hipGetLastError());
+    }
+  }
+  jobs.clear();
+  return PPLL_OK;
+}
 
 int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out) {
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((N + 15) / 16), dim3(256), 0, s, partial, chunks, N, stride, scale,
@@ -173,16 +237,18 @@ int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long
 int colsum_partial_floats(int rows, int N) { return ((rows + RED_ROWS - 1) / RED_ROWS) * N; }
 
 int colsum_mode(hipStream_t s, const void* x, int dt, int rows, int N, int mode, const float* shift, float scale,
-                float* partials, float* out) {
+                ReduceQueue& rq, float* out) {
   int chunks = (rows + RED_ROWS - 1) / RED_ROWS;
+  bool queued;
+  float* partials = rq.space((size_t)chunks * N, &queued);
   hipLaunchKernelGGL(colsum_partial_kernel, dim3((N + 255) / 256, chunks), dim3(256), 0, s, x, dt, rows, N, mode,
                      shift, partials);
   PPLL_HIP(hipGetLastError());
-  return reduce_partials(s, partials, chunks, N, N, scale, out);
+  return rq.reduce(s, queued, partials, chunks, N, N, scale, out);
 }
 
-int launch_colsum(hipStream_t s, const void* x, int dt, int rows, int N, float* partials, float* out) {
-  return colsum_mode(s, x, dt, rows, N, 0, nullptr, 1.0f, partials, out);
+int launch_colsum(hipStream_t s, const void* x, int dt, int rows, int N, ReduceQueue& rq, float* out) {
+  return colsum_mode(s, x, dt, rows, N, 0, nullptr, 1.0f, rq, out);
 }
 
 // ===================================================================== LayerNorm
@@ -398,9 +464,12 @@ int layernorm_bwd_partial_floats(int rows, int D) { return ((rows + LN_ROWS - 1)
 
 int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, long xs, int rows, int D,
                          const float* g, const float* mean, const float* rstd, const void* dres, void* dx_out,
-                         float* partials, float* dg, float* db) {
+                         ReduceQueue& rq, float* dg, float* db) {
   int chunks;
-  if (ln_fast_ok(dt, D, xs, x, dy, dres, dx_out) && !(((uintptr_t)g) & 7)) {
+  const bool fast = ln_fast_ok(dt, D, xs, x, dy, dres, dx_out) && !(((uintptr_t)g) & 7);
+  bool queued;
+  float* partials = rq.space((size_t)((rows + (fast ? LNF_ROWS : LN_ROWS) - 1) / (fast ? LNF_ROWS : LN_ROWS)) * 2 * D, &queued);
+  if (fast) {
     chunks = (rows + LNF_ROWS - 1) / LNF_ROWS;
     LN_DISPATCH(D / 128, hipLaunchKernelGGL((layernorm_bwd_bf16_kernel<NJ>), dim3(chunks), dim3(256), 0, s,
                                             (const uint16_t*)dy, (const uint16_t*)x, xs, rows, g, mean, rstd,
@@ -414,9 +483,9 @@ int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, l
   }
   PPLL_HIP(hipGetLastError());
   // each partial row is [dg | db]; the two gradients are neighbours in the parameter table
-  if (db == dg + D) return reduce_partials(s, partials, chunks, 2 * D, 2L * D, 1.0f, dg);
-  PPLL_TRY(reduce_partials(s, partials, chunks, D, 2L * D, 1.0f, dg));
-  return reduce_partials(s, partials + D, chunks, D, 2L * D, 1.0f, db);
+  if (db == dg + D) return rq.reduce(s, queued, partials, chunks, 2 * D, 2L * D, 1.0f, dg);
+  PPLL_TRY(rq.reduce(s, queued, partials, chunks, D, 2L * D, 1.0f, dg));
+  return rq.reduce(s, queued, partials + D, chunks, D, 2L * D, 1.0f, db);
 }
 
 // ===================================================================== cross-entropy
@@ -523,13 +592,15 @@ int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cl
   return PPLL_OK;
 }
 int embed_bwd_partial_floats(int B, int T, int D) { return ((B + EMB_ROWS - 1) / EMB_ROWS) * T * D; }
-int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, float* partials, float* dpos,
+int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D, ReduceQueue& rq, float* dpos,
                      float* dcls, void* dE) {
   const int total = T * D, chunks = (B + EMB_ROWS - 1) / EMB_ROWS;
+  bool queued;
+  float* partials = rq.space((size_t)chunks * total, &queued);
   hipLaunchKernelGGL(embed_bwd_kernel, dim3((total + 255) / 256, chunks), dim3(256), 0, s, dx, dt, B, T, D, partials, dE);
   PPLL_HIP(hipGetLastError());
-  PPLL_TRY(reduce_partials(s, partials, chunks, total, total, 1.0f, dpos));
-  return reduce_partials(s, partials, chunks, D, total, 1.0f, dcls);   // the cls row is token 0
+  PPLL_TRY(rq.reduce(s, queued, partials, chunks, total, total, 1.0f, dpos));
+  return rq.reduce(s, queued, partials, chunks, D, total, 1.0f, dcls);   // the cls row is token 0
 }
 int launch_scatter_cls(hipStream_t s, const void* dcls, int dt, int B, int T, int D, void* dx) {
   size_t total = (size_t)B * T * D;

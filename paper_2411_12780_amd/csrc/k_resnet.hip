@@ -212,8 +212,10 @@ int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float
     return launch_bn_stats_bf16(s, x, rows, C, eps, momentum, partials, ticket, mean, rstd, run_mean, run_var);
   float* var = partials;            // [C], then the chunk partials
   float* part = partials + C;
-  PPLL_TRY(colsum_mode(s, x, dt, rows, C, 0, nullptr, 1.0f / rows, part, mean));
-  PPLL_TRY(colsum_mode(s, x, dt, rows, C, 1, mean, 1.0f / rows, part, var));
+  ReduceQueue now;   // no arena: both reductions finish at once (the second one reads the first one's result)
+  now.scratch = part;
+  PPLL_TRY(colsum_mode(s, x, dt, rows, C, 0, nullptr, 1.0f / rows, now, mean));
+  PPLL_TRY(colsum_mode(s, x, dt, rows, C, 1, mean, 1.0f / rows, now, var));
   hipLaunchKernelGGL(bn_finalize_kernel, dim3((C + 255) / 256), dim3(256), 0, s, var, C, rows, eps, momentum, mean, rstd,
                      run_mean, run_var);
   PPLL_HIP(hipGetLastError());
