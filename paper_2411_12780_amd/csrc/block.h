@@ -69,6 +69,7 @@ struct Block {
   void *z = nullptr, *dz = nullptr, *dcls = nullptr;
   float *head_mean = nullptr, *head_rstd = nullptr, *logits = nullptr, *dlogits = nullptr;
   void *gA = nullptr, *gB = nullptr, *d_u = nullptr, *d_h = nullptr, *d_qkv = nullptr;
+  void *gA2 = nullptr, *gB2 = nullptr, *d_h2 = nullptr, *d_qkv2 = nullptr;   // second set: layers alternate
 
   // ResNet
   std::vector<BasicBlockParams> rb_p;
@@ -88,7 +89,7 @@ struct Block {
   hipStream_t side = nullptr;
   bool allow_side = true;        // the pipeline turns it off: its K blocks already overlap on K streams
   std::vector<hipEvent_t> ev_fork, ev_done;
-  hipEvent_t pending[4] = {nullptr, nullptr, nullptr, nullptr};   // last reader of gA, d_h, gB, d_qkv
+  hipEvent_t pending[8] = {};   // last second-stream reader of gA, d_h, gB, d_qkv (set 1), then of set 2
   hipEvent_t side_tail = nullptr;
   int ensure_side_stream();
   void release_side_stream();

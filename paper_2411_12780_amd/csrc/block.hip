@@ -165,6 +165,8 @@ size_t Block::plan(char* base) {
     head_mean = bump.floats(B); head_rstd = bump.floats(B);
     gA = bump.take(M * D * esz); gB = bump.take(M * D * esz); d_u = bump.take(M * D * esz);
     d_h = bump.take(M * F * esz); d_qkv = bump.take(M * 3 * D * esz);
+    gA2 = bump.take(M * D * esz); gB2 = bump.take(M * D * esz);
+    d_h2 = bump.take(M * F * esz); d_qkv2 = bump.take(M * 3 * D * esz);
     if (dt == BF16) {
       const size_t cand[] = {gemm_mfma_partial_floats(D, 3 * D, (int)M), gemm_mfma_partial_floats(D, D, (int)M),
                              gemm_mfma_partial_floats(D, F, (int)M), gemm_mfma_partial_floats(F, D, (int)M),
@@ -298,7 +300,12 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
   };
   // dW[in,out] = X^T dY and db = column sums of dY, reduction over the M rows.  `slot` names the
   // buffer dY lives in (0 gA, 1 d_h, 2 gB, 3 d_qkv).  With the fused MFMA kernel the product goes
-  // to the second stream; the buffer's next writer waits for it (before_write below).
+  // to the second stream; the buffer's next writer waits for it (before_write below).  Odd and even
+  // layers use different sets of these buffers, so that wait is for a product queued a whole layer
+  // earlier and the main stream rarely stalls on it.
+  const int set = l & 1;
+  void* d_h = set ? this->d_h2 : this->d_h;
+  void* d_qkv = set ? this->d_qkv2 : this->d_qkv;
   auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off, size_t b_off,
                    int slot) -> int {
     GemmArgs g = gemm_args();
@@ -314,7 +321,7 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
       PPLL_HIP(hipStreamWaitEvent(side, ev_fork[i], 0));
       PPLL_TRY(launch_gemm(side, g));
       PPLL_HIP(hipEventRecord(ev_done[i], side));
-      pending[slot] = ev_done[i];
+      pending[slot + 4 * set] = ev_done[i];
       side_tail = ev_done[i];
       return (int)PPLL_OK;
     }
@@ -322,29 +329,30 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
     return fused ? (int)PPLL_OK : launch_colsum(s, dy, dt, M, out_dim, rq, grads + b_off);
   };
   auto before_write = [&](int slot) -> int {
-    if (pending[slot]) {
-      PPLL_HIP(hipStreamWaitEvent(s, pending[slot], 0));
-      pending[slot] = nullptr;
+    hipEvent_t& e = pending[slot];
+    if (e) {
+      PPLL_HIP(hipStreamWaitEvent(s, e, 0));
+      e = nullptr;
     }
     return (int)PPLL_OK;
   };
   GemmArgs g = dgrad(g_in, D, p.fc2_w, F, d_h);
   g.epilogue = EPI_DGELU; g.aux = a.h; g.aux_dt = dt; g.ldaux = F;
-  PPLL_TRY(before_write(1));
+  PPLL_TRY(before_write(1 + 4 * set));
   PPLL_TRY(launch_gemm(s, g));
   PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w, p.fc2_b, 0));
   PPLL_TRY(launch_gemm(s, dgrad(d_h, F, p.fc1_w, D, d_u)));
   PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w, p.fc1_b, 1));
-  PPLL_TRY(before_write(2));
+  PPLL_TRY(before_write(2 + 4 * set));
   PPLL_TRY(launch_layernorm_bwd(s, d_u, a.x1, dt, D, M, D, params + p.ln2_g, a.mean2, a.rstd2, g_in, g_tmp, rq,
                                 grads + p.ln2_g, grads + p.ln2_b));
   PPLL_TRY(launch_gemm(s, dgrad(g_tmp, D, p.proj_w, D, d_u)));
   PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w, p.proj_b, 2));
-  PPLL_TRY(before_write(3));
+  PPLL_TRY(before_write(3 + 4 * set));
   PPLL_TRY(launch_attention_bwd(s, a.qkv, a.att, d_u, a.lse, dt, cfg.batch, T, H, D / H, d_qkv));
   PPLL_TRY(launch_gemm(s, dgrad(d_qkv, 3 * D, p.qkv_w, D, d_u)));
   PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b, 3));
-  PPLL_TRY(before_write(0));
+  PPLL_TRY(before_write(0 + 4 * (set ^ 1)));   // g_out is the other set's gA
   return launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, g_tmp,
                               need_dx ? g_out : nullptr, rq, grads + p.ln1_g, grads + p.ln1_b);
 }
@@ -404,11 +412,14 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   PPLL_TRY(launch_gemm_generic(s, g));
   PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
                                 rq, grads + head_ln_g, grads + head_ln_b));
-  PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, gA));
+  // layer l takes its output gradient in set l%2's gA, its mid-layer gradient in that set's gB, and
+  // leaves its input gradient in the other set's gA
+  auto g_of = [&](int l) { return (l & 1) ? gA2 : gA; };
+  PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, g_of(L + A - 1)));
   // ---- backward: auxiliary layers then module layers; the chain stops at x_in
   for (int l = L + A - 1; l >= 0; --l) {
     bool need_dx = l > 0 || image;
-    PPLL_TRY(encoder_bwd(l, layer_in[l], gA, gB, gA, need_dx, s));
+    PPLL_TRY(encoder_bwd(l, layer_in[l], g_of(l), (l & 1) ? gB2 : gB, g_of(l - 1), need_dx, s));
   }
   if (side_tail) {   // every weight gradient is in place (and the split-K scratch free) from here on
     PPLL_HIP(hipStreamWaitEvent(s, side_tail, 0));
@@ -416,7 +427,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     for (hipEvent_t& e : pending) e = nullptr;
   }
   if (image) {
-    PPLL_TRY(launch_embed_bwd(s, gA, dt, B, T, D, rq, grads + pos, grads + cls, embed_tmp));
+    PPLL_TRY(launch_embed_bwd(s, g_of(-1), dt, B, T, D, rq, grads + pos, grads + cls, embed_tmp));
     if (T > 1) {
       g = gemm_args();
       g.A = patches; g.a_dt = dt; g.a_sm = 1; g.a_sk = ppc;
