@@ -36,11 +36,12 @@ void set_error(const char* fmt, ...);
 #ifdef __HIPCC__
 // bf16 <-> fp32 by bit manipulation, round to nearest even.
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// float -> bf16, round to nearest even: gfx950's v_cvt_pk_bf16_f32 (one instruction for two values)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  const bf16x2_t v = {(__bf16)lo, (__bf16)hi};
+  return __builtin_bit_cast(uint32_t, v);
 }
 __device__ __forceinline__ float ld_f(const void* p, size_t i, int dt) {
   return dt == BF16 ? bf16_to_f32(((const uint16_t*)p)[i]) : ((const float*)p)[i];

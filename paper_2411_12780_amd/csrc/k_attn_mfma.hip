@@ -41,9 +41,7 @@ __device__ __forceinline__ bf16x8 ld_frag(const uint16_t* p, bool ok) {
   if (ok) v = *reinterpret_cast<const uint4*>(p);
   return __builtin_bit_cast(bf16x8, v);
 }
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 __device__ __forceinline__ bf16x8 pack8(const float* v) {
   uint4 u = make_uint4(pack2(v[0], v[1]), pack2(v[2], v[3]), pack2(v[4], v[5]), pack2(v[6], v[7]));
   return __builtin_bit_cast(bf16x8, u);

@@ -71,9 +71,7 @@ __device__ __forceinline__ void cdf_pdf(float h, float& cdf, float& pdf) {
 }
 __device__ __forceinline__ float gelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return h * c; }
 __device__ __forceinline__ float dgelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return c + h * d; }
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
 __device__ __forceinline__ int lds_off(int row, int granule16) {
   return row * ROW_BYTES + ((granule16 ^ ((row >> 4) & 7)) << 4);

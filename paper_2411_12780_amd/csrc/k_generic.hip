@@ -318,9 +318,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const void* dy, cons
 namespace {
 __device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-__device__ __forceinline__ uint32_t pack_bf(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
-}
+__device__ __forceinline__ uint32_t pack_bf(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
 template <int NJ>
 __global__ __launch_bounds__(256) void layernorm_fwd_bf16_kernel(const uint16_t* x, long xs, int rows,
