@@ -434,8 +434,10 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
       g.B = embed_tmp; g.b_dt = dt; g.b_sk = D; g.b_sn = 1;
       g.C = grads + pe_w; g.c_dt = F32; g.ldc = D; g.M = ppc; g.N = D; g.K = B * (T - 1);
       g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
+      g.colsum = grads + pe_b;   // bias gradient: column sums of dE, folded into the product when the MFMA kernel takes it
+      const bool fused = gemm_fuses_colsum(g);
       PPLL_TRY(launch_gemm(s, g));
-      PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, rq, grads + pe_b));
+      if (!fused) PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, rq, grads + pe_b));
     } else {
       PPLL_TRY(launch_fill_zero(s, grads + pe_w, ((size_t)ppc * D + D) * sizeof(float)));
     }

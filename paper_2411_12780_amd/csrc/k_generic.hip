@@ -320,108 +320,152 @@ __device__ __forceinline__ float lo_bf(uint32_t w) { return __uint_as_float(w <<
 __device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ uint32_t pack_bf(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
+// Fast bf16 LayerNorm.  A row of D = 128 NJ elements is held by LPR lanes (16 for D <= 384, 32 up
+// to 768, 64 for 1024), 8 consecutive elements (one 16-byte access) per lane and 8 LPR-column step,
+// so a wave works on 64 / LPR rows at once and the row sums are exchanges inside a lane group.
+template <int NJ> struct LnShape {
+  static constexpr int D = NJ * 128;
+  static constexpr int LPR = NJ <= 3 ? 16 : (NJ <= 6 ? 32 : 64);
+  static constexpr int NV = D / (8 * LPR);       // 16-byte pieces per lane and row
+  static constexpr int RPW = 64 / LPR;           // rows per wave and pass
+};
+template <int LPR>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int o = LPR / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ void unpack8(const uint4& w, float* v) {
+  v[0] = lo_bf(w.x); v[1] = hi_bf(w.x); v[2] = lo_bf(w.y); v[3] = hi_bf(w.y);
+  v[4] = lo_bf(w.z); v[5] = hi_bf(w.z); v[6] = lo_bf(w.w); v[7] = hi_bf(w.w);
+}
+
 template <int NJ>
 __global__ __launch_bounds__(256) void layernorm_fwd_bf16_kernel(const uint16_t* x, long xs, int rows,
                                                                  const float* g, const float* b, float eps,
                                                                  uint16_t* y, float* mean, float* rstd) {
-  constexpr int D = NJ * 128;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (row >= rows) return;
-  const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + (size_t)row * xs);
-  float v[2 * NJ];
+  using S = LnShape<NJ>;
+  constexpr int D = S::D, LPR = S::LPR, NV = S::NV, RPW = S::RPW;
+  const int lane = threadIdx.x & 63, lr = lane % LPR;
+  const int row = (blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW + lane / LPR;
+  const bool ok = row < rows;
+  float v[8 * NV];
   float s = 0.f;
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    uint32_t w = xr[lane + 64 * j];
-    v[2 * j] = lo_bf(w); v[2 * j + 1] = hi_bf(w);
-    s += v[2 * j] + v[2 * j + 1];
+  for (int j = 0; j < NV; ++j) {
+    uint4 w = make_uint4(0, 0, 0, 0);
+    if (ok) w = *reinterpret_cast<const uint4*>(x + (size_t)row * xs + 8 * lr + 8 * LPR * j);
+    unpack8(w, v + 8 * j);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) s += v[8 * j + e];
   }
-  const float mu = wave_sum(s) * (1.0f / D);
+  const float mu = group_sum<LPR>(s) * (1.0f / D);
   float q = 0.f;
 #pragma unroll
-  for (int j = 0; j < 2 * NJ; ++j) { v[j] -= mu; q += v[j] * v[j]; }
-  const float rs = rsqrtf(wave_sum(q) * (1.0f / D) + eps);
-  uint32_t* yr = reinterpret_cast<uint32_t*>(y + (size_t)row * D);
+  for (int j = 0; j < 8 * NV; ++j) { v[j] -= mu; q += v[j] * v[j]; }
+  const float rs = rsqrtf(group_sum<LPR>(q) * (1.0f / D) + eps);
+  if (!ok) return;
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int c = 2 * lane + 128 * j;
-    float2 gg = *reinterpret_cast<const float2*>(g + c), bb = *reinterpret_cast<const float2*>(b + c);
-    yr[lane + 64 * j] = pack_bf(v[2 * j] * rs * gg.x + bb.x, v[2 * j + 1] * rs * gg.y + bb.y);
+  for (int j = 0; j < NV; ++j) {
+    const int c = 8 * lr + 8 * LPR * j;
+    const float4 g0 = *reinterpret_cast<const float4*>(g + c), g1 = *reinterpret_cast<const float4*>(g + c + 4);
+    const float4 b0 = *reinterpret_cast<const float4*>(b + c), b1 = *reinterpret_cast<const float4*>(b + c + 4);
+    const float* t = v + 8 * j;
+    uint4 o;
+    o.x = pack_bf(t[0] * rs * g0.x + b0.x, t[1] * rs * g0.y + b0.y);
+    o.y = pack_bf(t[2] * rs * g0.z + b0.z, t[3] * rs * g0.w + b0.w);
+    o.z = pack_bf(t[4] * rs * g1.x + b1.x, t[5] * rs * g1.y + b1.y);
+    o.w = pack_bf(t[6] * rs * g1.z + b1.z, t[7] * rs * g1.w + b1.w);
+    *reinterpret_cast<uint4*>(y + (size_t)row * D + c) = o;
   }
-  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  if (lr == 0) { mean[row] = mu; rstd[row] = rs; }
 }
 
-constexpr int LNF_ROWS = 32;   // rows per workgroup in the fast backward (4 waves x 4 pairs)
+constexpr int LNF_ROWS = 32;   // rows per workgroup (and per partial of dg, db) in the fast backward
 template <int NJ>
 __global__ __launch_bounds__(256) void layernorm_bwd_bf16_kernel(const uint16_t* dy, const uint16_t* x, long xs,
                                                                  int rows, const float* g, const float* mean,
                                                                  const float* rstd, const uint16_t* dres,
                                                                  uint16_t* dx, float* partial) {
-  constexpr int D = NJ * 128;
+  using S = LnShape<NJ>;
+  constexpr int D = S::D, LPR = S::LPR, NV = S::NV, RPW = S::RPW;
   __shared__ float sm[4][2 * D];
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  float gg[2 * NJ], adg[2 * NJ], adb[2 * NJ];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lr = lane % LPR, sub = lane / LPR;
+  float gg[8 * NV], adg[8 * NV], adb[8 * NV];
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    float2 t = *reinterpret_cast<const float2*>(g + 2 * lane + 128 * j);
-    gg[2 * j] = t.x; gg[2 * j + 1] = t.y;
+  for (int j = 0; j < NV; ++j) {
+    const int c = 8 * lr + 8 * LPR * j;
+    const float4 g0 = *reinterpret_cast<const float4*>(g + c), g1 = *reinterpret_cast<const float4*>(g + c + 4);
+    gg[8 * j] = g0.x; gg[8 * j + 1] = g0.y; gg[8 * j + 2] = g0.z; gg[8 * j + 3] = g0.w;
+    gg[8 * j + 4] = g1.x; gg[8 * j + 5] = g1.y; gg[8 * j + 6] = g1.z; gg[8 * j + 7] = g1.w;
   }
 #pragma unroll
-  for (int j = 0; j < 2 * NJ; ++j) { adg[j] = 0.f; adb[j] = 0.f; }
+  for (int j = 0; j < 8 * NV; ++j) { adg[j] = 0.f; adb[j] = 0.f; }
   const int r0 = blockIdx.x * LNF_ROWS;
-  // two rows per pass so that their loads are in flight together
-  for (int rr = 2 * wave; rr < LNF_ROWS; rr += 8) {
-    uint32_t wx[2][NJ], wd[2][NJ], wr[2][NJ];
-    float mu[2], rs[2];
-    bool ok[2];
+  // a wave takes RPW rows per pass; the rows of a workgroup are summed in the same order whatever
+  // the grid: pass by pass inside a lane group, then across lane groups, then across waves
+  for (int rr = wave * RPW + sub; rr < LNF_ROWS; rr += 4 * RPW) {
+    const int row = r0 + rr;
+    const bool ok = row < rows;
+    uint4 wx[NV], wd[NV], wr[NV];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int row = r0 + rr + u;
-      ok[u] = row < rows;
-      mu[u] = ok[u] ? mean[row] : 0.f; rs[u] = ok[u] ? rstd[row] : 0.f;
-      const uint32_t* xr = reinterpret_cast<const uint32_t*>(x + (size_t)row * xs);
-      const uint32_t* dyr = reinterpret_cast<const uint32_t*>(dy + (size_t)row * D);
-      const uint32_t* rr_ = reinterpret_cast<const uint32_t*>(dres + (size_t)row * D);
-#pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        wx[u][j] = ok[u] ? xr[lane + 64 * j] : 0u;
-        wd[u][j] = ok[u] ? dyr[lane + 64 * j] : 0u;
-        wr[u][j] = (ok[u] && dres) ? rr_[lane + 64 * j] : 0u;
+    for (int j = 0; j < NV; ++j) {
+      const int c = 8 * lr + 8 * LPR * j;
+      wx[j] = wd[j] = wr[j] = make_uint4(0, 0, 0, 0);
+      if (ok) {
+        wx[j] = *reinterpret_cast<const uint4*>(x + (size_t)row * xs + c);
+        wd[j] = *reinterpret_cast<const uint4*>(dy + (size_t)row * D + c);
+        if (dres) wr[j] = *reinterpret_cast<const uint4*>(dres + (size_t)row * D + c);
       }
     }
+    const float mu = ok ? mean[row] : 0.f, rs = ok ? rstd[row] : 0.f;
+    float xh[8 * NV], dyh[8 * NV];
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      if (!ok[u]) continue;
-      const int row = r0 + rr + u;
-      float xh[2 * NJ], dyh[2 * NJ];
-      float s1 = 0.f, s2 = 0.f;
+    for (int j = 0; j < NV; ++j) {
+      float xv[8], dv[8];
+      unpack8(wx[j], xv);
+      unpack8(wd[j], dv);
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) {
-        float d0 = lo_bf(wd[u][j]), d1 = hi_bf(wd[u][j]);
-        xh[2 * j] = (lo_bf(wx[u][j]) - mu[u]) * rs[u]; xh[2 * j + 1] = (hi_bf(wx[u][j]) - mu[u]) * rs[u];
-        adg[2 * j] += d0 * xh[2 * j]; adg[2 * j + 1] += d1 * xh[2 * j + 1];
-        adb[2 * j] += d0; adb[2 * j + 1] += d1;
-        dyh[2 * j] = d0 * gg[2 * j]; dyh[2 * j + 1] = d1 * gg[2 * j + 1];
-        s1 += dyh[2 * j] + dyh[2 * j + 1];
-        s2 += dyh[2 * j] * xh[2 * j] + dyh[2 * j + 1] * xh[2 * j + 1];
+      for (int e = 0; e < 8; ++e) {
+        const int i = 8 * j + e;
+        xh[i] = ok ? (xv[e] - mu) * rs : 0.f;
+        adg[i] += dv[e] * xh[i];
+        adb[i] += dv[e];
+        dyh[i] = dv[e] * gg[i];
+        s1 += dyh[i];
+        s2 += dyh[i] * xh[i];
       }
-      s1 = wave_sum(s1) * (1.0f / D); s2 = wave_sum(s2) * (1.0f / D);
-      if (dx) {
-        uint32_t* dxr = reinterpret_cast<uint32_t*>(dx + (size_t)row * D);
+    }
+    s1 = group_sum<LPR>(s1) * (1.0f / D);
+    s2 = group_sum<LPR>(s2) * (1.0f / D);
+    if (dx && ok) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-          float a = rs[u] * (dyh[2 * j] - s1 - xh[2 * j] * s2), c = rs[u] * (dyh[2 * j + 1] - s1 - xh[2 * j + 1] * s2);
-          if (dres) { a += lo_bf(wr[u][j]); c += hi_bf(wr[u][j]); }
-          dxr[lane + 64 * j] = pack_bf(a, c);
-        }
+      for (int j = 0; j < NV; ++j) {
+        float o[8], rv[8];
+        unpack8(wr[j], rv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = rs * (dyh[8 * j + e] - s1 - xh[8 * j + e] * s2) + rv[e];
+        *reinterpret_cast<uint4*>(dx + (size_t)row * D + 8 * lr + 8 * LPR * j) =
+            make_uint4(pack_bf(o[0], o[1]), pack_bf(o[2], o[3]), pack_bf(o[4], o[5]), pack_bf(o[6], o[7]));
       }
     }
   }
+  // lane groups of a wave hold the same columns: fold them, then the four waves through LDS
 #pragma unroll
-  for (int j = 0; j < NJ; ++j) {
-    const int c = 2 * lane + 128 * j;
-    sm[wave][c] = adg[2 * j]; sm[wave][c + 1] = adg[2 * j + 1];
-    sm[wave][D + c] = adb[2 * j]; sm[wave][D + c + 1] = adb[2 * j + 1];
+  for (int i = 0; i < 8 * NV; ++i) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) { adg[i] += __shfl_xor(adg[i], o, 64); adb[i] += __shfl_xor(adb[i], o, 64); }
+  }
+  if (sub == 0) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int c = 8 * lr + 8 * LPR * j + e;
+        sm[wave][c] = adg[8 * j + e];
+        sm[wave][D + c] = adb[8 * j + e];
+      }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < 2 * D; i += 256)
@@ -431,7 +475,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_bf16_kernel(const uint16_t*
 bool ln_fast_ok(int dt, int D, long xs, const void* a, const void* b, const void* c, const void* d) {
   if (dt != BF16 || (xs & 1)) return false;
   if (!(D == 128 || D == 256 || D == 384 || D == 512 || D == 768 || D == 1024)) return false;
-  return !((((uintptr_t)a) | ((uintptr_t)b) | ((uintptr_t)c) | ((uintptr_t)d)) & 7);
+  return !(xs & 7) && !((((uintptr_t)a) | ((uintptr_t)b) | ((uintptr_t)c) | ((uintptr_t)d)) & 15);
 }
 }  // namespace
 
@@ -448,7 +492,8 @@ bool ln_fast_ok(int dt, int D, long xs, const void* a, const void* b, const void
 int launch_layernorm_fwd(hipStream_t s, const void* x, int dt, long xs, int rows, int D, const float* g,
                          const float* b, float eps, void* y, float* mean, float* rstd) {
   if (ln_fast_ok(dt, D, xs, x, y, g, b)) {
-    LN_DISPATCH(D / 128, hipLaunchKernelGGL((layernorm_fwd_bf16_kernel<NJ>), dim3((rows + 3) / 4), dim3(256), 0, s,
+    LN_DISPATCH(D / 128, hipLaunchKernelGGL((layernorm_fwd_bf16_kernel<NJ>),
+                                            dim3((rows + 4 * LnShape<NJ>::RPW - 1) / (4 * LnShape<NJ>::RPW)), dim3(256), 0, s,
                                             (const uint16_t*)x, xs, rows, g, b, eps, (uint16_t*)y, mean, rstd));
   } else {
     hipLaunchKernelGGL(layernorm_fwd_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, x, dt, xs, rows, D, g, b, eps, y,
@@ -464,7 +509,7 @@ int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, l
                          const float* g, const float* mean, const float* rstd, const void* dres, void* dx_out,
                          ReduceQueue& rq, float* dg, float* db) {
   int chunks;
-  const bool fast = ln_fast_ok(dt, D, xs, x, dy, dres, dx_out) && !(((uintptr_t)g) & 7);
+  const bool fast = ln_fast_ok(dt, D, xs, x, dy, dres, dx_out) && !(((uintptr_t)g) & 15);
   bool queued;
   float* partials = rq.space((size_t)((rows + (fast ? LNF_ROWS : LN_ROWS) - 1) / (fast ? LNF_ROWS : LN_ROWS)) * 2 * D, &queued);
   if (fast) {
@@ -547,6 +592,40 @@ __global__ __launch_bounds__(256) void assemble_tokens_kernel(const void* E, int
   st_f(x0, i, v + pos[(size_t)t * D + d], dt);
 }
 
+// bf16, D a multiple of 8: 8 elements per thread
+__global__ __launch_bounds__(256) void assemble_tokens_bf16_kernel(const uint16_t* E, const float* cls, const float* pos,
+                                                                   int B, int T, int D, uint16_t* x0) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= (size_t)B * T * D) return;
+  const int d = i % D, t = (i / D) % T;
+  const int b = i / ((size_t)D * T);
+  float v[8];
+  if (t == 0) {
+    const float4 c0 = *reinterpret_cast<const float4*>(cls + d), c1 = *reinterpret_cast<const float4*>(cls + d + 4);
+    v[0] = c0.x; v[1] = c0.y; v[2] = c0.z; v[3] = c0.w; v[4] = c1.x; v[5] = c1.y; v[6] = c1.z; v[7] = c1.w;
+  } else {
+    const uint4 w = *reinterpret_cast<const uint4*>(E + ((size_t)b * (T - 1) + (t - 1)) * D + d);
+    v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xffff0000u);
+    v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xffff0000u);
+    v[4] = __uint_as_float(w.z << 16); v[5] = __uint_as_float(w.z & 0xffff0000u);
+    v[6] = __uint_as_float(w.w << 16); v[7] = __uint_as_float(w.w & 0xffff0000u);
+  }
+  const float4 p0 = *reinterpret_cast<const float4*>(pos + (size_t)t * D + d);
+  const float4 p1 = *reinterpret_cast<const float4*>(pos + (size_t)t * D + d + 4);
+  *reinterpret_cast<uint4*>(x0 + i) =
+      make_uint4(f32x2_to_bf16x2(v[0] + p0.x, v[1] + p0.y), f32x2_to_bf16x2(v[2] + p0.z, v[3] + p0.w),
+                 f32x2_to_bf16x2(v[4] + p1.x, v[5] + p1.y), f32x2_to_bf16x2(v[6] + p1.z, v[7] + p1.w));
+}
+__global__ __launch_bounds__(256) void scatter_cls_bf16_kernel(const uint16_t* dcls, int B, int T, int D, uint16_t* dx) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= (size_t)B * T * D) return;
+  const int d = i % D, t = (i / D) % T;
+  const int b = i / ((size_t)D * T);
+  uint4 w = make_uint4(0, 0, 0, 0);
+  if (t == 0) w = *reinterpret_cast<const uint4*>(dcls + (size_t)b * D + d);
+  *reinterpret_cast<uint4*>(dx + i) = w;
+}
+
 constexpr int EMB_ROWS = 8;   // batch entries per partial
 // partial[c][t,d] = sum over the chunk's batch entries of dx[b,t,d]; dE = dx[:,1:,:] gathered
 __global__ __launch_bounds__(256) void embed_bwd_kernel(const void* dx, int dt, int B, int T, int D, float* partial,
@@ -585,7 +664,13 @@ int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W,
 int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cls, const float* pos, int B, int T,
                            int D, void* x0) {
   size_t total = (size_t)B * T * D;
-  hipLaunchKernelGGL(assemble_tokens_kernel, dim3((total + 255) / 256), dim3(256), 0, s, E, dt, cls, pos, B, T, D, x0);
+  const bool vec = dt == BF16 && !(D & 7) &&
+                   !((((uintptr_t)E) | ((uintptr_t)cls) | ((uintptr_t)pos) | ((uintptr_t)x0)) & 15);
+  if (vec)
+    hipLaunchKernelGGL(assemble_tokens_bf16_kernel, dim3((total / 8 + 255) / 256), dim3(256), 0, s, (const uint16_t*)E,
+                       cls, pos, B, T, D, (uint16_t*)x0);
+  else
+    hipLaunchKernelGGL(assemble_tokens_kernel, dim3((total + 255) / 256), dim3(256), 0, s, E, dt, cls, pos, B, T, D, x0);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
@@ -602,7 +687,11 @@ int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D,
 }
 int launch_scatter_cls(hipStream_t s, const void* dcls, int dt, int B, int T, int D, void* dx) {
   size_t total = (size_t)B * T * D;
-  hipLaunchKernelGGL(scatter_cls_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dcls, dt, B, T, D, dx);
+  if (dt == BF16 && !(D & 7) && !((((uintptr_t)dcls) | ((uintptr_t)dx)) & 15))
+    hipLaunchKernelGGL(scatter_cls_bf16_kernel, dim3((total / 8 + 255) / 256), dim3(256), 0, s, (const uint16_t*)dcls, B,
+                       T, D, (uint16_t*)dx);
+  else
+    hipLaunchKernelGGL(scatter_cls_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dcls, dt, B, T, D, dx);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
