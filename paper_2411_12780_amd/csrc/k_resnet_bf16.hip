@@ -206,27 +206,43 @@ __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
     for (int j = 0; j < 8; ++j) { mu[j] = p.mean[8 * cg + j]; rs[j] = p.rstd[8 * cg + j]; }
   }
   if (rl < lanes) {
-    for (int r = blockIdx.x * lanes + rl; r < p.rows; r += gridDim.x * lanes) {
-      const size_t off = (size_t)r * p.C + 8 * cg;
-      const uint4 xv = *reinterpret_cast<const uint4*>(p.x + off);
-      const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
-      if (KIND == 0) {
+    // four rows per trip, their loads issued together; the sums of a lane still run in row order
+    const int stride = gridDim.x * lanes;
+    for (int r = blockIdx.x * lanes + rl; r < p.rows; r += 4 * stride) {
+      uint4 xv[4], dv[4], yv[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float u = lo_bf(xw[j]), v = hi_bf(xw[j]);
-          a0[2 * j] += u; a0[2 * j + 1] += v; a1[2 * j] += u * u; a1[2 * j + 1] += v * v;
+      for (int u = 0; u < 4; ++u) {
+        const int ru = r + u * stride;
+        xv[u] = dv[u] = yv[u] = make_uint4(0, 0, 0, 0);
+        if (ru < p.rows) {
+          const size_t off = (size_t)ru * p.C + 8 * cg;
+          xv[u] = *reinterpret_cast<const uint4*>(p.x + off);
+          if (KIND == 1) {
+            dv[u] = *reinterpret_cast<const uint4*>(p.dy + off);
+            yv[u] = *reinterpret_cast<const uint4*>(p.y + off);
+          }
         }
-      } else {
-        const uint4 dv = *reinterpret_cast<const uint4*>(p.dy + off);
-        const uint4 yv = *reinterpret_cast<const uint4*>(p.y + off);
-        const uint32_t* dw = reinterpret_cast<const uint32_t*>(&dv);
-        const uint32_t* yw = reinterpret_cast<const uint32_t*>(&yv);
+      }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float d0 = lo_bf(yw[j]) > 0.f ? lo_bf(dw[j]) : 0.f, d1 = hi_bf(yw[j]) > 0.f ? hi_bf(dw[j]) : 0.f;
-          a0[2 * j] += d0; a0[2 * j + 1] += d1;
-          a1[2 * j] += d0 * (lo_bf(xw[j]) - mu[2 * j]) * rs[2 * j];
-          a1[2 * j + 1] += d1 * (hi_bf(xw[j]) - mu[2 * j + 1]) * rs[2 * j + 1];
+      for (int u = 0; u < 4; ++u) {
+        if (r + u * stride >= p.rows) break;
+        const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv[u]);
+        if (KIND == 0) {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float a = lo_bf(xw[j]), b = hi_bf(xw[j]);
+            a0[2 * j] += a; a0[2 * j + 1] += b; a1[2 * j] += a * a; a1[2 * j + 1] += b * b;
+          }
+        } else {
+          const uint32_t* dw = reinterpret_cast<const uint32_t*>(&dv[u]);
+          const uint32_t* yw = reinterpret_cast<const uint32_t*>(&yv[u]);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float d0 = lo_bf(yw[j]) > 0.f ? lo_bf(dw[j]) : 0.f, d1 = hi_bf(yw[j]) > 0.f ? hi_bf(dw[j]) : 0.f;
+            a0[2 * j] += d0; a0[2 * j + 1] += d1;
+            a1[2 * j] += d0 * (lo_bf(xw[j]) - mu[2 * j]) * rs[2 * j];
+            a1[2 * j + 1] += d1 * (hi_bf(xw[j]) - mu[2 * j + 1]) * rs[2 * j + 1];
+          }
         }
       }
     }
@@ -238,6 +254,7 @@ __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
   if (tid < 2 * p.C) {
     const int which = tid / p.C, c = tid % p.C, g = c / 8, j = c % 8;
     float t = 0.f;
+#pragma unroll 8
     for (int l = 0; l < lanes; ++l) t += red[l * groups + g][8 * which + j];
     p.partial[(size_t)blockIdx.x * 2 * p.C + tid] = t;
   }
@@ -254,7 +271,16 @@ __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
     if (tid < nv * parts) {
       const int v = tid % nv, part = tid / nv;
       float t = 0.f;
-      for (unsigned bk = part; bk < gridDim.x; bk += parts) t += p.partial[(size_t)bk * nv + v];
+      for (unsigned bk = part; bk < gridDim.x; bk += 8 * parts) {   // eight loads in flight; summed in workgroup order
+        float q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const unsigned bu = bk + u * parts;
+          q[u] = bu < gridDim.x ? p.partial[(size_t)bu * nv + v] : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) t += q[u];
+      }
       red[tid][0] = t;
     }
     __syncthreads();
