@@ -393,9 +393,124 @@ bool conv_fwd_bf16_ok(int Ci, int Co) { return Co % 32 == 0 && Co <= 64 && (size
 bool conv_dgrad_bf16_ok(int Ci, int Co) { return Ci % 32 == 0 && Ci <= 64 && (size_t)Ci * (18 * Co + 16) <= 64 * 1024; }
 bool conv_wgrad_bf16_ok(int Ci, int Co) { return (Co == 32 || Co == 64) && Ci % 16 == 0 && Ci >= 16 && Ci <= 64; }
 
+// ---------------------------------------------------------------------------------------------
+// Weight gradient on the matrix cores for 32 -> 32 channels, stride 1, 16-pixel image rows:
+// dw[ky][kx][ci][co] = sum over pixels of x[y+ky-1][x+kx-1][ci] * dy[y][x][co].  The reduction
+// index of the MFMA is the pixel, so a 16-wide k-step is exactly one image row and each of the 9
+// taps is one 32 x 32 accumulator tile.  A workgroup takes one image at a time: both tensors are
+// transposed into LDS as [channel][row][16 pixels] (in-register 4 x 8 transposes, as in the GEMM
+// loaders), a lane's operand fragment is then one aligned 16-byte read (8 consecutive pixels of
+// its channel), and the +-1 pixel shifts of the kx = 0 / 2 taps are made in registers from that
+// read and one value taken from the lane holding the other half of the row (zero at the image
+// border).  The 9 taps are dealt to the 4 waves (3, 2, 2, 2), each wave keeps its taps'
+// accumulators over all images of the workgroup, and the workgroups' tiles are added by the
+// ordered second-stage reduction.
+typedef __attribute__((ext_vector_type(8))) __bf16 wg_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float wg_f32x16;
+constexpr int WGM_C = 32, WGM_W = 16;
+__global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_kernel(const uint16_t* __restrict__ x,
+                                                                 const uint16_t* __restrict__ dy, int B, int H,
+                                                                 float* __restrict__ partial) {
+  extern __shared__ __align__(16) char sm[];
+  const int CS = H * WGM_W * 2 + 16;          // bytes between channels of a transposed tile (+16: spreads the banks)
+  char* xt = sm;                              // x  as [32 channels][H rows][16 pixels]
+  char* dt = sm + WGM_C * CS;                 // dy likewise
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c = lane & 31, h = lane >> 5;
+  wg_f32x16 acc[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+  const int items = H * 4 * 4;                // (row, group of 4 pixels, group of 8 channels)
+  for (int b = blockIdx.x; b < B; b += gridDim.x) {
+    const uint16_t* xb = x + (size_t)b * H * WGM_W * WGM_C;
+    const uint16_t* db = dy + (size_t)b * H * WGM_W * WGM_C;
+    __syncthreads();                          // the previous image's tiles are no longer read
+    for (int item = tid; item < items; item += 256) {
+      const int cg = item & 3, pg = item >> 2, y = pg >> 2, x0 = (pg & 3) * 4;
+      uint4 rx[4], rd[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const size_t off = ((size_t)(y * WGM_W + x0 + j)) * WGM_C + 8 * cg;
+        rx[j] = *reinterpret_cast<const uint4*>(xb + off);
+        rd[j] = *reinterpret_cast<const uint4*>(db + off);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        const int o = (8 * cg + i) * CS + y * (WGM_W * 2) + x0 * 2;
+        uint2 ox, od;
+        ox.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[0])[i >> 1], sel);
+        ox.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[2])[i >> 1], sel);
+        od.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[0])[i >> 1], sel);
+        od.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[2])[i >> 1], sel);
+        *reinterpret_cast<uint2*>(xt + o) = ox;
+        *reinterpret_cast<uint2*>(dt + o) = od;
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const int tap = wave + 4 * j;           // wave-uniform
+      if (tap < 9) {
+        const int ky = tap / 3, kx = tap % 3;
+        for (int y = 0; y < H; ++y) {
+          const int yi = y + ky - 1;
+          if (yi < 0 || yi >= H) continue;
+          const uint4 w = *reinterpret_cast<const uint4*>(xt + c * CS + yi * (WGM_W * 2) + h * 16);
+          const uint4 g = *reinterpret_cast<const uint4*>(dt + c * CS + y * (WGM_W * 2) + h * 16);
+          uint4 a = w;
+          if (kx != 1) {
+            // the pixel next to this lane's 8: the last of the lower half for h = 1, the first of the upper half for h = 0
+            const uint32_t other = (uint32_t)__shfl_xor((int)(h ? w.x : w.w), 32, 64);
+            if (kx == 0) {       // pixels x-1
+              const uint32_t prev = h ? (other >> 16) : 0u;
+              a.x = (w.x << 16) | prev;
+              a.y = __builtin_amdgcn_alignbyte(w.y, w.x, 2);
+              a.z = __builtin_amdgcn_alignbyte(w.z, w.y, 2);
+              a.w = __builtin_amdgcn_alignbyte(w.w, w.z, 2);
+            } else {             // pixels x+1
+              const uint32_t next = h ? 0u : (other & 0xffffu);
+              a.x = __builtin_amdgcn_alignbyte(w.y, w.x, 2);
+              a.y = __builtin_amdgcn_alignbyte(w.z, w.y, 2);
+              a.z = __builtin_amdgcn_alignbyte(w.w, w.z, 2);
+              a.w = (next << 16) | (w.w >> 16);
+            }
+          }
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(wg_bf16x8, a), __builtin_bit_cast(wg_bf16x8, g),
+                                                           acc[j], 0, 0, 0);
+        }
+      }
+    }
+  }
+  // acc[j][e] = dw[tap][ci = 8 (e/4) + 4 h + e%4][co = c]
+  float* out = partial + (size_t)blockIdx.x * 9 * WGM_C * WGM_C;
+#pragma unroll
+  for (int j = 0; j < 3; ++j) {
+    const int tap = wave + 4 * j;
+    if (tap < 9) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int ci = 8 * (e >> 2) + 4 * h + (e & 3);
+        out[((size_t)tap * WGM_C + ci) * WGM_C + c] = acc[j][e];
+      }
+    }
+  }
+}
+
+static int wgrad_mfma_blocks(int B) { return B < 128 ? B : 128; }
+static bool wgrad_mfma_ok(int H, int W, int Ci, int Co, int stride) {
+  return Ci == WGM_C && Co == WGM_C && W == WGM_W && stride == 1 && H >= 1 && H <= 64;
+}
+
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride) {
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
-  return (size_t)((P + WG_PIX_F - 1) / WG_PIX_F) * 9 * Ci * Co;
+  size_t n = (size_t)((P + WG_PIX_F - 1) / WG_PIX_F) * 9 * Ci * Co;
+  if (wgrad_mfma_ok(H, W, Ci, Co, stride)) {
+    const size_t m = (size_t)wgrad_mfma_blocks(B) * 9 * Ci * Co;
+    if (m > n) n = m;
+  }
+  return n;
 }
 
 template <int CO, int CPT>
@@ -416,6 +531,16 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   const int chunks = (int)((P + WG_PIX_F - 1) / WG_PIX_F), nw = 9 * Ci * Co;
   const int cpt = Ci / (256 / Co);
+  if (wgrad_mfma_ok(H, W, Ci, Co, stride)) {
+    const int blocks = wgrad_mfma_blocks(B);
+    const size_t lds = (size_t)2 * WGM_C * (H * WGM_W * 2 + 16);
+    if (lds > 64 * 1024)
+      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_wgrad_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(conv3x3_wgrad_mfma_kernel, dim3(blocks), dim3(256), lds, s, (const uint16_t*)x, (const uint16_t*)dy, B,
+                       H, partials);
+    PPLL_HIP(hipGetLastError());
+    return reduce_partials(s, partials, blocks, nw, nw, 1.0f, dw);
+  }
   int st = PPLL_ERR_CONFIG;
   if (Co == 32 && cpt == 2) st = wgrad_launch<32, 2>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
   else if (Co == 32 && cpt == 4) st = wgrad_launch<32, 4>(s, x, dy, B, H, W, Ci, stride, partials, chunks);

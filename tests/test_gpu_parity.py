@@ -231,6 +231,13 @@ def test_resnet_bf16_odd_sizes_on_the_mfma_path():
     run_case(wl, steps=1, check_bn=True)
 
 
+def test_resnet_bf16_weight_gradient_on_the_mfma_path_edges():
+    # 16-pixel rows select the matrix-core weight gradient; 131 images make its workgroups loop over
+    # images (128 workgroups), 5 rows give every tap a different set of valid row pairs
+    wl = synth.workload("resnet_stage_bf16", n_basic_blocks=1, batch=131, height=5, width=16)
+    run_case(wl, steps=1, check_bn=True)
+
+
 def test_resnet_bf16_stage_full_size_natural_statistics():
     run_case(synth.workload("resnet_stage_bf16"), steps=2, check_bn=True, grad_tol=0.3)
 
