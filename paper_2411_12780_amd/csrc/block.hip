@@ -223,6 +223,11 @@ size_t Block::plan(char* base) {
     if (!(dt == BF16))   // the generic GEMM does not fold bias gradients: one column sum per Linear layer
       arena_floats += (size_t)(cfg.depth + cfg.aux_depth) * 4 * ((size_t)colsum_partial_floats((int)M, widest) + 64);
   }
+  if (cfg.arch == PPLL_RESNET) {   // the weight-gradient partials of every convolution
+    const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
+    arena_floats = (size_t)2 * cfg.n_basic_blocks * ((size_t)conv3x3_wgrad_partial_floats(cfg.batch, Hh, W, Ch, Ch, 1) + 64) +
+                   (size_t)conv3x3_wgrad_partial_floats(cfg.batch, Hh, W, Ch, A, 2) + 64;
+  }
   rq.arena = arena_floats ? bump.floats(arena_floats) : nullptr;
   rq.arena_floats = arena_floats;
   return (bump.off + 255) & ~(size_t)255;
@@ -499,7 +504,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   PPLL_TRY(launch_gap_bwd(s, dpooled, dt, B, Ho * Wo, A, d_aux));
   PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials, ticket_dev,
                          grads + aux_bn_g, grads + aux_bn_b, d_aux));
-  PPLL_TRY(launch_conv3x3_wgrad(s, x, d_aux, dt, B, H, W, Ch, A, 2, partials, grads + aux_conv_w));
+  PPLL_TRY(launch_conv3x3_wgrad(s, x, d_aux, dt, B, H, W, Ch, A, 2, rq, grads + aux_conv_w));
   PPLL_TRY(launch_conv3x3_dgrad(s, d_aux, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, nullptr, nullptr, r_gA));
   // ---- backward: basic blocks, last to first; nothing is produced for x_in
   for (int i = n - 1; i >= 0; --i) {
@@ -507,11 +512,11 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     BasicBlockActs& a = rb_a[i];
     PPLL_TRY(launch_bn_bwd(s, r_gA, block_out[i], a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, partials, ticket_dev,
                            grads + p.bn2_g, grads + p.bn2_b, r_t2));
-    PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, H, W, Ch, Ch, 1, partials, grads + p.conv2_w));
+    PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, H, W, Ch, Ch, 1, rq, grads + p.conv2_w));
     PPLL_TRY(launch_conv3x3_dgrad(s, r_t2, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, nullptr, nullptr, r_t1));
     PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, partials, ticket_dev,
                            grads + p.bn1_g, grads + p.bn1_b, r_t1));
-    PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, H, W, Ch, Ch, 1, partials, grads + p.conv1_w));
+    PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, H, W, Ch, Ch, 1, rq, grads + p.conv1_w));
     if (i > 0)
       PPLL_TRY(launch_conv3x3_dgrad(s, r_t1, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, r_gA, block_out[i], r_gA));
   }

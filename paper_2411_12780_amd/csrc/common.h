@@ -180,7 +180,7 @@ int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, const void* dres, const void* ymask, void* dx);
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci,
-                         int Co, int stride, float* partials, float* dw);
+                         int Co, int stride, ReduceQueue& rq, float* dw);
 int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
 // training-mode statistics over rows of x [rows, C]; also updates running stats
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum,
@@ -203,7 +203,7 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
                               int stride, const void* dres, const void* ymask, void* dx);
 int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co,
-                              int stride, float* partials, float* dw);
+                              int stride, ReduceQueue& rq, float* dw);
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
 bool bn_bf16_supported(int dt, int C, const void* a, const void* b, const void* c, const void* d);
 size_t bn_bf16_partial_floats(int rows, int C);

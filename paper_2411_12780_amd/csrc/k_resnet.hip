@@ -145,8 +145,36 @@ __global__ __launch_bounds__(256) void gap_fwd_kernel(const void* x, int dt, int
   if (i >= B * C) return;
   int c = i % C, b = i / C;
   float acc = 0.f;
-  for (int p = 0; p < HW; ++p) acc += ld_f(x, ((size_t)b * HW + p) * C + c, dt);
+  for (int p = 0; p < HW; p += 8) {   // eight loads in flight; added in pixel order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p + u < HW ? ld_f(x, ((size_t)b * HW + p + u) * C + c, dt) : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
   st_f(pooled, i, acc / HW, dt);
+}
+
+// one workgroup per image; 256 / C thread groups split the pixels, and are added in group order
+__global__ __launch_bounds__(256) void gap_fwd_image_kernel(const void* x, int dt, int HW, int C, void* pooled) {
+  __shared__ float red[256];
+  const int b = blockIdx.x, c = threadIdx.x % C, g = threadIdx.x / C, G = 256 / C;
+  const int per = (HW + G - 1) / G, p0 = g * per, p1 = min(HW, p0 + per);
+  float acc = 0.f;
+  for (int p = p0; p < p1; p += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = p + u < p1 ? ld_f(x, ((size_t)b * HW + p + u) * C + c, dt) : 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u];
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  if (g == 0) {
+    float t = 0.f;
+    for (int k = 0; k < G; ++k) t += red[k * C + c];
+    st_f(pooled, (size_t)b * C + c, t / HW, dt);
+  }
 }
 
 __global__ __launch_bounds__(256) void gap_bwd_kernel(const void* dpooled, int dt, int B, int HW, int C, void* dx) {
@@ -189,13 +217,15 @@ int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride
   return (int)(a > b ? a : b);
 }
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci, int Co,
-                         int stride, float* partials, float* dw) {
+                         int stride, ReduceQueue& rq, float* dw) {
   if (conv_bf16_supported(dt, BF16, Ci, Co, x, dy, dw) && conv_wgrad_bf16_ok(Ci, Co))
-    return launch_conv3x3_wgrad_bf16(s, x, dy, B, H, W, Ci, Co, stride, partials, dw);
+    return launch_conv3x3_wgrad_bf16(s, x, dy, B, H, W, Ci, Co, stride, rq, dw);
   int chunks = (int)wgrad_chunks(B, H, W, stride), nw = 9 * Ci * Co;
+  bool queued;
+  float* partials = rq.space((size_t)chunks * nw, &queued);
   hipLaunchKernelGGL(conv3x3_wgrad_kernel, dim3(chunks), dim3(256), 0, s, x, dy, dt, B, H, W, Ci, Co, stride, partials);
   PPLL_HIP(hipGetLastError());
-  return reduce_partials(s, partials, chunks, nw, nw, 1.0f, dw);
+  return rq.reduce(s, queued, partials, chunks, nw, nw, 1.0f, dw);
 }
 
 int bn_partial_floats(int rows, int C) {
@@ -251,7 +281,10 @@ int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, i
 }
 
 int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, void* pooled) {
-  hipLaunchKernelGGL(gap_fwd_kernel, dim3((B * C + 255) / 256), dim3(256), 0, s, x, dt, B, HW, C, pooled);
+  if (C <= 256 && 256 % C == 0)
+    hipLaunchKernelGGL(gap_fwd_image_kernel, dim3(B), dim3(256), 0, s, x, dt, HW, C, pooled);
+  else
+    hipLaunchKernelGGL(gap_fwd_kernel, dim3((B * C + 255) / 256), dim3(256), 0, s, x, dt, B, HW, C, pooled);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }

@@ -42,11 +42,32 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   const int RSW = 18 * KC + 16;
   const int Ho = out_dim(p.H, p.stride), Wo = out_dim(p.W, p.stride);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
-  // filter -> LDS as [produced channel][tap*KC + reduced channel]
-  for (int e = tid; e < 9 * p.Ci * p.Co; e += 256) {
-    const int co = e % p.Co, ci = (e / p.Co) % p.Ci, tap = e / (p.Co * p.Ci);
-    const int row = MODE == 0 ? co : ci, k = tap * KC + (MODE == 0 ? ci : co);
-    *reinterpret_cast<uint16_t*>(wl + row * RSW + 2 * k) = p.w[e];
+  // filter -> LDS as [produced channel][tap*KC + reduced channel]; 8 output channels per 16-byte load,
+  // four loads in flight per thread
+  {
+    const int nvec = 9 * p.Ci * p.Co / 8;
+    for (int v0 = tid; v0 < nvec; v0 += 4 * 256) {
+      uint4 wv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int v = v0 + 256 * u;
+        wv[u] = make_uint4(0, 0, 0, 0);
+        if (v < nvec) wv[u] = *reinterpret_cast<const uint4*>(p.w + (size_t)v * 8);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int v = v0 + 256 * u;
+        if (v >= nvec) break;
+        const int e = v * 8, co = e % p.Co, ci = (e / p.Co) % p.Ci, tap = e / (p.Co * p.Ci);
+        if (MODE == 0) {       // 8 rows (co .. co+7), one k each
+          const uint16_t* h16 = reinterpret_cast<const uint16_t*>(&wv[u]);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) *reinterpret_cast<uint16_t*>(wl + (co + j) * RSW + 2 * (tap * KC + ci)) = h16[j];
+        } else {               // one row (ci), 8 consecutive k
+          *reinterpret_cast<uint4*>(wl + ci * RSW + 2 * (tap * KC + co)) = wv[u];
+        }
+      }
+    }
   }
   __syncthreads();
   const int OH = MODE == 0 ? Ho : p.H, OW = MODE == 0 ? Wo : p.W;      // output spatial size
@@ -527,11 +548,14 @@ static int wgrad_launch(hipStream_t s, const void* x, const void* dy, int B, int
 }
 
 int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co,
-                              int stride, float* partials, float* dw) {
+                              int stride, ReduceQueue& rq, float* dw) {
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   const int chunks = (int)((P + WG_PIX_F - 1) / WG_PIX_F), nw = 9 * Ci * Co;
   const int cpt = Ci / (256 / Co);
-  if (wgrad_mfma_ok(H, W, Ci, Co, stride)) {
+  const bool mfma = wgrad_mfma_ok(H, W, Ci, Co, stride);
+  bool queued;
+  float* partials = rq.space((size_t)(mfma ? wgrad_mfma_blocks(B) : chunks) * nw, &queued);
+  if (mfma) {
     const int blocks = wgrad_mfma_blocks(B);
     const size_t lds = (size_t)2 * WGM_C * (H * WGM_W * 2 + 16);
     if (lds > 64 * 1024)
@@ -539,7 +563,7 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
     hipLaunchKernelGGL(conv3x3_wgrad_mfma_kernel, dim3(blocks), dim3(256), lds, s, (const uint16_t*)x, (const uint16_t*)dy, B,
                        H, partials);
     PPLL_HIP(hipGetLastError());
-    return reduce_partials(s, partials, blocks, nw, nw, 1.0f, dw);
+    return rq.reduce(s, queued, partials, blocks, nw, nw, 1.0f, dw);
   }
   int st = PPLL_ERR_CONFIG;
   if (Co == 32 && cpt == 2) st = wgrad_launch<32, 2>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
@@ -552,7 +576,7 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   else if (Co == 64 && cpt == 16) st = wgrad_launch<64, 16>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
   else set_error("conv3x3 weight gradient: no kernel for %d -> %d channels", Ci, Co);
   PPLL_TRY(st);
-  return reduce_partials(s, partials, chunks, nw, nw, 1.0f, dw);
+  return rq.reduce(s, queued, partials, chunks, nw, nw, 1.0f, dw);
 }
 
 bool bn_bf16_supported(int dt, int C, const void* a, const void* b, const void* c, const void* d) {
