@@ -295,7 +295,6 @@ int ppll_block_destroy(ppll_block_t* h) {
   if (!h) { set_error("block handle is null"); return PPLL_ERR_NULL; }
   if (!h->b.alive) { set_error("block handle was destroyed"); return PPLL_ERR_STATE; }
   (void)hipStreamSynchronize(h->b.last_stream);
-  h->b.release_side_stream();
   h->b.alive = false;   // the handle stays allocated so that later misuse is reported, not undefined
   return PPLL_OK;
 }
@@ -370,7 +369,7 @@ int ppll_pipeline_init(const ppll_block_config* cfgs, int32_t K, int32_t depth, 
     }
     ppll_block* h = nullptr;
     st = ppll_block_init(&cfgs[j], bws, ws, init_params_host ? init_params_host[j] : nullptr, hip_streams[j], &h);
-    if (st == PPLL_OK) { h->b.allow_side = false; p->blocks.push_back(h); p->streams.push_back((hipStream_t)hip_streams[j]); }
+    if (st == PPLL_OK) { p->blocks.push_back(h); p->streams.push_back((hipStream_t)hip_streams[j]); }
   }
   p->losses = (float*)take((size_t)K * sizeof(float));
   auto cleanup = [&]() {
@@ -474,7 +473,7 @@ int ppll_pipeline_destroy(ppll_pipeline_t* p) {
   for (auto& v : p->ready) for (hipEvent_t e : v) (void)hipEventDestroy(e);
   for (auto& v : p->freed) for (hipEvent_t e : v) (void)hipEventDestroy(e);
   p->ready.clear(); p->freed.clear();
-  for (ppll_block* h : p->blocks) { h->b.release_side_stream(); h->b.alive = false; }
+  for (ppll_block* h : p->blocks) h->b.alive = false;
   p->alive = false;
   return PPLL_OK;
 }

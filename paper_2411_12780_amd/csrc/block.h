@@ -68,8 +68,13 @@ struct Block {
   void *patches = nullptr, *x0 = nullptr, *embed_tmp = nullptr;
   void *z = nullptr, *dz = nullptr, *dcls = nullptr;
   float *head_mean = nullptr, *head_rstd = nullptr, *logits = nullptr, *dlogits = nullptr;
-  void *gA = nullptr, *gB = nullptr, *d_u = nullptr, *d_h = nullptr, *d_qkv = nullptr;
-  void *gA2 = nullptr, *gB2 = nullptr, *d_h2 = nullptr, *d_qkv2 = nullptr;   // second set: layers alternate
+  // Backward buffers.  Every layer keeps the gradients its four weight-gradient products read
+  // (layer-output gradient, mid-layer gradient, d_h, d_qkv) until the end of the backward pass,
+  // where all those products run as one grouped launch.  g_res[l+1] is the gradient with respect
+  // to the output of layer l, g_res[0] the one with respect to the input of layer 0.
+  std::vector<void*> g_res, g_mid, d_h, d_qkv;
+  void* d_u = nullptr;
+  std::vector<GemmArgs> wgrad_jobs;   // weight-gradient products recorded during the backward pass
 
   // ResNet
   std::vector<BasicBlockParams> rb_p;
@@ -82,17 +87,6 @@ struct Block {
   long steps = 0;
   hipStream_t last_stream = nullptr;
 
-  // Weight-gradient GEMMs do not feed the backward chain, so they run on a second stream and
-  // fill the compute units the chain's small kernels leave idle.  ev_fork[i]: operands ready
-  // (main -> side); ev_done[i]: product finished (side -> main, waited on before a buffer the
-  // product reads is overwritten, and before the optimizer).
-  hipStream_t side = nullptr;
-  bool allow_side = true;        // the pipeline turns it off: its K blocks already overlap on K streams
-  std::vector<hipEvent_t> ev_fork, ev_done;
-  hipEvent_t pending[8] = {};   // last second-stream reader of gA, d_h, gB, d_qkv (set 1), then of set 2
-  hipEvent_t side_tail = nullptr;
-  int ensure_side_stream();
-  void release_side_stream();
 
   // Builds the parameter table and assigns every workspace pointer relative to
   // `base` (null: only measure).  Returns the bytes needed.

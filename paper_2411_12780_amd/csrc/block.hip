@@ -163,10 +163,15 @@ size_t Block::plan(char* base) {
     }
     z = bump.take((size_t)B * D * esz); dz = bump.take((size_t)B * D * esz); dcls = bump.take((size_t)B * D * esz);
     head_mean = bump.floats(B); head_rstd = bump.floats(B);
-    gA = bump.take(M * D * esz); gB = bump.take(M * D * esz); d_u = bump.take(M * D * esz);
-    d_h = bump.take(M * F * esz); d_qkv = bump.take(M * 3 * D * esz);
-    gA2 = bump.take(M * D * esz); gB2 = bump.take(M * D * esz);
-    d_h2 = bump.take(M * F * esz); d_qkv2 = bump.take(M * 3 * D * esz);
+    d_u = bump.take(M * D * esz);
+    g_res.clear(); g_mid.clear(); d_h.clear(); d_qkv.clear();
+    const int layers = cfg.depth + cfg.aux_depth;
+    for (int l = 0; l <= layers; ++l) g_res.push_back(bump.take(M * D * esz));
+    for (int l = 0; l < layers; ++l) {
+      g_mid.push_back(bump.take(M * D * esz));
+      d_h.push_back(bump.take(M * F * esz));
+      d_qkv.push_back(bump.take(M * 3 * D * esz));
+    }
     if (dt == BF16) {
       const size_t cand[] = {gemm_mfma_partial_floats(D, 3 * D, (int)M), gemm_mfma_partial_floats(D, D, (int)M),
                              gemm_mfma_partial_floats(D, F, (int)M), gemm_mfma_partial_floats(F, D, (int)M),
@@ -233,29 +238,6 @@ size_t Block::plan(char* base) {
   return (bump.off + 255) & ~(size_t)255;
 }
 
-// ------------------------------------------------------------------ second stream
-int Block::ensure_side_stream() {
-  if (side) return PPLL_OK;
-  static const bool single = getenv("PPLL_SINGLE_STREAM") != nullptr;
-  if (single || !allow_side || cfg.arch != PPLL_VIT || dt != BF16) return PPLL_OK;
-  PPLL_HIP(hipStreamCreateWithFlags(&side, hipStreamNonBlocking));
-  const int n = 4 * (cfg.depth + cfg.aux_depth);
-  for (int i = 0; i < n; ++i) {
-    hipEvent_t a = nullptr, b = nullptr;
-    PPLL_HIP(hipEventCreateWithFlags(&a, hipEventDisableTiming));
-    PPLL_HIP(hipEventCreateWithFlags(&b, hipEventDisableTiming));
-    ev_fork.push_back(a); ev_done.push_back(b);
-  }
-  return PPLL_OK;
-}
-
-void Block::release_side_stream() {
-  if (side) { (void)hipStreamSynchronize(side); (void)hipStreamDestroy(side); side = nullptr; }
-  for (hipEvent_t e : ev_fork) (void)hipEventDestroy(e);
-  for (hipEvent_t e : ev_done) (void)hipEventDestroy(e);
-  ev_fork.clear(); ev_done.clear();
-}
-
 // ------------------------------------------------------------------ ViT
 int Block::encoder_fwd(int l, const void* x, void* x2_out, hipStream_t s) {
   const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, M = cfg.batch * T;
@@ -290,7 +272,7 @@ int Block::encoder_fwd(int l, const void* x, void* x2_out, hipStream_t s) {
 }
 
 // g_in: gradient w.r.t. the layer output; g_tmp receives the gradient at the
-// mid-layer residual; g_out (may alias g_in) the gradient w.r.t. the layer input.
+// mid-layer residual; g_out the gradient w.r.t. the layer input.
 int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void* g_out, bool need_dx, hipStream_t s) {
   const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, M = cfg.batch * T;
   const EncoderParams& p = enc_p[l];
@@ -303,61 +285,38 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
     g.C = dxo; g.c_dt = dt; g.ldc = in_dim; g.M = M; g.N = in_dim; g.K = out_dim;
     return g;
   };
-  // dW[in,out] = X^T dY and db = column sums of dY, reduction over the M rows.  `slot` names the
-  // buffer dY lives in (0 gA, 1 d_h, 2 gB, 3 d_qkv).  With the fused MFMA kernel the product goes
-  // to the second stream; the buffer's next writer waits for it (before_write below).  Odd and even
-  // layers use different sets of these buffers, so that wait is for a product queued a whole layer
-  // earlier and the main stream rarely stalls on it.
-  const int set = l & 1;
-  void* d_h = set ? this->d_h2 : this->d_h;
-  void* d_qkv = set ? this->d_qkv2 : this->d_qkv;
-  auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off, size_t b_off,
-                   int slot) -> int {
+  // dW[in,out] = X^T dY and db = column sums of dY, reduction over the M rows.  Nothing in the
+  // backward chain reads them, so the products are only recorded here (their operands stay
+  // untouched until the end of the pass: every layer has its own gradient buffers) and all of
+  // them run as one grouped launch after the last layer: together they have enough output tiles
+  // to fill the chip without splitting K.  A product the MFMA kernel cannot take runs at once.
+  void* d_h = this->d_h[l];
+  void* d_qkv = this->d_qkv[l];
+  auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off, size_t b_off) -> int {
     GemmArgs g = gemm_args();
     g.A = xin; g.a_dt = dt; g.a_sm = 1; g.a_sk = in_dim;
     g.B = dy; g.b_dt = dt; g.b_sk = out_dim; g.b_sn = 1;
     g.C = grads + w_off; g.c_dt = F32; g.ldc = out_dim; g.M = in_dim; g.N = out_dim; g.K = M;
-    g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
     g.colsum = grads + b_off;
-    const bool fused = gemm_fuses_colsum(g);
-    if (fused && side) {
-      const int i = 4 * l + slot;
-      PPLL_HIP(hipEventRecord(ev_fork[i], s));
-      PPLL_HIP(hipStreamWaitEvent(side, ev_fork[i], 0));
-      PPLL_TRY(launch_gemm(side, g));
-      PPLL_HIP(hipEventRecord(ev_done[i], side));
-      pending[slot + 4 * set] = ev_done[i];
-      side_tail = ev_done[i];
-      return (int)PPLL_OK;
-    }
+    if (gemm_mfma_groupable(g)) { wgrad_jobs.push_back(g); return (int)PPLL_OK; }
+    g.colsum = nullptr;
+    g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
     PPLL_TRY(launch_gemm(s, g));
-    return fused ? (int)PPLL_OK : launch_colsum(s, dy, dt, M, out_dim, rq, grads + b_off);
-  };
-  auto before_write = [&](int slot) -> int {
-    hipEvent_t& e = pending[slot];
-    if (e) {
-      PPLL_HIP(hipStreamWaitEvent(s, e, 0));
-      e = nullptr;
-    }
-    return (int)PPLL_OK;
+    return launch_colsum(s, dy, dt, M, out_dim, rq, grads + b_off);
   };
   GemmArgs g = dgrad(g_in, D, p.fc2_w, F, d_h);
   g.epilogue = EPI_DGELU; g.aux = a.h; g.aux_dt = dt; g.ldaux = F;
-  PPLL_TRY(before_write(1 + 4 * set));
   PPLL_TRY(launch_gemm(s, g));
-  PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w, p.fc2_b, 0));
+  PPLL_TRY(wgrad(a.gl, F, g_in, D, p.fc2_w, p.fc2_b));
   PPLL_TRY(launch_gemm(s, dgrad(d_h, F, p.fc1_w, D, d_u)));
-  PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w, p.fc1_b, 1));
-  PPLL_TRY(before_write(2 + 4 * set));
+  PPLL_TRY(wgrad(a.u2, D, d_h, F, p.fc1_w, p.fc1_b));
   PPLL_TRY(launch_layernorm_bwd(s, d_u, a.x1, dt, D, M, D, params + p.ln2_g, a.mean2, a.rstd2, g_in, g_tmp, rq,
                                 grads + p.ln2_g, grads + p.ln2_b));
   PPLL_TRY(launch_gemm(s, dgrad(g_tmp, D, p.proj_w, D, d_u)));
-  PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w, p.proj_b, 2));
-  PPLL_TRY(before_write(3 + 4 * set));
+  PPLL_TRY(wgrad(a.att, D, g_tmp, D, p.proj_w, p.proj_b));
   PPLL_TRY(launch_attention_bwd(s, a.qkv, a.att, d_u, a.lse, dt, cfg.batch, T, H, D / H, d_qkv));
   PPLL_TRY(launch_gemm(s, dgrad(d_qkv, 3 * D, p.qkv_w, D, d_u)));
-  PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b, 3));
-  PPLL_TRY(before_write(0 + 4 * (set ^ 1)));   // g_out is the other set's gA
+  PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b));
   return launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, g_tmp,
                               need_dx ? g_out : nullptr, rq, grads + p.ln1_g, grads + p.ln1_b);
 }
@@ -417,36 +376,42 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   PPLL_TRY(launch_gemm_generic(s, g));
   PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
                                 rq, grads + head_ln_g, grads + head_ln_b));
-  // layer l takes its output gradient in set l%2's gA, its mid-layer gradient in that set's gB, and
-  // leaves its input gradient in the other set's gA
-  auto g_of = [&](int l) { return (l & 1) ? gA2 : gA; };
-  PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, g_of(L + A - 1)));
+  wgrad_jobs.clear();
+  PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, g_res[L + A]));
   // ---- backward: auxiliary layers then module layers; the chain stops at x_in
   for (int l = L + A - 1; l >= 0; --l) {
     bool need_dx = l > 0 || image;
-    PPLL_TRY(encoder_bwd(l, layer_in[l], g_of(l), (l & 1) ? gB2 : gB, g_of(l - 1), need_dx, s));
-  }
-  if (side_tail) {   // every weight gradient is in place (and the split-K scratch free) from here on
-    PPLL_HIP(hipStreamWaitEvent(s, side_tail, 0));
-    side_tail = nullptr;
-    for (hipEvent_t& e : pending) e = nullptr;
+    PPLL_TRY(encoder_bwd(l, layer_in[l], g_res[l + 1], g_mid[l], g_res[l], need_dx, s));
   }
   if (image) {
-    PPLL_TRY(launch_embed_bwd(s, g_of(-1), dt, B, T, D, rq, grads + pos, grads + cls, embed_tmp));
+    PPLL_TRY(launch_embed_bwd(s, g_res[0], dt, B, T, D, rq, grads + pos, grads + cls, embed_tmp));
     if (T > 1) {
       g = gemm_args();
       g.A = patches; g.a_dt = dt; g.a_sm = 1; g.a_sk = ppc;
       g.B = embed_tmp; g.b_dt = dt; g.b_sk = D; g.b_sn = 1;
       g.C = grads + pe_w; g.c_dt = F32; g.ldc = D; g.M = ppc; g.N = D; g.K = B * (T - 1);
-      g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
-      g.colsum = grads + pe_b;   // bias gradient: column sums of dE, folded into the product when the MFMA kernel takes it
-      const bool fused = gemm_fuses_colsum(g);
-      PPLL_TRY(launch_gemm(s, g));
-      if (!fused) PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, rq, grads + pe_b));
+      g.colsum = grads + pe_b;   // bias gradient: column sums of dE, folded into the product by the MFMA kernel
+      if (gemm_mfma_groupable(g)) {
+        wgrad_jobs.push_back(g);
+      } else {
+        g.colsum = nullptr;
+        g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
+        PPLL_TRY(launch_gemm(s, g));
+        PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, rq, grads + pe_b));
+      }
     } else {
       PPLL_TRY(launch_fill_zero(s, grads + pe_w, ((size_t)ppc * D + D) * sizeof(float)));
     }
   }
+  // ---- every recorded weight-gradient product, in one launch
+  if (wgrad_jobs.size() == 1) {   // a single product still needs split-K to fill the chip
+    GemmArgs one = wgrad_jobs[0];
+    one.splitk_ws = splitk; one.splitk_floats = splitk_floats;
+    PPLL_TRY(launch_gemm(s, one));
+  } else {
+    PPLL_TRY(launch_gemm_group(s, wgrad_jobs.data(), (int)wgrad_jobs.size()));
+  }
+  wgrad_jobs.clear();
   (void)M;
   return PPLL_OK;
 }
@@ -536,7 +501,6 @@ int Block::update(float lr, hipStream_t s) {
 int Block::step(const void* x_in, const int32_t* labels, float lr, void* x_out, float* loss_out, hipStream_t s,
                 const std::function<int()>& after_forward) {
   last_stream = s;
-  PPLL_TRY(ensure_side_stream());
   rq.reset();
   if (cfg.arch == PPLL_VIT) PPLL_TRY(vit_step(x_in, labels, x_out, s, after_forward));
   else PPLL_TRY(resnet_step(x_in, labels, x_out, s, after_forward));

@@ -96,6 +96,10 @@ bool gemm_mfma_supported(const GemmArgs& g);
 inline bool gemm_fuses_colsum(const GemmArgs& g) { return g.colsum && gemm_mfma_supported(g); }
 size_t gemm_mfma_partial_floats(int M, int N, int K);
 int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t partial_floats);
+bool gemm_mfma_groupable(const GemmArgs& g);
+int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n);   // every product must be groupable
+// A set of independent products; one launch when all of them are groupable, else one by one.
+int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n);
 void profile_enable(bool on);
 int profile_begin(hipStream_t s, double flops, void** token);   // event pair around one launch (profiling only)
 int profile_end(hipStream_t s, void* token);

@@ -61,6 +61,19 @@ int launch_gemm(hipStream_t s, const GemmArgs& g) {
   return gemm_mfma_supported(g) ? launch_gemm_mfma(s, g, g.splitk_ws, g.splitk_floats) : launch_gemm_generic(s, g);
 }
 
+int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n) {
+  if (n <= 0) return PPLL_OK;
+  bool all = n > 1;
+  for (int j = 0; j < n && all; ++j) all = gemm_mfma_groupable(gs[j]);
+  if (all) return launch_gemm_mfma_grouped(s, gs, n);
+  for (int j = 0; j < n; ++j) {
+    const bool fused = gemm_fuses_colsum(gs[j]);
+    if (gs[j].colsum && !fused) { set_error("launch_gemm_group: column sums need the MFMA kernel"); return PPLL_ERR_CONFIG; }
+    PPLL_TRY(launch_gemm(s, gs[j]));
+  }
+  return PPLL_OK;
+}
+
 int launch_attention_fwd(hipStream_t s, const void* qkv, int dt, int B, int T, int H, int dh, void* out, float* lse) {
   if (attention_mfma_supported(dt, T, H, dh, qkv, out, nullptr, nullptr)) return launch_attention_fwd_mfma(s, qkv, B, T, H, out, lse);
   return launch_attention_fwd_generic(s, qkv, dt, B, T, H, dh, out, lse);

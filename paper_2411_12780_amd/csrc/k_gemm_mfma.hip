@@ -168,8 +168,9 @@ struct TileRegs { uint4 a[4], b[4]; };
 // AT: A is stored [K][M] (transposing loader), else [M][K].  BT likewise for B ([K][N] / [N][K]).
 // TM = rows of the output tile: 128 (wave tile 64 x 64) or, for outputs with too few 128-row
 // tiles to fill the chip, 64 (wave tile 32 x 64; direct A loader only).
+// One output tile; bid_x, bid_y are the workgroup's place in the (virtual) grid of this product.
 template <bool AT, bool BT, int TM>
-__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
+__device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_x, const int bid_y) {
   static_assert(TM == 128 || (TM == 64 && !AT), "64-row tiles are for the direct A loader");
   constexpr int IM = TM / 64;                  // 32-row MFMA tiles per wave along m
   constexpr int OPER_BYTES = oper_bytes(TM);
@@ -181,20 +182,20 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   // land on one XCD, next to each other in its dispatch order, and the panel is fetched once.
   // With split-K (xcd_map 2) it is the splits that are dealt to the XCDs: all tiles of one k-range
   // run on one XCD, so the two token panels of that range are fetched from HBM once.
-  int tm, tn, split = blockIdx.y;
+  int tm, tn, split = bid_y;
   if (p.xcd_map == 1) {
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int xcd = bid_x & 7, slot = bid_x >> 3;
     tm = (slot / p.tiles_n) * 8 + xcd; tn = slot % p.tiles_n;
     if (tm >= p.tiles_m) return;
   } else if (p.xcd_map == 2) {
     const int tiles = p.tiles_m * p.tiles_n;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int xcd = bid_x & 7, slot = bid_x >> 3;
     split = (slot / tiles) * 8 + xcd;
     const int tile = slot % tiles;
     tm = tile / p.tiles_n; tn = tile % p.tiles_n;
     if (split >= p.splits) return;
   } else {
-    tm = blockIdx.x / p.tiles_n; tn = blockIdx.x % p.tiles_n;
+    tm = bid_x / p.tiles_n; tn = bid_x % p.tiles_n;
   }
   const int m0 = tm * TM, n0 = tn * BN;
   const int nkt = (p.K + BK - 1) / BK;
@@ -417,6 +418,50 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
   TRACE(4)
 }
 
+template <bool AT, bool BT, int TM>
+__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(MfmaArgs p) {
+  gemm_mfma_tile<AT, BT, TM>(p, (int)blockIdx.x, (int)blockIdx.y);
+}
+
+// Several products C_j = A_j^T B_j (both operands stored [K][.], fp32 output, optional column sums
+// of B_j: the weight and bias gradients of a set of Linear layers) in one launch, no split-K: the
+// tiles of all products together fill the chip, so every tile walks its whole K and nothing
+// passes through partial buffers.  Tiles are numbered product by product; XCD x (workgroup id % 8)
+// takes a contiguous range of them, so the tiles that share operand panels share an L2.
+struct GroupedProblem {
+  const uint16_t* A; const uint16_t* B; float* C; float* colsum;
+  int lda, ldb, ldc, M, N, K, tiles_m, tiles_n, first_tile;
+  uint32_t a_bytes, b_bytes, c_bytes;
+};
+constexpr int GROUP_MAX = 24;
+struct GroupedArgs {
+  int n, total_tiles, per_xcd;
+#ifdef PPLL_GEMM_TRACE
+  long long* trace;
+#endif
+  GroupedProblem prob[GROUP_MAX];
+};
+__global__ __launch_bounds__(256, 2) void gemm_mfma_grouped_kernel(GroupedArgs a) {
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int t = xcd * a.per_xcd + slot;
+  if (slot >= a.per_xcd || t >= a.total_tiles) return;
+  int j = 0;
+  while (j + 1 < a.n && t >= a.prob[j + 1].first_tile) ++j;
+  MfmaArgs p{};
+  p.A = a.prob[j].A; p.lda = a.prob[j].lda; p.B = a.prob[j].B; p.ldb = a.prob[j].ldb;
+  p.C = a.prob[j].C; p.c_f32 = 1; p.ldc = a.prob[j].ldc;
+  p.M = a.prob[j].M; p.N = a.prob[j].N; p.K = a.prob[j].K;
+  p.tiles_m = a.prob[j].tiles_m; p.tiles_n = a.prob[j].tiles_n;
+  p.kt_per_split = (p.K + BK - 1) / BK;
+  p.colsum = a.prob[j].colsum;
+  p.a_bytes = a.prob[j].a_bytes; p.b_bytes = a.prob[j].b_bytes; p.c_bytes = a.prob[j].c_bytes;
+  p.splits = 1; p.xcd_map = 0;
+#ifdef PPLL_GEMM_TRACE
+  p.trace = a.trace;
+#endif
+  gemm_mfma_tile<true, true, 128>(p, t - a.prob[j].first_tile, 0);
+}
+
 // C[i] = sum over splits of partial[s][i], fixed order; the trailing workgroups do the same for
 // the bias-gradient partials [splits][N] when there are any.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial, int splits, size_t mn, float* C,
@@ -493,6 +538,53 @@ int gemm_mfma_splits(int M, int N, int K) {
 size_t gemm_mfma_partial_floats(int M, int N, int K) {
   int s = gemm_mfma_splits(M, N, K);
   return s > 1 ? (size_t)s * M * N + (size_t)s * N : 0;   // tile partials, then bias-gradient partials
+}
+
+// True when a set of products can go into one grouped launch: each a transposed-transposed product
+// with a plain fp32 output (what a weight gradient is).
+bool gemm_mfma_groupable(const GemmArgs& g) {
+  if (!gemm_mfma_supported(g)) return false;
+  const bool at = g.a_sm == 1 && g.a_sk != 1, bt = g.b_sn == 1 && g.b_sk != 1;
+  return at && bt && !g.bias && !g.residual && g.epilogue == EPI_NONE && g.c_dt == F32;
+}
+
+int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n) {
+  static bool lds_opted_in = false;
+  if (!lds_opted_in) {
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+    lds_opted_in = true;
+  }
+  for (int j0 = 0; j0 < n; j0 += GROUP_MAX) {
+    GroupedArgs a{};
+    a.n = n - j0 < GROUP_MAX ? n - j0 : GROUP_MAX;
+    int tiles = 0;
+    double flops = 0.0;
+    for (int j = 0; j < a.n; ++j) {
+      const GemmArgs& g = gs[j0 + j];
+      GroupedProblem& q = a.prob[j];
+      q.A = (const uint16_t*)g.A; q.lda = (int)g.a_sk; q.B = (const uint16_t*)g.B; q.ldb = (int)g.b_sk;
+      q.C = (float*)g.C; q.ldc = (int)g.ldc; q.colsum = g.colsum;
+      q.M = g.M; q.N = g.N; q.K = g.K;
+      q.tiles_m = (g.M + BM - 1) / BM; q.tiles_n = (g.N + BN - 1) / BN;
+      q.first_tile = tiles;
+      tiles += q.tiles_m * q.tiles_n;
+      q.a_bytes = (uint32_t)operand_bytes(true, g.M, g.K, g.a_sk);
+      q.b_bytes = (uint32_t)operand_bytes(true, g.N, g.K, g.b_sk);
+      q.c_bytes = (uint32_t)(((long)(g.M - 1) * g.ldc + g.N) * 4);
+      flops += 2.0 * g.M * g.N * g.K;
+    }
+    a.total_tiles = tiles;
+    a.per_xcd = (tiles + 7) / 8;
+#ifdef PPLL_GEMM_TRACE
+    a.trace = g_gemm_trace;
+#endif
+    void* prof = nullptr;
+    PPLL_TRY(profile_begin(s, flops, &prof));
+    hipLaunchKernelGGL(gemm_mfma_grouped_kernel, dim3(8 * a.per_xcd), dim3(256), lds_bytes(128), s, a);
+    PPLL_HIP(hipGetLastError());
+    PPLL_TRY(profile_end(s, prof));
+  }
+  return PPLL_OK;
 }
 
 int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t partial_floats) {
