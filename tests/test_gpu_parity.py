@@ -188,6 +188,15 @@ def test_vit_bf16_activation_input_ragged():
     run_case(wl, steps=2)
 
 
+@pytest.mark.parametrize("dim,heads", [(256, 4), (512, 8), (768, 12), (1024, 16)])
+def test_vit_bf16_widths_of_the_fast_layernorm(dim, heads):
+    # the LayerNorm kernels hold a row in 16, 32 or 64 lanes depending on the width (256: 16, 512 and 768: 32,
+    # 1024: 64); 40 tokens leave a ragged last row group in every one of them
+    wl = synth.workload("vit_stage_act_bf16", batch=3, tokens=40, dim=dim, heads=heads, mlp_dim=2 * dim, depth=1,
+                        aux_depth=1)
+    run_case(wl, steps=1)
+
+
 def test_resnet_fp32_stage_full_size_decisive_masks():
     # not a named workload: fp32 at the full ResNet size.  Gradients pass 10 BatchNorm backward
     # stages, each a cancelling 32768-term reduction in fp32, so 1e-3 instead of 1e-4
