@@ -84,6 +84,7 @@ struct Block {
   float *aux_mean = nullptr, *aux_rstd = nullptr;
   void *r_gA = nullptr, *r_gB = nullptr, *r_t1 = nullptr, *r_t2 = nullptr;
 
+  float* loss_copy = nullptr;    // caller's loss slot of the step in flight (may be null)
   long steps = 0;
   hipStream_t last_stream = nullptr;
 

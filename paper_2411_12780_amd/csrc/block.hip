@@ -361,14 +361,13 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = D; g.bias = params + head_b;
   PPLL_TRY(launch_gemm_generic(s, g));
   // ---- local loss
-  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, dlogits, flag_dev));
+  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, loss_copy, dlogits, grads + head_b, flag_dev));
   // ---- backward: head
   g = gemm_args();
   g.A = z; g.a_dt = dt; g.a_sm = 1; g.a_sk = D;
   g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
   g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = D; g.N = C; g.K = B;
   PPLL_TRY(launch_gemm_generic(s, g));
-  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, rq, grads + head_b));
   g = gemm_args();
   g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
   g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
@@ -453,14 +452,13 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
   g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = A; g.bias = params + head_b;
   PPLL_TRY(launch_gemm_generic(s, g));
-  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, dlogits, flag_dev));
+  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, loss_copy, dlogits, grads + head_b, flag_dev));
   // ---- backward: head and auxiliary net
   g = gemm_args();
   g.A = pooled; g.a_dt = dt; g.a_sm = 1; g.a_sk = A;
   g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
   g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = A; g.N = C; g.K = B;
   PPLL_TRY(launch_gemm_generic(s, g));
-  PPLL_TRY(launch_colsum(s, dlogits, F32, B, C, rq, grads + head_b));
   g = gemm_args();
   g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
   g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
@@ -502,11 +500,12 @@ int Block::step(const void* x_in, const int32_t* labels, float lr, void* x_out, 
                 const std::function<int()>& after_forward) {
   last_stream = s;
   rq.reset();
+  loss_copy = loss_out;   // the loss kernel writes it there as well
   if (cfg.arch == PPLL_VIT) PPLL_TRY(vit_step(x_in, labels, x_out, s, after_forward));
   else PPLL_TRY(resnet_step(x_in, labels, x_out, s, after_forward));
   PPLL_TRY(rq.flush(s));
   PPLL_TRY(update(lr, s));
-  if (loss_out) PPLL_HIP(hipMemcpyAsync(loss_out, loss_dev, sizeof(float), hipMemcpyDeviceToDevice, s));
+
   return PPLL_OK;
 }
 

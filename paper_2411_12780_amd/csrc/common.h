@@ -139,8 +139,10 @@ int layernorm_bwd_partial_floats(int rows, int D);
 int launch_colsum(hipStream_t s, const void* x, int dt, int rows, int N, ReduceQueue& rq, float* out);
 int colsum_partial_floats(int rows, int N);
 
+// mean softmax cross-entropy and its gradient; loss2 (optional) receives a copy of the loss, dbias (optional)
+// the column sums of dlogits
 int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labels, int B, int C,
-                         float* loss, float* dlogits, int* flag);
+                         float* loss, float* loss2, float* dlogits, float* dbias, int* flag);
 
 // ---------------------------------------------------------------- ViT pieces
 int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W, int C, int P, void* patches);

@@ -533,9 +533,15 @@ int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, l
 
 // ===================================================================== cross-entropy
 namespace {
+constexpr size_t CE_LDS_FLOATS = 8192;
+// One workgroup: mean loss (also copied to loss2 when given), dlogits, and the head's bias gradient
+// db[c] = sum over the batch of dlogits[b][c], added in batch order.
 __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* logits, const int32_t* labels, int B, int C,
-                                                            float* loss, float* dlogits, int* flag) {
+                                                            float* loss, float* loss2, float* dlogits, float* dbias,
+                                                            int* flag) {
   __shared__ float red[256];
+  extern __shared__ float dl[];             // a copy of dlogits when the launcher gave it room (CE_LDS_FLOATS)
+  const bool in_lds = (size_t)B * C <= CE_LDS_FLOATS;
   float acc = 0.f;
   for (int b = threadIdx.x; b < B; b += 256) {
     const float* z = logits + (size_t)b * C;
@@ -547,7 +553,11 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* logits,
     int y = labels[b];
     bool ok = y >= 0 && y < C;
     if (!ok) *flag = 1;
-    for (int c = 0; c < C; ++c) dlogits[(size_t)b * C + c] = (expf(z[c] - lse) - ((ok && c == y) ? 1.f : 0.f)) / B;
+    for (int c = 0; c < C; ++c) {
+      const float d = (expf(z[c] - lse) - ((ok && c == y) ? 1.f : 0.f)) / B;
+      dlogits[(size_t)b * C + c] = d;
+      if (in_lds) dl[b * C + c] = d;
+    }
     if (ok) acc += lse - z[y];
   }
   red[threadIdx.x] = acc;
@@ -556,13 +566,34 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* logits,
     if (threadIdx.x < o) red[threadIdx.x] += red[threadIdx.x + o];
     __syncthreads();
   }
-  if (threadIdx.x == 0) *loss = red[0] / B;
+  if (threadIdx.x == 0) {
+    *loss = red[0] / B;
+    if (loss2) *loss2 = red[0] / B;
+  }
+  if (dbias)   // dlogits were written by this workgroup before the barriers above
+    for (int c = threadIdx.x; c < C; c += 256) {
+      float t = 0.f;
+      if (in_lds) {
+        for (int b = 0; b < B; ++b) t += dl[b * C + c];
+      } else {
+        for (int b = 0; b < B; b += 8) {    // eight loads in flight, added in batch order
+          float q[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) q[u] = b + u < B ? dlogits[(size_t)(b + u) * C + c] : 0.f;
+#pragma unroll
+          for (int u = 0; u < 8; ++u) t += q[u];
+        }
+      }
+      dbias[c] = t;
+    }
 }
 }  // namespace
 
 int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labels, int B, int C, float* loss,
-                         float* dlogits, int* flag) {
-  hipLaunchKernelGGL(cross_entropy_kernel, dim3(1), dim3(256), 0, s, logits, labels, B, C, loss, dlogits, flag);
+                         float* loss2, float* dlogits, float* dbias, int* flag) {
+  const size_t lds = (size_t)B * C <= CE_LDS_FLOATS ? (size_t)B * C * sizeof(float) : 0;
+  hipLaunchKernelGGL(cross_entropy_kernel, dim3(1), dim3(256), lds, s, logits, labels, B, C, loss, loss2, dlogits, dbias,
+                     flag);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
