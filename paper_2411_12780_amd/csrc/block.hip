@@ -298,9 +298,9 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
     g.B = dy; g.b_dt = dt; g.b_sk = out_dim; g.b_sn = 1;
     g.C = grads + w_off; g.c_dt = F32; g.ldc = out_dim; g.M = in_dim; g.N = out_dim; g.K = M;
     g.colsum = grads + b_off;
+    g.splitk_ws = splitk; g.splitk_floats = splitk_floats;   // used when the product ends up running on its own
     if (gemm_mfma_groupable(g)) { wgrad_jobs.push_back(g); return (int)PPLL_OK; }
     g.colsum = nullptr;
-    g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
     PPLL_TRY(launch_gemm(s, g));
     return launch_colsum(s, dy, dt, M, out_dim, rq, grads + b_off);
   };
@@ -390,11 +390,11 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
       g.B = embed_tmp; g.b_dt = dt; g.b_sk = D; g.b_sn = 1;
       g.C = grads + pe_w; g.c_dt = F32; g.ldc = D; g.M = ppc; g.N = D; g.K = B * (T - 1);
       g.colsum = grads + pe_b;   // bias gradient: column sums of dE, folded into the product by the MFMA kernel
+      g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
       if (gemm_mfma_groupable(g)) {
         wgrad_jobs.push_back(g);
       } else {
         g.colsum = nullptr;
-        g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
         PPLL_TRY(launch_gemm(s, g));
         PPLL_TRY(launch_colsum(s, embed_tmp, dt, B * (T - 1), D, rq, grads + pe_b));
       }
@@ -402,14 +402,8 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
       PPLL_TRY(launch_fill_zero(s, grads + pe_w, ((size_t)ppc * D + D) * sizeof(float)));
     }
   }
-  // ---- every recorded weight-gradient product, in one launch
-  if (wgrad_jobs.size() == 1) {   // a single product still needs split-K to fill the chip
-    GemmArgs one = wgrad_jobs[0];
-    one.splitk_ws = splitk; one.splitk_floats = splitk_floats;
-    PPLL_TRY(launch_gemm(s, one));
-  } else {
-    PPLL_TRY(launch_gemm_group(s, wgrad_jobs.data(), (int)wgrad_jobs.size()));
-  }
+  // ---- every recorded weight-gradient product: one launch, or one by one with split-K for a small set
+  PPLL_TRY(launch_gemm_group(s, wgrad_jobs.data(), (int)wgrad_jobs.size()));
   wgrad_jobs.clear();
   (void)M;
   return PPLL_OK;

@@ -64,8 +64,14 @@ int launch_gemm(hipStream_t s, const GemmArgs& g) {
 int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n) {
   if (n <= 0) return PPLL_OK;
   bool all = n > 1;
-  for (int j = 0; j < n && all; ++j) all = gemm_mfma_groupable(gs[j]);
-  if (all) return launch_gemm_mfma_grouped(s, gs, n);
+  long tiles = 0;
+  for (int j = 0; j < n && all; ++j) {
+    all = gemm_mfma_groupable(gs[j]);
+    tiles += (long)((gs[j].M + 127) / 128) * ((gs[j].N + 127) / 128);
+  }
+  // one launch when the products together have enough output tiles for the chip; a small set runs
+  // product by product, each with split-K (their reduction index is the long one)
+  if (all && tiles >= 128) return launch_gemm_mfma_grouped(s, gs, n);
   for (int j = 0; j < n; ++j) {
     const bool fused = gemm_fuses_colsum(gs[j]);
     if (gs[j].colsum && !fused) { set_error("launch_gemm_group: column sums need the MFMA kernel"); return PPLL_ERR_CONFIG; }
