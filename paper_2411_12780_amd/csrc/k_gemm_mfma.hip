@@ -11,10 +11,10 @@
 // dW = X^T dY) is transposed in registers on the way in, so no transposed copies
 // of weights or activations exist in HBM.
 //
-// LDS rows are 144 bytes apart (128 of data + 16 of padding) and the 16-byte
-// k-granule index is XORed with (row / 16) % 8: with that layout the fragment
-// reads (ds_read_b128, 32 rows x 2 granules per wave) and the 8-byte writes of
-// the transposing loader are both free of bank conflicts.
+// The 16-byte k-granules of an LDS row are permuted by an XOR with row bits, and
+// a tile written by the transposing loader also pads its rows (144 bytes apart):
+// each operand tile gets the layout for which both its stores and the fragment
+// reads (ds_read_b128, 32 rows x 2 granules per wave) are free of bank conflicts.
 //
 // The MFMA is issued with the B tile as its first operand, i.e. it produces C
 // transposed: a lane then holds 4 consecutive columns of one C row, so bias,
@@ -32,7 +32,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int ROW_BYTES = 144;
+
 
 struct MfmaArgs {
   const uint16_t* A; long lda;      // AT ? A[k*lda + m] : A[m*lda + k]
@@ -73,9 +73,19 @@ __device__ __forceinline__ float gelu_fast(float h) { float c, d; cdf_pdf(h, c, 
 __device__ __forceinline__ float dgelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return c + h * d; }
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
-__device__ __forceinline__ int lds_off(int row, int granule16) {
-  return row * ROW_BYTES + ((granule16 ^ ((row >> 4) & 7)) << 4);
-}
+// LDS layout of an operand tile, [row][64 k], chosen by how the tile is written (a brute-force model
+// of the 64 x 4-byte banks gives the conflict counts):
+//  - copied with 16-byte stores (k contiguous in memory): rows 128 bytes apart, the 16-byte granule
+//    index XORed with (row/2)%8: stores and fragment reads are both conflict-free;
+//  - written by the transposing loader (8-byte stores, 8 rows per thread): rows 144 bytes apart,
+//    granule index XORed with (row/16)%8: reads and those stores are conflict-free (the first
+//    layout would serialise the stores 8-fold).
+template <bool TR> struct TileLayout {
+  static constexpr int ROW = TR ? 144 : 128;
+  static __device__ __forceinline__ int off(int row, int granule16) {
+    return TR ? row * 144 + ((granule16 ^ ((row >> 4) & 7)) << 4) : row * 128 + ((granule16 ^ ((row >> 1) & 7)) << 4);
+  }
+};
 
 // ---- Buffer addressing.  Operands, outputs and epilogue inputs are reached through raw buffer
 // descriptors: a load whose byte offset lies beyond the buffer returns 0 and a store there is
@@ -148,20 +158,21 @@ struct OperandLoader {
         uint2 o;
         o.x = __builtin_amdgcn_perm(w1, w0, sel);   // k, k+1 of row 8 mg + 2 q + h
         o.y = __builtin_amdgcn_perm(w3, w2, sel);   // k+2, k+3
-        *reinterpret_cast<uint2*>(lds + lds_off(mg * 8 + 2 * q + h, kg >> 1) + (kg & 1) * 8) = o;
+        *reinterpret_cast<uint2*>(lds + TileLayout<true>::off(mg * 8 + 2 * q + h, kg >> 1) + (kg & 1) * 8) = o;
       }
     } else if (q < NP) {
       const int c = tid + 256 * q;
-      *reinterpret_cast<uint4*>(lds + lds_off(c >> 3, c & 7)) = r[q];
+      *reinterpret_cast<uint4*>(lds + TileLayout<false>::off(c >> 3, c & 7)) = r[q];
     }
   }
 };
 
 constexpr int STAGE_LD = BN + 4;                      // fp32 staging tile of the epilogue, padded row
-constexpr int oper_bytes(int tm) { return (tm + BN) * ROW_BYTES; }   // one stage of both operand tiles
-constexpr int lds_bytes(int tm) { return 2 * oper_bytes(tm); }        // two stages; the epilogue tile reuses them
-static_assert(BM * STAGE_LD * 4 <= lds_bytes(BM) && 64 * STAGE_LD * 4 <= lds_bytes(64),
-              "epilogue staging tile must fit in the operand stages");
+// one stage of both operand tiles; two stages, or the epilogue's staging tile if that is larger
+constexpr int oper_bytes(bool at, bool bt, int tm) { return tm * TileLayout<false>::ROW + (at ? tm * 16 : 0) + BN * TileLayout<false>::ROW + (bt ? BN * 16 : 0); }
+constexpr int lds_bytes(bool at, bool bt, int tm) {
+  return 2 * oper_bytes(at, bt, tm) > tm * STAGE_LD * 4 ? 2 * oper_bytes(at, bt, tm) : tm * STAGE_LD * 4;
+}
 
 struct TileRegs { uint4 a[4], b[4]; };
 
@@ -173,7 +184,8 @@ template <bool AT, bool BT, int TM>
 __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_x, const int bid_y) {
   static_assert(TM == 128 || (TM == 64 && !AT), "64-row tiles are for the direct A loader");
   constexpr int IM = TM / 64;                  // 32-row MFMA tiles per wave along m
-  constexpr int OPER_BYTES = oper_bytes(TM);
+  constexpr int OPER_BYTES = oper_bytes(AT, BT, TM);
+  constexpr int A_BYTES = TM * TileLayout<AT>::ROW;   // the B tile of a stage follows the A tile
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;
@@ -233,18 +245,18 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
   auto lstore_part = [&](int stage, const TileRegs& r, int q) {
     char* la = smem + stage * OPER_BYTES;
     ldA.store_part(la, tid, r.a, q);
-    ldB.store_part(la + TM * ROW_BYTES, tid, r.b, q);
+    ldB.store_part(la + A_BYTES, tid, r.b, q);
   };
   const int frag_row = lane & 31, frag_g = lane >> 5;
   auto load_frags = [&](int stage, int kk, bf16x8 (&fa)[IM], bf16x8 (&fb)[2]) {
     const char* la = smem + stage * OPER_BYTES;
-    const char* lb = la + TM * ROW_BYTES;
+    const char* lb = la + A_BYTES;
 #pragma unroll
     for (int im = 0; im < IM; ++im)
-      fa[im] = *reinterpret_cast<const bf16x8*>(la + lds_off(wm * (TM / 2) + im * 32 + frag_row, kk * 2 + frag_g));
+      fa[im] = *reinterpret_cast<const bf16x8*>(la + TileLayout<AT>::off(wm * (TM / 2) + im * 32 + frag_row, kk * 2 + frag_g));
 #pragma unroll
     for (int jn = 0; jn < 2; ++jn)
-      fb[jn] = *reinterpret_cast<const bf16x8*>(lb + lds_off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
+      fb[jn] = *reinterpret_cast<const bf16x8*>(lb + TileLayout<BT>::off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
   };
   // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k
   const bool do_colsum = p.colsum != nullptr && m0 == 0;
@@ -255,7 +267,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
   // that the LDS writes and the fragment reads of the following k-step run under the matrix pipe.
   auto multiply = [&](int stage, const TileRegs& rn, bool stage_next) {
     if (do_colsum) {   // thread (row = tid/2, half = tid%2) sums 4 of the row's 8 granules; their order is irrelevant
-      const char* rowp = smem + stage * OPER_BYTES + TM * ROW_BYTES + (tid >> 1) * ROW_BYTES + (tid & 1) * 64;
+      const char* rowp = smem + stage * OPER_BYTES + A_BYTES + (tid >> 1) * TileLayout<BT>::ROW + (tid & 1) * 64;
 #pragma unroll
       for (int gq = 0; gq < 4; ++gq) {
         uint4 w = *reinterpret_cast<const uint4*>(rowp + gq * 16);
@@ -551,7 +563,7 @@ bool gemm_mfma_groupable(const GemmArgs& g) {
 int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n) {
   static bool lds_opted_in = false;
   if (!lds_opted_in) {
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, true, 128)));
     lds_opted_in = true;
   }
   for (int j0 = 0; j0 < n; j0 += GROUP_MAX) {
@@ -580,7 +592,7 @@ int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n) {
 #endif
     void* prof = nullptr;
     PPLL_TRY(profile_begin(s, flops, &prof));
-    hipLaunchKernelGGL(gemm_mfma_grouped_kernel, dim3(8 * a.per_xcd), dim3(256), lds_bytes(128), s, a);
+    hipLaunchKernelGGL(gemm_mfma_grouped_kernel, dim3(8 * a.per_xcd), dim3(256), lds_bytes(true, true, 128), s, a);
     PPLL_HIP(hipGetLastError());
     PPLL_TRY(profile_end(s, prof));
   }
@@ -630,21 +642,21 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   if (p.xcd_map == 2) grid = dim3(p.tiles_m * p.tiles_n * splits, 1);
   static bool lds_opted_in = false;   // > 64 KB of dynamic LDS needs a one-time opt-in per kernel
   if (!lds_opted_in) {
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
-    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, true, 128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, false, 128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(false, true, 128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(false, false, 128)));
     lds_opted_in = true;
   }
   void* prof = nullptr;
   PPLL_TRY(profile_begin(s, 2.0 * g.M * g.N * g.K, &prof));
   if (small_m) {
-    if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 64>), grid, dim3(256), lds_bytes(64), s, p);
-    else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 64>), grid, dim3(256), lds_bytes(64), s, p);
-  } else if (at && bt) hipLaunchKernelGGL((gemm_mfma_kernel<true, true, 128>), grid, dim3(256), lds_bytes(128), s, p);
-  else if (at) hipLaunchKernelGGL((gemm_mfma_kernel<true, false, 128>), grid, dim3(256), lds_bytes(128), s, p);
-  else if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 128>), grid, dim3(256), lds_bytes(128), s, p);
-  else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 128>), grid, dim3(256), lds_bytes(128), s, p);
+    if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 64>), grid, dim3(256), lds_bytes(false, true, 64), s, p);
+    else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 64>), grid, dim3(256), lds_bytes(false, false, 64), s, p);
+  } else if (at && bt) hipLaunchKernelGGL((gemm_mfma_kernel<true, true, 128>), grid, dim3(256), lds_bytes(true, true, 128), s, p);
+  else if (at) hipLaunchKernelGGL((gemm_mfma_kernel<true, false, 128>), grid, dim3(256), lds_bytes(true, false, 128), s, p);
+  else if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 128>), grid, dim3(256), lds_bytes(false, true, 128), s, p);
+  else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 128>), grid, dim3(256), lds_bytes(false, false, 128), s, p);
   PPLL_HIP(hipGetLastError());
   PPLL_TRY(profile_end(s, prof));
   if (splits > 1) {
