@@ -189,6 +189,7 @@ size_t Block::plan(char* base) {
       size_t eb = (size_t)embed_bwd_partial_floats(B, T, D);
       if (eb > partial_floats) partial_floats = eb;
     }
+    if (vit_head_partial_floats(B, D, C) > partial_floats) partial_floats = vit_head_partial_floats(B, D, C);
   } else {
     const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
     const size_t act = (size_t)B * Hh * W * Ch;
@@ -222,7 +223,8 @@ size_t Block::plan(char* base) {
     const size_t M = (size_t)B * T;
     const int widest = cfg.mlp_dim > 3 * D ? cfg.mlp_dim : 3 * D;
     arena_floats = (size_t)(2 * (cfg.depth + cfg.aux_depth)) * (layernorm_bwd_partial_floats((int)M, D) + 64) +
-                   (size_t)layernorm_bwd_partial_floats(B, D) + (size_t)colsum_partial_floats(B, C) + 256;
+                   (size_t)layernorm_bwd_partial_floats(B, D) + (size_t)colsum_partial_floats(B, C) + 256 +
+                   vit_head_partial_floats(B, D, C) + 64;
     if (cfg.input_kind == PPLL_IN_IMAGE)
       arena_floats += (size_t)embed_bwd_partial_floats(B, T, D) + (size_t)colsum_partial_floats((int)M, D) + 128;
     if (!(dt == BF16))   // the generic GEMM does not fold bias gradients: one column sum per Linear layer
@@ -353,28 +355,36 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     PPLL_TRY(encoder_fwd(l, x, enc_a[l].x2, s));
     x = enc_a[l].x2;
   }
-  PPLL_TRY(launch_layernorm_fwd(s, x, dt, (long)T * D, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, z,
-                                head_mean, head_rstd));
   GemmArgs g = gemm_args();
-  g.A = z; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
-  g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
-  g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = D; g.bias = params + head_b;
-  PPLL_TRY(launch_gemm_generic(s, g));
-  // ---- local loss
-  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, loss_copy, dlogits, grads + head_b, flag_dev));
-  // ---- backward: head
-  g = gemm_args();
-  g.A = z; g.a_dt = dt; g.a_sm = 1; g.a_sk = D;
-  g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
-  g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = D; g.N = C; g.K = B;
-  PPLL_TRY(launch_gemm_generic(s, g));
-  g = gemm_args();
-  g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
-  g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
-  g.C = dz; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = C;
-  PPLL_TRY(launch_gemm_generic(s, g));
-  PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
-                                rq, grads + head_ln_g, grads + head_ln_b));
+  if (vit_head_fused_ok(D, C)) {
+    // ---- auxiliary head, local loss and the head's backward in one launch
+    PPLL_TRY(launch_vit_head(s, x, dt, (long)T * D, B, D, C, params + head_ln_g, params + head_ln_b, cfg.ln_eps,
+                             params + head_w, params + head_b, labels, dcls, rq, grads + head_ln_g, grads + head_ln_b,
+                             grads + head_w, grads + head_b, loss_dev, loss_copy, flag_dev));
+  } else {
+    PPLL_TRY(launch_layernorm_fwd(s, x, dt, (long)T * D, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, z,
+                                  head_mean, head_rstd));
+    g = gemm_args();
+    g.A = z; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+    g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+    g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = D; g.bias = params + head_b;
+    PPLL_TRY(launch_gemm_generic(s, g));
+    // ---- local loss
+    PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, loss_copy, dlogits, grads + head_b, flag_dev));
+    // ---- backward: head
+    g = gemm_args();
+    g.A = z; g.a_dt = dt; g.a_sm = 1; g.a_sk = D;
+    g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+    g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = D; g.N = C; g.K = B;
+    PPLL_TRY(launch_gemm_generic(s, g));
+    g = gemm_args();
+    g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
+    g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
+    g.C = dz; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = C;
+    PPLL_TRY(launch_gemm_generic(s, g));
+    PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
+                                  rq, grads + head_ln_g, grads + head_ln_b));
+  }
   wgrad_jobs.clear();
   PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, g_res[L + A]));
   // ---- backward: auxiliary layers then module layers; the chain stops at x_in

@@ -144,6 +144,15 @@ int colsum_partial_floats(int rows, int N);
 int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labels, int B, int C,
                          float* loss, float* loss2, float* dlogits, float* dbias, int* flag);
 
+// ViT auxiliary head in one launch: z = LN(x[:, 0, :]), logits = z W + b, mean cross-entropy, and back to
+// dcls = dL/dx[:, 0, :]; the batch sums (loss, dW, db, LayerNorm dg / db) go through the reduction queue.
+size_t vit_head_partial_floats(int B, int D, int C);
+bool vit_head_fused_ok(int D, int C);
+int launch_vit_head(hipStream_t s, const void* x, int dt, long x_row_stride, int B, int D, int C, const float* ln_g,
+                    const float* ln_b, float eps, const float* W, const float* bias, const int32_t* labels, void* dcls,
+                    ReduceQueue& rq, float* d_ln_g, float* d_ln_b, float* dW, float* dbias, float* loss, float* loss2,
+                    int* flag);
+
 // ---------------------------------------------------------------- ViT pieces
 int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W, int C, int P, void* patches);
 int launch_assemble_tokens(hipStream_t s, const void* E, int dt, const float* cls, const float* pos, int B,

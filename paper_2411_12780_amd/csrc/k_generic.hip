@@ -598,6 +598,135 @@ int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labe
   return PPLL_OK;
 }
 
+// ===================================================================== ViT auxiliary head, fused
+namespace {
+// LayerNorm of the class token, Linear to the classes, mean softmax cross-entropy, and everything
+// back to the gradient of the class token, for 4 batch rows per workgroup (one wave each).  Values
+// that the unfused kernels keep in the activation type (z = LN output, dz) are rounded to it here as
+// well.  What has to be summed over the batch (loss, head weight / bias gradient, LayerNorm scale /
+// shift gradient) leaves as one partial row per workgroup: [D*C | C | D | D | 1] floats.
+constexpr int HEAD_ROWS = 4;
+__device__ __forceinline__ float round_to(float v, int dt) { return dt == BF16 ? bf16_to_f32(f32_to_bf16(v)) : v; }
+__global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, long xs, int B, int D, int C,
+                                                       const float* ln_g, const float* ln_b, float eps,
+                                                       const float* W, const float* bias, const int32_t* labels,
+                                                       void* dcls, float* partial, int* flag) {
+  extern __shared__ float sm[];
+  float* xh = sm;                               // [4][D] normalised input
+  float* zs = xh + HEAD_ROWS * D;               // [4][D] LayerNorm output
+  float* dzs = zs + HEAD_ROWS * D;              // [4][D] gradient at the LayerNorm output
+  float* dl = dzs + HEAD_ROWS * D;              // [4][C] logits, then dlogits
+  float* lossw = dl + HEAD_ROWS * C;            // [4]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int b = blockIdx.x * HEAD_ROWS + wave;
+  const bool live = b < B;
+  float* xr = xh + wave * D; float* zr = zs + wave * D; float* dzr = dzs + wave * D; float* lr = dl + wave * C;
+  float rs = 0.f;
+  if (live) {
+    const size_t base = (size_t)b * xs;
+    float s = 0.f;
+    for (int d = lane; d < D; d += 64) { const float v = ld_f(x, base + d, dt); xr[d] = v; s += v; }
+    const float mu = wave_sum(s) / D;
+    float q = 0.f;
+    for (int d = lane; d < D; d += 64) { const float c = xr[d] - mu; q += c * c; }
+    rs = rsqrtf(wave_sum(q) / D + eps);
+    for (int d = lane; d < D; d += 64) {
+      const float h = (xr[d] - mu) * rs;
+      xr[d] = h;
+      zr[d] = round_to(h * ln_g[d] + ln_b[d], dt);
+    }
+    wave_sync();
+    for (int c = 0; c < C; ++c) {
+      float a = 0.f;
+      for (int d = lane; d < D; d += 64) a += zr[d] * W[(size_t)d * C + c];
+      a = wave_sum(a);
+      if (lane == 0) lr[c] = a + bias[c];
+    }
+    wave_sync();
+    float mx = -INFINITY;
+    for (int c = lane; c < C; c += 64) mx = fmaxf(mx, lr[c]);
+    mx = wave_max(mx);
+    float se = 0.f;
+    for (int c = lane; c < C; c += 64) se += expf(lr[c] - mx);
+    const float lse = mx + logf(wave_sum(se));
+    const int y = labels[b];
+    const bool ok = y >= 0 && y < C;
+    if (!ok && lane == 0) *flag = 1;
+    const float mine = ok ? lse - lr[y] : 0.f;
+    wave_sync();
+    for (int c = lane; c < C; c += 64) lr[c] = (expf(lr[c] - lse) - ((ok && c == y) ? 1.f : 0.f)) / B;
+    if (lane == 0) lossw[wave] = mine;
+    wave_sync();
+    float s1 = 0.f, s2 = 0.f;
+    for (int d = lane; d < D; d += 64) {
+      float a = 0.f;
+      for (int c = 0; c < C; ++c) a += lr[c] * W[(size_t)d * C + c];
+      a = round_to(a, dt);
+      dzr[d] = a;
+      const float dyh = a * ln_g[d];
+      s1 += dyh; s2 += dyh * xr[d];
+    }
+    s1 = wave_sum(s1) / D; s2 = wave_sum(s2) / D;
+    for (int d = lane; d < D; d += 64)
+      st_f(dcls, (size_t)b * D + d, rs * (dzr[d] * ln_g[d] - s1 - xr[d] * s2), dt);
+  } else {
+    for (int d = lane; d < D; d += 64) { xr[d] = 0.f; zr[d] = 0.f; dzr[d] = 0.f; }
+    for (int c = lane; c < C; c += 64) lr[c] = 0.f;
+    if (lane == 0) lossw[wave] = 0.f;
+  }
+  __syncthreads();
+  float* out = partial + (size_t)blockIdx.x * ((size_t)D * C + C + 2 * D + 1);
+  for (int i = threadIdx.x; i < D * C; i += 256) {
+    const int d = i / C, c = i % C;
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < HEAD_ROWS; ++w) t += zs[w * D + d] * dl[w * C + c];
+    out[i] = t;
+  }
+  float* o2 = out + (size_t)D * C;
+  for (int c = threadIdx.x; c < C; c += 256) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < HEAD_ROWS; ++w) t += dl[w * C + c];
+    o2[c] = t;
+  }
+  float* o3 = o2 + C;
+  for (int d = threadIdx.x; d < D; d += 256) {
+    float tg = 0.f, tb = 0.f;
+#pragma unroll
+    for (int w = 0; w < HEAD_ROWS; ++w) { tg += dzs[w * D + d] * xh[w * D + d]; tb += dzs[w * D + d]; }
+    o3[d] = tg; o3[D + d] = tb;
+  }
+  if (threadIdx.x == 0) o3[2 * D] = lossw[0] + lossw[1] + lossw[2] + lossw[3];
+}
+}  // namespace
+
+size_t vit_head_partial_floats(int B, int D, int C) {
+  return (size_t)((B + HEAD_ROWS - 1) / HEAD_ROWS) * ((size_t)D * C + C + 2 * D + 1);
+}
+bool vit_head_fused_ok(int D, int C) { return ((size_t)3 * HEAD_ROWS * D + HEAD_ROWS * C + HEAD_ROWS) * sizeof(float) <= 64 * 1024; }
+
+int launch_vit_head(hipStream_t s, const void* x, int dt, long xs, int B, int D, int C, const float* ln_g,
+                    const float* ln_b, float eps, const float* W, const float* bias, const int32_t* labels, void* dcls,
+                    ReduceQueue& rq, float* d_ln_g, float* d_ln_b, float* dW, float* dbias, float* loss, float* loss2,
+                    int* flag) {
+  const int chunks = (B + HEAD_ROWS - 1) / HEAD_ROWS;
+  const long P = (long)D * C + C + 2 * D + 1;
+  bool queued;
+  float* partials = rq.space((size_t)chunks * P, &queued);
+  const size_t lds = ((size_t)3 * HEAD_ROWS * D + HEAD_ROWS * C + HEAD_ROWS) * sizeof(float);
+  hipLaunchKernelGGL(vit_head_kernel, dim3(chunks), dim3(256), lds, s, x, dt, xs, B, D, C, ln_g, ln_b, eps, W, bias, labels,
+                     dcls, partials, flag);
+  PPLL_HIP(hipGetLastError());
+  PPLL_TRY(rq.reduce(s, queued, partials, chunks, D * C, P, 1.0f, dW));
+  PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C, chunks, C, P, 1.0f, dbias));
+  PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C, chunks, D, P, 1.0f, d_ln_g));
+  PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C + D, chunks, D, P, 1.0f, d_ln_b));
+  PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C + 2 * D, chunks, 1, P, 1.0f / B, loss));
+  if (loss2) PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C + 2 * D, chunks, 1, P, 1.0f / B, loss2));
+  return PPLL_OK;
+}
+
 // ===================================================================== ViT embedding pieces
 namespace {
 __global__ __launch_bounds__(256) void patchify_kernel(const void* img, int dt, int B, int H, int W, int C, int P,

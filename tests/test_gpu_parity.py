@@ -197,6 +197,15 @@ def test_vit_bf16_widths_of_the_fast_layernorm(dim, heads):
     run_case(wl, steps=1)
 
 
+@pytest.mark.parametrize("dim,heads,classes", [(128, 2, 200), (1024, 16, 1024)])
+def test_vit_bf16_head_with_many_classes(dim, heads, classes):
+    # 200 classes: more classes than lanes in the fused head kernel; 1024 x 1024: too large for its LDS,
+    # so the head runs as separate LayerNorm / Linear / cross-entropy kernels
+    wl = synth.workload("vit_stage_act_bf16", batch=5, tokens=8, dim=dim, heads=heads, mlp_dim=2 * dim, depth=1,
+                        aux_depth=1, num_classes=classes)
+    run_case(wl, steps=1)
+
+
 def test_resnet_fp32_stage_full_size_decisive_masks():
     # not a named workload: fp32 at the full ResNet size.  Gradients pass 10 BatchNorm backward
     # stages, each a cancelling 32768-term reduction in fp32, so 1e-3 instead of 1e-4
