@@ -610,13 +610,20 @@ __device__ __forceinline__ float round_to(float v, int dt) { return dt == BF16 ?
 __global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, long xs, int B, int D, int C,
                                                        const float* ln_g, const float* ln_b, float eps,
                                                        const float* W, const float* bias, const int32_t* labels,
-                                                       void* dcls, float* partial, int* flag) {
+                                                       void* dcls, float* partial, int* flag, int w_in_lds) {
   extern __shared__ float sm[];
   float* xh = sm;                               // [4][D] normalised input
   float* zs = xh + HEAD_ROWS * D;               // [4][D] LayerNorm output
   float* dzs = zs + HEAD_ROWS * D;              // [4][D] gradient at the LayerNorm output
   float* dl = dzs + HEAD_ROWS * D;              // [4][C] logits, then dlogits
   float* lossw = dl + HEAD_ROWS * C;            // [4]
+  // the head weight, read 2 C times per row, comes from LDS when there is room for it
+  if (w_in_lds) {
+    float* wl = lossw + HEAD_ROWS;
+    for (int i = threadIdx.x; i < D * C; i += 256) wl[i] = W[i];
+    __syncthreads();
+    W = wl;
+  }
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int b = blockIdx.x * HEAD_ROWS + wave;
   const bool live = b < B;
@@ -704,7 +711,10 @@ __global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, lo
 size_t vit_head_partial_floats(int B, int D, int C) {
   return (size_t)((B + HEAD_ROWS - 1) / HEAD_ROWS) * ((size_t)D * C + C + 2 * D + 1);
 }
-bool vit_head_fused_ok(int D, int C) { return ((size_t)3 * HEAD_ROWS * D + HEAD_ROWS * C + HEAD_ROWS) * sizeof(float) <= 64 * 1024; }
+static size_t vit_head_lds(int D, int C, bool with_w) {
+  return ((size_t)3 * HEAD_ROWS * D + HEAD_ROWS * C + HEAD_ROWS + (with_w ? (size_t)D * C : 0)) * sizeof(float);
+}
+bool vit_head_fused_ok(int D, int C) { return vit_head_lds(D, C, false) <= 64 * 1024; }
 
 int launch_vit_head(hipStream_t s, const void* x, int dt, long xs, int B, int D, int C, const float* ln_g,
                     const float* ln_b, float eps, const float* W, const float* bias, const int32_t* labels, void* dcls,
@@ -714,9 +724,9 @@ int launch_vit_head(hipStream_t s, const void* x, int dt, long xs, int B, int D,
   const long P = (long)D * C + C + 2 * D + 1;
   bool queued;
   float* partials = rq.space((size_t)chunks * P, &queued);
-  const size_t lds = ((size_t)3 * HEAD_ROWS * D + HEAD_ROWS * C + HEAD_ROWS) * sizeof(float);
-  hipLaunchKernelGGL(vit_head_kernel, dim3(chunks), dim3(256), lds, s, x, dt, xs, B, D, C, ln_g, ln_b, eps, W, bias, labels,
-                     dcls, partials, flag);
+  const bool with_w = vit_head_lds(D, C, true) <= 64 * 1024;
+  hipLaunchKernelGGL(vit_head_kernel, dim3(chunks), dim3(256), vit_head_lds(D, C, with_w), s, x, dt, xs, B, D, C, ln_g, ln_b,
+                     eps, W, bias, labels, dcls, partials, flag, (int)with_w);
   PPLL_HIP(hipGetLastError());
   PPLL_TRY(rq.reduce(s, queued, partials, chunks, D * C, P, 1.0f, dW));
   PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C, chunks, C, P, 1.0f, dbias));
@@ -807,6 +817,34 @@ __global__ __launch_bounds__(256) void embed_bwd_kernel(const void* dx, int dt, 
   partial[(size_t)blockIdx.y * T * D + i] = acc;
 }
 
+// bf16, D a multiple of 8: a thread takes 8 consecutive d of one token and the chunk's 8 batch entries,
+// whose loads are issued together; the sum still runs in batch order
+__global__ __launch_bounds__(256) void embed_bwd_bf16_kernel(const uint16_t* dx, int B, int T, int D, float* partial,
+                                                             uint16_t* dE) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;   // over [T, D]
+  if (i >= (size_t)T * D) return;
+  const int d = i % D, t = i / D;
+  const int b0 = blockIdx.y * EMB_ROWS;
+  uint4 v[EMB_ROWS];
+#pragma unroll
+  for (int u = 0; u < EMB_ROWS; ++u) {
+    v[u] = make_uint4(0, 0, 0, 0);
+    if (b0 + u < B) v[u] = *reinterpret_cast<const uint4*>(dx + ((size_t)(b0 + u) * T + t) * D + d);
+  }
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int u = 0; u < EMB_ROWS; ++u) {
+    if (b0 + u >= B) break;
+    const uint32_t* w = reinterpret_cast<const uint32_t*>(&v[u]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { acc[2 * e] += __uint_as_float(w[e] << 16); acc[2 * e + 1] += __uint_as_float(w[e] & 0xffff0000u); }
+    if (t > 0) *reinterpret_cast<uint4*>(dE + ((size_t)(b0 + u) * (T - 1) + (t - 1)) * D + d) = v[u];
+  }
+  float* out = partial + (size_t)blockIdx.y * T * D + i;
+  *reinterpret_cast<float4*>(out) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+  *reinterpret_cast<float4*>(out + 4) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+}
+
 __global__ __launch_bounds__(256) void scatter_cls_kernel(const void* dcls, int dt, int B, int T, int D, void* dx) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= (size_t)B * T * D) return;
@@ -840,7 +878,11 @@ int launch_embed_bwd(hipStream_t s, const void* dx, int dt, int B, int T, int D,
   const int total = T * D, chunks = (B + EMB_ROWS - 1) / EMB_ROWS;
   bool queued;
   float* partials = rq.space((size_t)chunks * total, &queued);
-  hipLaunchKernelGGL(embed_bwd_kernel, dim3((total + 255) / 256, chunks), dim3(256), 0, s, dx, dt, B, T, D, partials, dE);
+  if (dt == BF16 && !(D & 7) && !((((uintptr_t)dx) | ((uintptr_t)dE) | ((uintptr_t)partials)) & 15))
+    hipLaunchKernelGGL(embed_bwd_bf16_kernel, dim3((total / 8 + 255) / 256, chunks), dim3(256), 0, s, (const uint16_t*)dx, B,
+                       T, D, partials, (uint16_t*)dE);
+  else
+    hipLaunchKernelGGL(embed_bwd_kernel, dim3((total + 255) / 256, chunks), dim3(256), 0, s, dx, dt, B, T, D, partials, dE);
   PPLL_HIP(hipGetLastError());
   PPLL_TRY(rq.reduce(s, queued, partials, chunks, total, total, 1.0f, dpos));
   return rq.reduce(s, queued, partials, chunks, D, total, 1.0f, dcls);   // the cls row is token 0
