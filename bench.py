@@ -54,10 +54,16 @@ def measured_traffic(workload: str):
 
 
 def bench_pipeline(args, torch, P, synth, dev) -> int:
-    """configs[4]: the 12-layer ViT as 4 blocks of 3 layers on 4 HIP streams, depth-2 device queues.
-    A step is one batch entering the pipeline; timing is steady state (queues full)."""
-    first, rest = synth.workload("vit_stage_bf16"), synth.workload("vit_stage_act_bf16")
-    wls = [first, rest, rest, rest]
+    """configs[4]: the 12-layer ViT as 4 blocks of 3 layers on 4 HIP streams, depth-2 device queues
+    (vit_lpp12: as 12 blocks of one layer on 12 streams).  A step is one batch entering the pipeline;
+    timing is steady state (queues full)."""
+    if args.workload == "vit_lpp12":
+        # Section 4.2's finest partition: 12 one-layer blocks, auxiliary depths from the d' = 4 schedule
+        wls = synth.lpp_workloads(4)
+        first = wls[0]
+    else:
+        first, rest = synth.workload("vit_stage_bf16"), synth.workload("vit_stage_act_bf16")
+        wls = [first, dict(rest), dict(rest), dict(rest)]
     for j, w in enumerate(wls):
         w["seed"] = j
     cfgs = [P.make_config(w) for w in wls]
@@ -92,8 +98,9 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
         "value": first["batch"] / (elapsed / args.steps), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": max(args.warmup, 8), "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "vit_pipeline4", "batch": first["batch"], "blocks": 4, "queue_depth": depth,
-                   "streams": 4, "optimizer": "adamw"},
+        "config": {"workload": args.workload, "batch": first["batch"], "blocks": len(cfgs), "queue_depth": depth,
+                   "streams": len(cfgs), "optimizer": "adamw",
+                   "layers_per_block": [w["depth"] for w in wls], "aux_depths": [w["aux_depth"] for w in wls]},
         "step_gflop": flops / 1e9, "step_tflops": flops / (elapsed / args.steps) / 1e12,
         "mfma_peak_frac_step": flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
         "losses_last_batch": [float(v) for v in losses],
@@ -126,7 +133,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     dev = "cuda:0"
-    if args.workload == "vit_pipeline4":
+    if args.workload in ("vit_pipeline4", "vit_lpp12"):
         return bench_pipeline(args, torch, P, synth, dev)
     wl = synth.workload(args.workload)
     wl["seed"] = 0

@@ -50,6 +50,28 @@ def workload(name: str, **overrides) -> dict:
     return wl
 
 
+def aux_depth_schedule(d_max: int, n_blocks: int = 12, n: int = 3) -> list:
+    """Depth of the auxiliary network of local block l (0-based) of a ViT cut into n_blocks local
+    blocks: N_l = d' - floor(l / n) with n = 3 (Section 4.2, the auxiliary-depth heuristic), d' the
+    maximum depth (2, 3 or 4 in the paper).  The formula goes negative for d' < 4 and l >= 3 d';
+    a block cannot have fewer than zero auxiliary layers, so it is floored at 0 (head only)."""
+    return [max(0, d_max - l // n) for l in range(n_blocks)]
+
+
+def lpp_workloads(d_max: int, n_blocks: int = 12, **overrides) -> list:
+    """The finest partition of Section 4.2 ("largest pipeline parallelism"): every encoder layer of
+    the ViT is a local block of its own, with the auxiliary depth of aux_depth_schedule().  Block 0
+    takes images, the others the token activations of their predecessor."""
+    out = []
+    for l, a in enumerate(aux_depth_schedule(d_max, n_blocks)):
+        wl = workload("vit_stage_bf16" if l == 0 else "vit_stage_act_bf16", depth=1, aux_depth=a)
+        wl.update(overrides)
+        if l > 0:
+            wl["input_kind"] = ACTIVATION
+        out.append(wl)
+    return out
+
+
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """fp32 values rounded to the nearest bf16-representable value (ties to even),
     returned as fp32."""

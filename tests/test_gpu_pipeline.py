@@ -130,6 +130,28 @@ def test_pipeline_four_vit_blocks_bf16_full_size():
     assert np.abs(seq_losses[0] - ref_losses[0]).max() <= 2e-2 * np.abs(ref_losses[0]).max()
 
 
+@pytest.mark.parametrize("d_max", [2, 4])
+def test_pipeline_twelve_one_layer_blocks_with_the_aux_depth_schedule(d_max):
+    """The finest partition of Section 4.2: 12 local blocks of one encoder layer each on 12 streams, auxiliary
+    depths N_l = max(0, d' - floor(l/3)) (d' = 2 ends in six blocks with no auxiliary layer at all)."""
+    small = dict(batch=4, dim=128, heads=2, mlp_dim=256, precision=synth.FP32, optimizer=synth.SGD, momentum=0.0,
+                 nesterov=0, weight_decay=0.0, lr=0.01)
+    wls = synth.lpp_workloads(d_max, **small)
+    flats = [synth.make_params(O.param_spec(oracle_cfg(w)), seed=20 + j, jitter=True) for j, w in enumerate(wls)]
+    batches = [synth.make_batch(wls[0], seed=7, index=i) for i in range(3)]
+    seq_losses, seq_params = _run_sequential(wls, flats, batches, 0.01)
+    losses, params = _run_pipeline(wls, flats, batches, 2, 0.01)
+    assert np.array_equal(losses, seq_losses)
+    for j in range(12):
+        for a, b in zip(params[j], seq_params[j]):
+            assert np.array_equal(a, b), j
+    ref_losses, states = _oracle_chain(wls, flats, batches, 0.01)
+    assert np.abs(seq_losses - ref_losses).max() <= 1e-4 * np.abs(ref_losses).max()
+    for j, st in enumerate(states):
+        for (name, _), got in zip(O.param_spec(st.cfg), seq_params[j]):
+            assert rel_l2(got, st.params[name]) <= 1e-4, (j, name)
+
+
 def test_pipeline_runs_ahead_without_host_syncs():
     """Enqueue several batches back to back (no sync in between): the bounded queues and the
     event edges alone must keep the order; results equal the synchronised run."""
