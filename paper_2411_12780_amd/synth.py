@@ -39,6 +39,13 @@ WORKLOADS = {
                               n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
                               nesterov=1, weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1,
                               lr=0.01),
+    # the paper's own ViT shape (Section 4.1: ViT-base-patch16 on 32x32 images, batch 128: 4 patches + class
+    # token = 5 tokens of width 768, 12 heads, MLP 3072), one stage of 3 layers with a 1-layer auxiliary
+    # network, trained with the paper's optimizer (SGD, Nesterov 0.9, L2 1e-4, lr 0.01)
+    "vit_base_paper_bf16": dict(arch=VIT, precision=BF16, input_kind=IMAGE, batch=128, num_classes=10,
+                                img_h=32, img_w=32, img_c=3, patch=16, tokens=5, dim=768, heads=12,
+                                mlp_dim=3072, depth=3, aux_depth=1, optimizer=SGD, momentum=0.9, nesterov=1,
+                                weight_decay=1e-4, ln_eps=1e-6, lr=0.01),
     # configs[3]: STL-10-shaped ViT stage
     "vit_large_image_bf16": dict(_VIT_STAGE, batch=64, img_h=96, img_w=96, patch=8, tokens=145),
 }

@@ -264,6 +264,11 @@ def test_vit_stage_bf16_full_size():
     run_case(synth.workload("vit_stage_bf16"), steps=1)
 
 
+def test_vit_base_paper_shape_bf16_full_size():
+    # the paper's ViT-Base stage: 640 rows of width 768, K = 768 patch embedding, 5-token attention, SGD Nesterov
+    run_case(synth.workload("vit_base_paper_bf16"), steps=2)
+
+
 def test_vit_large_image_bf16_full_size():
     run_case(synth.workload("vit_large_image_bf16"), steps=1)
 
