@@ -106,6 +106,53 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
         "losses_last_batch": [float(v) for v in losses],
     }
     P.ppll_pipeline_destroy(pipe)
+    del ws
+
+    # Conventional local learning on the same GPU: the same blocks, one after the other on one stream
+    # (the sequential chain the pipeline is bit-identical to), and the stage-1 phase times in the
+    # symbols of the paper's time model (Section 3.3).
+    tdt = torch.bfloat16
+    blocks, keep = [], []
+    for w, c in zip(wls, cfgs):
+        n = P.ppll_block_workspace_bytes(c)
+        buf = torch.empty(n, dtype=torch.uint8, device=dev)
+        blocks.append(P.ppll_block_init(c, buf, n, None, None))
+        keep.append((buf, torch.empty(synth.output_shape(w), dtype=tdt, device=dev),
+                     torch.zeros(1, dtype=torch.float32, device=dev)))
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run_seq(n):
+        for i in range(n):
+            cur = xs[i % ring]
+            for b, (_, xo, ls) in zip(blocks, keep):
+                P.ppll_block_step(b, cur, ys[i % ring], lr, xo, ls, stream)
+                cur = xo
+
+    run_seq(max(args.warmup, 3))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_seq(args.steps)
+    torch.cuda.synchronize()
+    seq_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    P.ppll_block_phase_timers(blocks[0], True)
+    run_seq(3)
+    f1, fa, Bp, Up = P.ppll_block_phase_times(blocks[0])
+    P.ppll_block_phase_timers(blocks[0], False)
+    s_stages = len(wls)
+    k_layers = wls[0]["aux_depth"] / wls[0]["depth"]
+    out["sequential_chain_ms_per_step"] = seq_ms
+    out["pipelined_over_sequential"] = out["ms_per_step"] / seq_ms
+    out["time_model"] = {
+        "stage1_phases_ms": {"f_1": f1, "f_a1": fa, "B_a1": Bp, "U_a1": Up},
+        "S_PPLL_stage1_ms": f1 + fa + Bp + Up,
+        "s": s_stages, "k_aux_over_module_layers": k_layers, "k_measured_f_a1_over_f_1": fa / f1 if f1 > 0 else None,
+        "predicted_T_PPLL_over_T_PP": (k_layers + 1) / s_stages,
+        "note": "Section 3.3.1 predicts T_PPLL / T_PP = (k + 1) / s for s devices; on one GPU the blocks share the "
+                "device, so the measured pipelined / sequential ratio above is bounded below by the chip's idle "
+                "fraction, not by 1 / s",
+    }
+    for b in blocks:
+        P.ppll_block_destroy(b)
     print(json.dumps(out))
     return 0
 
@@ -202,6 +249,14 @@ def main() -> int:
                                "avg_launch_us": 1e3 * gemm_ms / launches,
                                "gemm_ms_per_step": gemm_ms / args.steps,
                                "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
+
+    if not args.no_roofline:
+        # third pass: phase times of the step in the paper's symbols (Section 3.3)
+        P.ppll_block_phase_timers(blk, True)
+        run(3)
+        f1, fa, Bp, Up = P.ppll_block_phase_times(blk)
+        P.ppll_block_phase_timers(blk, False)
+        out["phases_ms"] = {"f_1": f1, "f_a1": fa, "B_a1": Bp, "U_a1": Up}
 
     if args.probe_copy:
         nbytes = 256 << 20

@@ -184,6 +184,16 @@ int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
 int ppll_profile_enable(int32_t on);
 int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
 
+/* Phase timers in the symbols of the paper's time model (Section 3.3: S_PPLL = f_1 + f_a1 + B_a1 +
+ * U_a1): with timers on, every step of the block records HIP events on its stream at the ends of
+ * the module forward (f), the auxiliary forward with the local loss (f_a), the backward through
+ * auxiliary network and module including all parameter gradients (B), and the update (U).
+ * ppll_block_phase_times waits for the block's last step and writes its four durations in
+ * milliseconds to ms[0..3] (host memory) in that order; PPLL_ERR_STATE if timers are off or no step
+ * has run.  The events cost a little host time per step: leave timers off when timing whole steps. */
+int ppll_block_phase_timers(ppll_block_t* block, int32_t on);
+int ppll_block_phase_times(ppll_block_t* block, float* ms);
+
 /* Measurement aid: one plain copy kernel (copy_probe_kernel) moving `bytes` (a multiple of 16)
  * from src_dev to dst_dev on `hip_stream`.  Its known traffic (bytes read, bytes written) is
  * what the hardware byte counters of a profiler run are scaled against. */

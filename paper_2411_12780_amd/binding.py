@@ -80,6 +80,8 @@ _SIGS = {
     "ppll_pipeline_output": (C.c_int, [C.c_void_p, C.POINTER(C.c_void_p), C.POINTER(C.c_size_t)]),
     "ppll_pipeline_destroy": (C.c_int, [C.c_void_p]),
     "ppll_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "ppll_block_phase_timers": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ppll_block_phase_times": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
     "ppll_profile_enable": (C.c_int, [C.c_int32]),
     "ppll_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
@@ -242,6 +244,17 @@ def ppll_pipeline_output(pipe: int):
 
 def ppll_pipeline_destroy(pipe: int) -> None:
     _check(lib().ppll_pipeline_destroy(pipe))
+
+
+def ppll_block_phase_timers(block, on: bool) -> None:
+    _check(lib().ppll_block_phase_timers(block, 1 if on else 0))
+
+
+def ppll_block_phase_times(block):
+    """(f, f_a, B, U) of the block's last step in milliseconds."""
+    ms = (C.c_float * 4)()
+    _check(lib().ppll_block_phase_times(block, ms))
+    return tuple(float(v) for v in ms)
 
 
 def ppll_profile_enable(on: bool) -> None:

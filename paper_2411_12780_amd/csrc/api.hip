@@ -246,6 +246,28 @@ int ppll_block_sync(ppll_block_t* h, float* loss_host) {
   return PPLL_OK;
 }
 
+int ppll_block_phase_timers(ppll_block_t* h, int32_t on) {
+  PPLL_TRY(block_alive(h));
+  h->b.phase_timers = on != 0;
+  if (!on)
+    for (hipEvent_t& e : h->b.phase_ev) {
+      if (e) (void)hipEventDestroy(e);
+      e = nullptr;
+    }
+  return PPLL_OK;
+}
+
+int ppll_block_phase_times(ppll_block_t* h, float* ms) {
+  PPLL_TRY(block_alive(h));
+  if (!ms) { set_error("ms is null"); return PPLL_ERR_NULL; }
+  Block& b = h->b;
+  for (hipEvent_t e : b.phase_ev)
+    if (!b.phase_timers || !e) { set_error("phase timers are off or no step has run with them"); return PPLL_ERR_STATE; }
+  PPLL_HIP(hipEventSynchronize(b.phase_ev[4]));
+  for (int i = 0; i < 4; ++i) PPLL_HIP(hipEventElapsedTime(&ms[i], b.phase_ev[i], b.phase_ev[i + 1]));
+  return PPLL_OK;
+}
+
 int ppll_block_tensor_count(ppll_block_t* h, int32_t kind, int32_t* count) {
   PPLL_TRY(block_alive(h));
   if (!count) { set_error("count is null"); return PPLL_ERR_NULL; }
@@ -295,6 +317,10 @@ int ppll_block_destroy(ppll_block_t* h) {
   if (!h) { set_error("block handle is null"); return PPLL_ERR_NULL; }
   if (!h->b.alive) { set_error("block handle was destroyed"); return PPLL_ERR_STATE; }
   (void)hipStreamSynchronize(h->b.last_stream);
+  for (hipEvent_t& e : h->b.phase_ev) {
+    if (e) (void)hipEventDestroy(e);
+    e = nullptr;
+  }
   h->b.alive = false;   // the handle stays allocated so that later misuse is reported, not undefined
   return PPLL_OK;
 }

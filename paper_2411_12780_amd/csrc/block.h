@@ -85,6 +85,11 @@ struct Block {
   void *r_gA = nullptr, *r_gB = nullptr, *r_t1 = nullptr, *r_t2 = nullptr;
 
   float* loss_copy = nullptr;    // caller's loss slot of the step in flight (may be null)
+  // Phase timers (off by default): events at the boundaries of module forward, auxiliary forward +
+  // loss, backward, update, recorded on the step's stream.
+  bool phase_timers = false;
+  hipEvent_t phase_ev[5] = {};
+  int mark_phase(int i, hipStream_t s);
   long steps = 0;
   hipStream_t last_stream = nullptr;
 

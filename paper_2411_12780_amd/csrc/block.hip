@@ -348,6 +348,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     PPLL_TRY(encoder_fwd(l, x, dst, s));
     x = dst;
   }
+  PPLL_TRY(mark_phase(1, s));   // module forward done
   if (after_forward) PPLL_TRY(after_forward());
   // ---- auxiliary forward
   for (int l = L; l < L + A; ++l) {
@@ -385,6 +386,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
                                   rq, grads + head_ln_g, grads + head_ln_b));
   }
+  PPLL_TRY(mark_phase(2, s));   // auxiliary forward and loss done (the fused head kernel has also run its own backward)
   wgrad_jobs.clear();
   PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, g_res[L + A]));
   // ---- backward: auxiliary layers then module layers; the chain stops at x_in
@@ -444,6 +446,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, x, block_out[i]));
     x = block_out[i];
   }
+  PPLL_TRY(mark_phase(1, s));   // module forward done
   if (after_forward) PPLL_TRY(after_forward());
   // ---- auxiliary forward
   PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
@@ -457,6 +460,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = A; g.bias = params + head_b;
   PPLL_TRY(launch_gemm_generic(s, g));
   PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, loss_copy, dlogits, grads + head_b, flag_dev));
+  PPLL_TRY(mark_phase(2, s));   // auxiliary forward and loss done
   // ---- backward: head and auxiliary net
   g = gemm_args();
   g.A = pooled; g.a_dt = dt; g.a_sm = 1; g.a_sk = A;
@@ -500,15 +504,25 @@ int Block::update(float lr, hipStream_t s) {
   return launch_adamw(s, params, grads, mom1, mom2, shadow, P, lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay, bc1, bc2);
 }
 
+int Block::mark_phase(int i, hipStream_t s) {
+  if (!phase_timers) return PPLL_OK;
+  if (!phase_ev[i]) PPLL_HIP(hipEventCreate(&phase_ev[i]));
+  PPLL_HIP(hipEventRecord(phase_ev[i], s));
+  return PPLL_OK;
+}
+
 int Block::step(const void* x_in, const int32_t* labels, float lr, void* x_out, float* loss_out, hipStream_t s,
                 const std::function<int()>& after_forward) {
   last_stream = s;
   rq.reset();
   loss_copy = loss_out;   // the loss kernel writes it there as well
+  PPLL_TRY(mark_phase(0, s));
   if (cfg.arch == PPLL_VIT) PPLL_TRY(vit_step(x_in, labels, x_out, s, after_forward));
   else PPLL_TRY(resnet_step(x_in, labels, x_out, s, after_forward));
+  PPLL_TRY(mark_phase(3, s));   // backward done (weight gradients included); what follows is the update
   PPLL_TRY(rq.flush(s));
   PPLL_TRY(update(lr, s));
+  PPLL_TRY(mark_phase(4, s));
 
   return PPLL_OK;
 }

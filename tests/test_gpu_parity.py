@@ -274,6 +274,45 @@ def test_vit_large_image_bf16_full_size():
 
 
 # ------------------------------------------------------------------ error surfaced at sync
+def test_phase_timers_split_a_step_into_the_papers_four_terms():
+    """f_1, f_a1, B_a1, U_a1 of Section 3.3: four positive durations that add up to about the step time, leave
+    the step's results untouched, and are refused while the timers are off."""
+    import time
+    import torch
+    from paper_2411_12780_amd import binding as P
+    from gpu_harness import GpuBlock, to_device
+    wl = synth.workload("vit_stage_bf16", batch=16)
+    flat = synth.make_params(O.param_spec(oracle_cfg(wl)), seed=11, jitter=True)
+    x, y = synth.make_batch(wl, seed=11, index=0)
+    results = []
+    for timers in (False, True):
+        blk = GpuBlock(wl, flat)
+        xd, yd = to_device(x, wl), torch.from_numpy(y.astype(np.int32)).to("cuda:0")
+        stream = torch.cuda.current_stream().cuda_stream
+        if timers:
+            P.ppll_block_phase_timers(blk.h, True)
+        else:
+            with pytest.raises(RuntimeError):
+                P.ppll_block_phase_times(blk.h)
+        for _ in range(3):
+            P.ppll_block_step(blk.h, xd, yd, 1e-3, blk.x_out, blk.loss, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        P.ppll_block_step(blk.h, xd, yd, 1e-3, blk.x_out, blk.loss, stream)
+        loss = P.ppll_block_sync(blk.h)
+        wall_ms = 1e3 * (time.perf_counter() - t0)
+        if timers:
+            ms = P.ppll_block_phase_times(blk.h)
+            assert len(ms) == 4 and all(v > 0 for v in ms), ms
+            assert sum(ms) <= wall_ms * 1.05, (ms, wall_ms)
+            assert ms[2] > ms[0] and ms[2] > ms[1], ms       # the backward pass is the longest term
+        results.append((loss, [P.ppll_block_read_tensor(blk.h, P.T_PARAM, i) for i in range(len(blk.names))]))
+        blk.close()
+    assert results[0][0] == results[1][0]
+    for a, b in zip(results[0][1], results[1][1]):
+        assert np.array_equal(a, b)
+
+
 def test_out_of_range_label_is_reported_at_sync():
     from gpu_harness import GpuBlock
     from paper_2411_12780_amd import binding as P
