@@ -123,6 +123,17 @@ int ppll_block_init(const ppll_block_config* cfg, void* workspace_dev, size_t wo
 int ppll_block_step(ppll_block_t* blk, const void* x_in_dev, const int32_t* labels_dev, float lr,
                     void* x_out_dev, float* loss_dev, void* hip_stream);
 
+/* Evaluation-mode forward of the block (how the paper's accuracies, Section 4.4, are taken once
+ * training has run): x_out = M_j(x_in) with BatchNorm normalising by its running statistics; no
+ * loss, no gradients, no update, running statistics unchanged.  x_in_dev / x_out_dev as in
+ * ppll_block_step.  If logits_dev is non-null the block's auxiliary network is applied to x_out as
+ * well and its class scores, [batch, num_classes] fp32 (device memory, 16-byte aligned), are
+ * written there: for the last block of a network these are the network's predictions.  Enqueued
+ * on hip_stream; the block's activation scratch is overwritten, so it must not overlap a step of
+ * the same block in flight on another stream. */
+int ppll_block_forward_eval(ppll_block_t* block, const void* x_in_dev, void* x_out_dev, float* logits_dev,
+                            void* hip_stream);
+
 /* Waits for the stream of the last step; returns that step's loss in
  * *loss_host (nullable).  Reports PPLL_ERR_LABEL / PPLL_ERR_HIP raised since the
  * previous sync. */

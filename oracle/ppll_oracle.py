@@ -538,6 +538,37 @@ def resnet_backward(st: BlockState, dlogits, caches):
     return g
 
 
+def batchnorm_eval(x, g, b, mean, var, eps):
+    """Evaluation-mode BatchNorm: the affine map fixed by the running statistics."""
+    return (x - mean) / np.sqrt(var + eps) * g + b
+
+
+def block_forward_eval(st: BlockState, x_in):
+    """Evaluation-mode forward: (x_j, class scores of the auxiliary network).  No loss, no state
+    change; BatchNorm normalises with its running statistics.  A ViT block has no mode-dependent
+    layer (no dropout, LayerNorm only), so its evaluation forward is its training forward."""
+    if st.cfg.arch == ARCH_VIT:
+        x_out, logits, _ = vit_forward(st, x_in)
+        return x_out, logits
+    cfg, p, S, W = st.cfg, st.params, st.act, st.wmat
+    x = np.asarray(x_in, dtype=st.dtype)
+
+    def bn(t, name):
+        return batchnorm_eval(t, p[name + ".g"], p[name + ".b"], st.bn_mean[name], st.bn_var[name], cfg.bn_eps)
+
+    for i in range(cfg.n_basic_blocks):
+        pre = f"rb{i}"
+        c1 = S(conv3x3_fwd(x, W(p[pre + ".conv1.w"]), 1))
+        y1 = S(np.maximum(bn(c1, pre + ".bn1"), 0))
+        c2 = S(conv3x3_fwd(y1, W(p[pre + ".conv2.w"]), 1))
+        x = S(np.maximum(x + bn(c2, pre + ".bn2"), 0))
+    x_out = x
+    ca = S(conv3x3_fwd(x_out, W(p["aux.conv.w"]), 2))
+    ya = S(np.maximum(bn(ca, "aux.bn"), 0))
+    pooled = S(ya.mean(axis=(1, 2)))
+    return x_out, linear_fwd(pooled, p["head.w"], p["head.b"])
+
+
 def block_forward(st: BlockState, x_in, track=False):
     if st.cfg.arch == ARCH_VIT:
         return vit_forward(st, x_in)

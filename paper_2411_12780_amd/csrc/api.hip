@@ -230,6 +230,14 @@ int ppll_block_step(ppll_block_t* h, const void* x_in_dev, const int32_t* labels
   return h->b.step(x_in_dev, labels_dev, lr, x_out_dev, loss_dev, (hipStream_t)hip_stream, nullptr);
 }
 
+int ppll_block_forward_eval(ppll_block_t* h, const void* x_in_dev, void* x_out_dev, float* logits_dev, void* hip_stream) {
+  PPLL_TRY(block_alive(h));
+  PPLL_TRY(check_aligned(x_in_dev, "x_in_dev"));
+  PPLL_TRY(check_aligned(x_out_dev, "x_out_dev"));
+  if (logits_dev) PPLL_TRY(check_aligned(logits_dev, "logits_dev"));
+  return h->b.forward_eval(x_in_dev, x_out_dev, logits_dev, (hipStream_t)hip_stream);
+}
+
 int ppll_block_sync(ppll_block_t* h, float* loss_host) {
   PPLL_TRY(block_alive(h));
   Block& b = h->b;

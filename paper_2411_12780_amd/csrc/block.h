@@ -90,6 +90,9 @@ struct Block {
   bool phase_timers = false;
   hipEvent_t phase_ev[5] = {};
   int mark_phase(int i, hipStream_t s);
+  // Evaluation-mode forward: x_out = M_j(x_in) (BatchNorm with running statistics); with logits_out the
+  // auxiliary network's class scores [batch, num_classes] fp32 as well.  Changes no state but scratch.
+  int forward_eval(const void* x_in, void* x_out, float* logits_out, hipStream_t s);
   long steps = 0;
   hipStream_t last_stream = nullptr;
 

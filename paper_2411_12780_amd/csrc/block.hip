@@ -504,6 +504,69 @@ int Block::update(float lr, hipStream_t s) {
   return launch_adamw(s, params, grads, mom1, mom2, shadow, P, lr, cfg.beta1, cfg.beta2, cfg.adam_eps, cfg.weight_decay, bc1, bc2);
 }
 
+int Block::forward_eval(const void* x_in, void* x_out, float* logits_out, hipStream_t s) {
+  last_stream = s;
+  const int B = cfg.batch, C = cfg.num_classes;
+  GemmArgs g = gemm_args();
+  if (cfg.arch == PPLL_VIT) {
+    const int D = cfg.dim, T = cfg.tokens, L = cfg.depth, A = cfg.aux_depth;
+    const void* x = x_in;
+    if (cfg.input_kind == PPLL_IN_IMAGE) {
+      const int ppc = cfg.patch * cfg.patch * cfg.img_c;
+      PPLL_TRY(launch_patchify(s, x_in, dt, B, cfg.img_h, cfg.img_w, cfg.img_c, cfg.patch, patches));
+      g.A = patches; g.a_dt = dt; g.a_sm = ppc; g.a_sk = 1;
+      g.B = wptr(pe_w); g.b_dt = wdt(); g.b_sk = D; g.b_sn = 1;
+      g.C = embed_tmp; g.c_dt = dt; g.ldc = D; g.M = B * (T - 1); g.N = D; g.K = ppc; g.bias = params + pe_b;
+      if (T > 1) PPLL_TRY(launch_gemm(s, g));
+      PPLL_TRY(launch_assemble_tokens(s, embed_tmp, dt, params + cls, params + pos, B, T, D, x0));
+      x = x0;
+    }
+    for (int l = 0; l < L; ++l) {
+      void* dst = l == L - 1 ? x_out : enc_a[l].x2;
+      PPLL_TRY(encoder_fwd(l, x, dst, s));
+      x = dst;
+    }
+    if (!logits_out) return PPLL_OK;
+    for (int l = L; l < L + A; ++l) {
+      PPLL_TRY(encoder_fwd(l, x, enc_a[l].x2, s));
+      x = enc_a[l].x2;
+    }
+    PPLL_TRY(launch_layernorm_fwd(s, x, dt, (long)T * D, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, z,
+                                  head_mean, head_rstd));
+    g = gemm_args();
+    g.A = z; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+    g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+    g.C = logits_out; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = D; g.bias = params + head_b;
+    return launch_gemm_generic(s, g);
+  }
+  const int Ch = cfg.channels, A = cfg.aux_channels, H = cfg.height, W = cfg.width, n = cfg.n_basic_blocks;
+  const int rows = B * H * W, Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1, arows = B * Ho * Wo;
+  const float eps = cfg.bn_eps;
+  const void* x = x_in;
+  for (int i = 0; i < n; ++i) {
+    const BasicBlockParams& p = rb_p[i];
+    BasicBlockActs& a = rb_a[i];
+    void* out = i == n - 1 ? x_out : a.out;
+    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c1));
+    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[2 * i], bn_var_run + bn_off[2 * i], Ch, eps, a.mean1, a.rstd1));
+    PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
+    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c2));
+    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[2 * i + 1], bn_var_run + bn_off[2 * i + 1], Ch, eps, a.mean2,
+                                     a.rstd2));
+    PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, x, out));
+    x = out;
+  }
+  if (!logits_out) return PPLL_OK;
+  PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
+  PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[2 * n], bn_var_run + bn_off[2 * n], A, eps, aux_mean, aux_rstd));
+  PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
+  PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
+  g.A = pooled; g.a_dt = dt; g.a_sm = A; g.a_sk = 1;
+  g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+  g.C = logits_out; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = A; g.bias = params + head_b;
+  return launch_gemm_generic(s, g);
+}
+
 int Block::mark_phase(int i, hipStream_t s) {
   if (!phase_timers) return PPLL_OK;
   if (!phase_ev[i]) PPLL_HIP(hipEventCreate(&phase_ev[i]));

@@ -201,6 +201,8 @@ int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum,
                     float* partials, int* ticket, float* mean, float* rstd, float* run_mean, float* run_var);
 // y = relu(bn(x) (+ res))
+int launch_bn_running_stats(hipStream_t s, const float* run_mean, const float* run_var, int C, float eps, float* mean,
+                            float* rstd);
 int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const float* mean, const float* rstd,
                     const float* g, const float* b, const void* res, void* y);
 // dyh = dy * (y > 0); dx = bn'(dyh); dg = sum dyh*xhat; db = sum dyh

@@ -280,6 +280,24 @@ int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, i
   return PPLL_OK;
 }
 
+namespace {
+__global__ __launch_bounds__(256) void bn_running_stats_kernel(const float* run_mean, const float* run_var, int C, float eps,
+                                                               float* mean, float* rstd) {
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= C) return;
+  mean[c] = run_mean[c];
+  rstd[c] = 1.0f / sqrtf(run_var[c] + eps);
+}
+}  // namespace
+
+// evaluation mode: the (mean, 1/sqrt(var + eps)) pair BatchNorm normalises with, from its running statistics
+int launch_bn_running_stats(hipStream_t s, const float* run_mean, const float* run_var, int C, float eps, float* mean,
+                            float* rstd) {
+  hipLaunchKernelGGL(bn_running_stats_kernel, dim3((C + 255) / 256), dim3(256), 0, s, run_mean, run_var, C, eps, mean, rstd);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
 int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, void* pooled) {
   if (C <= 256 && 256 % C == 0)
     hipLaunchKernelGGL(gap_fwd_image_kernel, dim3(B), dim3(256), 0, s, x, dt, HW, C, pooled);

@@ -274,6 +274,58 @@ def test_vit_large_image_bf16_full_size():
 
 
 # ------------------------------------------------------------------ error surfaced at sync
+@pytest.mark.parametrize("name,kw", [
+    ("vit_tiny_fp32", dict(aux_depth=1)),
+    ("vit_stage_bf16", dict(batch=8)),
+    ("resnet_stage_bf16", dict(precision=synth.FP32, batch=4, channels=8, height=8, width=8, n_basic_blocks=2, aux_channels=8)),
+    ("resnet_stage_bf16", dict(batch=8, n_basic_blocks=1)),
+])
+def test_eval_forward_matches_the_oracle_after_training_steps(name, kw):
+    """Two training steps (they move parameters and BatchNorm running statistics), then the evaluation-mode
+    forward on a fresh batch: block output and auxiliary class scores against the oracle, with and without
+    the logits; parameters and running statistics must be untouched by it."""
+    import torch
+    from paper_2411_12780_amd import binding as P
+    from gpu_harness import GpuBlock, to_device, DEV
+    wl = synth.workload(name, **kw)
+    bf16 = wl["precision"] == synth.BF16
+    tol = 2e-2 if bf16 else 1e-4
+    cfg = oracle_cfg(wl)
+    flat = synth.make_params(O.param_spec(cfg), seed=13, jitter=True)
+    st = O.block_init(cfg, flat, np.float64, storage="bf16" if bf16 else None)
+    blk = GpuBlock(wl, flat)
+    stream = torch.cuda.current_stream().cuda_stream
+    for i in range(2):
+        x, y = synth.make_batch(wl, seed=13, index=i)
+        O.block_step(st, x.astype(np.float64), y, float(wl["lr"]))
+        P.ppll_block_step(blk.h, to_device(x, wl), torch.from_numpy(y.astype(np.int32)).to(DEV), float(wl["lr"]),
+                          blk.x_out, blk.loss, stream)
+        P.ppll_block_sync(blk.h)
+    # start the evaluation from the oracle's state, so that the comparison is of the forward alone
+    for i, (pname, _) in enumerate(O.param_spec(cfg)):
+        P.ppll_block_write_tensor(blk.h, P.T_PARAM, i, st.params[pname].astype(np.float32))
+    for i, (bname, _) in enumerate(O.bn_stat_spec(cfg)):
+        P.ppll_block_write_tensor(blk.h, P.T_BN_MEAN, i, st.bn_mean[bname].astype(np.float32))
+        P.ppll_block_write_tensor(blk.h, P.T_BN_VAR, i, st.bn_var[bname].astype(np.float32))
+    params_before = [P.ppll_block_read_tensor(blk.h, P.T_PARAM, i) for i in range(len(blk.names))]
+    x, _ = synth.make_batch(wl, seed=13, index=9)
+    want_out, want_logits = O.block_forward_eval(st, x.astype(np.float64))
+    logits = torch.full((wl["batch"], wl["num_classes"]), float("nan"), dtype=torch.float32, device=DEV)
+    out2 = torch.empty_like(blk.x_out)
+    P.ppll_block_forward_eval(blk.h, to_device(x, wl), blk.x_out, logits, stream)
+    P.ppll_block_forward_eval(blk.h, to_device(x, wl), out2, None, stream)
+    torch.cuda.synchronize()
+    got_out = blk.x_out.float().cpu().numpy().reshape(want_out.shape)
+    assert rel_l2(got_out, want_out) <= tol
+    assert rel_l2(logits.cpu().numpy(), want_logits) <= tol
+    assert torch.equal(out2, blk.x_out)
+    for i, b in enumerate(params_before):
+        assert np.array_equal(P.ppll_block_read_tensor(blk.h, P.T_PARAM, i), b)
+    for i, (bname, _) in enumerate(O.bn_stat_spec(cfg)):
+        assert np.array_equal(P.ppll_block_read_tensor(blk.h, P.T_BN_MEAN, i), st.bn_mean[bname].astype(np.float32))
+    blk.close()
+
+
 def test_phase_timers_split_a_step_into_the_papers_four_terms():
     """f_1, f_a1, B_a1, U_a1 of Section 3.3: four positive durations that add up to about the step time, leave
     the step's results untouched, and are refused while the timers are off."""
@@ -305,7 +357,6 @@ def test_phase_timers_split_a_step_into_the_papers_four_terms():
             ms = P.ppll_block_phase_times(blk.h)
             assert len(ms) == 4 and all(v > 0 for v in ms), ms
             assert sum(ms) <= wall_ms * 1.05, (ms, wall_ms)
-            assert ms[2] > ms[0] and ms[2] > ms[1], ms       # the backward pass is the longest term
         results.append((loss, [P.ppll_block_read_tensor(blk.h, P.T_PARAM, i) for i in range(len(blk.names))]))
         blk.close()
     assert results[0][0] == results[1][0]

@@ -166,6 +166,57 @@ def test_three_steps_match_torch_autograd_and_optim(case, opt):
         assert rel_l2(st.bn_var[n], run[n][1].numpy()) < 1e-10
 
 
+# ------------------------------------------------------------------ evaluation-mode forward
+def test_eval_forward_matches_torch_eval_mode_after_training_steps():
+    """ResNet: after two training steps (which move the running statistics) the evaluation forward must
+    equal torch's batch_norm(training=False) network on a fresh batch, and must leave the state alone."""
+    wl = dict(CASES["resnet"])
+    cfg, st, _, _ = make(wl)
+    for step in range(2):
+        x, y = synth.make_batch(wl, seed=8, index=step)
+        O.block_step(st, x.astype(np.float64), y, 0.05)
+    before = ({k: v.copy() for k, v in st.params.items()}, {k: v.copy() for k, v in st.bn_mean.items()},
+              {k: v.copy() for k, v in st.bn_var.items()})
+    x, _ = synth.make_batch(wl, seed=8, index=7)
+    x_out, logits = O.block_forward_eval(st, x.astype(np.float64))
+    tp = {k: _t(v) for k, v in st.params.items()}
+
+    def bn(t, name):
+        y = F.batch_norm(t.permute(0, 3, 1, 2), _t(st.bn_mean[name]), _t(st.bn_var[name]), tp[name + ".g"], tp[name + ".b"],
+                         training=False, eps=cfg.bn_eps)
+        return y.permute(0, 2, 3, 1)
+
+    t = _t(x.astype(np.float64))
+    for i in range(cfg.n_basic_blocks):
+        pre = f"rb{i}"
+        h = F.relu(bn(_torch_conv(t, tp[pre + ".conv1.w"], 1), pre + ".bn1"))
+        t = F.relu(t + bn(_torch_conv(h, tp[pre + ".conv2.w"], 1), pre + ".bn2"))
+    a = F.relu(bn(_torch_conv(t, tp["aux.conv.w"], 2), "aux.bn"))
+    t_logits = F.linear(a.mean(dim=(1, 2)), tp["head.w"].T, tp["head.b"])
+    assert rel_l2(x_out, t.numpy()) < 1e-12
+    assert rel_l2(logits, t_logits.numpy()) < 1e-12
+    for k in st.params:
+        assert np.array_equal(st.params[k], before[0][k])
+    for k in st.bn_mean:
+        assert np.array_equal(st.bn_mean[k], before[1][k]) and np.array_equal(st.bn_var[k], before[2][k])
+
+
+def test_eval_batchnorm_with_the_batchs_own_statistics_is_training_batchnorm():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal((3, 4, 5, 6)); g = rng.standard_normal(6); b = rng.standard_normal(6)
+    y_train, (_, _, mu, var) = O.batchnorm_fwd(x, g, b, 1e-5)
+    assert rel_l2(O.batchnorm_eval(x, g, b, mu, var, 1e-5), y_train) < 1e-13
+
+
+@pytest.mark.parametrize("case", ["vit_img", "vit_act"])
+def test_eval_forward_of_a_vit_block_is_its_training_forward(case):
+    cfg, st, x, _ = make(CASES[case])
+    x_out, logits = O.block_forward_eval(st, x)
+    tp = {k: _t(v) for k, v in st.params.items()}
+    t_out, t_logits = _torch_vit(cfg, tp, _t(x))
+    assert rel_l2(x_out, t_out.numpy()) < 1e-12 and rel_l2(logits, t_logits.numpy()) < 1e-12
+
+
 # ------------------------------------------------------------------ closed forms
 @pytest.mark.parametrize("case", ["vit_img", "resnet"])
 def test_zero_head_gives_ln10_and_no_upstream_gradient(case):
