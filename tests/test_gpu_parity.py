@@ -197,6 +197,12 @@ def test_vit_bf16_widths_of_the_fast_layernorm(dim, heads):
     run_case(wl, steps=1)
 
 
+def test_vit_bf16_deep_block_needs_two_grouped_weight_gradient_launches():
+    # 7 encoder layers = 28 weight-gradient products (more than one grouped launch takes) with 336 output tiles
+    wl = synth.workload("vit_stage_act_bf16", batch=4, tokens=32, dim=256, heads=4, mlp_dim=1024, depth=6, aux_depth=1)
+    run_case(wl, steps=1)
+
+
 @pytest.mark.parametrize("dim,heads,classes", [(128, 2, 200), (1024, 16, 1024)])
 def test_vit_bf16_head_with_many_classes(dim, heads, classes):
     # 200 classes: more classes than lanes in the fused head kernel; 1024 x 1024: too large for its LDS,
