@@ -72,6 +72,12 @@ def test_null_and_misaligned_arguments():
     with pytest.raises(P.PpllError) as e:
         P.ppll_block_step(None, 16, 16, 0.1, 16)
     assert e.value.status == 1
+    # the entry points added for evaluation and timing reject a null handle the same way
+    for call in (lambda: P.ppll_block_forward_eval(None, 16, 16), lambda: P.ppll_block_phase_timers(None, True),
+                 lambda: P.ppll_block_phase_times(None)):
+        with pytest.raises(P.PpllError) as e:
+            call()
+        assert e.value.status == 1
 
 
 def test_pipeline_shape_chain_is_checked():
