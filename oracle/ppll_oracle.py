@@ -69,6 +69,11 @@ class BlockConfig:
     width: int = 16
     n_basic_blocks: int = 5
     aux_channels: int = 64
+    # 0: every basic block keeps the shape; i+1: basic block i halves the resolution and doubles the
+    # channels, so the block input is [batch, 2*height, 2*width, channels/2] (ResNet-32 of Section 4.1:
+    # 16 -> 32 -> 64 channels on 32 -> 16 -> 8 pixel maps).  input_kind = IN_IMAGE puts the network's
+    # stem (conv3x3 img_c -> input channels, BatchNorm, ReLU) in front of the basic blocks.
+    transition_block: int = 0
     # optimizer (Section 4.1: SGD, Nesterov momentum 0.9, L2 weight decay 1e-4)
     optimizer: int = OPT_SGD
     momentum: float = 0.0
@@ -97,6 +102,27 @@ def _encoder_layer_spec(prefix: str, D: int, F: int) -> List[Tuple[str, Tuple[in
     ]
 
 
+def resnet_layout(cfg: BlockConfig) -> List[Tuple[int, int, int]]:
+    """(input channels, output channels, stride of the first convolution) of every basic block."""
+    C, t = cfg.channels, cfg.transition_block - 1
+    out = []
+    for i in range(cfg.n_basic_blocks):
+        if t >= 0 and i < t:
+            out.append((C // 2, C // 2, 1))
+        elif i == t:
+            out.append((C // 2, C, 2))
+        else:
+            out.append((C, C, 1))
+    return out
+
+
+def resnet_input_shape(cfg: BlockConfig) -> Tuple[int, int, int]:
+    """(height, width, channels) of the activation the first basic block reads."""
+    if cfg.transition_block > 0:
+        return 2 * cfg.height, 2 * cfg.width, cfg.channels // 2
+    return cfg.height, cfg.width, cfg.channels
+
+
 def param_spec(cfg: BlockConfig) -> List[Tuple[str, Tuple[int, ...]]]:
     """Ordered (name, shape) list of theta_j (module) then gamma_j (auxiliary)."""
     spec: List[Tuple[str, Tuple[int, ...]]] = []
@@ -113,9 +139,12 @@ def param_spec(cfg: BlockConfig) -> List[Tuple[str, Tuple[int, ...]]]:
                  ("head.w", (D, cfg.num_classes)), ("head.b", (cfg.num_classes,))]
     elif cfg.arch == ARCH_RESNET:
         C, A = cfg.channels, cfg.aux_channels
-        for i in range(cfg.n_basic_blocks):
-            spec += [(f"rb{i}.conv1.w", (3, 3, C, C)), (f"rb{i}.bn1.g", (C,)), (f"rb{i}.bn1.b", (C,)),
-                     (f"rb{i}.conv2.w", (3, 3, C, C)), (f"rb{i}.bn2.g", (C,)), (f"rb{i}.bn2.b", (C,))]
+        if cfg.input_kind == IN_IMAGE:
+            c0 = resnet_input_shape(cfg)[2]
+            spec += [("stem.conv.w", (3, 3, cfg.img_c, c0)), ("stem.bn.g", (c0,)), ("stem.bn.b", (c0,))]
+        for i, (ci, co, _) in enumerate(resnet_layout(cfg)):
+            spec += [(f"rb{i}.conv1.w", (3, 3, ci, co)), (f"rb{i}.bn1.g", (co,)), (f"rb{i}.bn1.b", (co,)),
+                     (f"rb{i}.conv2.w", (3, 3, co, co)), (f"rb{i}.bn2.g", (co,)), (f"rb{i}.bn2.b", (co,))]
         spec += [("aux.conv.w", (3, 3, C, A)), ("aux.bn.g", (A,)), ("aux.bn.b", (A,)),
                  ("head.w", (A, cfg.num_classes)), ("head.b", (cfg.num_classes,))]
     else:
@@ -128,8 +157,10 @@ def bn_stat_spec(cfg: BlockConfig) -> List[Tuple[str, int]]:
     if cfg.arch != ARCH_RESNET:
         return []
     out = []
-    for i in range(cfg.n_basic_blocks):
-        out += [(f"rb{i}.bn1", cfg.channels), (f"rb{i}.bn2", cfg.channels)]
+    if cfg.input_kind == IN_IMAGE:
+        out.append(("stem.bn", resnet_input_shape(cfg)[2]))
+    for i, (_, co, _) in enumerate(resnet_layout(cfg)):
+        out += [(f"rb{i}.bn1", co), (f"rb{i}.bn2", co)]
     out.append(("aux.bn", cfg.aux_channels))
     return out
 
@@ -319,6 +350,26 @@ def batchnorm_bwd(dy, cache, g):
 # momentum and L2 weight decay; AdamW is the workload definition's choice)
 # --------------------------------------------------------------------------
 
+def shortcut_fwd(x, c_out, stride):
+    """Parameter-free shortcut of a basic block (the CIFAR ResNet the paper trains, Section 4.1): the
+    identity where the shapes agree; where the block halves the map and widens it, every `stride`-th
+    pixel with zero channels appended after the original ones."""
+    if stride == 1 and x.shape[-1] == c_out:
+        return x
+    sub = x[:, ::stride, ::stride, :]
+    y = np.zeros(sub.shape[:-1] + (c_out,), dtype=x.dtype)
+    y[..., :x.shape[-1]] = sub
+    return y
+
+
+def shortcut_bwd(dy, in_shape, stride):
+    if stride == 1 and in_shape[-1] == dy.shape[-1]:
+        return dy
+    dx = np.zeros(in_shape, dtype=dy.dtype)
+    dx[:, ::stride, ::stride, :] = dy[..., :in_shape[-1]]
+    return dx
+
+
 def sgd_update(p, g, buf, lr, momentum, nesterov, weight_decay, first):
     """Coupled L2 decay, then momentum buffer (first step: buffer = gradient),
     then plain or Nesterov step.  Returns (new_p, new_buf)."""
@@ -481,19 +532,27 @@ def _bn_track(st: BlockState, name, cache, n):
 
 
 def resnet_forward(st: BlockState, x_in, track=True):
-    """n basic blocks: relu(x + bn2(conv2(relu(bn1(conv1(x)))))), then the
-    auxiliary head conv3x3/s2 -> BN -> ReLU -> global average -> Linear."""
+    """[stem conv3x3 -> BN -> ReLU when the input is the image] -> n basic blocks
+    relu(shortcut(x) + bn2(conv2(relu(bn1(conv1(x)))))) -> x_out, then the auxiliary head
+    conv3x3/s2 -> BN -> ReLU -> global average -> Linear."""
     cfg, p, S, W = st.cfg, st.params, st.act, st.wmat
     x = np.asarray(x_in, dtype=st.dtype)
     caches = {}
-    for i in range(cfg.n_basic_blocks):
+    if cfg.input_kind == IN_IMAGE:
+        c0 = S(conv3x3_fwd(x, W(p["stem.conv.w"]), 1))
+        b0, cb0 = batchnorm_fwd(c0, p["stem.bn.g"], p["stem.bn.b"], cfg.bn_eps)
+        if track:
+            _bn_track(st, "stem.bn", cb0, c0.size // c0.shape[-1])
+        caches["stem"] = (x, cb0, b0)
+        x = S(np.maximum(b0, 0))
+    for i, (_, co, stride) in enumerate(resnet_layout(cfg)):
         pre = f"rb{i}"
-        c1 = S(conv3x3_fwd(x, W(p[pre + ".conv1.w"]), 1))
+        c1 = S(conv3x3_fwd(x, W(p[pre + ".conv1.w"]), stride))
         b1, cb1 = batchnorm_fwd(c1, p[pre + ".bn1.g"], p[pre + ".bn1.b"], cfg.bn_eps)
         y1 = S(np.maximum(b1, 0))
         c2 = S(conv3x3_fwd(y1, W(p[pre + ".conv2.w"]), 1))
         b2, cb2 = batchnorm_fwd(c2, p[pre + ".bn2.g"], p[pre + ".bn2.b"], cfg.bn_eps)
-        s = x + b2
+        s = shortcut_fwd(x, co, stride) + b2
         caches[pre] = (x, cb1, b1, y1, cb2, s)
         if track:
             n = c1.size // c1.shape[-1]
@@ -523,8 +582,11 @@ def resnet_backward(st: BlockState, dlogits, caches):
     dca, g["aux.bn.g"], g["aux.bn.b"] = batchnorm_bwd(dba, cba, p["aux.bn.g"])
     g["aux.conv.w"] = conv3x3_bwd_weight(dca, x_out, 2)
     dx = conv3x3_bwd_input(dca, st.wmat(p["aux.conv.w"]), 2, x_out.shape)
+    stem = cfg.input_kind == IN_IMAGE
+    layout = resnet_layout(cfg)
     for i in reversed(range(cfg.n_basic_blocks)):
         pre = f"rb{i}"
+        stride = layout[i][2]
         x, cb1, b1, y1, cb2, s = caches[pre]
         ds = dx * (s > 0)
         dc2, g[pre + ".bn2.g"], g[pre + ".bn2.b"] = batchnorm_bwd(ds, cb2, p[pre + ".bn2.g"])
@@ -532,9 +594,14 @@ def resnet_backward(st: BlockState, dlogits, caches):
         dy1 = conv3x3_bwd_input(dc2, st.wmat(p[pre + ".conv2.w"]), 1, y1.shape)
         db1 = dy1 * (b1 > 0)
         dc1, g[pre + ".bn1.g"], g[pre + ".bn1.b"] = batchnorm_bwd(db1, cb1, p[pre + ".bn1.g"])
-        g[pre + ".conv1.w"] = conv3x3_bwd_weight(dc1, x, 1)
-        if i > 0:   # the first block's input is the detached x_{j-1}
-            dx = ds + conv3x3_bwd_input(dc1, st.wmat(p[pre + ".conv1.w"]), 1, x.shape)
+        g[pre + ".conv1.w"] = conv3x3_bwd_weight(dc1, x, stride)
+        if i > 0 or stem:   # without a stem the first block's input is the detached x_{j-1}
+            dx = shortcut_bwd(ds, x.shape, stride) + conv3x3_bwd_input(dc1, st.wmat(p[pre + ".conv1.w"]), stride, x.shape)
+    if stem:
+        img, cb0, b0 = caches["stem"]
+        db0 = dx * (b0 > 0)
+        dc0, g["stem.bn.g"], g["stem.bn.b"] = batchnorm_bwd(db0, cb0, p["stem.bn.g"])
+        g["stem.conv.w"] = conv3x3_bwd_weight(dc0, img, 1)
     return g
 
 
@@ -556,12 +623,14 @@ def block_forward_eval(st: BlockState, x_in):
     def bn(t, name):
         return batchnorm_eval(t, p[name + ".g"], p[name + ".b"], st.bn_mean[name], st.bn_var[name], cfg.bn_eps)
 
-    for i in range(cfg.n_basic_blocks):
+    if cfg.input_kind == IN_IMAGE:
+        x = S(np.maximum(bn(S(conv3x3_fwd(x, W(p["stem.conv.w"]), 1)), "stem.bn"), 0))
+    for i, (_, co, stride) in enumerate(resnet_layout(cfg)):
         pre = f"rb{i}"
-        c1 = S(conv3x3_fwd(x, W(p[pre + ".conv1.w"]), 1))
+        c1 = S(conv3x3_fwd(x, W(p[pre + ".conv1.w"]), stride))
         y1 = S(np.maximum(bn(c1, pre + ".bn1"), 0))
         c2 = S(conv3x3_fwd(y1, W(p[pre + ".conv2.w"]), 1))
-        x = S(np.maximum(x + bn(c2, pre + ".bn2"), 0))
+        x = S(np.maximum(shortcut_fwd(x, co, stride) + bn(c2, pre + ".bn2"), 0))
     x_out = x
     ca = S(conv3x3_fwd(x_out, W(p["aux.conv.w"]), 2))
     ya = S(np.maximum(bn(ca, "aux.bn"), 0))

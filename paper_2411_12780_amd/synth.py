@@ -92,6 +92,10 @@ def input_shape(wl: dict) -> tuple:
         if wl["input_kind"] == IMAGE:
             return (wl["batch"], wl["img_h"], wl["img_w"], wl["img_c"])
         return (wl["batch"], wl["tokens"], wl["dim"])
+    if wl["input_kind"] == IMAGE:     # the stem reads the image
+        return (wl["batch"], wl["img_h"], wl["img_w"], wl["img_c"])
+    if wl.get("transition_block", 0) > 0:   # a basic block of the stage halves the map and doubles the channels
+        return (wl["batch"], 2 * wl["height"], 2 * wl["width"], wl["channels"] // 2)
     return (wl["batch"], wl["height"], wl["width"], wl["channels"])
 
 

@@ -250,6 +250,27 @@ def test_conv3x3_centre_tap_is_identity_and_adjoint():
         assert abs(lhs - np.vdot(w, O.conv3x3_bwd_weight(dy, x, stride))) < 1e-10
 
 
+# ---------------------------------------------------------------- parameter-free shortcut
+def test_shortcut_is_identity_or_subsample_with_zero_channels():
+    x = RNG.standard_normal((2, 6, 5, 3))
+    assert O.shortcut_fwd(x, 3, 1) is x
+    y = O.shortcut_fwd(x, 6, 2)
+    assert y.shape == (2, 3, 3, 6)
+    for b in range(2):
+        for oy in range(3):
+            for ox in range(3):
+                for c in range(6):
+                    assert y[b, oy, ox, c] == (x[b, 2 * oy, 2 * ox, c] if c < 3 else 0.0)
+    # 1x1 stride-2 convolution with the [I | 0] matrix is the same map
+    w = torch.zeros(6, 3, 1, 1, dtype=torch.float64)
+    w[:3, :, 0, 0] = torch.eye(3, dtype=torch.float64)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x).permute(0, 3, 1, 2), w, stride=2).permute(0, 2, 3, 1).numpy()
+    close(y, ref, 1e-15)
+    dy = RNG.standard_normal(y.shape)
+    assert abs(np.vdot(y, dy) - np.vdot(x, O.shortcut_bwd(dy, x.shape, 2))) < 1e-12
+    assert O.shortcut_bwd(dy, y.shape, 1) is dy
+
+
 # ---------------------------------------------------------------- batchnorm
 def test_batchnorm_matches_torch_autograd_and_invariants():
     x = RNG.standard_normal((3, 4, 5, 6)) * 2 + 1

@@ -24,7 +24,15 @@ TINY_VIT_ACT = dict(TINY_VIT_IMG, input_kind=1, depth=2, aux_depth=0)
 TINY_RESNET = dict(arch=1, input_kind=1, batch=2, num_classes=10, channels=4, height=6, width=6,
                    n_basic_blocks=2, aux_channels=6, optimizer=0, momentum=0.9, nesterov=1,
                    weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1, precision=0)
-CASES = {"vit_img": TINY_VIT_IMG, "vit_act": TINY_VIT_ACT, "resnet": TINY_RESNET}
+# basic block 1 of 3 halves the map and doubles the channels: the backward pass crosses its shortcut
+TINY_RESNET_DOWN = dict(TINY_RESNET, channels=4, height=4, width=4, n_basic_blocks=3, transition_block=2)
+# the network's first module: stem on the image, then basic blocks; the stem is trained, so the
+# backward pass also crosses basic block 0
+TINY_RESNET_STEM = dict(TINY_RESNET, input_kind=0, img_h=6, img_w=6, img_c=3)
+TINY_RESNET_STEM_DOWN = dict(TINY_RESNET, input_kind=0, img_h=6, img_w=6, img_c=3, channels=4, height=3, width=3,
+                             transition_block=1)
+CASES = {"vit_img": TINY_VIT_IMG, "vit_act": TINY_VIT_ACT, "resnet": TINY_RESNET, "resnet_down": TINY_RESNET_DOWN,
+         "resnet_stem": TINY_RESNET_STEM, "resnet_stem_down": TINY_RESNET_STEM_DOWN}
 
 
 def make(wl, seed=0, dtype=np.float64):
@@ -115,10 +123,16 @@ def _torch_bn(x, g, b, eps, run):
 
 
 def _torch_resnet(cfg, p, x, run):
+    if cfg.input_kind == O.IN_IMAGE:
+        x = F.relu(_torch_bn(_torch_conv(x, p["stem.conv.w"], 1), p["stem.bn.g"], p["stem.bn.b"], cfg.bn_eps, run["stem.bn"]))
     for i in range(cfg.n_basic_blocks):
         pre = f"rb{i}"
-        y = F.relu(_torch_bn(_torch_conv(x, p[pre + ".conv1.w"], 1), p[pre + ".bn1.g"], p[pre + ".bn1.b"], cfg.bn_eps, run[pre + ".bn1"]))
+        down = i == cfg.transition_block - 1
+        y = F.relu(_torch_bn(_torch_conv(x, p[pre + ".conv1.w"], 2 if down else 1), p[pre + ".bn1.g"], p[pre + ".bn1.b"],
+                             cfg.bn_eps, run[pre + ".bn1"]))
         y = _torch_bn(_torch_conv(y, p[pre + ".conv2.w"], 1), p[pre + ".bn2.g"], p[pre + ".bn2.b"], cfg.bn_eps, run[pre + ".bn2"])
+        if down:   # every second pixel, as many zero channels appended as there are channels
+            x = F.pad(x[:, ::2, ::2, :], (0, x.shape[-1]))
         x = F.relu(x + y)
     x_out = x
     a = F.relu(_torch_bn(_torch_conv(x, p["aux.conv.w"], 2), p["aux.bn.g"], p["aux.bn.b"], cfg.bn_eps, run["aux.bn"]))
@@ -126,7 +140,8 @@ def _torch_resnet(cfg, p, x, run):
 
 
 @pytest.mark.parametrize("case,opt", [("vit_img", "sgd"), ("vit_act", "adamw"), ("vit_img", "adamw"),
-                                      ("resnet", "sgd_nesterov")])
+                                      ("resnet", "sgd_nesterov"), ("resnet_down", "sgd_nesterov"),
+                                      ("resnet_stem", "sgd_nesterov"), ("resnet_stem_down", "sgd_nesterov")])
 def test_three_steps_match_torch_autograd_and_optim(case, opt):
     wl = dict(CASES[case])
     if opt == "adamw":
@@ -167,10 +182,11 @@ def test_three_steps_match_torch_autograd_and_optim(case, opt):
 
 
 # ------------------------------------------------------------------ evaluation-mode forward
-def test_eval_forward_matches_torch_eval_mode_after_training_steps():
+@pytest.mark.parametrize("case", ["resnet", "resnet_down", "resnet_stem_down"])
+def test_eval_forward_matches_torch_eval_mode_after_training_steps(case):
     """ResNet: after two training steps (which move the running statistics) the evaluation forward must
     equal torch's batch_norm(training=False) network on a fresh batch, and must leave the state alone."""
-    wl = dict(CASES["resnet"])
+    wl = dict(CASES[case])
     cfg, st, _, _ = make(wl)
     for step in range(2):
         x, y = synth.make_batch(wl, seed=8, index=step)
@@ -187,9 +203,14 @@ def test_eval_forward_matches_torch_eval_mode_after_training_steps():
         return y.permute(0, 2, 3, 1)
 
     t = _t(x.astype(np.float64))
+    if cfg.input_kind == O.IN_IMAGE:
+        t = F.relu(bn(_torch_conv(t, tp["stem.conv.w"], 1), "stem.bn"))
     for i in range(cfg.n_basic_blocks):
         pre = f"rb{i}"
-        h = F.relu(bn(_torch_conv(t, tp[pre + ".conv1.w"], 1), pre + ".bn1"))
+        down = i == cfg.transition_block - 1
+        h = F.relu(bn(_torch_conv(t, tp[pre + ".conv1.w"], 2 if down else 1), pre + ".bn1"))
+        if down:
+            t = F.pad(t[:, ::2, ::2, :], (0, t.shape[-1]))
         t = F.relu(t + bn(_torch_conv(h, tp[pre + ".conv2.w"], 1), pre + ".bn2"))
     a = F.relu(bn(_torch_conv(t, tp["aux.conv.w"], 2), "aux.bn"))
     t_logits = F.linear(a.mean(dim=(1, 2)), tp["head.w"].T, tp["head.b"])
