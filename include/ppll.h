@@ -64,18 +64,25 @@ enum { PPLL_T_PARAM = 0, PPLL_T_GRAD = 1, PPLL_T_MOMENT1 = 2, PPLL_T_MOMENT2 = 3
  * (Section 3.2; model families and optimizer of Sections 4.1-4.2).
  * ViT: [patch-embed + cls + pos if PPLL_IN_IMAGE] -> depth pre-LN encoder
  * layers -> x_out; aux = aux_depth encoder layers -> LayerNorm -> cls token ->
- * Linear(dim, num_classes).  ResNet: n_basic_blocks x (conv3x3-BN-ReLU-conv3x3-
- * BN, + identity, ReLU) -> x_out; aux = conv3x3 stride 2 (channels ->
- * aux_channels) -> BN -> ReLU -> global average -> Linear. */
+ * Linear(dim, num_classes).  ResNet: [stem conv3x3 (img_c -> input channels)-
+ * BN-ReLU if PPLL_IN_IMAGE] -> n_basic_blocks x (conv3x3-BN-ReLU-conv3x3-BN,
+ * + shortcut, ReLU) -> x_out [batch, height, width, channels]; aux = conv3x3
+ * stride 2 (channels -> aux_channels) -> BN -> ReLU -> global average ->
+ * Linear.  With transition_block = i+1 basic block i is the one of the CIFAR
+ * ResNet (Section 4.1) that halves the map and doubles the channels: its first
+ * convolution has stride 2, its shortcut takes every second pixel and appends
+ * zero channels, the blocks before it work on [2*height, 2*width, channels/2]
+ * and that is also the shape of x_in (of the stem's output with a stem). */
 typedef struct {
   uint32_t struct_size;   /* = sizeof(ppll_block_config)                         */
   int32_t arch;           /* PPLL_VIT | PPLL_RESNET                              */
   int32_t precision;      /* PPLL_FP32 | PPLL_BF16 (fp32 master weights always)  */
-  int32_t input_kind;     /* PPLL_IN_IMAGE (ViT only) | PPLL_IN_ACTIVATION       */
+  int32_t input_kind;     /* PPLL_IN_IMAGE (ViT patches, ResNet stem) | PPLL_IN_ACTIVATION */
   int32_t batch, num_classes;
   int32_t img_h, img_w, img_c, patch;                    /* ViT image input      */
   int32_t tokens, dim, heads, mlp_dim, depth, aux_depth; /* ViT                  */
   int32_t channels, height, width, n_basic_blocks, aux_channels; /* ResNet       */
+  int32_t transition_block; /* ResNet: 0 = none, i+1 = basic block i downsamples */
   int32_t optimizer;      /* PPLL_SGD | PPLL_ADAMW                               */
   float momentum;         /* SGD                                                 */
   int32_t nesterov;       /* SGD                                                 */

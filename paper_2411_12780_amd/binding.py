@@ -33,7 +33,7 @@ class BlockConfig(C.Structure):
                 ("tokens", C.c_int32), ("dim", C.c_int32), ("heads", C.c_int32), ("mlp_dim", C.c_int32),
                 ("depth", C.c_int32), ("aux_depth", C.c_int32),
                 ("channels", C.c_int32), ("height", C.c_int32), ("width", C.c_int32),
-                ("n_basic_blocks", C.c_int32), ("aux_channels", C.c_int32),
+                ("n_basic_blocks", C.c_int32), ("aux_channels", C.c_int32), ("transition_block", C.c_int32),
                 ("optimizer", C.c_int32), ("momentum", C.c_float), ("nesterov", C.c_int32),
                 ("weight_decay", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
                 ("adam_eps", C.c_float), ("ln_eps", C.c_float), ("bn_eps", C.c_float),

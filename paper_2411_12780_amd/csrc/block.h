@@ -25,6 +25,8 @@ struct EncoderActs {     // saved by the forward for the backward
   float *mean1, *rstd1, *mean2, *rstd2, *lse;
 };
 struct BasicBlockParams { size_t conv1_w, bn1_g, bn1_b, conv2_w, bn2_g, bn2_b; };
+// conv1 maps [Hin, Win, Ci] to [Ho, Wo, Co] with `stride`; everything after it in the block is [Ho, Wo, Co]
+struct BasicBlockDims { int Ci, Co, stride, Hin, Win, Ho, Wo; };
 struct BasicBlockActs {
   void *c1, *y1, *c2, *out;
   float *mean1, *rstd1, *mean2, *rstd2;
@@ -79,6 +81,13 @@ struct Block {
   // ResNet
   std::vector<BasicBlockParams> rb_p;
   std::vector<BasicBlockActs> rb_a;
+  std::vector<BasicBlockDims> rb_d;
+  int in_h = 0, in_w = 0, in_c = 0;      // activation the first basic block reads
+  bool stem = false;                     // conv3x3 (img_c -> in_c) - BN - ReLU on the image in front of the blocks
+  size_t stem_w = 0, stem_g = 0, stem_b = 0;
+  void *stem_c = nullptr, *stem_y = nullptr, *shortcut = nullptr;
+  float *stem_mean = nullptr, *stem_rstd = nullptr;
+  int bn_base = 0;                       // index of rb0.bn1 among the BatchNorm layers (1 behind a stem)
   size_t aux_conv_w = 0, aux_bn_g = 0, aux_bn_b = 0;
   void *aux_c = nullptr, *aux_y = nullptr, *pooled = nullptr, *dpooled = nullptr, *d_aux = nullptr;
   float *aux_mean = nullptr, *aux_rstd = nullptr;

@@ -55,9 +55,18 @@ int validate_config(const ppll_block_config* c) {
         return bad("tokens must equal (img_h/patch)*(img_w/patch) + 1");
     }
   } else if (c->arch == PPLL_RESNET) {
-    if (c->input_kind != PPLL_IN_ACTIVATION) return bad("ResNet blocks take activations");
+    if (c->input_kind != PPLL_IN_IMAGE && c->input_kind != PPLL_IN_ACTIVATION) return bad("input_kind");
     if (c->channels < 1 || c->aux_channels < 1 || c->height < 2 || c->width < 2 || c->n_basic_blocks < 1)
       return bad("channels, aux_channels, n_basic_blocks >= 1 and height, width >= 2 required");
+    if (c->transition_block < 0 || c->transition_block > c->n_basic_blocks)
+      return bad("transition_block outside 0..n_basic_blocks");
+    if (c->transition_block > 0 && (c->channels % 2)) return bad("a downsampling basic block doubles the channels: channels must be even");
+    if (c->height > 4096 || c->width > 4096 || c->channels > 4096) return bad("height, width, channels above 4096");
+    if (c->input_kind == PPLL_IN_IMAGE) {
+      const int m = c->transition_block > 0 ? 2 : 1;
+      if (c->img_c < 1 || c->img_h != m * c->height || c->img_w != m * c->width)
+        return bad("the stem keeps the image size: img_h, img_w must equal the first basic block's input size");
+    }
     if (c->bn_eps <= 0.f || c->bn_momentum < 0.f || c->bn_momentum > 1.f) return bad("bn_eps > 0 and bn_momentum in [0,1] required");
   } else {
     return bad("arch must be PPLL_VIT or PPLL_RESNET");
@@ -69,7 +78,9 @@ int Block::in_elems() const {
   if (cfg.arch == PPLL_VIT)
     return cfg.input_kind == PPLL_IN_IMAGE ? cfg.batch * cfg.img_h * cfg.img_w * cfg.img_c
                                            : cfg.batch * cfg.tokens * cfg.dim;
-  return cfg.batch * cfg.height * cfg.width * cfg.channels;
+  if (cfg.input_kind == PPLL_IN_IMAGE) return cfg.batch * cfg.img_h * cfg.img_w * cfg.img_c;
+  const int m = cfg.transition_block > 0 ? 2 : 1;
+  return cfg.batch * (m * cfg.height) * (m * cfg.width) * (cfg.channels / m);
 }
 int Block::out_elems() const {
   if (cfg.arch == PPLL_VIT) return cfg.batch * cfg.tokens * cfg.dim;
@@ -79,7 +90,7 @@ int Block::out_elems() const {
 size_t Block::plan(char* base) {
   dt = cfg.precision == PPLL_BF16 ? BF16 : F32;
   esz = dtype_size(dt);
-  tensors.clear(); enc_p.clear(); enc_a.clear(); rb_p.clear(); rb_a.clear();
+  tensors.clear(); enc_p.clear(); enc_a.clear(); rb_p.clear(); rb_a.clear(); rb_d.clear();
   bn_names.clear(); bn_channels.clear(); bn_off.clear();
   size_t off = 0;
   auto add = [&](const std::string& name, int rows, int cols) {
@@ -113,15 +124,28 @@ size_t Block::plan(char* base) {
     head_ln_g = add("head.ln.g", 1, D); head_ln_b = add("head.ln.b", 1, D);
     head_w = add("head.w", D, C); head_b = add("head.b", 1, C);
   } else {
-    const int Ch = cfg.channels, A = cfg.aux_channels;
+    const int Ch = cfg.channels, A = cfg.aux_channels, t = cfg.transition_block - 1;
+    const int m = t >= 0 ? 2 : 1;
+    in_h = m * cfg.height; in_w = m * cfg.width; in_c = Ch / m;
+    stem = cfg.input_kind == PPLL_IN_IMAGE;
+    bn_base = stem ? 1 : 0;
+    if (stem) {
+      stem_w = add("stem.conv.w", 9 * cfg.img_c, in_c); stem_g = add("stem.bn.g", 1, in_c); stem_b = add("stem.bn.b", 1, in_c);
+      bn_names.push_back("stem.bn"); bn_channels.push_back(in_c);
+    }
     for (int i = 0; i < cfg.n_basic_blocks; ++i) {
       std::string p = "rb" + std::to_string(i);
+      BasicBlockDims d;
+      if (t >= 0 && i < t) d = {in_c, in_c, 1, in_h, in_w, in_h, in_w};
+      else if (i == t) d = {in_c, Ch, 2, in_h, in_w, cfg.height, cfg.width};
+      else d = {Ch, Ch, 1, cfg.height, cfg.width, cfg.height, cfg.width};
+      rb_d.push_back(d);
       BasicBlockParams r;
-      r.conv1_w = add(p + ".conv1.w", 9 * Ch, Ch); r.bn1_g = add(p + ".bn1.g", 1, Ch); r.bn1_b = add(p + ".bn1.b", 1, Ch);
-      r.conv2_w = add(p + ".conv2.w", 9 * Ch, Ch); r.bn2_g = add(p + ".bn2.g", 1, Ch); r.bn2_b = add(p + ".bn2.b", 1, Ch);
+      r.conv1_w = add(p + ".conv1.w", 9 * d.Ci, d.Co); r.bn1_g = add(p + ".bn1.g", 1, d.Co); r.bn1_b = add(p + ".bn1.b", 1, d.Co);
+      r.conv2_w = add(p + ".conv2.w", 9 * d.Co, d.Co); r.bn2_g = add(p + ".bn2.g", 1, d.Co); r.bn2_b = add(p + ".bn2.b", 1, d.Co);
       rb_p.push_back(r);
-      bn_names.push_back(p + ".bn1"); bn_channels.push_back(Ch);
-      bn_names.push_back(p + ".bn2"); bn_channels.push_back(Ch);
+      bn_names.push_back(p + ".bn1"); bn_channels.push_back(d.Co);
+      bn_names.push_back(p + ".bn2"); bn_channels.push_back(d.Co);
     }
     aux_conv_w = add("aux.conv.w", 9 * Ch, A); aux_bn_g = add("aux.bn.g", 1, A); aux_bn_b = add("aux.bn.b", 1, A);
     bn_names.push_back("aux.bn"); bn_channels.push_back(A);
@@ -192,24 +216,36 @@ size_t Block::plan(char* base) {
     if (vit_head_partial_floats(B, D, C) > partial_floats) partial_floats = vit_head_partial_floats(B, D, C);
   } else {
     const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
-    const size_t act = (size_t)B * Hh * W * Ch;
     const int Ho = (Hh - 1) / 2 + 1, Wo = (W - 1) / 2 + 1;
     const size_t aact = (size_t)B * Ho * Wo * A;
+    size_t widest = (size_t)B * in_h * in_w * in_c;   // largest activation a gradient buffer has to hold
+    auto grow = [&](size_t v) { if (v > partial_floats) partial_floats = v; };
+    partial_floats = 0;
+    if (stem) {
+      stem_c = bump.take(widest * esz); stem_y = bump.take(widest * esz);
+      stem_mean = bump.floats(in_c); stem_rstd = bump.floats(in_c);
+      grow((size_t)conv3x3_wgrad_partial_floats(B, in_h, in_w, cfg.img_c, in_c, 1));
+      grow((size_t)bn_partial_floats(B * in_h * in_w, in_c));
+    }
     for (int i = 0; i < cfg.n_basic_blocks; ++i) {
+      const BasicBlockDims& d = rb_d[i];
+      const size_t act = (size_t)B * d.Ho * d.Wo * d.Co;
+      if (act > widest) widest = act;
       BasicBlockActs a;
       a.c1 = bump.take(act * esz); a.y1 = bump.take(act * esz); a.c2 = bump.take(act * esz); a.out = bump.take(act * esz);
-      a.mean1 = bump.floats(Ch); a.rstd1 = bump.floats(Ch); a.mean2 = bump.floats(Ch); a.rstd2 = bump.floats(Ch);
+      a.mean1 = bump.floats(d.Co); a.rstd1 = bump.floats(d.Co); a.mean2 = bump.floats(d.Co); a.rstd2 = bump.floats(d.Co);
       rb_a.push_back(a);
+      if (d.stride != 1 || d.Ci != d.Co) shortcut = bump.take(act * esz);
+      grow((size_t)conv3x3_wgrad_partial_floats(B, d.Hin, d.Win, d.Ci, d.Co, d.stride));
+      grow((size_t)conv3x3_wgrad_partial_floats(B, d.Ho, d.Wo, d.Co, d.Co, 1));
+      grow((size_t)bn_partial_floats(B * d.Ho * d.Wo, d.Co));
     }
     aux_c = bump.take(aact * esz); aux_y = bump.take(aact * esz); d_aux = bump.take(aact * esz);
     pooled = bump.take((size_t)B * A * esz); dpooled = bump.take((size_t)B * A * esz);
     aux_mean = bump.floats(A); aux_rstd = bump.floats(A);
-    r_gA = bump.take(act * esz); r_t1 = bump.take(act * esz); r_t2 = bump.take(act * esz);
-    partial_floats = (size_t)conv3x3_wgrad_partial_floats(B, Hh, W, Ch, Ch, 1);
-    size_t o = (size_t)conv3x3_wgrad_partial_floats(B, Hh, W, Ch, A, 2);
-    if (o > partial_floats) partial_floats = o;
-    o = (size_t)bn_partial_floats(B * Hh * W, Ch > A ? Ch : A);
-    if (o > partial_floats) partial_floats = o;
+    r_gA = bump.take(widest * esz); r_gB = bump.take(widest * esz); r_t1 = bump.take(widest * esz); r_t2 = bump.take(widest * esz);
+    grow((size_t)conv3x3_wgrad_partial_floats(B, Hh, W, Ch, A, 2));
+    grow((size_t)bn_partial_floats(B * Ho * Wo, A));
   }
   size_t o = (size_t)colsum_partial_floats(B, C);
   if (o > partial_floats) partial_floats = o;
@@ -232,8 +268,11 @@ size_t Block::plan(char* base) {
   }
   if (cfg.arch == PPLL_RESNET) {   // the weight-gradient partials of every convolution
     const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
-    arena_floats = (size_t)2 * cfg.n_basic_blocks * ((size_t)conv3x3_wgrad_partial_floats(cfg.batch, Hh, W, Ch, Ch, 1) + 64) +
-                   (size_t)conv3x3_wgrad_partial_floats(cfg.batch, Hh, W, Ch, A, 2) + 64;
+    arena_floats = (size_t)conv3x3_wgrad_partial_floats(cfg.batch, Hh, W, Ch, A, 2) + 64;
+    for (const BasicBlockDims& d : rb_d)
+      arena_floats += (size_t)conv3x3_wgrad_partial_floats(cfg.batch, d.Hin, d.Win, d.Ci, d.Co, d.stride) +
+                      (size_t)conv3x3_wgrad_partial_floats(cfg.batch, d.Ho, d.Wo, d.Co, d.Co, 1) + 128;
+    if (stem) arena_floats += (size_t)conv3x3_wgrad_partial_floats(cfg.batch, in_h, in_w, cfg.img_c, in_c, 1) + 64;
   }
   rq.arena = arena_floats ? bump.floats(arena_floats) : nullptr;
   rq.arena_floats = arena_floats;
@@ -425,33 +464,48 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
 int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
                        const std::function<int()>& after_forward) {
   const int B = cfg.batch, Ch = cfg.channels, A = cfg.aux_channels, H = cfg.height, W = cfg.width;
-  const int C = cfg.num_classes, n = cfg.n_basic_blocks, rows = B * H * W;
+  const int C = cfg.num_classes, n = cfg.n_basic_blocks;
   const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1, arows = B * Ho * Wo;
   const float eps = cfg.bn_eps, mom = cfg.bn_momentum;
+  auto run_mean = [&](int i) { return bn_mean_run + bn_off[i]; };
+  auto run_var = [&](int i) { return bn_var_run + bn_off[i]; };
   std::vector<const void*> block_in(n);
   std::vector<void*> block_out(n);
   const void* x = x_in;
+  if (stem) {
+    const int rows0 = B * in_h * in_w;
+    PPLL_TRY(launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c));
+    PPLL_TRY(launch_bn_stats(s, stem_c, dt, rows0, in_c, eps, mom, partials, ticket_dev, stem_mean, stem_rstd, run_mean(0),
+                             run_var(0)));
+    PPLL_TRY(launch_bn_apply(s, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, params + stem_b, nullptr, stem_y));
+    x = stem_y;
+  }
   for (int i = 0; i < n; ++i) {
     const BasicBlockParams& p = rb_p[i];
+    const BasicBlockDims& d = rb_d[i];
     BasicBlockActs& a = rb_a[i];
+    const int rows = B * d.Ho * d.Wo, b1 = bn_base + 2 * i, b2 = b1 + 1;
     block_in[i] = x;
     block_out[i] = i == n - 1 ? x_out : a.out;
-    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c1));
-    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, Ch, eps, mom, partials, ticket_dev, a.mean1, a.rstd1, bn_mean_run + bn_off[2 * i],
-                             bn_var_run + bn_off[2 * i]));
-    PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
-    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c2));
-    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, Ch, eps, mom, partials, ticket_dev, a.mean2, a.rstd2, bn_mean_run + bn_off[2 * i + 1],
-                             bn_var_run + bn_off[2 * i + 1]));
-    PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, x, block_out[i]));
+    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, a.c1));
+    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, d.Co, eps, mom, partials, ticket_dev, a.mean1, a.rstd1, run_mean(b1), run_var(b1)));
+    PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
+    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, a.c2));
+    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, d.Co, eps, mom, partials, ticket_dev, a.mean2, a.rstd2, run_mean(b2), run_var(b2)));
+    const void* skip = x;
+    if (d.stride != 1 || d.Ci != d.Co) {
+      PPLL_TRY(launch_shortcut_fwd(s, x, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, shortcut));
+      skip = shortcut;
+    }
+    PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, skip, block_out[i]));
     x = block_out[i];
   }
   PPLL_TRY(mark_phase(1, s));   // module forward done
   if (after_forward) PPLL_TRY(after_forward());
   // ---- auxiliary forward
+  const int ba = bn_base + 2 * n;
   PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
-  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, ticket_dev, aux_mean, aux_rstd, bn_mean_run + bn_off[2 * n],
-                           bn_var_run + bn_off[2 * n]));
+  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, ticket_dev, aux_mean, aux_rstd, run_mean(ba), run_var(ba)));
   PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
   PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
   GemmArgs g = gemm_args();
@@ -476,20 +530,36 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials, ticket_dev,
                          grads + aux_bn_g, grads + aux_bn_b, d_aux));
   PPLL_TRY(launch_conv3x3_wgrad(s, x, d_aux, dt, B, H, W, Ch, A, 2, rq, grads + aux_conv_w));
-  PPLL_TRY(launch_conv3x3_dgrad(s, d_aux, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, nullptr, nullptr, r_gA));
+  void *gcur = r_gA, *gnext = r_gB;   // gradient with respect to the output of the block in hand / of the one before it
+  PPLL_TRY(launch_conv3x3_dgrad(s, d_aux, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, nullptr, nullptr, gcur));
   // ---- backward: basic blocks, last to first; nothing is produced for x_in
   for (int i = n - 1; i >= 0; --i) {
     const BasicBlockParams& p = rb_p[i];
+    const BasicBlockDims& d = rb_d[i];
     BasicBlockActs& a = rb_a[i];
-    PPLL_TRY(launch_bn_bwd(s, r_gA, block_out[i], a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, partials, ticket_dev,
+    const int rows = B * d.Ho * d.Wo;
+    PPLL_TRY(launch_bn_bwd(s, gcur, block_out[i], a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, partials, ticket_dev,
                            grads + p.bn2_g, grads + p.bn2_b, r_t2));
-    PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, H, W, Ch, Ch, 1, rq, grads + p.conv2_w));
-    PPLL_TRY(launch_conv3x3_dgrad(s, r_t2, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, nullptr, nullptr, r_t1));
-    PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, partials, ticket_dev,
+    PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, rq, grads + p.conv2_w));
+    PPLL_TRY(launch_conv3x3_dgrad(s, r_t2, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, nullptr, nullptr, r_t1));
+    PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, partials, ticket_dev,
                            grads + p.bn1_g, grads + p.bn1_b, r_t1));
-    PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, H, W, Ch, Ch, 1, rq, grads + p.conv1_w));
-    if (i > 0)
-      PPLL_TRY(launch_conv3x3_dgrad(s, r_t1, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, r_gA, block_out[i], r_gA));
+    PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, rq, grads + p.conv1_w));
+    if (i == 0 && !stem) break;   // the block input is the detached x_{j-1}
+    if (d.stride == 1 && d.Ci == d.Co) {   // identity shortcut folded into the input gradient
+      PPLL_TRY(launch_conv3x3_dgrad(s, r_t1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, 1, gcur, block_out[i], gcur));
+    } else {
+      PPLL_TRY(launch_conv3x3_dgrad(s, r_t1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, nullptr, nullptr,
+                                    gnext));
+      PPLL_TRY(launch_shortcut_bwd(s, gcur, block_out[i], dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, gnext));
+      std::swap(gcur, gnext);
+    }
+  }
+  if (stem) {
+    const int rows0 = B * in_h * in_w;
+    PPLL_TRY(launch_bn_bwd(s, gcur, stem_y, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, partials, ticket_dev,
+                           grads + stem_g, grads + stem_b, r_t1));
+    PPLL_TRY(launch_conv3x3_wgrad(s, x_in, r_t1, dt, B, in_h, in_w, cfg.img_c, in_c, 1, rq, grads + stem_w));
   }
   return PPLL_OK;
 }
@@ -540,25 +610,39 @@ int Block::forward_eval(const void* x_in, void* x_out, float* logits_out, hipStr
     return launch_gemm_generic(s, g);
   }
   const int Ch = cfg.channels, A = cfg.aux_channels, H = cfg.height, W = cfg.width, n = cfg.n_basic_blocks;
-  const int rows = B * H * W, Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1, arows = B * Ho * Wo;
+  const int Ho = (H - 1) / 2 + 1, Wo = (W - 1) / 2 + 1, arows = B * Ho * Wo;
   const float eps = cfg.bn_eps;
   const void* x = x_in;
+  if (stem) {
+    PPLL_TRY(launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c));
+    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[0], bn_var_run + bn_off[0], in_c, eps, stem_mean, stem_rstd));
+    PPLL_TRY(launch_bn_apply(s, stem_c, dt, B * in_h * in_w, in_c, stem_mean, stem_rstd, params + stem_g, params + stem_b, nullptr,
+                             stem_y));
+    x = stem_y;
+  }
   for (int i = 0; i < n; ++i) {
     const BasicBlockParams& p = rb_p[i];
+    const BasicBlockDims& d = rb_d[i];
     BasicBlockActs& a = rb_a[i];
+    const int rows = B * d.Ho * d.Wo, b1 = bn_base + 2 * i, b2 = b1 + 1;
     void* out = i == n - 1 ? x_out : a.out;
-    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c1));
-    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[2 * i], bn_var_run + bn_off[2 * i], Ch, eps, a.mean1, a.rstd1));
-    PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, Ch, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
-    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, H, W, Ch, Ch, 1, a.c2));
-    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[2 * i + 1], bn_var_run + bn_off[2 * i + 1], Ch, eps, a.mean2,
-                                     a.rstd2));
-    PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, Ch, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, x, out));
+    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, a.c1));
+    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[b1], bn_var_run + bn_off[b1], d.Co, eps, a.mean1, a.rstd1));
+    PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
+    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, a.c2));
+    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[b2], bn_var_run + bn_off[b2], d.Co, eps, a.mean2, a.rstd2));
+    const void* skip = x;
+    if (d.stride != 1 || d.Ci != d.Co) {
+      PPLL_TRY(launch_shortcut_fwd(s, x, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, shortcut));
+      skip = shortcut;
+    }
+    PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, skip, out));
     x = out;
   }
   if (!logits_out) return PPLL_OK;
   PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
-  PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[2 * n], bn_var_run + bn_off[2 * n], A, eps, aux_mean, aux_rstd));
+  PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[bn_base + 2 * n], bn_var_run + bn_off[bn_base + 2 * n], A, eps,
+                                   aux_mean, aux_rstd));
   PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
   PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
   g.A = pooled; g.a_dt = dt; g.a_sm = A; g.a_sk = 1;

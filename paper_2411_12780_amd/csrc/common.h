@@ -197,6 +197,11 @@ int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, 
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, ReduceQueue& rq, float* dw);
 int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
+// shortcut of a downsampling basic block: y = every stride-th pixel of x [B,H,W,Ci] with Co - Ci zero channels
+// appended; its transpose adds dy * (ymask > 0) into dx
+int launch_shortcut_fwd(hipStream_t s, const void* x, int dt, int B, int H, int W, int Ci, int Co, int stride, void* y);
+int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt, int B, int H, int W, int Ci, int Co,
+                        int stride, void* dx);
 // training-mode statistics over rows of x [rows, C]; also updates running stats
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum,
                     float* partials, int* ticket, float* mean, float* rstd, float* run_mean, float* run_var);

@@ -183,7 +183,50 @@ __global__ __launch_bounds__(256) void gap_bwd_kernel(const void* dpooled, int d
   int c = i % C; int b = i / ((size_t)HW * C);
   st_f(dx, i, ld_f(dpooled, (size_t)b * C + c, dt) / HW, dt);
 }
+
+// Parameter-free shortcut of a basic block that shrinks the map and widens it (the CIFAR ResNet of
+// Section 4.1): y[b,oy,ox,c] = x[b, oy*stride, ox*stride, c] for c < Ci, 0 for the appended channels.
+__global__ __launch_bounds__(256) void shortcut_fwd_kernel(const void* x, int dt, int B, int H, int W, int Ci, int Co,
+                                                           int stride, void* y) {
+  int Ho = out_dim(H, stride), Wo = out_dim(W, stride);
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * Ho * Wo * Co) return;
+  int c = i % Co; size_t pix = i / Co;
+  int ox = pix % Wo, oy = (pix / Wo) % Ho; int b = pix / ((size_t)Wo * Ho);
+  float v = c < Ci ? ld_f(x, (((size_t)b * H + oy * stride) * W + ox * stride) * Ci + c, dt) : 0.f;
+  st_f(y, i, v, dt);
+}
+
+// Its transpose added into dx: dx[b, oy*stride, ox*stride, c] += dy[b,oy,ox,c] * (ymask[b,oy,ox,c] > 0), c < Ci.
+// Every thread owns one element of dx.
+__global__ __launch_bounds__(256) void shortcut_bwd_kernel(const void* dy, const void* ymask, int dt, int B, int H, int W,
+                                                           int Ci, int Co, int stride, void* dx) {
+  int Ho = out_dim(H, stride), Wo = out_dim(W, stride);
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)B * Ho * Wo * Ci) return;
+  int c = i % Ci; size_t pix = i / Ci;
+  int ox = pix % Wo, oy = (pix / Wo) % Ho; int b = pix / ((size_t)Wo * Ho);
+  size_t yi = pix * Co + c;
+  if (!(ld_f(ymask, yi, dt) > 0.f)) return;
+  size_t xi = (((size_t)b * H + oy * stride) * W + ox * stride) * Ci + c;
+  st_f(dx, xi, ld_f(dx, xi, dt) + ld_f(dy, yi, dt), dt);
+}
 }  // namespace
+
+int launch_shortcut_fwd(hipStream_t s, const void* x, int dt, int B, int H, int W, int Ci, int Co, int stride, void* y) {
+  size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Co;
+  hipLaunchKernelGGL(shortcut_fwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, dt, B, H, W, Ci, Co, stride, y);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt, int B, int H, int W, int Ci, int Co,
+                        int stride, void* dx) {
+  size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Ci;
+  hipLaunchKernelGGL(shortcut_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dy, ymask, dt, B, H, W, Ci, Co, stride,
+                     dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
 
 int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                        int Co, int stride, void* y) {

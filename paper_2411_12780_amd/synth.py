@@ -46,6 +46,13 @@ WORKLOADS = {
                                 img_h=32, img_w=32, img_c=3, patch=16, tokens=5, dim=768, heads=12,
                                 mlp_dim=3072, depth=3, aux_depth=1, optimizer=SGD, momentum=0.9, nesterov=1,
                                 weight_decay=1e-4, ln_eps=1e-6, lr=0.01),
+    # second stage of ResNet-32 at the paper's CIFAR batch (Section 4.1: batch 1024; Section 4.3 names its
+    # 1024 x 32 x 16 x 16 activations): the basic block that halves the 32 x 32 x 16 input and doubles its
+    # channels, then four shape-keeping blocks
+    "resnet32_stage2_bf16": dict(arch=RESNET, precision=BF16, input_kind=ACTIVATION, batch=1024,
+                                 num_classes=10, channels=32, height=16, width=16, transition_block=1,
+                                 n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
+                                 nesterov=1, weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.01),
     # configs[3]: STL-10-shaped ViT stage
     "vit_large_image_bf16": dict(_VIT_STAGE, batch=64, img_h=96, img_w=96, patch=8, tokens=145),
 }
@@ -55,6 +62,36 @@ def workload(name: str, **overrides) -> dict:
     wl = dict(WORKLOADS[name])
     wl.update(overrides)
     return wl
+
+
+def resnet32_modules(k: int, **overrides) -> list:
+    """ResNet-32 for 32 x 32 images (Section 4.1) cut into k local modules: the stem (conv3x3 3 -> 16, BN,
+    ReLU) and 15 basic blocks, 5 each at 16 channels on 32 x 32, 32 on 16 x 16 and 64 on 8 x 8 maps, the
+    first block of the second and third group halving the map and doubling the channels.  The basic
+    blocks are dealt to the modules as evenly as possible, earlier modules taking the extra ones; the stem
+    belongs to module 0.  A module here holds at least one basic block, so k <= 15.  Every module carries
+    the conv-BN-ReLU-pool-Linear auxiliary head of the ResNet stage workload; the network's own classifier
+    (global average, Linear) is not part of any module."""
+    if not 1 <= k <= 15:
+        raise ValueError("k must be in 1..15")
+    base = dict(WORKLOADS["resnet32_stage2_bf16"], transition_block=0)
+    sizes = [15 // k + (1 if i < 15 % k else 0) for i in range(k)]
+    out, first = [], 0
+    for i, n in enumerate(sizes):
+        last = first + n - 1
+        group = last // 5                      # group of the module's output
+        wl = dict(base, n_basic_blocks=n, channels=16 << group, height=32 >> group, width=32 >> group)
+        for t in (5, 10):                      # the downsampling blocks of the network
+            if first <= t <= last:
+                wl["transition_block"] = t - first + 1
+        if (first <= 5 <= last) and (first <= 10 <= last):
+            raise ValueError("a module may hold one downsampling block: use k >= 2")
+        if i == 0:
+            wl.update(input_kind=IMAGE, img_h=32, img_w=32, img_c=3)
+        wl.update(overrides)
+        out.append(wl)
+        first += n
+    return out
 
 
 def aux_depth_schedule(d_max: int, n_blocks: int = 12, n: int = 3) -> list:

@@ -4,6 +4,7 @@ configurations before touching the device."""
 import os
 import re
 
+import numpy as np
 import pytest
 
 from paper_2411_12780_amd import binding as P
@@ -56,9 +57,25 @@ def test_bad_configurations_are_rejected_on_the_host():
     cfg.struct_size = 12
     with pytest.raises(P.PpllError):
         P.ppll_block_workspace_bytes(cfg)
-    res = P.make_config(dict(synth.workload("resnet_stage_bf16"), input_kind=synth.IMAGE))
-    with pytest.raises(P.PpllError):
-        P.ppll_block_workspace_bytes(res)
+    res = synth.workload("resnet_stage_bf16")
+    # a stem keeps the image size, a downsampling block needs an index inside the module and even channels
+    for bad in (dict(input_kind=synth.IMAGE, img_h=32, img_w=32, img_c=3), dict(transition_block=6),
+                dict(transition_block=-1), dict(transition_block=1, channels=31),
+                dict(input_kind=synth.IMAGE, transition_block=1, img_h=16, img_w=16, img_c=3)):
+        with pytest.raises(P.PpllError) as e:
+            P.ppll_block_workspace_bytes(P.make_config(dict(res, **bad)))
+        assert e.value.status == 2, bad
+
+
+def test_size_queries_of_every_resnet32_module():
+    wls = synth.resnet32_modules(8)
+    for wl in wls:
+        cfg = P.make_config(wl)
+        assert P.ppll_block_param_bytes(cfg) == 4 * O.param_count(oracle_cfg(wl))
+        assert P.ppll_block_in_bytes(cfg) == 2 * int(np.prod(synth.input_shape(wl)))
+        assert P.ppll_block_out_bytes(cfg) == 2 * int(np.prod(synth.output_shape(wl)))
+    # the chain of modules is accepted as a pipeline
+    assert P.ppll_pipeline_workspace_bytes([P.make_config(w) for w in wls], 2) > 0
 
 
 def test_null_and_misaligned_arguments():

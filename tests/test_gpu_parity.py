@@ -176,6 +176,27 @@ def test_resnet_fp32_odd_spatial_plain_sgd():
     run_case(wl, steps=2, check_bn=True)
 
 
+def test_resnet_fp32_downsampling_block_in_the_middle():
+    # basic block 1 of 3 halves a 10 x 12 map of 4 channels to 5 x 6 x 8: the backward pass crosses its
+    # zero-padded, subsampled shortcut and its stride-2 input gradient
+    wl = synth.workload("resnet_stage_bf16", precision=synth.FP32, batch=3, channels=8, height=5, width=6,
+                        n_basic_blocks=3, transition_block=2, aux_channels=12)
+    run_case(wl, steps=3, check_bn=True)
+
+
+def test_resnet_fp32_stem_in_front_of_the_blocks():
+    # first module of the network: the stem is trained, so the gradient also crosses basic block 0
+    wl = synth.workload("resnet_stage_bf16", precision=synth.FP32, input_kind=synth.IMAGE, img_h=6, img_w=10, img_c=3,
+                        batch=3, channels=8, height=6, width=10, n_basic_blocks=2, aux_channels=12)
+    run_case(wl, steps=3, check_bn=True)
+
+
+def test_resnet_fp32_stem_then_downsampling_first_block():
+    wl = synth.workload("resnet_stage_bf16", precision=synth.FP32, input_kind=synth.IMAGE, img_h=14, img_w=10, img_c=3,
+                        batch=2, channels=8, height=7, width=5, n_basic_blocks=2, transition_block=1, aux_channels=6)
+    run_case(wl, steps=2, check_bn=True)
+
+
 # ------------------------------------------------------------------ bf16 path
 def test_vit_bf16_medium():
     wl = synth.workload("vit_stage_bf16", batch=8, dim=128, heads=2, mlp_dim=256, depth=2, aux_depth=1)
@@ -262,6 +283,23 @@ def test_resnet_bf16_weight_gradient_on_the_mfma_path_edges():
     run_case(wl, steps=1, check_bn=True)
 
 
+def test_resnet_bf16_downsampling_first_block_on_the_mfma_path():
+    # 16 -> 32 channels with stride 2: matrix-core forward and the 16-input-channel weight gradient
+    wl = synth.workload("resnet32_stage2_bf16", batch=8, n_basic_blocks=2)
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
+def test_resnet_bf16_downsampling_block_behind_a_16_channel_block():
+    # blocks 4 and 5 of ResNet-32: a 16-channel block on the 32 x 32 map, then the downsampling block
+    wl = synth.workload("resnet32_stage2_bf16", batch=4, n_basic_blocks=2, transition_block=2)
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
+def test_resnet_bf16_stem_module():
+    wl = synth.resnet32_modules(8, batch=4)[0]
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
 def test_resnet_bf16_stage_full_size_natural_statistics():
     run_case(synth.workload("resnet_stage_bf16"), steps=2, check_bn=True, grad_tol=0.3)
 
@@ -285,6 +323,9 @@ def test_vit_large_image_bf16_full_size():
     ("vit_stage_bf16", dict(batch=8)),
     ("resnet_stage_bf16", dict(precision=synth.FP32, batch=4, channels=8, height=8, width=8, n_basic_blocks=2, aux_channels=8)),
     ("resnet_stage_bf16", dict(batch=8, n_basic_blocks=1)),
+    ("resnet_stage_bf16", dict(precision=synth.FP32, input_kind=synth.IMAGE, img_h=12, img_w=8, img_c=3, batch=3, channels=8,
+                               height=6, width=4, n_basic_blocks=2, transition_block=2, aux_channels=8)),
+    ("resnet32_stage2_bf16", dict(batch=8, n_basic_blocks=2)),
 ])
 def test_eval_forward_matches_the_oracle_after_training_steps(name, kw):
     """Two training steps (they move parameters and BatchNorm running statistics), then the evaluation-mode

@@ -152,6 +152,26 @@ def test_pipeline_twelve_one_layer_blocks_with_the_aux_depth_schedule(d_max):
             assert rel_l2(got, st.params[name]) <= 1e-4, (j, name)
 
 
+def test_pipeline_resnet32_in_eight_modules():
+    """ResNet-32 for 32 x 32 images cut into 8 local modules (Section 4.1): stem, 15 basic blocks with the
+    two downsampling blocks inside modules 2 and 5, one stream and one queue per module."""
+    small = dict(batch=4, precision=synth.FP32, lr=0.01)
+    wls = synth.resnet32_modules(8, **small)
+    flats = [synth.make_params(O.param_spec(oracle_cfg(w)), seed=40 + j, jitter=True) for j, w in enumerate(wls)]
+    batches = [synth.make_batch(wls[0], seed=9, index=i) for i in range(3)]
+    seq_losses, seq_params = _run_sequential(wls, flats, batches, 0.01)
+    losses, params = _run_pipeline(wls, flats, batches, 2, 0.01)
+    assert np.array_equal(losses, seq_losses)
+    for j in range(8):
+        for a, b in zip(params[j], seq_params[j]):
+            assert np.array_equal(a, b), j
+    ref_losses, states = _oracle_chain(wls, flats, batches, 0.01)
+    assert np.abs(seq_losses - ref_losses).max() <= 1e-4 * np.abs(ref_losses).max()
+    for j, st in enumerate(states):
+        for (name, _), got in zip(O.param_spec(st.cfg), seq_params[j]):
+            assert rel_l2(got, st.params[name]) <= 2e-4, (j, name)
+
+
 def test_pipeline_runs_ahead_without_host_syncs():
     """Enqueue several batches back to back (no sync in between): the bounded queues and the
     event edges alone must keep the order; results equal the synchronised run."""
