@@ -36,10 +36,26 @@ def step_flops(wl: dict) -> float:
         if wl["input_kind"] == 0:
             total += 2.0 * 2.0 * B * (T - 1) * wl["patch"] ** 2 * wl["img_c"] * D
         return total
-    C, A, HW = wl["channels"], wl["aux_channels"], wl["height"] * wl["width"]
-    conv = 2.0 * B * HW * 9 * C * C
-    aux = 2.0 * B * (HW // 4) * 9 * C * A
-    return 3.0 * conv * 2 * wl["n_basic_blocks"] - conv + 3.0 * aux + 3.0 * 2.0 * B * A * wl["num_classes"]
+    C, A, H, W = wl["channels"], wl["aux_channels"], wl["height"], wl["width"]
+    t = wl.get("transition_block", 0) - 1
+    stem = wl["input_kind"] == 0
+    total, first = 0.0, True
+    if stem:   # forward + weight gradient; the image needs no gradient
+        m = 2 if t >= 0 else 1
+        total += 2.0 * 2.0 * B * (m * H) * (m * W) * 9 * wl["img_c"] * (C // m)
+        first = False
+    for i in range(wl["n_basic_blocks"]):
+        if t >= 0 and i < t:
+            ci, co, hw = C // 2, C // 2, 4 * H * W
+        elif i == t:
+            ci, co, hw = C // 2, C, H * W
+        else:
+            ci, co, hw = C, C, H * W
+        conv1, conv2 = 2.0 * B * hw * 9 * ci * co, 2.0 * B * hw * 9 * co * co
+        total += (2.0 if first else 3.0) * conv1 + 3.0 * conv2   # the detached block input needs no gradient
+        first = False
+    aux = 2.0 * B * (((H - 1) // 2 + 1) * ((W - 1) // 2 + 1)) * 9 * C * A
+    return total + 3.0 * aux + 3.0 * 2.0 * B * A * wl["num_classes"]
 
 
 def measured_traffic(workload: str):
@@ -61,11 +77,16 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
         # Section 4.2's finest partition: 12 one-layer blocks, auxiliary depths from the d' = 4 schedule
         wls = synth.lpp_workloads(4)
         first = wls[0]
+    elif args.workload == "resnet32_k8":
+        # Section 4.1's ResNet-32 at its CIFAR batch of 1024, cut into 8 local modules
+        wls = synth.resnet32_modules(8)
+        first = wls[0]
     else:
         first, rest = synth.workload("vit_stage_bf16"), synth.workload("vit_stage_act_bf16")
         wls = [first, dict(rest), dict(rest), dict(rest)]
     for j, w in enumerate(wls):
         w["seed"] = j
+    vit = first["arch"] == 0
     cfgs = [P.make_config(w) for w in wls]
     depth = 2
     nbytes = P.ppll_pipeline_workspace_bytes(cfgs, depth)
@@ -98,9 +119,11 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
         "value": first["batch"] / (elapsed / args.steps), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": max(args.warmup, 8), "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": args.workload, "batch": first["batch"], "blocks": len(cfgs), "queue_depth": depth,
-                   "streams": len(cfgs), "optimizer": "adamw",
-                   "layers_per_block": [w["depth"] for w in wls], "aux_depths": [w["aux_depth"] for w in wls]},
+        "config": dict({"workload": args.workload, "batch": first["batch"], "blocks": len(cfgs), "queue_depth": depth,
+                        "streams": len(cfgs), "optimizer": "adamw" if first["optimizer"] == 1 else "sgd"},
+                       **({"layers_per_block": [w["depth"] for w in wls], "aux_depths": [w["aux_depth"] for w in wls]}
+                          if vit else {"basic_blocks_per_module": [w["n_basic_blocks"] for w in wls],
+                                       "channels": [w["channels"] for w in wls]})),
         "step_gflop": flops / 1e9, "step_tflops": flops / (elapsed / args.steps) / 1e12,
         "mfma_peak_frac_step": flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
         "losses_last_batch": [float(v) for v in losses],
@@ -139,14 +162,14 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
     f1, fa, Bp, Up = P.ppll_block_phase_times(blocks[0])
     P.ppll_block_phase_timers(blocks[0], False)
     s_stages = len(wls)
-    k_layers = wls[0]["aux_depth"] / wls[0]["depth"]
+    k_layers = wls[0]["aux_depth"] / wls[0]["depth"] if vit else None
     out["sequential_chain_ms_per_step"] = seq_ms
     out["pipelined_over_sequential"] = out["ms_per_step"] / seq_ms
     out["time_model"] = {
         "stage1_phases_ms": {"f_1": f1, "f_a1": fa, "B_a1": Bp, "U_a1": Up},
         "S_PPLL_stage1_ms": f1 + fa + Bp + Up,
         "s": s_stages, "k_aux_over_module_layers": k_layers, "k_measured_f_a1_over_f_1": fa / f1 if f1 > 0 else None,
-        "predicted_T_PPLL_over_T_PP": (k_layers + 1) / s_stages,
+        "predicted_T_PPLL_over_T_PP": (k_layers + 1) / s_stages if vit else None,
         "note": "Section 3.3.1 predicts T_PPLL / T_PP = (k + 1) / s for s devices; on one GPU the blocks share the "
                 "device, so the measured pipelined / sequential ratio above is bounded below by the chip's idle "
                 "fraction, not by 1 / s",
@@ -180,7 +203,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     dev = "cuda:0"
-    if args.workload in ("vit_pipeline4", "vit_lpp12"):
+    if args.workload in ("vit_pipeline4", "vit_lpp12", "resnet32_k8"):
         return bench_pipeline(args, torch, P, synth, dev)
     wl = synth.workload(args.workload)
     wl["seed"] = 0

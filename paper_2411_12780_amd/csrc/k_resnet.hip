@@ -214,6 +214,8 @@ __global__ __launch_bounds__(256) void shortcut_bwd_kernel(const void* dy, const
 }  // namespace
 
 int launch_shortcut_fwd(hipStream_t s, const void* x, int dt, int B, int H, int W, int Ci, int Co, int stride, void* y) {
+  if (eltwise_bf16_ok(dt, (size_t)B * H * W * Ci, Ci, Co, x, y, nullptr))
+    return launch_shortcut_fwd_bf16(s, x, B, H, W, Ci, Co, stride, y);
   size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Co;
   hipLaunchKernelGGL(shortcut_fwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, dt, B, H, W, Ci, Co, stride, y);
   PPLL_HIP(hipGetLastError());
@@ -221,6 +223,8 @@ int launch_shortcut_fwd(hipStream_t s, const void* x, int dt, int B, int H, int 
 }
 int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt, int B, int H, int W, int Ci, int Co,
                         int stride, void* dx) {
+  if (eltwise_bf16_ok(dt, (size_t)B * H * W * Ci, Ci, Co, dy, ymask, dx))
+    return launch_shortcut_bwd_bf16(s, dy, ymask, B, H, W, Ci, Co, stride, dx);
   size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Ci;
   hipLaunchKernelGGL(shortcut_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dy, ymask, dt, B, H, W, Ci, Co, stride,
                      dx);
@@ -350,6 +354,7 @@ int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, v
   return PPLL_OK;
 }
 int launch_gap_bwd(hipStream_t s, const void* dpooled, int dt, int B, int HW, int C, void* dx) {
+  if (eltwise_bf16_ok(dt, (size_t)B * HW * C, C, C, dpooled, dx, nullptr)) return launch_gap_bwd_bf16(s, dpooled, B, HW, C, dx);
   size_t total = (size_t)B * HW * C;
   hipLaunchKernelGGL(gap_bwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dpooled, dt, B, HW, C, dx);
   PPLL_HIP(hipGetLastError());

@@ -37,7 +37,7 @@ struct ConvArgs {
 // MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = channels reduced.
 template <int MODE>
 __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
-  extern __shared__ __align__(16) char wl[];        // [NO][9*KC] bf16, row stride RSW bytes
+  extern __shared__ __align__(16) char wl[];        // [NO rounded up to 32][9*KC] bf16, row stride RSW bytes
   const int NO = MODE == 0 ? p.Co : p.Ci, KC = MODE == 0 ? p.Ci : p.Co;
   const int RSW = 18 * KC + 16;
   const int Ho = out_dim(p.H, p.stride), Wo = out_dim(p.W, p.stride);
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   const long pix = (long)blockIdx.x * 128 + wave * 32 + li;
   const bool live = pix < P;
   const int ox = (int)(pix % OW), oy = (int)((pix / OW) % OH), b = (int)(pix / ((long)OW * OH));
-  const int NT = NO / 32;
+  const int NT = (NO + 31) / 32;     // NO = 16: the upper half of the one tile is never stored
   f32x16 acc[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t)
@@ -118,6 +118,7 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int c = 32 * t + 8 * q + 4 * hh;
+        if (c >= NO) continue;
         float v[4] = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
         if (MODE == 1 && p.dres) {
           const uint2 m = *reinterpret_cast<const uint2*>(p.ymask + pix * NO + c);
@@ -175,20 +176,28 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_bf16_kernel(const uint16_t*
   for (int lp = 0; lp < WG_PIX_F; ++lp) {
     const float d = bf16_to_f32(dys[(size_t)lp * CO + co]);
     const uint16_t* xp = xs + (size_t)lp * 9 * Ci + cig * CPT;
-    uint32_t xv[9][CPT / 2];
+    if constexpr (CPT == 1) {      // one input channel per thread: nine 16-bit reads
+      uint16_t x1[9];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) {
-      const uint32_t* xw = reinterpret_cast<const uint32_t*>(xp + t * Ci);
+      for (int t = 0; t < 9; ++t) x1[t] = xp[t * Ci];
 #pragma unroll
-      for (int j = 0; j < CPT / 2; ++j) xv[t][j] = xw[j];
-    }
+      for (int t = 0; t < 9; ++t) acc[t][0] = fmaf(bf16_to_f32(x1[t]), d, acc[t][0]);
+    } else {
+      uint32_t xv[9][CPT / 2];
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+      for (int t = 0; t < 9; ++t) {
+        const uint32_t* xw = reinterpret_cast<const uint32_t*>(xp + t * Ci);
 #pragma unroll
-      for (int j = 0; j < CPT / 2; ++j) {
-        acc[t][2 * j] = fmaf(lo_bf(xv[t][j]), d, acc[t][2 * j]);
-        acc[t][2 * j + 1] = fmaf(hi_bf(xv[t][j]), d, acc[t][2 * j + 1]);
+        for (int j = 0; j < CPT / 2; ++j) xv[t][j] = xw[j];
       }
+#pragma unroll
+      for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int j = 0; j < CPT / 2; ++j) {
+          acc[t][2 * j] = fmaf(lo_bf(xv[t][j]), d, acc[t][2 * j]);
+          acc[t][2 * j + 1] = fmaf(hi_bf(xv[t][j]), d, acc[t][2 * j + 1]);
+        }
+    }
   }
   float* out = partial + (size_t)blockIdx.x * 9 * Ci * CO;
 #pragma unroll
@@ -379,7 +388,75 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_bf16_kernel(const uint16_t* 
   *reinterpret_cast<uint4*>(dx + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// Elementwise helpers of the stage, 8 channels (16 bytes) per thread, 32-bit index arithmetic.
+// dx[b, p, c] = dpooled[b, c] / HW
+__global__ __launch_bounds__(256) void gap_bwd_bf16_kernel(const uint16_t* dpooled, uint32_t HW, uint32_t C, uint32_t chunks,
+                                                           uint16_t* dx) {
+  const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  const uint32_t cpr = C / 8, cg = i % cpr, b = (i / cpr) / HW;
+  const uint4 v = *reinterpret_cast<const uint4*>(dpooled + (size_t)b * C + 8 * cg);
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(&v);
+  const float hw = (float)HW;
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) o[j] = pack2(lo_bf(w[j]) / hw, hi_bf(w[j]) / hw);
+  *reinterpret_cast<uint4*>(dx + (size_t)i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// y[b,oy,ox,c] = x[b, oy*stride, ox*stride, c] for c < Ci, 0 above
+__global__ __launch_bounds__(256) void shortcut_fwd_bf16_kernel(const uint16_t* x, uint32_t H, uint32_t W, uint32_t Ci,
+                                                                uint32_t Co, uint32_t stride, uint32_t Ho, uint32_t Wo,
+                                                                uint32_t chunks, uint16_t* y) {
+  const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  const uint32_t cpr = Co / 8, cg = i % cpr, pix = i / cpr, ox = pix % Wo, oy = (pix / Wo) % Ho, b = pix / (Wo * Ho);
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (8 * cg < Ci) v = *reinterpret_cast<const uint4*>(x + ((size_t)(b * H + oy * stride) * W + ox * stride) * Ci + 8 * cg);
+  *reinterpret_cast<uint4*>(y + (size_t)i * 8) = v;
+}
+
+// dx[b, oy*stride, ox*stride, c] += dy[b,oy,ox,c] * (ymask[b,oy,ox,c] > 0) for c < Ci
+__global__ __launch_bounds__(256) void shortcut_bwd_bf16_kernel(const uint16_t* dy, const uint16_t* ymask, uint32_t H,
+                                                                uint32_t W, uint32_t Ci, uint32_t Co, uint32_t stride,
+                                                                uint32_t Ho, uint32_t Wo, uint32_t chunks, uint16_t* dx) {
+  const uint32_t i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= chunks) return;
+  const uint32_t cpr = Ci / 8, cg = i % cpr, pix = i / cpr, ox = pix % Wo, oy = (pix / Wo) % Ho, b = pix / (Wo * Ho);
+  const size_t yi = (size_t)pix * Co + 8 * cg, xi = ((size_t)(b * H + oy * stride) * W + ox * stride) * Ci + 8 * cg;
+  const uint4 dv = *reinterpret_cast<const uint4*>(dy + yi), mv = *reinterpret_cast<const uint4*>(ymask + yi);
+  const uint4 xv = *reinterpret_cast<const uint4*>(dx + xi);
+  const uint32_t* dw = reinterpret_cast<const uint32_t*>(&dv);
+  const uint32_t* mw = reinterpret_cast<const uint32_t*>(&mv);
+  const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float lo = lo_bf(xw[j]) + (lo_bf(mw[j]) > 0.f ? lo_bf(dw[j]) : 0.f);
+    const float hi = hi_bf(xw[j]) + (hi_bf(mw[j]) > 0.f ? hi_bf(dw[j]) : 0.f);
+    o[j] = pack2(lo, hi);
+  }
+  *reinterpret_cast<uint4*>(dx + xi) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
 bool al16(const void* p) { return !(((uintptr_t)p) & 15); }
+
+// LDS of the implicit-GEMM convolution: the filter as [produced channels rounded up to 32][9 * reduced + 8] bf16
+size_t conv_mfma_lds(int produced, int reduced) { return (size_t)((produced + 31) / 32 * 32) * (18 * reduced + 16); }
+constexpr size_t CONV_MFMA_LDS_MAX = 96 * 1024;
+template <int MODE>
+int conv_mfma_allow_lds(size_t lds) {
+  static bool raised[64] = {};    // per device: the attribute belongs to the device's copy of the kernel
+  if (lds <= 64 * 1024) return PPLL_OK;
+  int dev = 0;
+  PPLL_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64 || !raised[dev]) {
+    PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)CONV_MFMA_LDS_MAX));
+    if (dev >= 0 && dev < 64) raised[dev] = true;
+  }
+  return PPLL_OK;
+}
 }  // namespace
 
 bool conv_bf16_supported(int dt, int wdt, int Ci, int Co, const void* a, const void* b, const void* c) {
@@ -392,7 +469,8 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
                             int stride, void* y) {
   ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr};
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
-  const size_t lds = (size_t)Co * (18 * Ci + 16);
+  const size_t lds = conv_mfma_lds(Co, Ci);
+  PPLL_TRY(conv_mfma_allow_lds<0>(lds));
   hipLaunchKernelGGL(conv3x3_mfma_kernel<0>, dim3((unsigned)((P + 127) / 128)), dim3(256), lds, s, p);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
@@ -403,16 +481,20 @@ int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int 
   ConvArgs p{(const uint16_t*)dy, (const uint16_t*)w, (uint16_t*)dx, B, H, W, Ci, Co, stride, (const uint16_t*)dres,
              (const uint16_t*)ymask};
   const long P = (long)B * H * W;
-  const size_t lds = (size_t)Ci * (18 * Co + 16);
+  const size_t lds = conv_mfma_lds(Ci, Co);
+  PPLL_TRY(conv_mfma_allow_lds<1>(lds));
   hipLaunchKernelGGL(conv3x3_mfma_kernel<1>, dim3((unsigned)((P + 127) / 128)), dim3(256), lds, s, p);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
 
-// forward and input gradient need Co resp. Ci to be a multiple of 32 (one MFMA tile of produced channels)
-bool conv_fwd_bf16_ok(int Ci, int Co) { return Co % 32 == 0 && Co <= 64 && (size_t)Co * (18 * Ci + 16) <= 64 * 1024; }
-bool conv_dgrad_bf16_ok(int Ci, int Co) { return Ci % 32 == 0 && Ci <= 64 && (size_t)Ci * (18 * Co + 16) <= 64 * 1024; }
-bool conv_wgrad_bf16_ok(int Ci, int Co) { return (Co == 32 || Co == 64) && Ci % 16 == 0 && Ci >= 16 && Ci <= 64; }
+// forward and input gradient produce up to 64 channels (two MFMA tiles of 32; 16 and 48 leave half a tile idle)
+bool conv_fwd_bf16_ok(int Ci, int Co) { return Co % 16 == 0 && Co <= 64 && conv_mfma_lds(Co, Ci) <= CONV_MFMA_LDS_MAX; }
+bool conv_dgrad_bf16_ok(int Ci, int Co) { return Ci % 16 == 0 && Ci <= 64 && conv_mfma_lds(Ci, Co) <= CONV_MFMA_LDS_MAX; }
+bool conv_wgrad_bf16_ok(int Ci, int Co) {
+  if (Co == 16) return Ci == 16;
+  return (Co == 32 || Co == 64) && Ci % 16 == 0 && Ci >= 16 && Ci <= 64;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Weight gradient on the matrix cores for 32 -> 32 channels, stride 1, 16-pixel image rows:
@@ -566,7 +648,8 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
     return rq.reduce(s, queued, partials, blocks, nw, nw, 1.0f, dw);
   }
   int st = PPLL_ERR_CONFIG;
-  if (Co == 32 && cpt == 2) st = wgrad_launch<32, 2>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  if (Co == 16 && cpt == 1) st = wgrad_launch<16, 1>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
+  else if (Co == 32 && cpt == 2) st = wgrad_launch<32, 2>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
   else if (Co == 32 && cpt == 4) st = wgrad_launch<32, 4>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
   else if (Co == 32 && cpt == 6) st = wgrad_launch<32, 6>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
   else if (Co == 32 && cpt == 8) st = wgrad_launch<32, 8>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
@@ -589,6 +672,36 @@ static int bn_blocks(int rows, int C) {
   return blocks < 1 ? 1 : (blocks > 64 ? 64 : blocks);
 }
 size_t bn_bf16_partial_floats(int rows, int C) { return (size_t)bn_blocks(rows, C) * 2 * C; }
+
+// The three helpers need channel counts that are multiples of 8, 16-byte aligned tensors and fewer than 2^31 elements.
+bool eltwise_bf16_ok(int dt, size_t elems, int C0, int C1, const void* a, const void* b, const void* c) {
+  return dt == BF16 && (C0 % 8) == 0 && (C1 % 8) == 0 && elems < ((size_t)1 << 31) && al16(a) && al16(b) && al16(c);
+}
+int launch_gap_bwd_bf16(hipStream_t s, const void* dpooled, int B, int HW, int C, void* dx) {
+  const uint32_t chunks = (uint32_t)((size_t)B * HW * C / 8);
+  hipLaunchKernelGGL(gap_bwd_bf16_kernel, dim3((chunks + 255) / 256), dim3(256), 0, s, (const uint16_t*)dpooled, (uint32_t)HW,
+                     (uint32_t)C, chunks, (uint16_t*)dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_shortcut_fwd_bf16(hipStream_t s, const void* x, int B, int H, int W, int Ci, int Co, int stride, void* y) {
+  const uint32_t Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
+  const uint32_t chunks = (uint32_t)((size_t)B * Ho * Wo * Co / 8);
+  hipLaunchKernelGGL(shortcut_fwd_bf16_kernel, dim3((chunks + 255) / 256), dim3(256), 0, s, (const uint16_t*)x, (uint32_t)H,
+                     (uint32_t)W, (uint32_t)Ci, (uint32_t)Co, (uint32_t)stride, Ho, Wo, chunks, (uint16_t*)y);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_shortcut_bwd_bf16(hipStream_t s, const void* dy, const void* ymask, int B, int H, int W, int Ci, int Co, int stride,
+                             void* dx) {
+  const uint32_t Ho = (H - 1) / stride + 1, Wo = (W - 1) / stride + 1;
+  const uint32_t chunks = (uint32_t)((size_t)B * Ho * Wo * Ci / 8);
+  hipLaunchKernelGGL(shortcut_bwd_bf16_kernel, dim3((chunks + 255) / 256), dim3(256), 0, s, (const uint16_t*)dy,
+                     (const uint16_t*)ymask, (uint32_t)H, (uint32_t)W, (uint32_t)Ci, (uint32_t)Co, (uint32_t)stride, Ho, Wo, chunks,
+                     (uint16_t*)dx);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
 
 int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
                          int* ticket, float* mean, float* rstd, float* run_mean, float* run_var) {

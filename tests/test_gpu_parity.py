@@ -295,6 +295,19 @@ def test_resnet_bf16_downsampling_block_behind_a_16_channel_block():
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
 
 
+def test_resnet_bf16_third_stage_64_channels():
+    # 32 -> 64 downsampling block, then a 64-channel block on the 8 x 8 map: the filter of a 64 -> 64
+    # convolution needs more LDS than a kernel gets without asking (73 KiB)
+    wl = synth.workload("resnet32_stage2_bf16", batch=8, channels=64, height=8, width=8, n_basic_blocks=2)
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
+def test_resnet_bf16_16_channels_ragged():
+    # 16 produced channels fill half a matrix-core tile; 3*7*9 pixels leave a ragged last workgroup
+    wl = synth.workload("resnet_stage_bf16", n_basic_blocks=2, batch=3, height=7, width=9, channels=16, aux_channels=32)
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
 def test_resnet_bf16_stem_module():
     wl = synth.resnet32_modules(8, batch=4)[0]
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
