@@ -86,6 +86,11 @@ struct Block {
   bool stem = false;                     // conv3x3 (img_c -> in_c) - BN - ReLU on the image in front of the blocks
   size_t stem_w = 0, stem_g = 0, stem_b = 0;
   void *stem_c = nullptr, *stem_y = nullptr, *shortcut = nullptr;
+  // bf16 path: the image padded to 16 channels and the stem filter padded likewise, so that the stem runs on the
+  // 16-channel matrix-core kernels (null: the stem runs on the generic kernels)
+  void *stem_xp = nullptr, *stem_wp = nullptr;
+  bool stem_pad = false;
+  int stem_conv_fwd(const void* x_in, hipStream_t s);
   float *stem_mean = nullptr, *stem_rstd = nullptr;
   int bn_base = 0;                       // index of rb0.bn1 among the BatchNorm layers (1 behind a stem)
   size_t aux_conv_w = 0, aux_bn_g = 0, aux_bn_b = 0;

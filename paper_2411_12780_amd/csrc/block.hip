@@ -224,6 +224,13 @@ size_t Block::plan(char* base) {
     if (stem) {
       stem_c = bump.take(widest * esz); stem_y = bump.take(widest * esz);
       stem_mean = bump.floats(in_c); stem_rstd = bump.floats(in_c);
+      stem_xp = stem_wp = nullptr;
+      stem_pad = dt == BF16 && cfg.img_c < 16 && in_c % 16 == 0 && in_c <= 64;
+      if (stem_pad) {
+        stem_xp = bump.take((size_t)B * in_h * in_w * 16 * esz);
+        stem_wp = bump.take((size_t)9 * 16 * in_c * esz);
+        grow((size_t)conv3x3_wgrad_partial_floats(B, in_h, in_w, 16, in_c, 1));
+      }
       grow((size_t)conv3x3_wgrad_partial_floats(B, in_h, in_w, cfg.img_c, in_c, 1));
       grow((size_t)bn_partial_floats(B * in_h * in_w, in_c));
     }
@@ -272,7 +279,7 @@ size_t Block::plan(char* base) {
     for (const BasicBlockDims& d : rb_d)
       arena_floats += (size_t)conv3x3_wgrad_partial_floats(cfg.batch, d.Hin, d.Win, d.Ci, d.Co, d.stride) +
                       (size_t)conv3x3_wgrad_partial_floats(cfg.batch, d.Ho, d.Wo, d.Co, d.Co, 1) + 128;
-    if (stem) arena_floats += (size_t)conv3x3_wgrad_partial_floats(cfg.batch, in_h, in_w, cfg.img_c, in_c, 1) + 64;
+    if (stem) arena_floats += (size_t)conv3x3_wgrad_partial_floats(cfg.batch, in_h, in_w, stem_pad ? 16 : cfg.img_c, in_c, 1) + 64;
   }
   rq.arena = arena_floats ? bump.floats(arena_floats) : nullptr;
   rq.arena_floats = arena_floats;
@@ -461,6 +468,15 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
 }
 
 // ------------------------------------------------------------------ ResNet
+// stem convolution img_c -> in_c into stem_c
+int Block::stem_conv_fwd(const void* x_in, hipStream_t s) {
+  const int B = cfg.batch;
+  if (!stem_pad) return launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c);
+  PPLL_TRY(launch_pad_channels16(s, x_in, (size_t)B * in_h * in_w, cfg.img_c, stem_xp));
+  PPLL_TRY(launch_pad_filter16(s, params + stem_w, cfg.img_c, in_c, stem_wp));
+  return launch_conv3x3_fwd(s, stem_xp, stem_wp, BF16, dt, B, in_h, in_w, 16, in_c, 1, stem_c);
+}
+
 int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
                        const std::function<int()>& after_forward) {
   const int B = cfg.batch, Ch = cfg.channels, A = cfg.aux_channels, H = cfg.height, W = cfg.width;
@@ -474,7 +490,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   const void* x = x_in;
   if (stem) {
     const int rows0 = B * in_h * in_w;
-    PPLL_TRY(launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c));
+    PPLL_TRY(stem_conv_fwd(x_in, s));
     PPLL_TRY(launch_bn_stats(s, stem_c, dt, rows0, in_c, eps, mom, partials, ticket_dev, stem_mean, stem_rstd, run_mean(0),
                              run_var(0)));
     PPLL_TRY(launch_bn_apply(s, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, params + stem_b, nullptr, stem_y));
@@ -559,7 +575,10 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     const int rows0 = B * in_h * in_w;
     PPLL_TRY(launch_bn_bwd(s, gcur, stem_y, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, partials, ticket_dev,
                            grads + stem_g, grads + stem_b, r_t1));
-    PPLL_TRY(launch_conv3x3_wgrad(s, x_in, r_t1, dt, B, in_h, in_w, cfg.img_c, in_c, 1, rq, grads + stem_w));
+    if (stem_pad)   // the padded image is still in place from the forward pass
+      PPLL_TRY(launch_conv3x3_wgrad(s, stem_xp, r_t1, dt, B, in_h, in_w, 16, in_c, 1, rq, grads + stem_w, cfg.img_c));
+    else
+      PPLL_TRY(launch_conv3x3_wgrad(s, x_in, r_t1, dt, B, in_h, in_w, cfg.img_c, in_c, 1, rq, grads + stem_w));
   }
   return PPLL_OK;
 }
@@ -614,7 +633,7 @@ int Block::forward_eval(const void* x_in, void* x_out, float* logits_out, hipStr
   const float eps = cfg.bn_eps;
   const void* x = x_in;
   if (stem) {
-    PPLL_TRY(launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c));
+    PPLL_TRY(stem_conv_fwd(x_in, s));
     PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[0], bn_var_run + bn_off[0], in_c, eps, stem_mean, stem_rstd));
     PPLL_TRY(launch_bn_apply(s, stem_c, dt, B * in_h * in_w, in_c, stem_mean, stem_rstd, params + stem_g, params + stem_b, nullptr,
                              stem_y));

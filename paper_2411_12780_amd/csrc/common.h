@@ -194,8 +194,16 @@ int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int
 // dx = dgrad(dy, w) (+ dres * (ymask > 0) when dres != null)
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, const void* dres, const void* ymask, void* dx);
+// dw [9][ci_keep][Co]: the gradient for the first ci_keep input channels (all of them by default; fewer when
+// the caller padded x with zero channels)
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci,
-                         int Co, int stride, ReduceQueue& rq, float* dw);
+                         int Co, int stride, ReduceQueue& rq, float* dw, int ci_keep = -1);
+// second stage of a convolution weight gradient: adds `rows` partial filters [9][Ci][Co] into dw [9][keep][Co]
+int reduce_conv_filters(hipStream_t s, ReduceQueue& rq, bool queued, const float* partials, int rows, int Ci, int Co,
+                        int keep, float* dw);
+// x [P, c] -> y [P, 16] with zero channels appended (c < 16); w [9][c][Co] (fp32 master) -> wp [9][16][Co] bf16
+int launch_pad_channels16(hipStream_t s, const void* x, size_t P, int c, void* y);
+int launch_pad_filter16(hipStream_t s, const float* w, int c, int Co, void* wp);
 int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
 // shortcut of a downsampling basic block: y = every stride-th pixel of x [B,H,W,Ci] with Co - Ci zero channels
 // appended; its transpose adds dy * (ymask > 0) into dx
@@ -225,7 +233,7 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
                               int stride, const void* dres, const void* ymask, void* dx);
 int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co,
-                              int stride, ReduceQueue& rq, float* dw);
+                              int stride, ReduceQueue& rq, float* dw, int ci_keep);
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
 bool eltwise_bf16_ok(int dt, size_t elems, int C0, int C1, const void* a, const void* b, const void* c);
 int launch_gap_bwd_bf16(hipStream_t s, const void* dpooled, int B, int HW, int C, void* dx);

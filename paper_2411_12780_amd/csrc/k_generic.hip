@@ -533,7 +533,7 @@ int launch_layernorm_bwd(hipStream_t s, const void* dy, const void* x, int dt, l
 
 // ===================================================================== cross-entropy
 namespace {
-constexpr size_t CE_LDS_FLOATS = 8192;
+constexpr size_t CE_LDS_FLOATS = 12288;   // 48 KiB: batch 1024 x 10 classes fits
 // One workgroup: mean loss (also copied to loss2 when given), dlogits, and the head's bias gradient
 // db[c] = sum over the batch of dlogits[b][c], added in batch order.
 __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* logits, const int32_t* labels, int B, int C,

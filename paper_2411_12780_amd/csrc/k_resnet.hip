@@ -211,7 +211,38 @@ __global__ __launch_bounds__(256) void shortcut_bwd_kernel(const void* dy, const
   size_t xi = (((size_t)b * H + oy * stride) * W + ox * stride) * Ci + c;
   st_f(dx, xi, ld_f(dx, xi, dt) + ld_f(dy, yi, dt), dt);
 }
+
+// x [P, c] -> y [P, 16] bf16 with zero channels appended; one pixel per thread
+__global__ __launch_bounds__(256) void pad_channels16_kernel(const uint16_t* x, size_t P, int c, uint16_t* y) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= P) return;
+  uint16_t v[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) v[j] = j < c ? x[i * c + j] : (uint16_t)0;
+  uint4* out = reinterpret_cast<uint4*>(y + i * 16);
+  out[0] = *reinterpret_cast<const uint4*>(v);
+  out[1] = *reinterpret_cast<const uint4*>(v + 8);
+}
+// w [9][c][Co] fp32 -> wp [9][16][Co] bf16, zero rows appended
+__global__ __launch_bounds__(256) void pad_filter16_kernel(const float* w, int c, int Co, uint16_t* wp) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= 9 * 16 * Co) return;
+  const int co = i % Co, ci = (i / Co) % 16, tap = i / (16 * Co);
+  wp[i] = ci < c ? f32_to_bf16(w[((size_t)tap * c + ci) * Co + co]) : (uint16_t)0;
+}
 }  // namespace
+
+int launch_pad_channels16(hipStream_t s, const void* x, size_t P, int c, void* y) {
+  hipLaunchKernelGGL(pad_channels16_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, (const uint16_t*)x, P, c,
+                     (uint16_t*)y);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+int launch_pad_filter16(hipStream_t s, const float* w, int c, int Co, void* wp) {
+  hipLaunchKernelGGL(pad_filter16_kernel, dim3((9 * 16 * Co + 255) / 256), dim3(256), 0, s, w, c, Co, (uint16_t*)wp);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
 
 int launch_shortcut_fwd(hipStream_t s, const void* x, int dt, int B, int H, int W, int Ci, int Co, int stride, void* y) {
   if (eltwise_bf16_ok(dt, (size_t)B * H * W * Ci, Ci, Co, x, y, nullptr))
@@ -263,16 +294,26 @@ int conv3x3_wgrad_partial_floats(int B, int H, int W, int Ci, int Co, int stride
   size_t a = wgrad_chunks(B, H, W, stride) * 9 * Ci * Co, b = conv3x3_wgrad_bf16_partial_floats(B, H, W, Ci, Co, stride);
   return (int)(a > b ? a : b);
 }
+int reduce_conv_filters(hipStream_t s, ReduceQueue& rq, bool queued, const float* partials, int rows, int Ci, int Co,
+                        int keep, float* dw) {
+  const int nw = 9 * Ci * Co;
+  if (keep == Ci) return rq.reduce(s, queued, partials, rows, nw, nw, 1.0f, dw);
+  for (int tap = 0; tap < 9; ++tap)   // the leading `keep` input channels of every tap
+    PPLL_TRY(rq.reduce(s, queued, partials + (size_t)tap * Ci * Co, rows, keep * Co, nw, 1.0f, dw + (size_t)tap * keep * Co));
+  return PPLL_OK;
+}
+
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci, int Co,
-                         int stride, ReduceQueue& rq, float* dw) {
+                         int stride, ReduceQueue& rq, float* dw, int ci_keep) {
+  if (ci_keep < 0 || ci_keep > Ci) ci_keep = Ci;
   if (conv_bf16_supported(dt, BF16, Ci, Co, x, dy, dw) && conv_wgrad_bf16_ok(Ci, Co))
-    return launch_conv3x3_wgrad_bf16(s, x, dy, B, H, W, Ci, Co, stride, rq, dw);
+    return launch_conv3x3_wgrad_bf16(s, x, dy, B, H, W, Ci, Co, stride, rq, dw, ci_keep);
   int chunks = (int)wgrad_chunks(B, H, W, stride), nw = 9 * Ci * Co;
   bool queued;
   float* partials = rq.space((size_t)chunks * nw, &queued);
   hipLaunchKernelGGL(conv3x3_wgrad_kernel, dim3(chunks), dim3(256), 0, s, x, dy, dt, B, H, W, Ci, Co, stride, partials);
   PPLL_HIP(hipGetLastError());
-  return rq.reduce(s, queued, partials, chunks, nw, nw, 1.0f, dw);
+  return reduce_conv_filters(s, rq, queued, partials, chunks, Ci, Co, ci_keep, dw);
 }
 
 int bn_partial_floats(int rows, int C) {

@@ -220,7 +220,48 @@ struct BnSumArgs {
   float* run_mean; float* run_var;
 };
 
+// Adds the workgroup partials [nblocks][2][C] in workgroup order and finishes mean / rstd / running
+// statistics (KIND 0) or dbeta / dgamma (KIND 1).  One workgroup of 256 threads.
 template <int KIND>
+__device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, float (*red)[17]) {
+  const int tid = threadIdx.x;
+  // 2C values; 256/(2C) thread groups take the workgroup partials round-robin, then one thread
+  // per value adds the groups in order
+  const int nv = 2 * p.C, parts = 256 / nv;
+  if (tid < nv * parts) {
+    const int v = tid % nv, part = tid / nv;
+    float t = 0.f;
+    for (unsigned bk = part; bk < nblocks; bk += 8 * parts) {   // eight loads in flight; summed in workgroup order
+      float q[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const unsigned bu = bk + u * parts;
+        q[u] = bu < nblocks ? p.partial[(size_t)bu * nv + v] : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t += q[u];
+    }
+    red[tid][0] = t;
+  }
+  __syncthreads();
+  if (tid < p.C) {
+    float s0 = 0.f, s1 = 0.f;
+    for (int part = 0; part < parts; ++part) { s0 += red[part * nv + tid][0]; s1 += red[part * nv + p.C + tid][0]; }
+    if (KIND == 0) {
+      const float n = (float)p.rows, m = s0 / n;
+      const float var = fmaxf(s1 / n - m * m, 0.f);
+      p.out0[tid] = m;
+      p.out1[tid] = 1.0f / sqrtf(var + p.eps);
+      p.run_mean[tid] = (1.f - p.momentum) * p.run_mean[tid] + p.momentum * m;
+      p.run_var[tid] = (1.f - p.momentum) * p.run_var[tid] + p.momentum * var * (n / (n - 1.f));
+    } else {
+      p.out0[tid] = s0;
+      p.out1[tid] = s1;
+    }
+  }
+}
+
+template <int KIND, bool TICKET>
 __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
   __shared__ float red[256][17];
   __shared__ int is_last;
@@ -288,49 +329,21 @@ __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
     for (int l = 0; l < lanes; ++l) t += red[l * groups + g][8 * which + j];
     p.partial[(size_t)blockIdx.x * 2 * p.C + tid] = t;
   }
+  if (!TICKET) return;                        // wide launches: a one-workgroup kernel adds the partials afterwards
   __threadfence();
   __syncthreads();
   if (tid == 0) is_last = atomicAdd(p.ticket, 1) == (int)gridDim.x - 1;
   __syncthreads();
   if (!is_last) return;
   __threadfence();
-  {
-    // 2C values; 256/(2C) thread groups take the workgroup partials round-robin, then one thread
-    // per value adds the groups in order
-    const int nv = 2 * p.C, parts = 256 / nv;
-    if (tid < nv * parts) {
-      const int v = tid % nv, part = tid / nv;
-      float t = 0.f;
-      for (unsigned bk = part; bk < gridDim.x; bk += 8 * parts) {   // eight loads in flight; summed in workgroup order
-        float q[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-          const unsigned bu = bk + u * parts;
-          q[u] = bu < gridDim.x ? p.partial[(size_t)bu * nv + v] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) t += q[u];
-      }
-      red[tid][0] = t;
-    }
-    __syncthreads();
-    if (tid < p.C) {
-      float s0 = 0.f, s1 = 0.f;
-      for (int part = 0; part < parts; ++part) { s0 += red[part * nv + tid][0]; s1 += red[part * nv + p.C + tid][0]; }
-      if (KIND == 0) {
-        const float n = (float)p.rows, m = s0 / n;
-        const float var = fmaxf(s1 / n - m * m, 0.f);
-        p.out0[tid] = m;
-        p.out1[tid] = 1.0f / sqrtf(var + p.eps);
-        p.run_mean[tid] = (1.f - p.momentum) * p.run_mean[tid] + p.momentum * m;
-        p.run_var[tid] = (1.f - p.momentum) * p.run_var[tid] + p.momentum * var * (n / (n - 1.f));
-      } else {
-        p.out0[tid] = s0;
-        p.out1[tid] = s1;
-      }
-    }
-  }
+  bn_finish<KIND>(p, gridDim.x, red);
   if (tid == 0) *p.ticket = 0;
+}
+
+template <int KIND>
+__global__ __launch_bounds__(256) void bn_finish_kernel(BnSumArgs p, unsigned nblocks) {
+  __shared__ float red[256][17];
+  bn_finish<KIND>(p, nblocks, red);
 }
 
 // y = relu(bn(x) (+ res)), 8 channels per thread
@@ -601,6 +614,126 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_kernel(const uint16_t*
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Weight gradient on the matrix cores for C -> C channels (C = 16, 32, 64), stride 1, image rows of
+// 8, 16 or 32 pixels (any width that is a multiple of 8, with H*W a multiple of 32).  The reduction
+// index of a 16x16x32 MFMA is the pixel: a k-step is four groups of 8 consecutive pixels of one row.
+// A workgroup of 8 waves takes whole images: it transposes x and dy of an image to [channel][pixel]
+// in LDS (x with a 16-byte zero gap in front of every row and a zero row above and below, so that
+// no tap needs a bounds test), a wave owns one tile of 16 output channels for all 9 taps and all
+// input-channel tiles and every (8 / tiles)-th k-step.  The fragment of the taps one pixel to the
+// left / right is the aligned one shifted by two bytes with the neighbouring pixel read separately.
+// Per workgroup and k-split one partial, summed by the ordered second-stage reduction.
+typedef __attribute__((ext_vector_type(4))) float wg_f32x4;
+constexpr int WGT_WAVES = 8;
+__host__ __device__ inline int wgt_pad16(int bytes) { return bytes + ((16 - bytes % 128) + 128) % 128; }   // = 16 mod 128
+__host__ __device__ inline int wgt_row_stride(int W) { return 16 + 2 * W; }
+__host__ __device__ inline int wgt_x_stride(int H, int W) { return wgt_pad16((H + 2) * wgt_row_stride(W) + 16); }
+__host__ __device__ inline int wgt_dy_stride(int H, int W) { return wgt_pad16(H * W * 2); }
+
+template <int C>
+__global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(const uint16_t* __restrict__ x,
+                                                                            const uint16_t* __restrict__ dy, int B, int H,
+                                                                            int W, float* __restrict__ partial) {
+  constexpr int CT = C / 16, WN = CT, WK = WGT_WAVES / WN, NT = 64 * WGT_WAVES;
+  extern __shared__ __align__(16) char sm[];
+  const int RS = wgt_row_stride(W), CSX = wgt_x_stride(H, W), CSD = wgt_dy_stride(H, W);
+  char* xt = sm;                              // x  as [C][H + 2 rows][16-byte gap, W pixels]
+  char* dt = sm + C * CSX;                    // dy as [C][H * W pixels]
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, q = lane >> 4;
+  const int wn = wave % WN, kq = wave / WN;
+  for (int o = tid * 16; o < C * CSX; o += NT * 16) *reinterpret_cast<uint4*>(xt + o) = make_uint4(0, 0, 0, 0);
+  wg_f32x4 acc[9][CT];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int j = 0; j < CT; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[t][j][e] = 0.f;
+  const int w4 = W / 4, w8 = W / 8, items = H * w4 * (C / 8), ksteps = H * W / 32;
+  for (int b = blockIdx.x; b < B; b += gridDim.x) {
+    const uint16_t* xb = x + (size_t)b * H * W * C;
+    const uint16_t* db = dy + (size_t)b * H * W * C;
+    __syncthreads();                          // zero fill done / the previous image's tiles are no longer read
+    for (int item = tid; item < items; item += NT) {
+      const int cg = item % (C / 8), pg = item / (C / 8), y = pg / w4, x0 = (pg % w4) * 4;
+      uint4 rx[4], rd[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const size_t off = ((size_t)(y * W + x0 + j)) * C + 8 * cg;
+        rx[j] = *reinterpret_cast<const uint4*>(xb + off);
+        rd[j] = *reinterpret_cast<const uint4*>(db + off);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+        uint2 ox, od;
+        ox.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[0])[i >> 1], sel);
+        ox.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[2])[i >> 1], sel);
+        od.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[0])[i >> 1], sel);
+        od.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[2])[i >> 1], sel);
+        *reinterpret_cast<uint2*>(xt + (8 * cg + i) * CSX + (y + 1) * RS + 16 + 2 * x0) = ox;
+        *reinterpret_cast<uint2*>(dt + (8 * cg + i) * CSD + (y * W + x0) * 2) = od;
+      }
+    }
+    __syncthreads();
+    for (int ks = kq; ks < ksteps; ks += WK) {
+      const int g = 4 * ks + q, y = g / w8, x0 = 8 * (g % w8);
+      const wg_bf16x8 gf = *reinterpret_cast<const wg_bf16x8*>(dt + (16 * wn + r) * CSD + g * 16);
+#pragma unroll
+      for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+        for (int t = 0; t < CT; ++t) {
+          const char* base = xt + (16 * t + r) * CSX + (y + ky) * RS + 16 + 2 * x0;
+          const uint4 w = *reinterpret_cast<const uint4*>(base);
+          const uint32_t prev = *reinterpret_cast<const uint16_t*>(base - 2);
+          const uint32_t next = *reinterpret_cast<const uint16_t*>(base + 16);
+          uint4 a0, a2;
+          a0.x = (w.x << 16) | prev;
+          a0.y = __builtin_amdgcn_alignbyte(w.y, w.x, 2);
+          a0.z = __builtin_amdgcn_alignbyte(w.z, w.y, 2);
+          a0.w = __builtin_amdgcn_alignbyte(w.w, w.z, 2);
+          a2.x = a0.y; a2.y = a0.z; a2.z = a0.w;
+          a2.w = (next << 16) | (w.w >> 16);
+          acc[3 * ky][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(wg_bf16x8, a0), gf, acc[3 * ky][t], 0, 0, 0);
+          acc[3 * ky + 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(wg_bf16x8, w), gf, acc[3 * ky + 1][t], 0, 0, 0);
+          acc[3 * ky + 2][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(wg_bf16x8, a2), gf, acc[3 * ky + 2][t], 0, 0, 0);
+        }
+    }
+  }
+  // acc[tap][t][e] = dw[tap][ci = 16 t + 4 q + e][co = 16 wn + r] of this wave's k-steps
+  float* out = partial + ((size_t)blockIdx.x * WK + kq) * 9 * C * C;
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+    for (int t = 0; t < CT; ++t)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) out[((size_t)tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+}
+
+static size_t wgrad_tiles_lds(int H, int W, int C) { return (size_t)C * (wgt_x_stride(H, W) + wgt_dy_stride(H, W)); }
+static bool wgrad_tiles_ok(int H, int W, int Ci, int Co, int stride) {
+  return stride == 1 && Ci == Co && (Ci == 16 || Ci == 32 || Ci == 64) && W >= 8 && (W % 8) == 0 && ((H * W) % 32) == 0 &&
+         wgrad_tiles_lds(H, W, Ci) <= 160 * 1024;
+}
+// workgroups: one per image up to the number that keeps the partial sums near 32 MiB
+static int wgrad_tiles_blocks(int B, int C) {
+  const int wk = WGT_WAVES / (C / 16);
+  long cap = ((long)32 << 20) / ((long)wk * 9 * C * C * 4);
+  cap = cap < 32 ? 32 : (cap > 256 ? 256 : cap);
+  return B < cap ? B : (int)cap;
+}
+template <int C>
+static int wgrad_tiles_launch(hipStream_t s, const void* x, const void* dy, int B, int H, int W, float* partials, int blocks) {
+  const size_t lds = wgrad_tiles_lds(H, W, C);
+  if (lds > 64 * 1024)
+    PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_wgrad_tiles_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(conv3x3_wgrad_tiles_kernel<C>, dim3(blocks), dim3(64 * WGT_WAVES), lds, s, (const uint16_t*)x,
+                     (const uint16_t*)dy, B, H, W, partials);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+
 static int wgrad_mfma_blocks(int B) { return B < 128 ? B : 128; }
 static bool wgrad_mfma_ok(int H, int W, int Ci, int Co, int stride) {
   return Ci == WGM_C && Co == WGM_C && W == WGM_W && stride == 1 && H >= 1 && H <= 64;
@@ -611,6 +744,10 @@ size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, in
   size_t n = (size_t)((P + WG_PIX_F - 1) / WG_PIX_F) * 9 * Ci * Co;
   if (wgrad_mfma_ok(H, W, Ci, Co, stride)) {
     const size_t m = (size_t)wgrad_mfma_blocks(B) * 9 * Ci * Co;
+    if (m > n) n = m;
+  }
+  if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
+    const size_t m = (size_t)wgrad_tiles_blocks(B, Ci) * (WGT_WAVES / (Ci / 16)) * 9 * Ci * Co;
     if (m > n) n = m;
   }
   return n;
@@ -630,12 +767,20 @@ static int wgrad_launch(hipStream_t s, const void* x, const void* dy, int B, int
 }
 
 int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co,
-                              int stride, ReduceQueue& rq, float* dw) {
+                              int stride, ReduceQueue& rq, float* dw, int ci_keep) {
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   const int chunks = (int)((P + WG_PIX_F - 1) / WG_PIX_F), nw = 9 * Ci * Co;
   const int cpt = Ci / (256 / Co);
   const bool mfma = wgrad_mfma_ok(H, W, Ci, Co, stride);
   bool queued;
+  if (!mfma && wgrad_tiles_ok(H, W, Ci, Co, stride)) {
+    const int blocks = wgrad_tiles_blocks(B, Ci), rows = blocks * (WGT_WAVES / (Ci / 16));
+    float* part = rq.space((size_t)rows * nw, &queued);
+    if (Ci == 16) PPLL_TRY(wgrad_tiles_launch<16>(s, x, dy, B, H, W, part, blocks));
+    else if (Ci == 32) PPLL_TRY(wgrad_tiles_launch<32>(s, x, dy, B, H, W, part, blocks));
+    else PPLL_TRY(wgrad_tiles_launch<64>(s, x, dy, B, H, W, part, blocks));
+    return reduce_conv_filters(s, rq, queued, part, rows, Ci, Co, ci_keep, dw);
+  }
   float* partials = rq.space((size_t)(mfma ? wgrad_mfma_blocks(B) : chunks) * nw, &queued);
   if (mfma) {
     const int blocks = wgrad_mfma_blocks(B);
@@ -645,7 +790,7 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
     hipLaunchKernelGGL(conv3x3_wgrad_mfma_kernel, dim3(blocks), dim3(256), lds, s, (const uint16_t*)x, (const uint16_t*)dy, B,
                        H, partials);
     PPLL_HIP(hipGetLastError());
-    return rq.reduce(s, queued, partials, blocks, nw, nw, 1.0f, dw);
+    return reduce_conv_filters(s, rq, queued, partials, blocks, Ci, Co, ci_keep, dw);
   }
   int st = PPLL_ERR_CONFIG;
   if (Co == 16 && cpt == 1) st = wgrad_launch<16, 1>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
@@ -659,17 +804,32 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   else if (Co == 64 && cpt == 16) st = wgrad_launch<64, 16>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
   else set_error("conv3x3 weight gradient: no kernel for %d -> %d channels", Ci, Co);
   PPLL_TRY(st);
-  return rq.reduce(s, queued, partials, chunks, nw, nw, 1.0f, dw);
+  return reduce_conv_filters(s, rq, queued, partials, chunks, Ci, Co, ci_keep, dw);
 }
 
 bool bn_bf16_supported(int dt, int C, const void* a, const void* b, const void* c, const void* d) {
   if (dt != BF16 || (C % 8) || C < 8 || C > 128 || (256 % (C / 8))) return false;
   return al16(a) && al16(b) && al16(c) && al16(d);
 }
+constexpr int BN_TICKET_BLOCKS = 64;
 static int bn_blocks(int rows, int C) {
   const int lanes = 256 / (C / 8);
   int blocks = (rows + lanes * 8 - 1) / (lanes * 8);     // about eight rows per thread
-  return blocks < 1 ? 1 : (blocks > 64 ? 64 : blocks);
+  // Up to 64 workgroups the last one to arrive adds the partials (one launch).  Taller tensors take up to 1024
+  // workgroups and a second, one-workgroup launch: hundreds of device-scope fences cost more than that launch.
+  return blocks < 1 ? 1 : (blocks > 1024 ? 1024 : blocks);
+}
+template <int KIND>
+static int bn_sums_launch(hipStream_t s, const BnSumArgs& p, int blocks) {
+  if (blocks <= BN_TICKET_BLOCKS) {
+    hipLaunchKernelGGL((bn_sums_kernel<KIND, true>), dim3(blocks), dim3(256), 0, s, p);
+  } else {
+    hipLaunchKernelGGL((bn_sums_kernel<KIND, false>), dim3(blocks), dim3(256), 0, s, p);
+    PPLL_HIP(hipGetLastError());
+    hipLaunchKernelGGL(bn_finish_kernel<KIND>, dim3(1), dim3(256), 0, s, p, (unsigned)blocks);
+  }
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
 }
 size_t bn_bf16_partial_floats(int rows, int C) { return (size_t)bn_blocks(rows, C) * 2 * C; }
 
@@ -708,8 +868,7 @@ int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float ep
   BnSumArgs p{};
   p.x = (const uint16_t*)x; p.rows = rows; p.C = C; p.partial = partials; p.ticket = ticket; p.eps = eps;
   p.momentum = momentum; p.out0 = mean; p.out1 = rstd; p.run_mean = run_mean; p.run_var = run_var;
-  hipLaunchKernelGGL(bn_sums_kernel<0>, dim3(bn_blocks(rows, C)), dim3(256), 0, s, p);
-  PPLL_HIP(hipGetLastError());
+  PPLL_TRY(bn_sums_launch<0>(s, p, bn_blocks(rows, C)));
   return PPLL_OK;
 }
 
@@ -727,8 +886,7 @@ int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void*
   BnSumArgs p{};
   p.x = (const uint16_t*)x; p.dy = (const uint16_t*)dy; p.y = (const uint16_t*)y; p.rows = rows; p.C = C;
   p.mean = mean; p.rstd = rstd; p.partial = partials; p.ticket = ticket; p.out0 = db; p.out1 = dg;
-  hipLaunchKernelGGL(bn_sums_kernel<1>, dim3(bn_blocks(rows, C)), dim3(256), 0, s, p);
-  PPLL_HIP(hipGetLastError());
+  PPLL_TRY(bn_sums_launch<1>(s, p, bn_blocks(rows, C)));
   const size_t chunks = (size_t)rows * C / 8;
   hipLaunchKernelGGL(bn_bwd_apply_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
                      (const uint16_t*)dy, (const uint16_t*)y, (const uint16_t*)x, chunks, C, rows, mean, rstd, g, dg, db,

@@ -308,6 +308,15 @@ def test_resnet_bf16_16_channels_ragged():
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
 
 
+@pytest.mark.parametrize("channels,height,width,batch", [(32, 8, 8, 5), (32, 4, 32, 3), (16, 2, 16, 300), (64, 4, 8, 2)])
+def test_resnet_bf16_tiled_weight_gradient_shapes(channels, height, width, batch):
+    # the 16x16x32 matrix-core weight gradient: rows of 8, 16 and 32 pixels, 1 to 4 channel tiles, fewer
+    # k-steps per image than waves (2 x 16 pixels), more images than workgroups (300)
+    wl = synth.workload("resnet_stage_bf16", n_basic_blocks=1, batch=batch, height=height, width=width, channels=channels,
+                        aux_channels=32)
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
 def test_resnet_bf16_stem_module():
     wl = synth.resnet32_modules(8, batch=4)[0]
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
