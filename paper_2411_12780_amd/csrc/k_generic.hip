@@ -570,22 +570,36 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(const float* logits,
     *loss = red[0] / B;
     if (loss2) *loss2 = red[0] / B;
   }
-  if (dbias)   // dlogits were written by this workgroup before the barriers above
-    for (int c = threadIdx.x; c < C; c += 256) {
+  if (dbias) {   // dlogits were written by this workgroup before the barriers above
+    // 256 / C thread groups take the batch rows round-robin, then one thread per class adds the groups in order
+    const int parts = C <= 256 ? 256 / C : 1;
+    __syncthreads();   // red is reused
+    if (C <= 256) {
+      const int c = threadIdx.x % C, part = threadIdx.x / C;
       float t = 0.f;
-      if (in_lds) {
-        for (int b = 0; b < B; ++b) t += dl[b * C + c];
-      } else {
+      if (part < parts)
+        for (int b = part; b < B; b += parts) t += in_lds ? dl[b * C + c] : dlogits[(size_t)b * C + c];
+      red[threadIdx.x] = t;
+      __syncthreads();
+      if (threadIdx.x < C) {
+        float u = 0.f;
+        for (int k = 0; k < parts; ++k) u += red[k * C + threadIdx.x];
+        dbias[threadIdx.x] = u;
+      }
+    } else {
+      for (int c = threadIdx.x; c < C; c += 256) {
+        float t = 0.f;
         for (int b = 0; b < B; b += 8) {    // eight loads in flight, added in batch order
           float q[8];
 #pragma unroll
-          for (int u = 0; u < 8; ++u) q[u] = b + u < B ? dlogits[(size_t)(b + u) * C + c] : 0.f;
+          for (int u = 0; u < 8; ++u) q[u] = b + u < B ? (in_lds ? dl[(b + u) * C + c] : dlogits[(size_t)(b + u) * C + c]) : 0.f;
 #pragma unroll
           for (int u = 0; u < 8; ++u) t += q[u];
         }
+        dbias[c] = t;
       }
-      dbias[c] = t;
     }
+  }
 }
 }  // namespace
 

@@ -5,9 +5,10 @@
 //    channels = 16 bytes), the filter sits in LDS as [out channel][tap, in
 //    channel]; the product is issued filter-first so that a lane ends up with 4
 //    consecutive output channels of its pixel (8-byte stores).
-//  * weight gradient: 64 output pixels per workgroup, their nine shifted input
-//    vectors and dy staged in LDS, 36 / 72 fp32 accumulators per thread; partials
-//    per workgroup, summed in a fixed order.
+//  * weight gradient: stride 1 with equal channel counts on the matrix cores with the
+//    pixel as reduction index (images transposed in LDS); other shapes with 64 output
+//    pixels per workgroup, their nine shifted input vectors and dy staged in LDS and
+//    fp32 accumulators per thread; partials per workgroup, summed in a fixed order.
 //  * BatchNorm statistics / backward sums: 8 channels per thread (16-byte loads),
 //    per-workgroup partials, and the last workgroup to arrive (integer ticket)
 //    adds the partials in workgroup order and finishes mean / rstd / running
@@ -509,114 +510,10 @@ bool conv_wgrad_bf16_ok(int Ci, int Co) {
   return (Co == 32 || Co == 64) && Ci % 16 == 0 && Ci >= 16 && Ci <= 64;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Weight gradient on the matrix cores for 32 -> 32 channels, stride 1, 16-pixel image rows:
-// dw[ky][kx][ci][co] = sum over pixels of x[y+ky-1][x+kx-1][ci] * dy[y][x][co].  The reduction
-// index of the MFMA is the pixel, so a 16-wide k-step is exactly one image row and each of the 9
-// taps is one 32 x 32 accumulator tile.  A workgroup takes one image at a time: both tensors are
-// transposed into LDS as [channel][row][16 pixels] (in-register 4 x 8 transposes, as in the GEMM
-// loaders), a lane's operand fragment is then one aligned 16-byte read (8 consecutive pixels of
-// its channel), and the +-1 pixel shifts of the kx = 0 / 2 taps are made in registers from that
-// read and one value taken from the lane holding the other half of the row (zero at the image
-// border).  The 9 taps are dealt to the 4 waves (3, 2, 2, 2), each wave keeps its taps'
-// accumulators over all images of the workgroup, and the workgroups' tiles are added by the
-// ordered second-stage reduction.
 typedef __attribute__((ext_vector_type(8))) __bf16 wg_bf16x8;
-typedef __attribute__((ext_vector_type(16))) float wg_f32x16;
-constexpr int WGM_C = 32, WGM_W = 16;
-__global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_kernel(const uint16_t* __restrict__ x,
-                                                                 const uint16_t* __restrict__ dy, int B, int H,
-                                                                 float* __restrict__ partial) {
-  extern __shared__ __align__(16) char sm[];
-  const int CS = H * WGM_W * 2 + 16;          // bytes between channels of a transposed tile (+16: spreads the banks)
-  char* xt = sm;                              // x  as [32 channels][H rows][16 pixels]
-  char* dt = sm + WGM_C * CS;                 // dy likewise
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, c = lane & 31, h = lane >> 5;
-  wg_f32x16 acc[3];
-#pragma unroll
-  for (int j = 0; j < 3; ++j)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
-  const int items = H * 4 * 4;                // (row, group of 4 pixels, group of 8 channels)
-  for (int b = blockIdx.x; b < B; b += gridDim.x) {
-    const uint16_t* xb = x + (size_t)b * H * WGM_W * WGM_C;
-    const uint16_t* db = dy + (size_t)b * H * WGM_W * WGM_C;
-    __syncthreads();                          // the previous image's tiles are no longer read
-    for (int item = tid; item < items; item += 256) {
-      const int cg = item & 3, pg = item >> 2, y = pg >> 2, x0 = (pg & 3) * 4;
-      uint4 rx[4], rd[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const size_t off = ((size_t)(y * WGM_W + x0 + j)) * WGM_C + 8 * cg;
-        rx[j] = *reinterpret_cast<const uint4*>(xb + off);
-        rd[j] = *reinterpret_cast<const uint4*>(db + off);
-      }
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        const int o = (8 * cg + i) * CS + y * (WGM_W * 2) + x0 * 2;
-        uint2 ox, od;
-        ox.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[0])[i >> 1], sel);
-        ox.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[2])[i >> 1], sel);
-        od.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[0])[i >> 1], sel);
-        od.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[2])[i >> 1], sel);
-        *reinterpret_cast<uint2*>(xt + o) = ox;
-        *reinterpret_cast<uint2*>(dt + o) = od;
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 3; ++j) {
-      const int tap = wave + 4 * j;           // wave-uniform
-      if (tap < 9) {
-        const int ky = tap / 3, kx = tap % 3;
-        for (int y = 0; y < H; ++y) {
-          const int yi = y + ky - 1;
-          if (yi < 0 || yi >= H) continue;
-          const uint4 w = *reinterpret_cast<const uint4*>(xt + c * CS + yi * (WGM_W * 2) + h * 16);
-          const uint4 g = *reinterpret_cast<const uint4*>(dt + c * CS + y * (WGM_W * 2) + h * 16);
-          uint4 a = w;
-          if (kx != 1) {
-            // the pixel next to this lane's 8: the last of the lower half for h = 1, the first of the upper half for h = 0
-            const uint32_t other = (uint32_t)__shfl_xor((int)(h ? w.x : w.w), 32, 64);
-            if (kx == 0) {       // pixels x-1
-              const uint32_t prev = h ? (other >> 16) : 0u;
-              a.x = (w.x << 16) | prev;
-              a.y = __builtin_amdgcn_alignbyte(w.y, w.x, 2);
-              a.z = __builtin_amdgcn_alignbyte(w.z, w.y, 2);
-              a.w = __builtin_amdgcn_alignbyte(w.w, w.z, 2);
-            } else {             // pixels x+1
-              const uint32_t next = h ? 0u : (other & 0xffffu);
-              a.x = __builtin_amdgcn_alignbyte(w.y, w.x, 2);
-              a.y = __builtin_amdgcn_alignbyte(w.z, w.y, 2);
-              a.z = __builtin_amdgcn_alignbyte(w.w, w.z, 2);
-              a.w = (next << 16) | (w.w >> 16);
-            }
-          }
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(wg_bf16x8, a), __builtin_bit_cast(wg_bf16x8, g),
-                                                           acc[j], 0, 0, 0);
-        }
-      }
-    }
-  }
-  // acc[j][e] = dw[tap][ci = 8 (e/4) + 4 h + e%4][co = c]
-  float* out = partial + (size_t)blockIdx.x * 9 * WGM_C * WGM_C;
-#pragma unroll
-  for (int j = 0; j < 3; ++j) {
-    const int tap = wave + 4 * j;
-    if (tap < 9) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int ci = 8 * (e >> 2) + 4 * h + (e & 3);
-        out[((size_t)tap * WGM_C + ci) * WGM_C + c] = acc[j][e];
-      }
-    }
-  }
-}
-
 // ---------------------------------------------------------------------------------------------
 // Weight gradient on the matrix cores for C -> C channels (C = 16, 32, 64), stride 1, image rows of
-// 8, 16 or 32 pixels (any width that is a multiple of 8, with H*W a multiple of 32).  The reduction
+// 8, 16 or 32 pixels (any width that is a multiple of 8).  The reduction
 // index of a 16x16x32 MFMA is the pixel: a k-step is four groups of 8 consecutive pixels of one row.
 // A workgroup of 8 waves takes whole images: it transposes x and dy of an image to [channel][pixel]
 // in LDS (x with a 16-byte zero gap in front of every row and a zero row above and below, so that
@@ -626,6 +523,9 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_mfma_kernel(const uint16_t*
 // Per workgroup and k-split one partial, summed by the ordered second-stage reduction.
 typedef __attribute__((ext_vector_type(4))) float wg_f32x4;
 constexpr int WGT_WAVES = 8;
+// 16 and 32 channels: the workgroup's k-splits fit LDS together (72 / 144 KiB) and leave as one partial
+__host__ __device__ constexpr bool WGT_FOLD(int C) { return C <= 32; }
+__host__ __device__ constexpr int wgt_partials_per_block(int C) { return WGT_FOLD(C) ? 1 : WGT_WAVES / (C / 16); }
 __host__ __device__ inline int wgt_pad16(int bytes) { return bytes + ((16 - bytes % 128) + 128) % 128; }   // = 16 mod 128
 __host__ __device__ inline int wgt_row_stride(int W) { return 16 + 2 * W; }
 __host__ __device__ inline int wgt_x_stride(int H, int W) { return wgt_pad16((H + 2) * wgt_row_stride(W) + 16); }
@@ -650,7 +550,7 @@ __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(con
     for (int j = 0; j < CT; ++j)
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[t][j][e] = 0.f;
-  const int w4 = W / 4, w8 = W / 8, items = H * w4 * (C / 8), ksteps = H * W / 32;
+  const int w4 = W / 4, w8 = W / 8, items = H * w4 * (C / 8), groups = H * w8, ksteps = (groups + 3) / 4;
   for (int b = blockIdx.x; b < B; b += gridDim.x) {
     const uint16_t* xb = x + (size_t)b * H * W * C;
     const uint16_t* db = dy + (size_t)b * H * W * C;
@@ -678,8 +578,12 @@ __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(con
     }
     __syncthreads();
     for (int ks = kq; ks < ksteps; ks += WK) {
-      const int g = 4 * ks + q, y = g / w8, x0 = 8 * (g % w8);
-      const wg_bf16x8 gf = *reinterpret_cast<const wg_bf16x8*>(dt + (16 * wn + r) * CSD + g * 16);
+      // the last k-step of an image may hold fewer than four pixel groups: the others multiply by zero
+      const bool live = 4 * ks + q < groups;
+      const int g = live ? 4 * ks + q : 0, y = g / w8, x0 = 8 * (g % w8);
+      uint4 gv = make_uint4(0, 0, 0, 0);
+      if (live) gv = *reinterpret_cast<const uint4*>(dt + (16 * wn + r) * CSD + g * 16);
+      const wg_bf16x8 gf = __builtin_bit_cast(wg_bf16x8, gv);
 #pragma unroll
       for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
@@ -702,23 +606,48 @@ __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(con
     }
   }
   // acc[tap][t][e] = dw[tap][ci = 16 t + 4 q + e][co = 16 wn + r] of this wave's k-steps
-  float* out = partial + ((size_t)blockIdx.x * WK + kq) * 9 * C * C;
+  constexpr int NW = 9 * C * C;
+  if constexpr (WGT_FOLD(C)) {
+    // the k-splits of the workgroup are added in LDS, in k-split order: one partial per workgroup
+    float* fold = reinterpret_cast<float*>(sm);
+    __syncthreads();                          // the tiles are no longer read
 #pragma unroll
-  for (int tap = 0; tap < 9; ++tap)
+    for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
-    for (int t = 0; t < CT; ++t)
+      for (int t = 0; t < CT; ++t)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) out[((size_t)tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+        for (int e = 0; e < 4; ++e) fold[kq * NW + (tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+    __syncthreads();
+    float* out = partial + (size_t)blockIdx.x * NW;
+    for (int i = tid; i < NW; i += NT) {
+      float v = fold[i];
+#pragma unroll
+      for (int k = 1; k < WK; ++k) v += fold[k * NW + i];
+      out[i] = v;
+    }
+  } else {
+    float* out = partial + ((size_t)blockIdx.x * WK + kq) * NW;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+      for (int t = 0; t < CT; ++t)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[((size_t)tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+  }
 }
 
-static size_t wgrad_tiles_lds(int H, int W, int C) { return (size_t)C * (wgt_x_stride(H, W) + wgt_dy_stride(H, W)); }
+static size_t wgrad_tiles_lds(int H, int W, int C) {
+  const size_t tiles = (size_t)C * (wgt_x_stride(H, W) + wgt_dy_stride(H, W));
+  const size_t fold = WGT_FOLD(C) ? (size_t)(WGT_WAVES / (C / 16)) * 9 * C * C * sizeof(float) : 0;
+  return tiles > fold ? tiles : fold;
+}
 static bool wgrad_tiles_ok(int H, int W, int Ci, int Co, int stride) {
-  return stride == 1 && Ci == Co && (Ci == 16 || Ci == 32 || Ci == 64) && W >= 8 && (W % 8) == 0 && ((H * W) % 32) == 0 &&
+  return stride == 1 && Ci == Co && (Ci == 16 || Ci == 32 || Ci == 64) && W >= 8 && (W % 8) == 0 &&
          wgrad_tiles_lds(H, W, Ci) <= 160 * 1024;
 }
 // workgroups: one per image up to the number that keeps the partial sums near 32 MiB
 static int wgrad_tiles_blocks(int B, int C) {
-  const int wk = WGT_WAVES / (C / 16);
+  const int wk = wgt_partials_per_block(C);
   long cap = ((long)32 << 20) / ((long)wk * 9 * C * C * 4);
   cap = cap < 32 ? 32 : (cap > 256 ? 256 : cap);
   return B < cap ? B : (int)cap;
@@ -734,20 +663,11 @@ static int wgrad_tiles_launch(hipStream_t s, const void* x, const void* dy, int 
   return PPLL_OK;
 }
 
-static int wgrad_mfma_blocks(int B) { return B < 128 ? B : 128; }
-static bool wgrad_mfma_ok(int H, int W, int Ci, int Co, int stride) {
-  return Ci == WGM_C && Co == WGM_C && W == WGM_W && stride == 1 && H >= 1 && H <= 64;
-}
-
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride) {
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   size_t n = (size_t)((P + WG_PIX_F - 1) / WG_PIX_F) * 9 * Ci * Co;
-  if (wgrad_mfma_ok(H, W, Ci, Co, stride)) {
-    const size_t m = (size_t)wgrad_mfma_blocks(B) * 9 * Ci * Co;
-    if (m > n) n = m;
-  }
   if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
-    const size_t m = (size_t)wgrad_tiles_blocks(B, Ci) * (WGT_WAVES / (Ci / 16)) * 9 * Ci * Co;
+    const size_t m = (size_t)wgrad_tiles_blocks(B, Ci) * wgt_partials_per_block(Ci) * 9 * Ci * Co;
     if (m > n) n = m;
   }
   return n;
@@ -771,27 +691,16 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   const int chunks = (int)((P + WG_PIX_F - 1) / WG_PIX_F), nw = 9 * Ci * Co;
   const int cpt = Ci / (256 / Co);
-  const bool mfma = wgrad_mfma_ok(H, W, Ci, Co, stride);
   bool queued;
-  if (!mfma && wgrad_tiles_ok(H, W, Ci, Co, stride)) {
-    const int blocks = wgrad_tiles_blocks(B, Ci), rows = blocks * (WGT_WAVES / (Ci / 16));
+  if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
+    const int blocks = wgrad_tiles_blocks(B, Ci), rows = blocks * wgt_partials_per_block(Ci);
     float* part = rq.space((size_t)rows * nw, &queued);
     if (Ci == 16) PPLL_TRY(wgrad_tiles_launch<16>(s, x, dy, B, H, W, part, blocks));
     else if (Ci == 32) PPLL_TRY(wgrad_tiles_launch<32>(s, x, dy, B, H, W, part, blocks));
     else PPLL_TRY(wgrad_tiles_launch<64>(s, x, dy, B, H, W, part, blocks));
     return reduce_conv_filters(s, rq, queued, part, rows, Ci, Co, ci_keep, dw);
   }
-  float* partials = rq.space((size_t)(mfma ? wgrad_mfma_blocks(B) : chunks) * nw, &queued);
-  if (mfma) {
-    const int blocks = wgrad_mfma_blocks(B);
-    const size_t lds = (size_t)2 * WGM_C * (H * WGM_W * 2 + 16);
-    if (lds > 64 * 1024)
-      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_wgrad_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(conv3x3_wgrad_mfma_kernel, dim3(blocks), dim3(256), lds, s, (const uint16_t*)x, (const uint16_t*)dy, B,
-                       H, partials);
-    PPLL_HIP(hipGetLastError());
-    return reduce_conv_filters(s, rq, queued, partials, blocks, Ci, Co, ci_keep, dw);
-  }
+  float* partials = rq.space((size_t)chunks * nw, &queued);
   int st = PPLL_ERR_CONFIG;
   if (Co == 16 && cpt == 1) st = wgrad_launch<16, 1>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
   else if (Co == 32 && cpt == 2) st = wgrad_launch<32, 2>(s, x, dy, B, H, W, Ci, stride, partials, chunks);
@@ -815,9 +724,9 @@ constexpr int BN_TICKET_BLOCKS = 64;
 static int bn_blocks(int rows, int C) {
   const int lanes = 256 / (C / 8);
   int blocks = (rows + lanes * 8 - 1) / (lanes * 8);     // about eight rows per thread
-  // Up to 64 workgroups the last one to arrive adds the partials (one launch).  Taller tensors take up to 1024
+  // Up to 64 workgroups the last one to arrive adds the partials (one launch).  Taller tensors take up to 256
   // workgroups and a second, one-workgroup launch: hundreds of device-scope fences cost more than that launch.
-  return blocks < 1 ? 1 : (blocks > 1024 ? 1024 : blocks);
+  return blocks < 1 ? 1 : (blocks > 256 ? 256 : blocks);
 }
 template <int KIND>
 static int bn_sums_launch(hipStream_t s, const BnSumArgs& p, int blocks) {

@@ -53,6 +53,16 @@ WORKLOADS = {
                                  num_classes=10, channels=32, height=16, width=16, transition_block=1,
                                  n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
                                  nesterov=1, weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.01),
+    # first stage of the same network: the stem on the image and the five 16-channel blocks on 32 x 32 maps
+    "resnet32_stage1_bf16": dict(arch=RESNET, precision=BF16, input_kind=IMAGE, img_h=32, img_w=32, img_c=3,
+                                 batch=1024, num_classes=10, channels=16, height=32, width=32, transition_block=0,
+                                 n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
+                                 nesterov=1, weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.01),
+    # third stage: the block that halves the 16 x 16 x 32 input to 8 x 8 x 64, then four 64-channel blocks
+    "resnet32_stage3_bf16": dict(arch=RESNET, precision=BF16, input_kind=ACTIVATION, batch=1024,
+                                 num_classes=10, channels=64, height=8, width=8, transition_block=1,
+                                 n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
+                                 nesterov=1, weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.01),
     # configs[3]: STL-10-shaped ViT stage
     "vit_large_image_bf16": dict(_VIT_STAGE, batch=64, img_h=96, img_w=96, patch=8, tokens=145),
 }

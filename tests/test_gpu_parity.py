@@ -277,8 +277,8 @@ def test_resnet_bf16_odd_sizes_on_the_mfma_path():
 
 
 def test_resnet_bf16_weight_gradient_on_the_mfma_path_edges():
-    # 16-pixel rows select the matrix-core weight gradient; 131 images make its workgroups loop over
-    # images (128 workgroups), 5 rows give every tap a different set of valid row pairs
+    # 16-pixel rows select the matrix-core weight gradient; 131 images over fewer workgroups make them loop
+    # over images, 5 rows of 16 pixels leave the last 32-pixel reduction step of an image half empty
     wl = synth.workload("resnet_stage_bf16", n_basic_blocks=1, batch=131, height=5, width=16)
     run_case(wl, steps=1, check_bn=True)
 
