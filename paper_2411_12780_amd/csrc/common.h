@@ -225,6 +225,7 @@ int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, i
 int bn_partial_floats(int rows, int C);
 // bf16 fast path (k_resnet_bf16.hip); `ticket` is one zero-initialised int that the kernels reset themselves
 bool conv_bf16_supported(int dt, int wdt, int Ci, int Co, const void* a, const void* b, const void* c);
+bool conv_pixels_fit(int B, int H, int W);
 bool conv_fwd_bf16_ok(int Ci, int Co);
 bool conv_dgrad_bf16_ok(int Ci, int Co);
 bool conv_wgrad_bf16_ok(int Ci, int Co);
@@ -240,7 +241,7 @@ int launch_gap_bwd_bf16(hipStream_t s, const void* dpooled, int B, int HW, int C
 int launch_shortcut_fwd_bf16(hipStream_t s, const void* x, int B, int H, int W, int Ci, int Co, int stride, void* y);
 int launch_shortcut_bwd_bf16(hipStream_t s, const void* dy, const void* ymask, int B, int H, int W, int Ci, int Co, int stride,
                              void* dx);
-bool bn_bf16_supported(int dt, int C, const void* a, const void* b, const void* c, const void* d);
+bool bn_bf16_supported(int dt, int rows, int C, const void* a, const void* b, const void* c, const void* d);
 size_t bn_bf16_partial_floats(int rows, int C);
 int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
                          int* ticket, float* mean, float* rstd, float* run_mean, float* run_var);

@@ -265,7 +265,7 @@ int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt
 
 int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                        int Co, int stride, void* y) {
-  if (conv_bf16_supported(dt, wdt, Ci, Co, x, w, y) && conv_fwd_bf16_ok(Ci, Co))
+  if (conv_bf16_supported(dt, wdt, Ci, Co, x, w, y) && conv_fwd_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W))
     return launch_conv3x3_fwd_bf16(s, x, w, B, H, W, Ci, Co, stride, y);
   size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Co;
   hipLaunchKernelGGL(conv3x3_fwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, w, wdt, dt, B, H, W, Ci, Co,
@@ -276,7 +276,7 @@ int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int
 
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, const void* dres, const void* ymask, void* dx) {
-  if (conv_bf16_supported(dt, wdt, Ci, Co, dy, w, dx) && conv_dgrad_bf16_ok(Ci, Co) &&
+  if (conv_bf16_supported(dt, wdt, Ci, Co, dy, w, dx) && conv_dgrad_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W) &&
       !((((uintptr_t)dres) | ((uintptr_t)ymask)) & 15))
     return launch_conv3x3_dgrad_bf16(s, dy, w, B, H, W, Ci, Co, stride, dres, ymask, dx);
   size_t total = (size_t)B * H * W * Ci;
@@ -306,7 +306,7 @@ int reduce_conv_filters(hipStream_t s, ReduceQueue& rq, bool queued, const float
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci, int Co,
                          int stride, ReduceQueue& rq, float* dw, int ci_keep) {
   if (ci_keep < 0 || ci_keep > Ci) ci_keep = Ci;
-  if (conv_bf16_supported(dt, BF16, Ci, Co, x, dy, dw) && conv_wgrad_bf16_ok(Ci, Co))
+  if (conv_bf16_supported(dt, BF16, Ci, Co, x, dy, dw) && conv_wgrad_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W))
     return launch_conv3x3_wgrad_bf16(s, x, dy, B, H, W, Ci, Co, stride, rq, dw, ci_keep);
   int chunks = (int)wgrad_chunks(B, H, W, stride), nw = 9 * Ci * Co;
   bool queued;
@@ -326,7 +326,7 @@ int bn_partial_floats(int rows, int C) {
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
                     int* ticket, float* mean, float* rstd, float* run_mean, float* run_var) {
   if (rows < 2) { set_error("batchnorm needs at least 2 rows per channel"); return PPLL_ERR_CONFIG; }
-  if (bn_bf16_supported(dt, C, x, nullptr, nullptr, nullptr))
+  if (bn_bf16_supported(dt, rows, C, x, nullptr, nullptr, nullptr))
     return launch_bn_stats_bf16(s, x, rows, C, eps, momentum, partials, ticket, mean, rstd, run_mean, run_var);
   float* var = partials;            // [C], then the chunk partials
   float* part = partials + C;
@@ -342,7 +342,7 @@ int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float
 
 int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const float* mean, const float* rstd,
                     const float* g, const float* b, const void* res, void* y) {
-  if (bn_bf16_supported(dt, C, x, res, y, nullptr))
+  if (bn_bf16_supported(dt, rows, C, x, res, y, nullptr))
     return launch_bn_apply_bf16(s, x, rows, C, mean, rstd, g, b, res, y);
   size_t total = (size_t)rows * C;
   hipLaunchKernelGGL(bn_apply_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, dt, total, C, mean, rstd, g, b, res, y);
@@ -353,7 +353,7 @@ int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const
 int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
                   const float* mean, const float* rstd, const float* g, float* partials, int* ticket, float* dg,
                   float* db, void* dx) {
-  if (bn_bf16_supported(dt, C, dy, y, x, dx))
+  if (bn_bf16_supported(dt, rows, C, dy, y, x, dx))
     return launch_bn_bwd_bf16(s, dy, y, x, rows, C, mean, rstd, g, partials, ticket, dg, db, dx);
   int chunks = (rows + BN_ROWS - 1) / BN_ROWS;
   size_t total = (size_t)rows * C;

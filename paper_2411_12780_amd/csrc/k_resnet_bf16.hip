@@ -35,12 +35,15 @@ struct ConvArgs {
   const uint16_t* ymask;
 };
 
-// MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = channels reduced.
-template <int MODE>
+// MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = 16 * K16 channels reduced.
+// GRP: how many of a pixel's nine tap loads are issued before the first product waits for one
+// (0: one, 1: the three of a filter row, 3: all nine; a filter row measured best).
+template <int MODE, int K16, int GRP>
 __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   extern __shared__ __align__(16) char wl[];        // [NO rounded up to 32][9*KC] bf16, row stride RSW bytes
-  const int NO = MODE == 0 ? p.Co : p.Ci, KC = MODE == 0 ? p.Ci : p.Co;
-  const int RSW = 18 * KC + 16;
+  constexpr int KC = 16 * K16;
+  const int NO = MODE == 0 ? p.Co : p.Ci;
+  constexpr int RSW = 18 * KC + 16;
   const int Ho = out_dim(p.H, p.stride), Wo = out_dim(p.W, p.stride);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
   // filter -> LDS as [produced channel][tap*KC + reduced channel]; 8 output channels per 16-byte load,
@@ -73,65 +76,83 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   __syncthreads();
   const int OH = MODE == 0 ? Ho : p.H, OW = MODE == 0 ? Wo : p.W;      // output spatial size
   const int SH = MODE == 0 ? p.H : Ho, SW = MODE == 0 ? p.W : Wo;      // source spatial size
-  const long P = (long)p.B * OH * OW;
-  const long pix = (long)blockIdx.x * 128 + wave * 32 + li;
-  const bool live = pix < P;
-  const int ox = (int)(pix % OW), oy = (int)((pix / OW) % OH), b = (int)(pix / ((long)OW * OH));
+  const long P = (long)p.B * OH * OW, ntiles = (P + 127) / 128;
   const int NT = (NO + 31) / 32;     // NO = 16: the upper half of the one tile is never stored
-  f32x16 acc[2];
+  // the workgroup keeps its filter for several tiles of 128 pixels
+  for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    // 32-bit index arithmetic (the launcher checks that the pixel count fits): 64-bit division costs more than the tile
+    const uint32_t pix = (uint32_t)tile * 128 + wave * 32 + li;
+    const bool live = pix < (uint32_t)P;
+    const uint32_t prow = pix / (uint32_t)OW;
+    const int ox = (int)(pix - prow * (uint32_t)OW), oy = (int)(prow % (uint32_t)OH), b = (int)(prow / (uint32_t)OH);
+    f32x16 acc[2];
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+      for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+    constexpr int NG = GRP == 0 ? 9 : (GRP == 1 ? 3 : 1), TG = 9 / NG;   // groups of taps whose loads are in flight together
 #pragma unroll 1
-  for (int tap = 0; tap < 9; ++tap) {
-    const int ky = tap / 3, kx = tap % 3;
-    int sy, sx;
-    bool ok = live;
-    if (MODE == 0) {
-      sy = oy * p.stride + ky - 1; sx = ox * p.stride + kx - 1;
-    } else {
-      const int ty = oy + 1 - ky, tx = ox + 1 - kx;
-      ok = ok && ty >= 0 && tx >= 0 && (ty % p.stride) == 0 && (tx % p.stride) == 0;
-      sy = ty / p.stride; sx = tx / p.stride;
-    }
-    ok = ok && sy >= 0 && sy < SH && sx >= 0 && sx < SW;
-    const uint16_t* sp = p.src + (((long)b * SH + sy) * SW + sx) * KC + 8 * hh;
-    const char* wrow = wl + 2 * (tap * KC + 8 * hh);
-    for (int c16 = 0; c16 < KC / 16; ++c16) {
-      uint4 xv = make_uint4(0, 0, 0, 0);
-      if (ok) xv = *reinterpret_cast<const uint4*>(sp + 16 * c16);
-      const bf16x8 xf = __builtin_bit_cast(bf16x8, xv);
+    for (int grp = 0; grp < NG; ++grp) {
+      uint4 xv[TG][K16];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
-        if (t < NT) {
-          const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
-          acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
+      for (int j = 0; j < TG; ++j) {
+        const int tap = grp * TG + j, ky = tap / 3, kx = tap % 3;
+        int sy, sx;
+        bool ok = live;
+        if (MODE == 0) {
+          sy = oy * p.stride + ky - 1; sx = ox * p.stride + kx - 1;
+        } else {
+          const int ty = oy + 1 - ky, tx = ox + 1 - kx;
+          ok = ok && ty >= 0 && tx >= 0 && (ty % p.stride) == 0 && (tx % p.stride) == 0;
+          sy = ty / p.stride; sx = tx / p.stride;
         }
-    }
-  }
-  if (!live) return;
-  // acc[t][4q+e] = out[pix][32t + 8q + 4hh + e]
-  uint16_t* drow = p.dst + pix * NO;
+        ok = ok && sy >= 0 && sy < SH && sx >= 0 && sx < SW;
+        const uint16_t* sp = p.src + (((long)b * SH + sy) * SW + sx) * KC + 8 * hh;
 #pragma unroll
-  for (int t = 0; t < 2; ++t)
-    if (t < NT) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int c = 32 * t + 8 * q + 4 * hh;
-        if (c >= NO) continue;
-        float v[4] = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
-        if (MODE == 1 && p.dres) {
-          const uint2 m = *reinterpret_cast<const uint2*>(p.ymask + pix * NO + c);
-          const uint2 r = *reinterpret_cast<const uint2*>(p.dres + pix * NO + c);
-          if (lo_bf(m.x) > 0.f) v[0] += lo_bf(r.x);
-          if (hi_bf(m.x) > 0.f) v[1] += hi_bf(r.x);
-          if (lo_bf(m.y) > 0.f) v[2] += lo_bf(r.y);
-          if (hi_bf(m.y) > 0.f) v[3] += hi_bf(r.y);
+        for (int c16 = 0; c16 < K16; ++c16) {
+          xv[j][c16] = make_uint4(0, 0, 0, 0);
+          if (ok) xv[j][c16] = *reinterpret_cast<const uint4*>(sp + 16 * c16);
         }
-        *reinterpret_cast<uint2*>(drow + c) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+      }
+#pragma unroll
+      for (int j = 0; j < TG; ++j) {
+        const int tap = grp * TG + j;
+        const char* wrow = wl + 2 * (tap * KC + 8 * hh);
+#pragma unroll
+        for (int c16 = 0; c16 < K16; ++c16) {
+          const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[j][c16]);
+#pragma unroll
+          for (int t = 0; t < 2; ++t)
+            if (t < NT) {
+              const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
+              acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
+            }
+        }
       }
     }
+    if (!live) continue;
+    // acc[t][4q+e] = out[pix][32t + 8q + 4hh + e]
+    uint16_t* drow = p.dst + (size_t)pix * NO;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      if (t < NT) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int c = 32 * t + 8 * q + 4 * hh;
+          if (c >= NO) continue;
+          float v[4] = {acc[t][4 * q], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+          if (MODE == 1 && p.dres) {
+            const uint2 m = *reinterpret_cast<const uint2*>(p.ymask + (size_t)pix * NO + c);
+            const uint2 r = *reinterpret_cast<const uint2*>(p.dres + (size_t)pix * NO + c);
+            if (lo_bf(m.x) > 0.f) v[0] += lo_bf(r.x);
+            if (hi_bf(m.x) > 0.f) v[1] += hi_bf(r.x);
+            if (lo_bf(m.y) > 0.f) v[2] += lo_bf(r.y);
+            if (hi_bf(m.y) > 0.f) v[3] += hi_bf(r.y);
+          }
+          *reinterpret_cast<uint2*>(drow + c) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+        }
+      }
+  }
 }
 
 // Weight gradient.  CO = 32 or 64.  Thread (co = tid % CO, cig = tid / CO) owns
@@ -153,7 +174,8 @@ __global__ __launch_bounds__(256) void conv3x3_wgrad_bf16_kernel(const uint16_t*
     const long pp = p0 + lp;
     uint4 v = make_uint4(0, 0, 0, 0);
     if (pp < P) {
-      const int ox = (int)(pp % Wo), oy = (int)((pp / Wo) % Ho), b = (int)(pp / ((long)Wo * Ho));
+      const uint32_t p32 = (uint32_t)pp, prow = p32 / (uint32_t)Wo;   // the launcher checks that the pixel count fits
+      const int ox = (int)(p32 - prow * (uint32_t)Wo), oy = (int)(prow % (uint32_t)Ho), b = (int)(prow / (uint32_t)Ho);
       const int iy = oy * stride + tap / 3 - 1, ix = ox * stride + tap % 3 - 1;
       if (iy >= 0 && iy < H && ix >= 0 && ix < W)
         v = *reinterpret_cast<const uint4*>(x + (((long)b * H + iy) * W + ix) * Ci + 8 * ch);
@@ -351,9 +373,10 @@ __global__ __launch_bounds__(256) void bn_finish_kernel(BnSumArgs p, unsigned nb
 __global__ __launch_bounds__(256) void bn_apply_bf16_kernel(const uint16_t* x, size_t chunks, int C, const float* mean,
                                                             const float* rstd, const float* g, const float* b,
                                                             const uint16_t* res, uint16_t* y) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= chunks) return;
-  const int c0 = (int)((i * 8) % C);
+  const uint32_t i32 = blockIdx.x * 256 + threadIdx.x;     // fewer than 2^32 chunks (checked by the launcher)
+  if (i32 >= chunks) return;
+  const size_t i = i32;
+  const int c0 = (int)(8 * (i32 % (uint32_t)(C / 8)));
   const uint4 xv = *reinterpret_cast<const uint4*>(x + i * 8);
   const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
   uint4 rv = make_uint4(0, 0, 0, 0);
@@ -375,9 +398,10 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_bf16_kernel(const uint16_t* 
                                                                 const uint16_t* x, size_t chunks, int C, int rows,
                                                                 const float* mean, const float* rstd, const float* g,
                                                                 const float* dg, const float* db, uint16_t* dx) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= chunks) return;
-  const int c0 = (int)((i * 8) % C);
+  const uint32_t i32 = blockIdx.x * 256 + threadIdx.x;     // fewer than 2^32 chunks (checked by the launcher)
+  if (i32 >= chunks) return;
+  const size_t i = i32;
+  const int c0 = (int)(8 * (i32 % (uint32_t)(C / 8)));
   const uint4 xv = *reinterpret_cast<const uint4*>(x + i * 8);
   const uint4 dv = *reinterpret_cast<const uint4*>(dy + i * 8);
   const uint4 yv = *reinterpret_cast<const uint4*>(y + i * 8);
@@ -458,21 +482,45 @@ bool al16(const void* p) { return !(((uintptr_t)p) & 15); }
 // LDS of the implicit-GEMM convolution: the filter as [produced channels rounded up to 32][9 * reduced + 8] bf16
 size_t conv_mfma_lds(int produced, int reduced) { return (size_t)((produced + 31) / 32 * 32) * (18 * reduced + 16); }
 constexpr size_t CONV_MFMA_LDS_MAX = 96 * 1024;
-template <int MODE>
-int conv_mfma_allow_lds(size_t lds) {
+template <int MODE, int K16, int GRP>
+int conv_mfma_launch_g(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   static bool raised[64] = {};    // per device: the attribute belongs to the device's copy of the kernel
-  if (lds <= 64 * 1024) return PPLL_OK;
-  int dev = 0;
-  PPLL_HIP(hipGetDevice(&dev));
-  if (dev < 0 || dev >= 64 || !raised[dev]) {
-    PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                 (int)CONV_MFMA_LDS_MAX));
-    if (dev >= 0 && dev < 64) raised[dev] = true;
+  if (lds > 64 * 1024) {
+    int dev = 0;
+    PPLL_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64 || !raised[dev]) {
+      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE, K16, GRP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)CONV_MFMA_LDS_MAX));
+      if (dev >= 0 && dev < 64) raised[dev] = true;
+    }
   }
+  // a workgroup keeps its filter for up to 4 tiles of 128 pixels once there are more than 2048 of them
+  const long ntiles = (P + 127) / 128;
+  const long tpw = ntiles >= 8192 ? 4 : (ntiles >= 4096 ? 2 : 1);
+  hipLaunchKernelGGL((conv3x3_mfma_kernel<MODE, K16, GRP>), dim3((unsigned)((ntiles + tpw - 1) / tpw)), dim3(256), lds, s, p);
+  PPLL_HIP(hipGetLastError());
   return PPLL_OK;
+}
+template <int MODE, int K16>
+int conv_mfma_launch_k(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
+  return conv_mfma_launch_g<MODE, K16, 1>(s, p, P, lds);   // the three taps of a filter row in flight together
+}
+// k16 = reduced channels / 16: 1, 2, 3 or 4
+template <int MODE>
+int conv_mfma_launch(hipStream_t s, const ConvArgs& p, long P, int k16, size_t lds) {
+  switch (k16) {
+    case 1: return conv_mfma_launch_k<MODE, 1>(s, p, P, lds);
+    case 2: return conv_mfma_launch_k<MODE, 2>(s, p, P, lds);
+    case 3: return conv_mfma_launch_k<MODE, 3>(s, p, P, lds);
+    case 4: return conv_mfma_launch_k<MODE, 4>(s, p, P, lds);
+  }
+  set_error("conv3x3: %d reduced channels have no matrix-core kernel", 16 * k16);
+  return PPLL_ERR_CONFIG;
 }
 }  // namespace
 
+// the convolution kernels index pixels with 32 bits
+bool conv_pixels_fit(int B, int H, int W) { return (size_t)B * H * W < ((size_t)1 << 31) - 128; }
 bool conv_bf16_supported(int dt, int wdt, int Ci, int Co, const void* a, const void* b, const void* c) {
   if (dt != BF16 || wdt != BF16) return false;
   if ((Ci % 16) || (Co % 16) || Ci > 128 || Co > 128) return false;
@@ -484,10 +532,7 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
   ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr};
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   const size_t lds = conv_mfma_lds(Co, Ci);
-  PPLL_TRY(conv_mfma_allow_lds<0>(lds));
-  hipLaunchKernelGGL(conv3x3_mfma_kernel<0>, dim3((unsigned)((P + 127) / 128)), dim3(256), lds, s, p);
-  PPLL_HIP(hipGetLastError());
-  return PPLL_OK;
+  return conv_mfma_launch<0>(s, p, P, Ci / 16, lds);
 }
 
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
@@ -496,15 +541,12 @@ int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int 
              (const uint16_t*)ymask};
   const long P = (long)B * H * W;
   const size_t lds = conv_mfma_lds(Ci, Co);
-  PPLL_TRY(conv_mfma_allow_lds<1>(lds));
-  hipLaunchKernelGGL(conv3x3_mfma_kernel<1>, dim3((unsigned)((P + 127) / 128)), dim3(256), lds, s, p);
-  PPLL_HIP(hipGetLastError());
-  return PPLL_OK;
+  return conv_mfma_launch<1>(s, p, P, Co / 16, lds);
 }
 
 // forward and input gradient produce up to 64 channels (two MFMA tiles of 32; 16 and 48 leave half a tile idle)
-bool conv_fwd_bf16_ok(int Ci, int Co) { return Co % 16 == 0 && Co <= 64 && conv_mfma_lds(Co, Ci) <= CONV_MFMA_LDS_MAX; }
-bool conv_dgrad_bf16_ok(int Ci, int Co) { return Ci % 16 == 0 && Ci <= 64 && conv_mfma_lds(Ci, Co) <= CONV_MFMA_LDS_MAX; }
+bool conv_fwd_bf16_ok(int Ci, int Co) { return Co % 16 == 0 && Co <= 64 && Ci <= 64 && conv_mfma_lds(Co, Ci) <= CONV_MFMA_LDS_MAX; }
+bool conv_dgrad_bf16_ok(int Ci, int Co) { return Ci % 16 == 0 && Ci <= 64 && Co <= 64 && conv_mfma_lds(Ci, Co) <= CONV_MFMA_LDS_MAX; }
 bool conv_wgrad_bf16_ok(int Ci, int Co) {
   if (Co == 16) return Ci == 16;
   return (Co == 32 || Co == 64) && Ci % 16 == 0 && Ci >= 16 && Ci <= 64;
@@ -716,8 +758,9 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   return reduce_conv_filters(s, rq, queued, partials, chunks, Ci, Co, ci_keep, dw);
 }
 
-bool bn_bf16_supported(int dt, int C, const void* a, const void* b, const void* c, const void* d) {
+bool bn_bf16_supported(int dt, int rows, int C, const void* a, const void* b, const void* c, const void* d) {
   if (dt != BF16 || (C % 8) || C < 8 || C > 128 || (256 % (C / 8))) return false;
+  if ((size_t)rows * C / 8 >= ((size_t)1 << 32)) return false;   // the kernels index 16-byte chunks with 32 bits
   return al16(a) && al16(b) && al16(c) && al16(d);
 }
 constexpr int BN_TICKET_BLOCKS = 64;
