@@ -276,7 +276,7 @@ int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int
 
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, const void* dres, const void* ymask, void* dx) {
-  if (conv_bf16_supported(dt, wdt, Ci, Co, dy, w, dx) && conv_dgrad_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W) &&
+  if (conv_bf16_supported(dt, wdt, Ci, Co, dy, w, dx) && conv_dgrad_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W) && stride <= 2 &&
       !((((uintptr_t)dres) | ((uintptr_t)ymask)) & 15))
     return launch_conv3x3_dgrad_bf16(s, dy, w, B, H, W, Ci, Co, stride, dres, ymask, dx);
   size_t total = (size_t)B * H * W * Ci;

@@ -38,7 +38,7 @@ struct ConvArgs {
 // MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = 16 * K16 channels reduced.
 // GRP: how many of a pixel's nine tap loads are issued before the first product waits for one
 // (0: one, 1: the three of a filter row, 3: all nine; a filter row measured best).
-template <int MODE, int K16, int GRP>
+template <int MODE, int K16, int NT, int GRP>
 __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   extern __shared__ __align__(16) char wl[];        // [NO rounded up to 32][9*KC] bf16, row stride RSW bytes
   constexpr int KC = 16 * K16;
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   const int OH = MODE == 0 ? Ho : p.H, OW = MODE == 0 ? Wo : p.W;      // output spatial size
   const int SH = MODE == 0 ? p.H : Ho, SW = MODE == 0 ? p.W : Wo;      // source spatial size
   const long P = (long)p.B * OH * OW, ntiles = (P + 127) / 128;
-  const int NT = (NO + 31) / 32;     // NO = 16: the upper half of the one tile is never stored
+  // NT = tiles of 32 produced channels (NO = 16: the upper half of the one tile is never stored)
   // the workgroup keeps its filter for several tiles of 128 pixels
   for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     // 32-bit index arithmetic (the launcher checks that the pixel count fits): 64-bit division costs more than the tile
@@ -85,9 +85,9 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
     const bool live = pix < (uint32_t)P;
     const uint32_t prow = pix / (uint32_t)OW;
     const int ox = (int)(pix - prow * (uint32_t)OW), oy = (int)(prow % (uint32_t)OH), b = (int)(prow / (uint32_t)OH);
-    f32x16 acc[2];
+    f32x16 acc[NT];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
     constexpr int NG = GRP == 0 ? 9 : (GRP == 1 ? 3 : 1), TG = 9 / NG;   // groups of taps whose loads are in flight together
@@ -102,9 +102,10 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
         if (MODE == 0) {
           sy = oy * p.stride + ky - 1; sx = ox * p.stride + kx - 1;
         } else {
-          const int ty = oy + 1 - ky, tx = ox + 1 - kx;
-          ok = ok && ty >= 0 && tx >= 0 && (ty % p.stride) == 0 && (tx % p.stride) == 0;
-          sy = ty / p.stride; sx = tx / p.stride;
+          // stride is 1 or 2 (checked by the launcher): mask and shift instead of a division per tap
+          const int ty = oy + 1 - ky, tx = ox + 1 - kx, sm1 = p.stride - 1;
+          ok = ok && ty >= 0 && tx >= 0 && !((ty | tx) & sm1);
+          sy = ty >> sm1; sx = tx >> sm1;
         }
         ok = ok && sy >= 0 && sy < SH && sx >= 0 && sx < SW;
         const uint16_t* sp = p.src + (((long)b * SH + sy) * SW + sx) * KC + 8 * hh;
@@ -122,11 +123,10 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
         for (int c16 = 0; c16 < K16; ++c16) {
           const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[j][c16]);
 #pragma unroll
-          for (int t = 0; t < 2; ++t)
-            if (t < NT) {
-              const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
-              acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
-            }
+          for (int t = 0; t < NT; ++t) {
+            const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
+          }
         }
       }
     }
@@ -134,8 +134,7 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
     // acc[t][4q+e] = out[pix][32t + 8q + 4hh + e]
     uint16_t* drow = p.dst + (size_t)pix * NO;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-      if (t < NT) {
+    for (int t = 0; t < NT; ++t) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           const int c = 32 * t + 8 * q + 4 * hh;
@@ -482,14 +481,14 @@ bool al16(const void* p) { return !(((uintptr_t)p) & 15); }
 // LDS of the implicit-GEMM convolution: the filter as [produced channels rounded up to 32][9 * reduced + 8] bf16
 size_t conv_mfma_lds(int produced, int reduced) { return (size_t)((produced + 31) / 32 * 32) * (18 * reduced + 16); }
 constexpr size_t CONV_MFMA_LDS_MAX = 96 * 1024;
-template <int MODE, int K16, int GRP>
+template <int MODE, int K16, int NT, int GRP>
 int conv_mfma_launch_g(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   static bool raised[64] = {};    // per device: the attribute belongs to the device's copy of the kernel
   if (lds > 64 * 1024) {
     int dev = 0;
     PPLL_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64 || !raised[dev]) {
-      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE, K16, GRP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE, K16, NT, GRP>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)CONV_MFMA_LDS_MAX));
       if (dev >= 0 && dev < 64) raised[dev] = true;
     }
@@ -497,13 +496,16 @@ int conv_mfma_launch_g(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   // a workgroup keeps its filter for up to 4 tiles of 128 pixels once there are more than 2048 of them
   const long ntiles = (P + 127) / 128;
   const long tpw = ntiles >= 8192 ? 4 : (ntiles >= 4096 ? 2 : 1);
-  hipLaunchKernelGGL((conv3x3_mfma_kernel<MODE, K16, GRP>), dim3((unsigned)((ntiles + tpw - 1) / tpw)), dim3(256), lds, s, p);
+  hipLaunchKernelGGL((conv3x3_mfma_kernel<MODE, K16, NT, GRP>), dim3((unsigned)((ntiles + tpw - 1) / tpw)), dim3(256), lds, s, p);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
 template <int MODE, int K16>
 int conv_mfma_launch_k(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
-  return conv_mfma_launch_g<MODE, K16, 1>(s, p, P, lds);   // the three taps of a filter row in flight together
+  const int produced = MODE == 0 ? p.Co : p.Ci;
+  // GRP = 1: the three taps of a filter row in flight together
+  if (produced <= 32) return conv_mfma_launch_g<MODE, K16, 1, 1>(s, p, P, lds);
+  return conv_mfma_launch_g<MODE, K16, 2, 1>(s, p, P, lds);
 }
 // k16 = reduced channels / 16: 1, 2, 3 or 4
 template <int MODE>
