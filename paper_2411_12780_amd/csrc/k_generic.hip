@@ -162,17 +162,47 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float* parti
   }
 }
 
-// the same for up to 16 reductions in one launch: workgroups first[j] .. first[j+1]-1 belong to job j
+// the same for up to 16 reductions in one launch: workgroups first[j] .. first[j+1]-1 belong to job j.
+// A job whose rows are 16-byte aligned with a length that is a multiple of 4 takes four columns per
+// thread (64 columns per workgroup, 256-byte row segments); the 16 thread groups take the partial
+// rows round-robin, eight loads in flight, and are added in group order.
 constexpr int RED_BATCH = 16;
-struct ReduceBatch { int n; int first[RED_BATCH + 1]; ReduceJob job[RED_BATCH]; };
+struct ReduceBatch { int n; int first[RED_BATCH + 1]; int vec4[RED_BATCH]; ReduceJob job[RED_BATCH]; };
 __global__ __launch_bounds__(256) void reduce_batch_kernel(ReduceBatch a) {
-  __shared__ float red[16][17];
+  __shared__ float red[16][65];
   int j = 0;
   while (j + 1 < a.n && (int)blockIdx.x >= a.first[j + 1]) ++j;
   const float* partial = a.job[j].src;
   const int chunks = a.job[j].chunks, N = a.job[j].N;
   const long stride = a.job[j].stride;
   const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  if (a.vec4[j]) {
+    const int n = ((int)blockIdx.x - a.first[j]) * 64 + 4 * col;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (n < N)
+      for (int c = grp; c < chunks; c += 16 * 8) {
+        float4 q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const int cu = c + 16 * u;
+          q[u] = cu < chunks ? *reinterpret_cast<const float4*>(partial + (size_t)cu * stride + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { acc.x += q[u].x; acc.y += q[u].y; acc.z += q[u].z; acc.w += q[u].w; }
+      }
+    red[grp][4 * col] = acc.x; red[grp][4 * col + 1] = acc.y; red[grp][4 * col + 2] = acc.z; red[grp][4 * col + 3] = acc.w;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+      const int m = ((int)blockIdx.x - a.first[j]) * 64 + threadIdx.x;
+      if (m < N) {
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) t += red[g][threadIdx.x];
+        a.job[j].dst[m] = t * a.job[j].scale;
+      }
+    }
+    return;
+  }
   const int n = ((int)blockIdx.x - a.first[j]) * 16 + col;
   float acc = 0.f;
   if (n < N)
@@ -215,7 +245,9 @@ int ReduceQueue::flush(hipStream_t s) {
     for (int j = 0; j < b.n; ++j) {
       b.job[j] = jobs[j0 + j];
       b.first[j] = blocks;
-      blocks += (b.job[j].N + 15) / 16;
+      const ReduceJob& q = b.job[j];
+      b.vec4[j] = q.N >= 64 && (q.N % 4) == 0 && (q.stride % 4) == 0 && !(((uintptr_t)q.src) & 15);
+      blocks += b.vec4[j] ? (q.N + 63) / 64 : (q.N + 15) / 16;
     }
     b.first[b.n] = blocks;
     if (blocks > 0) {

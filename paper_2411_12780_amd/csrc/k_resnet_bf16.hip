@@ -567,9 +567,10 @@ typedef __attribute__((ext_vector_type(8))) __bf16 wg_bf16x8;
 // Per workgroup and k-split one partial, summed by the ordered second-stage reduction.
 typedef __attribute__((ext_vector_type(4))) float wg_f32x4;
 constexpr int WGT_WAVES = 8;
-// 16 and 32 channels: the workgroup's k-splits fit LDS together (72 / 144 KiB) and leave as one partial
+// A workgroup's k-splits are added in LDS and leave as one partial: 16 and 32 channels hold all of them at once
+// (72 / 144 KiB), 64 channels hand the second of two over (144 KiB)
 __host__ __device__ constexpr bool WGT_FOLD(int C) { return C <= 32; }
-__host__ __device__ constexpr int wgt_partials_per_block(int C) { return WGT_FOLD(C) ? 1 : WGT_WAVES / (C / 16); }
+__host__ __device__ constexpr int wgt_partials_per_block(int) { return 1; }
 __host__ __device__ inline int wgt_pad16(int bytes) { return bytes + ((16 - bytes % 128) + 128) % 128; }   // = 16 mod 128
 __host__ __device__ inline int wgt_row_stride(int W) { return 16 + 2 * W; }
 __host__ __device__ inline int wgt_x_stride(int H, int W) { return wgt_pad16((H + 2) * wgt_row_stride(W) + 16); }
@@ -670,19 +671,37 @@ __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(con
       out[i] = v;
     }
   } else {
-    float* out = partial + ((size_t)blockIdx.x * WK + kq) * NW;
+    // 64 channels, two k-splits: the second half of the waves hands its sums over through LDS
+    static_assert(WK == 2, "two k-splits expected");
+    float* fold = reinterpret_cast<float*>(sm);
+    __syncthreads();                          // the tiles are no longer read
+    if (kq == 1) {
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap)
+      for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
-      for (int t = 0; t < CT; ++t)
+        for (int t = 0; t < CT; ++t)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) out[((size_t)tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+          for (int e = 0; e < 4; ++e) fold[(tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+    }
+    __syncthreads();
+    if (kq == 0) {
+      float* out = partial + (size_t)blockIdx.x * NW;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int t = 0; t < CT; ++t)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int i = (tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r;
+            out[i] = acc[tap][t][e] + fold[i];
+          }
+    }
   }
 }
 
 static size_t wgrad_tiles_lds(int H, int W, int C) {
   const size_t tiles = (size_t)C * (wgt_x_stride(H, W) + wgt_dy_stride(H, W));
-  const size_t fold = WGT_FOLD(C) ? (size_t)(WGT_WAVES / (C / 16)) * 9 * C * C * sizeof(float) : 0;
+  const size_t fold = (size_t)(WGT_FOLD(C) ? WGT_WAVES / (C / 16) : 1) * 9 * C * C * sizeof(float);
   return tiles > fold ? tiles : fold;
 }
 static bool wgrad_tiles_ok(int H, int W, int Ci, int Co, int stride) {
