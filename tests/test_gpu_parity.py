@@ -322,6 +322,14 @@ def test_resnet_bf16_stem_module():
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
 
 
+@pytest.mark.parametrize("name", ["resnet32_stage1_bf16", "resnet32_stage2_bf16", "resnet32_stage3_bf16"])
+def test_resnet32_stages_at_their_full_shape(name):
+    # the three stages of ResNet-32 at their real map and channel sizes (stem, both downsampling blocks, 16 / 32 /
+    # 64 channels); batch 100 instead of 1024 keeps the float64 oracle to seconds and leaves ragged last tiles.
+    # Five blocks of stored bf16 values decorrelate single gradients (as in the 32-channel stage test below).
+    run_case(synth.workload(name, batch=100), steps=1, check_bn=True, grad_tol=0.3)
+
+
 def test_resnet_bf16_stage_full_size_natural_statistics():
     run_case(synth.workload("resnet_stage_bf16"), steps=2, check_bn=True, grad_tol=0.3)
 
