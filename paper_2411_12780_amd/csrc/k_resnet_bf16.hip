@@ -556,38 +556,49 @@ bool conv_wgrad_bf16_ok(int Ci, int Co) {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 wg_bf16x8;
 // ---------------------------------------------------------------------------------------------
-// Weight gradient on the matrix cores for C -> C channels (C = 16, 32, 64), stride 1, image rows of
-// 8, 16 or 32 pixels (any width that is a multiple of 8).  The reduction
-// index of a 16x16x32 MFMA is the pixel: a k-step is four groups of 8 consecutive pixels of one row.
-// A workgroup of 8 waves takes whole images: it transposes x and dy of an image to [channel][pixel]
-// in LDS (x with a 16-byte zero gap in front of every row and a zero row above and below, so that
-// no tap needs a bounds test), a wave owns one tile of 16 output channels for all 9 taps and all
-// input-channel tiles and every (8 / tiles)-th k-step.  The fragment of the taps one pixel to the
-// left / right is the aligned one shifted by two bytes with the neighbouring pixel read separately.
-// Per workgroup and k-split one partial, summed by the ordered second-stage reduction.
+// Weight gradient on the matrix cores for CI -> CO channels (16, 32 or 64 each), stride 1 or 2, output
+// rows of 8, 16, 24, ... pixels.  The reduction index of a 16x16x32 MFMA is the output pixel: a k-step is
+// four groups of 8 consecutive pixels of one output row.  A workgroup of 8 waves takes whole images: it
+// transposes x and dy of an image to [channel][pixel] in LDS.  x gets a 16-byte zero gap in front of every
+// row and a zero row above and below, so that no tap needs a bounds test; with stride 2 a row of x is
+// stored as its odd columns followed by its even columns, which makes the pixels that 8 consecutive
+// outputs read consecutive again.  A wave owns one tile of 16 output channels for all 9 taps and all
+// input-channel tiles and every (8 / tiles)-th k-step.  The fragment of the tap that starts one pixel to
+// the left (and, at stride 1, to the right) is the aligned one shifted by two bytes, the neighbouring
+// pixel read separately.  The k-splits of a workgroup are added in LDS in k-split order: one partial per
+// workgroup, summed over workgroups by the ordered second-stage reduction.
 typedef __attribute__((ext_vector_type(4))) float wg_f32x4;
 constexpr int WGT_WAVES = 8;
-// A workgroup's k-splits are added in LDS and leave as one partial: 16 and 32 channels hold all of them at once
-// (72 / 144 KiB), 64 channels hand the second of two over (144 KiB)
-__host__ __device__ constexpr bool WGT_FOLD(int C) { return C <= 32; }
-__host__ __device__ constexpr int wgt_partials_per_block(int) { return 1; }
+constexpr int WGT_FOLD_BYTES = 9 * 64 * 64 * 4;      // 144 KiB: LDS the k-split sums may take
 __host__ __device__ inline int wgt_pad16(int bytes) { return bytes + ((16 - bytes % 128) + 128) % 128; }   // = 16 mod 128
 __host__ __device__ inline int wgt_row_stride(int W) { return 16 + 2 * W; }
 __host__ __device__ inline int wgt_x_stride(int H, int W) { return wgt_pad16((H + 2) * wgt_row_stride(W) + 16); }
-__host__ __device__ inline int wgt_dy_stride(int H, int W) { return wgt_pad16(H * W * 2); }
+__host__ __device__ inline int wgt_dy_stride(int Ho, int Wo) { return wgt_pad16(Ho * Wo * 2); }
 
-template <int C>
+// 4 pixels x 8 channels (one uint4 per pixel) -> for channel i the 4 pixels as one uint2
+__device__ __forceinline__ uint2 wgt_gather4(const uint4& p0, const uint4& p1, const uint4& p2, const uint4& p3, int i) {
+  const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
+  uint2 o;
+  o.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&p1)[i >> 1], reinterpret_cast<const uint32_t*>(&p0)[i >> 1], sel);
+  o.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&p3)[i >> 1], reinterpret_cast<const uint32_t*>(&p2)[i >> 1], sel);
+  return o;
+}
+
+template <int CI, int CO, int S>
 __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(const uint16_t* __restrict__ x,
                                                                             const uint16_t* __restrict__ dy, int B, int H,
                                                                             int W, float* __restrict__ partial) {
-  constexpr int CT = C / 16, WN = CT, WK = WGT_WAVES / WN, NT = 64 * WGT_WAVES;
+  constexpr int CT = CI / 16, WN = CO / 16, WK = WGT_WAVES / WN, NT = 64 * WGT_WAVES, NW = 9 * CI * CO;
+  constexpr bool FOLD_ALL = WK * NW * 4 <= WGT_FOLD_BYTES;
+  static_assert(FOLD_ALL || WK == 2, "the k-splits either fit LDS together or are two");
   extern __shared__ __align__(16) char sm[];
-  const int RS = wgt_row_stride(W), CSX = wgt_x_stride(H, W), CSD = wgt_dy_stride(H, W);
-  char* xt = sm;                              // x  as [C][H + 2 rows][16-byte gap, W pixels]
-  char* dt = sm + C * CSX;                    // dy as [C][H * W pixels]
+  const int Ho = H / S, Wo = W / S;            // S = 2: H and W are even
+  const int RS = wgt_row_stride(W), CSX = wgt_x_stride(H, W), CSD = wgt_dy_stride(Ho, Wo);
+  char* xt = sm;                              // x  as [CI][H + 2 rows][16-byte gap, W pixels]
+  char* dt = sm + CI * CSX;                   // dy as [CO][Ho * Wo pixels]
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, r = lane & 15, q = lane >> 4;
   const int wn = wave % WN, kq = wave / WN;
-  for (int o = tid * 16; o < C * CSX; o += NT * 16) *reinterpret_cast<uint4*>(xt + o) = make_uint4(0, 0, 0, 0);
+  for (int o = tid * 16; o < CI * CSX; o += NT * 16) *reinterpret_cast<uint4*>(xt + o) = make_uint4(0, 0, 0, 0);
   wg_f32x4 acc[9][CT];
 #pragma unroll
   for (int t = 0; t < 9; ++t)
@@ -595,37 +606,46 @@ __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(con
     for (int j = 0; j < CT; ++j)
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[t][j][e] = 0.f;
-  const int w4 = W / 4, w8 = W / 8, items = H * w4 * (C / 8), groups = H * w8, ksteps = (groups + 3) / 4;
+  const int wo8 = Wo / 8, groups = Ho * wo8, ksteps = (groups + 3) / 4;
+  const int xw = S == 1 ? W / 4 : W / 8, xitems = H * xw * (CI / 8);     // (row, 4 or 8 pixels, 8 channels)
+  const int dw4 = Wo / 4, ditems = Ho * dw4 * (CO / 8);
   for (int b = blockIdx.x; b < B; b += gridDim.x) {
-    const uint16_t* xb = x + (size_t)b * H * W * C;
-    const uint16_t* db = dy + (size_t)b * H * W * C;
+    const uint16_t* xb = x + (size_t)b * H * W * CI;
+    const uint16_t* db = dy + (size_t)b * Ho * Wo * CO;
     __syncthreads();                          // zero fill done / the previous image's tiles are no longer read
-    for (int item = tid; item < items; item += NT) {
-      const int cg = item % (C / 8), pg = item / (C / 8), y = pg / w4, x0 = (pg % w4) * 4;
-      uint4 rx[4], rd[4];
+    for (int item = tid; item < xitems; item += NT) {
+      const int cg = item % (CI / 8), pg = item / (CI / 8), y = pg / xw, xg = pg % xw;
+      char* row = xt + (8 * cg) * CSX + (y + 1) * RS + 16;
+      if (S == 1) {
+        uint4 rx[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const size_t off = ((size_t)(y * W + x0 + j)) * C + 8 * cg;
-        rx[j] = *reinterpret_cast<const uint4*>(xb + off);
-        rd[j] = *reinterpret_cast<const uint4*>(db + off);
-      }
+        for (int j = 0; j < 4; ++j) rx[j] = *reinterpret_cast<const uint4*>(xb + ((size_t)(y * W + 4 * xg + j)) * CI + 8 * cg);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint32_t sel = (i & 1) ? 0x07060302u : 0x05040100u;
-        uint2 ox, od;
-        ox.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[0])[i >> 1], sel);
-        ox.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rx[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rx[2])[i >> 1], sel);
-        od.x = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[1])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[0])[i >> 1], sel);
-        od.y = __builtin_amdgcn_perm(reinterpret_cast<const uint32_t*>(&rd[3])[i >> 1], reinterpret_cast<const uint32_t*>(&rd[2])[i >> 1], sel);
-        *reinterpret_cast<uint2*>(xt + (8 * cg + i) * CSX + (y + 1) * RS + 16 + 2 * x0) = ox;
-        *reinterpret_cast<uint2*>(dt + (8 * cg + i) * CSD + (y * W + x0) * 2) = od;
+        for (int i = 0; i < 8; ++i) *reinterpret_cast<uint2*>(row + i * CSX + 8 * xg) = wgt_gather4(rx[0], rx[1], rx[2], rx[3], i);
+      } else {
+        uint4 rx[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) rx[j] = *reinterpret_cast<const uint4*>(xb + ((size_t)(y * W + 8 * xg + j)) * CI + 8 * cg);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {   // odd columns first, then the even ones
+          *reinterpret_cast<uint2*>(row + i * CSX + 8 * xg) = wgt_gather4(rx[1], rx[3], rx[5], rx[7], i);
+          *reinterpret_cast<uint2*>(row + i * CSX + 2 * Wo + 8 * xg) = wgt_gather4(rx[0], rx[2], rx[4], rx[6], i);
+        }
       }
+    }
+    for (int item = tid; item < ditems; item += NT) {
+      const int cg = item % (CO / 8), pg = item / (CO / 8);      // pg = 4-pixel group of the image, row-major
+      uint4 rd[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) rd[j] = *reinterpret_cast<const uint4*>(db + ((size_t)(4 * pg + j)) * CO + 8 * cg);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *reinterpret_cast<uint2*>(dt + (8 * cg + i) * CSD + 8 * pg) = wgt_gather4(rd[0], rd[1], rd[2], rd[3], i);
     }
     __syncthreads();
     for (int ks = kq; ks < ksteps; ks += WK) {
       // the last k-step of an image may hold fewer than four pixel groups: the others multiply by zero
       const bool live = 4 * ks + q < groups;
-      const int g = live ? 4 * ks + q : 0, y = g / w8, x0 = 8 * (g % w8);
+      const int g = live ? 4 * ks + q : 0, oy = g / wo8, x0 = 8 * (g % wo8);
       uint4 gv = make_uint4(0, 0, 0, 0);
       if (live) gv = *reinterpret_cast<const uint4*>(dt + (16 * wn + r) * CSD + g * 16);
       const wg_bf16x8 gf = __builtin_bit_cast(wg_bf16x8, gv);
@@ -633,37 +653,42 @@ __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(con
       for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
         for (int t = 0; t < CT; ++t) {
-          const char* base = xt + (16 * t + r) * CSX + (y + ky) * RS + 16 + 2 * x0;
-          const uint4 w = *reinterpret_cast<const uint4*>(base);
+          // row S*oy + ky - 1 of the image = row S*oy + ky of the padded tile
+          const char* base = xt + (16 * t + r) * CSX + (S * oy + ky) * RS + 16 + 2 * x0;
+          const uint4 w = *reinterpret_cast<const uint4*>(base);     // S = 1: pixels x0..x0+7; S = 2: odd columns 2 x0 + 1 ..
           const uint32_t prev = *reinterpret_cast<const uint16_t*>(base - 2);
-          const uint32_t next = *reinterpret_cast<const uint16_t*>(base + 16);
-          uint4 a0, a2;
+          uint4 a0, a1, a2;
           a0.x = (w.x << 16) | prev;
           a0.y = __builtin_amdgcn_alignbyte(w.y, w.x, 2);
           a0.z = __builtin_amdgcn_alignbyte(w.z, w.y, 2);
           a0.w = __builtin_amdgcn_alignbyte(w.w, w.z, 2);
-          a2.x = a0.y; a2.y = a0.z; a2.z = a0.w;
-          a2.w = (next << 16) | (w.w >> 16);
+          if (S == 1) {
+            const uint32_t next = *reinterpret_cast<const uint16_t*>(base + 16);
+            a1 = w;
+            a2.x = a0.y; a2.y = a0.z; a2.z = a0.w;
+            a2.w = (next << 16) | (w.w >> 16);
+          } else {
+            a1 = *reinterpret_cast<const uint4*>(base + 2 * Wo);     // even columns 2 x0 ..
+            a2 = w;
+          }
           acc[3 * ky][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(wg_bf16x8, a0), gf, acc[3 * ky][t], 0, 0, 0);
-          acc[3 * ky + 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(wg_bf16x8, w), gf, acc[3 * ky + 1][t], 0, 0, 0);
+          acc[3 * ky + 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(wg_bf16x8, a1), gf, acc[3 * ky + 1][t], 0, 0, 0);
           acc[3 * ky + 2][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(wg_bf16x8, a2), gf, acc[3 * ky + 2][t], 0, 0, 0);
         }
     }
   }
   // acc[tap][t][e] = dw[tap][ci = 16 t + 4 q + e][co = 16 wn + r] of this wave's k-steps
-  constexpr int NW = 9 * C * C;
-  if constexpr (WGT_FOLD(C)) {
-    // the k-splits of the workgroup are added in LDS, in k-split order: one partial per workgroup
-    float* fold = reinterpret_cast<float*>(sm);
-    __syncthreads();                          // the tiles are no longer read
+  float* fold = reinterpret_cast<float*>(sm);
+  float* out = partial + (size_t)blockIdx.x * NW;
+  __syncthreads();                            // the tiles are no longer read
+  if constexpr (FOLD_ALL) {
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
       for (int t = 0; t < CT; ++t)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) fold[kq * NW + (tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+        for (int e = 0; e < 4; ++e) fold[kq * NW + (tap * CI + 16 * t + 4 * q + e) * CO + 16 * wn + r] = acc[tap][t][e];
     __syncthreads();
-    float* out = partial + (size_t)blockIdx.x * NW;
     for (int i = tid; i < NW; i += NT) {
       float v = fold[i];
 #pragma unroll
@@ -671,66 +696,78 @@ __global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(con
       out[i] = v;
     }
   } else {
-    // 64 channels, two k-splits: the second half of the waves hands its sums over through LDS
-    static_assert(WK == 2, "two k-splits expected");
-    float* fold = reinterpret_cast<float*>(sm);
-    __syncthreads();                          // the tiles are no longer read
+    // two k-splits: the second half of the waves hands its sums over through LDS
     if (kq == 1) {
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
         for (int t = 0; t < CT; ++t)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) fold[(tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r] = acc[tap][t][e];
+          for (int e = 0; e < 4; ++e) fold[(tap * CI + 16 * t + 4 * q + e) * CO + 16 * wn + r] = acc[tap][t][e];
     }
     __syncthreads();
     if (kq == 0) {
-      float* out = partial + (size_t)blockIdx.x * NW;
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
         for (int t = 0; t < CT; ++t)
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
-            const int i = (tap * C + 16 * t + 4 * q + e) * C + 16 * wn + r;
+            const int i = (tap * CI + 16 * t + 4 * q + e) * CO + 16 * wn + r;
             out[i] = acc[tap][t][e] + fold[i];
           }
     }
   }
 }
 
-static size_t wgrad_tiles_lds(int H, int W, int C) {
-  const size_t tiles = (size_t)C * (wgt_x_stride(H, W) + wgt_dy_stride(H, W));
-  const size_t fold = (size_t)(WGT_FOLD(C) ? WGT_WAVES / (C / 16) : 1) * 9 * C * C * sizeof(float);
+static size_t wgrad_tiles_lds(int H, int W, int Ci, int Co, int stride) {
+  const size_t tiles = (size_t)Ci * wgt_x_stride(H, W) + (size_t)Co * wgt_dy_stride(H / stride, W / stride);
+  const size_t nw = (size_t)9 * Ci * Co * 4, wk = WGT_WAVES / (Co / 16);
+  const size_t fold = wk * nw <= (size_t)WGT_FOLD_BYTES ? wk * nw : nw;
   return tiles > fold ? tiles : fold;
 }
 static bool wgrad_tiles_ok(int H, int W, int Ci, int Co, int stride) {
-  return stride == 1 && Ci == Co && (Ci == 16 || Ci == 32 || Ci == 64) && W >= 8 && (W % 8) == 0 &&
-         wgrad_tiles_lds(H, W, Ci) <= 160 * 1024;
+  const bool chan = stride == 1 ? (Ci == Co && (Ci == 16 || Ci == 32 || Ci == 64))
+                                : ((Ci == 16 && (Co == 32 || Co == 64)) || (Ci == 32 && Co == 64) || (Ci == 64 && Co == 64));
+  if (!chan || stride < 1 || stride > 2 || (H % stride) || (W % stride)) return false;
+  const int Wo = W / stride;
+  return Wo >= 8 && (Wo % 8) == 0 && wgrad_tiles_lds(H, W, Ci, Co, stride) <= 160 * 1024;
 }
 // workgroups: one per image up to the number that keeps the partial sums near 32 MiB
-static int wgrad_tiles_blocks(int B, int C) {
-  const int wk = wgt_partials_per_block(C);
-  long cap = ((long)32 << 20) / ((long)wk * 9 * C * C * 4);
+static int wgrad_tiles_blocks(int B, int Ci, int Co) {
+  long cap = ((long)32 << 20) / ((long)9 * Ci * Co * 4);
   cap = cap < 32 ? 32 : (cap > 256 ? 256 : cap);
   return B < cap ? B : (int)cap;
 }
-template <int C>
+template <int CI, int CO, int S>
 static int wgrad_tiles_launch(hipStream_t s, const void* x, const void* dy, int B, int H, int W, float* partials, int blocks) {
-  const size_t lds = wgrad_tiles_lds(H, W, C);
+  const size_t lds = wgrad_tiles_lds(H, W, CI, CO, S);
   if (lds > 64 * 1024)
-    PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_wgrad_tiles_kernel<C>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(conv3x3_wgrad_tiles_kernel<C>, dim3(blocks), dim3(64 * WGT_WAVES), lds, s, (const uint16_t*)x,
+    PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_wgrad_tiles_kernel<CI, CO, S>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                 (int)lds));
+  hipLaunchKernelGGL((conv3x3_wgrad_tiles_kernel<CI, CO, S>), dim3(blocks), dim3(64 * WGT_WAVES), lds, s, (const uint16_t*)x,
                      (const uint16_t*)dy, B, H, W, partials);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
+}
+static int wgrad_tiles_dispatch(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co, int stride,
+                                float* part, int blocks) {
+  if (stride == 1) {
+    if (Ci == 16) return wgrad_tiles_launch<16, 16, 1>(s, x, dy, B, H, W, part, blocks);
+    if (Ci == 32) return wgrad_tiles_launch<32, 32, 1>(s, x, dy, B, H, W, part, blocks);
+    return wgrad_tiles_launch<64, 64, 1>(s, x, dy, B, H, W, part, blocks);
+  }
+  if (Ci == 16 && Co == 32) return wgrad_tiles_launch<16, 32, 2>(s, x, dy, B, H, W, part, blocks);
+  if (Ci == 16 && Co == 64) return wgrad_tiles_launch<16, 64, 2>(s, x, dy, B, H, W, part, blocks);
+  if (Ci == 32 && Co == 64) return wgrad_tiles_launch<32, 64, 2>(s, x, dy, B, H, W, part, blocks);
+  return wgrad_tiles_launch<64, 64, 2>(s, x, dy, B, H, W, part, blocks);
 }
 
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride) {
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   size_t n = (size_t)((P + WG_PIX_F - 1) / WG_PIX_F) * 9 * Ci * Co;
   if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
-    const size_t m = (size_t)wgrad_tiles_blocks(B, Ci) * wgt_partials_per_block(Ci) * 9 * Ci * Co;
+    const size_t m = (size_t)wgrad_tiles_blocks(B, Ci, Co) * 9 * Ci * Co;
     if (m > n) n = m;
   }
   return n;
@@ -756,12 +793,10 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   const int cpt = Ci / (256 / Co);
   bool queued;
   if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
-    const int blocks = wgrad_tiles_blocks(B, Ci), rows = blocks * wgt_partials_per_block(Ci);
-    float* part = rq.space((size_t)rows * nw, &queued);
-    if (Ci == 16) PPLL_TRY(wgrad_tiles_launch<16>(s, x, dy, B, H, W, part, blocks));
-    else if (Ci == 32) PPLL_TRY(wgrad_tiles_launch<32>(s, x, dy, B, H, W, part, blocks));
-    else PPLL_TRY(wgrad_tiles_launch<64>(s, x, dy, B, H, W, part, blocks));
-    return reduce_conv_filters(s, rq, queued, part, rows, Ci, Co, ci_keep, dw);
+    const int blocks = wgrad_tiles_blocks(B, Ci, Co);
+    float* part = rq.space((size_t)blocks * nw, &queued);
+    PPLL_TRY(wgrad_tiles_dispatch(s, x, dy, B, H, W, Ci, Co, stride, part, blocks));
+    return reduce_conv_filters(s, rq, queued, part, blocks, Ci, Co, ci_keep, dw);
   }
   float* partials = rq.space((size_t)chunks * nw, &queued);
   int st = PPLL_ERR_CONFIG;

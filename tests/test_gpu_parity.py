@@ -317,6 +317,13 @@ def test_resnet_bf16_tiled_weight_gradient_shapes(channels, height, width, batch
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
 
 
+def test_resnet_bf16_stride_2_weight_gradient_64_to_64():
+    # the auxiliary convolution 64 -> 64 at stride 2 on a 16 x 16 map: odd / even column planes in the tiled weight
+    # gradient, second k-split handed over through LDS
+    wl = synth.workload("resnet_stage_bf16", n_basic_blocks=1, batch=3, height=16, width=16, channels=64, aux_channels=64)
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
 def test_resnet_bf16_stem_module():
     wl = synth.resnet32_modules(8, batch=4)[0]
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
