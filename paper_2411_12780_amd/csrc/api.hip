@@ -205,7 +205,6 @@ int ppll_block_init(const ppll_block_config* cfg, void* workspace_dev, size_t wo
   if (st == PPLL_OK && b.mom2) st = launch_fill_zero(s, b.mom2, b.P * sizeof(float));
   if (st == PPLL_OK) st = launch_fill_zero(s, b.loss_dev, sizeof(float));
   if (st == PPLL_OK) st = launch_fill_zero(s, b.flag_dev, sizeof(int));
-  if (st == PPLL_OK) st = launch_fill_zero(s, b.ticket_dev, sizeof(int));
   if (st != PPLL_OK) return fail(st);
   size_t bn_total = 0;
   for (int c : b.bn_channels) bn_total += c;

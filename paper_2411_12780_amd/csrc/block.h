@@ -55,7 +55,6 @@ struct Block {
   std::vector<size_t> bn_off;
   float* loss_dev = nullptr;
   int* flag_dev = nullptr;
-  int* ticket_dev = nullptr;     // arrival counter of the last-workgroup reductions (self-resetting)
   float* partials = nullptr;
   size_t partial_floats = 0;
   ReduceQueue rq;                 // second stages of the gradient reductions, run in one launch before the update

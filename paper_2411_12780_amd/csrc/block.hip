@@ -163,7 +163,6 @@ size_t Block::plan(char* base) {
   bn_var_run = bump.floats(bn_total ? bn_total : 1);
   loss_dev = bump.floats(1);
   flag_dev = (int*)bump.take(sizeof(int));
-  ticket_dev = (int*)bump.take(sizeof(int));
   logits = bump.floats((size_t)B * C);
   dlogits = bump.floats((size_t)B * C);
 
@@ -491,7 +490,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   if (stem) {
     const int rows0 = B * in_h * in_w;
     PPLL_TRY(stem_conv_fwd(x_in, s));
-    PPLL_TRY(launch_bn_stats(s, stem_c, dt, rows0, in_c, eps, mom, partials, ticket_dev, stem_mean, stem_rstd, run_mean(0),
+    PPLL_TRY(launch_bn_stats(s, stem_c, dt, rows0, in_c, eps, mom, partials, stem_mean, stem_rstd, run_mean(0),
                              run_var(0)));
     PPLL_TRY(launch_bn_apply(s, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, params + stem_b, nullptr, stem_y));
     x = stem_y;
@@ -504,10 +503,10 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     block_in[i] = x;
     block_out[i] = i == n - 1 ? x_out : a.out;
     PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, a.c1));
-    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, d.Co, eps, mom, partials, ticket_dev, a.mean1, a.rstd1, run_mean(b1), run_var(b1)));
+    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, d.Co, eps, mom, partials, a.mean1, a.rstd1, run_mean(b1), run_var(b1)));
     PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
     PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, a.c2));
-    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, d.Co, eps, mom, partials, ticket_dev, a.mean2, a.rstd2, run_mean(b2), run_var(b2)));
+    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, d.Co, eps, mom, partials, a.mean2, a.rstd2, run_mean(b2), run_var(b2)));
     const void* skip = x;
     if (d.stride != 1 || d.Ci != d.Co) {
       PPLL_TRY(launch_shortcut_fwd(s, x, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, shortcut));
@@ -521,7 +520,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   // ---- auxiliary forward
   const int ba = bn_base + 2 * n;
   PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
-  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, ticket_dev, aux_mean, aux_rstd, run_mean(ba), run_var(ba)));
+  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, aux_mean, aux_rstd, run_mean(ba), run_var(ba)));
   PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
   PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
   GemmArgs g = gemm_args();
@@ -543,7 +542,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   g.C = dpooled; g.c_dt = dt; g.ldc = A; g.M = B; g.N = A; g.K = C;
   PPLL_TRY(launch_gemm_generic(s, g));
   PPLL_TRY(launch_gap_bwd(s, dpooled, dt, B, Ho * Wo, A, d_aux));
-  PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials, ticket_dev,
+  PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials,
                          grads + aux_bn_g, grads + aux_bn_b, d_aux));
   PPLL_TRY(launch_conv3x3_wgrad(s, x, d_aux, dt, B, H, W, Ch, A, 2, rq, grads + aux_conv_w));
   void *gcur = r_gA, *gnext = r_gB;   // gradient with respect to the output of the block in hand / of the one before it
@@ -554,11 +553,11 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     const BasicBlockDims& d = rb_d[i];
     BasicBlockActs& a = rb_a[i];
     const int rows = B * d.Ho * d.Wo;
-    PPLL_TRY(launch_bn_bwd(s, gcur, block_out[i], a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, partials, ticket_dev,
+    PPLL_TRY(launch_bn_bwd(s, gcur, block_out[i], a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, partials,
                            grads + p.bn2_g, grads + p.bn2_b, r_t2));
     PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, rq, grads + p.conv2_w));
     PPLL_TRY(launch_conv3x3_dgrad(s, r_t2, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, nullptr, nullptr, r_t1));
-    PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, partials, ticket_dev,
+    PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, partials,
                            grads + p.bn1_g, grads + p.bn1_b, r_t1));
     PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, rq, grads + p.conv1_w));
     if (i == 0 && !stem) break;   // the block input is the detached x_{j-1}
@@ -573,7 +572,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   }
   if (stem) {
     const int rows0 = B * in_h * in_w;
-    PPLL_TRY(launch_bn_bwd(s, gcur, stem_y, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, partials, ticket_dev,
+    PPLL_TRY(launch_bn_bwd(s, gcur, stem_y, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, partials,
                            grads + stem_g, grads + stem_b, r_t1));
     if (stem_pad)   // the padded image is still in place from the forward pass
       PPLL_TRY(launch_conv3x3_wgrad(s, stem_xp, r_t1, dt, B, in_h, in_w, 16, in_c, 1, rq, grads + stem_w, cfg.img_c));

@@ -212,7 +212,7 @@ int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt
                         int stride, void* dx);
 // training-mode statistics over rows of x [rows, C]; also updates running stats
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum,
-                    float* partials, int* ticket, float* mean, float* rstd, float* run_mean, float* run_var);
+                    float* partials, float* mean, float* rstd, float* run_mean, float* run_var);
 // y = relu(bn(x) (+ res))
 int launch_bn_running_stats(hipStream_t s, const float* run_mean, const float* run_var, int C, float eps, float* mean,
                             float* rstd);
@@ -220,10 +220,10 @@ int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const
                     const float* g, const float* b, const void* res, void* y);
 // dyh = dy * (y > 0); dx = bn'(dyh); dg = sum dyh*xhat; db = sum dyh
 int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
-                  const float* mean, const float* rstd, const float* g, float* partials, int* ticket, float* dg,
+                  const float* mean, const float* rstd, const float* g, float* partials, float* dg,
                   float* db, void* dx);
 int bn_partial_floats(int rows, int C);
-// bf16 fast path (k_resnet_bf16.hip); `ticket` is one zero-initialised int that the kernels reset themselves
+// bf16 fast path (k_resnet_bf16.hip)
 bool conv_bf16_supported(int dt, int wdt, int Ci, int Co, const void* a, const void* b, const void* c);
 bool conv_pixels_fit(int B, int H, int W);
 bool conv_fwd_bf16_ok(int Ci, int Co);
@@ -244,11 +244,11 @@ int launch_shortcut_bwd_bf16(hipStream_t s, const void* dy, const void* ymask, i
 bool bn_bf16_supported(int dt, int rows, int C, const void* a, const void* b, const void* c, const void* d);
 size_t bn_bf16_partial_floats(int rows, int C);
 int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
-                         int* ticket, float* mean, float* rstd, float* run_mean, float* run_var);
+                         float* mean, float* rstd, float* run_mean, float* run_var);
 int launch_bn_apply_bf16(hipStream_t s, const void* x, int rows, int C, const float* mean, const float* rstd,
                          const float* g, const float* b, const void* res, void* y);
 int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void* x, int rows, int C, const float* mean,
-                       const float* rstd, const float* g, float* partials, int* ticket, float* dg, float* db, void* dx);
+                       const float* rstd, const float* g, float* partials, float* dg, float* db, void* dx);
 int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, void* pooled);
 int launch_gap_bwd(hipStream_t s, const void* dpooled, int dt, int B, int HW, int C, void* dx);
 

@@ -324,10 +324,10 @@ int bn_partial_floats(int rows, int C) {
 }
 
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
-                    int* ticket, float* mean, float* rstd, float* run_mean, float* run_var) {
+                    float* mean, float* rstd, float* run_mean, float* run_var) {
   if (rows < 2) { set_error("batchnorm needs at least 2 rows per channel"); return PPLL_ERR_CONFIG; }
   if (bn_bf16_supported(dt, rows, C, x, nullptr, nullptr, nullptr))
-    return launch_bn_stats_bf16(s, x, rows, C, eps, momentum, partials, ticket, mean, rstd, run_mean, run_var);
+    return launch_bn_stats_bf16(s, x, rows, C, eps, momentum, partials, mean, rstd, run_mean, run_var);
   float* var = partials;            // [C], then the chunk partials
   float* part = partials + C;
   ReduceQueue now;   // no arena: both reductions finish at once (the second one reads the first one's result)
@@ -351,10 +351,10 @@ int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const
 }
 
 int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
-                  const float* mean, const float* rstd, const float* g, float* partials, int* ticket, float* dg,
+                  const float* mean, const float* rstd, const float* g, float* partials, float* dg,
                   float* db, void* dx) {
   if (bn_bf16_supported(dt, rows, C, dy, y, x, dx))
-    return launch_bn_bwd_bf16(s, dy, y, x, rows, C, mean, rstd, g, partials, ticket, dg, db, dx);
+    return launch_bn_bwd_bf16(s, dy, y, x, rows, C, mean, rstd, g, partials, dg, db, dx);
   int chunks = (rows + BN_ROWS - 1) / BN_ROWS;
   size_t total = (size_t)rows * C;
   hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3((C + 255) / 256, chunks), dim3(256), 0, s, dy, y, x, dt, rows, C, mean,

@@ -10,9 +10,9 @@
 //    pixels per workgroup, their nine shifted input vectors and dy staged in LDS and
 //    fp32 accumulators per thread; partials per workgroup, summed in a fixed order.
 //  * BatchNorm statistics / backward sums: 8 channels per thread (16-byte loads),
-//    per-workgroup partials, and the last workgroup to arrive (integer ticket)
-//    adds the partials in workgroup order and finishes mean / rstd / running
-//    stats or dgamma / dbeta: one launch, still deterministic.
+//    per-workgroup partials; a second, one-workgroup launch adds them in workgroup
+//    order and finishes mean / rstd / running stats or dgamma / dbeta (a last-arrival
+//    scheme in one launch was slower: its device-scope fences cost more than a launch).
 #include "common.h"
 
 namespace ppll {
@@ -236,20 +236,19 @@ struct BnSumArgs {
   int rows, C;
   const float* mean; const float* rstd;        // KIND 1 inputs
   float* partial;                              // [blocks][2][C]
-  int* ticket;                                 // zero before the launch; reset by the last workgroup
   float eps, momentum;
   float* out0; float* out1;                    // KIND 0: mean, rstd; KIND 1: dbeta, dgamma
   float* run_mean; float* run_var;
 };
 
 // Adds the workgroup partials [nblocks][2][C] in workgroup order and finishes mean / rstd / running
-// statistics (KIND 0) or dbeta / dgamma (KIND 1).  One workgroup of 256 threads.
-template <int KIND>
-__device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, float (*red)[17]) {
+// statistics (KIND 0) or dbeta / dgamma (KIND 1).  One workgroup of NTHR threads.
+template <int KIND, int NTHR>
+__device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, float* red) {
   const int tid = threadIdx.x;
-  // 2C values; 256/(2C) thread groups take the workgroup partials round-robin, then one thread
+  // 2C values; NTHR/(2C) thread groups take the workgroup partials round-robin, then one thread
   // per value adds the groups in order
-  const int nv = 2 * p.C, parts = 256 / nv;
+  const int nv = 2 * p.C, parts = NTHR / nv;
   if (tid < nv * parts) {
     const int v = tid % nv, part = tid / nv;
     float t = 0.f;
@@ -263,12 +262,12 @@ __device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, 
 #pragma unroll
       for (int u = 0; u < 8; ++u) t += q[u];
     }
-    red[tid][0] = t;
+    red[tid] = t;
   }
   __syncthreads();
   if (tid < p.C) {
     float s0 = 0.f, s1 = 0.f;
-    for (int part = 0; part < parts; ++part) { s0 += red[part * nv + tid][0]; s1 += red[part * nv + p.C + tid][0]; }
+    for (int part = 0; part < parts; ++part) { s0 += red[part * nv + tid]; s1 += red[part * nv + p.C + tid]; }
     if (KIND == 0) {
       const float n = (float)p.rows, m = s0 / n;
       const float var = fmaxf(s1 / n - m * m, 0.f);
@@ -283,10 +282,9 @@ __device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, 
   }
 }
 
-template <int KIND, bool TICKET>
+template <int KIND>
 __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
   __shared__ float red[256][17];
-  __shared__ int is_last;
   const int groups = p.C / 8;                   // channel groups of 8
   const int lanes = 256 / groups;               // row lanes per workgroup
   const int tid = threadIdx.x, cg = tid % groups, rl = tid / groups;
@@ -351,21 +349,12 @@ __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
     for (int l = 0; l < lanes; ++l) t += red[l * groups + g][8 * which + j];
     p.partial[(size_t)blockIdx.x * 2 * p.C + tid] = t;
   }
-  if (!TICKET) return;                        // wide launches: a one-workgroup kernel adds the partials afterwards
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) is_last = atomicAdd(p.ticket, 1) == (int)gridDim.x - 1;
-  __syncthreads();
-  if (!is_last) return;
-  __threadfence();
-  bn_finish<KIND>(p, gridDim.x, red);
-  if (tid == 0) *p.ticket = 0;
 }
 
 template <int KIND>
-__global__ __launch_bounds__(256) void bn_finish_kernel(BnSumArgs p, unsigned nblocks) {
-  __shared__ float red[256][17];
-  bn_finish<KIND>(p, nblocks, red);
+__global__ __launch_bounds__(1024) void bn_finish_kernel(BnSumArgs p, unsigned nblocks) {
+  __shared__ float red[1024];
+  bn_finish<KIND, 1024>(p, nblocks, red);
 }
 
 // y = relu(bn(x) (+ res)), 8 channels per thread
@@ -819,23 +808,16 @@ bool bn_bf16_supported(int dt, int rows, int C, const void* a, const void* b, co
   if ((size_t)rows * C / 8 >= ((size_t)1 << 32)) return false;   // the kernels index 16-byte chunks with 32 bits
   return al16(a) && al16(b) && al16(c) && al16(d);
 }
-constexpr int BN_TICKET_BLOCKS = 64;
 static int bn_blocks(int rows, int C) {
   const int lanes = 256 / (C / 8);
   int blocks = (rows + lanes * 8 - 1) / (lanes * 8);     // about eight rows per thread
-  // Up to 64 workgroups the last one to arrive adds the partials (one launch).  Taller tensors take up to 256
-  // workgroups and a second, one-workgroup launch: hundreds of device-scope fences cost more than that launch.
   return blocks < 1 ? 1 : (blocks > 256 ? 256 : blocks);
 }
 template <int KIND>
 static int bn_sums_launch(hipStream_t s, const BnSumArgs& p, int blocks) {
-  if (blocks <= BN_TICKET_BLOCKS) {
-    hipLaunchKernelGGL((bn_sums_kernel<KIND, true>), dim3(blocks), dim3(256), 0, s, p);
-  } else {
-    hipLaunchKernelGGL((bn_sums_kernel<KIND, false>), dim3(blocks), dim3(256), 0, s, p);
-    PPLL_HIP(hipGetLastError());
-    hipLaunchKernelGGL(bn_finish_kernel<KIND>, dim3(1), dim3(256), 0, s, p, (unsigned)blocks);
-  }
+  hipLaunchKernelGGL(bn_sums_kernel<KIND>, dim3(blocks), dim3(256), 0, s, p);
+  PPLL_HIP(hipGetLastError());
+  hipLaunchKernelGGL(bn_finish_kernel<KIND>, dim3(1), dim3(1024), 0, s, p, (unsigned)blocks);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
@@ -872,9 +854,9 @@ int launch_shortcut_bwd_bf16(hipStream_t s, const void* dy, const void* ymask, i
 }
 
 int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
-                         int* ticket, float* mean, float* rstd, float* run_mean, float* run_var) {
+                         float* mean, float* rstd, float* run_mean, float* run_var) {
   BnSumArgs p{};
-  p.x = (const uint16_t*)x; p.rows = rows; p.C = C; p.partial = partials; p.ticket = ticket; p.eps = eps;
+  p.x = (const uint16_t*)x; p.rows = rows; p.C = C; p.partial = partials; p.eps = eps;
   p.momentum = momentum; p.out0 = mean; p.out1 = rstd; p.run_mean = run_mean; p.run_var = run_var;
   PPLL_TRY(bn_sums_launch<0>(s, p, bn_blocks(rows, C)));
   return PPLL_OK;
@@ -890,10 +872,10 @@ int launch_bn_apply_bf16(hipStream_t s, const void* x, int rows, int C, const fl
 }
 
 int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void* x, int rows, int C, const float* mean,
-                       const float* rstd, const float* g, float* partials, int* ticket, float* dg, float* db, void* dx) {
+                       const float* rstd, const float* g, float* partials, float* dg, float* db, void* dx) {
   BnSumArgs p{};
   p.x = (const uint16_t*)x; p.dy = (const uint16_t*)dy; p.y = (const uint16_t*)y; p.rows = rows; p.C = C;
-  p.mean = mean; p.rstd = rstd; p.partial = partials; p.ticket = ticket; p.out0 = db; p.out1 = dg;
+  p.mean = mean; p.rstd = rstd; p.partial = partials; p.out0 = db; p.out1 = dg;
   PPLL_TRY(bn_sums_launch<1>(s, p, bn_blocks(rows, C)));
   const size_t chunks = (size_t)rows * C / 8;
   hipLaunchKernelGGL(bn_bwd_apply_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
