@@ -29,6 +29,7 @@ struct BasicBlockParams { size_t conv1_w, bn1_g, bn1_b, conv2_w, bn2_g, bn2_b; }
 struct BasicBlockDims { int Ci, Co, stride, Hin, Win, Ho, Wo; };
 struct BasicBlockActs {
   void *c1, *y1, *c2, *out;
+  void *d1, *d2;   // gradients at the outputs of conv1 / conv2, kept until the grouped weight-gradient launch
   float *mean1, *rstd1, *mean2, *rstd2;
 };
 
@@ -95,7 +96,7 @@ struct Block {
   size_t aux_conv_w = 0, aux_bn_g = 0, aux_bn_b = 0;
   void *aux_c = nullptr, *aux_y = nullptr, *pooled = nullptr, *dpooled = nullptr, *d_aux = nullptr;
   float *aux_mean = nullptr, *aux_rstd = nullptr;
-  void *r_gA = nullptr, *r_gB = nullptr, *r_t1 = nullptr, *r_t2 = nullptr;
+  void *r_gA = nullptr, *r_gB = nullptr, *r_t1 = nullptr;
 
   float* loss_copy = nullptr;    // caller's loss slot of the step in flight (may be null)
   // Phase timers (off by default): events at the boundaries of module forward, auxiliary forward +

@@ -239,6 +239,7 @@ size_t Block::plan(char* base) {
       if (act > widest) widest = act;
       BasicBlockActs a;
       a.c1 = bump.take(act * esz); a.y1 = bump.take(act * esz); a.c2 = bump.take(act * esz); a.out = bump.take(act * esz);
+      a.d1 = bump.take(act * esz); a.d2 = bump.take(act * esz);
       a.mean1 = bump.floats(d.Co); a.rstd1 = bump.floats(d.Co); a.mean2 = bump.floats(d.Co); a.rstd2 = bump.floats(d.Co);
       rb_a.push_back(a);
       if (d.stride != 1 || d.Ci != d.Co) shortcut = bump.take(act * esz);
@@ -249,7 +250,7 @@ size_t Block::plan(char* base) {
     aux_c = bump.take(aact * esz); aux_y = bump.take(aact * esz); d_aux = bump.take(aact * esz);
     pooled = bump.take((size_t)B * A * esz); dpooled = bump.take((size_t)B * A * esz);
     aux_mean = bump.floats(A); aux_rstd = bump.floats(A);
-    r_gA = bump.take(widest * esz); r_gB = bump.take(widest * esz); r_t1 = bump.take(widest * esz); r_t2 = bump.take(widest * esz);
+    r_gA = bump.take(widest * esz); r_gB = bump.take(widest * esz); r_t1 = bump.take(widest * esz);
     grow((size_t)conv3x3_wgrad_partial_floats(B, Hh, W, Ch, A, 2));
     grow((size_t)bn_partial_floats(B * Ho * Wo, A));
   }
@@ -547,29 +548,42 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   PPLL_TRY(launch_conv3x3_wgrad(s, x, d_aux, dt, B, H, W, Ch, A, 2, rq, grads + aux_conv_w));
   void *gcur = r_gA, *gnext = r_gB;   // gradient with respect to the output of the block in hand / of the one before it
   PPLL_TRY(launch_conv3x3_dgrad(s, d_aux, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, nullptr, nullptr, gcur));
-  // ---- backward: basic blocks, last to first; nothing is produced for x_in
+  // ---- backward: basic blocks, last to first; nothing is produced for x_in.  The weight gradients wait:
+  // those of one shape run as one launch after the loop.
+  struct Shape { int H, W, Ci, Co, stride; };
+  std::vector<Shape> shapes;
+  std::vector<std::vector<ConvWgradJob>> shape_jobs;
+  auto defer = [&](const void* xin, const void* dyp, float* dw, int Hh, int Ww, int Ci, int Co, int st) {
+    size_t k = 0;
+    while (k < shapes.size() && !(shapes[k].H == Hh && shapes[k].W == Ww && shapes[k].Ci == Ci && shapes[k].Co == Co && shapes[k].stride == st)) ++k;
+    if (k == shapes.size()) { shapes.push_back({Hh, Ww, Ci, Co, st}); shape_jobs.emplace_back(); }
+    shape_jobs[k].push_back({xin, dyp, dw});
+  };
   for (int i = n - 1; i >= 0; --i) {
     const BasicBlockParams& p = rb_p[i];
     const BasicBlockDims& d = rb_d[i];
     BasicBlockActs& a = rb_a[i];
     const int rows = B * d.Ho * d.Wo;
     PPLL_TRY(launch_bn_bwd(s, gcur, block_out[i], a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, partials,
-                           grads + p.bn2_g, grads + p.bn2_b, r_t2));
-    PPLL_TRY(launch_conv3x3_wgrad(s, a.y1, r_t2, dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, rq, grads + p.conv2_w));
-    PPLL_TRY(launch_conv3x3_dgrad(s, r_t2, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, nullptr, nullptr, r_t1));
+                           grads + p.bn2_g, grads + p.bn2_b, a.d2));
+    defer(a.y1, a.d2, grads + p.conv2_w, d.Ho, d.Wo, d.Co, d.Co, 1);
+    PPLL_TRY(launch_conv3x3_dgrad(s, a.d2, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, nullptr, nullptr, r_t1));
     PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, partials,
-                           grads + p.bn1_g, grads + p.bn1_b, r_t1));
-    PPLL_TRY(launch_conv3x3_wgrad(s, block_in[i], r_t1, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, rq, grads + p.conv1_w));
+                           grads + p.bn1_g, grads + p.bn1_b, a.d1));
+    defer(block_in[i], a.d1, grads + p.conv1_w, d.Hin, d.Win, d.Ci, d.Co, d.stride);
     if (i == 0 && !stem) break;   // the block input is the detached x_{j-1}
     if (d.stride == 1 && d.Ci == d.Co) {   // identity shortcut folded into the input gradient
-      PPLL_TRY(launch_conv3x3_dgrad(s, r_t1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, 1, gcur, block_out[i], gcur));
+      PPLL_TRY(launch_conv3x3_dgrad(s, a.d1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, 1, gcur, block_out[i], gcur));
     } else {
-      PPLL_TRY(launch_conv3x3_dgrad(s, r_t1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, nullptr, nullptr,
+      PPLL_TRY(launch_conv3x3_dgrad(s, a.d1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, nullptr, nullptr,
                                     gnext));
       PPLL_TRY(launch_shortcut_bwd(s, gcur, block_out[i], dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, gnext));
       std::swap(gcur, gnext);
     }
   }
+  for (size_t k = 0; k < shapes.size(); ++k)
+    PPLL_TRY(launch_conv3x3_wgrad_group(s, shape_jobs[k].data(), (int)shape_jobs[k].size(), dt, B, shapes[k].H, shapes[k].W,
+                                        shapes[k].Ci, shapes[k].Co, shapes[k].stride, rq));
   if (stem) {
     const int rows0 = B * in_h * in_w;
     PPLL_TRY(launch_bn_bwd(s, gcur, stem_y, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, partials,

@@ -198,6 +198,13 @@ int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, 
 // the caller padded x with zero channels)
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, ReduceQueue& rq, float* dw, int ci_keep = -1);
+// weight gradients of n convolutions of one shape (x [B,H,W,Ci], dy [B,Ho,Wo,Co] each): one launch where the
+// matrix-core kernel takes the shape, else one launch per convolution
+struct ConvWgradJob { const void* x; const void* dy; float* dw; };
+int launch_conv3x3_wgrad_group(hipStream_t s, const ConvWgradJob* jobs, int n, int dt, int B, int H, int W, int Ci, int Co,
+                               int stride, ReduceQueue& rq);
+int launch_conv3x3_wgrad_group_bf16(hipStream_t s, const ConvWgradJob* jobs, int n, int B, int H, int W, int Ci, int Co,
+                                    int stride, ReduceQueue& rq, bool* done);
 // second stage of a convolution weight gradient: adds `rows` partial filters [9][Ci][Co] into dw [9][keep][Co]
 int reduce_conv_filters(hipStream_t s, ReduceQueue& rq, bool queued, const float* partials, int rows, int Ci, int Co,
                         int keep, float* dw);

@@ -316,6 +316,19 @@ int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, i
   return reduce_conv_filters(s, rq, queued, partials, chunks, Ci, Co, ci_keep, dw);
 }
 
+int launch_conv3x3_wgrad_group(hipStream_t s, const ConvWgradJob* jobs, int n, int dt, int B, int H, int W, int Ci, int Co,
+                               int stride, ReduceQueue& rq) {
+  bool fast = conv_wgrad_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W);
+  for (int j = 0; j < n && fast; ++j) fast = conv_bf16_supported(dt, BF16, Ci, Co, jobs[j].x, jobs[j].dy, jobs[j].dw);
+  if (fast && n > 1) {
+    bool done = false;
+    PPLL_TRY(launch_conv3x3_wgrad_group_bf16(s, jobs, n, B, H, W, Ci, Co, stride, rq, &done));
+    if (done) return PPLL_OK;
+  }
+  for (int j = 0; j < n; ++j) PPLL_TRY(launch_conv3x3_wgrad(s, jobs[j].x, jobs[j].dy, dt, B, H, W, Ci, Co, stride, rq, jobs[j].dw));
+  return PPLL_OK;
+}
+
 int bn_partial_floats(int rows, int C) {
   int a = colsum_partial_floats(rows, C), b = ((rows + BN_ROWS - 1) / BN_ROWS) * 2 * C;
   int c = (C % 8 == 0 && C >= 8 && C <= 128 && 256 % (C / 8) == 0) ? (int)bn_bf16_partial_floats(rows, C) : 0;

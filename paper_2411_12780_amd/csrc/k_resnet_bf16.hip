@@ -573,10 +573,15 @@ __device__ __forceinline__ uint2 wgt_gather4(const uint4& p0, const uint4& p1, c
   return o;
 }
 
+// up to 16 convolutions of one shape in a launch: blockIdx.y picks the convolution
+constexpr int WGT_GROUP = 16;
+struct WgtGroup { const uint16_t* x[WGT_GROUP]; const uint16_t* dy[WGT_GROUP]; float* partial[WGT_GROUP]; };
+
 template <int CI, int CO, int S>
-__global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(const uint16_t* __restrict__ x,
-                                                                            const uint16_t* __restrict__ dy, int B, int H,
-                                                                            int W, float* __restrict__ partial) {
+__global__ __launch_bounds__(64 * WGT_WAVES) void conv3x3_wgrad_tiles_kernel(WgtGroup grp, int B, int H, int W) {
+  const uint16_t* __restrict__ x = grp.x[blockIdx.y];
+  const uint16_t* __restrict__ dy = grp.dy[blockIdx.y];
+  float* __restrict__ partial = grp.partial[blockIdx.y];
   constexpr int CT = CI / 16, WN = CO / 16, WK = WGT_WAVES / WN, NT = 64 * WGT_WAVES, NW = 9 * CI * CO;
   constexpr bool FOLD_ALL = WK * NW * 4 <= WGT_FOLD_BYTES;
   static_assert(FOLD_ALL || WK == 2, "the k-splits either fit LDS together or are two");
@@ -729,27 +734,26 @@ static int wgrad_tiles_blocks(int B, int Ci, int Co) {
   return B < cap ? B : (int)cap;
 }
 template <int CI, int CO, int S>
-static int wgrad_tiles_launch(hipStream_t s, const void* x, const void* dy, int B, int H, int W, float* partials, int blocks) {
+static int wgrad_tiles_launch(hipStream_t s, const WgtGroup& g, int n, int B, int H, int W, int blocks) {
   const size_t lds = wgrad_tiles_lds(H, W, CI, CO, S);
   if (lds > 64 * 1024)
     PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_wgrad_tiles_kernel<CI, CO, S>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                  (int)lds));
-  hipLaunchKernelGGL((conv3x3_wgrad_tiles_kernel<CI, CO, S>), dim3(blocks), dim3(64 * WGT_WAVES), lds, s, (const uint16_t*)x,
-                     (const uint16_t*)dy, B, H, W, partials);
+  hipLaunchKernelGGL((conv3x3_wgrad_tiles_kernel<CI, CO, S>), dim3(blocks, n), dim3(64 * WGT_WAVES), lds, s, g, B, H, W);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
-static int wgrad_tiles_dispatch(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co, int stride,
-                                float* part, int blocks) {
+static int wgrad_tiles_dispatch(hipStream_t s, const WgtGroup& g, int n, int B, int H, int W, int Ci, int Co, int stride,
+                                int blocks) {
   if (stride == 1) {
-    if (Ci == 16) return wgrad_tiles_launch<16, 16, 1>(s, x, dy, B, H, W, part, blocks);
-    if (Ci == 32) return wgrad_tiles_launch<32, 32, 1>(s, x, dy, B, H, W, part, blocks);
-    return wgrad_tiles_launch<64, 64, 1>(s, x, dy, B, H, W, part, blocks);
+    if (Ci == 16) return wgrad_tiles_launch<16, 16, 1>(s, g, n, B, H, W, blocks);
+    if (Ci == 32) return wgrad_tiles_launch<32, 32, 1>(s, g, n, B, H, W, blocks);
+    return wgrad_tiles_launch<64, 64, 1>(s, g, n, B, H, W, blocks);
   }
-  if (Ci == 16 && Co == 32) return wgrad_tiles_launch<16, 32, 2>(s, x, dy, B, H, W, part, blocks);
-  if (Ci == 16 && Co == 64) return wgrad_tiles_launch<16, 64, 2>(s, x, dy, B, H, W, part, blocks);
-  if (Ci == 32 && Co == 64) return wgrad_tiles_launch<32, 64, 2>(s, x, dy, B, H, W, part, blocks);
-  return wgrad_tiles_launch<64, 64, 2>(s, x, dy, B, H, W, part, blocks);
+  if (Ci == 16 && Co == 32) return wgrad_tiles_launch<16, 32, 2>(s, g, n, B, H, W, blocks);
+  if (Ci == 16 && Co == 64) return wgrad_tiles_launch<16, 64, 2>(s, g, n, B, H, W, blocks);
+  if (Ci == 32 && Co == 64) return wgrad_tiles_launch<32, 64, 2>(s, g, n, B, H, W, blocks);
+  return wgrad_tiles_launch<64, 64, 2>(s, g, n, B, H, W, blocks);
 }
 
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride) {
@@ -784,7 +788,9 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
     const int blocks = wgrad_tiles_blocks(B, Ci, Co);
     float* part = rq.space((size_t)blocks * nw, &queued);
-    PPLL_TRY(wgrad_tiles_dispatch(s, x, dy, B, H, W, Ci, Co, stride, part, blocks));
+    WgtGroup g{};
+    g.x[0] = (const uint16_t*)x; g.dy[0] = (const uint16_t*)dy; g.partial[0] = part;
+    PPLL_TRY(wgrad_tiles_dispatch(s, g, 1, B, H, W, Ci, Co, stride, blocks));
     return reduce_conv_filters(s, rq, queued, part, blocks, Ci, Co, ci_keep, dw);
   }
   float* partials = rq.space((size_t)chunks * nw, &queued);
@@ -801,6 +807,31 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   else set_error("conv3x3 weight gradient: no kernel for %d -> %d channels", Ci, Co);
   PPLL_TRY(st);
   return reduce_conv_filters(s, rq, queued, partials, chunks, Ci, Co, ci_keep, dw);
+}
+
+// Weight gradients of n convolutions of one shape in as few launches as possible (16 per launch).  Returns
+// PPLL_OK with *done = false, having launched nothing, when the shape is not one the tiled kernel takes or the
+// queue has no private room left for all partial sums (the caller then launches them one by one).
+int launch_conv3x3_wgrad_group_bf16(hipStream_t s, const ConvWgradJob* jobs, int n, int B, int H, int W, int Ci, int Co,
+                                    int stride, ReduceQueue& rq, bool* done) {
+  *done = false;
+  if (!wgrad_tiles_ok(H, W, Ci, Co, stride)) return PPLL_OK;
+  const int blocks = wgrad_tiles_blocks(B, Ci, Co), nw = 9 * Ci * Co;
+  const size_t need = ((size_t)blocks * nw + 63) & ~(size_t)63;
+  if (!rq.arena || rq.used + need * n > rq.arena_floats) return PPLL_OK;
+  for (int j0 = 0; j0 < n; j0 += WGT_GROUP) {
+    const int m = n - j0 < WGT_GROUP ? n - j0 : WGT_GROUP;
+    WgtGroup g{};
+    for (int j = 0; j < m; ++j) {
+      bool queued;
+      g.x[j] = (const uint16_t*)jobs[j0 + j].x; g.dy[j] = (const uint16_t*)jobs[j0 + j].dy;
+      g.partial[j] = rq.space((size_t)blocks * nw, &queued);     // queued: room was checked above
+    }
+    PPLL_TRY(wgrad_tiles_dispatch(s, g, m, B, H, W, Ci, Co, stride, blocks));
+    for (int j = 0; j < m; ++j) PPLL_TRY(reduce_conv_filters(s, rq, true, g.partial[j], blocks, Ci, Co, Ci, jobs[j0 + j].dw));
+  }
+  *done = true;
+  return PPLL_OK;
 }
 
 bool bn_bf16_supported(int dt, int rows, int C, const void* a, const void* b, const void* c, const void* d) {
