@@ -727,10 +727,13 @@ static bool wgrad_tiles_ok(int H, int W, int Ci, int Co, int stride) {
   const int Wo = W / stride;
   return Wo >= 8 && (Wo % 8) == 0 && wgrad_tiles_lds(H, W, Ci, Co, stride) <= 160 * 1024;
 }
-// workgroups: one per image up to the number that keeps the partial sums near 32 MiB
-static int wgrad_tiles_blocks(int B, int Ci, int Co) {
+// workgroups per convolution: one per image up to the number that keeps the partial sums near 32 MiB; a launch
+// of n convolutions needs about 1024 workgroups in all, not that many each (fewer partial sums to add up)
+static int wgrad_tiles_blocks(int B, int Ci, int Co, int n = 1) {
   long cap = ((long)32 << 20) / ((long)9 * Ci * Co * 4);
   cap = cap < 32 ? 32 : (cap > 256 ? 256 : cap);
+  const long share = (1024 + n - 1) / n;
+  if (n > 1 && share < cap) cap = share < 32 ? 32 : share;
   return B < cap ? B : (int)cap;
 }
 template <int CI, int CO, int S>
@@ -816,7 +819,7 @@ int launch_conv3x3_wgrad_group_bf16(hipStream_t s, const ConvWgradJob* jobs, int
                                     int stride, ReduceQueue& rq, bool* done) {
   *done = false;
   if (!wgrad_tiles_ok(H, W, Ci, Co, stride)) return PPLL_OK;
-  const int blocks = wgrad_tiles_blocks(B, Ci, Co), nw = 9 * Ci * Co;
+  const int blocks = wgrad_tiles_blocks(B, Ci, Co, n < WGT_GROUP ? n : WGT_GROUP), nw = 9 * Ci * Co;
   const size_t need = ((size_t)blocks * nw + 63) & ~(size_t)63;
   if (!rq.arena || rq.used + need * n > rq.arena_floats) return PPLL_OK;
   for (int j0 = 0; j0 < n; j0 += WGT_GROUP) {
