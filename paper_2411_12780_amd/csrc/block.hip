@@ -252,6 +252,7 @@ size_t Block::plan(char* base) {
     aux_mean = bump.floats(A); aux_rstd = bump.floats(A);
     r_gA = bump.take(widest * esz); r_gB = bump.take(widest * esz); r_t1 = bump.take(widest * esz);
     grow((size_t)conv3x3_wgrad_partial_floats(B, Hh, W, Ch, A, 2));
+    grow(vit_head_partial_floats(B, A, C));
     grow((size_t)bn_partial_floats(B * Ho * Wo, A));
   }
   size_t o = (size_t)colsum_partial_floats(B, C);
@@ -275,7 +276,8 @@ size_t Block::plan(char* base) {
   }
   if (cfg.arch == PPLL_RESNET) {   // the weight-gradient partials of every convolution
     const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
-    arena_floats = (size_t)conv3x3_wgrad_partial_floats(cfg.batch, Hh, W, Ch, A, 2) + 64;
+    arena_floats = (size_t)conv3x3_wgrad_partial_floats(cfg.batch, Hh, W, Ch, A, 2) + 64 +
+                   vit_head_partial_floats(cfg.batch, A, cfg.num_classes) + 256;
     for (const BasicBlockDims& d : rb_d)
       arena_floats += (size_t)conv3x3_wgrad_partial_floats(cfg.batch, d.Hin, d.Win, d.Ci, d.Co, d.stride) +
                       (size_t)conv3x3_wgrad_partial_floats(cfg.batch, d.Ho, d.Wo, d.Co, d.Co, 1) + 128;
@@ -524,24 +526,32 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, aux_mean, aux_rstd, run_mean(ba), run_var(ba)));
   PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
   PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
-  GemmArgs g = gemm_args();
-  g.A = pooled; g.a_dt = dt; g.a_sm = A; g.a_sk = 1;
-  g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
-  g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = A; g.bias = params + head_b;
-  PPLL_TRY(launch_gemm_generic(s, g));
-  PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, loss_copy, dlogits, grads + head_b, flag_dev));
-  PPLL_TRY(mark_phase(2, s));   // auxiliary forward and loss done
-  // ---- backward: head and auxiliary net
-  g = gemm_args();
-  g.A = pooled; g.a_dt = dt; g.a_sm = 1; g.a_sk = A;
-  g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
-  g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = A; g.N = C; g.K = B;
-  PPLL_TRY(launch_gemm_generic(s, g));
-  g = gemm_args();
-  g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
-  g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
-  g.C = dpooled; g.c_dt = dt; g.ldc = A; g.M = B; g.N = A; g.K = C;
-  PPLL_TRY(launch_gemm_generic(s, g));
+  if (vit_head_fused_ok(A, C)) {
+    // ---- Linear head, local loss and the head's backward in one launch (the fused head without a LayerNorm)
+    PPLL_TRY(launch_vit_head(s, pooled, dt, (long)A, B, A, C, nullptr, nullptr, 0.f, params + head_w, params + head_b, labels,
+                             dpooled, rq, nullptr, nullptr, grads + head_w, grads + head_b, loss_dev, loss_copy, flag_dev));
+    PPLL_TRY(mark_phase(2, s));   // auxiliary forward and loss done
+  } else {
+    GemmArgs g = gemm_args();
+    g.A = pooled; g.a_dt = dt; g.a_sm = A; g.a_sk = 1;
+    g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+    g.C = logits; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = A; g.bias = params + head_b;
+    PPLL_TRY(launch_gemm_generic(s, g));
+    PPLL_TRY(launch_cross_entropy(s, logits, labels, B, C, loss_dev, loss_copy, dlogits, grads + head_b, flag_dev));
+    PPLL_TRY(mark_phase(2, s));   // auxiliary forward and loss done
+    // ---- backward: head
+    g = gemm_args();
+    g.A = pooled; g.a_dt = dt; g.a_sm = 1; g.a_sk = A;
+    g.B = dlogits; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
+    g.C = grads + head_w; g.c_dt = F32; g.ldc = C; g.M = A; g.N = C; g.K = B;
+    PPLL_TRY(launch_gemm_generic(s, g));
+    g = gemm_args();
+    g.A = dlogits; g.a_dt = F32; g.a_sm = C; g.a_sk = 1;
+    g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
+    g.C = dpooled; g.c_dt = dt; g.ldc = A; g.M = B; g.N = A; g.K = C;
+    PPLL_TRY(launch_gemm_generic(s, g));
+  }
+  // ---- backward: auxiliary net
   PPLL_TRY(launch_gap_bwd(s, dpooled, dt, B, Ho * Wo, A, d_aux));
   PPLL_TRY(launch_bn_bwd(s, d_aux, aux_y, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, partials,
                          grads + aux_bn_g, grads + aux_bn_b, d_aux));

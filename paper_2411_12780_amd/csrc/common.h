@@ -245,6 +245,8 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
 bool eltwise_bf16_ok(int dt, size_t elems, int C0, int C1, const void* a, const void* b, const void* c);
 int launch_gap_bwd_bf16(hipStream_t s, const void* dpooled, int B, int HW, int C, void* dx);
+bool gap_fwd_bf16_ok(int dt, int C, const void* x, const void* pooled);
+int launch_gap_fwd_bf16(hipStream_t s, const void* x, int B, int HW, int C, void* pooled);
 int launch_shortcut_fwd_bf16(hipStream_t s, const void* x, int B, int H, int W, int Ci, int Co, int stride, void* y);
 int launch_shortcut_bwd_bf16(hipStream_t s, const void* dy, const void* ymask, int B, int H, int W, int Ci, int Co, int stride,
                              void* dx);

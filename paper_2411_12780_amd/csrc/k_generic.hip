@@ -644,10 +644,12 @@ int launch_cross_entropy(hipStream_t s, const float* logits, const int32_t* labe
   return PPLL_OK;
 }
 
-// ===================================================================== ViT auxiliary head, fused
+// ===================================================================== auxiliary head, fused
 namespace {
 // LayerNorm of the class token, Linear to the classes, mean softmax cross-entropy, and everything
-// back to the gradient of the class token, for 4 batch rows per workgroup (one wave each).  Values
+// back to the gradient of the class token, for 4 batch rows per workgroup (one wave each).  Without
+// LayerNorm parameters (ln_g null) the rows go to the Linear layer as they are: the ResNet head on
+// the pooled features.  Values
 // that the unfused kernels keep in the activation type (z = LN output, dz) are rounded to it here as
 // well.  What has to be summed over the batch (loss, head weight / bias gradient, LayerNorm scale /
 // shift gradient) leaves as one partial row per workgroup: [D*C | C | D | D | 1] floats.
@@ -672,21 +674,25 @@ __global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, lo
   }
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int b = blockIdx.x * HEAD_ROWS + wave;
-  const bool live = b < B;
+  const bool live = b < B, ln = ln_g != nullptr;
   float* xr = xh + wave * D; float* zr = zs + wave * D; float* dzr = dzs + wave * D; float* lr = dl + wave * C;
   float rs = 0.f;
   if (live) {
     const size_t base = (size_t)b * xs;
-    float s = 0.f;
-    for (int d = lane; d < D; d += 64) { const float v = ld_f(x, base + d, dt); xr[d] = v; s += v; }
-    const float mu = wave_sum(s) / D;
-    float q = 0.f;
-    for (int d = lane; d < D; d += 64) { const float c = xr[d] - mu; q += c * c; }
-    rs = rsqrtf(wave_sum(q) / D + eps);
-    for (int d = lane; d < D; d += 64) {
-      const float h = (xr[d] - mu) * rs;
-      xr[d] = h;
-      zr[d] = round_to(h * ln_g[d] + ln_b[d], dt);
+    if (ln) {
+      float s = 0.f;
+      for (int d = lane; d < D; d += 64) { const float v = ld_f(x, base + d, dt); xr[d] = v; s += v; }
+      const float mu = wave_sum(s) / D;
+      float q = 0.f;
+      for (int d = lane; d < D; d += 64) { const float c = xr[d] - mu; q += c * c; }
+      rs = rsqrtf(wave_sum(q) / D + eps);
+      for (int d = lane; d < D; d += 64) {
+        const float h = (xr[d] - mu) * rs;
+        xr[d] = h;
+        zr[d] = round_to(h * ln_g[d] + ln_b[d], dt);
+      }
+    } else {
+      for (int d = lane; d < D; d += 64) { const float v = ld_f(x, base + d, dt); xr[d] = 0.f; zr[d] = v; }
     }
     wave_sync();
     for (int c = 0; c < C; ++c) {
@@ -716,12 +722,18 @@ __global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, lo
       for (int c = 0; c < C; ++c) a += lr[c] * W[(size_t)d * C + c];
       a = round_to(a, dt);
       dzr[d] = a;
-      const float dyh = a * ln_g[d];
-      s1 += dyh; s2 += dyh * xr[d];
+      if (ln) {
+        const float dyh = a * ln_g[d];
+        s1 += dyh; s2 += dyh * xr[d];
+      } else {
+        st_f(dcls, (size_t)b * D + d, a, dt);
+      }
     }
-    s1 = wave_sum(s1) / D; s2 = wave_sum(s2) / D;
-    for (int d = lane; d < D; d += 64)
-      st_f(dcls, (size_t)b * D + d, rs * (dzr[d] * ln_g[d] - s1 - xr[d] * s2), dt);
+    if (ln) {
+      s1 = wave_sum(s1) / D; s2 = wave_sum(s2) / D;
+      for (int d = lane; d < D; d += 64)
+        st_f(dcls, (size_t)b * D + d, rs * (dzr[d] * ln_g[d] - s1 - xr[d] * s2), dt);
+    }
   } else {
     for (int d = lane; d < D; d += 64) { xr[d] = 0.f; zr[d] = 0.f; dzr[d] = 0.f; }
     for (int c = lane; c < C; c += 64) lr[c] = 0.f;
@@ -776,8 +788,10 @@ int launch_vit_head(hipStream_t s, const void* x, int dt, long xs, int B, int D,
   PPLL_HIP(hipGetLastError());
   PPLL_TRY(rq.reduce(s, queued, partials, chunks, D * C, P, 1.0f, dW));
   PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C, chunks, C, P, 1.0f, dbias));
-  PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C, chunks, D, P, 1.0f, d_ln_g));
-  PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C + D, chunks, D, P, 1.0f, d_ln_b));
+  if (ln_g) {
+    PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C, chunks, D, P, 1.0f, d_ln_g));
+    PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C + D, chunks, D, P, 1.0f, d_ln_b));
+  }
   PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C + 2 * D, chunks, 1, P, 1.0f / B, loss));
   if (loss2) PPLL_TRY(rq.reduce(s, queued, partials + (size_t)D * C + C + 2 * D, chunks, 1, P, 1.0f / B, loss2));
   return PPLL_OK;

@@ -400,6 +400,7 @@ int launch_bn_running_stats(hipStream_t s, const float* run_mean, const float* r
 }
 
 int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, void* pooled) {
+  if (gap_fwd_bf16_ok(dt, C, x, pooled)) return launch_gap_fwd_bf16(s, x, B, HW, C, pooled);
   if (C <= 256 && 256 % C == 0)
     hipLaunchKernelGGL(gap_fwd_image_kernel, dim3(B), dim3(256), 0, s, x, dt, HW, C, pooled);
   else

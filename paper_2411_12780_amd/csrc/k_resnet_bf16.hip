@@ -430,6 +430,39 @@ __global__ __launch_bounds__(256) void gap_bwd_bf16_kernel(const uint16_t* dpool
   *reinterpret_cast<uint4*>(dx + (size_t)i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
+// pooled[b, c] = mean over the HW pixels of x[b, p, c]: one workgroup per image, thread (channel group of 8, pixel
+// lane); the pixel lanes are added in order
+__global__ __launch_bounds__(256) void gap_fwd_bf16_kernel(const uint16_t* x, int HW, int C, uint16_t* pooled) {
+  __shared__ float red[256][9];
+  const int groups = C / 8, lanes = 256 / groups, cg = threadIdx.x % groups, pl = threadIdx.x / groups;
+  const uint16_t* xb = x + (size_t)blockIdx.x * HW * C + 8 * cg;
+  float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (pl < lanes)
+    for (int p0 = pl; p0 < HW; p0 += 4 * lanes) {     // four loads in flight
+      uint4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int pp = p0 + u * lanes;
+        v[u] = pp < HW ? *reinterpret_cast<const uint4*>(xb + (size_t)pp * C) : make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t* w = reinterpret_cast<const uint32_t*>(&v[u]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { a[2 * j] += lo_bf(w[j]); a[2 * j + 1] += hi_bf(w[j]); }
+      }
+    }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) red[threadIdx.x][j] = a[j];
+  __syncthreads();
+  if (threadIdx.x < C) {
+    const int g = threadIdx.x / 8, j = threadIdx.x % 8;
+    float t = 0.f;
+    for (int l = 0; l < lanes; ++l) t += red[l * groups + g][j];
+    pooled[(size_t)blockIdx.x * C + threadIdx.x] = f32_to_bf16(t / HW);
+  }
+}
+
 // y[b,oy,ox,c] = x[b, oy*stride, ox*stride, c] for c < Ci, 0 above
 __global__ __launch_bounds__(256) void shortcut_fwd_bf16_kernel(const uint16_t* x, uint32_t H, uint32_t W, uint32_t Ci,
                                                                 uint32_t Co, uint32_t stride, uint32_t Ho, uint32_t Wo,
@@ -860,6 +893,15 @@ size_t bn_bf16_partial_floats(int rows, int C) { return (size_t)bn_blocks(rows, 
 // The three helpers need channel counts that are multiples of 8, 16-byte aligned tensors and fewer than 2^31 elements.
 bool eltwise_bf16_ok(int dt, size_t elems, int C0, int C1, const void* a, const void* b, const void* c) {
   return dt == BF16 && (C0 % 8) == 0 && (C1 % 8) == 0 && elems < ((size_t)1 << 31) && al16(a) && al16(b) && al16(c);
+}
+// C a multiple of 8 that divides 256 * 8 into whole pixel lanes, at most 256 channels
+bool gap_fwd_bf16_ok(int dt, int C, const void* x, const void* pooled) {
+  return dt == BF16 && (C % 8) == 0 && C >= 8 && C <= 256 && (256 % (C / 8)) == 0 && al16(x) && !(((uintptr_t)pooled) & 1);
+}
+int launch_gap_fwd_bf16(hipStream_t s, const void* x, int B, int HW, int C, void* pooled) {
+  hipLaunchKernelGGL(gap_fwd_bf16_kernel, dim3(B), dim3(256), 0, s, (const uint16_t*)x, HW, C, (uint16_t*)pooled);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
 }
 int launch_gap_bwd_bf16(hipStream_t s, const void* dpooled, int B, int HW, int C, void* dx) {
   const uint32_t chunks = (uint32_t)((size_t)B * HW * C / 8);
