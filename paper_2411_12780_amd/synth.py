@@ -104,6 +104,14 @@ def resnet32_modules(k: int, **overrides) -> list:
     return out
 
 
+def cosine_lr(step: int, total_steps: int, lr0: float = 0.01) -> float:
+    """Learning rate of call `step` (0-based) under cosine annealing from lr0 to 0 over total_steps calls
+    (Section 4.1: initial rate 0.01, cosine schedule).  The library takes the rate per call; the schedule
+    lives on the host."""
+    import math
+    return 0.5 * lr0 * (1.0 + math.cos(math.pi * step / total_steps))
+
+
 def aux_depth_schedule(d_max: int, n_blocks: int = 12, n: int = 3) -> list:
     """Depth of the auxiliary network of local block l (0-based) of a ViT cut into n_blocks local
     blocks: N_l = d' - floor(l / n) with n = 3 (Section 4.2, the auxiliary-depth heuristic), d' the

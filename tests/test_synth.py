@@ -64,3 +64,14 @@ def test_resnet32_partitions_outside_the_supported_range_are_refused():
             synth.resnet32_modules(k)
     with pytest.raises(ValueError):
         synth.resnet32_modules(1)     # one module would hold both downsampling blocks
+
+
+def test_cosine_schedule_endpoints_midpoint_and_symmetry():
+    T = 400
+    assert synth.cosine_lr(0, T) == 0.01
+    assert abs(synth.cosine_lr(T // 2, T) - 0.005) < 1e-15
+    assert abs(synth.cosine_lr(T, T)) < 1e-15
+    rates = [synth.cosine_lr(t, T) for t in range(T + 1)]
+    assert all(a > b for a, b in zip(rates, rates[1:]))
+    # lr(t) + lr(T - t) = lr0: the curve is point-symmetric about its midpoint
+    assert all(abs(rates[t] + rates[T - t] - 0.01) < 1e-15 for t in range(T + 1))
