@@ -26,6 +26,15 @@ __device__ __forceinline__ float hi_bf(uint32_t w) { return __uint_as_float(w & 
 __device__ __forceinline__ uint32_t pack2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 __device__ __forceinline__ int out_dim(int in, int stride) { return (in - 1) / stride + 1; }
 
+// Raw buffer access: a load whose byte offset lies beyond the buffer returns 0, so a tap outside the image needs
+// no branch, only the offset CONV_OOB (buffers here stay below 2^30 bytes, checked by the launcher).
+typedef __attribute__((ext_vector_type(4))) uint32_t conv_u32x4;
+constexpr int CONV_OOB = 0x7fffffff;
+__device__ __forceinline__ uint4 conv_buf_load16(__amdgpu_buffer_rsrc_t r, int off) {
+  const conv_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 struct ConvArgs {
   const uint16_t* src;     // forward: x [B,H,W,Ci]; input gradient: dy [B,Ho,Wo,Co]
   const uint16_t* w;       // [9][Ci][Co]
@@ -38,7 +47,9 @@ struct ConvArgs {
 // MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = 16 * K16 channels reduced.
 // GRP: how many of a pixel's nine tap loads are issued before the first product waits for one
 // (0: one, 1: the three of a filter row, 3: all nine; a filter row measured best).
-template <int MODE, int K16, int NT, int GRP>
+// LIN (forward, and input gradient at stride 1): a tap's source is the centre pixel's plus a constant,
+// so a tap costs one offset addition and one select between that offset and "out of range".
+template <int MODE, int K16, int NT, int GRP, bool LIN>
 __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   extern __shared__ __align__(16) char wl[];        // [NO rounded up to 32][9*KC] bf16, row stride RSW bytes
   constexpr int KC = 16 * K16;
@@ -78,6 +89,8 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   const int SH = MODE == 0 ? p.H : Ho, SW = MODE == 0 ? p.W : Wo;      // source spatial size
   const long P = (long)p.B * OH * OW, ntiles = (P + 127) / 128;
   // NT = tiles of 32 produced channels (NO = 16: the upper half of the one tile is never stored)
+  const __amdgpu_buffer_rsrc_t rsrc =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.src), 0, (int)((long)p.B * SH * SW * KC * 2), 0x00020000);
   // the workgroup keeps its filter for several tiles of 128 pixels
   for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     // 32-bit index arithmetic (the launcher checks that the pixel count fits): 64-bit division costs more than the tile
@@ -91,28 +104,45 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
     constexpr int NG = GRP == 0 ? 9 : (GRP == 1 ? 3 : 1), TG = 9 / NG;   // groups of taps whose loads are in flight together
-#pragma unroll 1
-    for (int grp = 0; grp < NG; ++grp) {
+    // LIN: centre source pixel (cy, cx); tap (ky, kx) reads (cy + sg (ky-1), cx + sg (kx-1)), sg = +1 forward, -1 gradient
+    const int sg = MODE == 0 ? 1 : -1;
+    const int cy = MODE == 0 ? oy * p.stride : oy, cx = MODE == 0 ? ox * p.stride : ox;
+    const int base = (((b * SH + cy) * SW + cx) * KC + 8 * hh) * 2;
+    bool rowok[3], colok[3];
+#pragma unroll
+    for (int d = 0; d < 3; ++d) {
+      rowok[d] = live && (unsigned)(cy + sg * (d - 1)) < (unsigned)SH;
+      colok[d] = (unsigned)(cx + sg * (d - 1)) < (unsigned)SW;
+    }
+    auto tap_group = [&](const int grp) {
       uint4 xv[TG][K16];
 #pragma unroll
       for (int j = 0; j < TG; ++j) {
         const int tap = grp * TG + j, ky = tap / 3, kx = tap % 3;
-        int sy, sx;
-        bool ok = live;
-        if (MODE == 0) {
-          sy = oy * p.stride + ky - 1; sx = ox * p.stride + kx - 1;
-        } else {
-          // stride is 1 or 2 (checked by the launcher): mask and shift instead of a division per tap
-          const int ty = oy + 1 - ky, tx = ox + 1 - kx, sm1 = p.stride - 1;
-          ok = ok && ty >= 0 && tx >= 0 && !((ty | tx) & sm1);
-          sy = ty >> sm1; sx = tx >> sm1;
-        }
-        ok = ok && sy >= 0 && sy < SH && sx >= 0 && sx < SW;
-        const uint16_t* sp = p.src + (((long)b * SH + sy) * SW + sx) * KC + 8 * hh;
+        if (LIN) {
+          // ky is uniform (GRP = 1: ky = grp, kx = j): the row test is picked with scalar selects
+          const bool ok = (ky == 0 ? rowok[0] : (ky == 1 ? rowok[1] : rowok[2])) && (kx == 0 ? colok[0] : (kx == 1 ? colok[1] : colok[2]));
+          const int off = base + sg * (((ky - 1) * SW + (kx - 1)) * KC * 2);
 #pragma unroll
-        for (int c16 = 0; c16 < K16; ++c16) {
-          xv[j][c16] = make_uint4(0, 0, 0, 0);
-          if (ok) xv[j][c16] = *reinterpret_cast<const uint4*>(sp + 16 * c16);
+          for (int c16 = 0; c16 < K16; ++c16) xv[j][c16] = conv_buf_load16(rsrc, ok ? off + 32 * c16 : CONV_OOB);
+        } else {
+          int sy, sx;
+          bool ok = live;
+          if (MODE == 0) {
+            sy = oy * p.stride + ky - 1; sx = ox * p.stride + kx - 1;
+          } else {
+            // stride is 1 or 2 (checked by the launcher): mask and shift instead of a division per tap
+            const int ty = oy + 1 - ky, tx = ox + 1 - kx, sm1 = p.stride - 1;
+            ok = ok && ty >= 0 && tx >= 0 && !((ty | tx) & sm1);
+            sy = ty >> sm1; sx = tx >> sm1;
+          }
+          ok = ok && sy >= 0 && sy < SH && sx >= 0 && sx < SW;
+          const uint16_t* sp = p.src + (((long)b * SH + sy) * SW + sx) * KC + 8 * hh;
+#pragma unroll
+          for (int c16 = 0; c16 < K16; ++c16) {
+            xv[j][c16] = make_uint4(0, 0, 0, 0);
+            if (ok) xv[j][c16] = *reinterpret_cast<const uint4*>(sp + 16 * c16);
+          }
         }
       }
 #pragma unroll
@@ -129,6 +159,16 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
           }
         }
       }
+    };
+    // 16 reduced channels: straight-line over the tap groups (a rolled loop makes the compiler carry the accumulators
+    // in ordinary registers and copy them to the MFMA's accumulation registers and back on every trip); with more
+    // reduced channels the straight-line form costs too many registers and the rolled loop measured faster
+    if constexpr (K16 == 1) {
+#pragma unroll
+      for (int grp = 0; grp < NG; ++grp) tap_group(grp);
+    } else {
+#pragma unroll 1
+      for (int grp = 0; grp < NG; ++grp) tap_group(grp);
     }
     if (!live) continue;
     // acc[t][4q+e] = out[pix][32t + 8q + 4hh + e]
@@ -503,14 +543,14 @@ bool al16(const void* p) { return !(((uintptr_t)p) & 15); }
 // LDS of the implicit-GEMM convolution: the filter as [produced channels rounded up to 32][9 * reduced + 8] bf16
 size_t conv_mfma_lds(int produced, int reduced) { return (size_t)((produced + 31) / 32 * 32) * (18 * reduced + 16); }
 constexpr size_t CONV_MFMA_LDS_MAX = 96 * 1024;
-template <int MODE, int K16, int NT, int GRP>
+template <int MODE, int K16, int NT, int GRP, bool LIN>
 int conv_mfma_launch_g(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   static bool raised[64] = {};    // per device: the attribute belongs to the device's copy of the kernel
   if (lds > 64 * 1024) {
     int dev = 0;
     PPLL_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64 || !raised[dev]) {
-      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE, K16, NT, GRP>, hipFuncAttributeMaxDynamicSharedMemorySize,
+      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE, K16, NT, GRP, LIN>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    (int)CONV_MFMA_LDS_MAX));
       if (dev >= 0 && dev < 64) raised[dev] = true;
     }
@@ -518,7 +558,7 @@ int conv_mfma_launch_g(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   // a workgroup keeps its filter for up to 4 tiles of 128 pixels once there are more than 2048 of them
   const long ntiles = (P + 127) / 128;
   const long tpw = ntiles >= 8192 ? 4 : (ntiles >= 4096 ? 2 : 1);
-  hipLaunchKernelGGL((conv3x3_mfma_kernel<MODE, K16, NT, GRP>), dim3((unsigned)((ntiles + tpw - 1) / tpw)), dim3(256), lds, s, p);
+  hipLaunchKernelGGL((conv3x3_mfma_kernel<MODE, K16, NT, GRP, LIN>), dim3((unsigned)((ntiles + tpw - 1) / tpw)), dim3(256), lds, s, p);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
@@ -526,8 +566,12 @@ template <int MODE, int K16>
 int conv_mfma_launch_k(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   const int produced = MODE == 0 ? p.Co : p.Ci;
   // GRP = 1: the three taps of a filter row in flight together
-  if (produced <= 32) return conv_mfma_launch_g<MODE, K16, 1, 1>(s, p, P, lds);
-  return conv_mfma_launch_g<MODE, K16, 2, 1>(s, p, P, lds);
+  // linear tap addressing through a buffer descriptor: forward always, input gradient at stride 1; the source
+  // tensor has to stay below 2^30 bytes
+  const bool lin = (MODE == 0 || p.stride == 1) && (long)p.B * p.H * p.W * (16 * K16) * 2 < ((long)1 << 30);
+  if (produced <= 32)
+    return lin ? conv_mfma_launch_g<MODE, K16, 1, 1, true>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 1, 1, false>(s, p, P, lds);
+  return lin ? conv_mfma_launch_g<MODE, K16, 2, 1, true>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 2, 1, false>(s, p, P, lds);
 }
 // k16 = reduced channels / 16: 1, 2, 3 or 4
 template <int MODE>
