@@ -493,9 +493,8 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   if (stem) {
     const int rows0 = B * in_h * in_w;
     PPLL_TRY(stem_conv_fwd(x_in, s));
-    PPLL_TRY(launch_bn_stats(s, stem_c, dt, rows0, in_c, eps, mom, partials, stem_mean, stem_rstd, run_mean(0),
-                             run_var(0)));
-    PPLL_TRY(launch_bn_apply(s, stem_c, dt, rows0, in_c, stem_mean, stem_rstd, params + stem_g, params + stem_b, nullptr, stem_y));
+    PPLL_TRY(launch_bn_train_fwd(s, stem_c, dt, rows0, in_c, eps, mom, partials, stem_mean, stem_rstd, run_mean(0), run_var(0),
+                                 params + stem_g, params + stem_b, nullptr, stem_y));
     x = stem_y;
   }
   for (int i = 0; i < n; ++i) {
@@ -506,16 +505,16 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     block_in[i] = x;
     block_out[i] = i == n - 1 ? x_out : a.out;
     PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, a.c1));
-    PPLL_TRY(launch_bn_stats(s, a.c1, dt, rows, d.Co, eps, mom, partials, a.mean1, a.rstd1, run_mean(b1), run_var(b1)));
-    PPLL_TRY(launch_bn_apply(s, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
+    PPLL_TRY(launch_bn_train_fwd(s, a.c1, dt, rows, d.Co, eps, mom, partials, a.mean1, a.rstd1, run_mean(b1), run_var(b1),
+                                 params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
     PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, a.c2));
-    PPLL_TRY(launch_bn_stats(s, a.c2, dt, rows, d.Co, eps, mom, partials, a.mean2, a.rstd2, run_mean(b2), run_var(b2)));
     const void* skip = x;
     if (d.stride != 1 || d.Ci != d.Co) {
       PPLL_TRY(launch_shortcut_fwd(s, x, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, shortcut));
       skip = shortcut;
     }
-    PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, skip, block_out[i]));
+    PPLL_TRY(launch_bn_train_fwd(s, a.c2, dt, rows, d.Co, eps, mom, partials, a.mean2, a.rstd2, run_mean(b2), run_var(b2),
+                                 params + p.bn2_g, params + p.bn2_b, skip, block_out[i]));
     x = block_out[i];
   }
   PPLL_TRY(mark_phase(1, s));   // module forward done
@@ -523,8 +522,8 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   // ---- auxiliary forward
   const int ba = bn_base + 2 * n;
   PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
-  PPLL_TRY(launch_bn_stats(s, aux_c, dt, arows, A, eps, mom, partials, aux_mean, aux_rstd, run_mean(ba), run_var(ba)));
-  PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
+  PPLL_TRY(launch_bn_train_fwd(s, aux_c, dt, arows, A, eps, mom, partials, aux_mean, aux_rstd, run_mean(ba), run_var(ba),
+                               params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
   PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
   if (vit_head_fused_ok(A, C)) {
     // ---- Linear head, local loss and the head's backward in one launch (the fused head without a LayerNorm)

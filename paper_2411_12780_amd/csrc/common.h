@@ -220,6 +220,10 @@ int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt
 // training-mode statistics over rows of x [rows, C]; also updates running stats
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum,
                     float* partials, float* mean, float* rstd, float* run_mean, float* run_var);
+// statistics of x, running-statistics update and y = relu(bn(x) (+ res)): the BatchNorm of a training step
+int launch_bn_train_fwd(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
+                        float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
+                        const void* res, void* y);
 // y = relu(bn(x) (+ res))
 int launch_bn_running_stats(hipStream_t s, const float* run_mean, const float* run_var, int C, float eps, float* mean,
                             float* rstd);
@@ -254,6 +258,9 @@ bool bn_bf16_supported(int dt, int rows, int C, const void* a, const void* b, co
 size_t bn_bf16_partial_floats(int rows, int C);
 int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
                          float* mean, float* rstd, float* run_mean, float* run_var);
+int launch_bn_train_fwd_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
+                             float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
+                             const void* res, void* y);
 int launch_bn_apply_bf16(hipStream_t s, const void* x, int rows, int C, const float* mean, const float* rstd,
                          const float* g, const float* b, const void* res, void* y);
 int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void* x, int rows, int C, const float* mean,

@@ -353,6 +353,15 @@ int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float
   return PPLL_OK;
 }
 
+int launch_bn_train_fwd(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
+                        float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
+                        const void* res, void* y) {
+  if (rows >= 2 && bn_bf16_supported(dt, rows, C, x, res, y, nullptr))
+    return launch_bn_train_fwd_bf16(s, x, rows, C, eps, momentum, partials, mean, rstd, run_mean, run_var, g, b, res, y);
+  PPLL_TRY(launch_bn_stats(s, x, dt, rows, C, eps, momentum, partials, mean, rstd, run_mean, run_var));
+  return launch_bn_apply(s, x, dt, rows, C, mean, rstd, g, b, res, y);
+}
+
 int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const float* mean, const float* rstd,
                     const float* g, const float* b, const void* res, void* y) {
   if (bn_bf16_supported(dt, rows, C, x, res, y, nullptr))

@@ -283,8 +283,10 @@ struct BnSumArgs {
 
 // Adds the workgroup partials [nblocks][2][C] in workgroup order and finishes mean / rstd / running
 // statistics (KIND 0) or dbeta / dgamma (KIND 1).  One workgroup of NTHR threads.
+// l0 / l1 (LDS, may be null) also receive the two results per channel; `global` says whether this
+// workgroup writes them (and the running statistics) to memory.
 template <int KIND, int NTHR>
-__device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, float* red) {
+__device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, float* red, float* l0, float* l1, bool global) {
   const int tid = threadIdx.x;
   // 2C values; NTHR/(2C) thread groups take the workgroup partials round-robin, then one thread
   // per value adds the groups in order
@@ -308,17 +310,19 @@ __device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, 
   if (tid < p.C) {
     float s0 = 0.f, s1 = 0.f;
     for (int part = 0; part < parts; ++part) { s0 += red[part * nv + tid]; s1 += red[part * nv + p.C + tid]; }
+    float v0 = s0, v1 = s1;
     if (KIND == 0) {
       const float n = (float)p.rows, m = s0 / n;
       const float var = fmaxf(s1 / n - m * m, 0.f);
-      p.out0[tid] = m;
-      p.out1[tid] = 1.0f / sqrtf(var + p.eps);
-      p.run_mean[tid] = (1.f - p.momentum) * p.run_mean[tid] + p.momentum * m;
-      p.run_var[tid] = (1.f - p.momentum) * p.run_var[tid] + p.momentum * var * (n / (n - 1.f));
-    } else {
-      p.out0[tid] = s0;
-      p.out1[tid] = s1;
+      v0 = m;
+      v1 = 1.0f / sqrtf(var + p.eps);
+      if (global) {
+        p.run_mean[tid] = (1.f - p.momentum) * p.run_mean[tid] + p.momentum * m;
+        p.run_var[tid] = (1.f - p.momentum) * p.run_var[tid] + p.momentum * var * (n / (n - 1.f));
+      }
     }
+    if (global) { p.out0[tid] = v0; p.out1[tid] = v1; }
+    if (l0) { l0[tid] = v0; l1[tid] = v1; }
   }
 }
 
@@ -394,7 +398,7 @@ __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
 template <int KIND>
 __global__ __launch_bounds__(1024) void bn_finish_kernel(BnSumArgs p, unsigned nblocks) {
   __shared__ float red[1024];
-  bn_finish<KIND, 1024>(p, nblocks, red);
+  bn_finish<KIND, 1024>(p, nblocks, red, nullptr, nullptr, true);
 }
 
 // y = relu(bn(x) (+ res)), 8 channels per thread
@@ -448,6 +452,65 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_bf16_kernel(const uint16_t* 
       const float xx = h ? hi_bf(xw[j]) : lo_bf(xw[j]);
       const float d = yy > 0.f ? dd : 0.f, xh = (xx - mean[c]) * rstd[c];
       r[h] = g[c] * rstd[c] / n * (n * d - db[c] - xh * dg[c]);
+    }
+    o[j] = pack2(r[0], r[1]);
+  }
+  *reinterpret_cast<uint4*>(dx + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+// Small tensors: the apply kernels add up the partial sums themselves (every workgroup, in the same order;
+// workgroup 0 writes the results to memory), which saves the finishing launch.
+__global__ __launch_bounds__(256) void bn_apply_fused_kernel(BnSumArgs p, unsigned nblocks, size_t chunks, const float* g,
+                                                             const float* b, const uint16_t* res, uint16_t* y) {
+  __shared__ float red[256], s_mean[128], s_rstd[128];
+  bn_finish<0, 256>(p, nblocks, red, s_mean, s_rstd, blockIdx.x == 0);
+  __syncthreads();
+  const uint32_t i32 = blockIdx.x * 256 + threadIdx.x;
+  if (i32 >= chunks) return;
+  const size_t i = i32;
+  const int c0 = (int)(8 * (i32 % (uint32_t)(p.C / 8)));
+  const uint4 xv = *reinterpret_cast<const uint4*>(p.x + i * 8);
+  const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
+  uint4 rv = make_uint4(0, 0, 0, 0);
+  if (res) rv = *reinterpret_cast<const uint4*>(res + i * 8);
+  const uint32_t* rw = reinterpret_cast<const uint32_t*>(&rv);
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int c = c0 + 2 * j;
+    float u = (lo_bf(xw[j]) - s_mean[c]) * s_rstd[c] * g[c] + b[c] + lo_bf(rw[j]);
+    float v = (hi_bf(xw[j]) - s_mean[c + 1]) * s_rstd[c + 1] * g[c + 1] + b[c + 1] + hi_bf(rw[j]);
+    o[j] = pack2(fmaxf(u, 0.f), fmaxf(v, 0.f));
+  }
+  *reinterpret_cast<uint4*>(y + i * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+}
+__global__ __launch_bounds__(256) void bn_bwd_apply_fused_kernel(BnSumArgs p, unsigned nblocks, size_t chunks, const float* g,
+                                                                 uint16_t* dx) {
+  __shared__ float red[256], s_db[128], s_dg[128];
+  bn_finish<1, 256>(p, nblocks, red, s_db, s_dg, blockIdx.x == 0);
+  __syncthreads();
+  const uint32_t i32 = blockIdx.x * 256 + threadIdx.x;
+  if (i32 >= chunks) return;
+  const size_t i = i32;
+  const int c0 = (int)(8 * (i32 % (uint32_t)(p.C / 8)));
+  const uint4 xv = *reinterpret_cast<const uint4*>(p.x + i * 8);
+  const uint4 dv = *reinterpret_cast<const uint4*>(p.dy + i * 8);
+  const uint4 yv = *reinterpret_cast<const uint4*>(p.y + i * 8);
+  const uint32_t* xw = reinterpret_cast<const uint32_t*>(&xv);
+  const uint32_t* dw = reinterpret_cast<const uint32_t*>(&dv);
+  const uint32_t* yw = reinterpret_cast<const uint32_t*>(&yv);
+  const float n = (float)p.rows;
+  uint32_t o[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    float r[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int c = c0 + 2 * j + h;
+      const float yy = h ? hi_bf(yw[j]) : lo_bf(yw[j]), dd = h ? hi_bf(dw[j]) : lo_bf(dw[j]);
+      const float xx = h ? hi_bf(xw[j]) : lo_bf(xw[j]);
+      const float d = yy > 0.f ? dd : 0.f, xh = (xx - p.mean[c]) * p.rstd[c];
+      r[h] = g[c] * p.rstd[c] / n * (n * d - s_db[c] - xh * s_dg[c]);
     }
     o[j] = pack2(r[0], r[1]);
   }
@@ -925,13 +988,17 @@ static int bn_blocks(int rows, int C) {
   return blocks < 1 ? 1 : (blocks > 256 ? 256 : blocks);
 }
 template <int KIND>
-static int bn_sums_launch(hipStream_t s, const BnSumArgs& p, int blocks) {
+static int bn_sums_launch(hipStream_t s, const BnSumArgs& p, int blocks, bool finish) {
   hipLaunchKernelGGL(bn_sums_kernel<KIND>, dim3(blocks), dim3(256), 0, s, p);
   PPLL_HIP(hipGetLastError());
-  hipLaunchKernelGGL(bn_finish_kernel<KIND>, dim3(1), dim3(1024), 0, s, p, (unsigned)blocks);
-  PPLL_HIP(hipGetLastError());
+  if (finish) {
+    hipLaunchKernelGGL(bn_finish_kernel<KIND>, dim3(1), dim3(1024), 0, s, p, (unsigned)blocks);
+    PPLL_HIP(hipGetLastError());
+  }
   return PPLL_OK;
 }
+// the apply kernel of a small tensor (at most 1024 workgroups) finishes the sums itself
+static bool bn_fused_finish(size_t chunks) { return (chunks + 255) / 256 <= 1024; }
 size_t bn_bf16_partial_floats(int rows, int C) { return (size_t)bn_blocks(rows, C) * 2 * C; }
 
 // The three helpers need channel counts that are multiples of 8, 16-byte aligned tensors and fewer than 2^31 elements.
@@ -978,7 +1045,27 @@ int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float ep
   BnSumArgs p{};
   p.x = (const uint16_t*)x; p.rows = rows; p.C = C; p.partial = partials; p.eps = eps;
   p.momentum = momentum; p.out0 = mean; p.out1 = rstd; p.run_mean = run_mean; p.run_var = run_var;
-  PPLL_TRY(bn_sums_launch<0>(s, p, bn_blocks(rows, C)));
+  PPLL_TRY(bn_sums_launch<0>(s, p, bn_blocks(rows, C), true));
+  return PPLL_OK;
+}
+
+// statistics and y = relu(bn(x) (+ res)) of a training step
+int launch_bn_train_fwd_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
+                             float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
+                             const void* res, void* y) {
+  BnSumArgs p{};
+  p.x = (const uint16_t*)x; p.rows = rows; p.C = C; p.partial = partials; p.eps = eps;
+  p.momentum = momentum; p.out0 = mean; p.out1 = rstd; p.run_mean = run_mean; p.run_var = run_var;
+  const size_t chunks = (size_t)rows * C / 8;
+  const int blocks = bn_blocks(rows, C);
+  if (!bn_fused_finish(chunks)) {
+    PPLL_TRY(bn_sums_launch<0>(s, p, blocks, true));
+    return launch_bn_apply_bf16(s, x, rows, C, mean, rstd, g, b, res, y);
+  }
+  PPLL_TRY(bn_sums_launch<0>(s, p, blocks, false));
+  hipLaunchKernelGGL(bn_apply_fused_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, p, (unsigned)blocks, chunks,
+                     g, b, (const uint16_t*)res, (uint16_t*)y);
+  PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
 
@@ -996,8 +1083,16 @@ int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void*
   BnSumArgs p{};
   p.x = (const uint16_t*)x; p.dy = (const uint16_t*)dy; p.y = (const uint16_t*)y; p.rows = rows; p.C = C;
   p.mean = mean; p.rstd = rstd; p.partial = partials; p.out0 = db; p.out1 = dg;
-  PPLL_TRY(bn_sums_launch<1>(s, p, bn_blocks(rows, C)));
   const size_t chunks = (size_t)rows * C / 8;
+  const int blocks = bn_blocks(rows, C);
+  if (bn_fused_finish(chunks)) {
+    PPLL_TRY(bn_sums_launch<1>(s, p, blocks, false));
+    hipLaunchKernelGGL(bn_bwd_apply_fused_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, p, (unsigned)blocks,
+                       chunks, g, (uint16_t*)dx);
+    PPLL_HIP(hipGetLastError());
+    return PPLL_OK;
+  }
+  PPLL_TRY(bn_sums_launch<1>(s, p, blocks, true));
   hipLaunchKernelGGL(bn_bwd_apply_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
                      (const uint16_t*)dy, (const uint16_t*)y, (const uint16_t*)x, chunks, C, rows, mean, rstd, g, dg, db,
                      (uint16_t*)dx);
