@@ -258,9 +258,11 @@ def main() -> int:
         # second pass over the same workload with every GEMM launch bracketed by HIP events
         P.ppll_profile_enable(True)
         P.ppll_profile_read()
+        P.ppll_profile_read_conv()
         run(args.steps)
         torch.cuda.synchronize()
         gemm_ms, gemm_flops, launches = P.ppll_profile_read()
+        conv_ms, conv_bytes, conv_launches = P.ppll_profile_read_conv()
         P.ppll_profile_enable(False)
         if launches > 0:
             achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
@@ -272,6 +274,16 @@ def main() -> int:
                                "avg_launch_us": 1e3 * gemm_ms / launches,
                                "gemm_ms_per_step": gemm_ms / args.steps,
                                "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
+
+        elif conv_launches > 0:
+            # ResNet blocks: the dominant kernel is the 3x3 convolution (forward + input gradient), bound by HBM
+            gbs = conv_bytes / (conv_ms * 1e-3) / 1e9
+            out["roofline"] = {"bound": "hbm", "kernel": "conv3x3_mfma_kernel (forward and input gradient)",
+                               "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
+                               "traffic": None, "launches_per_step": conv_launches / args.steps,
+                               "avg_launch_us": 1e3 * conv_ms / conv_launches,
+                               "conv_ms_per_step": conv_ms / args.steps,
+                               "algorithmic_bytes_per_launch": conv_bytes / conv_launches}
 
     if not args.no_roofline:
         # third pass: phase times of the step in the paper's symbols (Section 3.3)

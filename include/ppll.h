@@ -201,6 +201,10 @@ int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
  * add host and stream overhead: time whole steps with profiling off. */
 int ppll_profile_enable(int32_t on);
 int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
+/* The same for the bf16 matrix-core convolution kernel (forward and input gradient of the ResNet
+ * blocks): summed duration, algorithmic bytes (input tensor + output tensor + filter once each, plus the
+ * two tensors of the fused shortcut gradient where present) and launch count since the previous read. */
+int ppll_profile_read_conv(double* conv_ms, double* conv_bytes, int64_t* conv_launches);
 
 /* Phase timers in the symbols of the paper's time model (Section 3.3: S_PPLL = f_1 + f_a1 + B_a1 +
  * U_a1): with timers on, every step of the block records HIP events on its stream at the ends of

@@ -85,6 +85,7 @@ _SIGS = {
     "ppll_block_phase_times": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
     "ppll_profile_enable": (C.c_int, [C.c_int32]),
     "ppll_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "ppll_profile_read_conv": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -271,6 +272,13 @@ def ppll_profile_read():
     ms, fl, n = C.c_double(0), C.c_double(0), C.c_int64(0)
     _check(lib().ppll_profile_read(C.byref(ms), C.byref(fl), C.byref(n)))
     return ms.value, fl.value, n.value
+
+
+def ppll_profile_read_conv():
+    """(milliseconds, algorithmic bytes, launches) of the convolution launches bracketed since the last read."""
+    ms, by, n = C.c_double(0), C.c_double(0), C.c_int64(0)
+    _check(lib().ppll_profile_read_conv(C.byref(ms), C.byref(by), C.byref(n)))
+    return ms.value, by.value, n.value
 
 
 def ppll_probe_copy(src, dst, nbytes: int, stream=None) -> None:

@@ -126,11 +126,32 @@ int ppll_probe_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_
 
 int ppll_profile_enable(int32_t on) { profile_enable(on != 0); return PPLL_OK; }
 
-int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches) {
-  long long n = 0;
-  PPLL_TRY(profile_read(gemm_ms, gemm_flops, &n));
-  if (gemm_launches) *gemm_launches = n;
+// One read drains both kinds; the other kind's figures are kept for its own read call.
+namespace {
+double g_read_ms[2] = {0, 0}, g_read_units[2] = {0, 0};
+long long g_read_n[2] = {0, 0};
+int profile_drain() {
+  double ms[2], units[2];
+  long long n[2];
+  PPLL_TRY(profile_read(ms, units, n));
+  for (int k = 0; k < 2; ++k) { g_read_ms[k] += ms[k]; g_read_units[k] += units[k]; g_read_n[k] += n[k]; }
   return PPLL_OK;
+}
+int profile_take(int kind, double* ms, double* units, int64_t* launches) {
+  PPLL_TRY(profile_drain());
+  if (ms) *ms = g_read_ms[kind];
+  if (units) *units = g_read_units[kind];
+  if (launches) *launches = g_read_n[kind];
+  g_read_ms[kind] = 0; g_read_units[kind] = 0; g_read_n[kind] = 0;
+  return PPLL_OK;
+}
+}  // namespace
+
+int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches) {
+  return profile_take(0, gemm_ms, gemm_flops, gemm_launches);
+}
+int ppll_profile_read_conv(double* conv_ms, double* conv_bytes, int64_t* conv_launches) {
+  return profile_take(1, conv_ms, conv_bytes, conv_launches);
 }
 
 int ppll_block_workspace_bytes(const ppll_block_config* cfg, size_t* bytes) {

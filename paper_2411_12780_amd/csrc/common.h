@@ -101,9 +101,10 @@ int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n);   // eve
 // A set of independent products; one launch when all of them are groupable, else one by one.
 int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n);
 void profile_enable(bool on);
-int profile_begin(hipStream_t s, double flops, void** token);   // event pair around one launch (profiling only)
+// event pair around one launch (profiling only); kind 0: GEMM, units = flops; kind 1: convolution, units = bytes
+int profile_begin(hipStream_t s, double units, void** token, int kind = 0);
 int profile_end(hipStream_t s, void* token);
-int profile_read(double* ms, double* flops, long long* launches);
+int profile_read(double ms[2], double units[2], long long launches[2]);   // index = kind
 int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out);
 
 // Second stage of the two-stage (ordered, atomic-free) reductions.  A first-stage kernel asks for

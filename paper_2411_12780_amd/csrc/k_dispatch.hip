@@ -8,7 +8,7 @@
 namespace ppll {
 
 namespace {
-struct TimedLaunch { hipEvent_t a, b; double flops; };
+struct TimedLaunch { hipEvent_t a, b; double units; int kind; };   // kind 0: GEMM (units = flops), 1: convolution (units = bytes)
 bool g_profile = false;
 std::vector<TimedLaunch> g_timed;
 std::vector<hipEvent_t> g_pool;
@@ -23,28 +23,25 @@ hipEvent_t pooled_event() {
 
 void profile_enable(bool on) { g_profile = on; }
 
-// Sums the elapsed time of every bracketed launch since the last read.
-int profile_read(double* ms, double* flops, long long* launches) {
-  double t = 0.0, f = 0.0;
+// Sums the elapsed time of every bracketed launch since the last read, per kind (0: GEMM, 1: convolution).
+int profile_read(double ms[2], double units[2], long long launches[2]) {
+  for (int k = 0; k < 2; ++k) { ms[k] = 0.0; units[k] = 0.0; launches[k] = 0; }
   for (TimedLaunch& l : g_timed) {
     PPLL_HIP(hipEventSynchronize(l.b));
     float dt = 0.f;
     PPLL_HIP(hipEventElapsedTime(&dt, l.a, l.b));
-    t += dt; f += l.flops;
+    ms[l.kind] += dt; units[l.kind] += l.units; ++launches[l.kind];
     g_pool.push_back(l.a); g_pool.push_back(l.b);
   }
-  if (ms) *ms = t;
-  if (flops) *flops = f;
-  if (launches) *launches = (long long)g_timed.size();
   g_timed.clear();
   return PPLL_OK;
 }
 
 // Brackets one kernel launch with a pair of events when profiling is on.
-int profile_begin(hipStream_t s, double flops, void** token) {
+int profile_begin(hipStream_t s, double units, void** token, int kind) {
   *token = nullptr;
   if (!g_profile) return PPLL_OK;
-  TimedLaunch tl{pooled_event(), pooled_event(), flops};
+  TimedLaunch tl{pooled_event(), pooled_event(), units, kind};
   if (!tl.a || !tl.b) { set_error("hipEventCreate failed"); return PPLL_ERR_HIP; }
   PPLL_HIP(hipEventRecord(tl.a, s));
   g_timed.push_back(tl);

@@ -663,7 +663,10 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
   ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr};
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   const size_t lds = conv_mfma_lds(Co, Ci);
-  return conv_mfma_launch<0>(s, p, P, Ci / 16, lds);
+  void* prof = nullptr;   // algorithmic bytes: input, output and filter once
+  PPLL_TRY(profile_begin(s, 2.0 * ((double)B * H * W * Ci + (double)P * Co + 9.0 * Ci * Co), &prof, 1));
+  PPLL_TRY((conv_mfma_launch<0>(s, p, P, Ci / 16, lds)));
+  return profile_end(s, prof);
 }
 
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
@@ -672,7 +675,11 @@ int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int 
              (const uint16_t*)ymask};
   const long P = (long)B * H * W;
   const size_t lds = conv_mfma_lds(Ci, Co);
-  return conv_mfma_launch<1>(s, p, P, Co / 16, lds);
+  const double Po = (double)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+  void* prof = nullptr;   // algorithmic bytes: dy, dx and filter once, plus the shortcut gradient and its mask
+  PPLL_TRY(profile_begin(s, 2.0 * (Po * Co + (double)P * Ci * (dres ? 3.0 : 1.0) + 9.0 * Ci * Co), &prof, 1));
+  PPLL_TRY((conv_mfma_launch<1>(s, p, P, Co / 16, lds)));
+  return profile_end(s, prof);
 }
 
 // forward and input gradient produce up to 64 channels (two MFMA tiles of 32; 16 and 48 leave half a tile idle)
