@@ -653,9 +653,9 @@ namespace {
 // that the unfused kernels keep in the activation type (z = LN output, dz) are rounded to it here as
 // well.  What has to be summed over the batch (loss, head weight / bias gradient, LayerNorm scale /
 // shift gradient) leaves as one partial row per workgroup: [D*C | C | D | D | 1] floats.
-constexpr int HEAD_ROWS = 4;
+constexpr int HEAD_ROWS = 4, HEAD_THREADS = 64 * HEAD_ROWS;   // 1 and 2 rows per workgroup measured slower (more partial rows)
 __device__ __forceinline__ float round_to(float v, int dt) { return dt == BF16 ? bf16_to_f32(f32_to_bf16(v)) : v; }
-__global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, long xs, int B, int D, int C,
+__global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, int dt, long xs, int B, int D, int C,
                                                        const float* ln_g, const float* ln_b, float eps,
                                                        const float* W, const float* bias, const int32_t* labels,
                                                        void* dcls, float* partial, int* flag, int w_in_lds) {
@@ -668,7 +668,7 @@ __global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, lo
   // the head weight, read 2 C times per row, comes from LDS when there is room for it
   if (w_in_lds) {
     float* wl = lossw + HEAD_ROWS;
-    for (int i = threadIdx.x; i < D * C; i += 256) wl[i] = W[i];
+    for (int i = threadIdx.x; i < D * C; i += HEAD_THREADS) wl[i] = W[i];
     __syncthreads();
     W = wl;
   }
@@ -741,7 +741,7 @@ __global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, lo
   }
   __syncthreads();
   float* out = partial + (size_t)blockIdx.x * ((size_t)D * C + C + 2 * D + 1);
-  for (int i = threadIdx.x; i < D * C; i += 256) {
+  for (int i = threadIdx.x; i < D * C; i += HEAD_THREADS) {
     const int d = i / C, c = i % C;
     float t = 0.f;
 #pragma unroll
@@ -749,20 +749,25 @@ __global__ __launch_bounds__(256) void vit_head_kernel(const void* x, int dt, lo
     out[i] = t;
   }
   float* o2 = out + (size_t)D * C;
-  for (int c = threadIdx.x; c < C; c += 256) {
+  for (int c = threadIdx.x; c < C; c += HEAD_THREADS) {
     float t = 0.f;
 #pragma unroll
     for (int w = 0; w < HEAD_ROWS; ++w) t += dl[w * C + c];
     o2[c] = t;
   }
   float* o3 = o2 + C;
-  for (int d = threadIdx.x; d < D; d += 256) {
+  for (int d = threadIdx.x; d < D; d += HEAD_THREADS) {
     float tg = 0.f, tb = 0.f;
 #pragma unroll
     for (int w = 0; w < HEAD_ROWS; ++w) { tg += dzs[w * D + d] * xh[w * D + d]; tb += dzs[w * D + d]; }
     o3[d] = tg; o3[D + d] = tb;
   }
-  if (threadIdx.x == 0) o3[2 * D] = lossw[0] + lossw[1] + lossw[2] + lossw[3];
+  if (threadIdx.x == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int w = 0; w < HEAD_ROWS; ++w) t += lossw[w];
+    o3[2 * D] = t;
+  }
 }
 }  // namespace
 
@@ -783,7 +788,7 @@ int launch_vit_head(hipStream_t s, const void* x, int dt, long xs, int B, int D,
   bool queued;
   float* partials = rq.space((size_t)chunks * P, &queued);
   const bool with_w = vit_head_lds(D, C, true) <= 64 * 1024;
-  hipLaunchKernelGGL(vit_head_kernel, dim3(chunks), dim3(256), vit_head_lds(D, C, with_w), s, x, dt, xs, B, D, C, ln_g, ln_b,
+  hipLaunchKernelGGL(vit_head_kernel, dim3(chunks), dim3(HEAD_THREADS), vit_head_lds(D, C, with_w), s, x, dt, xs, B, D, C, ln_g, ln_b,
                      eps, W, bias, labels, dcls, partials, flag, (int)with_w);
   PPLL_HIP(hipGetLastError());
   PPLL_TRY(rq.reduce(s, queued, partials, chunks, D * C, P, 1.0f, dW));
