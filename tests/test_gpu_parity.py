@@ -448,6 +448,62 @@ def test_phase_timers_split_a_step_into_the_papers_four_terms():
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("name,kw", [
+    ("vit_stage_bf16", dict(batch=16)),
+    ("resnet_stage_bf16", dict(batch=16, n_basic_blocks=2)),
+    ("resnet32_stage1_bf16", dict(batch=8, n_basic_blocks=1)),
+])
+def test_two_runs_from_the_same_state_are_bit_identical(name, kw):
+    """Every reduction on the path is ordered (two-stage partial sums, no floating-point atomics): the same
+    inputs give the same bits, run after run, which is what lets the pipeline tests demand equality."""
+    from gpu_harness import GpuBlock
+    from paper_2411_12780_amd import binding as P
+    wl = synth.workload(name, **kw)
+    flat = synth.make_params(O.param_spec(oracle_cfg(wl)), seed=21, jitter=True)
+    runs = []
+    for _ in range(2):
+        gb = GpuBlock(wl, flat)
+        outs = []
+        for i in range(3):
+            x, y = synth.make_batch(wl, seed=21, index=i)
+            out, loss = gb.step(x, y, float(wl["lr"]))
+            outs.append((out.copy(), loss))
+        runs.append((outs, [P.ppll_block_read_tensor(gb.h, P.T_PARAM, i) for i in range(len(gb.names))]))
+        gb.close()
+    for (oa, la), (ob, lb) in zip(runs[0][0], runs[1][0]):
+        assert la == lb and np.array_equal(oa, ob)
+    for a, b in zip(runs[0][1], runs[1][1]):
+        assert np.array_equal(a, b)
+
+
+def test_zero_learning_rate_leaves_parameters_alone_but_not_the_moments():
+    from gpu_harness import GpuBlock
+    from paper_2411_12780_amd import binding as P
+    for wl in (synth.workload("vit_stage_bf16", batch=4, weight_decay=0.0), synth.workload("resnet_stage_bf16", batch=4, n_basic_blocks=1)):
+        flat = synth.make_params(O.param_spec(oracle_cfg(wl)), seed=5, jitter=True)
+        gb = GpuBlock(wl, flat)
+        before = [P.ppll_block_read_tensor(gb.h, P.T_PARAM, i) for i in range(len(gb.names))]
+        x, y = synth.make_batch(wl, seed=5)
+        gb.step(x, y, 0.0)
+        after = [P.ppll_block_read_tensor(gb.h, P.T_PARAM, i) for i in range(len(gb.names))]
+        for a, b in zip(before, after):
+            assert np.array_equal(a, b)
+        m1 = [P.ppll_block_read_tensor(gb.h, P.T_MOMENT1, i) for i in range(len(gb.names))]
+        assert any(np.abs(m).max() > 0 for m in m1)
+        gb.close()
+
+
+def test_resnet_downsampling_block_as_the_last_of_the_module_and_batch_of_one():
+    # the module's output comes straight out of the downsampling block; one image still gives BatchNorm its rows
+    wl = synth.workload("resnet_stage_bf16", precision=synth.FP32, batch=1, channels=8, height=4, width=6, n_basic_blocks=2,
+                        transition_block=2, aux_channels=8)
+    run_case(wl, steps=2, check_bn=True)
+
+
+def test_vit_batch_of_one():
+    run_case(synth.workload("vit_stage_bf16", batch=1, depth=1, aux_depth=1), steps=1)
+
+
 def test_launch_brackets_count_the_contraction_kernels_and_their_work():
     """The measurement aid behind bench.py's roofline: with brackets on, a ViT step reports its matrix-core GEMM
     launches with 2 M N K flops each, a ResNet step its convolution launches with their algorithmic bytes; the
