@@ -1,18 +1,20 @@
-// bf16 fast path of the ResNet stage (channel counts that are multiples of 16):
+// bf16 fast path of the ResNet blocks (channel counts 16, 32, 48, 64):
 //  * 3x3 convolution forward and input gradient as an implicit GEMM on the
 //    matrix cores: a lane owns one output pixel, reads its 3x3 neighbourhood
 //    straight from the NHWC tensor in MFMA fragment order (8 consecutive
 //    channels = 16 bytes), the filter sits in LDS as [out channel][tap, in
 //    channel]; the product is issued filter-first so that a lane ends up with 4
 //    consecutive output channels of its pixel (8-byte stores).
-//  * weight gradient: stride 1 with equal channel counts on the matrix cores with the
-//    pixel as reduction index (images transposed in LDS); other shapes with 64 output
-//    pixels per workgroup, their nine shifted input vectors and dy staged in LDS and
-//    fp32 accumulators per thread; partials per workgroup, summed in a fixed order.
+//  * weight gradient on the matrix cores with the output pixel as reduction index
+//    (images transposed in LDS; stride 1 and 2, up to 16 convolutions of one shape per
+//    launch); shapes it refuses: 64 output pixels per workgroup, their nine shifted
+//    input vectors and dy staged in LDS, fp32 accumulators per thread.  Partial sums
+//    per workgroup, added in a fixed order by the queued second stage.
 //  * BatchNorm statistics / backward sums: 8 channels per thread (16-byte loads),
-//    per-workgroup partials; a second, one-workgroup launch adds them in workgroup
-//    order and finishes mean / rstd / running stats or dgamma / dbeta (a last-arrival
-//    scheme in one launch was slower: its device-scope fences cost more than a launch).
+//    per-workgroup partials, added in workgroup order either by a one-workgroup launch
+//    or, on small tensors, by every workgroup of the kernel that applies them (a
+//    last-arrival scheme in one launch was slower: device-scope fences cost more).
+//  * the elementwise pieces: shortcut of a downsampling block, global average pooling.
 #include "common.h"
 
 namespace ppll {
