@@ -81,9 +81,9 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2
 //    granule index XORed with (row/16)%8: reads and those stores are conflict-free (the first
 //    layout would serialise the stores 8-fold).
 template <bool TR> struct TileLayout {
-  static constexpr int ROW = TR ? 144 : 128;
+  static constexpr int ROW = TR ? 160 : 128;
   static __device__ __forceinline__ int off(int row, int granule16) {
-    return TR ? row * 144 + ((granule16 ^ ((row >> 4) & 7)) << 4) : row * 128 + ((granule16 ^ ((row >> 1) & 7)) << 4);
+    return TR ? row * 160 + ((granule16 ^ ((row >> 4) & 7)) << 4) : row * 128 + ((granule16 ^ ((row >> 1) & 7)) << 4);
   }
 };
 
@@ -169,7 +169,7 @@ struct OperandLoader {
 
 constexpr int STAGE_LD = BN + 4;                      // fp32 staging tile of the epilogue, padded row
 // one stage of both operand tiles; two stages, or the epilogue's staging tile if that is larger
-constexpr int oper_bytes(bool at, bool bt, int tm) { return tm * TileLayout<false>::ROW + (at ? tm * 16 : 0) + BN * TileLayout<false>::ROW + (bt ? BN * 16 : 0); }
+constexpr int oper_bytes(bool at, bool bt, int tm) { return tm * TileLayout<false>::ROW + (at ? tm * 32 : 0) + BN * TileLayout<false>::ROW + (bt ? BN * 32 : 0); }
 constexpr int lds_bytes(bool at, bool bt, int tm) {
   return 2 * oper_bytes(at, bt, tm) > tm * STAGE_LD * 4 ? 2 * oper_bytes(at, bt, tm) : tm * STAGE_LD * 4;
 }
