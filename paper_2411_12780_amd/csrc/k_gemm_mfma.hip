@@ -12,9 +12,10 @@
 // of weights or activations exist in HBM.
 //
 // The 16-byte k-granules of an LDS row are permuted by an XOR with row bits, and
-// a tile written by the transposing loader also pads its rows (144 bytes apart):
-// each operand tile gets the layout for which both its stores and the fragment
-// reads (ds_read_b128, 32 rows x 2 granules per wave) are free of bank conflicts.
+// a tile written by the transposing loader also pads its rows (160 bytes apart):
+// each operand tile gets the layout for which the fragment reads (ds_read_b128,
+// 32 rows x 2 granules per wave) are free of bank conflicts and its stores as
+// cheap as they get (timed with a micro-benchmark of the two access patterns).
 //
 // The MFMA is issued with the B tile as its first operand, i.e. it produces C
 // transposed: a lane then holds 4 consecutive columns of one C row, so bias,
@@ -73,13 +74,15 @@ __device__ __forceinline__ float gelu_fast(float h) { float c, d; cdf_pdf(h, c, 
 __device__ __forceinline__ float dgelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return c + h * d; }
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
-// LDS layout of an operand tile, [row][64 k], chosen by how the tile is written (a brute-force model
-// of the 64 x 4-byte banks gives the conflict counts):
+// LDS layout of an operand tile, [row][64 k], chosen by how the tile is written.  Measured on the chip
+// (16 waves of one compute unit issuing one access pattern; cycles per wave instruction, a linear
+// ds_read_b128 takes 4.1 and a linear ds_write_b64 6.2):
 //  - copied with 16-byte stores (k contiguous in memory): rows 128 bytes apart, the 16-byte granule
-//    index XORed with (row/2)%8: stores and fragment reads are both conflict-free;
-//  - written by the transposing loader (8-byte stores, 8 rows per thread): rows 144 bytes apart,
-//    granule index XORed with (row/16)%8: reads and those stores are conflict-free (the first
-//    layout would serialise the stores 8-fold).
+//    index XORed with (row/2)%8: fragment reads 4.1, stores as fast as linear ones;
+//  - written by the transposing loader (8-byte stores, 8 rows per thread): rows 160 bytes apart,
+//    granule index XORed with (row/16)%8: fragment reads 4.1, stores 8.0.  (At 144 bytes per row,
+//    which a model of 64 independent 4-byte banks calls conflict-free, the reads took 8.0; the
+//    first layout would serialise the transposing stores 8-fold.)
 template <bool TR> struct TileLayout {
   static constexpr int ROW = TR ? 160 : 128;
   static __device__ __forceinline__ int off(int row, int granule16) {
