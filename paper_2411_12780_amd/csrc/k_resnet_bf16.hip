@@ -196,6 +196,79 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   }
 }
 
+// Input gradient at stride 2 (H and W even, no fused shortcut gradient).  An input pixel (y, x) receives from
+// the taps ky with (y + 1 - ky) even only: one tap per axis for even y (ky = 1), two for odd y (ky = 0, 2).  The
+// pixels are therefore taken class by class (y parity, x parity): a tile of 128 pixels is of one class, and
+// its 1, 2 or 4 live taps are the only ones loaded and multiplied (2.25 on average instead of 9).
+template <int K16, int NT>
+__global__ __launch_bounds__(256) void conv3x3_dgrad_s2_kernel(ConvArgs p) {
+  extern __shared__ __align__(16) char wl[];        // [Ci rounded up to 32][9*Co] bf16, row stride RSW bytes
+  constexpr int KC = 16 * K16, RSW = 18 * KC + 16;
+  const int NO = p.Ci;
+  const int Ho = p.H / 2, Wo = p.W / 2;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
+  {
+    const int nvec = 9 * p.Ci * p.Co / 8;           // the filter row of an input channel: 8 consecutive output channels per copy
+    for (int v = tid; v < nvec; v += 256) {
+      const int e = v * 8, co = e % p.Co, ci = (e / p.Co) % p.Ci, tap = e / (p.Co * p.Ci);
+      *reinterpret_cast<uint4*>(wl + ci * RSW + 2 * (tap * KC + co)) = *reinterpret_cast<const uint4*>(p.w + (size_t)v * 8);
+    }
+  }
+  __syncthreads();
+  const uint32_t Pc = (uint32_t)p.B * Ho * Wo, tpc = (Pc + 127) / 128;    // pixels and tiles per class
+  const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.src), 0, (int)(Pc * KC * 2), 0x00020000);
+  for (uint32_t tile = blockIdx.x; tile < 4 * tpc; tile += gridDim.x) {
+    const int cls = (int)(tile / tpc), cy = cls >> 1, cx = cls & 1;
+    const uint32_t q = (tile - cls * tpc) * 128 + wave * 32 + li;
+    const bool live = q < Pc;
+    const uint32_t qrow = q / (uint32_t)Wo;
+    const int hx = (int)(q - qrow * (uint32_t)Wo), hy = (int)(qrow % (uint32_t)Ho), b = (int)(qrow / (uint32_t)Ho);
+    f32x16 acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+    const int base = (((b * Ho + hy) * Wo + hx) * KC + 8 * hh) * 2;
+    // axis parity 0: tap 1 reads source hy; parity 1: tap 0 reads hy + 1, tap 2 reads hy
+#pragma unroll
+    for (int iy = 0; iy < 2; ++iy) {
+      if (iy > cy) break;
+      const int ky = cy ? 2 * iy : 1, dy = (cy && iy == 0) ? 1 : 0;
+#pragma unroll
+      for (int ix = 0; ix < 2; ++ix) {
+        if (ix > cx) break;
+        const int kx = cx ? 2 * ix : 1, dx = (cx && ix == 0) ? 1 : 0;
+        const bool ok = live && hy + dy < Ho && hx + dx < Wo;
+        const int off = base + ((dy * Wo + dx) * KC) * 2;
+        uint4 xv[K16];
+#pragma unroll
+        for (int c16 = 0; c16 < K16; ++c16) xv[c16] = conv_buf_load16(rsrc, ok ? off + 32 * c16 : CONV_OOB);
+        const char* wrow = wl + 2 * ((ky * 3 + kx) * KC + 8 * hh);
+#pragma unroll
+        for (int c16 = 0; c16 < K16; ++c16) {
+          const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[c16]);
+#pragma unroll
+          for (int t = 0; t < NT; ++t) {
+            const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (!live) continue;
+    uint16_t* drow = p.dst + ((size_t)(b * p.H + 2 * hy + cy) * p.W + 2 * hx + cx) * NO;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+#pragma unroll
+      for (int qq = 0; qq < 4; ++qq) {
+        const int c = 32 * t + 8 * qq + 4 * hh;
+        if (c >= NO) continue;
+        *reinterpret_cast<uint2*>(drow + c) = make_uint2(pack2(acc[t][4 * qq], acc[t][4 * qq + 1]), pack2(acc[t][4 * qq + 2], acc[t][4 * qq + 3]));
+      }
+    }
+  }
+}
+
 // Weight gradient.  CO = 32 or 64.  Thread (co = tid % CO, cig = tid / CO) owns
 // dw[tap][cig*CPT .. +CPT-1][co], CPT = Ci / (256 / CO) input channels.
 constexpr int WG_PIX_F = 64;
@@ -660,6 +733,36 @@ bool conv_bf16_supported(int dt, int wdt, int Ci, int Co, const void* a, const v
   return al16(a) && al16(b) && al16(c);
 }
 
+template <int K16, int NT>
+static int conv_dgrad_s2_launch_k(hipStream_t s, const ConvArgs& p, size_t lds) {
+  static bool raised[64] = {};
+  if (lds > 64 * 1024) {
+    int dev = 0;
+    PPLL_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64 || !raised[dev]) {
+      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_dgrad_s2_kernel<K16, NT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)CONV_MFMA_LDS_MAX));
+      if (dev >= 0 && dev < 64) raised[dev] = true;
+    }
+  }
+  const long pc = (long)p.B * (p.H / 2) * (p.W / 2), tiles = 4 * ((pc + 127) / 128);
+  const long tpw = tiles >= 8192 ? 4 : (tiles >= 4096 ? 2 : 1);
+  hipLaunchKernelGGL((conv3x3_dgrad_s2_kernel<K16, NT>), dim3((unsigned)((tiles + tpw - 1) / tpw)), dim3(256), lds, s, p);
+  PPLL_HIP(hipGetLastError());
+  return PPLL_OK;
+}
+static int conv_dgrad_s2_launch(hipStream_t s, const ConvArgs& p, int k16, size_t lds) {
+  const bool two = p.Ci > 32;
+  switch (k16) {
+    case 1: return two ? conv_dgrad_s2_launch_k<1, 2>(s, p, lds) : conv_dgrad_s2_launch_k<1, 1>(s, p, lds);
+    case 2: return two ? conv_dgrad_s2_launch_k<2, 2>(s, p, lds) : conv_dgrad_s2_launch_k<2, 1>(s, p, lds);
+    case 3: return two ? conv_dgrad_s2_launch_k<3, 2>(s, p, lds) : conv_dgrad_s2_launch_k<3, 1>(s, p, lds);
+    case 4: return two ? conv_dgrad_s2_launch_k<4, 2>(s, p, lds) : conv_dgrad_s2_launch_k<4, 1>(s, p, lds);
+  }
+  set_error("conv3x3: %d reduced channels have no matrix-core kernel", 16 * k16);
+  return PPLL_ERR_CONFIG;
+}
+
 int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, int H, int W, int Ci, int Co,
                             int stride, void* y) {
   ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr};
@@ -680,7 +783,10 @@ int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int 
   const double Po = (double)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   void* prof = nullptr;   // algorithmic bytes: dy, dx and filter once, plus the shortcut gradient and its mask
   PPLL_TRY(profile_begin(s, 2.0 * (Po * Co + (double)P * Ci * (dres ? 3.0 : 1.0) + 9.0 * Ci * Co), &prof, 1));
-  PPLL_TRY((conv_mfma_launch<1>(s, p, P, Co / 16, lds)));
+  if (stride == 2 && !(H & 1) && !(W & 1) && !dres && Po * Co * 2 < (double)(1 << 30))
+    PPLL_TRY(conv_dgrad_s2_launch(s, p, Co / 16, lds));
+  else
+    PPLL_TRY((conv_mfma_launch<1>(s, p, P, Co / 16, lds)));
   return profile_end(s, prof);
 }
 
