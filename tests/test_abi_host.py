@@ -67,6 +67,13 @@ def test_bad_configurations_are_rejected_on_the_host():
         assert e.value.status == 2, bad
 
 
+def test_library_and_published_size_of_vit_base_patch16_224_agree():
+    # the library's own parameter table for ViT-base-patch16-224 as one block: the published 86,567,656 parameters
+    wl = dict(synth.workload("vit_base_paper_bf16"), img_h=224, img_w=224, tokens=197, depth=12, aux_depth=0, num_classes=1000,
+              batch=1)
+    assert P.ppll_block_param_bytes(P.make_config(wl)) == 4 * 86567656
+
+
 def test_size_queries_of_every_resnet32_module():
     wls = synth.resnet32_modules(8)
     for wl in wls:

@@ -53,6 +53,18 @@ def test_param_counts_of_the_named_workloads():
     assert O.param_count(oracle_cfg(synth.workload("resnet_stage_bf16"))) == 112010
 
 
+def test_parameter_table_reproduces_the_published_size_of_vit_base_patch16_224():
+    # Section 4.1 names ViT-base-patch16-224.  Written as one block (12 encoder layers, no auxiliary layers, the
+    # head's LayerNorm as the final norm, a 1000-class Linear head, 224 x 224 images) the parameter table must add
+    # up to that model's published 86,567,656 parameters: 7,087,872 per encoder layer, 590,592 patch embedding,
+    # 768 class token, 197 x 768 positions, 1,536 final norm, 769,000 classifier.
+    cfg = O.BlockConfig(arch=O.ARCH_VIT, input_kind=O.IN_IMAGE, batch=1, num_classes=1000, img_h=224, img_w=224, img_c=3,
+                        patch=16, tokens=197, dim=768, heads=12, mlp_dim=3072, depth=12, aux_depth=0)
+    assert O.param_count(cfg) == 86567656
+    layer = sum(int(np.prod(shape)) for name, shape in O.param_spec(cfg) if name.startswith("blk0."))
+    assert layer == 7087872
+
+
 # ------------------------------------------------------------------ finite differences
 @pytest.mark.parametrize("case", list(CASES))
 def test_gradients_match_central_finite_differences(case):
