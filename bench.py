@@ -77,6 +77,11 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
         # Section 4.2's finest partition: 12 one-layer blocks, auxiliary depths from the d' = 4 schedule
         wls = synth.lpp_workloads(4)
         first = wls[0]
+    elif args.workload == "vit_base224_pipeline4":
+        # Section 4.3's ViT-Base at 224 x 224 (197 tokens of width 768), its 12 layers as 4 blocks of 3 with one
+        # auxiliary layer each, SGD Nesterov
+        first = synth.workload("vit_base_224_bf16")
+        wls = [first] + [dict(first, input_kind=synth.ACTIVATION) for _ in range(3)]
     elif args.workload == "resnet32_k8":
         # Section 4.1's ResNet-32 at its CIFAR batch of 1024, cut into 8 local modules
         wls = synth.resnet32_modules(8)
@@ -203,7 +208,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     dev = "cuda:0"
-    if args.workload in ("vit_pipeline4", "vit_lpp12", "resnet32_k8"):
+    if args.workload in ("vit_pipeline4", "vit_lpp12", "resnet32_k8", "vit_base224_pipeline4"):
         return bench_pipeline(args, torch, P, synth, dev)
     wl = synth.workload(args.workload)
     wl["seed"] = 0

@@ -46,6 +46,12 @@ WORKLOADS = {
                                 img_h=32, img_w=32, img_c=3, patch=16, tokens=5, dim=768, heads=12,
                                 mlp_dim=3072, depth=3, aux_depth=1, optimizer=SGD, momentum=0.9, nesterov=1,
                                 weight_decay=1e-4, ln_eps=1e-6, lr=0.01),
+    # the same model at the input resolution Section 4.3 states for the speed measurements (224 x 224: 196 patches + class
+    # token = 197 tokens), one stage of 3 layers with a 1-layer auxiliary network, batch 128
+    "vit_base_224_bf16": dict(arch=VIT, precision=BF16, input_kind=IMAGE, batch=128, num_classes=10,
+                              img_h=224, img_w=224, img_c=3, patch=16, tokens=197, dim=768, heads=12,
+                              mlp_dim=3072, depth=3, aux_depth=1, optimizer=SGD, momentum=0.9, nesterov=1,
+                              weight_decay=1e-4, ln_eps=1e-6, lr=0.01),
     # second stage of ResNet-32 at the paper's CIFAR batch (Section 4.1: batch 1024; Section 4.3 names its
     # 1024 x 32 x 16 x 16 activations): the basic block that halves the 32 x 32 x 16 input and doubles its
     # channels, then four shape-keeping blocks

@@ -350,6 +350,12 @@ def test_vit_base_paper_shape_bf16_full_size():
     run_case(synth.workload("vit_base_paper_bf16"), steps=2)
 
 
+def test_vit_base_224_shape_bf16():
+    # the paper's ViT-Base at 224 x 224 (197 tokens of width 768: seven 32-token attention tiles, K = 768 and 3072
+    # contractions); batch 8 instead of 128 keeps the float64 oracle to seconds
+    run_case(synth.workload("vit_base_224_bf16", batch=8), steps=1)
+
+
 def test_vit_large_image_bf16_full_size():
     run_case(synth.workload("vit_large_image_bf16"), steps=1)
 
