@@ -247,6 +247,7 @@ int ppll_block_step(ppll_block_t* h, const void* x_in_dev, const int32_t* labels
   PPLL_TRY(check_aligned(x_out_dev, "x_out_dev"));
   if (!labels_dev) { set_error("labels_dev is null"); return PPLL_ERR_NULL; }
   if (!(lr == lr)) { set_error("lr is NaN"); return PPLL_ERR_CONFIG; }
+  h->b.use_side = true;
   return h->b.step(x_in_dev, labels_dev, lr, x_out_dev, loss_dev, (hipStream_t)hip_stream, nullptr);
 }
 
@@ -349,6 +350,7 @@ int ppll_block_destroy(ppll_block_t* h) {
     if (e) (void)hipEventDestroy(e);
     e = nullptr;
   }
+  h->b.side_destroy();
   h->b.alive = false;   // the handle stays allocated so that later misuse is reported, not undefined
   return PPLL_OK;
 }
@@ -484,6 +486,7 @@ int ppll_pipeline_step(ppll_pipeline_t* p, const void* x0_dev, const int32_t* la
       return PPLL_OK;
     };
     float* loss_j = losses_dev ? losses_dev + j : nullptr;
+    p->blocks[j]->b.use_side = false;   // the other blocks' streams fill the chip
     PPLL_TRY(p->blocks[j]->b.step(x_in, y_in, lr, x_out, p->losses + j, s, publish));
     if (loss_j) PPLL_HIP(hipMemcpyAsync(loss_j, p->losses + j, sizeof(float), hipMemcpyDeviceToDevice, s));
     if (j > 0) {                                                                        // slot of B_{j-1} is free again

@@ -77,6 +77,17 @@ struct Block {
   std::vector<void*> g_res, g_mid, d_h, d_qkv;
   void* d_u = nullptr;
   std::vector<GemmArgs> wgrad_jobs;   // weight-gradient products recorded during the backward pass
+  // Side stream of the backward pass (created at first use, default priority).  The weight-gradient products of a
+  // layer are launched there once the layer's backward is enqueued, so they run next to the input-gradient chain of
+  // the layers below, which never reads them; the step's stream waits for the side stream before the update.
+  // Off for blocks driven by a pipeline: there the other blocks' streams already fill the chip.
+  bool use_side = true;
+  hipStream_t side = nullptr;
+  hipEvent_t side_fork = nullptr, side_join = nullptr;
+  bool side_busy = false;              // something was launched on the side stream in this step
+  int side_launch_wgrads(hipStream_t s);   // launches wgrad_jobs on the side stream behind everything enqueued on s
+  int side_wait(hipStream_t s);            // s waits for the side stream's work of this step
+  void side_destroy();
 
   // ResNet
   std::vector<BasicBlockParams> rb_p;

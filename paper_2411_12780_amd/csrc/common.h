@@ -99,7 +99,9 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
 bool gemm_mfma_groupable(const GemmArgs& g);
 int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n);   // every product must be groupable
 // A set of independent products; one launch when all of them are groupable, else one by one.
-int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n);
+// `one_launch`: take the grouped kernel whenever all products allow it, however few tiles they have
+int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch = false);
+bool gemm_group_in_one_launch(const GemmArgs* gs, int n);   // every product fits the grouped kernel (n > 1)
 void profile_enable(bool on);
 // event pair around one launch (profiling only); kind 0: GEMM, units = flops; kind 1: convolution, units = bytes
 int profile_begin(hipStream_t s, double units, void** token, int kind = 0);

@@ -58,7 +58,13 @@ int launch_gemm(hipStream_t s, const GemmArgs& g) {
   return gemm_mfma_supported(g) ? launch_gemm_mfma(s, g, g.splitk_ws, g.splitk_floats) : launch_gemm_generic(s, g);
 }
 
-int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n) {
+bool gemm_group_in_one_launch(const GemmArgs* gs, int n) {
+  bool all = n > 1;
+  for (int j = 0; j < n && all; ++j) all = gemm_mfma_groupable(gs[j]);
+  return all;
+}
+
+int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch) {
   if (n <= 0) return PPLL_OK;
   bool all = n > 1;
   long tiles = 0;
@@ -68,7 +74,7 @@ int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n) {
   }
   // one launch when the products together have enough output tiles for the chip; a small set runs
   // product by product, each with split-K (their reduction index is the long one)
-  if (all && tiles >= 128) return launch_gemm_mfma_grouped(s, gs, n);
+  if (all && (tiles >= 128 || one_launch)) return launch_gemm_mfma_grouped(s, gs, n);
   for (int j = 0; j < n; ++j) {
     const bool fused = gemm_fuses_colsum(gs[j]);
     if (gs[j].colsum && !fused) { set_error("launch_gemm_group: column sums need the MFMA kernel"); return PPLL_ERR_CONFIG; }

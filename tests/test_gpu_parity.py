@@ -356,6 +356,13 @@ def test_vit_base_224_shape_bf16():
     run_case(synth.workload("vit_base_224_bf16", batch=8), steps=1)
 
 
+def test_weight_gradients_on_the_side_stream_bf16():
+    # 21 x 197 = 4137 rows of width 768: a layer's weight-gradient products have 432 output tiles and a reduction
+    # over more than 4096 rows, so the auxiliary layer's run on the block's side stream beside the backward of the
+    # module layer; two steps, so that the second forward and update also meet the first step's side work
+    run_case(synth.workload("vit_base_224_bf16", batch=21, depth=1, aux_depth=1), steps=2)
+
+
 def test_vit_large_image_bf16_full_size():
     run_case(synth.workload("vit_large_image_bf16"), steps=1)
 
