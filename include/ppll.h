@@ -198,7 +198,10 @@ int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
  * ppll_profile_read waits for those events and returns, since the previous
  * read: their summed duration in milliseconds, the algorithmic flops 2*M*N*K of
  * the bracketed launches, and their count (each pointer nullable).  The events
- * add host and stream overhead: time whole steps with profiling off. */
+ * add host and stream overhead: time whole steps with profiling off.  While
+ * enabled, a block also keeps every launch on the step's own stream (no side
+ * stream for weight gradients), so that each bracket holds one kernel running
+ * alone. */
 int ppll_profile_enable(int32_t on);
 int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
 /* The same for the bf16 matrix-core convolution kernel (forward and input gradient of the ResNet

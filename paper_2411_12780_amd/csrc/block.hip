@@ -453,7 +453,8 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     // beside the backward of the layers below, where they take up the slots that the chain's ragged last rounds of
     // workgroups leave empty (measured: 5 % of the step at width 768 and 197 tokens).  Smaller sets only slow the
     // chain down (measured at width 384: 2 to 8 % slower), so they wait for the grouped launch at the end.
-    if (use_side && l > 0 && M >= SIDE_MIN_ROWS && gemm_group_in_one_launch(wgrad_jobs.data(), (int)wgrad_jobs.size())) {
+    // (not while launches are being timed one by one: overlapping kernels would stretch each other's brackets)
+    if (use_side && !profile_enabled() && l > 0 && M >= SIDE_MIN_ROWS && gemm_group_in_one_launch(wgrad_jobs.data(), (int)wgrad_jobs.size())) {
       long tiles = 0;
       for (size_t j = first_job; j < wgrad_jobs.size(); ++j)
         tiles += (long)((wgrad_jobs[j].M + 127) / 128) * ((wgrad_jobs[j].N + 127) / 128);

@@ -103,6 +103,7 @@ int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n);   // eve
 int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch = false);
 bool gemm_group_in_one_launch(const GemmArgs* gs, int n);   // every product fits the grouped kernel (n > 1)
 void profile_enable(bool on);
+bool profile_enabled();
 // event pair around one launch (profiling only); kind 0: GEMM, units = flops; kind 1: convolution, units = bytes
 int profile_begin(hipStream_t s, double units, void** token, int kind = 0);
 int profile_end(hipStream_t s, void* token);

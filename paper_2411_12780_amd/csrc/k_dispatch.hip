@@ -22,6 +22,7 @@ hipEvent_t pooled_event() {
 }  // namespace
 
 void profile_enable(bool on) { g_profile = on; }
+bool profile_enabled() { return g_profile; }
 
 // Sums the elapsed time of every bracketed launch since the last read, per kind (0: GEMM, 1: convolution).
 int profile_read(double ms[2], double units[2], long long launches[2]) {
