@@ -818,6 +818,21 @@ __global__ __launch_bounds__(256) void patchify_kernel(const void* img, int dt, 
   else ((float*)out)[i] = ((const float*)img)[src];
 }
 
+// bf16, P*C and W*C multiples of 8: a patch row (P*C contiguous elements in the image and in the patch vector) moves as
+// 16-byte pieces, one per thread; 32-bit index arithmetic
+__global__ __launch_bounds__(256) void patchify_bf16_kernel(const uint16_t* img, int B, int H, int W, int C, int P,
+                                                            uint16_t* out) {
+  const uint32_t row8 = (uint32_t)(P * C) >> 3, gw = W / P, gh = H / P;
+  const uint32_t total = (uint32_t)B * gh * gw * P * row8;
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i >= total) return;
+  const uint32_t v = i % row8, t = i / row8;      // piece within the patch row; (patch, row)
+  const uint32_t r = t % P, pidx = t / P;
+  const uint32_t gx = pidx % gw, q = pidx / gw, gy = q % gh, b = q / gh;
+  const size_t src = (((size_t)b * H + gy * P + r) * W + gx * P) * C + 8 * v;
+  *reinterpret_cast<uint4*>(out + (size_t)i * 8) = *reinterpret_cast<const uint4*>(img + src);
+}
+
 __global__ __launch_bounds__(256) void assemble_tokens_kernel(const void* E, int dt, const float* cls,
                                                               const float* pos, int B, int T, int D, void* x0) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -920,6 +935,14 @@ __global__ __launch_bounds__(256) void scatter_cls_kernel(const void* dcls, int 
 
 int launch_patchify(hipStream_t s, const void* img, int dt, int B, int H, int W, int C, int P, void* patches) {
   size_t total = (size_t)B * H * W * C;
+  const size_t used = (size_t)B * (H / P) * (W / P) * P * P * C;   // pixels of whole patches
+  if (dt == BF16 && !((P * C) & 7) && !((W * C) & 7) && !((((uintptr_t)img) | ((uintptr_t)patches)) & 15) &&
+      used / 8 < ((size_t)1 << 31)) {
+    hipLaunchKernelGGL(patchify_bf16_kernel, dim3((unsigned)((used / 8 + 255) / 256)), dim3(256), 0, s, (const uint16_t*)img, B,
+                       H, W, C, P, (uint16_t*)patches);
+    PPLL_HIP(hipGetLastError());
+    return PPLL_OK;
+  }
   hipLaunchKernelGGL(patchify_kernel, dim3((total + 255) / 256), dim3(256), 0, s, img, dt, B, H, W, C, P, patches);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
