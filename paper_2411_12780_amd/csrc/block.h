@@ -101,7 +101,7 @@ struct Block {
   // 16-channel matrix-core kernels (null: the stem runs on the generic kernels)
   void *stem_xp = nullptr, *stem_wp = nullptr;
   bool stem_pad = false;
-  int stem_conv_fwd(const void* x_in, hipStream_t s);
+  int stem_conv_fwd(const void* x_in, hipStream_t s, float* stat = nullptr, int* stat_blocks = nullptr);
   float *stem_mean = nullptr, *stem_rstd = nullptr;
   int bn_base = 0;                       // index of rb0.bn1 among the BatchNorm layers (1 behind a stem)
   size_t aux_conv_w = 0, aux_bn_g = 0, aux_bn_b = 0;

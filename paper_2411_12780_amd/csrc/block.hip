@@ -490,12 +490,13 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
 
 // ------------------------------------------------------------------ ResNet
 // stem convolution img_c -> in_c into stem_c
-int Block::stem_conv_fwd(const void* x_in, hipStream_t s) {
+int Block::stem_conv_fwd(const void* x_in, hipStream_t s, float* stat, int* stat_blocks) {
   const int B = cfg.batch;
-  if (!stem_pad) return launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c);
+  if (!stem_pad)
+    return launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c, stat, stat_blocks);
   PPLL_TRY(launch_pad_channels16(s, x_in, (size_t)B * in_h * in_w, cfg.img_c, stem_xp));
   PPLL_TRY(launch_pad_filter16(s, params + stem_w, cfg.img_c, in_c, stem_wp));
-  return launch_conv3x3_fwd(s, stem_xp, stem_wp, BF16, dt, B, in_h, in_w, 16, in_c, 1, stem_c);
+  return launch_conv3x3_fwd(s, stem_xp, stem_wp, BF16, dt, B, in_h, in_w, 16, in_c, 1, stem_c, stat, stat_blocks);
 }
 
 int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
@@ -511,9 +512,10 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   const void* x = x_in;
   if (stem) {
     const int rows0 = B * in_h * in_w;
-    PPLL_TRY(stem_conv_fwd(x_in, s));
+    int ready = 0;   // partial rows of the BatchNorm sums that the convolution has written itself
+    PPLL_TRY(stem_conv_fwd(x_in, s, partials, &ready));
     PPLL_TRY(launch_bn_train_fwd(s, stem_c, dt, rows0, in_c, eps, mom, partials, stem_mean, stem_rstd, run_mean(0), run_var(0),
-                                 params + stem_g, params + stem_b, nullptr, stem_y));
+                                 params + stem_g, params + stem_b, nullptr, stem_y, ready));
     x = stem_y;
   }
   for (int i = 0; i < n; ++i) {
@@ -523,26 +525,28 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     const int rows = B * d.Ho * d.Wo, b1 = bn_base + 2 * i, b2 = b1 + 1;
     block_in[i] = x;
     block_out[i] = i == n - 1 ? x_out : a.out;
-    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, a.c1));
+    int ready = 0;
+    PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, a.c1, partials, &ready));
     PPLL_TRY(launch_bn_train_fwd(s, a.c1, dt, rows, d.Co, eps, mom, partials, a.mean1, a.rstd1, run_mean(b1), run_var(b1),
-                                 params + p.bn1_g, params + p.bn1_b, nullptr, a.y1));
-    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, a.c2));
+                                 params + p.bn1_g, params + p.bn1_b, nullptr, a.y1, ready));
+    PPLL_TRY(launch_conv3x3_fwd(s, a.y1, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, a.c2, partials, &ready));
     const void* skip = x;
     if (d.stride != 1 || d.Ci != d.Co) {
       PPLL_TRY(launch_shortcut_fwd(s, x, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, shortcut));
       skip = shortcut;
     }
     PPLL_TRY(launch_bn_train_fwd(s, a.c2, dt, rows, d.Co, eps, mom, partials, a.mean2, a.rstd2, run_mean(b2), run_var(b2),
-                                 params + p.bn2_g, params + p.bn2_b, skip, block_out[i]));
+                                 params + p.bn2_g, params + p.bn2_b, skip, block_out[i], ready));
     x = block_out[i];
   }
   PPLL_TRY(mark_phase(1, s));   // module forward done
   if (after_forward) PPLL_TRY(after_forward());
   // ---- auxiliary forward
   const int ba = bn_base + 2 * n;
-  PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
+  int aux_ready = 0;
+  PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c, partials, &aux_ready));
   PPLL_TRY(launch_bn_train_fwd(s, aux_c, dt, arows, A, eps, mom, partials, aux_mean, aux_rstd, run_mean(ba), run_var(ba),
-                               params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
+                               params + aux_bn_g, params + aux_bn_b, nullptr, aux_y, aux_ready));
   PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
   if (vit_head_fused_ok(A, C)) {
     // ---- Linear head, local loss and the head's backward in one launch (the fused head without a LayerNorm)

@@ -193,8 +193,11 @@ int launch_fill_zero(hipStream_t s, void* p, size_t bytes);
 int launch_copy_probe(hipStream_t s, const void* src, void* dst, size_t bytes);
 
 // ---------------------------------------------------------------- ResNet pieces
+// stat / stat_blocks (nullable): room for the sums a BatchNorm over y needs (bn_partial_floats of y's shape); on
+// return *stat_blocks is the number of partial rows the convolution wrote there itself (0: none, the BatchNorm
+// has to make its own pass)
 int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
-                       int Co, int stride, void* y);
+                       int Co, int stride, void* y, float* stat = nullptr, int* stat_blocks = nullptr);
 // dx = dgrad(dy, w) (+ dres * (ymask > 0) when dres != null)
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                          int Co, int stride, const void* dres, const void* ymask, void* dx);
@@ -225,9 +228,10 @@ int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt
 int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum,
                     float* partials, float* mean, float* rstd, float* run_mean, float* run_var);
 // statistics of x, running-statistics update and y = relu(bn(x) (+ res)): the BatchNorm of a training step
+// ready_blocks: rows of `partials` the producing convolution has already filled (see launch_conv3x3_fwd), else 0
 int launch_bn_train_fwd(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
                         float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
-                        const void* res, void* y);
+                        const void* res, void* y, int ready_blocks = 0);
 // y = relu(bn(x) (+ res))
 int launch_bn_running_stats(hipStream_t s, const float* run_mean, const float* run_var, int C, float eps, float* mean,
                             float* rstd);
@@ -244,8 +248,10 @@ bool conv_pixels_fit(int B, int H, int W);
 bool conv_fwd_bf16_ok(int Ci, int Co);
 bool conv_dgrad_bf16_ok(int Ci, int Co);
 bool conv_wgrad_bf16_ok(int Ci, int Co);
+// stat (nullable): the kernel also writes per-workgroup per-channel sums of its stored outputs there
+// ([*stat_blocks][2][Co] floats: what the BatchNorm behind the convolution reduces)
 int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, int H, int W, int Ci, int Co,
-                            int stride, void* y);
+                            int stride, void* y, float* stat = nullptr, int* stat_blocks = nullptr);
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
                               int stride, const void* dres, const void* ymask, void* dx);
 int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co,
@@ -264,7 +270,7 @@ int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float ep
                          float* mean, float* rstd, float* run_mean, float* run_var);
 int launch_bn_train_fwd_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
                              float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
-                             const void* res, void* y);
+                             const void* res, void* y, int ready_blocks = 0);
 int launch_bn_apply_bf16(hipStream_t s, const void* x, int rows, int C, const float* mean, const float* rstd,
                          const float* g, const float* b, const void* res, void* y);
 int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void* x, int rows, int C, const float* mean,

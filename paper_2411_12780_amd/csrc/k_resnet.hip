@@ -264,9 +264,14 @@ int launch_shortcut_bwd(hipStream_t s, const void* dy, const void* ymask, int dt
 }
 
 int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
-                       int Co, int stride, void* y) {
-  if (conv_bf16_supported(dt, wdt, Ci, Co, x, w, y) && conv_fwd_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W))
-    return launch_conv3x3_fwd_bf16(s, x, w, B, H, W, Ci, Co, stride, y);
+                       int Co, int stride, void* y, float* stat, int* stat_blocks) {
+  if (stat_blocks) *stat_blocks = 0;
+  if (conv_bf16_supported(dt, wdt, Ci, Co, x, w, y) && conv_fwd_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W)) {
+    // the sums are only of use to the bf16 BatchNorm kernels (same partial layout); they refuse fewer than 2 rows
+    const long rows = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+    const bool want = stat && stat_blocks && rows >= 2 && bn_bf16_supported(dt, (int)rows, Co, y, nullptr, nullptr, nullptr);
+    return launch_conv3x3_fwd_bf16(s, x, w, B, H, W, Ci, Co, stride, y, want ? stat : nullptr, stat_blocks);
+  }
   size_t total = (size_t)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1) * Co;
   hipLaunchKernelGGL(conv3x3_fwd_kernel, dim3((total + 255) / 256), dim3(256), 0, s, x, w, wdt, dt, B, H, W, Ci, Co,
                      stride, y);
@@ -355,9 +360,10 @@ int launch_bn_stats(hipStream_t s, const void* x, int dt, int rows, int C, float
 
 int launch_bn_train_fwd(hipStream_t s, const void* x, int dt, int rows, int C, float eps, float momentum, float* partials,
                         float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
-                        const void* res, void* y) {
+                        const void* res, void* y, int ready_blocks) {
   if (rows >= 2 && bn_bf16_supported(dt, rows, C, x, res, y, nullptr))
-    return launch_bn_train_fwd_bf16(s, x, rows, C, eps, momentum, partials, mean, rstd, run_mean, run_var, g, b, res, y);
+    return launch_bn_train_fwd_bf16(s, x, rows, C, eps, momentum, partials, mean, rstd, run_mean, run_var, g, b, res, y,
+                                    ready_blocks);
   PPLL_TRY(launch_bn_stats(s, x, dt, rows, C, eps, momentum, partials, mean, rstd, run_mean, run_var));
   return launch_bn_apply(s, x, dt, rows, C, mean, rstd, g, b, res, y);
 }

@@ -44,15 +44,52 @@ struct ConvArgs {
   int B, H, W, Ci, Co, stride;
   const uint16_t* dres;    // input gradient only: dx += dres * (ymask > 0)
   const uint16_t* ymask;
+  float* stat;             // forward with STAT: [workgroups][2][Co] per-channel sum and sum of squares of the stored outputs
 };
+
+// One halving step of a butterfly sum over lanes `step` apart: of the N values a lane holds, it keeps one half
+// (the upper one if `up`), hands the other to its partner and adds what the partner hands over.
+template <int N>
+__device__ __forceinline__ void butterfly_halve(float* v, bool up, int step) {
+#pragma unroll
+  for (int i = 0; i < N / 2; ++i) {
+    const float send = up ? v[i] : v[i + N / 2], keep = up ? v[i + N / 2] : v[i];
+    v[i] = keep + __shfl_xor(send, step, 64);
+  }
+}
+// Sums NV (16 or 32) per-lane values over the 32 lanes of a half-wave in a fixed order: afterwards v[0] of lane li holds
+// the total of value index li >> 1 (NV = 16) or li (NV = 32).
+template <int NV>
+__device__ __forceinline__ void halfwave_sums(float (&v)[NV], int li) {
+  static_assert(NV == 16 || NV == 32, "16 or 32 values per lane");
+  if (NV == 32) {
+    butterfly_halve<32>(v, (li & 16) != 0, 16);
+    butterfly_halve<16>(v, (li & 8) != 0, 8);
+    butterfly_halve<8>(v, (li & 4) != 0, 4);
+    butterfly_halve<4>(v, (li & 2) != 0, 2);
+    butterfly_halve<2>(v, (li & 1) != 0, 1);
+  } else {
+    butterfly_halve<16>(v, (li & 16) != 0, 16);
+    butterfly_halve<8>(v, (li & 8) != 0, 8);
+    butterfly_halve<4>(v, (li & 4) != 0, 4);
+    butterfly_halve<2>(v, (li & 2) != 0, 2);
+    v[0] += __shfl_xor(v[0], 1, 64);
+  }
+}
+constexpr long CONV_STAT_MAX_BLOCKS = 512;    // the forward convolution sums its outputs for the BatchNorm up to this many workgroups
+constexpr int CONV_STAT_LDS = 4 * 2 * 2 * 32 * 4;   // [wave][sum kind][lane half][32] floats behind the filter
 
 // MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = 16 * K16 channels reduced.
 // GRP: how many of a pixel's nine tap loads are issued before the first product waits for one
 // (0: one, 1: the three of a filter row, 3: all nine; a filter row measured best).
 // LIN (forward, and input gradient at stride 1): a tap's source is the centre pixel's plus a constant,
 // so a tap costs one offset addition and one select between that offset and "out of range".
-template <int MODE, int K16, int NT, int GRP, bool LIN>
+// STAT (forward): the workgroup also writes the per-channel sum and sum of squares of the values it stored (as
+// stored: after rounding to bf16), which is what the BatchNorm behind the convolution needs of its input; the sums
+// run per lane over the workgroup's tiles, then over the lanes of a half-wave, then over the four waves.
+template <int MODE, int K16, int NT, int GRP, bool LIN, bool STAT>
 __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
+  static_assert(!STAT || MODE == 0, "statistics belong to the forward convolution");
   extern __shared__ __align__(16) char wl[];        // [NO rounded up to 32][9*KC] bf16, row stride RSW bytes
   constexpr int KC = 16 * K16;
   const int NO = MODE == 0 ? p.Co : p.Ci;
@@ -93,6 +130,12 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
   // NT = tiles of 32 produced channels (NO = 16: the upper half of the one tile is never stored)
   const __amdgpu_buffer_rsrc_t rsrc =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(p.src), 0, (int)((long)p.B * SH * SW * KC * 2), 0x00020000);
+  constexpr int NV = NT * 16;
+  float st0[STAT ? NV : 1], st1[STAT ? NV : 1];
+  if (STAT) {
+#pragma unroll
+    for (int j = 0; j < NV; ++j) { st0[j] = 0.f; st1[j] = 0.f; }
+  }
   // the workgroup keeps its filter for several tiles of 128 pixels
   for (long tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     // 32-bit index arithmetic (the launcher checks that the pixel count fits): 64-bit division costs more than the tile
@@ -190,9 +233,34 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
             if (lo_bf(m.y) > 0.f) v[2] += lo_bf(r.y);
             if (hi_bf(m.y) > 0.f) v[3] += hi_bf(r.y);
           }
-          *reinterpret_cast<uint2*>(drow + c) = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+          const uint2 o = make_uint2(pack2(v[0], v[1]), pack2(v[2], v[3]));
+          *reinterpret_cast<uint2*>(drow + c) = o;
+          if (STAT) {
+            const float r[4] = {lo_bf(o.x), hi_bf(o.x), lo_bf(o.y), hi_bf(o.y)};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { st0[16 * t + 4 * q + e] += r[e]; st1[16 * t + 4 * q + e] += r[e] * r[e]; }
+          }
         }
       }
+  }
+  if constexpr (STAT) {
+    // value index j = 16 t + 4 q + e of lane half hh is channel 32 t + 8 q + 4 hh + e
+    float* red = reinterpret_cast<float*>(wl + (size_t)((NO + 31) / 32 * 32) * RSW);
+    halfwave_sums<NV>(st0, li);
+    halfwave_sums<NV>(st1, li);
+    if (NV == 32 || !(li & 1)) {
+      const int j = NV == 32 ? li : li >> 1;
+      red[((wave * 2 + 0) * 2 + hh) * 32 + j] = st0[0];
+      red[((wave * 2 + 1) * 2 + hh) * 32 + j] = st1[0];
+    }
+    __syncthreads();
+    if (tid < 2 * NO) {
+      const int which = tid / NO, c = tid % NO, j = 16 * (c >> 5) + 4 * ((c & 31) >> 3) + (c & 3), h2 = (c & 7) >> 2;
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) tot += red[((w * 2 + which) * 2 + h2) * 32 + j];
+      p.stat[(size_t)blockIdx.x * 2 * NO + tid] = tot;
+    }
   }
 }
 
@@ -363,23 +431,24 @@ struct BnSumArgs {
 template <int KIND, int NTHR>
 __device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, float* red, float* l0, float* l1, bool global) {
   const int tid = threadIdx.x;
-  // 2C values; NTHR/(2C) thread groups take the workgroup partials round-robin, then one thread
-  // per value adds the groups in order
-  const int nv = 2 * p.C, parts = NTHR / nv;
-  if (tid < nv * parts) {
-    const int v = tid % nv, part = tid / nv;
-    float t = 0.f;
-    for (unsigned bk = part; bk < nblocks; bk += 8 * parts) {   // eight loads in flight; summed in workgroup order
-      float q[8];
+  // 2C values, four per thread (one 16-byte load per partial row); NTHR/(2C/4) thread groups take the workgroup
+  // partials round-robin, eight loads in flight each, then one thread per value adds the groups in order
+  // (at most 32 groups: the last stage adds them one after the other)
+  const int nv = 2 * p.C, nq = nv / 4, parts = NTHR / nq < 32 ? NTHR / nq : 32;
+  if (tid < nq * parts) {
+    const int v4 = tid % nq, part = tid / nq;
+    float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (unsigned bk = part; bk < nblocks; bk += 8 * parts) {   // summed in workgroup order
+      float4 q[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const unsigned bu = bk + u * parts;
-        q[u] = bu < nblocks ? p.partial[(size_t)bu * nv + v] : 0.f;
+        q[u] = bu < nblocks ? *reinterpret_cast<const float4*>(p.partial + (size_t)bu * nv + 4 * v4) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) t += q[u];
+      for (int u = 0; u < 8; ++u) { t.x += q[u].x; t.y += q[u].y; t.z += q[u].z; t.w += q[u].w; }
     }
-    red[tid] = t;
+    *reinterpret_cast<float4*>(red + part * nv + 4 * v4) = t;
   }
   __syncthreads();
   if (tid < p.C) {
@@ -472,7 +541,7 @@ __global__ __launch_bounds__(256) void bn_sums_kernel(BnSumArgs p) {
 
 template <int KIND>
 __global__ __launch_bounds__(1024) void bn_finish_kernel(BnSumArgs p, unsigned nblocks) {
-  __shared__ float red[1024];
+  __shared__ __align__(16) float red[4096];
   bn_finish<KIND, 1024>(p, nblocks, red, nullptr, nullptr, true);
 }
 
@@ -537,7 +606,8 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_bf16_kernel(const uint16_t* 
 // workgroup 0 writes the results to memory), which saves the finishing launch.
 __global__ __launch_bounds__(256) void bn_apply_fused_kernel(BnSumArgs p, unsigned nblocks, size_t chunks, const float* g,
                                                              const float* b, const uint16_t* res, uint16_t* y) {
-  __shared__ float red[256], s_mean[128], s_rstd[128];
+  __shared__ __align__(16) float red[1024];
+  __shared__ float s_mean[128], s_rstd[128];
   bn_finish<0, 256>(p, nblocks, red, s_mean, s_rstd, blockIdx.x == 0);
   __syncthreads();
   const uint32_t i32 = blockIdx.x * 256 + threadIdx.x;
@@ -561,7 +631,8 @@ __global__ __launch_bounds__(256) void bn_apply_fused_kernel(BnSumArgs p, unsign
 }
 __global__ __launch_bounds__(256) void bn_bwd_apply_fused_kernel(BnSumArgs p, unsigned nblocks, size_t chunks, const float* g,
                                                                  uint16_t* dx) {
-  __shared__ float red[256], s_db[128], s_dg[128];
+  __shared__ __align__(16) float red[1024];
+  __shared__ float s_db[128], s_dg[128];
   bn_finish<1, 256>(p, nblocks, red, s_db, s_dg, blockIdx.x == 0);
   __syncthreads();
   const uint32_t i32 = blockIdx.x * 256 + threadIdx.x;
@@ -681,22 +752,27 @@ bool al16(const void* p) { return !(((uintptr_t)p) & 15); }
 // LDS of the implicit-GEMM convolution: the filter as [produced channels rounded up to 32][9 * reduced + 8] bf16
 size_t conv_mfma_lds(int produced, int reduced) { return (size_t)((produced + 31) / 32 * 32) * (18 * reduced + 16); }
 constexpr size_t CONV_MFMA_LDS_MAX = 96 * 1024;
-template <int MODE, int K16, int NT, int GRP, bool LIN>
+// workgroups of the forward / stride-1 kernel for P output pixels: a workgroup keeps its filter for up to 4 tiles of
+// 128 pixels once there are more than 2048 of them
+long conv_mfma_blocks(long P) {
+  const long ntiles = (P + 127) / 128;
+  const long tpw = ntiles >= 8192 ? 4 : (ntiles >= 4096 ? 2 : 1);
+  return (ntiles + tpw - 1) / tpw;
+}
+template <int MODE, int K16, int NT, int GRP, bool LIN, bool STAT>
 int conv_mfma_launch_g(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   static bool raised[64] = {};    // per device: the attribute belongs to the device's copy of the kernel
+  lds += STAT ? CONV_STAT_LDS : 0;
   if (lds > 64 * 1024) {
     int dev = 0;
     PPLL_HIP(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64 || !raised[dev]) {
-      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE, K16, NT, GRP, LIN>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)CONV_MFMA_LDS_MAX));
+      PPLL_HIP(hipFuncSetAttribute((const void*)conv3x3_mfma_kernel<MODE, K16, NT, GRP, LIN, STAT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)(CONV_MFMA_LDS_MAX + CONV_STAT_LDS)));
       if (dev >= 0 && dev < 64) raised[dev] = true;
     }
   }
-  // a workgroup keeps its filter for up to 4 tiles of 128 pixels once there are more than 2048 of them
-  const long ntiles = (P + 127) / 128;
-  const long tpw = ntiles >= 8192 ? 4 : (ntiles >= 4096 ? 2 : 1);
-  hipLaunchKernelGGL((conv3x3_mfma_kernel<MODE, K16, NT, GRP, LIN>), dim3((unsigned)((ntiles + tpw - 1) / tpw)), dim3(256), lds, s, p);
+  hipLaunchKernelGGL((conv3x3_mfma_kernel<MODE, K16, NT, GRP, LIN, STAT>), dim3((unsigned)conv_mfma_blocks(P)), dim3(256), lds, s, p);
   PPLL_HIP(hipGetLastError());
   return PPLL_OK;
 }
@@ -707,9 +783,16 @@ int conv_mfma_launch_k(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   // linear tap addressing through a buffer descriptor: forward always, input gradient at stride 1; the source
   // tensor has to stay below 2^30 bytes
   const bool lin = (MODE == 0 || p.stride == 1) && (long)p.B * p.H * p.W * (16 * K16) * 2 < ((long)1 << 30);
+  if constexpr (MODE == 0) {
+    if (p.stat) {
+      if (produced <= 32)
+        return lin ? conv_mfma_launch_g<0, K16, 1, 1, true, true>(s, p, P, lds) : conv_mfma_launch_g<0, K16, 1, 1, false, true>(s, p, P, lds);
+      return lin ? conv_mfma_launch_g<0, K16, 2, 1, true, true>(s, p, P, lds) : conv_mfma_launch_g<0, K16, 2, 1, false, true>(s, p, P, lds);
+    }
+  }
   if (produced <= 32)
-    return lin ? conv_mfma_launch_g<MODE, K16, 1, 1, true>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 1, 1, false>(s, p, P, lds);
-  return lin ? conv_mfma_launch_g<MODE, K16, 2, 1, true>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 2, 1, false>(s, p, P, lds);
+    return lin ? conv_mfma_launch_g<MODE, K16, 1, 1, true, false>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 1, 1, false, false>(s, p, P, lds);
+  return lin ? conv_mfma_launch_g<MODE, K16, 2, 1, true, false>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 2, 1, false, false>(s, p, P, lds);
 }
 // k16 = reduced channels / 16: 1, 2, 3 or 4
 template <int MODE>
@@ -764,9 +847,14 @@ static int conv_dgrad_s2_launch(hipStream_t s, const ConvArgs& p, int k16, size_
 }
 
 int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, int H, int W, int Ci, int Co,
-                            int stride, void* y) {
-  ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr};
+                            int stride, void* y, float* stat, int* stat_blocks) {
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+  // The sums cost the kernel registers and ~25 % of its time at 16 channels; they pay where the BatchNorm's own pass
+  // over the tensor is mostly launch and ramp, i.e. on small tensors (measured: 9 % of the step at 128 x 16 x 16 x 32,
+  // 3 % at 1024 x 8 x 8 x 64, a loss at 1024 x 16 x 16 x 32 and above, where also 2048 partial rows have to be added up)
+  if (conv_mfma_blocks(P) > CONV_STAT_MAX_BLOCKS) stat = nullptr;
+  ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr, stat};
+  if (stat_blocks) *stat_blocks = stat ? (int)conv_mfma_blocks(P) : 0;
   const size_t lds = conv_mfma_lds(Co, Ci);
   void* prof = nullptr;   // algorithmic bytes: input, output and filter once
   PPLL_TRY(profile_begin(s, 2.0 * ((double)B * H * W * Ci + (double)P * Co + 9.0 * Ci * Co), &prof, 1));
@@ -777,7 +865,7 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
                               int stride, const void* dres, const void* ymask, void* dx) {
   ConvArgs p{(const uint16_t*)dy, (const uint16_t*)w, (uint16_t*)dx, B, H, W, Ci, Co, stride, (const uint16_t*)dres,
-             (const uint16_t*)ymask};
+             (const uint16_t*)ymask, nullptr};
   const long P = (long)B * H * W;
   const size_t lds = conv_mfma_lds(Ci, Co);
   const double Po = (double)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
@@ -1114,7 +1202,12 @@ static int bn_sums_launch(hipStream_t s, const BnSumArgs& p, int blocks, bool fi
 }
 // the apply kernel of a small tensor (at most 1024 workgroups) finishes the sums itself
 static bool bn_fused_finish(size_t chunks) { return (chunks + 255) / 256 <= 1024; }
-size_t bn_bf16_partial_floats(int rows, int C) { return (size_t)bn_blocks(rows, C) * 2 * C; }
+// room for the partials of the BatchNorm's own sums kernels or of the convolution that produced its input (one row of
+// pixels per BatchNorm row), whichever are more
+size_t bn_bf16_partial_floats(int rows, int C) {
+  const long a = bn_blocks(rows, C), b = conv_mfma_blocks(rows);
+  return (size_t)(a > b ? a : b) * 2 * C;
+}
 
 // The three helpers need channel counts that are multiples of 8, 16-byte aligned tensors and fewer than 2^31 elements.
 bool eltwise_bf16_ok(int dt, size_t elems, int C0, int C1, const void* a, const void* b, const void* c) {
@@ -1165,19 +1258,26 @@ int launch_bn_stats_bf16(hipStream_t s, const void* x, int rows, int C, float ep
 }
 
 // statistics and y = relu(bn(x) (+ res)) of a training step
+// ready_blocks > 0: `partials` already holds that many rows of sums, written by the convolution that produced x
 int launch_bn_train_fwd_bf16(hipStream_t s, const void* x, int rows, int C, float eps, float momentum, float* partials,
                              float* mean, float* rstd, float* run_mean, float* run_var, const float* g, const float* b,
-                             const void* res, void* y) {
+                             const void* res, void* y, int ready_blocks) {
   BnSumArgs p{};
   p.x = (const uint16_t*)x; p.rows = rows; p.C = C; p.partial = partials; p.eps = eps;
   p.momentum = momentum; p.out0 = mean; p.out1 = rstd; p.run_mean = run_mean; p.run_var = run_var;
   const size_t chunks = (size_t)rows * C / 8;
-  const int blocks = bn_blocks(rows, C);
-  if (!bn_fused_finish(chunks)) {
-    PPLL_TRY(bn_sums_launch<0>(s, p, blocks, true));
+  const int blocks = ready_blocks > 0 ? ready_blocks : bn_blocks(rows, C);
+  // every workgroup of the fused kernel adds up all partial rows itself: only worth it for few of both
+  if (!bn_fused_finish(chunks) || blocks > 256) {
+    if (ready_blocks > 0) {
+      hipLaunchKernelGGL(bn_finish_kernel<0>, dim3(1), dim3(1024), 0, s, p, (unsigned)blocks);
+      PPLL_HIP(hipGetLastError());
+    } else {
+      PPLL_TRY(bn_sums_launch<0>(s, p, blocks, true));
+    }
     return launch_bn_apply_bf16(s, x, rows, C, mean, rstd, g, b, res, y);
   }
-  PPLL_TRY(bn_sums_launch<0>(s, p, blocks, false));
+  if (ready_blocks <= 0) PPLL_TRY(bn_sums_launch<0>(s, p, blocks, false));
   hipLaunchKernelGGL(bn_apply_fused_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, p, (unsigned)blocks, chunks,
                      g, b, (const uint16_t*)res, (uint16_t*)y);
   PPLL_HIP(hipGetLastError());
