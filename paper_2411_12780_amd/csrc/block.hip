@@ -591,21 +591,32 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
     if (k == shapes.size()) { shapes.push_back({Hh, Ww, Ci, Co, st}); shape_jobs.emplace_back(); }
     shape_jobs[k].push_back({xin, dyp, dw});
   };
+  // An input-gradient convolution whose result is the output gradient of a BatchNorm also writes that BatchNorm's
+  // backward sums where it can (`ready` partial rows in `partials`, consumed by the launch_bn_bwd right behind it).
+  int ready = 0;
   for (int i = n - 1; i >= 0; --i) {
     const BasicBlockParams& p = rb_p[i];
     const BasicBlockDims& d = rb_d[i];
     BasicBlockActs& a = rb_a[i];
     const int rows = B * d.Ho * d.Wo;
     PPLL_TRY(launch_bn_bwd(s, gcur, block_out[i], a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, partials,
-                           grads + p.bn2_g, grads + p.bn2_b, a.d2));
+                           grads + p.bn2_g, grads + p.bn2_b, a.d2, ready));
+    ready = 0;
     defer(a.y1, a.d2, grads + p.conv2_w, d.Ho, d.Wo, d.Co, d.Co, 1);
-    PPLL_TRY(launch_conv3x3_dgrad(s, a.d2, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, nullptr, nullptr, r_t1));
+    const BnBwdSums bn1{a.y1, a.c1, a.mean1, a.rstd1, partials};
+    PPLL_TRY(launch_conv3x3_dgrad(s, a.d2, wptr(p.conv2_w), wdt(), dt, B, d.Ho, d.Wo, d.Co, d.Co, 1, nullptr, nullptr, r_t1, &bn1,
+                                  &ready));
     PPLL_TRY(launch_bn_bwd(s, r_t1, a.y1, a.c1, dt, rows, d.Co, a.mean1, a.rstd1, params + p.bn1_g, partials,
-                           grads + p.bn1_g, grads + p.bn1_b, a.d1));
+                           grads + p.bn1_g, grads + p.bn1_b, a.d1, ready));
+    ready = 0;
     defer(block_in[i], a.d1, grads + p.conv1_w, d.Hin, d.Win, d.Ci, d.Co, d.stride);
     if (i == 0 && !stem) break;   // the block input is the detached x_{j-1}
     if (d.stride == 1 && d.Ci == d.Co) {   // identity shortcut folded into the input gradient
-      PPLL_TRY(launch_conv3x3_dgrad(s, a.d1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, 1, gcur, block_out[i], gcur));
+      // the result is the output gradient of the second BatchNorm of the block before
+      BnBwdSums bn2{};
+      if (i > 0) bn2 = BnBwdSums{block_out[i - 1], rb_a[i - 1].c2, rb_a[i - 1].mean2, rb_a[i - 1].rstd2, partials};
+      PPLL_TRY(launch_conv3x3_dgrad(s, a.d1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, 1, gcur, block_out[i], gcur,
+                                    i > 0 ? &bn2 : nullptr, &ready));
     } else {
       PPLL_TRY(launch_conv3x3_dgrad(s, a.d1, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, nullptr, nullptr,
                                     gnext));

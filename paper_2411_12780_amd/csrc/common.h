@@ -199,8 +199,14 @@ int launch_copy_probe(hipStream_t s, const void* src, void* dst, size_t bytes);
 int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
                        int Co, int stride, void* y, float* stat = nullptr, int* stat_blocks = nullptr);
 // dx = dgrad(dy, w) (+ dres * (ymask > 0) when dres != null)
+// The BatchNorm whose output gradient a convolution's input gradient dx is: output y (ReLU mask), input x, saved
+// statistics, and room for the partial sums of its backward pass (bn_partial_floats of its shape).
+struct BnBwdSums { const void* y; const void* x; const float* mean; const float* rstd; float* partials; };
+// bn / stat_blocks (nullable): on return *stat_blocks is the number of partial rows of that BatchNorm's two backward
+// sums that the convolution wrote to bn->partials itself (0: none, launch_bn_bwd has to make its own pass)
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
-                         int Co, int stride, const void* dres, const void* ymask, void* dx);
+                         int Co, int stride, const void* dres, const void* ymask, void* dx, const BnBwdSums* bn = nullptr,
+                         int* stat_blocks = nullptr);
 // dw [9][ci_keep][Co]: the gradient for the first ci_keep input channels (all of them by default; fewer when
 // the caller padded x with zero channels)
 int launch_conv3x3_wgrad(hipStream_t s, const void* x, const void* dy, int dt, int B, int H, int W, int Ci,
@@ -238,9 +244,10 @@ int launch_bn_running_stats(hipStream_t s, const float* run_mean, const float* r
 int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const float* mean, const float* rstd,
                     const float* g, const float* b, const void* res, void* y);
 // dyh = dy * (y > 0); dx = bn'(dyh); dg = sum dyh*xhat; db = sum dyh
+// ready_blocks: rows of `partials` the convolution that produced dy has already filled (see launch_conv3x3_dgrad), else 0
 int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
                   const float* mean, const float* rstd, const float* g, float* partials, float* dg,
-                  float* db, void* dx);
+                  float* db, void* dx, int ready_blocks = 0);
 int bn_partial_floats(int rows, int C);
 // bf16 fast path (k_resnet_bf16.hip)
 bool conv_bf16_supported(int dt, int wdt, int Ci, int Co, const void* a, const void* b, const void* c);
@@ -253,7 +260,8 @@ bool conv_wgrad_bf16_ok(int Ci, int Co);
 int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, int H, int W, int Ci, int Co,
                             int stride, void* y, float* stat = nullptr, int* stat_blocks = nullptr);
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
-                              int stride, const void* dres, const void* ymask, void* dx);
+                              int stride, const void* dres, const void* ymask, void* dx, const BnBwdSums* bn = nullptr,
+                              int* stat_blocks = nullptr);
 int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int B, int H, int W, int Ci, int Co,
                               int stride, ReduceQueue& rq, float* dw, int ci_keep);
 size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, int stride);
@@ -274,7 +282,7 @@ int launch_bn_train_fwd_bf16(hipStream_t s, const void* x, int rows, int C, floa
 int launch_bn_apply_bf16(hipStream_t s, const void* x, int rows, int C, const float* mean, const float* rstd,
                          const float* g, const float* b, const void* res, void* y);
 int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void* x, int rows, int C, const float* mean,
-                       const float* rstd, const float* g, float* partials, float* dg, float* db, void* dx);
+                       const float* rstd, const float* g, float* partials, float* dg, float* db, void* dx, int ready_blocks = 0);
 int launch_gap_fwd(hipStream_t s, const void* x, int dt, int B, int HW, int C, void* pooled);
 int launch_gap_bwd(hipStream_t s, const void* dpooled, int dt, int B, int HW, int C, void* dx);
 

@@ -280,10 +280,16 @@ int launch_conv3x3_fwd(hipStream_t s, const void* x, const void* w, int wdt, int
 }
 
 int launch_conv3x3_dgrad(hipStream_t s, const void* dy, const void* w, int wdt, int dt, int B, int H, int W, int Ci,
-                         int Co, int stride, const void* dres, const void* ymask, void* dx) {
+                         int Co, int stride, const void* dres, const void* ymask, void* dx, const BnBwdSums* bn,
+                         int* stat_blocks) {
+  if (stat_blocks) *stat_blocks = 0;
   if (conv_bf16_supported(dt, wdt, Ci, Co, dy, w, dx) && conv_dgrad_bf16_ok(Ci, Co) && conv_pixels_fit(B, H, W) && stride <= 2 &&
-      !((((uintptr_t)dres) | ((uintptr_t)ymask)) & 15))
-    return launch_conv3x3_dgrad_bf16(s, dy, w, B, H, W, Ci, Co, stride, dres, ymask, dx);
+      !((((uintptr_t)dres) | ((uintptr_t)ymask)) & 15)) {
+    // the sums are only of use to the bf16 BatchNorm kernels (same partial layout)
+    const long rows = (long)B * H * W;
+    const bool want = bn && stat_blocks && rows >= 2 && bn_bf16_supported(dt, (int)rows, Ci, dx, bn->y, bn->x, nullptr);
+    return launch_conv3x3_dgrad_bf16(s, dy, w, B, H, W, Ci, Co, stride, dres, ymask, dx, want ? bn : nullptr, stat_blocks);
+  }
   size_t total = (size_t)B * H * W * Ci;
   hipLaunchKernelGGL(conv3x3_dgrad_kernel, dim3((total + 255) / 256), dim3(256), 0, s, dy, w, wdt, dt, B, H, W, Ci,
                      Co, stride, dres, ymask, dx);
@@ -380,9 +386,9 @@ int launch_bn_apply(hipStream_t s, const void* x, int dt, int rows, int C, const
 
 int launch_bn_bwd(hipStream_t s, const void* dy, const void* y, const void* x, int dt, int rows, int C,
                   const float* mean, const float* rstd, const float* g, float* partials, float* dg,
-                  float* db, void* dx) {
+                  float* db, void* dx, int ready_blocks) {
   if (bn_bf16_supported(dt, rows, C, dy, y, x, dx))
-    return launch_bn_bwd_bf16(s, dy, y, x, rows, C, mean, rstd, g, partials, dg, db, dx);
+    return launch_bn_bwd_bf16(s, dy, y, x, rows, C, mean, rstd, g, partials, dg, db, dx, ready_blocks);
   int chunks = (rows + BN_ROWS - 1) / BN_ROWS;
   size_t total = (size_t)rows * C;
   hipLaunchKernelGGL(bn_bwd_partial_kernel, dim3((C + 255) / 256, chunks), dim3(256), 0, s, dy, y, x, dt, rows, C, mean,

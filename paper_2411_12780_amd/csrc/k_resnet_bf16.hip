@@ -44,7 +44,11 @@ struct ConvArgs {
   int B, H, W, Ci, Co, stride;
   const uint16_t* dres;    // input gradient only: dx += dres * (ymask > 0)
   const uint16_t* ymask;
-  float* stat;             // forward with STAT: [workgroups][2][Co] per-channel sum and sum of squares of the stored outputs
+  float* stat;             // STAT: [workgroups][2][channels produced] partial sums for the BatchNorm next in line:
+                           //  forward: sum and sum of squares of the stored outputs;
+                           //  input gradient: the two backward sums of the BatchNorm whose output gradient dx is
+                           //  (sum dyh, sum dyh * xhat with dyh = dx * (bn_y > 0), xhat = (bn_x - bn_mean) * bn_rstd)
+  const uint16_t* bn_y; const uint16_t* bn_x; const float* bn_mean; const float* bn_rstd;
 };
 
 // One halving step of a butterfly sum over lanes `step` apart: of the N values a lane holds, it keeps one half
@@ -76,7 +80,9 @@ __device__ __forceinline__ void halfwave_sums(float (&v)[NV], int li) {
     v[0] += __shfl_xor(v[0], 1, 64);
   }
 }
-constexpr long CONV_STAT_MAX_BLOCKS = 512;    // the forward convolution sums its outputs for the BatchNorm up to this many workgroups
+// the forward convolution sums its outputs for the BatchNorm behind it up to this many workgroups; the input gradient
+// the backward sums of the BatchNorm before it up to fewer (at 512, 1024 x 8 x 8 x 64, it measured 5 % of the step slower)
+constexpr long CONV_STAT_MAX_BLOCKS = 512, CONV_BWD_STAT_MAX_BLOCKS = 256;
 constexpr int CONV_STAT_LDS = 4 * 2 * 2 * 32 * 4;   // [wave][sum kind][lane half][32] floats behind the filter
 
 // MODE 0: forward.  MODE 1: input gradient.  NO = channels produced, KC = 16 * K16 channels reduced.
@@ -89,7 +95,6 @@ constexpr int CONV_STAT_LDS = 4 * 2 * 2 * 32 * 4;   // [wave][sum kind][lane hal
 // run per lane over the workgroup's tiles, then over the lanes of a half-wave, then over the four waves.
 template <int MODE, int K16, int NT, int GRP, bool LIN, bool STAT>
 __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
-  static_assert(!STAT || MODE == 0, "statistics belong to the forward convolution");
   extern __shared__ __align__(16) char wl[];        // [NO rounded up to 32][9*KC] bf16, row stride RSW bytes
   constexpr int KC = 16 * K16;
   const int NO = MODE == 0 ? p.Co : p.Ci;
@@ -237,8 +242,23 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
           *reinterpret_cast<uint2*>(drow + c) = o;
           if (STAT) {
             const float r[4] = {lo_bf(o.x), hi_bf(o.x), lo_bf(o.y), hi_bf(o.y)};
+            if (MODE == 0) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { st0[16 * t + 4 * q + e] += r[e]; st1[16 * t + 4 * q + e] += r[e] * r[e]; }
+              for (int e = 0; e < 4; ++e) { st0[16 * t + 4 * q + e] += r[e]; st1[16 * t + 4 * q + e] += r[e] * r[e]; }
+            } else {
+              const uint2 by = *reinterpret_cast<const uint2*>(p.bn_y + (size_t)pix * NO + c);
+              const uint2 bx = *reinterpret_cast<const uint2*>(p.bn_x + (size_t)pix * NO + c);
+              const float4 mu = *reinterpret_cast<const float4*>(p.bn_mean + c), rs = *reinterpret_cast<const float4*>(p.bn_rstd + c);
+              const float yv[4] = {lo_bf(by.x), hi_bf(by.x), lo_bf(by.y), hi_bf(by.y)};
+              const float xv[4] = {lo_bf(bx.x), hi_bf(bx.x), lo_bf(bx.y), hi_bf(bx.y)};
+              const float mv[4] = {mu.x, mu.y, mu.z, mu.w}, rv[4] = {rs.x, rs.y, rs.z, rs.w};
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const float d = yv[e] > 0.f ? r[e] : 0.f;
+                st0[16 * t + 4 * q + e] += d;
+                st1[16 * t + 4 * q + e] += d * (xv[e] - mv[e]) * rv[e];
+              }
+            }
           }
         }
       }
@@ -783,12 +803,10 @@ int conv_mfma_launch_k(hipStream_t s, const ConvArgs& p, long P, size_t lds) {
   // linear tap addressing through a buffer descriptor: forward always, input gradient at stride 1; the source
   // tensor has to stay below 2^30 bytes
   const bool lin = (MODE == 0 || p.stride == 1) && (long)p.B * p.H * p.W * (16 * K16) * 2 < ((long)1 << 30);
-  if constexpr (MODE == 0) {
-    if (p.stat) {
-      if (produced <= 32)
-        return lin ? conv_mfma_launch_g<0, K16, 1, 1, true, true>(s, p, P, lds) : conv_mfma_launch_g<0, K16, 1, 1, false, true>(s, p, P, lds);
-      return lin ? conv_mfma_launch_g<0, K16, 2, 1, true, true>(s, p, P, lds) : conv_mfma_launch_g<0, K16, 2, 1, false, true>(s, p, P, lds);
-    }
+  if (p.stat) {
+    if (produced <= 32)
+      return lin ? conv_mfma_launch_g<MODE, K16, 1, 1, true, true>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 1, 1, false, true>(s, p, P, lds);
+    return lin ? conv_mfma_launch_g<MODE, K16, 2, 1, true, true>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 2, 1, false, true>(s, p, P, lds);
   }
   if (produced <= 32)
     return lin ? conv_mfma_launch_g<MODE, K16, 1, 1, true, false>(s, p, P, lds) : conv_mfma_launch_g<MODE, K16, 1, 1, false, false>(s, p, P, lds);
@@ -853,7 +871,8 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
   // over the tensor is mostly launch and ramp, i.e. on small tensors (measured: 9 % of the step at 128 x 16 x 16 x 32,
   // 3 % at 1024 x 8 x 8 x 64, a loss at 1024 x 16 x 16 x 32 and above, where also 2048 partial rows have to be added up)
   if (conv_mfma_blocks(P) > CONV_STAT_MAX_BLOCKS) stat = nullptr;
-  ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr, stat};
+  ConvArgs p{(const uint16_t*)x, (const uint16_t*)w, (uint16_t*)y, B, H, W, Ci, Co, stride, nullptr, nullptr, stat,
+             nullptr, nullptr, nullptr, nullptr};
   if (stat_blocks) *stat_blocks = stat ? (int)conv_mfma_blocks(P) : 0;
   const size_t lds = conv_mfma_lds(Co, Ci);
   void* prof = nullptr;   // algorithmic bytes: input, output and filter once
@@ -863,10 +882,16 @@ int launch_conv3x3_fwd_bf16(hipStream_t s, const void* x, const void* w, int B, 
 }
 
 int launch_conv3x3_dgrad_bf16(hipStream_t s, const void* dy, const void* w, int B, int H, int W, int Ci, int Co,
-                              int stride, const void* dres, const void* ymask, void* dx) {
-  ConvArgs p{(const uint16_t*)dy, (const uint16_t*)w, (uint16_t*)dx, B, H, W, Ci, Co, stride, (const uint16_t*)dres,
-             (const uint16_t*)ymask, nullptr};
+                              int stride, const void* dres, const void* ymask, void* dx, const BnBwdSums* bn,
+                              int* stat_blocks) {
   const long P = (long)B * H * W;
+  // sums for the BatchNorm that dx is the output gradient of: stride 1 only, small tensors only (as in the forward)
+  const bool sums = bn && bn->partials && stride == 1 && conv_mfma_blocks(P) <= CONV_BWD_STAT_MAX_BLOCKS && al16(bn->y) &&
+                    al16(bn->x) && al16(bn->mean) && al16(bn->rstd);
+  if (stat_blocks) *stat_blocks = sums ? (int)conv_mfma_blocks(P) : 0;
+  ConvArgs p{(const uint16_t*)dy, (const uint16_t*)w, (uint16_t*)dx, B, H, W, Ci, Co, stride, (const uint16_t*)dres,
+             (const uint16_t*)ymask, sums ? bn->partials : nullptr, sums ? (const uint16_t*)bn->y : nullptr,
+             sums ? (const uint16_t*)bn->x : nullptr, sums ? bn->mean : nullptr, sums ? bn->rstd : nullptr};
   const size_t lds = conv_mfma_lds(Ci, Co);
   const double Po = (double)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   void* prof = nullptr;   // algorithmic bytes: dy, dx and filter once, plus the shortcut gradient and its mask
@@ -1293,21 +1318,27 @@ int launch_bn_apply_bf16(hipStream_t s, const void* x, int rows, int C, const fl
   return PPLL_OK;
 }
 
+// ready_blocks > 0: `partials` already holds that many rows of the two sums, written by the convolution that produced dy
 int launch_bn_bwd_bf16(hipStream_t s, const void* dy, const void* y, const void* x, int rows, int C, const float* mean,
-                       const float* rstd, const float* g, float* partials, float* dg, float* db, void* dx) {
+                       const float* rstd, const float* g, float* partials, float* dg, float* db, void* dx, int ready_blocks) {
   BnSumArgs p{};
   p.x = (const uint16_t*)x; p.dy = (const uint16_t*)dy; p.y = (const uint16_t*)y; p.rows = rows; p.C = C;
   p.mean = mean; p.rstd = rstd; p.partial = partials; p.out0 = db; p.out1 = dg;
   const size_t chunks = (size_t)rows * C / 8;
-  const int blocks = bn_blocks(rows, C);
-  if (bn_fused_finish(chunks)) {
-    PPLL_TRY(bn_sums_launch<1>(s, p, blocks, false));
+  const int blocks = ready_blocks > 0 ? ready_blocks : bn_blocks(rows, C);
+  if (bn_fused_finish(chunks) && blocks <= 256) {
+    if (ready_blocks <= 0) PPLL_TRY(bn_sums_launch<1>(s, p, blocks, false));
     hipLaunchKernelGGL(bn_bwd_apply_fused_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, p, (unsigned)blocks,
                        chunks, g, (uint16_t*)dx);
     PPLL_HIP(hipGetLastError());
     return PPLL_OK;
   }
-  PPLL_TRY(bn_sums_launch<1>(s, p, blocks, true));
+  if (ready_blocks > 0) {
+    hipLaunchKernelGGL(bn_finish_kernel<1>, dim3(1), dim3(1024), 0, s, p, (unsigned)blocks);
+    PPLL_HIP(hipGetLastError());
+  } else {
+    PPLL_TRY(bn_sums_launch<1>(s, p, blocks, true));
+  }
   hipLaunchKernelGGL(bn_bwd_apply_bf16_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s,
                      (const uint16_t*)dy, (const uint16_t*)y, (const uint16_t*)x, chunks, C, rows, mean, rstd, g, dg, db,
                      (uint16_t*)dx);
