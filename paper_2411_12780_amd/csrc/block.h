@@ -20,7 +20,7 @@ struct TensorDesc {
 struct EncoderParams {   // element offsets into the blob
   size_t ln1_g, ln1_b, qkv_w, qkv_b, proj_w, proj_b, ln2_g, ln2_b, fc1_w, fc1_b, fc2_w, fc2_b;
 };
-struct EncoderActs {     // saved by the forward for the backward
+struct EncoderActs {     // saved by the forward for the backward (h: gelu' at the MLP pre-activation, gl: its gelu)
   void *u1, *qkv, *att, *x1, *u2, *h, *gl, *x2;
   float *mean1, *rstd1, *mean2, *rstd2, *lse;
 };

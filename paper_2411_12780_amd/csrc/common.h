@@ -73,8 +73,10 @@ __device__ __forceinline__ float wave_max(float v) {
 // operands so that one routine covers Y = X W, dX = dY W^T and dW = X^T dY.
 enum Epilogue : int {
   EPI_NONE = 0,   // C = acc (+bias) (+residual)
-  EPI_GELU = 1,   // C = acc + bias (pre-activation), C2 = gelu(C)
-  EPI_DGELU = 2   // C = acc * gelu'(aux)   (aux = saved pre-activation)
+  // GELU of h = acc + bias: C2 = gelu(h) and C = gelu'(h), the factor the backward pass multiplies by (h itself is
+  // needed nowhere else, and the forward has the normal CDF and density at hand anyway)
+  EPI_GELU = 1,
+  EPI_DGELU = 2   // C = acc * aux   (aux = the gelu'(h) saved by EPI_GELU)
 };
 struct GemmArgs {
   const void* A; int a_dt; long a_sm, a_sk;   // A(m,k) = A[m*a_sm + k*a_sk]
@@ -85,7 +87,7 @@ struct GemmArgs {
   const void* residual; int r_dt; long ldr;   // [M,N] or null
   int epilogue;
   void* C2;                                   // EPI_GELU second output (c_dt, ldc)
-  const void* aux; int aux_dt; long ldaux;    // EPI_DGELU saved pre-activation
+  const void* aux; int aux_dt; long ldaux;    // EPI_DGELU: the saved GELU derivative
   float* splitk_ws; size_t splitk_floats;     // optional scratch for split-K partial sums
   float* colsum;                              // optional: out[n] = sum_k B(k,n) (bias gradient of a dW product);
                                               // honoured only by the MFMA kernel, see gemm_fuses_colsum()

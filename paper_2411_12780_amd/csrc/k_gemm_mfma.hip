@@ -19,7 +19,7 @@
 //
 // The MFMA is issued with the B tile as its first operand, i.e. it produces C
 // transposed: a lane then holds 4 consecutive columns of one C row, so bias,
-// residual, saved pre-activation and the output move as 8/16-byte vectors.
+// residual, saved GELU derivative and the output move as 8/16-byte vectors.
 //
 // Split-K (weight gradients: tiny outputs, reduction over all tokens): every
 // split writes its fp32 partial tile, a second kernel adds the splits in a
@@ -70,8 +70,6 @@ __device__ __forceinline__ void cdf_pdf(float h, float& cdf, float& pdf) {
   cdf = 0.5f * (1.0f + copysignf(erf_abs, h));
   pdf = 0.39894228040143268f * ex;
 }
-__device__ __forceinline__ float gelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return h * c; }
-__device__ __forceinline__ float dgelu_fast(float h) { float c, d; cdf_pdf(h, c, d); return c + h * d; }
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
 // LDS layout of an operand tile, [row][64 k], chosen by how the tile is written.  Measured on the chip
@@ -337,7 +335,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
 
   // Epilogue through LDS: the accumulators (lane = one C row, 4 consecutive columns per group)
   // are laid down as an fp32 tile, then every thread takes 8 consecutive columns of a row, so
-  // bias / residual / saved pre-activation are read and C is written in full 128-column rows.
+  // bias / residual / saved GELU derivative are read and C is written in full 128-column rows.
   // What the write-out needs from memory is requested first, so it arrives during the staging.
   constexpr int NPASS = TM / 16;
   const int prow = tid >> 4, c8 = (tid & 15) * 8, n = n0 + c8;
@@ -407,9 +405,9 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
     if (has_aux) {
       const uint32_t* w = reinterpret_cast<const uint32_t*>(&auxv[pass]);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        v[2 * e] *= dgelu_fast(__uint_as_float(w[e] << 16));
-        v[2 * e + 1] *= dgelu_fast(__uint_as_float(w[e] & 0xffff0000u));
+      for (int e = 0; e < 4; ++e) {   // the saved GELU derivative
+        v[2 * e] *= __uint_as_float(w[e] << 16);
+        v[2 * e + 1] *= __uint_as_float(w[e] & 0xffff0000u);
       }
     }
     if (out_f32) {
@@ -419,14 +417,23 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
       buf_store16(rsC, ok ? off + 16 : OOB, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
     } else {
       const int off = ok ? (int)(((long)m * p.ldc) * 2) + ncol2 : OOB;
-      uint4 o;
-      o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]); o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
-      buf_store16(rsC, off, o);
-      if (p.epilogue == EPI_GELU) {
-        uint4 g;
-        g.x = pack_bf16x2(gelu_fast(v[0]), gelu_fast(v[1])); g.y = pack_bf16x2(gelu_fast(v[2]), gelu_fast(v[3]));
-        g.z = pack_bf16x2(gelu_fast(v[4]), gelu_fast(v[5])); g.w = pack_bf16x2(gelu_fast(v[6]), gelu_fast(v[7]));
+      if (p.epilogue == EPI_GELU) {   // C2 = gelu(h), C = gelu'(h) from one evaluation of the normal CDF and density
+        float gl[8], dg[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          float cdf, pdf;
+          cdf_pdf(v[e], cdf, pdf);
+          gl[e] = v[e] * cdf; dg[e] = cdf + v[e] * pdf;
+        }
+        uint4 o, g;
+        o.x = pack_bf16x2(dg[0], dg[1]); o.y = pack_bf16x2(dg[2], dg[3]); o.z = pack_bf16x2(dg[4], dg[5]); o.w = pack_bf16x2(dg[6], dg[7]);
+        g.x = pack_bf16x2(gl[0], gl[1]); g.y = pack_bf16x2(gl[2], gl[3]); g.z = pack_bf16x2(gl[4], gl[5]); g.w = pack_bf16x2(gl[6], gl[7]);
+        buf_store16(rsC, off, o);
         buf_store16(rsC2, off, g);
+      } else {
+        uint4 o;
+        o.x = pack_bf16x2(v[0], v[1]); o.y = pack_bf16x2(v[2], v[3]); o.z = pack_bf16x2(v[4], v[5]); o.w = pack_bf16x2(v[6], v[7]);
+        buf_store16(rsC, off, o);
       }
     }
   }

@@ -68,10 +68,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmArgs g) {
       if (g.residual) v += ld_f(g.residual, (size_t)((long)m * g.ldr + n), g.r_dt);
       size_t o = (size_t)((long)m * g.ldc + n);
       if (g.epilogue == EPI_GELU) {
-        st_f(g.C, o, v, g.c_dt);
+        st_f(g.C, o, dgelu_f(v), g.c_dt);
         st_f(g.C2, o, gelu_f(v), g.c_dt);
       } else if (g.epilogue == EPI_DGELU) {
-        st_f(g.C, o, v * dgelu_f(ld_f(g.aux, (size_t)((long)m * g.ldaux + n), g.aux_dt)), g.c_dt);
+        st_f(g.C, o, v * ld_f(g.aux, (size_t)((long)m * g.ldaux + n), g.aux_dt), g.c_dt);
       } else {
         st_f(g.C, o, v, g.c_dt);
       }
