@@ -665,23 +665,51 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
   float* dzs = zs + HEAD_ROWS * D;              // [4][D] gradient at the LayerNorm output
   float* dl = dzs + HEAD_ROWS * D;              // [4][C] logits, then dlogits
   float* lossw = dl + HEAD_ROWS * C;            // [4]
+  // Everything that is read once per class or per column inside the dependent chains below comes from LDS: a global
+  // load in such a chain (the bias of class c behind the c-th dot product, the LayerNorm scale behind a column of
+  // dz) stalls its wave for a full memory latency each time (measured: 24.9 -> 21.3 us at 128 rows of width 384).
+  const bool ln = ln_g != nullptr;
+  float* bs = lossw + HEAD_ROWS;                // [C] head bias
+  float* lng = bs + C;                          // [D] LayerNorm scale, [D] shift (unused without LayerNorm)
+  float* lnb = lng + D;
+  // copies with eight loads in flight per thread
+  auto stage_in = [&](float* dst, const float* src, int n) {
+    for (int i0 = threadIdx.x; i0 < n; i0 += 8 * HEAD_THREADS) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { const int i = i0 + u * HEAD_THREADS; v[u] = i < n ? src[i] : 0.f; }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { const int i = i0 + u * HEAD_THREADS; if (i < n) dst[i] = v[u]; }
+    }
+  };
+  stage_in(bs, bias, C);
+  if (ln) { stage_in(lng, ln_g, D); stage_in(lnb, ln_b, D); }
   // the head weight, read 2 C times per row, comes from LDS when there is room for it
   if (w_in_lds) {
-    float* wl = lossw + HEAD_ROWS;
-    for (int i = threadIdx.x; i < D * C; i += HEAD_THREADS) wl[i] = W[i];
-    __syncthreads();
+    float* wl = lnb + D;
+    stage_in(wl, W, D * C);
     W = wl;
   }
+  __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int b = blockIdx.x * HEAD_ROWS + wave;
-  const bool live = b < B, ln = ln_g != nullptr;
+  const bool live = b < B;
+  const int y = live ? labels[b] : 0;           // asked for early, used after the logits
   float* xr = xh + wave * D; float* zr = zs + wave * D; float* dzr = dzs + wave * D; float* lr = dl + wave * C;
   float rs = 0.f;
   if (live) {
     const size_t base = (size_t)b * xs;
+    // the row comes in with up to eight loads in flight per lane
+    for (int d0 = lane; d0 < D; d0 += 8 * 64) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { const int d = d0 + 64 * u; v[u] = d < D ? ld_f(x, base + d, dt) : 0.f; }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { const int d = d0 + 64 * u; if (d < D) xr[d] = v[u]; }
+    }
     if (ln) {
       float s = 0.f;
-      for (int d = lane; d < D; d += 64) { const float v = ld_f(x, base + d, dt); xr[d] = v; s += v; }
+      for (int d = lane; d < D; d += 64) s += xr[d];
       const float mu = wave_sum(s) / D;
       float q = 0.f;
       for (int d = lane; d < D; d += 64) { const float c = xr[d] - mu; q += c * c; }
@@ -689,17 +717,17 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
       for (int d = lane; d < D; d += 64) {
         const float h = (xr[d] - mu) * rs;
         xr[d] = h;
-        zr[d] = round_to(h * ln_g[d] + ln_b[d], dt);
+        zr[d] = round_to(h * lng[d] + lnb[d], dt);
       }
     } else {
-      for (int d = lane; d < D; d += 64) { const float v = ld_f(x, base + d, dt); xr[d] = 0.f; zr[d] = v; }
+      for (int d = lane; d < D; d += 64) { zr[d] = xr[d]; xr[d] = 0.f; }
     }
     wave_sync();
     for (int c = 0; c < C; ++c) {
       float a = 0.f;
       for (int d = lane; d < D; d += 64) a += zr[d] * W[(size_t)d * C + c];
       a = wave_sum(a);
-      if (lane == 0) lr[c] = a + bias[c];
+      if (lane == 0) lr[c] = a + bs[c];
     }
     wave_sync();
     float mx = -INFINITY;
@@ -708,7 +736,6 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
     float se = 0.f;
     for (int c = lane; c < C; c += 64) se += expf(lr[c] - mx);
     const float lse = mx + logf(wave_sum(se));
-    const int y = labels[b];
     const bool ok = y >= 0 && y < C;
     if (!ok && lane == 0) *flag = 1;
     const float mine = ok ? lse - lr[y] : 0.f;
@@ -723,7 +750,7 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
       a = round_to(a, dt);
       dzr[d] = a;
       if (ln) {
-        const float dyh = a * ln_g[d];
+        const float dyh = a * lng[d];
         s1 += dyh; s2 += dyh * xr[d];
       } else {
         st_f(dcls, (size_t)b * D + d, a, dt);
@@ -732,7 +759,7 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
     if (ln) {
       s1 = wave_sum(s1) / D; s2 = wave_sum(s2) / D;
       for (int d = lane; d < D; d += 64)
-        st_f(dcls, (size_t)b * D + d, rs * (dzr[d] * ln_g[d] - s1 - xr[d] * s2), dt);
+        st_f(dcls, (size_t)b * D + d, rs * (dzr[d] * lng[d] - s1 - xr[d] * s2), dt);
     }
   } else {
     for (int d = lane; d < D; d += 64) { xr[d] = 0.f; zr[d] = 0.f; dzr[d] = 0.f; }
@@ -775,7 +802,7 @@ size_t vit_head_partial_floats(int B, int D, int C) {
   return (size_t)((B + HEAD_ROWS - 1) / HEAD_ROWS) * ((size_t)D * C + C + 2 * D + 1);
 }
 static size_t vit_head_lds(int D, int C, bool with_w) {
-  return ((size_t)3 * HEAD_ROWS * D + HEAD_ROWS * C + HEAD_ROWS + (with_w ? (size_t)D * C : 0)) * sizeof(float);
+  return ((size_t)3 * HEAD_ROWS * D + HEAD_ROWS * C + HEAD_ROWS + C + 2 * D + (with_w ? (size_t)D * C : 0)) * sizeof(float);
 }
 bool vit_head_fused_ok(int D, int C) { return vit_head_lds(D, C, false) <= 64 * 1024; }
 
