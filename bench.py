@@ -70,7 +70,7 @@ def measured_traffic(workload: str):
 
 
 def bench_pipeline(args, torch, P, synth, dev) -> int:
-    """configs[4]: the 12-layer ViT as 4 blocks of 3 layers on 4 HIP streams, depth-2 device queues
+    """The pipeline workload: the 12-layer ViT as 4 blocks of 3 layers on 4 HIP streams, depth-2 device queues
     (vit_lpp12: as 12 blocks of one layer on 12 streams).  A step is one batch entering the pipeline;
     timing is steady state (queues full)."""
     if args.workload == "vit_lpp12":

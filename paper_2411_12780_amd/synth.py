@@ -24,16 +24,16 @@ _VIT_STAGE = dict(arch=VIT, precision=BF16, input_kind=IMAGE, batch=128, num_cla
                   beta1=0.9, beta2=0.999, adam_eps=1e-8, ln_eps=1e-6, lr=1e-3)
 
 WORKLOADS = {
-    # configs[0]: tiny fp32 ViT block, one plain SGD step
+    # the small fp32 case the CPU oracle finishes in seconds: tiny ViT block, one plain SGD step
     "vit_tiny_fp32": dict(arch=VIT, precision=FP32, input_kind=IMAGE, batch=8, num_classes=10,
                           img_h=32, img_w=32, img_c=3, patch=4, tokens=65, dim=64, heads=4,
                           mlp_dim=128, depth=2, aux_depth=0, optimizer=SGD, momentum=0.0,
                           nesterov=0, weight_decay=0.0, ln_eps=1e-6, lr=0.01),
-    # configs[1]: one of 4 blocks of a 12-layer ViT
+    # the headline workload: one of 4 blocks of a 12-layer ViT
     "vit_stage_bf16": dict(_VIT_STAGE),
-    # blocks 2..4 of configs[4]: same stage fed with token activations
+    # blocks 2..4 of the 4-block pipeline: same stage fed with token activations
     "vit_stage_act_bf16": dict(_VIT_STAGE, input_kind=ACTIVATION),
-    # configs[2]: ResNet stage (Section 4.1 optimizer: Nesterov 0.9, L2 1e-4, lr 0.01)
+    # ResNet stage at batch 128 (Section 4.1 optimizer: Nesterov 0.9, L2 1e-4, lr 0.01)
     "resnet_stage_bf16": dict(arch=RESNET, precision=BF16, input_kind=ACTIVATION, batch=128,
                               num_classes=10, channels=32, height=16, width=16,
                               n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
@@ -69,7 +69,7 @@ WORKLOADS = {
                                  num_classes=10, channels=64, height=8, width=8, transition_block=1,
                                  n_basic_blocks=5, aux_channels=64, optimizer=SGD, momentum=0.9,
                                  nesterov=1, weight_decay=1e-4, bn_eps=1e-5, bn_momentum=0.1, lr=0.01),
-    # configs[3]: STL-10-shaped ViT stage
+    # STL-10-shaped ViT stage (96 x 96 images)
     "vit_large_image_bf16": dict(_VIT_STAGE, batch=64, img_h=96, img_w=96, patch=8, tokens=145),
 }
 
