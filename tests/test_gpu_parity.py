@@ -308,6 +308,13 @@ def test_resnet_bf16_16_channels_ragged():
     run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
 
 
+def test_resnet_bf16_48_channels():
+    # 48 channels: three 16-channel reduction steps and one and a half 32-channel output tiles in the matrix-core
+    # convolutions; BatchNorm and weight gradient take the run-time-typed kernels at this width
+    wl = synth.workload("resnet_stage_bf16", n_basic_blocks=2, batch=6, height=8, width=8, channels=48, aux_channels=48)
+    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+
+
 @pytest.mark.parametrize("channels,height,width,batch", [(32, 8, 8, 5), (32, 4, 32, 3), (16, 2, 16, 300), (64, 4, 8, 2)])
 def test_resnet_bf16_tiled_weight_gradient_shapes(channels, height, width, batch):
     # the 16x16x32 matrix-core weight gradient: rows of 8, 16 and 32 pixels, 1 to 4 channel tiles, fewer
