@@ -253,6 +253,14 @@ def test_vit_bf16_token_counts_at_tile_edges(tokens):
     run_case(wl, steps=1)
 
 
+@pytest.mark.parametrize("tokens,dim,heads", [(20, 128, 4), (65, 96, 1)])
+def test_vit_bf16_attention_shapes_outside_the_matrix_core_kernel(tokens, dim, heads):
+    # a head dimension other than 64 (32, 96): the run-time-typed attention kernels on bf16 tensors
+    wl = synth.workload("vit_stage_act_bf16", batch=2, tokens=tokens, dim=dim, heads=heads, mlp_dim=2 * dim, depth=1,
+                        aux_depth=1)
+    run_case(wl, steps=1)
+
+
 def test_resnet_bf16_one_block_full_activation_size():
     run_case(synth.workload("resnet_stage_bf16", n_basic_blocks=1), steps=1, check_bn=True)
 
