@@ -2,20 +2,22 @@
 // accumulation in v_mfma_f32_32x32x16_bf16, operands staged through LDS.
 //
 // One 256-thread workgroup (4 waves, 2 x 2) owns a 128 x 128 output tile and
-// walks K in steps of 64; each wave owns 64 x 64 = 2 x 2 MFMA tiles.  Both
-// operands live in LDS as [row][k] with k contiguous, which is what an MFMA
-// operand fragment wants (a lane holds 8 consecutive k of one row).  An operand
-// whose k is contiguous in memory (activations in Y = X W^T-style products, the
-// [in,out] weight in dX = dY W^T) is copied with 16-byte loads; an operand whose
-// other index is contiguous (the [in,out] weight in Y = X W, both operands of
-// dW = X^T dY) is transposed in registers on the way in, so no transposed copies
-// of weights or activations exist in HBM.
+// walks K in steps of 64; each wave owns 64 x 64 = 2 x 2 MFMA tiles.  An MFMA
+// operand fragment is 8 consecutive k of one row per lane.  An operand whose k is
+// contiguous in memory (activations in Y = X W^T-style products, the [in,out]
+// weight in dX = dY W^T) lies in LDS as [row][k] and a fragment is one 16-byte
+// read.  An operand whose other index is contiguous (the [in,out] weight in
+// Y = X W, both operands of dW = X^T dY) lies in LDS as it lies in memory, [k][row],
+// and the fragment comes out of two transposing LDS reads (ds_read_b64_tr_b16: 16
+// lanes hand in the addresses of a 16 x 4 block of 16-bit elements and get it back
+// transposed), so no transposed copies of weights or activations exist in HBM and
+// no lane shuffles happen on the way in: every tile is copied with 16-byte loads
+// and 16-byte LDS stores.
 //
-// The 16-byte k-granules of an LDS row are permuted by an XOR with row bits, and
-// a tile written by the transposing loader also pads its rows (160 bytes apart):
-// each operand tile gets the layout for which the fragment reads (ds_read_b128,
-// 32 rows x 2 granules per wave) are free of bank conflicts and its stores as
-// cheap as they get (timed with a micro-benchmark of the two access patterns).
+// The 16-byte k-granules of a [row][k] tile are permuted by an XOR with row bits;
+// a [k][row] tile has its k rows 320 bytes apart: with these the fragment reads
+// and the stores run at the rate of linear ones (timed with a micro-benchmark of
+// the access patterns).
 //
 // The MFMA is issued with the B tile as its first operand, i.e. it produces C
 // transposed: a lane then holds 4 consecutive columns of one C row, so bias,
@@ -72,21 +74,27 @@ __device__ __forceinline__ void cdf_pdf(float h, float& cdf, float& pdf) {
 }
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
-// LDS layout of an operand tile, [row][64 k], chosen by how the tile is written.  Measured on the chip
-// (16 waves of one compute unit issuing one access pattern; cycles per wave instruction, a linear
-// ds_read_b128 takes 4.1 and a linear ds_write_b64 6.2):
-//  - copied with 16-byte stores (k contiguous in memory): rows 128 bytes apart, the 16-byte granule
-//    index XORed with (row/2)%8: fragment reads 4.1, stores as fast as linear ones;
-//  - written by the transposing loader (8-byte stores, 8 rows per thread): rows 160 bytes apart,
-//    granule index XORed with (row/16)%8: fragment reads 4.1, stores 8.0.  (At 144 bytes per row,
-//    which a model of 64 independent 4-byte banks calls conflict-free, the reads took 8.0; the
-//    first layout would serialise the transposing stores 8-fold.)
-template <bool TR> struct TileLayout {
-  static constexpr int ROW = TR ? 160 : 128;
-  static __device__ __forceinline__ int off(int row, int granule16) {
-    return TR ? row * 160 + ((granule16 ^ ((row >> 4) & 7)) << 4) : row * 128 + ((granule16 ^ ((row >> 1) & 7)) << 4);
-  }
+// LDS layout of an operand tile.  Measured on the chip (16 waves of one compute unit issuing one access pattern;
+// units per wave instruction: a linear ds_read_b128 takes 4.1, a linear ds_read_b64 2.4, a linear ds_write_b128 13):
+//  - [row][64 k] (k contiguous in memory): rows 128 bytes apart, the 16-byte granule index XORed with (row/2)%8:
+//    fragment reads 4.1, stores as fast as linear ones;
+//  - [64 k][128 rows] (row index contiguous in memory): k rows TR_PITCH = 320 bytes apart: the two transposing
+//    8-byte reads of a fragment take 2.4 each (4.0 at 288 or 384 bytes, 8.0 at 256), the stores are 256-byte
+//    rows.  (The earlier layout, transposed in registers on the way in, [row][k] with rows 160 bytes apart, paid
+//    8.0 per 8-byte store, eight of them and sixteen byte permutes per thread and k-step.)
+constexpr int TR_PITCH = 320;
+struct RowMajorTile {   // [row][64 k]
+  static __device__ __forceinline__ int off(int row, int granule16) { return row * 128 + ((granule16 ^ ((row >> 1) & 7)) << 4); }
 };
+constexpr int tile_bytes(bool tr, int rows) { return tr ? BK * TR_PITCH : rows * 128; }
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+// 4 consecutive k of one row out of a [k][row] tile: lane r of a 16-lane group hands in the address of 4 rows
+// (4 (r % 4) ..) at k row r / 4 and receives row r of the group's 16 at those four k rows
+__device__ __forceinline__ uint2 lds_read_tr(const char* p) {
+  const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p);
+  return __builtin_bit_cast(uint2, v);
+}
 
 // ---- Buffer addressing.  Operands, outputs and epilogue inputs are reached through raw buffer
 // descriptors: a load whose byte offset lies beyond the buffer returns 0 and a store there is
@@ -110,22 +118,21 @@ __device__ __forceinline__ void buf_store16(__amdgpu_buffer_rsrc_t r, int off, u
 }
 
 // One operand tile (ROWS x 64) on its way from memory to LDS, as seen by one thread.
-//  direct (k contiguous in memory): ROWS/32 pieces of 8 bf16; piece i is row (tid + 256 i)/8,
-//    k-granule tid%8.
-//  transposed (row index contiguous): thread (mg = tid%16, kg = tid/16) takes rows 8 mg..+7 at
-//    k = 4 kg..+3, four 16-byte loads, and turns them into eight 8-byte LDS writes.
+//  [row][k] (k contiguous in memory): ROWS/32 pieces of 8 bf16; piece i is row (tid + 256 i)/8, k-granule tid%8.
+//  [k][row] (row index contiguous; ROWS = 128): 4 pieces; piece j is k row tid/16 + 16 j, rows 8 (tid%16) .. +7.
 template <bool TR, int ROWS>
 struct OperandLoader {
+  static_assert(!TR || ROWS == 128, "a [k][row] tile is 128 rows wide");
   static constexpr int NP = TR ? 4 : ROWS / 32;
   int off[NP];      // byte offset of each piece at k = 0 of the thread's k-range; OOB_BASE if its row does not exist
   int kl;           // first k (within a tile) of the thread's pieces
-  int ld2;          // transposed: bytes between consecutive k
+  int ld2;          // [k][row]: bytes between consecutive k
   __device__ __forceinline__ void init(long ld, int row0, int nrows, int tid) {
     if (TR) {
-      const int mg = tid & 15, kg = tid >> 4, row = row0 + mg * 8;
-      kl = kg * 4; ld2 = (int)(ld * 2);
+      const int row = row0 + (tid & 15) * 8;
+      kl = tid >> 4; ld2 = (int)(ld * 2);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) off[j] = row < nrows ? (int)(((long)(kl + j) * ld + row) * 2) : OOB_BASE;
+      for (int j = 0; j < 4; ++j) off[j] = row < nrows ? (int)(((long)(kl + 16 * j) * ld + row) * 2) : OOB_BASE;
     } else {
       kl = (tid & 7) * 8; ld2 = 0;
 #pragma unroll
@@ -140,37 +147,27 @@ struct OperandLoader {
     if (TR) {
       const int step = k0 * ld2;
 #pragma unroll
-      for (int j = 0; j < 4; ++j) r[j] = buf_load16(rsrc, (k0 + kl + j < kend) ? off[j] + step : OOB);
+      for (int j = 0; j < 4; ++j) r[j] = buf_load16(rsrc, (k0 + kl + 16 * j < kend) ? off[j] + step : OOB);
     } else {
       const bool kin = k0 + kl < kend;
 #pragma unroll
       for (int i = 0; i < NP; ++i) r[i] = buf_load16(rsrc, kin ? off[i] + 2 * k0 : OOB);
     }
   }
-  // quarter q (0..3) of the thread's LDS writes of one tile
+  // piece q (0..3) of the thread's LDS writes of one tile
   __device__ __forceinline__ void store_part(char* lds, int tid, const uint4 (&r)[4], int q) const {
     if (TR) {
-      const int mg = tid & 15, kg = tid >> 4;
-      const uint32_t w0 = reinterpret_cast<const uint32_t*>(&r[0])[q], w1 = reinterpret_cast<const uint32_t*>(&r[1])[q];
-      const uint32_t w2 = reinterpret_cast<const uint32_t*>(&r[2])[q], w3 = reinterpret_cast<const uint32_t*>(&r[3])[q];
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const uint32_t sel = h ? 0x07060302u : 0x05040100u;
-        uint2 o;
-        o.x = __builtin_amdgcn_perm(w1, w0, sel);   // k, k+1 of row 8 mg + 2 q + h
-        o.y = __builtin_amdgcn_perm(w3, w2, sel);   // k+2, k+3
-        *reinterpret_cast<uint2*>(lds + TileLayout<true>::off(mg * 8 + 2 * q + h, kg >> 1) + (kg & 1) * 8) = o;
-      }
+      *reinterpret_cast<uint4*>(lds + (kl + 16 * q) * TR_PITCH + (tid & 15) * 16) = r[q];
     } else if (q < NP) {
       const int c = tid + 256 * q;
-      *reinterpret_cast<uint4*>(lds + TileLayout<false>::off(c >> 3, c & 7)) = r[q];
+      *reinterpret_cast<uint4*>(lds + RowMajorTile::off(c >> 3, c & 7)) = r[q];
     }
   }
 };
 
 constexpr int STAGE_LD = BN + 4;                      // fp32 staging tile of the epilogue, padded row
 // one stage of both operand tiles; two stages, or the epilogue's staging tile if that is larger
-constexpr int oper_bytes(bool at, bool bt, int tm) { return tm * TileLayout<false>::ROW + (at ? tm * 32 : 0) + BN * TileLayout<false>::ROW + (bt ? BN * 32 : 0); }
+constexpr int oper_bytes(bool at, bool bt, int tm) { return tile_bytes(at, tm) + tile_bytes(bt, BN); }
 constexpr int lds_bytes(bool at, bool bt, int tm) {
   return 2 * oper_bytes(at, bt, tm) > tm * STAGE_LD * 4 ? 2 * oper_bytes(at, bt, tm) : tm * STAGE_LD * 4;
 }
@@ -186,7 +183,7 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
   static_assert(TM == 128 || (TM == 64 && !AT), "64-row tiles are for the direct A loader");
   constexpr int IM = TM / 64;                  // 32-row MFMA tiles per wave along m
   constexpr int OPER_BYTES = oper_bytes(AT, BT, TM);
-  constexpr int A_BYTES = TM * TileLayout<AT>::ROW;   // the B tile of a stage follows the A tile
+  constexpr int A_BYTES = tile_bytes(AT, TM);   // the B tile of a stage follows the A tile
   extern __shared__ __align__(16) char smem[];
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wm = wave >> 1, wn = wave & 1;
@@ -249,35 +246,40 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
     ldB.store_part(la + A_BYTES, tid, r.b, q);
   };
   const int frag_row = lane & 31, frag_g = lane >> 5;
+  // lane part of a fragment address in a [k][row] tile: k row 8 (lane/32) + (lane%16)/4, rows 16 ((lane/16)%2) + 4 (lane%4)
+  const int tr_lane = (8 * (lane >> 5) + ((lane & 15) >> 2)) * TR_PITCH + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+  // fragment of rows row0 .. row0+31 at k = 16 kk .. +15 of an operand tile
+  auto frag = [&](const char* tile, bool tr, int row0, int kk) -> bf16x8 {
+    if (tr) {
+      const char* p = tile + tr_lane + kk * 16 * TR_PITCH + row0 * 2;
+      const uint2 lo = lds_read_tr(p), hi = lds_read_tr(p + 4 * TR_PITCH);
+      return __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+    }
+    return *reinterpret_cast<const bf16x8*>(tile + RowMajorTile::off(row0 + frag_row, kk * 2 + frag_g));
+  };
   auto load_frags = [&](int stage, int kk, bf16x8 (&fa)[IM], bf16x8 (&fb)[2]) {
     const char* la = smem + stage * OPER_BYTES;
     const char* lb = la + A_BYTES;
 #pragma unroll
-    for (int im = 0; im < IM; ++im)
-      fa[im] = *reinterpret_cast<const bf16x8*>(la + TileLayout<AT>::off(wm * (TM / 2) + im * 32 + frag_row, kk * 2 + frag_g));
+    for (int im = 0; im < IM; ++im) fa[im] = frag(la, AT, wm * (TM / 2) + im * 32, kk);
 #pragma unroll
-    for (int jn = 0; jn < 2; ++jn)
-      fb[jn] = *reinterpret_cast<const bf16x8*>(lb + TileLayout<BT>::off(wn * 64 + jn * 32 + frag_row, kk * 2 + frag_g));
+    for (int jn = 0; jn < 2; ++jn) fb[jn] = frag(lb, BT, wn * 64 + jn * 32, kk);
   };
-  // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k
-  const bool do_colsum = p.colsum != nullptr && m0 == 0;
-  float csum = 0.f;
+  // bias gradient riding along: the workgroups of the first tile row also add up their B tile over k, each thread
+  // the pieces it copies itself (8 columns at its k rows), out of the registers they travel in
+  const bool do_colsum = BT && p.colsum != nullptr && m0 == 0;
+  float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  auto colsum_add = [&](const uint4& w) {
+    csum[0] += bf16_to_f32((uint16_t)(w.x & 0xffff)); csum[1] += bf16_to_f32((uint16_t)(w.x >> 16));
+    csum[2] += bf16_to_f32((uint16_t)(w.y & 0xffff)); csum[3] += bf16_to_f32((uint16_t)(w.y >> 16));
+    csum[4] += bf16_to_f32((uint16_t)(w.z & 0xffff)); csum[5] += bf16_to_f32((uint16_t)(w.z >> 16));
+    csum[6] += bf16_to_f32((uint16_t)(w.w & 0xffff)); csum[7] += bf16_to_f32((uint16_t)(w.w >> 16));
+  };
   bf16x8 fa[2][IM], fb[2][2];   // operand fragments of two consecutive 16-wide k-steps
   // Multiplies the k-tile in LDS stage `stage` (its first fragments are already in fa[0], fb[0])
   // and, between the groups of MFMAs, writes the next tile (registers rn) to the other stage, so
   // that the LDS writes and the fragment reads of the following k-step run under the matrix pipe.
   auto multiply = [&](int stage, const TileRegs& rn, bool stage_next) {
-    if (do_colsum) {   // thread (row = tid/2, half = tid%2) sums 4 of the row's 8 granules; their order is irrelevant
-      const char* rowp = smem + stage * OPER_BYTES + A_BYTES + (tid >> 1) * TileLayout<BT>::ROW + (tid & 1) * 64;
-#pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        uint4 w = *reinterpret_cast<const uint4*>(rowp + gq * 16);
-        csum += bf16_to_f32((uint16_t)(w.x & 0xffff)) + bf16_to_f32((uint16_t)(w.x >> 16)) +
-                bf16_to_f32((uint16_t)(w.y & 0xffff)) + bf16_to_f32((uint16_t)(w.y >> 16)) +
-                bf16_to_f32((uint16_t)(w.z & 0xffff)) + bf16_to_f32((uint16_t)(w.z >> 16)) +
-                bf16_to_f32((uint16_t)(w.w & 0xffff)) + bf16_to_f32((uint16_t)(w.w >> 16));
-      }
-    }
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       if (kk + 1 < BK / 16) load_frags(stage, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
@@ -286,7 +288,10 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
 #pragma unroll
         for (int im = 0; im < IM; ++im)
           acc[jn][im] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][jn], fa[kk & 1][im], acc[jn][im], 0, 0, 0);
-      if (stage_next) lstore_part(stage ^ 1, rn, kk);
+      if (stage_next) {
+        lstore_part(stage ^ 1, rn, kk);
+        if (do_colsum) colsum_add(rn.b[kk]);
+      }
     }
   };
   // One full step: multiply tile i (stage u), stage tile i+1, then refill the freed register
@@ -307,7 +312,10 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
   gload(0, r[0]);
   gload(1, r[1]);
 #pragma unroll
-  for (int q = 0; q < 4; ++q) lstore_part(0, r[0], q);
+  for (int q = 0; q < 4; ++q) {
+    lstore_part(0, r[0], q);
+    if (do_colsum) colsum_add(r[0].b[q]);
+  }
   __syncthreads();
   TRACE(1)
   gload(2, r[0]);
@@ -327,11 +335,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
   }
 
   TRACE(2)
-  if (do_colsum) {
-    csum += __shfl_xor(csum, 1, 64);
-    const int n = n0 + (tid >> 1);
-    if (!(tid & 1) && n < p.N) p.colsum[(size_t)split * p.N + n] = csum;
-  }
 
   // Epilogue through LDS: the accumulators (lane = one C row, 4 consecutive columns per group)
   // are laid down as an fp32 tile, then every thread takes 8 consecutive columns of a row, so
@@ -370,6 +373,19 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
   }
   __syncthreads();   // every wave is done with the operand stages
   float* stage = reinterpret_cast<float*>(smem);
+  if (do_colsum) {   // 16 threads (k rows tid/16 + 16 j) hold partial sums of the same 8 columns: added in order of tid/16
+    float* cs = stage;                                  // [16][128]
+#pragma unroll
+    for (int e = 0; e < 8; ++e) cs[(tid >> 4) * BN + (tid & 15) * 8 + e] = csum[e];
+    __syncthreads();
+    if (tid < BN) {
+      float t = 0.f;
+#pragma unroll
+      for (int g = 0; g < 16; ++g) t += cs[g * BN + tid];
+      if (n0 + tid < p.N) p.colsum[(size_t)split * p.N + n0 + tid] = t;
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int im = 0; im < IM; ++im)
 #pragma unroll
