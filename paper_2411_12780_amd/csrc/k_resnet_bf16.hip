@@ -2,9 +2,10 @@
 //  * 3x3 convolution forward and input gradient as an implicit GEMM on the
 //    matrix cores: a lane owns one output pixel, reads its 3x3 neighbourhood
 //    straight from the NHWC tensor in MFMA fragment order (8 consecutive
-//    channels = 16 bytes), the filter sits in LDS as [out channel][tap, in
-//    channel]; the product is issued filter-first so that a lane ends up with 4
-//    consecutive output channels of its pixel (8-byte stores).
+//    channels = 16 bytes), the filter sits in LDS (forward: as in memory, read
+//    with transposing LDS reads; input gradient: [in channel][tap, out channel]);
+//    the product is issued filter-first so that a lane ends up with 4 consecutive
+//    output channels of its pixel (8-byte stores).
 //  * weight gradient on the matrix cores with the output pixel as reduction index
 //    (images transposed in LDS; stride 1 and 2, up to 16 convolutions of one shape per
 //    launch); shapes it refuses: 64 output pixels per workgroup, their nine shifted
@@ -35,6 +36,14 @@ constexpr int CONV_OOB = 0x7fffffff;
 __device__ __forceinline__ uint4 conv_buf_load16(__amdgpu_buffer_rsrc_t r, int off) {
   const conv_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0);
   return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Transposing LDS read of 16-bit elements: lane r of a 16-lane group hands in the address of 4 elements and receives
+// element r % 4 from the addresses of lanes r / 4, r / 4 + 4, r / 4 + 8, r / 4 + 12 of its group.
+typedef __attribute__((ext_vector_type(4))) short conv_s16x4;
+__device__ __forceinline__ uint2 conv_lds_read_tr(const char* p) {
+  const conv_s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) conv_s16x4*)p);
+  return __builtin_bit_cast(uint2, v);
 }
 
 struct ConvArgs {
@@ -95,14 +104,18 @@ constexpr int CONV_STAT_LDS = 4 * 2 * 2 * 32 * 4;   // [wave][sum kind][lane hal
 // run per lane over the workgroup's tiles, then over the lanes of a half-wave, then over the four waves.
 template <int MODE, int K16, int NT, int GRP, bool LIN, bool STAT>
 __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
-  extern __shared__ __align__(16) char wl[];        // [NO rounded up to 32][9*KC] bf16, row stride RSW bytes
+  // The filter in LDS.  Input gradient: [produced channel ci][tap, co] with rows RSW bytes apart (co, the reduced
+  // index, is the contiguous one in memory: a fragment is one 16-byte read).  Forward: as in memory, [tap, ci][co]
+  // with rows of PB bytes (the produced channels rounded up to 32); a fragment, 8 consecutive (tap, ci) of one co,
+  // comes out of two transposing LDS reads.
+  extern __shared__ __align__(16) char wl[];
   constexpr int KC = 16 * K16;
   const int NO = MODE == 0 ? p.Co : p.Ci;
   constexpr int RSW = 18 * KC + 16;
+  const int PB = (NO + 31) / 32 * 64;
   const int Ho = out_dim(p.H, p.stride), Wo = out_dim(p.W, p.stride);
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 31, hh = lane >> 5;
-  // filter -> LDS as [produced channel][tap*KC + reduced channel]; 8 output channels per 16-byte load,
-  // four loads in flight per thread
+  // filter -> LDS; 8 output channels per 16-byte load, four loads in flight per thread
   {
     const int nvec = 9 * p.Ci * p.Co / 8;
     for (int v0 = tid; v0 < nvec; v0 += 4 * 256) {
@@ -118,10 +131,8 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
         const int v = v0 + 256 * u;
         if (v >= nvec) break;
         const int e = v * 8, co = e % p.Co, ci = (e / p.Co) % p.Ci, tap = e / (p.Co * p.Ci);
-        if (MODE == 0) {       // 8 rows (co .. co+7), one k each
-          const uint16_t* h16 = reinterpret_cast<const uint16_t*>(&wv[u]);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) *reinterpret_cast<uint16_t*>(wl + (co + j) * RSW + 2 * (tap * KC + ci)) = h16[j];
+        if (MODE == 0) {       // row (tap, ci), 8 consecutive co: a plain copy
+          *reinterpret_cast<uint4*>(wl + (tap * KC + ci) * PB + 2 * co) = wv[u];
         } else {               // one row (ci), 8 consecutive k
           *reinterpret_cast<uint4*>(wl + ci * RSW + 2 * (tap * KC + co)) = wv[u];
         }
@@ -129,6 +140,8 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
     }
   }
   __syncthreads();
+  // forward: lane part of a fragment address: (tap, ci) row 8 (lane/32) + (lane%16)/4, co 16 ((lane/16)%2) + 4 (lane%4)
+  const int tr_lane = (8 * hh + ((lane & 15) >> 2)) * PB + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
   const int OH = MODE == 0 ? Ho : p.H, OW = MODE == 0 ? Wo : p.W;      // output spatial size
   const int SH = MODE == 0 ? p.H : Ho, SW = MODE == 0 ? p.W : Wo;      // source spatial size
   const long P = (long)p.B * OH * OW, ntiles = (P + 127) / 128;
@@ -204,7 +217,14 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
           const bf16x8 xf = __builtin_bit_cast(bf16x8, xv[j][c16]);
 #pragma unroll
           for (int t = 0; t < NT; ++t) {
-            const bf16x8 wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
+            bf16x8 wf;
+            if (MODE == 0) {
+              const char* fp = wl + tr_lane + (tap * KC + 16 * c16) * PB + 64 * t;
+              const uint2 lo = conv_lds_read_tr(fp), hi = conv_lds_read_tr(fp + 4 * PB);
+              wf = __builtin_bit_cast(bf16x8, make_uint4(lo.x, lo.y, hi.x, hi.y));
+            } else {
+              wf = *reinterpret_cast<const bf16x8*>(wrow + (t * 32 + li) * RSW + 32 * c16);
+            }
             acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[t], 0, 0, 0);
           }
         }
