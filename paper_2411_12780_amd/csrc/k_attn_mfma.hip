@@ -19,8 +19,8 @@
 // tokens x one granule per half wave) and the reads of the transposer below are
 // then free of bank conflicts without padding.  First operands whose reduction
 // index is the token (V^T, K^T, Q^T, dO^T) are transposed once per workgroup into
-// [64][T padded] arrays (8 bytes of padding per row) with the in-register 4 x 8
-// transpose used by the GEMM loaders.
+// [64][T padded] arrays (8 bytes of padding per row) with an in-register 4 x 8
+// transpose (v_perm_b32 on four 16-byte rows).
 //
 // Backward: phase A (wave = query tile) forms P and dS with a lane per query
 // and accumulates dQ; phase B (wave = key tile) forms them again with a lane
