@@ -723,11 +723,22 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
       for (int d = lane; d < D; d += 64) { zr[d] = xr[d]; xr[d] = 0.f; }
     }
     wave_sync();
-    for (int c = 0; c < C; ++c) {
-      float a = 0.f;
-      for (int d = lane; d < D; d += 64) a += zr[d] * W[(size_t)d * C + c];
-      a = wave_sum(a);
-      if (lane == 0) lr[c] = a + bs[c];
+    // five classes per pass over the row: a wave alone on its SIMD has nothing to hide an LDS read behind, so the
+    // reads of a pass are independent of each other and the five sums are exchanged side by side
+    for (int c0 = 0; c0 < C; c0 += 5) {
+      float a[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+      for (int d = lane; d < D; d += 64) {
+        const float zv = zr[d];
+        const float* wr = W + d * C + c0;
+#pragma unroll
+        for (int u = 0; u < 5; ++u) a[u] += zv * (c0 + u < C ? wr[u] : 0.f);
+      }
+#pragma unroll
+      for (int u = 0; u < 5; ++u) a[u] = wave_sum(a[u]);
+      if (lane == 0) {
+#pragma unroll
+        for (int u = 0; u < 5; ++u) if (c0 + u < C) lr[c0 + u] = a[u] + bs[c0 + u];
+      }
     }
     wave_sync();
     float mx = -INFINITY;
@@ -746,7 +757,9 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
     float s1 = 0.f, s2 = 0.f;
     for (int d = lane; d < D; d += 64) {
       float a = 0.f;
-      for (int c = 0; c < C; ++c) a += lr[c] * W[(size_t)d * C + c];
+      const float* wr = W + d * C;
+#pragma unroll 5
+      for (int c = 0; c < C; ++c) a += lr[c] * wr[c];
       a = round_to(a, dt);
       dzr[d] = a;
       if (ln) {
@@ -768,12 +781,18 @@ __global__ __launch_bounds__(HEAD_THREADS) void vit_head_kernel(const void* x, i
   }
   __syncthreads();
   float* out = partial + (size_t)blockIdx.x * ((size_t)D * C + C + 2 * D + 1);
-  for (int i = threadIdx.x; i < D * C; i += HEAD_THREADS) {
-    const int d = i / C, c = i % C;
-    float t = 0.f;
+  {
+    // (d, c) of element i = d C + c, stepped along with i instead of divided out every time
+    const int dstep = HEAD_THREADS / C, cstep = HEAD_THREADS % C;
+    int d = (int)threadIdx.x / C, c = (int)threadIdx.x % C;
+    for (int i = threadIdx.x; i < D * C; i += HEAD_THREADS) {
+      float t = 0.f;
 #pragma unroll
-    for (int w = 0; w < HEAD_ROWS; ++w) t += zs[w * D + d] * dl[w * C + c];
-    out[i] = t;
+      for (int w = 0; w < HEAD_ROWS; ++w) t += zs[w * D + d] * dl[w * C + c];
+      out[i] = t;
+      d += dstep; c += cstep;
+      if (c >= C) { c -= C; ++d; }
+    }
   }
   float* o2 = out + (size_t)D * C;
   for (int c = threadIdx.x; c < C; c += HEAD_THREADS) {
