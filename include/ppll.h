@@ -126,7 +126,12 @@ int ppll_block_init(const ppll_block_config* cfg, void* workspace_dev, size_t wo
  * read only; x_out_dev [out_bytes] is written during the forward part and read
  * again by the backward part, so all three must stay valid and unmodified until
  * the stream has passed this call's work.  loss_dev: one float on the device
- * (may be null; ppll_block_sync still returns the loss). */
+ * (may be null; ppll_block_sync still returns the loss).
+ * A block with wide layers also launches part of its backward pass (the weight
+ * gradients of upper layers) on a stream of its own, created at first use at
+ * the default priority, forked from and joined back into `hip_stream` inside
+ * this call: everything the call enqueued is complete once `hip_stream` has
+ * passed it, and a caller never sees that stream. */
 int ppll_block_step(ppll_block_t* blk, const void* x_in_dev, const int32_t* labels_dev, float lr,
                     void* x_out_dev, float* loss_dev, void* hip_stream);
 
