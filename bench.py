@@ -82,6 +82,11 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
         # auxiliary layer each, SGD Nesterov
         first = synth.workload("vit_base_224_bf16")
         wls = [first] + [dict(first, input_kind=synth.ACTIVATION) for _ in range(3)]
+    elif args.workload == "vit_base224_pipeline4_d4":
+        # the same 4 blocks with the auxiliary depths of Section 4.2 for d' = 4 (N_l = d' - floor(l / 3) at the last layer
+        # l = 2, 5, 8, 11 of each block): 4, 3, 2, 1 auxiliary layers
+        first = synth.workload("vit_base_224_bf16", aux_depth=4)
+        wls = [first] + [dict(first, input_kind=synth.ACTIVATION, aux_depth=a) for a in (3, 2, 1)]
     elif args.workload == "resnet32_k8":
         # Section 4.1's ResNet-32 at its CIFAR batch of 1024, cut into 8 local modules
         wls = synth.resnet32_modules(8)
@@ -208,7 +213,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     dev = "cuda:0"
-    if args.workload in ("vit_pipeline4", "vit_lpp12", "resnet32_k8", "vit_base224_pipeline4"):
+    if args.workload in ("vit_pipeline4", "vit_lpp12", "resnet32_k8", "vit_base224_pipeline4", "vit_base224_pipeline4_d4"):
         return bench_pipeline(args, torch, P, synth, dev)
     wl = synth.workload(args.workload)
     wl["seed"] = 0
