@@ -82,6 +82,13 @@ def bench_pipeline(args, torch, P, synth, dev) -> int:
         # auxiliary layer each, SGD Nesterov
         first = synth.workload("vit_base_224_bf16")
         wls = [first] + [dict(first, input_kind=synth.ACTIVATION) for _ in range(3)]
+    elif args.workload == "vit_base224_lpp12":
+        # the layer-wise partition of Section 4.2 at ViT-Base / 224 x 224: 12 one-layer blocks, auxiliary depths for d' = 4
+        base = synth.workload("vit_base_224_bf16")
+        shape = {k: base[k] for k in ("img_h", "img_w", "img_c", "patch", "tokens", "dim", "heads", "mlp_dim", "optimizer",
+                                      "momentum", "nesterov", "weight_decay", "lr", "batch")}
+        wls = synth.lpp_workloads(4, **shape)
+        first = wls[0]
     elif args.workload == "vit_base224_pipeline4_d4":
         # the same 4 blocks with the auxiliary depths of Section 4.2 for d' = 4 (N_l = d' - floor(l / 3) at the last layer
         # l = 2, 5, 8, 11 of each block): 4, 3, 2, 1 auxiliary layers
@@ -213,7 +220,7 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU (there is no CPU fallback)"
     dev = "cuda:0"
-    if args.workload in ("vit_pipeline4", "vit_lpp12", "resnet32_k8", "vit_base224_pipeline4", "vit_base224_pipeline4_d4"):
+    if args.workload in ("vit_pipeline4", "vit_lpp12", "resnet32_k8", "vit_base224_pipeline4", "vit_base224_pipeline4_d4", "vit_base224_lpp12"):
         return bench_pipeline(args, torch, P, synth, dev)
     wl = synth.workload(args.workload)
     wl["seed"] = 0
