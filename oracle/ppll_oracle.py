@@ -24,6 +24,11 @@ biased variance, ...).
 Weights are stored [in, out]; rows of activation matrices are tokens/pixels.
 Images and ResNet activations are NHWC.
 
+Mixed precision: the oracle itself is float64 throughout.  For the ReLU network
+only, block_init(storage="bf16") rounds the tensors stored between layers to bf16
+values, because a ReLU mask is a binary decision that both sides of a comparison
+have to take on values of the same precision; the ViT path has no such switch.
+
 Parity pins for every function live in tests/test_oracle_*.py (finite
 differences in float64, torch.autograd on library ops, scipy routines, closed
 forms, brute-force loops, invariants).
@@ -431,11 +436,18 @@ def bf16_values(a):
 
 def block_init(cfg: BlockConfig, flat_params: np.ndarray, dtype=np.float64,
                storage: Optional[str] = None) -> BlockState:
-    """storage=None: everything in `dtype`.  storage="bf16": activations the
-    mixed-precision path keeps in bf16, and the weight matrices its contractions
-    read, are rounded to bf16 values at the point of storage (arithmetic, norm
-    statistics, loss, gradients w.r.t. parameters and the optimizer stay in
-    `dtype`)."""
+    """storage=None: everything in `dtype`; this is the definition and the gate.
+    storage="bf16" exists for the ReLU network only, where floating point takes a
+    binary decision (the ReLU mask): every tensor a mixed-precision run hands from
+    one layer to the next in bf16 (convolution outputs, post-ReLU activations,
+    pooled features, and in the backward pass the gradients with respect to those
+    same tensors) and the filters its contractions read are rounded to bf16 values,
+    so that the masks are decided on values of that precision and cancelling sums
+    over such tensors carry that precision's noise (arithmetic, norm statistics,
+    loss, parameter gradients and the optimizer stay in `dtype`).  The ViT block
+    has no such decision and takes no storage mode."""
+    if storage is not None and (storage != "bf16" or cfg.arch != ARCH_RESNET):
+        raise ValueError("storage emulation is defined for the ResNet block only, as storage='bf16'")
     params = unflatten(cfg, flat_params, dtype)
     st = BlockState(cfg, dtype, params,
                     {k: np.zeros_like(v) for k, v in params.items()},
@@ -447,33 +459,28 @@ def block_init(cfg: BlockConfig, flat_params: np.ndarray, dtype=np.float64,
 
 
 def _encoder_fwd(x, p, pre, st):
-    cfg, S, W = st.cfg, st.act, st.wmat
+    cfg = st.cfg
     u, c_ln1 = layernorm_fwd(x, p[pre + ".ln1.g"], p[pre + ".ln1.b"], cfg.ln_eps)
-    u = S(u)
-    qkv = S(linear_fwd(u, W(p[pre + ".qkv.w"]), p[pre + ".qkv.b"]))
+    qkv = linear_fwd(u, p[pre + ".qkv.w"], p[pre + ".qkv.b"])
     o, c_att = attention_fwd(qkv, cfg.heads)
-    o = S(o)
-    x1 = S(x + linear_fwd(o, W(p[pre + ".proj.w"]), p[pre + ".proj.b"]))
+    x1 = x + linear_fwd(o, p[pre + ".proj.w"], p[pre + ".proj.b"])
     u2, c_ln2 = layernorm_fwd(x1, p[pre + ".ln2.g"], p[pre + ".ln2.b"], cfg.ln_eps)
-    u2 = S(u2)
-    h = linear_fwd(u2, W(p[pre + ".fc1.w"]), p[pre + ".fc1.b"])
-    gl = S(gelu_fwd(h))
-    h = S(h)
-    x2 = S(x1 + linear_fwd(gl, W(p[pre + ".fc2.w"]), p[pre + ".fc2.b"]))
+    h = linear_fwd(u2, p[pre + ".fc1.w"], p[pre + ".fc1.b"])
+    gl = gelu_fwd(h)
+    x2 = x1 + linear_fwd(gl, p[pre + ".fc2.w"], p[pre + ".fc2.b"])
     return x2, (c_ln1, u, c_att, o, c_ln2, u2, h, gl)
 
 
 def _encoder_bwd(dx2, cache, p, pre, grads, st):
-    W = st.wmat
     c_ln1, u, c_att, o, c_ln2, u2, h, gl = cache
-    dgl, grads[pre + ".fc2.w"], grads[pre + ".fc2.b"] = linear_bwd(dx2, gl, W(p[pre + ".fc2.w"]))
+    dgl, grads[pre + ".fc2.w"], grads[pre + ".fc2.b"] = linear_bwd(dx2, gl, p[pre + ".fc2.w"])
     dh = gelu_bwd(dgl, h)
-    du2, grads[pre + ".fc1.w"], grads[pre + ".fc1.b"] = linear_bwd(dh, u2, W(p[pre + ".fc1.w"]))
+    du2, grads[pre + ".fc1.w"], grads[pre + ".fc1.b"] = linear_bwd(dh, u2, p[pre + ".fc1.w"])
     d, grads[pre + ".ln2.g"], grads[pre + ".ln2.b"] = layernorm_bwd(du2, c_ln2, p[pre + ".ln2.g"])
     dx1 = dx2 + d
-    do, grads[pre + ".proj.w"], grads[pre + ".proj.b"] = linear_bwd(dx1, o, W(p[pre + ".proj.w"]))
+    do, grads[pre + ".proj.w"], grads[pre + ".proj.b"] = linear_bwd(dx1, o, p[pre + ".proj.w"])
     dqkv = attention_bwd(do, c_att)
-    du, grads[pre + ".qkv.w"], grads[pre + ".qkv.b"] = linear_bwd(dqkv, u, W(p[pre + ".qkv.w"]))
+    du, grads[pre + ".qkv.w"], grads[pre + ".qkv.b"] = linear_bwd(dqkv, u, p[pre + ".qkv.w"])
     d, grads[pre + ".ln1.g"], grads[pre + ".ln1.b"] = layernorm_bwd(du, c_ln1, p[pre + ".ln1.g"])
     return dx1 + d
 
@@ -486,8 +493,8 @@ def vit_forward(st: BlockState, x_in):
     caches = {}
     if cfg.input_kind == IN_IMAGE:
         pt = patchify(x_in, cfg.patch)
-        e = st.act(linear_fwd(pt, st.wmat(p["pe.w"]), p["pe.b"]))
-        x = st.act(np.concatenate([np.broadcast_to(p["cls"], (cfg.batch, 1, cfg.dim)), e], axis=1) + p["pos"])
+        e = linear_fwd(pt, p["pe.w"], p["pe.b"])
+        x = np.concatenate([np.broadcast_to(p["cls"], (cfg.batch, 1, cfg.dim)), e], axis=1) + p["pos"]
         caches["patches"] = pt
     else:
         x = x_in
@@ -497,7 +504,6 @@ def vit_forward(st: BlockState, x_in):
     for a in range(cfg.aux_depth):
         x, caches[f"aux{a}"] = _encoder_fwd(x, p, f"aux{a}", st)
     z, caches["head.ln"] = layernorm_fwd(x[:, 0, :], p["head.ln.g"], p["head.ln.b"], cfg.ln_eps)
-    z = st.act(z)
     caches["z"] = z
     logits = linear_fwd(z, p["head.w"], p["head.b"])
     return x_out, logits, caches
@@ -519,7 +525,7 @@ def vit_backward(st: BlockState, dlogits, caches):
     if cfg.input_kind == IN_IMAGE:
         g["pos"] = dx.sum(axis=0)
         g["cls"] = dx[:, 0, :].sum(axis=0)
-        _, g["pe.w"], g["pe.b"] = linear_bwd(dx[:, 1:, :], caches["patches"], st.wmat(p["pe.w"]))
+        _, g["pe.w"], g["pe.b"] = linear_bwd(dx[:, 1:, :], caches["patches"], p["pe.w"])
     return g
 
 
@@ -572,16 +578,18 @@ def resnet_forward(st: BlockState, x_in, track=True):
 
 
 def resnet_backward(st: BlockState, dlogits, caches):
-    cfg, p = st.cfg, st.params
+    cfg, p, S = st.cfg, st.params, st.act
     g: Dict[str, np.ndarray] = {}
     x_out, cba, ba, ya, pooled = caches["aux"]
     dpool, g["head.w"], g["head.b"] = linear_bwd(dlogits, pooled, p["head.w"])
+    dpool = S(dpool)
     hw = ya.shape[1] * ya.shape[2]
-    dya = np.broadcast_to(dpool[:, None, None, :] / hw, ya.shape)
+    dya = S(np.broadcast_to(dpool[:, None, None, :] / hw, ya.shape))
     dba = dya * (ba > 0)
     dca, g["aux.bn.g"], g["aux.bn.b"] = batchnorm_bwd(dba, cba, p["aux.bn.g"])
+    dca = S(dca)
     g["aux.conv.w"] = conv3x3_bwd_weight(dca, x_out, 2)
-    dx = conv3x3_bwd_input(dca, st.wmat(p["aux.conv.w"]), 2, x_out.shape)
+    dx = S(conv3x3_bwd_input(dca, st.wmat(p["aux.conv.w"]), 2, x_out.shape))
     stem = cfg.input_kind == IN_IMAGE
     layout = resnet_layout(cfg)
     for i in reversed(range(cfg.n_basic_blocks)):
@@ -590,17 +598,20 @@ def resnet_backward(st: BlockState, dlogits, caches):
         x, cb1, b1, y1, cb2, s = caches[pre]
         ds = dx * (s > 0)
         dc2, g[pre + ".bn2.g"], g[pre + ".bn2.b"] = batchnorm_bwd(ds, cb2, p[pre + ".bn2.g"])
+        dc2 = S(dc2)
         g[pre + ".conv2.w"] = conv3x3_bwd_weight(dc2, y1, 1)
-        dy1 = conv3x3_bwd_input(dc2, st.wmat(p[pre + ".conv2.w"]), 1, y1.shape)
+        dy1 = S(conv3x3_bwd_input(dc2, st.wmat(p[pre + ".conv2.w"]), 1, y1.shape))
         db1 = dy1 * (b1 > 0)
         dc1, g[pre + ".bn1.g"], g[pre + ".bn1.b"] = batchnorm_bwd(db1, cb1, p[pre + ".bn1.g"])
+        dc1 = S(dc1)
         g[pre + ".conv1.w"] = conv3x3_bwd_weight(dc1, x, stride)
         if i > 0 or stem:   # without a stem the first block's input is the detached x_{j-1}
-            dx = shortcut_bwd(ds, x.shape, stride) + conv3x3_bwd_input(dc1, st.wmat(p[pre + ".conv1.w"]), stride, x.shape)
+            dx = S(shortcut_bwd(ds, x.shape, stride) + conv3x3_bwd_input(dc1, st.wmat(p[pre + ".conv1.w"]), stride, x.shape))
     if stem:
         img, cb0, b0 = caches["stem"]
         db0 = dx * (b0 > 0)
         dc0, g["stem.bn.g"], g["stem.bn.b"] = batchnorm_bwd(db0, cb0, p["stem.bn.g"])
+        dc0 = S(dc0)
         g["stem.conv.w"] = conv3x3_bwd_weight(dc0, img, 1)
     return g
 

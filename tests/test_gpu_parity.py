@@ -1,46 +1,73 @@
 """Parity of the HIP path (through the C ABI) with the CPU oracle, element by
 element on the same seeded inputs.
 
-Tolerances (relative L2 per tensor, |dloss|/|loss| for the loss): 1e-4 on the
-fp32 path, 2e-2 on the bf16 path, for the output activation, the local loss,
-every parameter-gradient tensor and every updated parameter tensor.
+Tolerances: 1e-4 on the fp32 path, 2e-2 on the bf16 path, for the local loss
+(|dloss|/|loss|), every parameter-gradient tensor and every updated parameter
+tensor; the output activation is held to 1e-2 on the bf16 path.  A tensor passes
+when its relative L2 error is within the tolerance, no single element is off by
+more than MAX_ABS_FACTOR x tolerance x the largest reference magnitude, and (for
+the output activation) every row, i.e. every token or pixel, is within 2e-2 /
+1e-4 on its own (helpers.assert_close).
 
-bf16 path.  The gate is the float64 oracle with bf16 *storage* emulated
-(activations and weight shadows rounded to bf16 values at the points where the
-kernels store them; arithmetic, statistics, loss and parameter gradients stay
-float64), so that sign decisions (ReLU masks) are taken on the same stored
-values on both sides.  The distance to the pure float64 oracle is asserted for
-the loss and the output activation and printed for the gradients.
+The reference is the float64 oracle, nothing else, for every ViT case: that
+network takes no binary decision on a floating-point value.
 
-ReLU masks.  A ReLU gradient is discontinuous in the pre-activation: one
-element whose mask differs changes a gradient tensor by that element's full
-magnitude.  Two bf16 evaluations that differ only in accumulation order (fp32 on
-the GPU, float64 in the oracle) disagree on a few roundings of stored values
-after the first convolution, and every disagreement reaches 9*C outputs of the
-next one, so the stored values decorrelate to the bf16 noise level within a few
-layers and masks then differ at that rate, whatever the oracle emulates.
-Measured: GPU vs storage-emulating oracle gradients agree to 7e-3 with one basic
-block, 2e-2 with two, 6e-2 with three and 1.4e-1 with five; oracle vs oracle
-(pure vs bf16 storage, CPU only, tests/test_oracle_step.py) is 9-19 % at five.
-The bf16 ResNet arithmetic is therefore gated at 2e-2 on one- and two-block
-stages at the full activation size, the same kernels at five blocks on the fp32
-path (1e-3; 1e-4 class agreement needs every mask equal, and fp32 summation order
-already flips about one in a million), and the named five-block bf16 workload at
-2e-2 on loss and output with a 0.3 ceiling on gradients.
+ReLU networks.  A ReLU mask is such a decision, and its gradient is discontinuous
+in the pre-activation: one element whose mask differs changes a gradient tensor
+by that element's full magnitude.  The oracle is run up to three times, all on
+the CPU:
+  P    the float64 oracle (the definition);
+  E    the float64 oracle deciding its masks on values of the path's precision:
+       bf16 storage emulated on the bf16 path; on the fp32 path (only where a test
+       asks for it: at small sizes that path meets 1e-4) the oracle in float32;
+  E32  bf16 path only: E again with float32 arithmetic, i.e. a second evaluation
+       that rounds to bf16 at the same places and differs from E in nothing but
+       accumulation precision, which is how a correct GPU result differs from E.
+Loss and output are held to the tolerance against P and against E.  A gradient
+tensor is held
+  against P to max(tolerance, FLOOR_FACTOR x d(E, P)):  the GPU result is one more
+      evaluation in that precision, so it may stand as far from the definition as
+      E does and not much further (one basic block at natural statistics already
+      gives d(E, P) of 0.07 to 0.17: rounding the stored values to bf16 flips the
+      masks nearest zero);
+  against E to max(tolerance, FLOOR_FACTOR x d(E32, E)):  with one or two blocks
+      this is the plain 2e-2; stored bf16 values decorrelate layer by layer, and
+      at five blocks two evaluations that differ only in accumulation order stand
+      0.1 to 0.15 apart.
+Both distances are taken per tensor for the very case under test (depth, seed,
+statistics), oracle against oracle; the largest-element criterion, and the
+worst-row criterion of the output against P, are bounded the same way.  E rounds
+every tensor that passes from one layer to the next, forward and backward, so a
+cancelling sum over such a tensor (a weight gradient whose input carries a large
+common offset) shows in d(E, P) with the noise it has in any bf16 evaluation.  The shift gradient of a BatchNorm is measured on the scale of the
+(scale, shift) gradient pair of that layer: both are sums of the same terms with
+weights of order one, and where everything behind the layer is invariant to a
+shift (a channel whose ReLU is open everywhere, another BatchNorm further on) the
+true shift gradient is a cancelling sum with no scale of its own.  Cases with wide
+mask margins (_decisive_shifts) remove the mask flips altogether: there E32 and E
+stand 1e-2 to 2e-2 apart at five blocks, and that is how close the GPU has to come
+to E; the offsets that make the masks decisive also make every weight gradient
+behind them a cancelling sum, so d(E, P) is not small in those cases.
 """
 import numpy as np
 import pytest
 
 from oracle import ppll_oracle as O
 from paper_2411_12780_amd import synth
-from helpers import oracle_cfg, rel_l2
+from helpers import MAX_ABS_FACTOR, assert_close, closeness, oracle_cfg, rel_l2
 
 pytestmark = pytest.mark.gpu
 
 TOL = {synth.FP32: 1e-4, synth.BF16: 2e-2}
+OUT_TOL = {synth.FP32: 1e-4, synth.BF16: 1e-2}     # whole output activation (ViT, and against E); its rows are held to TOL
+FLOOR_FACTOR = 1.5        # a GPU tensor may stand this many times as far from a reference as the oracle's own runs do
+FLOOR_FACTOR_MAX = 2.0    # the same for the largest single element error, which varies more from run to run than a norm
 
 
-def run_case(wl, steps, seed=0, check_bn=False, tol=None, grad_tol=None, tweak=None):
+def run_case(wl, steps, seed=0, check_bn=False, tweak=None, precision_floor=False):
+    """precision_floor: on the fp32 path of a ReLU network, also run the oracle in float32 and bound the
+    gradients by its distance to the float64 oracle (the bf16 path of a ReLU network always does the same
+    with bf16 storage emulated)."""
     from gpu_harness import GpuBlock
     from paper_2411_12780_amd import binding as P
     wl = {**dict(beta1=0.9, beta2=0.999, adam_eps=1e-8, momentum=0.0, nesterov=0, weight_decay=0.0), **wl}
@@ -51,19 +78,32 @@ def run_case(wl, steps, seed=0, check_bn=False, tol=None, grad_tol=None, tweak=N
         tweak(tensors)
         flat = O.flatten(cfg, tensors).astype(np.float32)
     bf16 = wl["precision"] == synth.BF16
-    st = O.block_init(cfg, flat, np.float64, storage="bf16" if bf16 else None)
-    pure = O.block_init(cfg, flat, np.float64) if bf16 else None
+    relu_net = wl["arch"] == synth.RESNET
+    pure = O.block_init(cfg, flat, np.float64)
+    emul = emul32 = None
+    if relu_net and bf16:
+        emul = O.block_init(cfg, flat, np.float64, storage="bf16")
+        emul32 = O.block_init(cfg, flat, np.float32, storage="bf16")
+    elif relu_net and precision_floor:
+        emul = O.block_init(cfg, flat, np.float32)
+    st = emul if (relu_net and bf16) else pure     # the state that loss, output, parameters and statistics are held to
     gb = GpuBlock(wl, flat)
     assert gb.names == [n for n, _ in O.param_spec(cfg)]
-    tol = tol or TOL[wl["precision"]]
-    grad_tol = grad_tol or tol
+    tol, out_tol = TOL[wl["precision"]], OUT_TOL[wl["precision"]]
+    out_tol_pure = tol if relu_net else out_tol    # masks decided in bf16 put the ReLU network's output up to 1e-2 from P
+    row_len = wl["dim"] if wl["arch"] == synth.VIT else wl["channels"]
     adamw = wl["optimizer"] == synth.ADAMW
     # AdamW moves a coordinate by about lr*sign(g) however small |g| is, so where the true
     # gradient is zero (key bias) or under the bf16 noise floor the end-to-end parameter is
     # noise-determined.  There the update is checked as arithmetic on the GPU's own gradient
     # (always done, tight tolerance) and end to end on coordinates with a resolvable gradient.
-    masked = adamw and wl["precision"] == synth.BF16
+    masked = adamw and bf16
     worst = {}
+
+    def note(key, c):
+        for k, v in c.items():
+            worst[f"{key}.{k}"] = max(worst.get(f"{key}.{k}", 0.0), v)
+
     try:
         for i in range(steps):
             x, y = synth.make_batch(wl, seed=seed, index=i)
@@ -77,27 +117,44 @@ def run_case(wl, steps, seed=0, check_bn=False, tol=None, grad_tol=None, tweak=N
                     P.ppll_block_write_tensor(gb.h, P.T_MOMENT2, idx, st.mom2[name])
             p_before, m_before = gb.tensors(P.T_PARAM), gb.tensors(P.T_MOMENT1)
             v_before = gb.tensors(P.T_MOMENT2) if adamw else None
-            ref_out, ref_loss = O.block_step(st, x.astype(np.float64), y, wl["lr"])
+            pure_out, pure_loss = O.block_step(pure, x.astype(np.float64), y, wl["lr"])
+            if emul is not None:
+                emul_out, emul_loss = O.block_step(emul, x.astype(emul.dtype), y, wl["lr"])
+            if emul32 is not None:
+                O.block_step(emul32, x.astype(np.float32), y, wl["lr"])
             out, loss = gb.step(x, y, wl["lr"])
-            assert abs(loss - ref_loss) <= tol * abs(ref_loss), (i, loss, ref_loss)
-            e = rel_l2(out, ref_out)
-            assert e <= tol, (i, "x_out", e)
-            worst["x_out"] = max(worst.get("x_out", 0), e)
+            assert abs(loss - pure_loss) <= tol * abs(pure_loss), (i, "loss against the float64 oracle", loss, pure_loss)
+            row_tol = max_tol = None
+            if emul is not None:       # single pixels next to a flipped mask: bounded by what the precision alone does to them
+                apart = closeness(emul_out, pure_out, row_len)
+                row_tol = max(tol, FLOOR_FACTOR_MAX * apart["row"])
+                max_tol = max(MAX_ABS_FACTOR * out_tol_pure, FLOOR_FACTOR_MAX * apart["max_abs"])
+            note("x_out", assert_close(out, pure_out, out_tol_pure, f"step {i} x_out against the float64 oracle", row_len,
+                                       row_tol if row_tol else tol, max_tol))
+            if st is emul:
+                assert abs(loss - emul_loss) <= tol * abs(emul_loss), (i, "loss against the oracle with bf16 masks", loss, emul_loss)
+                note("x_out_E", assert_close(out, emul_out, out_tol, f"step {i} x_out against the oracle with bf16 masks",
+                                             row_len, tol))
             grads, params = gb.tensors(P.T_GRAD), gb.tensors(P.T_PARAM)
-            if pure is not None and i == 0:
-                pure_out, pure_loss = O.block_step(pure, x.astype(np.float64), y, wl["lr"])
-                assert abs(loss - pure_loss) <= tol * abs(pure_loss), ("pure oracle", loss, pure_loss)
-                worst["pure_x_out"] = rel_l2(out, pure_out)
-                assert worst["pure_x_out"] <= tol, ("pure oracle x_out", worst["pure_x_out"])
-                worst["pure_grad"] = max(rel_l2(grads[n], pure.grads[n]) for n in grads)
-            gerr = {name: rel_l2(grads[name], st.grads[name]) for name, _ in O.param_spec(cfg)}
-            top = sorted(gerr.items(), key=lambda kv: -kv[1])[:8]
-            print("  largest gradient errors:", [(n, f"{e:.2e}") for n, e in top], flush=True)
+            report = []
             for name, shape in O.param_spec(cfg):
-                g_ref = st.grads[name].reshape(-1)
-                e = gerr[name]
-                assert e <= grad_tol, (i, "grad", name, e)
-                worst["grad"] = max(worst.get("grad", 0), e)
+                bound, max_bound = tol, None
+                mate = name[:-2] + ".g" if relu_net and ".bn" in name and name.endswith(".b") else None
+                if emul is not None:
+                    floor = closeness(emul.grads[name], pure.grads[name], floor_ref=pure.grads[mate] if mate else None)
+                    bound = max(tol, FLOOR_FACTOR * floor["rel_l2"])
+                    max_bound = max(MAX_ABS_FACTOR * tol, FLOOR_FACTOR_MAX * floor["max_abs"])
+                if emul32 is not None:
+                    apart = closeness(emul32.grads[name], emul.grads[name], floor_ref=emul.grads[mate] if mate else None)
+                    note("grad_E", assert_close(grads[name], emul.grads[name], max(tol, FLOOR_FACTOR * apart["rel_l2"]),
+                                                f"step {i} grad {name} against the oracle with bf16 masks (float32 against "
+                                                f"float64 arithmetic in that oracle: {apart['rel_l2']:.1e})",
+                                                max_tol=max(MAX_ABS_FACTOR * tol, FLOOR_FACTOR_MAX * apart["max_abs"]),
+                                                floor_ref=emul.grads[mate] if mate else None))
+                c = assert_close(grads[name], pure.grads[name], bound, f"step {i} grad {name} against the float64 oracle",
+                                 max_tol=max_bound, floor_ref=pure.grads[mate] if mate else None)
+                note("grad", c)
+                report.append((name, c["rel_l2"], bound))
                 # update arithmetic: the oracle's rule applied to the GPU's own tensors
                 if adamw:
                     want, _, _ = O.adamw_update(p_before[name], grads[name], m_before[name], v_before[name], i + 1,
@@ -108,32 +165,42 @@ def run_case(wl, steps, seed=0, check_bn=False, tol=None, grad_tol=None, tweak=N
                 e = rel_l2(params[name], want)
                 assert e <= 1e-5, (i, "update", name, e)
                 worst["update"] = max(worst.get("update", 0), e)
+                g_ref = st.grads[name].reshape(-1)
                 p_ref = st.params[name].reshape(-1)
                 if masked:
                     keep = np.abs(g_ref) >= 0.05 * np.sqrt(np.mean(g_ref ** 2) + 1e-300)
-                    e = rel_l2(params[name][keep], p_ref[keep]) if keep.any() else 0.0
+                    if keep.any():
+                        note("param", assert_close(params[name][keep], p_ref[keep], tol, f"step {i} param {name}"))
                 else:
-                    e = rel_l2(params[name], p_ref)
-                assert e <= tol, (i, "param", name, e)
-                worst["param"] = max(worst.get("param", 0), e)
+                    note("param", assert_close(params[name], p_ref, tol, f"step {i} param {name}"))
+            top = sorted(report, key=lambda r: -r[1] / r[2])[:6]
+            print("  gradient errors nearest their bounds:", [(n, f"{e:.2e}/{b:.2e}") for n, e, b in top], flush=True)
         if check_bn:
             mean, var = gb.bn(P.T_BN_MEAN), gb.bn(P.T_BN_VAR)
             for name, _ in O.bn_stat_spec(cfg):
-                assert rel_l2(mean[name], st.bn_mean[name]) <= tol, name
-                assert rel_l2(var[name], st.bn_var[name]) <= tol, name
+                assert_close(mean[name], st.bn_mean[name], tol, f"running mean {name}")
+                assert_close(var[name], st.bn_var[name], tol, f"running variance {name}")
     finally:
         gb.close()
-    print("  worst rel L2:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
+    print("  worst:", {k: f"{v:.2e}" for k, v in worst.items()}, flush=True)
     return worst
 
 
 def _decisive_shifts(tensors):
-    """BatchNorm shifts of +6 / -6 by channel parity: every ReLU decision has a wide margin."""
+    """BatchNorm shifts of +5 / -5 by channel parity: every ReLU decision has a margin of several standard
+    deviations, so no mask depends on a rounding.  The second BatchNorm of a block feeds the skip sum: the first
+    block lifts it to +5 and the later ones add little to it (scale 0.35, shift 0.5), which keeps that sum
+    positive with the same margin without letting the stored values grow block by block (larger values cost
+    bf16 its absolute precision)."""
     for name, v in tensors.items():
         if ".bn" in name and name.endswith(".b"):
-            v[:] = np.where(np.arange(v.size) % 2 == 0, 6.0, -6.0)
-        if name.endswith("bn2.b") or name == "aux.bn.b":      # keep the skip sum and the pooled features alive
-            v[:] = 6.0
+            v[:] = np.where(np.arange(v.size) % 2 == 0, 5.0, -5.0)
+        if name == "aux.bn.b" or name == "stem.bn.b":      # keep the pooled features and the first block's input alive
+            v[:] = 5.0
+        if name.endswith("bn2.b"):
+            v[:] = 5.0 if name.startswith("rb0.") else 0.5
+        if name.endswith("bn2.g") and not name.startswith("rb0."):
+            v[:] = 0.35
 
 
 # ------------------------------------------------------------------ fp32 path
@@ -234,15 +301,16 @@ def test_vit_bf16_head_with_many_classes(dim, heads, classes):
 
 
 def test_resnet_fp32_stage_full_size_decisive_masks():
-    # not a named workload: fp32 at the full ResNet size.  Gradients pass 10 BatchNorm backward
-    # stages, each a cancelling 32768-term reduction in fp32, so 1e-3 instead of 1e-4
-    run_case(synth.workload("resnet_stage_bf16", precision=synth.FP32), steps=1, check_bn=True, tol=1e-3,
-             tweak=_decisive_shifts)
+    # not a named workload: fp32 at the full ResNet size.  Gradients pass 10 BatchNorm backward stages, each a
+    # cancelling 32768-term reduction: the float32 oracle's own distance to the float64 one bounds them
+    run_case(synth.workload("resnet_stage_bf16", precision=synth.FP32), steps=1, check_bn=True, tweak=_decisive_shifts,
+             precision_floor=True)
 
 
 def test_resnet_fp32_stage_full_size_natural_statistics():
-    # a single flipped mask among ~1e6 elements moves a layer's gradient by ~1e-3
-    run_case(synth.workload("resnet_stage_bf16", precision=synth.FP32), steps=1, check_bn=True, tol=1e-3, grad_tol=5e-3)
+    # a single flipped mask among ~1e6 elements moves a layer's gradient by ~1e-3: float32 arithmetic alone puts
+    # the oracle 2e-3 to 5e-3 from its float64 self here, and that distance is the bound
+    run_case(synth.workload("resnet_stage_bf16", precision=synth.FP32), steps=1, check_bn=True, precision_floor=True)
 
 
 @pytest.mark.parametrize("tokens", [1, 32, 64, 256])
@@ -272,10 +340,9 @@ def test_resnet_bf16_two_narrow_blocks():
 
 
 def test_resnet_bf16_two_blocks_on_the_mfma_path():
-    # 32 channels: matrix-core convolutions incl. the input gradient with the skip path; with two blocks the
-    # stored values have begun to decorrelate (measured 2e-2), hence the wider gradient bound
+    # 32 channels: matrix-core convolutions incl. the input gradient with the skip path
     wl = synth.workload("resnet_stage_bf16", n_basic_blocks=2)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 def test_resnet_bf16_odd_sizes_on_the_mfma_path():
@@ -294,33 +361,33 @@ def test_resnet_bf16_weight_gradient_on_the_mfma_path_edges():
 def test_resnet_bf16_downsampling_first_block_on_the_mfma_path():
     # 16 -> 32 channels with stride 2: matrix-core forward and the 16-input-channel weight gradient
     wl = synth.workload("resnet32_stage2_bf16", batch=8, n_basic_blocks=2)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 def test_resnet_bf16_downsampling_block_behind_a_16_channel_block():
     # blocks 4 and 5 of ResNet-32: a 16-channel block on the 32 x 32 map, then the downsampling block
     wl = synth.workload("resnet32_stage2_bf16", batch=4, n_basic_blocks=2, transition_block=2)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 def test_resnet_bf16_third_stage_64_channels():
     # 32 -> 64 downsampling block, then a 64-channel block on the 8 x 8 map: the filter of a 64 -> 64
     # convolution needs more LDS than a kernel gets without asking (73 KiB)
     wl = synth.workload("resnet32_stage2_bf16", batch=8, channels=64, height=8, width=8, n_basic_blocks=2)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 def test_resnet_bf16_16_channels_ragged():
     # 16 produced channels fill half a matrix-core tile; 3*7*9 pixels leave a ragged last workgroup
     wl = synth.workload("resnet_stage_bf16", n_basic_blocks=2, batch=3, height=7, width=9, channels=16, aux_channels=32)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 def test_resnet_bf16_48_channels():
     # 48 channels: three 16-channel reduction steps and one and a half 32-channel output tiles in the matrix-core
     # convolutions; BatchNorm and weight gradient take the run-time-typed kernels at this width
     wl = synth.workload("resnet_stage_bf16", n_basic_blocks=2, batch=6, height=8, width=8, channels=48, aux_channels=48)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 @pytest.mark.parametrize("channels,height,width,batch", [(32, 8, 8, 5), (32, 4, 32, 3), (16, 2, 16, 300), (64, 4, 8, 2)])
@@ -329,35 +396,47 @@ def test_resnet_bf16_tiled_weight_gradient_shapes(channels, height, width, batch
     # k-steps per image than waves (2 x 16 pixels), more images than workgroups (300)
     wl = synth.workload("resnet_stage_bf16", n_basic_blocks=1, batch=batch, height=height, width=width, channels=channels,
                         aux_channels=32)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 def test_resnet_bf16_stride_2_weight_gradient_64_to_64():
     # the auxiliary convolution 64 -> 64 at stride 2 on a 16 x 16 map: odd / even column planes in the tiled weight
     # gradient, second k-split handed over through LDS
     wl = synth.workload("resnet_stage_bf16", n_basic_blocks=1, batch=3, height=16, width=16, channels=64, aux_channels=64)
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 def test_resnet_bf16_stem_module():
     wl = synth.resnet32_modules(8, batch=4)[0]
-    run_case(wl, steps=1, check_bn=True, grad_tol=5e-2)
+    run_case(wl, steps=1, check_bn=True)
 
 
 @pytest.mark.parametrize("name", ["resnet32_stage1_bf16", "resnet32_stage2_bf16", "resnet32_stage3_bf16"])
 def test_resnet32_stages_at_their_full_shape(name):
     # the three stages of ResNet-32 at their real map and channel sizes (stem, both downsampling blocks, 16 / 32 /
     # 64 channels); batch 100 instead of 1024 keeps the float64 oracle to seconds and leaves ragged last tiles.
-    # Five blocks of stored bf16 values decorrelate single gradients (as in the 32-channel stage test below).
-    run_case(synth.workload(name, batch=100), steps=1, check_bn=True, grad_tol=0.3)
+    # Five blocks of stored bf16 values decorrelate the masks: every gradient tensor is bounded by what bf16
+    # storage alone does to it in the oracle.
+    run_case(synth.workload(name, batch=100), steps=1, check_bn=True)
+
+
+@pytest.mark.parametrize("name", ["resnet32_stage1_bf16", "resnet32_stage2_bf16", "resnet32_stage3_bf16"])
+def test_resnet32_stages_at_their_full_shape_decisive_masks(name):
+    # the same three stages with every ReLU decision several standard deviations from zero: GPU and oracle take
+    # the same masks, so what is compared is the arithmetic of the five-block bf16 backward pass itself
+    run_case(synth.workload(name, batch=100), steps=1, check_bn=True, tweak=_decisive_shifts)
 
 
 def test_resnet_bf16_stage_full_size_natural_statistics():
-    run_case(synth.workload("resnet_stage_bf16"), steps=2, check_bn=True, grad_tol=0.3)
+    run_case(synth.workload("resnet_stage_bf16"), steps=2, check_bn=True)
+
+
+def test_resnet_bf16_stage_full_size_decisive_masks():
+    run_case(synth.workload("resnet_stage_bf16"), steps=2, check_bn=True, tweak=_decisive_shifts)
 
 
 def test_vit_stage_bf16_full_size():
-    run_case(synth.workload("vit_stage_bf16"), steps=1)
+    run_case(synth.workload("vit_stage_bf16"), steps=3)
 
 
 def test_vit_base_paper_shape_bf16_full_size():
@@ -404,7 +483,7 @@ def test_eval_forward_matches_the_oracle_after_training_steps(name, kw):
     tol = 2e-2 if bf16 else 1e-4
     cfg = oracle_cfg(wl)
     flat = synth.make_params(O.param_spec(cfg), seed=13, jitter=True)
-    st = O.block_init(cfg, flat, np.float64, storage="bf16" if bf16 else None)
+    st = O.block_init(cfg, flat, np.float64, storage="bf16" if bf16 and wl["arch"] == synth.RESNET else None)
     blk = GpuBlock(wl, flat)
     stream = torch.cuda.current_stream().cuda_stream
     for i in range(2):
@@ -428,8 +507,8 @@ def test_eval_forward_matches_the_oracle_after_training_steps(name, kw):
     P.ppll_block_forward_eval(blk.h, to_device(x, wl), out2, None, stream)
     torch.cuda.synchronize()
     got_out = blk.x_out.float().cpu().numpy().reshape(want_out.shape)
-    assert rel_l2(got_out, want_out) <= tol
-    assert rel_l2(logits.cpu().numpy(), want_logits) <= tol
+    assert_close(got_out, want_out, OUT_TOL[wl["precision"]], "evaluation output", wl["dim"] if wl["arch"] == synth.VIT else wl["channels"], tol)
+    assert_close(logits.cpu().numpy(), want_logits, tol, "evaluation logits")
     assert torch.equal(out2, blk.x_out)
     for i, b in enumerate(params_before):
         assert np.array_equal(P.ppll_block_read_tensor(blk.h, P.T_PARAM, i), b)

@@ -380,12 +380,12 @@ def test_loss_decreases_when_overfitting_one_batch(case):
 
 
 # ------------------------------------------------------------------ what bf16 storage alone does
-def test_bf16_storage_alone_moves_relu_gradients_but_not_gelu_gradients():
-    """Oracle vs oracle: rounding stored activations and weight shadows to bf16 (arithmetic
-    still float64) flips the ReLU masks nearest zero, which moves the ResNet stage's
-    gradients by far more than 2e-2; the GELU network stays well inside it.  This is the
-    evidence behind the gradient ceiling used for the natural-statistics bf16 ResNet case
-    of the GPU parity tests."""
+def test_bf16_storage_alone_moves_relu_gradients_by_more_than_the_tolerance():
+    """Oracle vs oracle: rounding stored activations and filters to bf16 (arithmetic still
+    float64) flips the ReLU masks nearest zero, which moves the five-block ResNet stage's
+    gradients by far more than 2e-2 while loss and output stay inside it.  This is why the GPU
+    parity tests bound a ReLU network's bf16 gradients by this same oracle-vs-oracle distance,
+    computed per tensor in the test itself, instead of a flat figure."""
     wl = synth.workload("resnet_stage_bf16", batch=32)
     cfg = oracle_cfg(wl)
     flat = synth.make_params(O.param_spec(cfg), seed=0, jitter=True)
@@ -397,12 +397,13 @@ def test_bf16_storage_alone_moves_relu_gradients_but_not_gelu_gradients():
     worst = max(rel_l2(b.grads[n], a.grads[n]) for n in a.grads)
     assert 0.05 < worst < 0.3, worst
 
-    wl = synth.workload("vit_stage_bf16", batch=4, dim=96, heads=2, mlp_dim=192)
+
+def test_storage_mode_is_refused_for_the_vit_block():
+    """The ViT block takes no binary decision on a floating-point value, so its oracle has one mode: float64."""
+    wl = synth.workload("vit_stage_bf16", batch=2, dim=32, heads=2, mlp_dim=64)
     cfg = oracle_cfg(wl)
-    flat = synth.make_params(O.param_spec(cfg), seed=0, jitter=True)
-    x, y = synth.make_batch(wl)
-    a, b = O.block_init(cfg, flat), O.block_init(cfg, flat, storage="bf16")
-    oa, la = O.block_step(a, x.astype(np.float64), y, 1e-3)
-    ob, lb = O.block_step(b, x.astype(np.float64), y, 1e-3)
-    assert rel_l2(ob, oa) < 1e-2
-    assert max(rel_l2(b.grads[n], a.grads[n]) for n in a.grads) < 2e-2
+    flat = synth.make_params(O.param_spec(cfg), seed=0)
+    with pytest.raises(ValueError):
+        O.block_init(cfg, flat, storage="bf16")
+    with pytest.raises(ValueError):
+        O.block_init(oracle_cfg(synth.workload("resnet_stage_bf16", batch=2)), None, storage="fp16")
