@@ -146,6 +146,27 @@ int ppll_block_step(ppll_block_t* blk, const void* x_in_dev, const int32_t* labe
 int ppll_block_forward_eval(ppll_block_t* block, const void* x_in_dev, void* x_out_dev, float* logits_dev,
                             void* hip_stream);
 
+/* For callers that cannot allocate device memory or let a library do it (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it) and that have no spare block workspace to evaluate in:
+ * ppll_block_forward_eval with every intermediate activation placed in a buffer that is part of the library's
+ * own device image, PPLL_EVAL_SCRATCH_BYTES long, instead of the block's workspace.  The call allocates nothing
+ * on host or device and creates no stream or event; it reads the block's parameters and running statistics and
+ * writes only x_out_dev, logits_dev and that buffer, so the activations a training step of the same block has
+ * saved stay intact.  Results are bit-identical to ppll_block_forward_eval.
+ *  - Limit: all layers share one set of activation buffers; a block whose largest layer needs more than
+ *    PPLL_EVAL_SCRATCH_BYTES (a ViT stage of width 384, MLP 1536, 65 tokens fits up to batch 74) is refused
+ *    with PPLL_ERR_WORKSPACE before anything is enqueued.
+ *  - Every GPU the library has been used on holds its own copy of the buffer until the process ends; its
+ *    address is looked up once per device by ppll_block_init.  The block must live on the current device
+ *    (PPLL_ERR_STATE otherwise).
+ *  - All calls on one GPU share that GPU's buffer, whatever block or stream they are made for: calls that
+ *    overlap in time on one GPU race.  Order them on one stream or with events.  Nothing in the buffer has to
+ *    start at zero (every kernel of the path writes what it later reads), so it is never cleared and keeps the
+ *    previous call's contents. */
+#define PPLL_EVAL_SCRATCH_BYTES (64u << 20)
+int ppll_block_forward_eval_noalloc(ppll_block_t* block, const void* x_in_dev, void* x_out_dev, float* logits_dev,
+                                    void* hip_stream);
+
 /* Waits for the stream of the last step; returns that step's loss in
  * *loss_host (nullable).  Reports PPLL_ERR_LABEL / PPLL_ERR_HIP raised since the
  * previous sync. */

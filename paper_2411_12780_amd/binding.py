@@ -81,6 +81,7 @@ _SIGS = {
     "ppll_pipeline_destroy": (C.c_int, [C.c_void_p]),
     "ppll_probe_copy": (C.c_int, [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "ppll_block_forward_eval": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "ppll_block_forward_eval_noalloc": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ppll_block_phase_timers": (C.c_int, [C.c_void_p, C.c_int32]),
     "ppll_block_phase_times": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
     "ppll_profile_enable": (C.c_int, [C.c_int32]),
@@ -250,6 +251,13 @@ def ppll_pipeline_destroy(pipe: int) -> None:
 
 def ppll_block_forward_eval(block, x_in, x_out, logits=None, stream=None) -> None:
     _check(lib().ppll_block_forward_eval(block, _ptr(x_in), _ptr(x_out), _ptr(logits), _ptr(stream)))
+
+
+EVAL_SCRATCH_BYTES = 64 << 20
+
+
+def ppll_block_forward_eval_noalloc(block, x_in, x_out, logits=None, stream=None) -> None:
+    _check(lib().ppll_block_forward_eval_noalloc(block, _ptr(x_in), _ptr(x_out), _ptr(logits), _ptr(stream)))
 
 
 def ppll_block_phase_timers(block, on: bool) -> None:

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -24,6 +25,12 @@ using namespace ppll;
 struct ppll_block {
   Block b;
 };
+
+// Activation scratch of ppll_block_forward_eval_noalloc: part of the library's device image, so every GPU the
+// library runs on holds its own copy, at its own address, until the process ends.  In host code the name below
+// is only a handle for hipGetSymbolAddress; the address kernels can use is looked up once per device
+// (scratch_lookup) and kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[PPLL_EVAL_SCRATCH_BYTES];
 
 struct ppll_pipeline {
   int K = 0, depth = 0;
@@ -104,6 +111,31 @@ int tensor_lookup(ppll_block* h, int32_t kind, int32_t index, float** dev, size_
   *dev = base + b.tensors[index].off;
   *n = b.tensors[index].n;
   if (name) *name = b.tensors[index].name.c_str();
+  return PPLL_OK;
+}
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each HIP device, null until looked up
+std::mutex g_scratch_mu;
+
+// Device address of the built-in scratch buffer on the current device; the first call on a device asks the runtime
+// for it (with that device current, as it is here).  *dev_out receives the device ordinal.
+int scratch_lookup(void** ptr_out, int* dev_out) {
+  int dev = -1;
+  PPLL_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) { set_error("HIP device %d outside 0..%d", dev, kMaxDevices - 1); return PPLL_ERR_STATE; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      set_error("hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+      return PPLL_ERR_HIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  if (ptr_out) *ptr_out = g_scratch_ptr[dev];
+  if (dev_out) *dev_out = dev;
   return PPLL_OK;
 }
 
@@ -196,10 +228,13 @@ int ppll_block_init(const ppll_block_config* cfg, void* workspace_dev, size_t wo
   PPLL_TRY(validate_config(cfg));
   if (!out) { set_error("out is null"); return PPLL_ERR_NULL; }
   PPLL_TRY(check_aligned(workspace_dev, "workspace_dev"));
+  int device = -1;
+  PPLL_TRY(scratch_lookup(nullptr, &device));   // the library's set-up call: the built-in scratch address of this device
   ppll_block* h = new (std::nothrow) ppll_block();
   if (!h) { set_error("out of host memory"); return PPLL_ERR_STATE; }
   Block& b = h->b;
   b.cfg = *cfg;
+  b.device = device;
   size_t need = b.plan((char*)workspace_dev);
   if (workspace_bytes < need) {
     set_error("workspace has %zu bytes, %zu needed", workspace_bytes, need);
@@ -257,6 +292,28 @@ int ppll_block_forward_eval(ppll_block_t* h, const void* x_in_dev, void* x_out_d
   PPLL_TRY(check_aligned(x_out_dev, "x_out_dev"));
   if (logits_dev) PPLL_TRY(check_aligned(logits_dev, "logits_dev"));
   return h->b.forward_eval(x_in_dev, x_out_dev, logits_dev, (hipStream_t)hip_stream);
+}
+
+int ppll_block_forward_eval_noalloc(ppll_block_t* h, const void* x_in_dev, void* x_out_dev, float* logits_dev,
+                                    void* hip_stream) {
+  PPLL_TRY(block_alive(h));
+  PPLL_TRY(check_aligned(x_in_dev, "x_in_dev"));
+  PPLL_TRY(check_aligned(x_out_dev, "x_out_dev"));
+  if (logits_dev) PPLL_TRY(check_aligned(logits_dev, "logits_dev"));
+  int dev = -1;
+  PPLL_HIP(hipGetDevice(&dev));
+  if (dev != h->b.device) {
+    set_error("the block lives on HIP device %d, the current device is %d", h->b.device, dev);
+    return PPLL_ERR_STATE;
+  }
+  void* ptr = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    ptr = g_scratch_ptr[dev];   // looked up by ppll_block_init on this device
+  }
+  if (!ptr) { set_error("the built-in scratch buffer of device %d was never looked up", dev); return PPLL_ERR_STATE; }
+  return h->b.forward_eval_in_scratch(x_in_dev, x_out_dev, logits_dev, (hipStream_t)hip_stream, ptr,
+                                      (size_t)PPLL_EVAL_SCRATCH_BYTES);
 }
 
 int ppll_block_sync(ppll_block_t* h, float* loss_host) {

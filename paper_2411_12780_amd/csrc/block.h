@@ -33,6 +33,23 @@ struct BasicBlockActs {
   float *mean1, *rstd1, *mean2, *rstd2;
 };
 
+// Which buffers an evaluation-mode forward writes its intermediate activations to.  Either every layer has a
+// set of its own (the block's training buffers: per_layer / per_block point at them), or all layers share one
+// set and only the layer outputs alternate between two buffers (shared[l % 2]; the two sets differ in x2 / out).
+struct EvalBuffers {
+  const EncoderActs* per_layer = nullptr;
+  EncoderActs shared_enc[2] = {};
+  const EncoderActs& enc(int l) const { return per_layer ? per_layer[l] : shared_enc[l & 1]; }
+  const BasicBlockActs* per_block = nullptr;
+  BasicBlockActs shared_rb[2] = {};
+  const BasicBlockActs& rb(int i) const { return per_block ? per_block[i] : shared_rb[i & 1]; }
+  void *patches = nullptr, *embed_tmp = nullptr, *x0 = nullptr, *z = nullptr;          // ViT
+  float *head_mean = nullptr, *head_rstd = nullptr;
+  void *stem_c = nullptr, *stem_y = nullptr, *stem_xp = nullptr, *stem_wp = nullptr;   // ResNet
+  void *shortcut = nullptr, *aux_c = nullptr, *aux_y = nullptr, *pooled = nullptr;
+  float *stem_mean = nullptr, *stem_rstd = nullptr, *aux_mean = nullptr, *aux_rstd = nullptr;
+};
+
 struct Block {
   ppll_block_config cfg{};
   int dt = F32;              // activation element type
@@ -101,7 +118,8 @@ struct Block {
   // 16-channel matrix-core kernels (null: the stem runs on the generic kernels)
   void *stem_xp = nullptr, *stem_wp = nullptr;
   bool stem_pad = false;
-  int stem_conv_fwd(const void* x_in, hipStream_t s, float* stat = nullptr, int* stat_blocks = nullptr);
+  int stem_conv_fwd(const void* x_in, void* xp, void* wp, void* out, hipStream_t s, float* stat = nullptr,
+                    int* stat_blocks = nullptr);
   float *stem_mean = nullptr, *stem_rstd = nullptr;
   int bn_base = 0;                       // index of rb0.bn1 among the BatchNorm layers (1 behind a stem)
   size_t aux_conv_w = 0, aux_bn_g = 0, aux_bn_b = 0;
@@ -118,6 +136,12 @@ struct Block {
   // Evaluation-mode forward: x_out = M_j(x_in) (BatchNorm with running statistics); with logits_out the
   // auxiliary network's class scores [batch, num_classes] fp32 as well.  Changes no state but scratch.
   int forward_eval(const void* x_in, void* x_out, float* logits_out, hipStream_t s);
+  // The same with every intermediate activation inside [scratch, scratch + scratch_bytes) instead of the block's
+  // own buffers (all layers share one set there).  PPLL_ERR_WORKSPACE, before anything is enqueued, if the
+  // shapes need more than scratch_bytes.  Allocates nothing on host or device.
+  int forward_eval_in_scratch(const void* x_in, void* x_out, float* logits_out, hipStream_t s, void* scratch,
+                              size_t scratch_bytes);
+  int device = -1;               // HIP device the block was created on
   long steps = 0;
   hipStream_t last_stream = nullptr;
 
@@ -140,7 +164,9 @@ struct Block {
                const std::function<int()>& after_forward);
   int resnet_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
                   const std::function<int()>& after_forward);
-  int encoder_fwd(int l, const void* x, void* x2_out, hipStream_t s);
+  int encoder_fwd(int l, const EncoderActs& a, const void* x, void* x2_out, hipStream_t s);
+  int forward_eval_with(const EvalBuffers& e, const void* x_in, void* x_out, float* logits_out, hipStream_t s);
+  size_t plan_eval_scratch(char* base, EvalBuffers* e) const;
   int encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void* g_out, bool need_dx, hipStream_t s);
   int update(float lr, hipStream_t s);
 };

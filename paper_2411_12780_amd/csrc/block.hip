@@ -296,10 +296,9 @@ size_t Block::plan(char* base) {
 }
 
 // ------------------------------------------------------------------ ViT
-int Block::encoder_fwd(int l, const void* x, void* x2_out, hipStream_t s) {
+int Block::encoder_fwd(int l, const EncoderActs& a, const void* x, void* x2_out, hipStream_t s) {
   const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, M = cfg.batch * T;
   const EncoderParams& p = enc_p[l];
-  EncoderActs& a = enc_a[l];
   PPLL_TRY(launch_layernorm_fwd(s, x, dt, D, M, D, params + p.ln1_g, params + p.ln1_b, cfg.ln_eps, a.u1, a.mean1, a.rstd1));
   GemmArgs g = gemm_args();
   g.A = a.u1; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
@@ -400,7 +399,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   for (int l = 0; l < L; ++l) {
     layer_in[l] = x;
     void* dst = l == L - 1 ? x_out : enc_a[l].x2;
-    PPLL_TRY(encoder_fwd(l, x, dst, s));
+    PPLL_TRY(encoder_fwd(l, enc_a[l], x, dst, s));
     x = dst;
   }
   PPLL_TRY(mark_phase(1, s));   // module forward done
@@ -408,7 +407,7 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   // ---- auxiliary forward
   for (int l = L; l < L + A; ++l) {
     layer_in[l] = x;
-    PPLL_TRY(encoder_fwd(l, x, enc_a[l].x2, s));
+    PPLL_TRY(encoder_fwd(l, enc_a[l], x, enc_a[l].x2, s));
     x = enc_a[l].x2;
   }
   GemmArgs g = gemm_args();
@@ -490,13 +489,13 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
 
 // ------------------------------------------------------------------ ResNet
 // stem convolution img_c -> in_c into stem_c
-int Block::stem_conv_fwd(const void* x_in, hipStream_t s, float* stat, int* stat_blocks) {
+int Block::stem_conv_fwd(const void* x_in, void* xp, void* wp, void* out, hipStream_t s, float* stat, int* stat_blocks) {
   const int B = cfg.batch;
   if (!stem_pad)
-    return launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, stem_c, stat, stat_blocks);
-  PPLL_TRY(launch_pad_channels16(s, x_in, (size_t)B * in_h * in_w, cfg.img_c, stem_xp));
-  PPLL_TRY(launch_pad_filter16(s, params + stem_w, cfg.img_c, in_c, stem_wp));
-  return launch_conv3x3_fwd(s, stem_xp, stem_wp, BF16, dt, B, in_h, in_w, 16, in_c, 1, stem_c, stat, stat_blocks);
+    return launch_conv3x3_fwd(s, x_in, wptr(stem_w), wdt(), dt, B, in_h, in_w, cfg.img_c, in_c, 1, out, stat, stat_blocks);
+  PPLL_TRY(launch_pad_channels16(s, x_in, (size_t)B * in_h * in_w, cfg.img_c, xp));
+  PPLL_TRY(launch_pad_filter16(s, params + stem_w, cfg.img_c, in_c, wp));
+  return launch_conv3x3_fwd(s, xp, wp, BF16, dt, B, in_h, in_w, 16, in_c, 1, out, stat, stat_blocks);
 }
 
 int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
@@ -513,7 +512,7 @@ int Block::resnet_step(const void* x_in, const int32_t* labels, void* x_out, hip
   if (stem) {
     const int rows0 = B * in_h * in_w;
     int ready = 0;   // partial rows of the BatchNorm sums that the convolution has written itself
-    PPLL_TRY(stem_conv_fwd(x_in, s, partials, &ready));
+    PPLL_TRY(stem_conv_fwd(x_in, stem_xp, stem_wp, stem_c, s, partials, &ready));
     PPLL_TRY(launch_bn_train_fwd(s, stem_c, dt, rows0, in_c, eps, mom, partials, stem_mean, stem_rstd, run_mean(0), run_var(0),
                                  params + stem_g, params + stem_b, nullptr, stem_y, ready));
     x = stem_y;
@@ -650,6 +649,84 @@ int Block::update(float lr, hipStream_t s) {
 }
 
 int Block::forward_eval(const void* x_in, void* x_out, float* logits_out, hipStream_t s) {
+  EvalBuffers e;
+  e.per_layer = enc_a.data(); e.per_block = rb_a.data();
+  e.patches = patches; e.embed_tmp = embed_tmp; e.x0 = x0; e.z = z; e.head_mean = head_mean; e.head_rstd = head_rstd;
+  e.stem_c = stem_c; e.stem_y = stem_y; e.stem_xp = stem_xp; e.stem_wp = stem_wp; e.shortcut = shortcut;
+  e.aux_c = aux_c; e.aux_y = aux_y; e.pooled = pooled;
+  e.stem_mean = stem_mean; e.stem_rstd = stem_rstd; e.aux_mean = aux_mean; e.aux_rstd = aux_rstd;
+  return forward_eval_with(e, x_in, x_out, logits_out, s);
+}
+
+// One set of activation buffers for all layers, carved from `base` (null: only measure).  Returns the bytes used.
+size_t Block::plan_eval_scratch(char* base, EvalBuffers* e) const {
+  Bump bump(base);
+  const size_t B = (size_t)cfg.batch;
+  if (cfg.arch == PPLL_VIT) {
+    const size_t D = (size_t)cfg.dim, F = (size_t)cfg.mlp_dim, T = (size_t)cfg.tokens, H = (size_t)cfg.heads, M = B * T;
+    if (cfg.input_kind == PPLL_IN_IMAGE) {
+      e->patches = bump.take(B * (T - 1) * cfg.patch * cfg.patch * cfg.img_c * esz);
+      e->embed_tmp = bump.take(B * (T - 1) * D * esz);
+      e->x0 = bump.take(M * D * esz);
+    }
+    EncoderActs a{};
+    a.u1 = bump.take(M * D * esz); a.qkv = bump.take(M * 3 * D * esz); a.att = bump.take(M * D * esz);
+    a.x1 = bump.take(M * D * esz); a.u2 = bump.take(M * D * esz);
+    a.h = bump.take(M * F * esz); a.gl = bump.take(M * F * esz);
+    a.mean1 = bump.floats(M); a.rstd1 = bump.floats(M); a.mean2 = bump.floats(M); a.rstd2 = bump.floats(M);
+    a.lse = bump.floats(B * H * T);
+    e->shared_enc[0] = a; e->shared_enc[1] = a;
+    e->shared_enc[0].x2 = bump.take(M * D * esz);
+    e->shared_enc[1].x2 = bump.take(M * D * esz);
+    e->z = bump.take(B * D * esz);
+    e->head_mean = bump.floats(B); e->head_rstd = bump.floats(B);
+  } else {
+    const size_t A = (size_t)cfg.aux_channels;
+    const size_t Ho = (size_t)(cfg.height - 1) / 2 + 1, Wo = (size_t)(cfg.width - 1) / 2 + 1;
+    size_t widest = B * in_h * in_w * in_c;
+    int cmax = in_c;
+    for (const BasicBlockDims& d : rb_d) {
+      const size_t act = B * d.Ho * d.Wo * d.Co;
+      if (act > widest) widest = act;
+      if (d.Co > cmax) cmax = d.Co;
+    }
+    if (stem) {
+      e->stem_c = bump.take(widest * esz); e->stem_y = bump.take(widest * esz);
+      e->stem_mean = bump.floats(in_c); e->stem_rstd = bump.floats(in_c);
+      if (stem_pad) {
+        e->stem_xp = bump.take(B * in_h * in_w * 16 * esz);
+        e->stem_wp = bump.take((size_t)9 * 16 * in_c * esz);
+      }
+    }
+    BasicBlockActs a{};
+    a.c1 = bump.take(widest * esz); a.y1 = bump.take(widest * esz); a.c2 = bump.take(widest * esz);
+    a.mean1 = bump.floats(cmax); a.rstd1 = bump.floats(cmax); a.mean2 = bump.floats(cmax); a.rstd2 = bump.floats(cmax);
+    e->shared_rb[0] = a; e->shared_rb[1] = a;
+    e->shared_rb[0].out = bump.take(widest * esz);
+    e->shared_rb[1].out = bump.take(widest * esz);
+    e->shortcut = bump.take(widest * esz);
+    e->aux_c = bump.take(B * Ho * Wo * A * esz); e->aux_y = bump.take(B * Ho * Wo * A * esz);
+    e->pooled = bump.take(B * A * esz);
+    e->aux_mean = bump.floats(A); e->aux_rstd = bump.floats(A);
+  }
+  return (bump.off + 255) & ~(size_t)255;
+}
+
+int Block::forward_eval_in_scratch(const void* x_in, void* x_out, float* logits_out, hipStream_t s, void* scratch,
+                                   size_t scratch_bytes) {
+  EvalBuffers e;
+  const size_t need = plan_eval_scratch(nullptr, &e);
+  if (need > scratch_bytes) {
+    set_error("the evaluation forward of this block needs %zu bytes of activation scratch, the built-in buffer holds %zu",
+              need, scratch_bytes);
+    return PPLL_ERR_WORKSPACE;
+  }
+  e = EvalBuffers();
+  plan_eval_scratch((char*)scratch, &e);
+  return forward_eval_with(e, x_in, x_out, logits_out, s);
+}
+
+int Block::forward_eval_with(const EvalBuffers& e, const void* x_in, void* x_out, float* logits_out, hipStream_t s) {
   last_stream = s;
   const int B = cfg.batch, C = cfg.num_classes;
   GemmArgs g = gemm_args();
@@ -658,28 +735,28 @@ int Block::forward_eval(const void* x_in, void* x_out, float* logits_out, hipStr
     const void* x = x_in;
     if (cfg.input_kind == PPLL_IN_IMAGE) {
       const int ppc = cfg.patch * cfg.patch * cfg.img_c;
-      PPLL_TRY(launch_patchify(s, x_in, dt, B, cfg.img_h, cfg.img_w, cfg.img_c, cfg.patch, patches));
-      g.A = patches; g.a_dt = dt; g.a_sm = ppc; g.a_sk = 1;
+      PPLL_TRY(launch_patchify(s, x_in, dt, B, cfg.img_h, cfg.img_w, cfg.img_c, cfg.patch, e.patches));
+      g.A = e.patches; g.a_dt = dt; g.a_sm = ppc; g.a_sk = 1;
       g.B = wptr(pe_w); g.b_dt = wdt(); g.b_sk = D; g.b_sn = 1;
-      g.C = embed_tmp; g.c_dt = dt; g.ldc = D; g.M = B * (T - 1); g.N = D; g.K = ppc; g.bias = params + pe_b;
+      g.C = e.embed_tmp; g.c_dt = dt; g.ldc = D; g.M = B * (T - 1); g.N = D; g.K = ppc; g.bias = params + pe_b;
       if (T > 1) PPLL_TRY(launch_gemm(s, g));
-      PPLL_TRY(launch_assemble_tokens(s, embed_tmp, dt, params + cls, params + pos, B, T, D, x0));
-      x = x0;
+      PPLL_TRY(launch_assemble_tokens(s, e.embed_tmp, dt, params + cls, params + pos, B, T, D, e.x0));
+      x = e.x0;
     }
     for (int l = 0; l < L; ++l) {
-      void* dst = l == L - 1 ? x_out : enc_a[l].x2;
-      PPLL_TRY(encoder_fwd(l, x, dst, s));
+      void* dst = l == L - 1 ? x_out : e.enc(l).x2;
+      PPLL_TRY(encoder_fwd(l, e.enc(l), x, dst, s));
       x = dst;
     }
     if (!logits_out) return PPLL_OK;
     for (int l = L; l < L + A; ++l) {
-      PPLL_TRY(encoder_fwd(l, x, enc_a[l].x2, s));
-      x = enc_a[l].x2;
+      PPLL_TRY(encoder_fwd(l, e.enc(l), x, e.enc(l).x2, s));
+      x = e.enc(l).x2;
     }
-    PPLL_TRY(launch_layernorm_fwd(s, x, dt, (long)T * D, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, z,
-                                  head_mean, head_rstd));
+    PPLL_TRY(launch_layernorm_fwd(s, x, dt, (long)T * D, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, e.z,
+                                  e.head_mean, e.head_rstd));
     g = gemm_args();
-    g.A = z; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+    g.A = e.z; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
     g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
     g.C = logits_out; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = D; g.bias = params + head_b;
     return launch_gemm_generic(s, g);
@@ -689,16 +766,16 @@ int Block::forward_eval(const void* x_in, void* x_out, float* logits_out, hipStr
   const float eps = cfg.bn_eps;
   const void* x = x_in;
   if (stem) {
-    PPLL_TRY(stem_conv_fwd(x_in, s));
-    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[0], bn_var_run + bn_off[0], in_c, eps, stem_mean, stem_rstd));
-    PPLL_TRY(launch_bn_apply(s, stem_c, dt, B * in_h * in_w, in_c, stem_mean, stem_rstd, params + stem_g, params + stem_b, nullptr,
-                             stem_y));
-    x = stem_y;
+    PPLL_TRY(stem_conv_fwd(x_in, e.stem_xp, e.stem_wp, e.stem_c, s));
+    PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[0], bn_var_run + bn_off[0], in_c, eps, e.stem_mean, e.stem_rstd));
+    PPLL_TRY(launch_bn_apply(s, e.stem_c, dt, B * in_h * in_w, in_c, e.stem_mean, e.stem_rstd, params + stem_g, params + stem_b,
+                             nullptr, e.stem_y));
+    x = e.stem_y;
   }
   for (int i = 0; i < n; ++i) {
     const BasicBlockParams& p = rb_p[i];
     const BasicBlockDims& d = rb_d[i];
-    BasicBlockActs& a = rb_a[i];
+    const BasicBlockActs& a = e.rb(i);
     const int rows = B * d.Ho * d.Wo, b1 = bn_base + 2 * i, b2 = b1 + 1;
     void* out = i == n - 1 ? x_out : a.out;
     PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(p.conv1_w), wdt(), dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, a.c1));
@@ -708,19 +785,20 @@ int Block::forward_eval(const void* x_in, void* x_out, float* logits_out, hipStr
     PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[b2], bn_var_run + bn_off[b2], d.Co, eps, a.mean2, a.rstd2));
     const void* skip = x;
     if (d.stride != 1 || d.Ci != d.Co) {
-      PPLL_TRY(launch_shortcut_fwd(s, x, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, shortcut));
-      skip = shortcut;
+      PPLL_TRY(launch_shortcut_fwd(s, x, dt, B, d.Hin, d.Win, d.Ci, d.Co, d.stride, e.shortcut));
+      skip = e.shortcut;
     }
     PPLL_TRY(launch_bn_apply(s, a.c2, dt, rows, d.Co, a.mean2, a.rstd2, params + p.bn2_g, params + p.bn2_b, skip, out));
     x = out;
   }
   if (!logits_out) return PPLL_OK;
-  PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, aux_c));
+  PPLL_TRY(launch_conv3x3_fwd(s, x, wptr(aux_conv_w), wdt(), dt, B, H, W, Ch, A, 2, e.aux_c));
   PPLL_TRY(launch_bn_running_stats(s, bn_mean_run + bn_off[bn_base + 2 * n], bn_var_run + bn_off[bn_base + 2 * n], A, eps,
-                                   aux_mean, aux_rstd));
-  PPLL_TRY(launch_bn_apply(s, aux_c, dt, arows, A, aux_mean, aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr, aux_y));
-  PPLL_TRY(launch_gap_fwd(s, aux_y, dt, B, Ho * Wo, A, pooled));
-  g.A = pooled; g.a_dt = dt; g.a_sm = A; g.a_sk = 1;
+                                   e.aux_mean, e.aux_rstd));
+  PPLL_TRY(launch_bn_apply(s, e.aux_c, dt, arows, A, e.aux_mean, e.aux_rstd, params + aux_bn_g, params + aux_bn_b, nullptr,
+                           e.aux_y));
+  PPLL_TRY(launch_gap_fwd(s, e.aux_y, dt, B, Ho * Wo, A, e.pooled));
+  g.A = e.pooled; g.a_dt = dt; g.a_sm = A; g.a_sk = 1;
   g.B = params + head_w; g.b_dt = F32; g.b_sk = C; g.b_sn = 1;
   g.C = logits_out; g.c_dt = F32; g.ldc = C; g.M = B; g.N = C; g.K = A; g.bias = params + head_b;
   return launch_gemm_generic(s, g);
