@@ -58,15 +58,59 @@ def step_flops(wl: dict) -> float:
     return total + 3.0 * aux + 3.0 * 2.0 * B * A * wl["num_classes"]
 
 
-def measured_traffic(workload: str):
-    """HBM bytes per GEMM launch from the committed counter summary of this workload (two rocprofv3
-    --pmc runs, scaled by the copy probe); None for a workload without such a summary."""
-    path = os.path.join(ROOT, "profiles", f"{workload}_gemm_hbm_traffic.json")
+def kernel_source_sha() -> str:
+    """Hash of the kernel sources the library is built from: a counter summary is only valid for the sources it
+    was taken with."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2411_12780_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".hip", ".h")):
+            with open(os.path.join(csrc, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str, kind: str):
+    """HBM bytes per launch of the dominant kernel class (kind "gemm" or "conv") from the committed counter
+    summary of this workload (two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by what the same
+    counter reads for the copy probe).  Counters cannot be read inside a timing run, so the figure comes from
+    profiles/; it is reported only if that summary was taken with the kernel sources this library is built from
+    (their hash is stamped into it), else None with the reason."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_{kind}_hbm_traffic.json")
     try:
         with open(path) as f:
-            return float(json.load(f)["bytes_per_launch"])
+            rec = json.load(f)
+        if rec.get("kernel_source_sha") != kernel_source_sha():
+            return None, f"{os.path.basename(path)} was taken with other kernel sources ({rec.get('kernel_source_sha')})"
+        return float(rec["bytes_per_launch"]), None
     except (OSError, KeyError, ValueError):
-        return None
+        return None, "no counter summary committed for this workload"
+
+
+def device_clock_mhz():
+    """Peak engine clock the HIP runtime reports for device 0 (hipDeviceAttributeClockRate, kHz), or None."""
+    import ctypes
+    try:
+        hip = ctypes.CDLL("libamdhip64.so")       # already loaded by PyTorch: the same runtime
+        v = ctypes.c_int(0)
+        if hip.hipDeviceGetAttribute(ctypes.byref(v), 5, 0) == 0 and 2e5 < v.value < 1e7:
+            return v.value / 1e3
+    except OSError:
+        pass
+    return None
+
+
+def event_step_times(torch, run_one, steps: int):
+    """Per-step durations in milliseconds from HIP events recorded on the stream the steps are enqueued on (the
+    caller's current stream) between consecutive steps."""
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evs[0].record()
+    for i in range(steps):
+        run_one(i)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    return [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
 
 
 def bench_pipeline(args, torch, P, synth, dev) -> int:
@@ -254,6 +298,13 @@ def main() -> int:
     last_loss = P.ppll_block_sync(blk)
     ms_per_step = 1e3 * elapsed / args.steps
     flops = step_flops(wl)
+    # the same steps once more, each between two events on the stream: median and minimum step time
+    per_step = sorted(event_step_times(torch, lambda i: P.ppll_block_step(blk, xs[i % ring], ys[i % ring], lr, x_out, loss, stream),
+                                       args.steps))
+    props = torch.cuda.get_device_properties(0)
+    clock_mhz = device_clock_mhz()
+    # CUs x 4096 flop/clk/CU (dense bf16 MFMA) x the clock the device reports
+    device_peak_tflops = props.multi_processor_count * 4096 * clock_mhz * 1e6 / 1e12 if clock_mhz else None
     out = {
         "metric": "local-block train step images/sec on 1 MI355X; % bf16 MFMA peak",
         "value": wl["batch"] / (elapsed / args.steps),
@@ -268,24 +319,32 @@ def main() -> int:
         "step_gflop": flops / 1e9,
         "step_tflops": flops / (elapsed / args.steps) / 1e12,
         "mfma_peak_frac_step": flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
+        "ms_per_step_events": {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]},
+        "images_per_s_at_median": wl["batch"] / (per_step[len(per_step) // 2] * 1e-3),
+        "device_reported": {"compute_units": props.multi_processor_count, "clock_mhz": clock_mhz,
+                            "bf16_peak_tflops_at_that_clock": device_peak_tflops,
+                            "mfma_peak_frac_step_at_that_clock":
+                                flops / (elapsed / args.steps) / 1e12 / device_peak_tflops if device_peak_tflops else None},
         "loss_last_step": last_loss,
     }
 
     if not args.no_roofline:
         # second pass over the same workload with every GEMM launch bracketed by HIP events
-        P.ppll_profile_enable(True)
-        P.ppll_profile_read()
-        P.ppll_profile_read_conv()
+        P.ppll_block_profile_enable(blk, True)
+        P.ppll_block_profile_read(blk)
+        P.ppll_block_profile_read_conv(blk)
         run(args.steps)
         torch.cuda.synchronize()
-        gemm_ms, gemm_flops, launches = P.ppll_profile_read()
-        conv_ms, conv_bytes, conv_launches = P.ppll_profile_read_conv()
-        P.ppll_profile_enable(False)
+        gemm_ms, gemm_flops, launches = P.ppll_block_profile_read(blk)
+        conv_ms, conv_bytes, conv_launches = P.ppll_block_profile_read_conv(blk)
+        P.ppll_block_profile_enable(blk, False)
         if launches > 0:
             achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
+            traffic, why_not = measured_traffic(args.workload, "gemm")
             out["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all variants: Linear fwd/dgrad/wgrad)",
                                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                               "frac": achieved / PEAK_BF16_TFLOPS, "traffic": measured_traffic(args.workload),
+                               "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                               **({"traffic_missing_because": why_not} if why_not else {}),
                                "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy probe)",
                                "launches_per_step": launches / args.steps,
                                "avg_launch_us": 1e3 * gemm_ms / launches,
@@ -295,9 +354,12 @@ def main() -> int:
         elif conv_launches > 0:
             # ResNet blocks: the dominant kernel is the 3x3 convolution (forward + input gradient), bound by HBM
             gbs = conv_bytes / (conv_ms * 1e-3) / 1e9
+            traffic, why_not = measured_traffic(args.workload, "conv")
             out["roofline"] = {"bound": "hbm", "kernel": "conv3x3_mfma_kernel (forward and input gradient)",
                                "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
-                               "traffic": None, "launches_per_step": conv_launches / args.steps,
+                               "traffic": traffic, **({"traffic_missing_because": why_not} if why_not else {}),
+                               "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy probe)",
+                               "launches_per_step": conv_launches / args.steps,
                                "avg_launch_us": 1e3 * conv_ms / conv_launches,
                                "conv_ms_per_step": conv_ms / args.steps,
                                "algorithmic_bytes_per_launch": conv_bytes / conv_launches}
@@ -335,6 +397,15 @@ def main() -> int:
         out["cpu_baseline"] = {"value": wl["batch"] / cpu_s, "unit": "images/s", "cores": threads,
                                "kind": "oracle", "sample": f"{n_steps} full step(s) of the same workload "
                                f"(batch {wl['batch']}), float64 numpy oracle, {cpu_s:.2f} s per step"}
+        if n_steps > 1:   # a small workload: the same on one core as well
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                t0 = time.perf_counter()
+                for _ in range(n_steps):
+                    O.block_step(st, x.astype(np.float64), y, lr)
+                one_s = (time.perf_counter() - t0) / n_steps
+            out["cpu_baseline"]["one_core"] = {"value": wl["batch"] / one_s, "unit": "images/s", "cores": 1,
+                                               "sample": f"{n_steps} step(s), {one_s:.3f} s per step"}
     P.ppll_block_destroy(blk)
     print(json.dumps(out))
     return 0

@@ -21,7 +21,7 @@
  *  - The caller allocates and frees every device byte (workspace, inputs,
  *    outputs, loss) and owns the HIP streams.  The library carves parameters,
  *    optimizer moments, saved activations and queue slots out of the workspace
- *    and frees only its host-side handle.
+ *    and owns only its host-side records, events and side streams.
  *  - Argument errors are detected on the host before anything is enqueued and
  *    leave the handle untouched.  An out-of-range label raises a sticky device
  *    flag that the next *_sync reports as PPLL_ERR_LABEL.
@@ -181,7 +181,10 @@ int ppll_block_tensor_info(ppll_block_t* blk, int32_t kind, int32_t index, const
 int ppll_block_read_tensor(ppll_block_t* blk, int32_t kind, int32_t index, float* host_out, size_t n);
 int ppll_block_write_tensor(ppll_block_t* blk, int32_t kind, int32_t index, const float* host_in, size_t n);
 
-/* Frees the host-side handle (device memory belongs to the caller). */
+/* Ends the block: waits for its last stream, releases the events and the side stream it created, and marks the
+ * handle destroyed.  Device memory belongs to the caller.  The small host-side record itself stays allocated for
+ * the life of the process, so that a later call with the stale handle is reported as PPLL_ERR_STATE instead of
+ * touching freed memory. */
 int ppll_block_destroy(ppll_block_t* blk);
 
 /* Pipeline of K blocks on K HIP streams of one GPU (Algorithm 1, "parallel
@@ -215,25 +218,23 @@ int ppll_pipeline_block(ppll_pipeline_t* pipe, int32_t j, ppll_block_t** borrowe
 /* Device address and byte size of the last block's most recent output. */
 int ppll_pipeline_output(ppll_pipeline_t* pipe, const void** x_out_dev, size_t* bytes);
 
+/* Ends the pipeline and its K blocks (as ppll_block_destroy: handles are marked destroyed, their host-side
+ * records stay allocated so that stale handles are reported, not dereferenced after free). */
 int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
 
-/* Measurement aid (no part of the method).  While enabled, every launch of the
- * bf16 matrix-core GEMM kernel (gemm_mfma_kernel, all variants), which carries
- * the bulk of the step's arithmetic, is bracketed by a pair of HIP events on its
- * own stream (the split-K reduce that may follow is outside the bracket).
- * ppll_profile_read waits for those events and returns, since the previous
- * read: their summed duration in milliseconds, the algorithmic flops 2*M*N*K of
- * the bracketed launches, and their count (each pointer nullable).  The events
- * add host and stream overhead: time whole steps with profiling off.  While
- * enabled, a block also keeps every launch on the step's own stream (no side
- * stream for weight gradients), so that each bracket holds one kernel running
- * alone. */
-int ppll_profile_enable(int32_t on);
-int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
-/* The same for the bf16 matrix-core convolution kernel (forward and input gradient of the ResNet
- * blocks): summed duration, algorithmic bytes (input tensor + output tensor + filter once each, plus the
- * two tensors of the fused shortcut gradient where present) and launch count since the previous read. */
-int ppll_profile_read_conv(double* conv_ms, double* conv_bytes, int64_t* conv_launches);
+/* Measurement aid (no part of the method), per block.  While it is on for a block, every launch of the bf16
+ * matrix-core GEMM kernel (gemm_mfma_kernel, all variants) and of the bf16 matrix-core convolution kernel that the
+ * block's steps make is bracketed by a pair of HIP events on its own stream (a split-K reduce that may follow is
+ * outside the bracket), and the block keeps every launch on the step's own stream (no side stream for weight
+ * gradients), so that each bracket holds one kernel running alone.  Other blocks are not affected.
+ * ppll_block_profile_read waits for those events and returns, since the previous read: the summed duration of the
+ * GEMM launches in milliseconds, their algorithmic flops 2*M*N*K, and their count (each pointer nullable);
+ * ppll_block_profile_read_conv the same for the convolution launches (forward and input gradient of the ResNet
+ * blocks) with their algorithmic bytes: input tensor + output tensor + filter once each, plus the two tensors of
+ * the fused shortcut gradient where present.  The events add host and stream overhead: time whole steps with it off. */
+int ppll_block_profile_enable(ppll_block_t* block, int32_t on);
+int ppll_block_profile_read(ppll_block_t* block, double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
+int ppll_block_profile_read_conv(ppll_block_t* block, double* conv_ms, double* conv_bytes, int64_t* conv_launches);
 
 /* Phase timers in the symbols of the paper's time model (Section 3.3: S_PPLL = f_1 + f_a1 + B_a1 +
  * U_a1): with timers on, every step of the block records HIP events on its stream at the ends of

@@ -84,9 +84,9 @@ _SIGS = {
     "ppll_block_forward_eval_noalloc": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
     "ppll_block_phase_timers": (C.c_int, [C.c_void_p, C.c_int32]),
     "ppll_block_phase_times": (C.c_int, [C.c_void_p, C.POINTER(C.c_float)]),
-    "ppll_profile_enable": (C.c_int, [C.c_int32]),
-    "ppll_profile_read": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
-    "ppll_profile_read_conv": (C.c_int, [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "ppll_block_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
+    "ppll_block_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "ppll_block_profile_read_conv": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -271,21 +271,21 @@ def ppll_block_phase_times(block):
     return tuple(float(v) for v in ms)
 
 
-def ppll_profile_enable(on: bool) -> None:
-    _check(lib().ppll_profile_enable(1 if on else 0))
+def ppll_block_profile_enable(block, on: bool) -> None:
+    _check(lib().ppll_block_profile_enable(block, 1 if on else 0))
 
 
-def ppll_profile_read():
-    """(milliseconds, flops, launches) of the GEMM launches bracketed since the last read."""
+def ppll_block_profile_read(block):
+    """(milliseconds, flops, launches) of the block's GEMM launches bracketed since the last read."""
     ms, fl, n = C.c_double(0), C.c_double(0), C.c_int64(0)
-    _check(lib().ppll_profile_read(C.byref(ms), C.byref(fl), C.byref(n)))
+    _check(lib().ppll_block_profile_read(block, C.byref(ms), C.byref(fl), C.byref(n)))
     return ms.value, fl.value, n.value
 
 
-def ppll_profile_read_conv():
-    """(milliseconds, algorithmic bytes, launches) of the convolution launches bracketed since the last read."""
+def ppll_block_profile_read_conv(block):
+    """(milliseconds, algorithmic bytes, launches) of the block's convolution launches bracketed since the last read."""
     ms, by, n = C.c_double(0), C.c_double(0), C.c_int64(0)
-    _check(lib().ppll_profile_read_conv(C.byref(ms), C.byref(by), C.byref(n)))
+    _check(lib().ppll_block_profile_read_conv(block, C.byref(ms), C.byref(by), C.byref(n)))
     return ms.value, by.value, n.value
 
 

@@ -156,36 +156,6 @@ int ppll_probe_copy(const void* src_dev, void* dst_dev, size_t bytes, void* hip_
   return launch_copy_probe((hipStream_t)hip_stream, src_dev, dst_dev, bytes);
 }
 
-int ppll_profile_enable(int32_t on) { profile_enable(on != 0); return PPLL_OK; }
-
-// One read drains both kinds; the other kind's figures are kept for its own read call.
-namespace {
-double g_read_ms[2] = {0, 0}, g_read_units[2] = {0, 0};
-long long g_read_n[2] = {0, 0};
-int profile_drain() {
-  double ms[2], units[2];
-  long long n[2];
-  PPLL_TRY(profile_read(ms, units, n));
-  for (int k = 0; k < 2; ++k) { g_read_ms[k] += ms[k]; g_read_units[k] += units[k]; g_read_n[k] += n[k]; }
-  return PPLL_OK;
-}
-int profile_take(int kind, double* ms, double* units, int64_t* launches) {
-  PPLL_TRY(profile_drain());
-  if (ms) *ms = g_read_ms[kind];
-  if (units) *units = g_read_units[kind];
-  if (launches) *launches = g_read_n[kind];
-  g_read_ms[kind] = 0; g_read_units[kind] = 0; g_read_n[kind] = 0;
-  return PPLL_OK;
-}
-}  // namespace
-
-int ppll_profile_read(double* gemm_ms, double* gemm_flops, int64_t* gemm_launches) {
-  return profile_take(0, gemm_ms, gemm_flops, gemm_launches);
-}
-int ppll_profile_read_conv(double* conv_ms, double* conv_bytes, int64_t* conv_launches) {
-  return profile_take(1, conv_ms, conv_bytes, conv_launches);
-}
-
 int ppll_block_workspace_bytes(const ppll_block_config* cfg, size_t* bytes) {
   PPLL_TRY(validate_config(cfg));
   if (!bytes) { set_error("bytes is null"); return PPLL_ERR_NULL; }
@@ -332,6 +302,32 @@ int ppll_block_sync(ppll_block_t* h, float* loss_host) {
   return PPLL_OK;
 }
 
+int ppll_block_profile_enable(ppll_block_t* h, int32_t on) {
+  PPLL_TRY(block_alive(h));
+  h->b.time_launches = on != 0;
+  return PPLL_OK;
+}
+
+namespace {
+int profile_take(ppll_block* h, int kind, double* ms, double* units, int64_t* launches) {
+  PPLL_TRY(block_alive(h));
+  LaunchTimes& t = h->b.times;
+  PPLL_TRY(profile_drain(t));
+  if (ms) *ms = t.ms[kind];
+  if (units) *units = t.units[kind];
+  if (launches) *launches = t.launches[kind];
+  t.ms[kind] = 0; t.units[kind] = 0; t.launches[kind] = 0;
+  return PPLL_OK;
+}
+}  // namespace
+
+int ppll_block_profile_read(ppll_block_t* h, double* gemm_ms, double* gemm_flops, int64_t* gemm_launches) {
+  return profile_take(h, 0, gemm_ms, gemm_flops, gemm_launches);
+}
+int ppll_block_profile_read_conv(ppll_block_t* h, double* conv_ms, double* conv_bytes, int64_t* conv_launches) {
+  return profile_take(h, 1, conv_ms, conv_bytes, conv_launches);
+}
+
 int ppll_block_phase_timers(ppll_block_t* h, int32_t on) {
   PPLL_TRY(block_alive(h));
   h->b.phase_timers = on != 0;
@@ -408,6 +404,7 @@ int ppll_block_destroy(ppll_block_t* h) {
     e = nullptr;
   }
   h->b.side_destroy();
+  profile_destroy(h->b.times);
   h->b.alive = false;   // the handle stays allocated so that later misuse is reported, not undefined
   return PPLL_OK;
 }

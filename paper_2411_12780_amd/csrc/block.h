@@ -99,6 +99,8 @@ struct Block {
   // the layers below, which never reads them; the step's stream waits for the side stream before the update.
   // Off for blocks driven by a pipeline: there the other blocks' streams already fill the chip.
   bool use_side = true;
+  bool time_launches = false;          // bracket every contraction launch of this block's steps with events
+  LaunchTimes times;
   hipStream_t side = nullptr;
   hipEvent_t side_fork = nullptr, side_join = nullptr;
   bool side_busy = false;              // something was launched on the side stream in this step
@@ -150,8 +152,8 @@ struct Block {
   // `base` (null: only measure).  Returns the bytes needed.
   size_t plan(char* base);
 
-  int in_elems() const;
-  int out_elems() const;
+  size_t in_elems() const;
+  size_t out_elems() const;
 
   // Forward of the module into x_out; `after_forward` runs on the host right
   // after the forward kernels are enqueued (the pipeline publishes the slot

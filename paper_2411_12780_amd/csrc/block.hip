@@ -61,6 +61,16 @@ int validate_config(const ppll_block_config* c) {
       if ((c->img_h / c->patch) * (c->img_w / c->patch) + 1 != c->tokens)
         return bad("tokens must equal (img_h/patch)*(img_w/patch) + 1");
     }
+    // every limit a kernel of the step would otherwise hit at launch time, when earlier kernels are already enqueued
+    const size_t dh = (size_t)(c->dim / c->heads), T = (size_t)c->tokens;
+    if (c->precision != PPLL_BF16 || dh != 64) {   // the run-time-typed attention kernels keep K, V (or Q, dO) of one head in LDS
+      const size_t lds = (2 * T * (dh + 1) + 8 * dh + 10 * T) * sizeof(float);
+      if (lds > 160 * 1024) return bad("tokens x head dimension needs more than 160 KB of LDS in the attention kernels of this path");
+    }
+    const size_t widest = (size_t)(3 * c->dim > c->mlp_dim ? 3 * c->dim : c->mlp_dim);
+    if ((size_t)c->batch * T * widest > ((size_t)1 << 31) - 1) return bad("batch x tokens x layer width above 2^31 - 1 elements");
+    if (c->input_kind == PPLL_IN_IMAGE && (size_t)c->batch * c->img_h * c->img_w * c->img_c > ((size_t)1 << 31) - 1)
+      return bad("image batch above 2^31 - 1 elements");
   } else if (c->arch == PPLL_RESNET) {
     if (c->input_kind != PPLL_IN_IMAGE && c->input_kind != PPLL_IN_ACTIVATION) return bad("input_kind");
     if (c->channels < 1 || c->aux_channels < 1 || c->height < 2 || c->width < 2 || c->n_basic_blocks < 1)
@@ -75,23 +85,28 @@ int validate_config(const ppll_block_config* c) {
         return bad("the stem keeps the image size: img_h, img_w must equal the first basic block's input size");
     }
     if (c->bn_eps <= 0.f || c->bn_momentum < 0.f || c->bn_momentum > 1.f) return bad("bn_eps > 0 and bn_momentum in [0,1] required");
+    {
+      const size_t m = c->transition_block > 0 ? 2 : 1, wide = c->channels > c->aux_channels ? c->channels : c->aux_channels;
+      if ((size_t)c->batch * (m * c->height) * (m * c->width) * wide > ((size_t)1 << 31) - 1)
+        return bad("batch x map x channels above 2^31 - 1 elements");
+    }
   } else {
     return bad("arch must be PPLL_VIT or PPLL_RESNET");
   }
   return PPLL_OK;
 }
 
-int Block::in_elems() const {
+size_t Block::in_elems() const {
+  const size_t B = (size_t)cfg.batch;
   if (cfg.arch == PPLL_VIT)
-    return cfg.input_kind == PPLL_IN_IMAGE ? cfg.batch * cfg.img_h * cfg.img_w * cfg.img_c
-                                           : cfg.batch * cfg.tokens * cfg.dim;
-  if (cfg.input_kind == PPLL_IN_IMAGE) return cfg.batch * cfg.img_h * cfg.img_w * cfg.img_c;
-  const int m = cfg.transition_block > 0 ? 2 : 1;
-  return cfg.batch * (m * cfg.height) * (m * cfg.width) * (cfg.channels / m);
+    return cfg.input_kind == PPLL_IN_IMAGE ? B * cfg.img_h * cfg.img_w * cfg.img_c : B * cfg.tokens * cfg.dim;
+  if (cfg.input_kind == PPLL_IN_IMAGE) return B * cfg.img_h * cfg.img_w * cfg.img_c;
+  const size_t m = cfg.transition_block > 0 ? 2 : 1;
+  return B * (m * cfg.height) * (m * cfg.width) * (cfg.channels / m);
 }
-int Block::out_elems() const {
-  if (cfg.arch == PPLL_VIT) return cfg.batch * cfg.tokens * cfg.dim;
-  return cfg.batch * cfg.height * cfg.width * cfg.channels;
+size_t Block::out_elems() const {
+  if (cfg.arch == PPLL_VIT) return (size_t)cfg.batch * cfg.tokens * cfg.dim;
+  return (size_t)cfg.batch * cfg.height * cfg.width * cfg.channels;
 }
 
 size_t Block::plan(char* base) {
@@ -837,16 +852,24 @@ int Block::mark_phase(int i, hipStream_t s) {
   return PPLL_OK;
 }
 
+namespace {
+struct TimesBinding {   // binds a block's launch record to this thread for the extent of a step
+  explicit TimesBinding(LaunchTimes* t) { profile_bind(t); }
+  ~TimesBinding() { profile_bind(nullptr); }
+};
+}  // namespace
+
 int Block::step(const void* x_in, const int32_t* labels, float lr, void* x_out, float* loss_out, hipStream_t s,
                 const std::function<int()>& after_forward) {
   last_stream = s;
+  TimesBinding binding(time_launches ? &times : nullptr);
   rq.reset();
   loss_copy = loss_out;   // the loss kernel writes it there as well
   PPLL_TRY(mark_phase(0, s));
   if (cfg.arch == PPLL_VIT) PPLL_TRY(vit_step(x_in, labels, x_out, s, after_forward));
   else PPLL_TRY(resnet_step(x_in, labels, x_out, s, after_forward));
+  PPLL_TRY(rq.flush(s));        // the queued second stages of the gradient reductions belong to the backward pass
   PPLL_TRY(mark_phase(3, s));   // backward done (weight gradients included); what follows is the update
-  PPLL_TRY(rq.flush(s));
   PPLL_TRY(update(lr, s));
   PPLL_TRY(mark_phase(4, s));
 

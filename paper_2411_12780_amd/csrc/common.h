@@ -104,12 +104,22 @@ int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n);   // eve
 // `one_launch`: take the grouped kernel whenever all products allow it, however few tiles they have
 int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch = false);
 bool gemm_group_in_one_launch(const GemmArgs* gs, int n);   // every product fits the grouped kernel (n > 1)
-void profile_enable(bool on);
-bool profile_enabled();
-// event pair around one launch (profiling only); kind 0: GEMM, units = flops; kind 1: convolution, units = bytes
+// Per-launch timing of the contraction kernels (a measurement aid, off unless a block asks for it).  A block that
+// times its launches binds its record to the calling thread for the duration of a step; the launch functions
+// below the block engine then bracket each contraction launch with a pair of events on its stream.
+struct TimedLaunch { hipEvent_t a, b; double units; int kind; };   // kind 0: GEMM (units = flops), 1: convolution (units = bytes)
+struct LaunchTimes {
+  std::vector<TimedLaunch> timed;
+  std::vector<hipEvent_t> pool;
+  double ms[2] = {0, 0}, units[2] = {0, 0};
+  long long launches[2] = {0, 0};
+};
+void profile_bind(LaunchTimes* t);     // null: launches of this thread are not timed
+bool profile_enabled();                // a record is bound to this thread
 int profile_begin(hipStream_t s, double units, void** token, int kind = 0);
 int profile_end(hipStream_t s, void* token);
-int profile_read(double ms[2], double units[2], long long launches[2]);   // index = kind
+int profile_drain(LaunchTimes& t);     // waits for the recorded events and adds them to t.ms / t.units / t.launches
+void profile_destroy(LaunchTimes& t);
 int reduce_partials(hipStream_t s, const float* partial, int chunks, int N, long stride, float scale, float* out);
 
 // Second stage of the two-stage (ordered, atomic-free) reductions.  A first-stage kernel asks for

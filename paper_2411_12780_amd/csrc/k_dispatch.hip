@@ -1,6 +1,6 @@
 // Kernel selection: the MFMA kernels take the bf16 shapes they are built for,
 // everything else goes to the run-time-typed kernels.  Also holds the optional
-// per-launch timing of the contraction kernels used by the benchmark.
+// per-launch timing of a block's contraction kernels used by the benchmark.
 #include <vector>
 
 #include "common.h"
@@ -8,50 +8,52 @@
 namespace ppll {
 
 namespace {
-struct TimedLaunch { hipEvent_t a, b; double units; int kind; };   // kind 0: GEMM (units = flops), 1: convolution (units = bytes)
-bool g_profile = false;
-std::vector<TimedLaunch> g_timed;
-std::vector<hipEvent_t> g_pool;
+thread_local LaunchTimes* t_times = nullptr;
 
-hipEvent_t pooled_event() {
-  if (!g_pool.empty()) { hipEvent_t e = g_pool.back(); g_pool.pop_back(); return e; }
+hipEvent_t pooled_event(LaunchTimes& t) {
+  if (!t.pool.empty()) { hipEvent_t e = t.pool.back(); t.pool.pop_back(); return e; }
   hipEvent_t e = nullptr;
   if (hipEventCreate(&e) != hipSuccess) return nullptr;
   return e;
 }
 }  // namespace
 
-void profile_enable(bool on) { g_profile = on; }
-bool profile_enabled() { return g_profile; }
+void profile_bind(LaunchTimes* t) { t_times = t; }
+bool profile_enabled() { return t_times != nullptr; }
 
-// Sums the elapsed time of every bracketed launch since the last read, per kind (0: GEMM, 1: convolution).
-int profile_read(double ms[2], double units[2], long long launches[2]) {
-  for (int k = 0; k < 2; ++k) { ms[k] = 0.0; units[k] = 0.0; launches[k] = 0; }
-  for (TimedLaunch& l : g_timed) {
+// Adds the elapsed time of every bracketed launch since the last drain, per kind (0: GEMM, 1: convolution).
+int profile_drain(LaunchTimes& t) {
+  for (TimedLaunch& l : t.timed) {
     PPLL_HIP(hipEventSynchronize(l.b));
     float dt = 0.f;
     PPLL_HIP(hipEventElapsedTime(&dt, l.a, l.b));
-    ms[l.kind] += dt; units[l.kind] += l.units; ++launches[l.kind];
-    g_pool.push_back(l.a); g_pool.push_back(l.b);
+    t.ms[l.kind] += dt; t.units[l.kind] += l.units; ++t.launches[l.kind];
+    t.pool.push_back(l.a); t.pool.push_back(l.b);
   }
-  g_timed.clear();
+  t.timed.clear();
   return PPLL_OK;
 }
 
-// Brackets one kernel launch with a pair of events when profiling is on.
+void profile_destroy(LaunchTimes& t) {
+  for (TimedLaunch& l : t.timed) { (void)hipEventDestroy(l.a); (void)hipEventDestroy(l.b); }
+  for (hipEvent_t e : t.pool) (void)hipEventDestroy(e);
+  t.timed.clear(); t.pool.clear();
+}
+
+// Brackets one kernel launch with a pair of events when the calling thread has a record bound.
 int profile_begin(hipStream_t s, double units, void** token, int kind) {
   *token = nullptr;
-  if (!g_profile) return PPLL_OK;
-  TimedLaunch tl{pooled_event(), pooled_event(), units, kind};
+  if (!t_times) return PPLL_OK;
+  TimedLaunch tl{pooled_event(*t_times), pooled_event(*t_times), units, kind};
   if (!tl.a || !tl.b) { set_error("hipEventCreate failed"); return PPLL_ERR_HIP; }
   PPLL_HIP(hipEventRecord(tl.a, s));
-  g_timed.push_back(tl);
-  *token = (void*)(uintptr_t)g_timed.size();
+  t_times->timed.push_back(tl);
+  *token = (void*)(uintptr_t)t_times->timed.size();
   return PPLL_OK;
 }
 int profile_end(hipStream_t s, void* token) {
-  if (!token) return PPLL_OK;
-  PPLL_HIP(hipEventRecord(g_timed[(size_t)(uintptr_t)token - 1].b, s));
+  if (!token || !t_times) return PPLL_OK;
+  PPLL_HIP(hipEventRecord(t_times->timed[(size_t)(uintptr_t)token - 1].b, s));
   return PPLL_OK;
 }
 

@@ -51,9 +51,6 @@ struct MfmaArgs {
   int epilogue;
   uint16_t* C2;
   const uint16_t* aux; long ldaux;
-#ifdef PPLL_GEMM_TRACE
-  long long* trace;                 // [workgroup][8] wall-clock stamps (development builds only)
-#endif
   uint32_t a_bytes, b_bytes, c_bytes, r_bytes, aux_bytes, partial_bytes;   // extents of the buffers above
   int xcd_map;                      // 1: ids 8 apart share a tile row (many tile rows), 2: ids 8 apart share a
                                     // split (split-K), 0: row-major ids
@@ -221,14 +218,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-#ifdef PPLL_GEMM_TRACE
-  long long* tr = p.trace + ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8;
-  if (tid == 0) tr[0] = wall_clock64();
-#define TRACE(i) if (tid == 0) tr[i] = wall_clock64();
-#else
-#define TRACE(i)
-#endif
-
   const __amdgpu_buffer_rsrc_t rsA = make_rsrc(p.A, p.a_bytes), rsB = make_rsrc(p.B, p.b_bytes);
   OperandLoader<AT, TM> ldA;
   OperandLoader<BT, BN> ldB;
@@ -317,7 +306,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
     if (do_colsum) colsum_add(r[0].b[q]);
   }
   __syncthreads();
-  TRACE(1)
   gload(2, r[0]);
   if (nk > 0) {
     load_frags(0, 0, fa[0], fb[0]);
@@ -334,7 +322,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
     }
   }
 
-  TRACE(2)
 
   // Epilogue through LDS: the accumulators (lane = one C row, 4 consecutive columns per group)
   // are laid down as an fp32 tile, then every thread takes 8 consecutive columns of a row, so
@@ -397,7 +384,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
             make_float4(acc[jn][im][4 * q], acc[jn][im][4 * q + 1], acc[jn][im][4 * q + 2], acc[jn][im][4 * q + 3]);
       }
   __syncthreads();
-  TRACE(3)
   const __amdgpu_buffer_rsrc_t rsC = p.partial ? make_rsrc(p.partial, p.partial_bytes) : make_rsrc(p.C, p.c_bytes);
   const __amdgpu_buffer_rsrc_t rsC2 = make_rsrc(p.C2 ? (const void*)p.C2 : p.C, p.C2 ? p.c_bytes : 0u);
   const bool out_f32 = p.partial != nullptr || p.c_f32;
@@ -453,7 +439,6 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
       }
     }
   }
-  TRACE(4)
 }
 
 template <bool AT, bool BT, int TM>
@@ -474,9 +459,6 @@ struct GroupedProblem {
 constexpr int GROUP_MAX = 24;
 struct GroupedArgs {
   int n, total_tiles, per_xcd;
-#ifdef PPLL_GEMM_TRACE
-  long long* trace;
-#endif
   GroupedProblem prob[GROUP_MAX];
 };
 __global__ __launch_bounds__(256, 2) void gemm_mfma_grouped_kernel(GroupedArgs a) {
@@ -494,9 +476,6 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_grouped_kernel(GroupedArgs a
   p.colsum = a.prob[j].colsum;
   p.a_bytes = a.prob[j].a_bytes; p.b_bytes = a.prob[j].b_bytes; p.c_bytes = a.prob[j].c_bytes;
   p.splits = 1; p.xcd_map = 0;
-#ifdef PPLL_GEMM_TRACE
-  p.trace = a.trace;
-#endif
   gemm_mfma_tile<true, true, 128>(p, t - a.prob[j].first_tile, 0);
 }
 
@@ -523,9 +502,6 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial
   *reinterpret_cast<float4*>(C + i) = acc;
 }
 
-#ifdef PPLL_GEMM_TRACE
-long long* g_gemm_trace = nullptr;
-#endif
 bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
 // bytes from the first to one past the last element of an operand (transposed: [K][rows], else [rows][K])
 long operand_bytes(bool transposed, int rows, int K, long ld) {
@@ -613,9 +589,6 @@ int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n) {
     }
     a.total_tiles = tiles;
     a.per_xcd = (tiles + 7) / 8;
-#ifdef PPLL_GEMM_TRACE
-    a.trace = g_gemm_trace;
-#endif
     void* prof = nullptr;
     PPLL_TRY(profile_begin(s, flops, &prof));
     hipLaunchKernelGGL(gemm_mfma_grouped_kernel, dim3(8 * a.per_xcd), dim3(256), lds_bytes(true, true, 128), s, a);
@@ -640,9 +613,6 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   p.tiles_m = (g.M + tm_rows - 1) / tm_rows;
   p.bias = g.bias; p.residual = (const uint16_t*)g.residual; p.ldr = g.ldr;
   p.epilogue = g.epilogue; p.C2 = (uint16_t*)g.C2; p.aux = (const uint16_t*)g.aux; p.ldaux = g.ldaux;
-#ifdef PPLL_GEMM_TRACE
-  p.trace = g_gemm_trace;
-#endif
   const int nkt = (g.K + BK - 1) / BK;
   int splits = 1;
   const bool plain = !g.bias && !g.residual && g.epilogue == EPI_NONE && g.c_dt == F32 && g.ldc == g.N;

@@ -612,44 +612,46 @@ def test_vit_batch_of_one():
 
 
 def test_launch_brackets_count_the_contraction_kernels_and_their_work():
-    """The measurement aid behind bench.py's roofline: with brackets on, a ViT step reports its matrix-core GEMM
-    launches with 2 M N K flops each, a ResNet step its convolution launches with their algorithmic bytes; the
-    two kinds are read separately and the step's results do not change."""
-    import torch
+    """The measurement aid behind bench.py's roofline: with brackets on for a block, its ViT step reports its
+    matrix-core GEMM launches with 2 M N K flops each, a ResNet block's step its convolution launches with their
+    algorithmic bytes; the setting belongs to the block (a second block stepped in between reports nothing) and
+    the step's results do not change."""
     from paper_2411_12780_amd import binding as P
     from gpu_harness import GpuBlock
     vit = synth.workload("vit_stage_act_bf16", batch=8, depth=2, aux_depth=0)
     res = synth.workload("resnet_stage_bf16", batch=4, n_basic_blocks=1)
     losses = {}
     for on in (False, True):
-        P.ppll_profile_enable(on)
-        P.ppll_profile_read(); P.ppll_profile_read_conv()
         for name, wl in (("vit", vit), ("resnet", res)):
-            gb = GpuBlock(wl, synth.make_params(O.param_spec(oracle_cfg(wl)), seed=3, jitter=True))
+            flat = synth.make_params(O.param_spec(oracle_cfg(wl)), seed=3, jitter=True)
+            gb, other = GpuBlock(wl, flat), GpuBlock(wl, flat)
+            P.ppll_block_profile_enable(gb.h, on)
             x, y = synth.make_batch(wl, seed=3)
             _, loss = gb.step(x, y, float(wl["lr"]))
+            other.step(x, y, float(wl["lr"]))            # not timed: the switch is per block
             losses[(name, on)] = loss
-            gb.close()
-        gemm_ms, gemm_flops, gemm_n = P.ppll_profile_read()
-        conv_ms, conv_bytes, conv_n = P.ppll_profile_read_conv()
-        if not on:
-            assert gemm_n == 0 and conv_n == 0
-            continue
-        # two encoder layers: forward, input gradient and weight gradient of QKV, proj, fc1, fc2 each (the first
-        # layer's QKV input gradient too: LayerNorm 1 needs it for its scale and shift), however they are grouped
-        M, D, F = 8 * vit["tokens"], vit["dim"], vit["mlp_dim"]
-        fwd = 2.0 * M * (D * 3 * D + D * D + 2 * D * F)
-        assert gemm_n >= 16 and gemm_ms > 0
-        assert abs(gemm_flops - 2 * 3 * fwd) <= 1e-6 * gemm_flops
-        # one basic block + auxiliary convolution: 3 forward launches, conv2's and the auxiliary input gradient
-        px, C, A = 4 * 16 * 16, 32, 64
-        f_block = 2.0 * (2 * px * C + 9 * C * C)
-        f_aux = 2.0 * (px * C + (px // 4) * A + 9 * C * A)
-        assert conv_n == 5 and conv_ms > 0
-        assert abs(conv_bytes - (3 * f_block + 2 * f_aux)) <= 1e-6 * conv_bytes
-        # a second read finds nothing new
-        assert P.ppll_profile_read()[2] == 0 and P.ppll_profile_read_conv()[2] == 0
-    P.ppll_profile_enable(False)
+            gemm_ms, gemm_flops, gemm_n = P.ppll_block_profile_read(gb.h)
+            conv_ms, conv_bytes, conv_n = P.ppll_block_profile_read_conv(gb.h)
+            assert P.ppll_block_profile_read(other.h)[2] == 0 and P.ppll_block_profile_read_conv(other.h)[2] == 0
+            if not on:
+                assert gemm_n == 0 and conv_n == 0
+            elif name == "vit":
+                # two encoder layers: forward, input gradient and weight gradient of QKV, proj, fc1, fc2 each (the first
+                # layer's QKV input gradient too: LayerNorm 1 needs it for its scale and shift), however they are grouped
+                M, D, F = 8 * vit["tokens"], vit["dim"], vit["mlp_dim"]
+                fwd = 2.0 * M * (D * 3 * D + D * D + 2 * D * F)
+                assert gemm_n >= 16 and gemm_ms > 0 and conv_n == 0
+                assert abs(gemm_flops - 2 * 3 * fwd) <= 1e-6 * gemm_flops
+            else:
+                # one basic block + auxiliary convolution: 3 forward launches, conv2's and the auxiliary input gradient
+                px, C, A = 4 * 16 * 16, 32, 64
+                f_block = 2.0 * (2 * px * C + 9 * C * C)
+                f_aux = 2.0 * (px * C + (px // 4) * A + 9 * C * A)
+                assert conv_n == 5 and conv_ms > 0 and gemm_n == 0
+                assert abs(conv_bytes - (3 * f_block + 2 * f_aux)) <= 1e-6 * conv_bytes
+            # a second read finds nothing new
+            assert P.ppll_block_profile_read(gb.h)[2] == 0 and P.ppll_block_profile_read_conv(gb.h)[2] == 0
+            gb.close(); other.close()
     assert losses[("vit", False)] == losses[("vit", True)] and losses[("resnet", False)] == losses[("resnet", True)]
 
 
