@@ -23,15 +23,21 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
-def step_flops(wl: dict) -> float:
-    """Dense-definition flop count of one step (multiply-add = 2): forward + 2x backward for
-    every contraction, minus the input gradient that gradient isolation never needs."""
+def step_flops(wl: dict, dense: bool = False) -> float:
+    """Flop count of one step (multiply-add = 2): forward + 2x backward for every contraction, minus the input
+    gradient that gradient isolation never needs.  dense=True: every encoder layer computed for all tokens (the
+    plain definition).  dense=False: what the library executes: of the last auxiliary layer only the class-token
+    row is computed behind the key / value projection (the head reads nothing else of it; the result is the same),
+    so that layer counts K, V for all tokens and query, attention, projection and MLP for one row per image."""
     B = wl["batch"]
     if wl["arch"] == 0:
         T, D, F, H = wl["tokens"], wl["dim"], wl["mlp_dim"], wl["heads"]
         M = B * T
         layer_fwd = 2.0 * M * (D * 3 * D + D * D + 2 * D * F) + 4.0 * B * H * T * T * (D // H)
         total = 3.0 * layer_fwd * (wl["depth"] + wl["aux_depth"])
+        if not dense and wl["aux_depth"] >= 1:
+            cls_fwd = 2.0 * M * D * 2 * D + 2.0 * B * (D * D + D * D + 2 * D * F) + 4.0 * B * H * T * (D // H)
+            total += 3.0 * (cls_fwd - layer_fwd)
         total += 3.0 * 2.0 * B * D * wl["num_classes"]
         if wl["input_kind"] == 0:
             total += 2.0 * 2.0 * B * (T - 1) * wl["patch"] ** 2 * wl["img_c"] * D
@@ -317,6 +323,8 @@ def main() -> int:
                                                 "channels", "height", "width", "n_basic_blocks") if k in wl},
                    "optimizer": "adamw" if wl["optimizer"] == synth.ADAMW else "sgd"},
         "step_gflop": flops / 1e9,
+        "step_gflop_note": "executed work: of the last auxiliary layer only the class-token row is computed behind K, V",
+        "step_gflop_dense_definition": step_flops(wl, dense=True) / 1e9,
         "step_tflops": flops / (elapsed / args.steps) / 1e12,
         "mfma_peak_frac_step": flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
         "ms_per_step_events": {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]},

@@ -24,6 +24,13 @@ struct EncoderActs {     // saved by the forward for the backward (h: gelu' at t
   void *u1, *qkv, *att, *x1, *u2, *h, *gl, *x2;
   float *mean1, *rstd1, *mean2, *rstd2, *lse;
 };
+// Compact buffers of the last auxiliary encoder layer, of which only the class-token row is computed behind the
+// key / value projection ([B, .] instead of [B*T, .]; see Block::encoder_fwd_cls).
+struct ClsActs {
+  void *q, *att, *x1, *u2, *h, *gl, *x2;          // forward (h: gelu' at the MLP pre-activation, gl: its gelu)
+  void *d_h, *d_u2, *d_x1, *d_att, *d_q;          // backward
+  float *mean2, *rstd2, *prob;                     // prob [B, H, T]
+};
 struct BasicBlockParams { size_t conv1_w, bn1_g, bn1_b, conv2_w, bn2_g, bn2_b; };
 // conv1 maps [Hin, Win, Ci] to [Ho, Wo, Co] with `stride`; everything after it in the block is [Ho, Wo, Co]
 struct BasicBlockDims { int Ci, Co, stride, Hin, Win, Ho, Wo; };
@@ -86,6 +93,10 @@ struct Block {
   std::vector<EncoderActs> enc_a;
   void *patches = nullptr, *x0 = nullptr, *embed_tmp = nullptr;
   void *z = nullptr, *dz = nullptr, *dcls = nullptr;
+  // The last auxiliary layer feeds the head through its class-token row alone, so behind its key / value projection
+  // only that row is computed (exact: no other row of that layer reaches the loss).  Off without auxiliary layers.
+  bool prune_cls = false;
+  ClsActs cls_a{};
   float *head_mean = nullptr, *head_rstd = nullptr, *logits = nullptr, *dlogits = nullptr;
   // Backward buffers.  Every layer keeps the gradients its four weight-gradient products read
   // (layer-output gradient, mid-layer gradient, d_h, d_qkv) until the end of the backward pass,
@@ -170,6 +181,12 @@ struct Block {
   int forward_eval_with(const EvalBuffers& e, const void* x_in, void* x_out, float* logits_out, hipStream_t s);
   size_t plan_eval_scratch(char* base, EvalBuffers* e) const;
   int encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void* g_out, bool need_dx, hipStream_t s);
+  int encoder_fwd_cls(int l, const void* x, hipStream_t s);
+  int encoder_bwd_cls(int l, const void* x, const void* d_x2, void* g_out, hipStream_t s);
+  // dW[in, out] (row stride ldw) = X^T dY over K rows and db = column sums of dY; recorded for the grouped launch when
+  // the matrix-core kernel can take it, else run at once.  x_ld / dy_ld: row strides of X [K, in] and dY [K, out].
+  int wgrad_product(const void* xin, long x_ld, int in_dim, const void* dy, long dy_ld, int out_dim, int K, float* dW,
+                    long ldw, float* db, hipStream_t s);
   int update(float lr, hipStream_t s);
 };
 

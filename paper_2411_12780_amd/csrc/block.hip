@@ -207,6 +207,15 @@ size_t Block::plan(char* base) {
       enc_a.push_back(a);
     }
     z = bump.take((size_t)B * D * esz); dz = bump.take((size_t)B * D * esz); dcls = bump.take((size_t)B * D * esz);
+    prune_cls = cfg.aux_depth >= 1 && attention_cls_lds_bytes(T, D / H) <= 160 * 1024;
+    if (prune_cls) {
+      ClsActs& c = cls_a;
+      const size_t bd = (size_t)B * D * esz, bf = (size_t)B * F * esz;
+      c.q = bump.take(bd); c.att = bump.take(bd); c.x1 = bump.take(bd); c.u2 = bump.take(bd); c.x2 = bump.take(bd);
+      c.h = bump.take(bf); c.gl = bump.take(bf); c.d_h = bump.take(bf);
+      c.d_u2 = bump.take(bd); c.d_x1 = bump.take(bd); c.d_att = bump.take(bd); c.d_q = bump.take(bd);
+      c.mean2 = bump.floats(B); c.rstd2 = bump.floats(B); c.prob = bump.floats((size_t)B * H * T);
+    }
     head_mean = bump.floats(B); head_rstd = bump.floats(B);
     d_u = bump.take(M * D * esz);
     g_res.clear(); g_mid.clear(); d_h.clear(); d_qkv.clear();
@@ -295,6 +304,8 @@ size_t Block::plan(char* base) {
       arena_floats += (size_t)embed_bwd_partial_floats(B, T, D) + (size_t)colsum_partial_floats((int)M, D) + 128;
     if (!(dt == BF16))   // the generic GEMM does not fold bias gradients: one column sum per Linear layer
       arena_floats += (size_t)(cfg.depth + cfg.aux_depth) * 4 * ((size_t)colsum_partial_floats((int)M, widest) + 64);
+    if (prune_cls)   // the class-token layer: one more LayerNorm backward over B rows and column sums of its split products
+      arena_floats += (size_t)layernorm_bwd_partial_floats(B, D) + 6 * ((size_t)colsum_partial_floats((int)M, widest) + 64);
   }
   if (cfg.arch == PPLL_RESNET) {   // the weight-gradient partials of every convolution
     const int Ch = cfg.channels, A = cfg.aux_channels, Hh = cfg.height, W = cfg.width;
@@ -364,16 +375,7 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
   void* d_h = this->d_h[l];
   void* d_qkv = this->d_qkv[l];
   auto wgrad = [&](const void* xin, int in_dim, const void* dy, int out_dim, size_t w_off, size_t b_off) -> int {
-    GemmArgs g = gemm_args();
-    g.A = xin; g.a_dt = dt; g.a_sm = 1; g.a_sk = in_dim;
-    g.B = dy; g.b_dt = dt; g.b_sk = out_dim; g.b_sn = 1;
-    g.C = grads + w_off; g.c_dt = F32; g.ldc = out_dim; g.M = in_dim; g.N = out_dim; g.K = M;
-    g.colsum = grads + b_off;
-    g.splitk_ws = splitk; g.splitk_floats = splitk_floats;   // used when the product ends up running on its own
-    if (gemm_mfma_groupable(g)) { wgrad_jobs.push_back(g); return (int)PPLL_OK; }
-    g.colsum = nullptr;
-    PPLL_TRY(launch_gemm(s, g));
-    return launch_colsum(s, dy, dt, M, out_dim, rq, grads + b_off);
+    return wgrad_product(xin, in_dim, in_dim, dy, out_dim, out_dim, M, grads + w_off, out_dim, grads + b_off, s);
   };
   GemmArgs g = dgrad(g_in, D, p.fc2_w, F, d_h);
   g.epilogue = EPI_DGELU; g.aux = a.h; g.aux_dt = dt; g.ldaux = F;
@@ -390,6 +392,105 @@ int Block::encoder_bwd(int l, const void* x, const void* g_in, void* g_tmp, void
   PPLL_TRY(wgrad(a.u1, D, d_qkv, 3 * D, p.qkv_w, p.qkv_b));
   return launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, g_tmp,
                               need_dx ? g_out : nullptr, rq, grads + p.ln1_g, grads + p.ln1_b);
+}
+
+int Block::wgrad_product(const void* xin, long x_ld, int in_dim, const void* dy, long dy_ld, int out_dim, int K, float* dW,
+                         long ldw, float* db, hipStream_t s) {
+  GemmArgs g = gemm_args();
+  g.A = xin; g.a_dt = dt; g.a_sm = 1; g.a_sk = x_ld;
+  g.B = dy; g.b_dt = dt; g.b_sk = dy_ld; g.b_sn = 1;
+  g.C = dW; g.c_dt = F32; g.ldc = ldw; g.M = in_dim; g.N = out_dim; g.K = K;
+  g.colsum = db;
+  g.splitk_ws = splitk; g.splitk_floats = splitk_floats;
+  if (gemm_mfma_groupable(g)) { wgrad_jobs.push_back(g); return PPLL_OK; }
+  g.colsum = nullptr;
+  PPLL_TRY(launch_gemm(s, g));
+  if (dy_ld != out_dim) { set_error("bias gradient of a strided product needs the matrix-core kernel"); return PPLL_ERR_CONFIG; }
+  return launch_colsum(s, dy, dt, K, out_dim, rq, db);
+}
+
+// Last auxiliary layer, class-token row only.  The keys and values need every token (LayerNorm 1 and the K, V columns of
+// the QKV projection run over all B*T rows); the query, the attention output, the output projection, LayerNorm 2 and
+// the MLP are needed for the B class-token rows alone, because only those rows of the layer output reach the head.
+// a.qkv holds [B*T, 2D] keys and values here, cls_a the compact [B, .] tensors; the layer output is cls_a.x2 [B, D].
+int Block::encoder_fwd_cls(int l, const void* x, hipStream_t s) {
+  const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, B = cfg.batch, M = B * T;
+  const EncoderParams& p = enc_p[l];
+  const EncoderActs& a = enc_a[l];
+  const ClsActs& c = cls_a;
+  const size_t wsz = dtype_size(wdt());
+  PPLL_TRY(launch_layernorm_fwd(s, x, dt, D, M, D, params + p.ln1_g, params + p.ln1_b, cfg.ln_eps, a.u1, a.mean1, a.rstd1));
+  GemmArgs g = gemm_args();   // keys and values of all tokens: columns D..3D of the QKV weight
+  g.A = a.u1; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+  g.B = (const char*)wptr(p.qkv_w) + (size_t)D * wsz; g.b_dt = wdt(); g.b_sk = 3 * D; g.b_sn = 1;
+  g.C = a.qkv; g.c_dt = dt; g.ldc = 2 * D; g.M = M; g.N = 2 * D; g.K = D; g.bias = params + p.qkv_b + D;
+  PPLL_TRY(launch_gemm(s, g));
+  g = gemm_args();            // query of the class token (row b*T of u1)
+  g.A = a.u1; g.a_dt = dt; g.a_sm = (long)T * D; g.a_sk = 1;
+  g.B = wptr(p.qkv_w); g.b_dt = wdt(); g.b_sk = 3 * D; g.b_sn = 1;
+  g.C = c.q; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = D; g.bias = params + p.qkv_b;
+  PPLL_TRY(launch_gemm(s, g));
+  PPLL_TRY(launch_attention_cls_fwd(s, c.q, a.qkv, dt, B, T, H, D / H, c.att, c.prob));
+  g = gemm_args();
+  g.A = c.att; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+  g.B = wptr(p.proj_w); g.b_dt = wdt(); g.b_sk = D; g.b_sn = 1;
+  g.C = c.x1; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = D; g.bias = params + p.proj_b;
+  g.residual = x; g.r_dt = dt; g.ldr = (long)T * D;
+  PPLL_TRY(launch_gemm(s, g));
+  PPLL_TRY(launch_layernorm_fwd(s, c.x1, dt, D, B, D, params + p.ln2_g, params + p.ln2_b, cfg.ln_eps, c.u2, c.mean2, c.rstd2));
+  g = gemm_args();
+  g.A = c.u2; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
+  g.B = wptr(p.fc1_w); g.b_dt = wdt(); g.b_sk = F; g.b_sn = 1;
+  g.C = c.h; g.c_dt = dt; g.ldc = F; g.M = B; g.N = F; g.K = D; g.bias = params + p.fc1_b;
+  g.epilogue = EPI_GELU; g.C2 = c.gl;
+  PPLL_TRY(launch_gemm(s, g));
+  g = gemm_args();
+  g.A = c.gl; g.a_dt = dt; g.a_sm = F; g.a_sk = 1;
+  g.B = wptr(p.fc2_w); g.b_dt = wdt(); g.b_sk = D; g.b_sn = 1;
+  g.C = c.x2; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = F; g.bias = params + p.fc2_b;
+  g.residual = c.x1; g.r_dt = dt; g.ldr = D;
+  return launch_gemm(s, g);
+}
+
+// d_x2 [B, D]: gradient with respect to the class-token rows of the layer output; g_out [B*T, D] receives the gradient
+// with respect to the layer input (all rows: the keys and values depend on every token).
+int Block::encoder_bwd_cls(int l, const void* x, const void* d_x2, void* g_out, hipStream_t s) {
+  const int D = cfg.dim, F = cfg.mlp_dim, T = cfg.tokens, H = cfg.heads, B = cfg.batch, M = B * T;
+  const EncoderParams& p = enc_p[l];
+  const EncoderActs& a = enc_a[l];
+  const ClsActs& c = cls_a;
+  const size_t wsz = dtype_size(wdt());
+  void* d_kv = d_qkv[l];      // [B*T, 2D] here
+  auto dgrad = [&](const void* dy, int rows, int out_dim, const void* w, long w_ld, int in_dim, void* dxo) {
+    GemmArgs g = gemm_args();   // dY W^T with W rows w_ld apart:  B(k = out index, n = in index) = w[n*w_ld + k]
+    g.A = dy; g.a_dt = dt; g.a_sm = out_dim; g.a_sk = 1;
+    g.B = w; g.b_dt = wdt(); g.b_sk = 1; g.b_sn = w_ld;
+    g.C = dxo; g.c_dt = dt; g.ldc = in_dim; g.M = rows; g.N = in_dim; g.K = out_dim;
+    return g;
+  };
+  GemmArgs g = dgrad(d_x2, B, D, wptr(p.fc2_w), D, F, c.d_h);
+  g.epilogue = EPI_DGELU; g.aux = c.h; g.aux_dt = dt; g.ldaux = F;
+  PPLL_TRY(launch_gemm(s, g));
+  PPLL_TRY(wgrad_product(c.gl, F, F, d_x2, D, D, B, grads + p.fc2_w, D, grads + p.fc2_b, s));
+  PPLL_TRY(launch_gemm(s, dgrad(c.d_h, B, F, wptr(p.fc1_w), F, D, c.d_u2)));
+  PPLL_TRY(wgrad_product(c.u2, D, D, c.d_h, F, F, B, grads + p.fc1_w, F, grads + p.fc1_b, s));
+  PPLL_TRY(launch_layernorm_bwd(s, c.d_u2, c.x1, dt, D, B, D, params + p.ln2_g, c.mean2, c.rstd2, d_x2, c.d_x1, rq,
+                                grads + p.ln2_g, grads + p.ln2_b));
+  PPLL_TRY(launch_gemm(s, dgrad(c.d_x1, B, D, wptr(p.proj_w), D, D, c.d_att)));
+  PPLL_TRY(wgrad_product(c.att, D, D, c.d_x1, D, D, B, grads + p.proj_w, D, grads + p.proj_b, s));
+  PPLL_TRY(launch_attention_cls_bwd(s, c.q, a.qkv, c.prob, c.d_att, dt, B, T, H, D / H, c.d_q, d_kv));
+  // gradient at LayerNorm 1's output: keys and values of all rows, plus the query's share on the class-token rows
+  PPLL_TRY(launch_gemm(s, dgrad(d_kv, M, 2 * D, (const char*)wptr(p.qkv_w) + (size_t)D * wsz, 3 * D, D, d_u)));
+  g = dgrad(c.d_q, B, D, wptr(p.qkv_w), 3 * D, D, d_u);
+  g.ldc = (long)T * D;
+  g.residual = d_u; g.r_dt = dt; g.ldr = (long)T * D;     // added to what the product above left in those rows
+  PPLL_TRY(launch_gemm(s, g));
+  PPLL_TRY(wgrad_product(a.u1, D, D, d_kv, 2 * D, 2 * D, M, grads + p.qkv_w + D, 3 * D, grads + p.qkv_b + D, s));
+  PPLL_TRY(wgrad_product(a.u1, (long)T * D, D, c.d_q, D, D, B, grads + p.qkv_w, 3 * D, grads + p.qkv_b, s));
+  PPLL_TRY(launch_layernorm_bwd(s, d_u, x, dt, D, M, D, params + p.ln1_g, a.mean1, a.rstd1, nullptr, g_out, rq,
+                                grads + p.ln1_g, grads + p.ln1_b));
+  // the residual path around the attention block carries d_x1, which lives on the class-token rows only
+  return launch_add_rows(s, g_out, (long)T * D, c.d_x1, B, D, dt);
 }
 
 int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStream_t s,
@@ -420,19 +521,26 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
   PPLL_TRY(mark_phase(1, s));   // module forward done
   if (after_forward) PPLL_TRY(after_forward());
   // ---- auxiliary forward
+  long head_xs = (long)T * D;   // distance between the class-token rows the head reads
   for (int l = L; l < L + A; ++l) {
     layer_in[l] = x;
-    PPLL_TRY(encoder_fwd(l, enc_a[l], x, enc_a[l].x2, s));
-    x = enc_a[l].x2;
+    if (prune_cls && l == L + A - 1) {
+      PPLL_TRY(encoder_fwd_cls(l, x, s));
+      x = cls_a.x2;
+      head_xs = D;
+    } else {
+      PPLL_TRY(encoder_fwd(l, enc_a[l], x, enc_a[l].x2, s));
+      x = enc_a[l].x2;
+    }
   }
   GemmArgs g = gemm_args();
   if (vit_head_fused_ok(D, C)) {
     // ---- auxiliary head, local loss and the head's backward in one launch
-    PPLL_TRY(launch_vit_head(s, x, dt, (long)T * D, B, D, C, params + head_ln_g, params + head_ln_b, cfg.ln_eps,
+    PPLL_TRY(launch_vit_head(s, x, dt, head_xs, B, D, C, params + head_ln_g, params + head_ln_b, cfg.ln_eps,
                              params + head_w, params + head_b, labels, dcls, rq, grads + head_ln_g, grads + head_ln_b,
                              grads + head_w, grads + head_b, loss_dev, loss_copy, flag_dev));
   } else {
-    PPLL_TRY(launch_layernorm_fwd(s, x, dt, (long)T * D, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, z,
+    PPLL_TRY(launch_layernorm_fwd(s, x, dt, head_xs, B, D, params + head_ln_g, params + head_ln_b, cfg.ln_eps, z,
                                   head_mean, head_rstd));
     g = gemm_args();
     g.A = z; g.a_dt = dt; g.a_sm = D; g.a_sk = 1;
@@ -452,17 +560,19 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     g.B = params + head_w; g.b_dt = F32; g.b_sk = 1; g.b_sn = C;
     g.C = dz; g.c_dt = dt; g.ldc = D; g.M = B; g.N = D; g.K = C;
     PPLL_TRY(launch_gemm_generic(s, g));
-    PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, (long)T * D, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
+    PPLL_TRY(launch_layernorm_bwd(s, dz, x, dt, head_xs, B, D, params + head_ln_g, head_mean, head_rstd, nullptr, dcls,
                                   rq, grads + head_ln_g, grads + head_ln_b));
   }
   PPLL_TRY(mark_phase(2, s));   // auxiliary forward and loss done (the fused head kernel has also run its own backward)
   wgrad_jobs.clear();
-  PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, g_res[L + A]));
+  const bool pruned = prune_cls && A >= 1;
+  if (!pruned) PPLL_TRY(launch_scatter_cls(s, dcls, dt, B, T, D, g_res[L + A]));
   // ---- backward: auxiliary layers then module layers; the chain stops at x_in
   for (int l = L + A - 1; l >= 0; --l) {
     bool need_dx = l > 0 || image;
     const size_t first_job = wgrad_jobs.size();
-    PPLL_TRY(encoder_bwd(l, layer_in[l], g_res[l + 1], g_mid[l], g_res[l], need_dx, s));
+    if (pruned && l == L + A - 1) PPLL_TRY(encoder_bwd_cls(l, layer_in[l], dcls, g_res[l], s));
+    else PPLL_TRY(encoder_bwd(l, layer_in[l], g_res[l + 1], g_mid[l], g_res[l], need_dx, s));
     // A layer whose weight-gradient products fill the chip on their own (SIDE_MIN_TILES output tiles) has them run
     // beside the backward of the layers below, where they take up the slots that the chain's ragged last rounds of
     // workgroups leave empty (measured: 5 % of the step at width 768 and 197 tokens).  Smaller sets only slow the

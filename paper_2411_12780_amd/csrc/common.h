@@ -194,6 +194,16 @@ int launch_attention_fwd_generic(hipStream_t s, const void* qkv, int dt, int B, 
 int launch_attention_bwd_generic(hipStream_t s, const void* qkv, const void* out, const void* dout,
                                  const float* lse, int dt, int B, int T, int H, int dh, void* dqkv);
 
+// Attention of the class token's query alone against all keys and values of its (batch, head): q, out, dq, dout are
+// [B, H*dh], kv and dkv [B*T, 2*H*dh] (keys then values), prob [B, H, T] fp32 (saved by the forward).
+size_t attention_cls_lds_bytes(int T, int dh);
+int launch_attention_cls_fwd(hipStream_t s, const void* q, const void* kv, int dt, int B, int T, int H, int dh, void* out,
+                             float* prob);
+int launch_attention_cls_bwd(hipStream_t s, const void* q, const void* kv, const float* prob, const void* dout, int dt, int B,
+                             int T, int H, int dh, void* dq, void* dkv);
+// dst[r * dst_stride + d] += src[r * D + d] for r < rows
+int launch_add_rows(hipStream_t s, void* dst, long dst_stride, const void* src, int rows, int D, int dt);
+
 // ---------------------------------------------------------------- optimizers
 // `shadow` (nullable): bf16 copy of the updated parameters, same offsets
 int launch_sgd(hipStream_t s, float* p, const float* g, float* buf, uint16_t* shadow, size_t n, float lr,
