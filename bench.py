@@ -323,8 +323,8 @@ def main() -> int:
                                                 "channels", "height", "width", "n_basic_blocks") if k in wl},
                    "optimizer": "adamw" if wl["optimizer"] == synth.ADAMW else "sgd"},
         "step_gflop": flops / 1e9,
-        "step_gflop_note": "executed work: of the last auxiliary layer only the class-token row is computed behind K, V",
-        "step_gflop_dense_definition": step_flops(wl, dense=True) / 1e9,
+        **({"step_gflop_note": "executed work: of the last auxiliary layer only the class-token row is computed behind K, V",
+            "step_gflop_dense_definition": step_flops(wl, dense=True) / 1e9} if wl["arch"] == synth.VIT else {}),
         "step_tflops": flops / (elapsed / args.steps) / 1e12,
         "mfma_peak_frac_step": flops / (elapsed / args.steps) / 1e12 / PEAK_BF16_TFLOPS,
         "ms_per_step_events": {"median": per_step[len(per_step) // 2], "min": per_step[0], "max": per_step[-1]},
