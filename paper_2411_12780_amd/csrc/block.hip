@@ -233,6 +233,8 @@ size_t Block::plan(char* base) {
                                  ? gemm_mfma_partial_floats(cfg.patch * cfg.patch * cfg.img_c, D, B * (T - 1)) : 0};
       splitk_floats = 0;
       for (size_t c : cand) if (c > splitk_floats) splitk_floats = c;
+      // the grouped weight-gradient launch at the end of the backward pass passes divided tiles through the same scratch
+      if (gemm_mfma_balanced_floats() > splitk_floats) splitk_floats = gemm_mfma_balanced_floats();
       splitk = splitk_floats ? bump.floats(splitk_floats) : nullptr;
     }
     int widest = 3 * D > F ? 3 * D : F;
@@ -606,7 +608,8 @@ int Block::vit_step(const void* x_in, const int32_t* labels, void* x_out, hipStr
     }
   }
   // ---- every recorded weight-gradient product: one launch, or one by one with split-K for a small set
-  PPLL_TRY(launch_gemm_group(s, wgrad_jobs.data(), (int)wgrad_jobs.size(), side_busy));
+  // (this launch is the only user of the split-K scratch while it runs: the side stream's launches take none)
+  PPLL_TRY(launch_gemm_group(s, wgrad_jobs.data(), (int)wgrad_jobs.size(), side_busy, true));
   wgrad_jobs.clear();
   PPLL_TRY(side_wait(s));
   return PPLL_OK;

@@ -99,10 +99,13 @@ inline bool gemm_fuses_colsum(const GemmArgs& g) { return g.colsum && gemm_mfma_
 size_t gemm_mfma_partial_floats(int M, int N, int K);
 int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t partial_floats);
 bool gemm_mfma_groupable(const GemmArgs& g);
-int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n);   // every product must be groupable
+// every product must be groupable; ws (gemm_mfma_balanced_floats() floats or more), when given, lets the launch deal
+// the k-steps out evenly over the compute units (parts of divided tiles pass through it)
+int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n, float* ws = nullptr, size_t ws_floats = 0);
+size_t gemm_mfma_balanced_floats();
 // A set of independent products; one launch when all of them are groupable, else one by one.
 // `one_launch`: take the grouped kernel whenever all products allow it, however few tiles they have
-int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch = false);
+int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch = false, bool use_workspace = false);
 bool gemm_group_in_one_launch(const GemmArgs* gs, int n);   // every product fits the grouped kernel (n > 1)
 // Per-launch timing of the contraction kernels (a measurement aid, off unless a block asks for it).  A block that
 // times its launches binds its record to the calling thread for the duration of a step; the launch functions

@@ -67,7 +67,9 @@ bool gemm_group_in_one_launch(const GemmArgs* gs, int n) {
   return all;
 }
 
-int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch) {
+// use_workspace: the grouped launch may pass divided tiles through the products' split-K scratch (gs[0].splitk_ws);
+// only for a launch that is the sole user of that scratch while it runs.
+int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch, bool use_workspace) {
   if (n <= 0) return PPLL_OK;
   bool all = n > 1;
   long tiles = 0;
@@ -77,7 +79,8 @@ int launch_gemm_group(hipStream_t s, const GemmArgs* gs, int n, bool one_launch)
   }
   // one launch when the products together have enough output tiles for the chip; a small set runs
   // product by product, each with split-K (their reduction index is the long one)
-  if (all && (tiles >= 128 || one_launch)) return launch_gemm_mfma_grouped(s, gs, n);
+  if (all && (tiles >= 128 || one_launch))
+    return launch_gemm_mfma_grouped(s, gs, n, use_workspace ? gs[0].splitk_ws : nullptr, use_workspace ? gs[0].splitk_floats : 0);
   for (int j = 0; j < n; ++j) {
     const bool fused = gemm_fuses_colsum(gs[j]);
     if (gs[j].colsum && !fused) { set_error("launch_gemm_group: column sums need the MFMA kernel"); return PPLL_ERR_CONFIG; }

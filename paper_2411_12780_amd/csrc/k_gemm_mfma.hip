@@ -55,6 +55,10 @@ struct MfmaArgs {
   int xcd_map;                      // 1: ids 8 apart share a tile row (many tile rows), 2: ids 8 apart share a
                                     // split (split-K), 0: row-major ids
   int splits;
+  // k_range set: the k-range is given outright (balanced grouped launch), kt_count k-tiles from k-tile kt_first on.
+  // tile_partial, when set, receives the whole fp32 tile ([128][128], then 128 column sums) in place of C and colsum.
+  int k_range, kt_first, kt_count;
+  float* tile_partial;
 };
 
 // Exact-form GELU through the rational erf approximation of Abramowitz & Stegun 7.1.26
@@ -206,8 +210,8 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
   }
   const int m0 = tm * TM, n0 = tn * BN;
   const int nkt = (p.K + BK - 1) / BK;
-  const int kt0 = split * p.kt_per_split;
-  const int nk = min(nkt, kt0 + p.kt_per_split) - kt0;   // k-tiles of this workgroup (a trailing split may have none)
+  const int kt0 = p.k_range ? p.kt_first : split * p.kt_per_split;
+  const int nk = p.k_range ? p.kt_count : min(nkt, kt0 + p.kt_per_split) - kt0;   // k-tiles of this workgroup (a trailing split may have none)
   const int kbeg = kt0 * BK, kend = min(p.K, (kt0 + nk) * BK);
 
   f32x16 acc[2][IM];
@@ -369,7 +373,8 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
       float t = 0.f;
 #pragma unroll
       for (int g = 0; g < 16; ++g) t += cs[g * BN + tid];
-      if (n0 + tid < p.N) p.colsum[(size_t)split * p.N + n0 + tid] = t;
+      if (p.tile_partial) p.tile_partial[BM * BN + tid] = t;
+      else if (n0 + tid < p.N) p.colsum[(size_t)split * p.N + n0 + tid] = t;
     }
     __syncthreads();
   }
@@ -384,9 +389,10 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
             make_float4(acc[jn][im][4 * q], acc[jn][im][4 * q + 1], acc[jn][im][4 * q + 2], acc[jn][im][4 * q + 3]);
       }
   __syncthreads();
-  const __amdgpu_buffer_rsrc_t rsC = p.partial ? make_rsrc(p.partial, p.partial_bytes) : make_rsrc(p.C, p.c_bytes);
+  const __amdgpu_buffer_rsrc_t rsC = p.tile_partial ? make_rsrc(p.tile_partial, BM * BN * 4)
+                                     : p.partial    ? make_rsrc(p.partial, p.partial_bytes) : make_rsrc(p.C, p.c_bytes);
   const __amdgpu_buffer_rsrc_t rsC2 = make_rsrc(p.C2 ? (const void*)p.C2 : p.C, p.C2 ? p.c_bytes : 0u);
-  const bool out_f32 = p.partial != nullptr || p.c_f32;
+  const bool out_f32 = p.partial != nullptr || p.tile_partial != nullptr || p.c_f32;
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
     const int row = pass * 16 + prow, m = m0 + row;
@@ -414,9 +420,9 @@ __device__ __forceinline__ void gemm_mfma_tile(const MfmaArgs& p, const int bid_
     }
     if (out_f32) {
       const long e0 = p.partial ? ((long)split * p.M + m) * p.N : (long)m * p.ldc;
-      const int off = ok ? (int)(e0 * 4) + ncol4 : OOB;
+      const int off = p.tile_partial ? (row * BN + c8) * 4 : ok ? (int)(e0 * 4) + ncol4 : OOB;
       buf_store16(rsC, off, make_uint4(__float_as_uint(v[0]), __float_as_uint(v[1]), __float_as_uint(v[2]), __float_as_uint(v[3])));
-      buf_store16(rsC, ok ? off + 16 : OOB, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
+      buf_store16(rsC, (ok || p.tile_partial) ? off + 16 : OOB, make_uint4(__float_as_uint(v[4]), __float_as_uint(v[5]), __float_as_uint(v[6]), __float_as_uint(v[7])));
     } else {
       const int off = ok ? (int)(((long)m * p.ldc) * 2) + ncol2 : OOB;
       if (p.epilogue == EPI_GELU) {   // C2 = gelu(h), C = gelu'(h) from one evaluation of the normal CDF and density
@@ -461,12 +467,20 @@ struct GroupedArgs {
   int n, total_tiles, per_xcd;
   GroupedProblem prob[GROUP_MAX];
 };
-__global__ __launch_bounds__(256, 2) void gemm_mfma_grouped_kernel(GroupedArgs a) {
-  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int t = xcd * a.per_xcd + slot;
-  if (slot >= a.per_xcd || t >= a.total_tiles) return;
+// Tile t of the set -> its product and its place there (tm * tiles_n + tn).  Within a product the tiles are numbered
+// across its shorter side first: a stretch of consecutive tiles then needs all panels of the short side and only its
+// own panels of the long side, so where a stretch ends inside a product the next XCD fetches the few short-side panels
+// again and nothing else twice.
+template <class Args>
+__device__ __forceinline__ int grouped_locate(const Args& a, int t, int& bid) {
   int j = 0;
   while (j + 1 < a.n && t >= a.prob[j + 1].first_tile) ++j;
+  const int local = t - a.prob[j].first_tile, tiles_m = a.prob[j].tiles_m, tiles_n = a.prob[j].tiles_n;
+  bid = tiles_m >= tiles_n ? local : (local % tiles_m) * tiles_n + local / tiles_m;
+  return j;
+}
+template <class Args>
+__device__ __forceinline__ MfmaArgs grouped_problem(const Args& a, int j) {
   MfmaArgs p{};
   p.A = a.prob[j].A; p.lda = a.prob[j].lda; p.B = a.prob[j].B; p.ldb = a.prob[j].ldb;
   p.C = a.prob[j].C; p.c_f32 = 1; p.ldc = a.prob[j].ldc;
@@ -476,7 +490,89 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_grouped_kernel(GroupedArgs a
   p.colsum = a.prob[j].colsum;
   p.a_bytes = a.prob[j].a_bytes; p.b_bytes = a.prob[j].b_bytes; p.c_bytes = a.prob[j].c_bytes;
   p.splits = 1; p.xcd_map = 0;
-  gemm_mfma_tile<true, true, 128>(p, t - a.prob[j].first_tile, 0);
+  return p;
+}
+__global__ __launch_bounds__(256, 2) void gemm_mfma_grouped_kernel(GroupedArgs a) {
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int t = xcd * a.per_xcd + slot;
+  if (slot >= a.per_xcd || t >= a.total_tiles) return;
+  int bid;
+  const int j = grouped_locate(a, t, bid);
+  const MfmaArgs p = grouped_problem(a, j);
+  gemm_mfma_tile<true, true, 128>(p, bid, 0);
+}
+
+// The same set of products with the work dealt out more evenly.  One whole tile per workgroup leaves the chip unevenly
+// loaded when the tiles number a little more than the compute units (345 tiles of 130 k-steps on 256 units with two
+// workgroups each: 89 units work on two tiles from start to end while 167 finish their one tile early and idle, and
+// the launch lasts as long as the pairs).  Here the tiles beyond the last full round of one-per-unit are cut along k
+// into `cuts` parts, each a workgroup of its own: a unit then holds a whole tile and a part of one.  A part leaves its
+// fp32 sums in a slot of a workspace and a second kernel adds the parts of each divided tile in ascending k: results
+// do not depend on timing.
+constexpr int SLOT_FLOATS = BM * BN + BN;           // a tile's partial sums, then its 128 column sums
+struct BalancedArgs {
+  // products with a long reduction come first: their tiles [0, whole_tiles) run whole, [whole_tiles, long_tiles) are
+  // divided into `cuts` parts; the tiles of products with a short reduction, [long_tiles, total_tiles), run whole at the end
+  int n, total_tiles, long_tiles, whole_tiles, cuts;
+  float* ws;                                        // [divided tile][part] slots
+  GroupedProblem prob[GROUP_MAX];
+};
+__global__ __launch_bounds__(256, 2) void gemm_mfma_balanced_kernel(BalancedArgs a) {
+  // workgroup id -> item.  Ids are handed out in order, round-robin over the 8 XCDs: the whole tiles come first (they
+  // start first and take longest), then the parts, then the short tiles; within each kind XCD x takes a contiguous
+  // stretch, so neighbouring tiles (they share operand panels) share an L2.
+  const int xcd = blockIdx.x & 7;
+  int slot = blockIdx.x >> 3;
+  const int parts = (a.long_tiles - a.whole_tiles) * a.cuts;
+  const int per1 = (a.whole_tiles + 7) >> 3, per2 = (parts + 7) >> 3, per3 = (a.total_tiles - a.long_tiles + 7) >> 3;
+  int t, c = -1;
+  if (slot < per1) {
+    t = xcd * per1 + slot;
+    if (t >= a.whole_tiles) return;
+  } else if ((slot -= per1) < per2) {
+    const int i = xcd * per2 + slot;
+    if (i >= parts) return;
+    t = a.whole_tiles + i / a.cuts; c = i % a.cuts;
+  } else {
+    slot -= per2;
+    t = a.long_tiles + xcd * per3 + slot;
+    if (slot >= per3 || t >= a.total_tiles) return;
+  }
+  int bid;
+  const int j = grouped_locate(a, t, bid);
+  MfmaArgs p = grouped_problem(a, j);
+  if (c >= 0) {
+    const int nkt = p.kt_per_split, per = (nkt + a.cuts - 1) / a.cuts;
+    p.k_range = 1; p.kt_first = min(c * per, nkt); p.kt_count = min(per, nkt - p.kt_first);
+    p.tile_partial = a.ws + ((size_t)(t - a.whole_tiles) * a.cuts + c) * SLOT_FLOATS;
+  }
+  gemm_mfma_tile<true, true, 128>(p, bid, 0);
+}
+// One workgroup per divided tile: the sum of its parts, added in ascending k.
+__global__ __launch_bounds__(256) void gemm_mfma_balanced_sum_kernel(BalancedArgs a) {
+  const int d = blockIdx.x >> 2, quarter = blockIdx.x & 3, t = a.whole_tiles + d;   // 4 workgroups per tile, 32 rows each
+  int bid;
+  const int j = grouped_locate(a, t, bid);
+  const GroupedProblem& q = a.prob[j];
+  const int m0 = (bid / q.tiles_n) * BM, n0 = (bid % q.tiles_n) * BN;
+  const int tid = threadIdx.x, c4 = (tid & 31) * 4;
+  const float* slot0 = a.ws + (size_t)d * a.cuts * SLOT_FLOATS;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = quarter * 32 + r * 8 + (tid >> 5);
+    float4 acc = *reinterpret_cast<const float4*>(slot0 + row * BN + c4);
+    for (int c = 1; c < a.cuts; ++c) {
+      const float4 v = *reinterpret_cast<const float4*>(slot0 + (size_t)c * SLOT_FLOATS + row * BN + c4);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const int m = m0 + row, n = n0 + c4;
+    if (m < q.M && n < q.N) *reinterpret_cast<float4*>(q.C + (size_t)m * q.ldc + n) = acc;   // N is a multiple of 8
+  }
+  if (quarter == 0 && q.colsum && m0 == 0 && tid < BN) {
+    float acc = slot0[BM * BN + tid];
+    for (int c = 1; c < a.cuts; ++c) acc += slot0[(size_t)c * SLOT_FLOATS + BM * BN + tid];
+    if (n0 + tid < q.N) q.colsum[n0 + tid] = acc;
+  }
 }
 
 // C[i] = sum over splits of partial[s][i], fixed order; the trailing workgroups do the same for
@@ -562,12 +658,83 @@ bool gemm_mfma_groupable(const GemmArgs& g) {
   return at && bt && !g.bias && !g.residual && g.epilogue == EPI_NONE && g.c_dt == F32;
 }
 
-int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n) {
+// Workgroups of a balanced grouped launch on the current device: one per compute unit, a multiple of 8.
+static int balanced_workgroups() {
+  static int cached[64] = {0};
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (!cached[dev]) {
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    cached[dev] = (cus / 8) * 8;
+  }
+  return cached[dev];
+}
+constexpr int BALANCED_MAX_CUTS = 4;
+// room for the parts of the divided tiles: at most two per workgroup
+size_t gemm_mfma_balanced_floats() { return (size_t)balanced_workgroups() * 2 * SLOT_FLOATS; }
+
+static void fill_problem(GroupedProblem& q, const GemmArgs& g, int first_tile) {
+  q.A = (const uint16_t*)g.A; q.lda = (int)g.a_sk; q.B = (const uint16_t*)g.B; q.ldb = (int)g.b_sk;
+  q.C = (float*)g.C; q.ldc = (int)g.ldc; q.colsum = g.colsum;
+  q.M = g.M; q.N = g.N; q.K = g.K;
+  q.tiles_m = (g.M + BM - 1) / BM; q.tiles_n = (g.N + BN - 1) / BN;
+  q.first_tile = first_tile;
+  q.a_bytes = (uint32_t)operand_bytes(true, g.M, g.K, g.a_sk);
+  q.b_bytes = (uint32_t)operand_bytes(true, g.N, g.K, g.b_sk);
+  q.c_bytes = (uint32_t)(((long)(g.M - 1) * g.ldc + g.N) * 4);
+}
+
+int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n, float* ws, size_t ws_floats) {
   static bool lds_opted_in = false;
   if (!lds_opted_in) {
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, true, 128)));
+    PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_balanced_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, true, 128)));
     lds_opted_in = true;
   }
+  // Balanced launch: the whole set in one launch, a workspace for the divided tiles, tiles that leave a last round
+  // partly filled, and a reduction long enough to cut
+  const int wgs = balanced_workgroups();
+  if (ws && wgs >= 8 && n <= GROUP_MAX && ws_floats >= (size_t)wgs * 2 * SLOT_FLOATS) {
+    BalancedArgs a{};
+    a.n = n; a.ws = ws;
+    constexpr int LONG_NKT = 32;                    // k-steps from which a reduction counts as long
+    int tiles = 0, min_nkt = 1 << 30, filled = 0;
+    double flops = 0.0;
+    for (int pass = 0; pass < 2; ++pass) {          // long reductions first, then the short ones
+      for (int j = 0; j < n; ++j) {
+        const int nkt = (gs[j].K + BK - 1) / BK;
+        if ((nkt >= LONG_NKT) != (pass == 0)) continue;
+        fill_problem(a.prob[filled], gs[j], tiles);
+        tiles += a.prob[filled].tiles_m * a.prob[filled].tiles_n;
+        ++filled;
+        if (pass == 0) min_nkt = std::min(min_nkt, nkt);
+        flops += 2.0 * gs[j].M * gs[j].N * gs[j].K;
+      }
+      if (pass == 0) a.long_tiles = tiles;
+    }
+    const int rest = a.long_tiles % wgs;
+    // parts per left-over tile: 2, more when the left-over tiles are few (measured at 89 left-over tiles on 256 units:
+    // 2 parts 124 + 10 us for the two kernels, 3 parts 123 + 13, 4 parts 121 + 16; undivided 160), each of 8 k-steps or
+    // more, within the workspace
+    int cuts = rest > 0 ? std::max(2, wgs / (2 * rest)) : 1;
+    cuts = std::min(cuts, BALANCED_MAX_CUTS);
+    while (cuts > 1 && (min_nkt / cuts < 8 || (long)rest * cuts > 2L * wgs)) --cuts;
+    if (rest > 0 && cuts > 1) {
+      a.total_tiles = tiles; a.whole_tiles = a.long_tiles - rest; a.cuts = cuts;
+      void* prof = nullptr;
+      PPLL_TRY(profile_begin(s, flops, &prof));
+      const int parts = rest * cuts;
+      const int grid = 8 * ((a.whole_tiles + 7) / 8 + (parts + 7) / 8 + (tiles - a.long_tiles + 7) / 8);
+      hipLaunchKernelGGL(gemm_mfma_balanced_kernel, dim3(grid), dim3(256), lds_bytes(true, true, 128), s, a);
+      PPLL_HIP(hipGetLastError());
+      hipLaunchKernelGGL(gemm_mfma_balanced_sum_kernel, dim3(4 * rest), dim3(256), 0, s, a);
+      PPLL_HIP(hipGetLastError());
+      PPLL_TRY(profile_end(s, prof));
+      return PPLL_OK;
+    }
+  }
+
   for (int j0 = 0; j0 < n; j0 += GROUP_MAX) {
     GroupedArgs a{};
     a.n = n - j0 < GROUP_MAX ? n - j0 : GROUP_MAX;
@@ -575,16 +742,8 @@ int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n) {
     double flops = 0.0;
     for (int j = 0; j < a.n; ++j) {
       const GemmArgs& g = gs[j0 + j];
-      GroupedProblem& q = a.prob[j];
-      q.A = (const uint16_t*)g.A; q.lda = (int)g.a_sk; q.B = (const uint16_t*)g.B; q.ldb = (int)g.b_sk;
-      q.C = (float*)g.C; q.ldc = (int)g.ldc; q.colsum = g.colsum;
-      q.M = g.M; q.N = g.N; q.K = g.K;
-      q.tiles_m = (g.M + BM - 1) / BM; q.tiles_n = (g.N + BN - 1) / BN;
-      q.first_tile = tiles;
-      tiles += q.tiles_m * q.tiles_n;
-      q.a_bytes = (uint32_t)operand_bytes(true, g.M, g.K, g.a_sk);
-      q.b_bytes = (uint32_t)operand_bytes(true, g.N, g.K, g.b_sk);
-      q.c_bytes = (uint32_t)(((long)(g.M - 1) * g.ldc + g.N) * 4);
+      fill_problem(a.prob[j], g, tiles);
+      tiles += a.prob[j].tiles_m * a.prob[j].tiles_n;
       flops += 2.0 * g.M * g.N * g.K;
     }
     a.total_tiles = tiles;
