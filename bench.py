@@ -77,18 +77,22 @@ def kernel_source_sha() -> str:
     return h.hexdigest()[:16]
 
 
-def measured_traffic(workload: str, kind: str):
+def measured_traffic(workload: str, kind: str, launches_per_step: float):
     """HBM bytes per launch of the dominant kernel class (kind "gemm" or "conv") from the committed counter
     summary of this workload (two rocprofv3 --pmc runs, FETCH_SIZE then WRITE_SIZE, each scaled by what the same
     counter reads for the copy probe).  Counters cannot be read inside a timing run, so the figure comes from
     profiles/; it is reported only if that summary was taken with the kernel sources this library is built from
-    (their hash is stamped into it), else None with the reason."""
+    (their hash is stamped into it) and counts as many launches of the class per step as this run has just
+    bracketed, else None with the reason."""
     path = os.path.join(ROOT, "profiles", f"{workload}_{kind}_hbm_traffic.json")
     try:
         with open(path) as f:
             rec = json.load(f)
         if rec.get("kernel_source_sha") != kernel_source_sha():
             return None, f"{os.path.basename(path)} was taken with other kernel sources ({rec.get('kernel_source_sha')})"
+        if abs(float(rec["launches_per_step"]) - launches_per_step) > 1e-9:
+            return None, (f"{os.path.basename(path)} counts {rec['launches_per_step']} launches of the class per step, "
+                          f"this run {launches_per_step}")
         return float(rec["bytes_per_launch"]), None
     except (OSError, KeyError, ValueError):
         return None, "no counter summary committed for this workload"
@@ -341,15 +345,18 @@ def main() -> int:
         P.ppll_block_profile_enable(blk, True)
         P.ppll_block_profile_read(blk)
         P.ppll_block_profile_read_conv(blk)
+        P.ppll_block_profile_read_small(blk)
         run(args.steps)
         torch.cuda.synchronize()
         gemm_ms, gemm_flops, launches = P.ppll_block_profile_read(blk)
         conv_ms, conv_bytes, conv_launches = P.ppll_block_profile_read_conv(blk)
+        small_ms, small_flops, small_launches = P.ppll_block_profile_read_small(blk)
         P.ppll_block_profile_enable(blk, False)
         if launches > 0:
             achieved = gemm_flops / (gemm_ms * 1e-3) / 1e12
-            traffic, why_not = measured_traffic(args.workload, "gemm")
-            out["roofline"] = {"bound": "mfma", "kernel": "gemm_mfma_kernel (all variants: Linear fwd/dgrad/wgrad)",
+            traffic, why_not = measured_traffic(args.workload, "gemm", launches / args.steps)
+            out["roofline"] = {"bound": "mfma",
+                               "kernel": "gemm_mfma_kernel on the token matrices (Linear forward, input gradient) and the grouped weight-gradient launch",
                                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                                "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                                **({"traffic_missing_because": why_not} if why_not else {}),
@@ -358,11 +365,18 @@ def main() -> int:
                                "avg_launch_us": 1e3 * gemm_ms / launches,
                                "gemm_ms_per_step": gemm_ms / args.steps,
                                "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
+            if small_launches > 0:
+                # the class-token products of the pruned last auxiliary layer: a few rows each, bound by launch latency
+                out["small_products"] = {"kernel": "gemm_mfma_kernel on products with fewer than 256 output rows",
+                                         "launches_per_step": small_launches / args.steps,
+                                         "avg_launch_us": 1e3 * small_ms / small_launches,
+                                         "ms_per_step": small_ms / args.steps,
+                                         "achieved_tflops": small_flops / (small_ms * 1e-3) / 1e12}
 
         elif conv_launches > 0:
             # ResNet blocks: the dominant kernel is the 3x3 convolution (forward + input gradient), bound by HBM
             gbs = conv_bytes / (conv_ms * 1e-3) / 1e9
-            traffic, why_not = measured_traffic(args.workload, "conv")
+            traffic, why_not = measured_traffic(args.workload, "conv", conv_launches / args.steps)
             out["roofline"] = {"bound": "hbm", "kernel": "conv3x3_mfma_kernel (forward and input gradient)",
                                "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS,
                                "traffic": traffic, **({"traffic_missing_because": why_not} if why_not else {}),

@@ -229,12 +229,15 @@ int ppll_pipeline_destroy(ppll_pipeline_t* pipe);
  * gradients), so that each bracket holds one kernel running alone.  Other blocks are not affected.
  * ppll_block_profile_read waits for those events and returns, since the previous read: the summed duration of the
  * GEMM launches in milliseconds, their algorithmic flops 2*M*N*K, and their count (each pointer nullable);
+ * products with fewer than 256 output rows (the class-token products of a pruned last auxiliary layer, Section
+ * 3.2's auxiliary network) are kept apart and read with ppll_block_profile_read_small;
  * ppll_block_profile_read_conv the same for the convolution launches (forward and input gradient of the ResNet
  * blocks) with their algorithmic bytes: input tensor + output tensor + filter once each, plus the two tensors of
  * the fused shortcut gradient where present.  The events add host and stream overhead: time whole steps with it off. */
 int ppll_block_profile_enable(ppll_block_t* block, int32_t on);
 int ppll_block_profile_read(ppll_block_t* block, double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
 int ppll_block_profile_read_conv(ppll_block_t* block, double* conv_ms, double* conv_bytes, int64_t* conv_launches);
+int ppll_block_profile_read_small(ppll_block_t* block, double* gemm_ms, double* gemm_flops, int64_t* gemm_launches);
 
 /* Phase timers in the symbols of the paper's time model (Section 3.3: S_PPLL = f_1 + f_a1 + B_a1 +
  * U_a1): with timers on, every step of the block records HIP events on its stream at the ends of

@@ -87,6 +87,7 @@ _SIGS = {
     "ppll_block_profile_enable": (C.c_int, [C.c_void_p, C.c_int32]),
     "ppll_block_profile_read": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
     "ppll_block_profile_read_conv": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
+    "ppll_block_profile_read_small": (C.c_int, [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]),
 }
 EXPORTS = tuple(_SIGS)
 
@@ -287,6 +288,13 @@ def ppll_block_profile_read_conv(block):
     ms, by, n = C.c_double(0), C.c_double(0), C.c_int64(0)
     _check(lib().ppll_block_profile_read_conv(block, C.byref(ms), C.byref(by), C.byref(n)))
     return ms.value, by.value, n.value
+
+
+def ppll_block_profile_read_small(block):
+    """(milliseconds, flops, launches) of the block's GEMM launches with fewer than 256 output rows since the last read."""
+    ms, fl, n = C.c_double(0), C.c_double(0), C.c_int64(0)
+    _check(lib().ppll_block_profile_read_small(block, C.byref(ms), C.byref(fl), C.byref(n)))
+    return ms.value, fl.value, n.value
 
 
 def ppll_probe_copy(src, dst, nbytes: int, stream=None) -> None:

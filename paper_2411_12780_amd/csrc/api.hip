@@ -327,6 +327,9 @@ int ppll_block_profile_read(ppll_block_t* h, double* gemm_ms, double* gemm_flops
 int ppll_block_profile_read_conv(ppll_block_t* h, double* conv_ms, double* conv_bytes, int64_t* conv_launches) {
   return profile_take(h, 1, conv_ms, conv_bytes, conv_launches);
 }
+int ppll_block_profile_read_small(ppll_block_t* h, double* gemm_ms, double* gemm_flops, int64_t* gemm_launches) {
+  return profile_take(h, 2, gemm_ms, gemm_flops, gemm_launches);
+}
 
 int ppll_block_phase_timers(ppll_block_t* h, int32_t on) {
   PPLL_TRY(block_alive(h));

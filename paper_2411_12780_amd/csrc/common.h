@@ -110,12 +110,14 @@ bool gemm_group_in_one_launch(const GemmArgs* gs, int n);   // every product fit
 // Per-launch timing of the contraction kernels (a measurement aid, off unless a block asks for it).  A block that
 // times its launches binds its record to the calling thread for the duration of a step; the launch functions
 // below the block engine then bracket each contraction launch with a pair of events on its stream.
-struct TimedLaunch { hipEvent_t a, b; double units; int kind; };   // kind 0: GEMM (units = flops), 1: convolution (units = bytes)
+// kind 0: GEMM over a token matrix (units = flops), 1: convolution (units = bytes), 2: GEMM with fewer than 256 output rows
+// (the class-token products of the pruned auxiliary layer; units = flops)
+struct TimedLaunch { hipEvent_t a, b; double units; int kind; };
 struct LaunchTimes {
   std::vector<TimedLaunch> timed;
   std::vector<hipEvent_t> pool;
-  double ms[2] = {0, 0}, units[2] = {0, 0};
-  long long launches[2] = {0, 0};
+  double ms[3] = {0, 0, 0}, units[3] = {0, 0, 0};
+  long long launches[3] = {0, 0, 0};
 };
 void profile_bind(LaunchTimes* t);     // null: launches of this thread are not timed
 bool profile_enabled();                // a record is bound to this thread

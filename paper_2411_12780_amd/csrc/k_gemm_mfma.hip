@@ -804,7 +804,7 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
     lds_opted_in = true;
   }
   void* prof = nullptr;
-  PPLL_TRY(profile_begin(s, 2.0 * g.M * g.N * g.K, &prof));
+  PPLL_TRY(profile_begin(s, 2.0 * g.M * g.N * g.K, &prof, g.M < 256 && !at ? 2 : 0));   // few output rows: a class of its own
   if (small_m) {
     if (bt) hipLaunchKernelGGL((gemm_mfma_kernel<false, true, 64>), grid, dim3(256), lds_bytes(false, true, 64), s, p);
     else hipLaunchKernelGGL((gemm_mfma_kernel<false, false, 64>), grid, dim3(256), lds_bytes(false, false, 64), s, p);

@@ -641,6 +641,7 @@ def test_launch_brackets_count_the_contraction_kernels_and_their_work():
                 M, D, F = 8 * vit["tokens"], vit["dim"], vit["mlp_dim"]
                 fwd = 2.0 * M * (D * 3 * D + D * D + 2 * D * F)
                 assert gemm_n >= 16 and gemm_ms > 0 and conv_n == 0
+                assert P.ppll_block_profile_read_small(gb.h)[2] == 0      # no product with fewer than 256 rows here
                 assert abs(gemm_flops - 2 * 3 * fwd) <= 1e-6 * gemm_flops
             else:
                 # one basic block + auxiliary convolution: 3 forward launches, conv2's and the auxiliary input gradient
