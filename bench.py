@@ -367,7 +367,7 @@ def main() -> int:
                                "gemm_flop_share_of_step": gemm_flops / args.steps / flops}
             if small_launches > 0:
                 # the class-token products of the pruned last auxiliary layer: a few rows each, bound by launch latency
-                out["small_products"] = {"kernel": "gemm_mfma_kernel on products with fewer than 256 output rows",
+                out["small_products"] = {"kernel": "gemm_rows_kernel (products with fewer than 256 output rows)",
                                          "launches_per_step": small_launches / args.steps,
                                          "avg_launch_us": 1e3 * small_ms / small_launches,
                                          "ms_per_step": small_ms / args.steps,

@@ -61,6 +61,18 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
+// Exact-form GELU through the rational erf approximation of Abramowitz & Stegun 7.1.26
+// (|error| < 1.5e-7, far below bf16 resolution); erf(h/sqrt 2) and the normal density share
+// one exponential: e^{-z^2} with z = h/sqrt 2 is e^{-h^2/2}.
+__device__ __forceinline__ void cdf_pdf(float h, float& cdf, float& pdf) {
+  const float z = fabsf(h) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
+  const float ex = __expf(-z * z);
+  const float poly = ((((1.061405429f * t - 1.453152027f) * t + 1.421413741f) * t - 0.284496736f) * t + 0.254829592f) * t;
+  const float erf_abs = 1.0f - poly * ex;
+  cdf = 0.5f * (1.0f + copysignf(erf_abs, h));
+  pdf = 0.39894228040143268f * ex;
+}
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -94,6 +106,9 @@ struct GemmArgs {
 };
 int launch_gemm(hipStream_t s, const GemmArgs& g);          // picks the MFMA kernel when the shape allows
 int launch_gemm_generic(hipStream_t s, const GemmArgs& g);
+// Products with few output rows (the class-token rows of a pruned auxiliary layer): see k_gemm_rows.hip
+bool gemm_rows_supported(const GemmArgs& g);
+int launch_gemm_rows(hipStream_t s, const GemmArgs& g);
 bool gemm_mfma_supported(const GemmArgs& g);
 inline bool gemm_fuses_colsum(const GemmArgs& g) { return g.colsum && gemm_mfma_supported(g); }
 size_t gemm_mfma_partial_floats(int M, int N, int K);

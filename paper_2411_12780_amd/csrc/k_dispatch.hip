@@ -58,6 +58,7 @@ int profile_end(hipStream_t s, void* token) {
 }
 
 int launch_gemm(hipStream_t s, const GemmArgs& g) {
+  if (gemm_rows_supported(g)) return launch_gemm_rows(s, g);   // few output rows: latency, not throughput
   return gemm_mfma_supported(g) ? launch_gemm_mfma(s, g, g.splitk_ws, g.splitk_floats) : launch_gemm_generic(s, g);
 }
 

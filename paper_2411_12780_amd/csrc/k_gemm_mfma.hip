@@ -61,18 +61,6 @@ struct MfmaArgs {
   float* tile_partial;
 };
 
-// Exact-form GELU through the rational erf approximation of Abramowitz & Stegun 7.1.26
-// (|error| < 1.5e-7, far below bf16 resolution); erf(h/sqrt 2) and the normal density share
-// one exponential: e^{-z^2} with z = h/sqrt 2 is e^{-h^2/2}.
-__device__ __forceinline__ void cdf_pdf(float h, float& cdf, float& pdf) {
-  const float z = fabsf(h) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
-  const float ex = __expf(-z * z);
-  const float poly = ((((1.061405429f * t - 1.453152027f) * t + 1.421413741f) * t - 0.284496736f) * t + 0.254829592f) * t;
-  const float erf_abs = 1.0f - poly * ex;
-  cdf = 0.5f * (1.0f + copysignf(erf_abs, h));
-  pdf = 0.39894228040143268f * ex;
-}
 __device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) { return f32x2_to_bf16x2(a, b); }
 
 // LDS layout of an operand tile.  Measured on the chip (16 waves of one compute unit issuing one access pattern;
