@@ -439,6 +439,15 @@ def test_vit_stage_bf16_full_size():
     run_case(synth.workload("vit_stage_bf16"), steps=3)
 
 
+@pytest.mark.parametrize("batch,depth", [(37, 3), (50, 1)])
+def test_vit_stage_bf16_divided_weight_gradient_tiles_with_a_ragged_reduction(batch, depth):
+    # batch 37: 2405 token rows = 37 whole 64-row reduction steps and one of 37 rows, and 345 weight-gradient tiles, so
+    # the grouped launch divides 89 of them along the token index and the last part ends in the ragged step; batch 50
+    # with one module layer: 129 tiles with a long reduction, fewer than there are compute units, so every one of them is
+    # summed from two parts (3250 rows = 50 steps + 50 rows), and 90 class-token tiles with a one-step reduction
+    run_case(synth.workload("vit_stage_bf16", batch=batch, depth=depth), steps=1)
+
+
 def test_vit_base_paper_shape_bf16_full_size():
     # the paper's ViT-Base stage: 640 rows of width 768, K = 768 patch embedding, 5-token attention, SGD Nesterov
     run_case(synth.workload("vit_base_paper_bf16"), steps=2)
