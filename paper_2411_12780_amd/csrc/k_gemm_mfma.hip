@@ -27,6 +27,8 @@
 // split writes its fp32 partial tile, a second kernel adds the splits in a
 // fixed order, so results are reproducible (no float atomics).
 #include "common.h"
+#include <atomic>
+#include <algorithm>
 
 namespace ppll {
 
@@ -648,15 +650,17 @@ bool gemm_mfma_groupable(const GemmArgs& g) {
 
 // Workgroups of a balanced grouped launch on the current device: one per compute unit, a multiple of 8.
 static int balanced_workgroups() {
-  static int cached[64] = {0};
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  return (cus / 8) * 8;
+}
+// More than 64 KB of dynamic LDS needs an opt-in per kernel, and the attribute belongs to a device's copy of the
+// kernel: true (once per device and flag set) when the caller still has to raise it on the current device.
+static bool lds_opt_in_due(std::atomic<bool> (&done)[64]) {
   int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
-  if (!cached[dev]) {
-    int cus = 0;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    cached[dev] = (cus / 8) * 8;
-  }
-  return cached[dev];
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return true;
+  return !done[dev].exchange(true);
 }
 constexpr int BALANCED_MAX_CUTS = 4;
 // room for the parts of the divided tiles: at most two per workgroup
@@ -674,11 +678,10 @@ static void fill_problem(GroupedProblem& q, const GemmArgs& g, int first_tile) {
 }
 
 int launch_gemm_mfma_grouped(hipStream_t s, const GemmArgs* gs, int n, float* ws, size_t ws_floats) {
-  static bool lds_opted_in = false;
-  if (!lds_opted_in) {
+  static std::atomic<bool> opted_in[64];
+  if (lds_opt_in_due(opted_in)) {
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_grouped_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, true, 128)));
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_balanced_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, true, 128)));
-    lds_opted_in = true;
   }
   // Balanced launch: the whole set in one launch, a workspace for the divided tiles, tiles that leave a last round
   // partly filled, and a reduction long enough to cut
@@ -783,13 +786,12 @@ int launch_gemm_mfma(hipStream_t s, const GemmArgs& g, float* partial, size_t pa
   dim3 grid(p.tiles_m * p.tiles_n, splits);
   if (p.xcd_map == 1) grid = dim3(((p.tiles_m + 7) / 8) * 8 * p.tiles_n, splits);
   if (p.xcd_map == 2) grid = dim3(p.tiles_m * p.tiles_n * splits, 1);
-  static bool lds_opted_in = false;   // > 64 KB of dynamic LDS needs a one-time opt-in per kernel
-  if (!lds_opted_in) {
+  static std::atomic<bool> opted_in[64];
+  if (lds_opt_in_due(opted_in)) {
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, true, 128)));
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<true, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(true, false, 128)));
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, true, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(false, true, 128)));
     PPLL_HIP(hipFuncSetAttribute((const void*)gemm_mfma_kernel<false, false, 128>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(false, false, 128)));
-    lds_opted_in = true;
   }
   void* prof = nullptr;
   PPLL_TRY(profile_begin(s, 2.0 * g.M * g.N * g.K, &prof, g.M < 256 && !at ? 2 : 0));   // few output rows: a class of its own
