@@ -410,16 +410,18 @@ def main() -> int:
         ocfg = oracle_cfg(wl)
         st = O.block_init(ocfg, synth.make_params(O.param_spec(ocfg), seed=0), np.float64)
         x, y = synth.make_batch(wl, seed=0, index=0)
-        n_steps = 10 if wl["batch"] * wl.get("tokens", 1) < 2048 else 1
-        t0 = time.perf_counter()
-        for _ in range(n_steps):
+        # a bounded sample: whole steps until about 10 s of CPU work are spent (at least 1, at most 10 steps)
+        small = wl["batch"] * wl.get("tokens", 1) < 2048
+        n_steps, t0 = 0, time.perf_counter()
+        while n_steps < 10 and (n_steps == 0 or time.perf_counter() - t0 < 10.0):
             O.block_step(st, x.astype(np.float64), y, lr)
+            n_steps += 1
         cpu_s = (time.perf_counter() - t0) / n_steps
         threads = max([i.get("num_threads", 1) for i in threadpool_info()] + [1])
         out["cpu_baseline"] = {"value": wl["batch"] / cpu_s, "unit": "images/s", "cores": threads,
                                "kind": "oracle", "sample": f"{n_steps} full step(s) of the same workload "
                                f"(batch {wl['batch']}), float64 numpy oracle, {cpu_s:.2f} s per step"}
-        if n_steps > 1:   # a small workload: the same on one core as well
+        if small:   # a small workload: the same on one core as well
             from threadpoolctl import threadpool_limits
             with threadpool_limits(limits=1):
                 t0 = time.perf_counter()
