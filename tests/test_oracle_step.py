@@ -407,3 +407,52 @@ def test_storage_mode_is_refused_for_the_vit_block():
         O.block_init(cfg, flat, storage="bf16")
     with pytest.raises(ValueError):
         O.block_init(oracle_cfg(synth.workload("resnet_stage_bf16", batch=2)), None, storage="fp16")
+
+
+def test_bf16_storage_rounds_what_passes_between_layers_and_nothing_else(monkeypatch):
+    """What the storage emulation means, stated without reference to any implementation: one rounding for every
+    tensor that one layer hands to the next, forward (convolution output, activation behind BatchNorm + ReLU, block
+    output, pooled features) and backward (the gradient maps travelling the other way), one for every filter a
+    convolution reads, and none anywhere else: statistics, the values inside a BatchNorm, logits, loss and every
+    parameter gradient keep full precision.  Counted here on a stage of n = 3 basic blocks without a stem (the
+    first block's input gradient is not formed): 4 n + 3 activations and 4 n + 3 gradient maps, 4 n + 1 filter reads;
+    every rounded tensor is made of bfloat16 values; parameter gradients are not."""
+    n = 3
+    wl = synth.workload("resnet_stage_bf16", batch=4, channels=8, height=6, width=6, n_basic_blocks=n, aux_channels=8)
+    cfg = oracle_cfg(wl)
+    flat = synth.make_params(O.param_spec(cfg), seed=2, jitter=True)
+    x, y = synth.make_batch(wl, seed=2)
+    seen = {"act": [], "wmat": []}
+    real_act, real_wmat = O.BlockState.act, O.BlockState.wmat
+
+    def act(self, a):
+        out = real_act(self, a)
+        seen["act"].append(out)
+        return out
+
+    def wmat(self, w):
+        out = real_wmat(self, w)
+        seen["wmat"].append(out)
+        return out
+
+    monkeypatch.setattr(O.BlockState, "act", act)
+    monkeypatch.setattr(O.BlockState, "wmat", wmat)
+    st = O.block_init(cfg, flat, storage="bf16")
+    O.block_step(st, x.astype(np.float64), y, 0.01)
+    # forward: c1, y1, c2, out per block; aux conv output, aux activation, pooled.  backward: dpooled, its broadcast
+    # map, the aux conv-output gradient, the block-output gradient; per block dc2, dy1, dc1 and (not for the first
+    # block) the input gradient
+    assert len(seen["act"]) == (4 * n + 3) + (4 + 4 * n - 1)
+    assert len(seen["wmat"]) == (2 * n + 1) + (1 + n + (n - 1))
+
+    def is_bf16(a):
+        a32 = np.asarray(a, dtype=np.float32)
+        return np.array_equal(a32.view(np.uint32) & 0xFFFF, np.zeros(a32.shape, np.uint32)) and np.array_equal(a32.astype(np.float64), a)
+
+    assert all(is_bf16(a) for a in seen["act"]) and all(is_bf16(w) for w in seen["wmat"])
+    assert not any(is_bf16(g) for k, g in st.grads.items() if g.size > 8), "parameter gradients keep full precision"
+    # and with the emulation off nothing is rounded
+    seen["act"].clear()
+    st2 = O.block_init(cfg, flat)
+    O.block_step(st2, x.astype(np.float64), y, 0.01)
+    assert seen["act"] and not any(is_bf16(a) for a in seen["act"] if a.size > 8)
