@@ -1115,14 +1115,24 @@ static bool wgrad_tiles_ok(int H, int W, int Ci, int Co, int stride) {
   const int Wo = W / stride;
   return Wo >= 8 && (Wo % 8) == 0 && wgrad_tiles_lds(H, W, Ci, Co, stride) <= 160 * 1024;
 }
-// workgroups per convolution: one per image up to the number that keeps the partial sums near 32 MiB; a launch
-// of n convolutions needs about 1024 workgroups in all, not that many each (fewer partial sums to add up)
-static int wgrad_tiles_blocks(int B, int Ci, int Co, int n = 1) {
-  long cap = ((long)32 << 20) / ((long)9 * Ci * Co * 4);
-  cap = cap < 32 ? 32 : (cap > 256 ? 256 : cap);
-  const long share = (1024 + n - 1) / n;
-  if (n > 1 && share < cap) cap = share < 32 ? 32 : share;
-  return B < cap ? B : (int)cap;
+// Workgroups per convolution.  A workgroup costs about 10 us before and after its images (clearing its LDS tiles,
+// folding the k-splits, writing its partial filter) against 1-1.5 us per image, and its LDS footprint lets one or two
+// of them run on a compute unit, so the n convolutions of a launch together get one round of those places and each
+// workgroup walks over several images (measured at 10 convolutions 32 -> 32 on 128 images: 103 workgroups each 31 us
+// + 9 us for adding the partial filters, 51: 26 + 6, 25: 22 + 5, 12: 32 + 5).  n = 1 gives the most there can be
+// (what the partial sums are sized for).
+static int wgrad_tiles_blocks(int B, int n, int places) {
+  int blocks = places / (n < 1 ? 1 : n);
+  blocks = blocks < 1 ? 1 : blocks;
+  return B < blocks ? B : blocks;
+}
+// places for the workgroups of one launch on the current device: compute units x workgroups that fit one unit's LDS
+static int wgrad_tiles_places(size_t lds) {
+  int dev = 0, cus = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  const size_t per = lds ? ((size_t)160 * 1024) / lds : 2;
+  return cus * (int)(per < 1 ? 1 : (per > 2 ? 2 : per));     // 512 threads each: two at most
 }
 template <int CI, int CO, int S>
 static int wgrad_tiles_launch(hipStream_t s, const WgtGroup& g, int n, int B, int H, int W, int blocks) {
@@ -1151,7 +1161,7 @@ size_t conv3x3_wgrad_bf16_partial_floats(int B, int H, int W, int Ci, int Co, in
   const long P = (long)B * ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
   size_t n = (size_t)((P + WG_PIX_F - 1) / WG_PIX_F) * 9 * Ci * Co;
   if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
-    const size_t m = (size_t)wgrad_tiles_blocks(B, Ci, Co) * 9 * Ci * Co;
+    const size_t m = (size_t)wgrad_tiles_blocks(B, 1, wgrad_tiles_places(wgrad_tiles_lds(H, W, Ci, Co, stride))) * 9 * Ci * Co;
     if (m > n) n = m;
   }
   return n;
@@ -1177,7 +1187,7 @@ int launch_conv3x3_wgrad_bf16(hipStream_t s, const void* x, const void* dy, int 
   const int cpt = Ci / (256 / Co);
   bool queued;
   if (wgrad_tiles_ok(H, W, Ci, Co, stride)) {
-    const int blocks = wgrad_tiles_blocks(B, Ci, Co);
+    const int blocks = wgrad_tiles_blocks(B, 1, wgrad_tiles_places(wgrad_tiles_lds(H, W, Ci, Co, stride)));
     float* part = rq.space((size_t)blocks * nw, &queued);
     WgtGroup g{};
     g.x[0] = (const uint16_t*)x; g.dy[0] = (const uint16_t*)dy; g.partial[0] = part;
@@ -1207,7 +1217,8 @@ int launch_conv3x3_wgrad_group_bf16(hipStream_t s, const ConvWgradJob* jobs, int
                                     int stride, ReduceQueue& rq, bool* done) {
   *done = false;
   if (!wgrad_tiles_ok(H, W, Ci, Co, stride)) return PPLL_OK;
-  const int blocks = wgrad_tiles_blocks(B, Ci, Co, n < WGT_GROUP ? n : WGT_GROUP), nw = 9 * Ci * Co;
+  const int blocks = wgrad_tiles_blocks(B, n < WGT_GROUP ? n : WGT_GROUP, wgrad_tiles_places(wgrad_tiles_lds(H, W, Ci, Co, stride)));
+  const int nw = 9 * Ci * Co;
   const size_t need = ((size_t)blocks * nw + 63) & ~(size_t)63;
   if (!rq.arena || rq.used + need * n > rq.arena_floats) return PPLL_OK;
   for (int j0 = 0; j0 < n; j0 += WGT_GROUP) {
