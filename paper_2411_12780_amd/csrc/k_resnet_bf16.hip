@@ -177,8 +177,7 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
       rowok[d] = live && (unsigned)(cy + sg * (d - 1)) < (unsigned)SH;
       colok[d] = (unsigned)(cx + sg * (d - 1)) < (unsigned)SW;
     }
-    auto tap_group = [&](const int grp) {
-      uint4 xv[TG][K16];
+    auto tap_load = [&](const int grp, uint4 (&xv)[TG][K16]) {
 #pragma unroll
       for (int j = 0; j < TG; ++j) {
         const int tap = grp * TG + j, ky = tap / 3, kx = tap % 3;
@@ -208,6 +207,8 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
           }
         }
       }
+    };
+    auto tap_mma = [&](const int grp, const uint4 (&xv)[TG][K16]) {
 #pragma unroll
       for (int j = 0; j < TG; ++j) {
         const int tap = grp * TG + j;
@@ -230,15 +231,26 @@ __global__ __launch_bounds__(256) void conv3x3_mfma_kernel(ConvArgs p) {
         }
       }
     };
-    // 16 reduced channels: straight-line over the tap groups (a rolled loop makes the compiler carry the accumulators
-    // in ordinary registers and copy them to the MFMA's accumulation registers and back on every trip); with more
-    // reduced channels the straight-line form costs too many registers and the rolled loop measured faster
-    if constexpr (K16 == 1) {
-#pragma unroll
-      for (int grp = 0; grp < NG; ++grp) tap_group(grp);
+    // Up to 32 reduced channels: the loads of a tap group are in flight while the group before it is multiplied (two
+    // register sets); with three groups of three taps (GRP = 1) that leaves one load latency per tile exposed instead
+    // of three (7.1 -> 6.4 us for the 32 -> 32 forward at 128 x 16 x 16).  With 48 or 64 reduced channels the second
+    // register set (96 registers at 64 channels) spills, and the rolled loop over the groups measured faster
+    // (0.92 against 0.97 ms per step at the 8 x 8 stage of ResNet-32).
+    if constexpr (NG == 3 && K16 <= 2) {
+      uint4 xa[TG][K16], xb[TG][K16];
+      tap_load(0, xa);
+      tap_load(1, xb);
+      tap_mma(0, xa);
+      tap_load(2, xa);
+      tap_mma(1, xb);
+      tap_mma(2, xa);
     } else {
 #pragma unroll 1
-      for (int grp = 0; grp < NG; ++grp) tap_group(grp);
+      for (int grp = 0; grp < NG; ++grp) {
+        uint4 xv[TG][K16];
+        tap_load(grp, xv);
+        tap_mma(grp, xv);
+      }
     }
     if (!live) continue;
     // acc[t][4q+e] = out[pix][32t + 8q + 4hh + e]
