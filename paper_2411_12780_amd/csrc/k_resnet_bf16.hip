@@ -490,15 +490,16 @@ __device__ __forceinline__ void bn_finish(const BnSumArgs& p, unsigned nblocks, 
   if (tid < nq * parts) {
     const int v4 = tid % nq, part = tid / nq;
     float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (unsigned bk = part; bk < nblocks; bk += 8 * parts) {   // summed in workgroup order
-      float4 q[8];
+    constexpr int U = 16;                                        // partial rows in flight per thread
+    for (unsigned bk = part; bk < nblocks; bk += U * parts) {   // summed in workgroup order
+      float4 q[U];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < U; ++u) {
         const unsigned bu = bk + u * parts;
         q[u] = bu < nblocks ? *reinterpret_cast<const float4*>(p.partial + (size_t)bu * nv + 4 * v4) : make_float4(0.f, 0.f, 0.f, 0.f);
       }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) { t.x += q[u].x; t.y += q[u].y; t.z += q[u].z; t.w += q[u].w; }
+      for (int u = 0; u < U; ++u) { t.x += q[u].x; t.y += q[u].y; t.z += q[u].z; t.w += q[u].w; }
     }
     *reinterpret_cast<float4*>(red + part * nv + 4 * v4) = t;
   }
